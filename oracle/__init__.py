@@ -1,0 +1,208 @@
+"""ctypes front end of the fp64 CPU oracle -- TEST INFRASTRUCTURE ONLY.
+
+Only `tests/`, `__graft_entry__.smoke()` and the `cpu_baseline` leg of
+`bench.py` may import this package.  It shares nothing with the HIP library:
+its arithmetic lives in `qlora_oracle.c` (plain C, fp64), this file only
+widens 16-bit inputs to double (exactly) and marshals numpy arrays.
+
+Paper passages each entry follows are cited in the C file.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "qlora_oracle.c")
+_LIB = os.path.join(_HERE, "libqlora_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (OpenMP, no fast-math)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall", "-o", _LIB, _SRC]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+        _lib.qo_num_threads.restype = ctypes.c_int
+    return _lib
+
+
+def num_threads() -> int:
+    return int(_load().qo_num_threads())
+
+
+def _p(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _c(a, dtype) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+def _l(v) -> ctypes.c_long:
+    return ctypes.c_long(int(v))
+
+
+def widen(bits16: np.ndarray, dtype: str) -> np.ndarray:
+    """Exact conversion of raw fp16 / bf16 bit patterns (uint16) to float64."""
+    b = np.ascontiguousarray(bits16, dtype=np.uint16)
+    if dtype == "f16":
+        return b.view(np.float16).astype(np.float64)
+    if dtype == "bf16":
+        return (b.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    raise ValueError(dtype)
+
+
+# ------------------------------------------------------------------ codes
+
+def pack(codes: np.ndarray, bits: int) -> np.ndarray:
+    codes = _c(codes, np.uint8)
+    N, K = codes.shape
+    assert (K * bits) % 32 == 0
+    P = np.empty((N, K * bits // 32), dtype=np.uint32)
+    _load().qo_pack(_p(codes), _p(P), _l(N), _l(K), ctypes.c_int(bits))
+    return P
+
+
+def unpack(P: np.ndarray, K: int, bits: int) -> np.ndarray:
+    P = _c(P, np.uint32)
+    N = P.shape[0]
+    assert P.shape[1] == K * bits // 32
+    codes = np.empty((N, K), dtype=np.uint8)
+    _load().qo_unpack(_p(P), _p(codes), _l(N), _l(K), ctypes.c_int(bits))
+    return codes
+
+
+def dequant(P: np.ndarray, scales: np.ndarray, zeros: np.ndarray, K: int, bits: int, G: int) -> np.ndarray:
+    """Wd [N,K] float64.  `scales` float64 [N,K/G], `zeros` uint8 [N,K/G]."""
+    P = _c(P, np.uint32)
+    s = _c(scales, np.float64)
+    z = _c(zeros, np.uint8)
+    N = P.shape[0]
+    assert s.shape == (N, K // G) and z.shape == (N, K // G) and K % G == 0
+    Wd = np.empty((N, K), dtype=np.float64)
+    _load().qo_dequant(_p(P), _p(s), _p(z), _p(Wd), _l(N), _l(K), ctypes.c_int(bits), _l(G))
+    return Wd
+
+
+# ------------------------------------------------------------ layer passes
+
+def lora_down(x: np.ndarray, A: np.ndarray) -> np.ndarray:
+    x = _c(x, np.float64)
+    A = _c(A, np.float64)
+    M, K = x.shape
+    r = A.shape[0]
+    t = np.zeros((M, r), dtype=np.float64)
+    if r:
+        _load().qo_lora_down(_p(x), _p(A), _p(t), _l(M), _l(K), _l(r))
+    return t
+
+
+def lora_u(dy: np.ndarray, B: np.ndarray) -> np.ndarray:
+    dy = _c(dy, np.float64)
+    B = _c(B, np.float64)
+    M, N = dy.shape
+    r = B.shape[1]
+    u = np.zeros((M, r), dtype=np.float64)
+    if r:
+        _load().qo_lora_u(_p(dy), _p(B), _p(u), _l(M), _l(N), _l(r))
+    return u
+
+
+def forward(x, Wd, A, B, alpha: float) -> Tuple[np.ndarray, np.ndarray]:
+    """y [M,N] and t = x A^T [M,r], all float64.  Rows of x are independent."""
+    x = _c(x, np.float64)
+    Wd = _c(Wd, np.float64)
+    A = _c(A, np.float64)
+    B = _c(B, np.float64)
+    M, K = x.shape
+    N = Wd.shape[0]
+    r = A.shape[0]
+    assert Wd.shape == (N, K) and A.shape == (r, K) and B.shape == (N, r)
+    t = lora_down(x, A)
+    y = np.empty((M, N), dtype=np.float64)
+    _load().qo_forward(_p(x), _p(Wd), _p(t), _p(B), ctypes.c_double(alpha), _p(y),
+                       _l(M), _l(N), _l(K), _l(r))
+    return y, t
+
+
+def backward_dx(dy, Wd, A, B, alpha: float) -> np.ndarray:
+    """dX [M,K] float64.  Rows of dY are independent."""
+    dy = _c(dy, np.float64)
+    Wd = _c(Wd, np.float64)
+    A = _c(A, np.float64)
+    B = _c(B, np.float64)
+    M, N = dy.shape
+    K = Wd.shape[1]
+    r = A.shape[0]
+    assert Wd.shape == (N, K) and A.shape == (r, K) and B.shape == (N, r)
+    u = lora_u(dy, B)
+    dx = np.empty((M, K), dtype=np.float64)
+    _load().qo_backward_dx(_p(dy), _p(Wd), _p(u), _p(A), ctypes.c_double(alpha), _p(dx),
+                           _l(M), _l(N), _l(K), _l(r))
+    return dx
+
+
+def backward_adapters(dy, x, A, B, alpha: float) -> Tuple[np.ndarray, np.ndarray]:
+    """(dA [r,K], dB [N,r]) float64; needs every row m (sums over tokens)."""
+    dy = _c(dy, np.float64)
+    x = _c(x, np.float64)
+    A = _c(A, np.float64)
+    B = _c(B, np.float64)
+    M, N = dy.shape
+    K = x.shape[1]
+    r = A.shape[0]
+    assert x.shape == (M, K) and A.shape == (r, K) and B.shape == (N, r)
+    t = lora_down(x, A)
+    u = lora_u(dy, B)
+    dA = np.zeros((r, K), dtype=np.float64)
+    dB = np.zeros((N, r), dtype=np.float64)
+    if r:
+        _load().qo_backward_adapters(_p(dy), _p(x), _p(t), _p(u), ctypes.c_double(alpha),
+                                     _p(dA), _p(dB), _l(M), _l(N), _l(K), _l(r))
+    return dA, dB
+
+
+class LayerOracle:
+    """The layer on one set of stored inputs (raw 16-bit patterns + codes).
+
+    Widening and dequantisation are done once; forward / backward can then be
+    asked for any subset of token rows.
+    """
+
+    def __init__(self, codes, scales_f16_bits, zeros, A_bits, B_bits, *, bits: int, group_size: int,
+                 alpha: float, dtype: str):
+        codes = _c(codes, np.uint8)
+        self.N, self.K = codes.shape
+        self.bits, self.G, self.alpha, self.dtype = bits, group_size, float(alpha), dtype
+        self.P = pack(codes, bits)
+        self.s = widen(scales_f16_bits, "f16")
+        self.z = _c(zeros, np.uint8)
+        self.Wd = dequant(self.P, self.s, self.z, self.K, bits, group_size)
+        self.A = widen(A_bits, dtype).reshape(-1, self.K)
+        self.B = widen(B_bits, dtype).reshape(self.N, -1)
+        self.r = self.A.shape[0]
+
+    def forward(self, x_bits, rows: Optional[np.ndarray] = None):
+        x = widen(x_bits if rows is None else np.asarray(x_bits)[rows], self.dtype)
+        return forward(x, self.Wd, self.A, self.B, self.alpha)
+
+    def backward_dx(self, dy_bits, rows: Optional[np.ndarray] = None):
+        dy = widen(dy_bits if rows is None else np.asarray(dy_bits)[rows], self.dtype)
+        return backward_dx(dy, self.Wd, self.A, self.B, self.alpha)
+
+    def backward_adapters(self, dy_bits, x_bits):
+        return backward_adapters(widen(dy_bits, self.dtype), widen(x_bits, self.dtype),
+                                 self.A, self.B, self.alpha)

@@ -1,0 +1,338 @@
+"""Pins for the CPU oracle: it is checked against things that are not itself.
+
+hand-derived packed words, a big-integer bit-stream writer, numpy float64
+products, pure-Python loops on tiny shapes, finite differences, adjoint
+identities and the special cases the layer's definition implies
+(Sec. 3.1 and Fig. 1 of the paper; Appendix B for the adapter shapes).
+"""
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2306_08162_amd import workloads as wl
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+RTOL = 1e-11
+
+
+def _rel(a, b):
+    d = np.linalg.norm(np.asarray(a, np.float64) - np.asarray(b, np.float64))
+    n = np.linalg.norm(np.asarray(b, np.float64))
+    return d / n if n > 0 else d
+
+
+def _read_pack_golden():
+    rows = []
+    with open(os.path.join(GOLDEN, "pack_words.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            b, codes, words = [p.strip() for p in line.split("|")]
+            rows.append((int(b), np.array(codes.split(), dtype=np.uint8),
+                         np.array([int(w, 16) for w in words.split()], dtype=np.uint32)))
+    return rows
+
+
+def _bigint_pack(row, b):
+    """Independent writer: the row as one big little-endian integer."""
+    stream = 0
+    for k, q in enumerate(row.tolist()):
+        stream |= int(q) << (b * k)
+    nw = len(row) * b // 32
+    return np.array([(stream >> (32 * w)) & 0xFFFFFFFF for w in range(nw)], dtype=np.uint32)
+
+
+# ------------------------------------------------------------------ codes
+
+@pytest.mark.parametrize("case", _read_pack_golden(), ids=lambda c: f"b{c[0]}_{c[2][0]:08X}")
+def test_pack_matches_hand_derived_words(case):
+    b, codes, words = case
+    P = oracle.pack(codes[None, :], b)
+    assert P.shape == (1, len(words))
+    assert np.array_equal(P[0], words)
+    assert np.array_equal(oracle.unpack(words[None, :], len(codes), b)[0], codes)
+
+
+@pytest.mark.parametrize("b", [2, 3, 4, 8])
+@pytest.mark.parametrize("K", [32, 96, 256, 11008])
+def test_pack_matches_bigint_stream_and_roundtrips(b, K):
+    N = 5
+    codes = wl.uniform_ints(1234 + b * 100 + K, N * K, 1 << b).reshape(N, K)
+    P = oracle.pack(codes, b)
+    assert P.dtype == np.uint32 and P.shape == (N, K * b // 32)
+    for n in range(N):
+        assert np.array_equal(P[n], _bigint_pack(codes[n], b))
+    assert np.array_equal(oracle.unpack(P, K, b), codes)
+
+
+@pytest.mark.parametrize("b", [2, 3, 4, 8])
+def test_pack_extreme_codes(b):
+    K = 64
+    top = (1 << b) - 1
+    P = oracle.pack(np.full((2, K), top, np.uint8), b)
+    assert np.all(P == 0xFFFFFFFF)
+    assert np.all(oracle.pack(np.zeros((2, K), np.uint8), b) == 0)
+
+
+def test_rows_are_independent_streams():
+    # INT3 with K=32: each row is 3 whole words; row 1 must not leak into row 0.
+    codes = np.zeros((2, 32), np.uint8)
+    codes[1, :] = 7
+    P = oracle.pack(codes, 3)
+    assert np.all(P[0] == 0) and np.all(P[1] == 0xFFFFFFFF)
+
+
+def test_adapter_shape_pin_from_paper():
+    with open(os.path.join(GOLDEN, "shape_pins.txt")) as f:
+        line = [l for l in f if l.strip() and not l.startswith("#")][0]
+    L, d, r, total = [int(v) for v in line.split("|")]
+    assert 2 * L * d * r == total
+    cfg = wl.config2()                       # a 4096 -> 4096 projection with r = 8
+    assert (cfg.K, cfg.N, cfg.rank) == (d, d, r)
+    inp = wl.make_inputs(wl.config1())
+    assert inp.A.shape == (inp.cfg.rank, inp.cfg.K) and inp.B.shape == (inp.cfg.N, inp.cfg.rank)
+    per_projection = cfg.rank * (cfg.K + cfg.N)
+    assert L * per_projection == total
+
+
+# ---------------------------------------------------------------- dequant
+
+def _np_dequant(codes, s, z, G):
+    g = np.arange(codes.shape[1]) // G
+    return s[:, g] * (codes.astype(np.float64) - z[:, g].astype(np.float64))
+
+
+@pytest.mark.parametrize("b,G,K", [(2, 32, 96), (3, 32, 64), (4, 64, 256), (8, 128, 256), (3, 128, 384), (4, 96, 96)])
+def test_dequant_is_scale_times_code_minus_zero(b, G, K):
+    N = 7
+    codes = wl.uniform_ints(77 + b, N * K, 1 << b).reshape(N, K)
+    s = wl.uniform_range(78, N * (K // G), 0.002, 0.05).reshape(N, K // G)
+    z = wl.uniform_ints(79 + b, N * (K // G), 1 << b).reshape(N, K // G)
+    Wd = oracle.dequant(oracle.pack(codes, b), s, z, K, b, G)
+    assert np.array_equal(Wd, _np_dequant(codes, s, z, G))      # same two fp64 ops: exact
+    # scalar spot checks written out longhand
+    for (n, k) in [(0, 0), (3, K - 1), (6, G % K), (2, G - 1)]:
+        assert Wd[n, k] == s[n, k // G] * (float(codes[n, k]) - float(z[n, k // G]))
+
+
+def test_widen_is_exact():
+    h = np.array([0x3C00, 0xC000, 0x0001, 0x7BFF, 0x8000], np.uint16)   # 1, -2, 2^-24, 65504, -0
+    assert oracle.widen(h, "f16").tolist() == [1.0, -2.0, 2.0 ** -24, 65504.0, -0.0]
+    bf = np.array([0x3F80, 0xC000, 0x3F81, 0x0080], np.uint16)          # 1, -2, 1+2^-7, 2^-126
+    assert oracle.widen(bf, "bf16").tolist() == [1.0, -2.0, 1.0 + 2.0 ** -7, 2.0 ** -126]
+
+
+# ---------------------------------------------------------------- helpers
+
+def _small_problem(seed, M, N, K, r, b, G, alpha=16.0):
+    codes = wl.uniform_ints(seed, N * K, 1 << b).reshape(N, K)
+    s = wl.uniform_range(seed + 1, N * (K // G), 0.005, 0.03).reshape(N, K // G)
+    z = wl.uniform_ints(seed + 2, N * (K // G), 1 << b).reshape(N, K // G)
+    A = wl.normal(seed + 3, r * K, K ** -0.5).reshape(r, K)
+    B = wl.normal(seed + 4, N * r, 0.1).reshape(N, r)
+    x = wl.normal(seed + 5, M * K).reshape(M, K)
+    dy = wl.normal(seed + 6, M * N).reshape(M, N)
+    Wd = oracle.dequant(oracle.pack(codes, b), s, z, K, b, G)
+    return dict(codes=codes, s=s, z=z, A=A, B=B, x=x, dy=dy, Wd=Wd, alpha=alpha, r=r, G=G, b=b)
+
+
+def _loops_forward(p):
+    """Pure-Python triple loops straight from the definition (tiny shapes only)."""
+    x, codes, s, z, A, B = p["x"], p["codes"], p["s"], p["z"], p["A"], p["B"]
+    M, K = x.shape
+    N = codes.shape[0]
+    r, G = p["r"], p["G"]
+    y = [[0.0] * N for _ in range(M)]
+    for m in range(M):
+        t = [sum(float(x[m, k]) * float(A[j, k]) for k in range(K)) for j in range(r)]
+        for n in range(N):
+            acc = 0.0
+            for k in range(K):
+                w = float(s[n, k // G]) * (float(codes[n, k]) - float(z[n, k // G]))
+                acc += float(x[m, k]) * w
+            lo = sum(t[j] * float(B[n, j]) for j in range(r))
+            y[m][n] = acc + (p["alpha"] / r) * lo
+    return np.array(y)
+
+
+def _loops_backward(p):
+    x, dy, codes, s, z, A, B = p["x"], p["dy"], p["codes"], p["s"], p["z"], p["A"], p["B"]
+    M, K = x.shape
+    N = codes.shape[0]
+    r, G = p["r"], p["G"]
+    sc = p["alpha"] / r
+    dx = np.zeros((M, K))
+    dA = np.zeros((r, K))
+    dB = np.zeros((N, r))
+    for m in range(M):
+        t = [sum(float(x[m, k]) * float(A[j, k]) for k in range(K)) for j in range(r)]
+        u = [sum(float(dy[m, n]) * float(B[n, j]) for n in range(N)) for j in range(r)]
+        for k in range(K):
+            acc = 0.0
+            for n in range(N):
+                w = float(s[n, k // G]) * (float(codes[n, k]) - float(z[n, k // G]))
+                acc += float(dy[m, n]) * w
+            acc += sc * sum(u[j] * float(A[j, k]) for j in range(r))
+            dx[m, k] = acc
+        for j in range(r):
+            for k in range(K):
+                dA[j, k] += sc * u[j] * float(x[m, k])
+            for n in range(N):
+                dB[n, j] += sc * float(dy[m, n]) * t[j]
+    return dx, dA, dB
+
+
+# ---------------------------------------------------------------- forward
+
+@pytest.mark.parametrize("b,K,G", [(2, 32, 32), (3, 64, 32), (4, 96, 32), (8, 64, 32)])
+def test_forward_matches_python_loops(b, K, G):
+    p = _small_problem(100 + b, M=5, N=7, K=K, r=3, b=b, G=G)
+    y, t = oracle.forward(p["x"], p["Wd"], p["A"], p["B"], p["alpha"])
+    assert _rel(y, _loops_forward(p)) < RTOL
+    assert _rel(t, p["x"] @ p["A"].T) < RTOL
+
+
+def test_forward_with_B_zero_is_the_dequantised_gemm():
+    p = _small_problem(200, M=33, N=40, K=256, r=8, b=4, G=64)
+    y, _ = oracle.forward(p["x"], p["Wd"], p["A"], np.zeros_like(p["B"]), p["alpha"])
+    assert _rel(y, p["x"] @ _np_dequant(p["codes"], p["s"], p["z"], p["G"]).T) < RTOL
+
+
+def test_forward_full_against_numpy_float64():
+    p = _small_problem(201, M=21, N=48, K=384, r=16, b=3, G=128, alpha=32.0)
+    y, t = oracle.forward(p["x"], p["Wd"], p["A"], p["B"], p["alpha"])
+    W = _np_dequant(p["codes"], p["s"], p["z"], p["G"])
+    ref = p["x"] @ W.T + (p["alpha"] / p["r"]) * (p["x"] @ p["A"].T) @ p["B"].T
+    assert _rel(y, ref) < RTOL
+
+
+def test_forward_codes_equal_zero_point_leaves_only_the_lora_branch():
+    p = _small_problem(202, M=9, N=16, K=64, r=8, b=2, G=32)
+    g = np.arange(64) // 32
+    codes = p["z"][:, g]                                    # q == z everywhere -> Wd == 0
+    Wd = oracle.dequant(oracle.pack(codes, 2), p["s"], p["z"], 64, 2, 32)
+    assert np.all(Wd == 0.0)
+    y, _ = oracle.forward(p["x"], Wd, p["A"], p["B"], p["alpha"])
+    assert _rel(y, 2.0 * (p["x"] @ p["A"].T) @ p["B"].T) < RTOL     # alpha/r = 16/8
+
+
+def test_forward_rank_zero_is_plain_quantised_linear():
+    p = _small_problem(203, M=6, N=8, K=64, r=8, b=4, G=32)
+    y, t = oracle.forward(p["x"], p["Wd"], np.zeros((0, 64)), np.zeros((8, 0)), 16.0)
+    assert t.shape == (6, 0)
+    assert _rel(y, p["x"] @ p["Wd"].T) < RTOL
+
+
+def test_forward_is_linear_in_x():
+    p = _small_problem(204, M=12, N=24, K=128, r=8, b=4, G=64)
+    x2 = wl.normal(999, 12 * 128).reshape(12, 128)
+    f = lambda v: oracle.forward(v, p["Wd"], p["A"], p["B"], p["alpha"])[0]
+    assert _rel(f(p["x"] + x2), f(p["x"]) + f(x2)) < RTOL
+    assert _rel(f(3.0 * p["x"]), 3.0 * f(p["x"])) < RTOL
+
+
+def test_forward_integer_exact_case():
+    # s = 1, x in {-1,0,1}, no adapter contribution: y is an exactly representable integer.
+    M, N, K, b, G = 8, 16, 256, 2, 64
+    codes = wl.uniform_ints(300, N * K, 4).reshape(N, K)
+    z = wl.uniform_ints(301, N * (K // G), 4).reshape(N, K // G)
+    x = wl.uniform_ints(302, M * K, 3).reshape(M, K).astype(np.float64) - 1.0
+    Wd = oracle.dequant(oracle.pack(codes, b), np.ones((N, K // G)), z, K, b, G)
+    y, _ = oracle.forward(x, Wd, np.zeros((8, K)), wl.normal(5, N * 8).reshape(N, 8), 16.0)
+    g = np.arange(K) // G
+    want = x.astype(np.int64) @ (codes.astype(np.int64) - z[:, g].astype(np.int64)).T
+    assert np.array_equal(y, want.astype(np.float64))
+    assert np.abs(want).max() < 2048
+
+
+# --------------------------------------------------------------- backward
+
+@pytest.mark.parametrize("b,K,G", [(2, 32, 32), (3, 64, 32), (4, 96, 32), (8, 64, 32)])
+def test_backward_matches_python_loops(b, K, G):
+    p = _small_problem(400 + b, M=4, N=6, K=K, r=3, b=b, G=G)
+    dx = oracle.backward_dx(p["dy"], p["Wd"], p["A"], p["B"], p["alpha"])
+    dA, dB = oracle.backward_adapters(p["dy"], p["x"], p["A"], p["B"], p["alpha"])
+    ldx, ldA, ldB = _loops_backward(p)
+    assert _rel(dx, ldx) < RTOL and _rel(dA, ldA) < RTOL and _rel(dB, ldB) < RTOL
+
+
+def test_backward_against_numpy_float64():
+    p = _small_problem(500, M=19, N=40, K=256, r=8, b=4, G=128)
+    sc = p["alpha"] / p["r"]
+    W = _np_dequant(p["codes"], p["s"], p["z"], p["G"])
+    dx = oracle.backward_dx(p["dy"], p["Wd"], p["A"], p["B"], p["alpha"])
+    dA, dB = oracle.backward_adapters(p["dy"], p["x"], p["A"], p["B"], p["alpha"])
+    assert _rel(dx, p["dy"] @ W + sc * (p["dy"] @ p["B"]) @ p["A"]) < RTOL
+    assert _rel(dA, sc * (p["dy"] @ p["B"]).T @ p["x"]) < RTOL
+    assert _rel(dB, sc * p["dy"].T @ (p["x"] @ p["A"].T)) < RTOL
+    assert dA.shape == p["A"].shape and dB.shape == p["B"].shape and dx.shape == p["x"].shape
+
+
+def test_backward_finite_differences():
+    # L = <dY, y> is linear in each of x, A, B, so central differences are exact to rounding.
+    p = _small_problem(600, M=5, N=9, K=64, r=4, b=3, G=32)
+    L = lambda x, A, B: float(np.sum(p["dy"] * oracle.forward(x, p["Wd"], A, B, p["alpha"])[0]))
+    dx = oracle.backward_dx(p["dy"], p["Wd"], p["A"], p["B"], p["alpha"])
+    dA, dB = oracle.backward_adapters(p["dy"], p["x"], p["A"], p["B"], p["alpha"])
+    h = 1e-3
+    rng = np.random.RandomState(0)
+    for name, grad in (("x", dx), ("A", dA), ("B", dB)):
+        for _ in range(12):
+            idx = tuple(rng.randint(0, s) for s in grad.shape)
+            args = {k: p[k].copy() for k in ("x", "A", "B")}
+            args[name][idx] += h
+            up = L(args["x"], args["A"], args["B"])
+            args[name][idx] -= 2 * h
+            dn = L(args["x"], args["A"], args["B"])
+            fd = (up - dn) / (2 * h)
+            assert abs(fd - grad[idx]) <= 1e-8 * max(1.0, abs(fd)), (name, idx, fd, grad[idx])
+
+
+def test_backward_adjoint_identities():
+    p = _small_problem(700, M=11, N=24, K=128, r=8, b=4, G=64)
+    fwd = lambda x, A, B: oracle.forward(x, p["Wd"], A, B, p["alpha"])[0]
+    dx = oracle.backward_dx(p["dy"], p["Wd"], p["A"], p["B"], p["alpha"])
+    dA, dB = oracle.backward_adapters(p["dy"], p["x"], p["A"], p["B"], p["alpha"])
+    y0 = fwd(p["x"], p["A"], p["B"])
+    v = wl.normal(701, p["x"].size).reshape(p["x"].shape)
+    VA = wl.normal(702, p["A"].size).reshape(p["A"].shape)
+    VB = wl.normal(703, p["B"].size).reshape(p["B"].shape)
+    lhs_x = np.sum(p["dy"] * (fwd(p["x"] + v, p["A"], p["B"]) - y0))
+    lhs_A = np.sum(p["dy"] * (fwd(p["x"], p["A"] + VA, p["B"]) - y0))
+    lhs_B = np.sum(p["dy"] * (fwd(p["x"], p["A"], p["B"] + VB) - y0))
+    assert abs(lhs_x - np.sum(dx * v)) < 1e-9 * abs(lhs_x)
+    assert abs(lhs_A - np.sum(dA * VA)) < 1e-9 * abs(lhs_A)
+    assert abs(lhs_B - np.sum(dB * VB)) < 1e-9 * abs(lhs_B)
+
+
+def test_backward_special_cases():
+    p = _small_problem(800, M=7, N=16, K=64, r=8, b=4, G=32)
+    Z_B = np.zeros_like(p["B"])
+    Z_A = np.zeros_like(p["A"])
+    dA, dB = oracle.backward_adapters(p["dy"], p["x"], p["A"], Z_B, p["alpha"])
+    assert np.all(dA == 0.0) and np.any(dB != 0.0)                  # B = 0  =>  dA = 0
+    dx = oracle.backward_dx(p["dy"], p["Wd"], p["A"], Z_B, p["alpha"])
+    assert _rel(dx, p["dy"] @ p["Wd"]) < RTOL                        # and dX is the pure dY Wd
+    dA, dB = oracle.backward_adapters(p["dy"], p["x"], Z_A, p["B"], p["alpha"])
+    assert np.all(dB == 0.0) and np.any(dA != 0.0)                  # A = 0  =>  dB = 0
+
+
+def test_layer_oracle_row_subsets_equal_full_rows():
+    inp = wl.make_inputs(wl.config1())
+    c = inp.cfg
+    lo = oracle.LayerOracle(inp.codes, inp.scales, inp.zeros, inp.A, inp.B, bits=c.bits,
+                            group_size=c.group_size, alpha=c.alpha, dtype=c.dtype)
+    y, t = lo.forward(inp.x)
+    rows = np.array([3, 17, 63])
+    ys, ts = lo.forward(inp.x, rows)
+    assert np.array_equal(ys, y[rows]) and np.array_equal(ts, t[rows])
+    dx = lo.backward_dx(inp.dy)
+    assert np.array_equal(lo.backward_dx(inp.dy, rows), dx[rows])
+    # config 1 against numpy on the widened stored values
+    W = _np_dequant(inp.codes, oracle.widen(inp.scales, "f16"), inp.zeros, c.group_size)
+    X = oracle.widen(inp.x, "f16")
+    ref = X @ W.T + 2.0 * (X @ oracle.widen(inp.A, "f16").T) @ oracle.widen(inp.B, "f16").T
+    assert _rel(y, ref) < RTOL
