@@ -1,0 +1,122 @@
+/*
+ * qlora.h -- C ABI of the MI355X (gfx950) quantized LoRA linear layer.
+ *
+ * The layer is the one every projection of a GPTQ-quantized, LoRA-injected
+ * LLaMA runs through during fine-tuning (EMEF) and error correction (LREC):
+ *
+ *   forward   y  = x deq(W_q)^T + (alpha/r) (x A^T) B^T            (paper Fig. 1, Sec. 3.1)
+ *   backward  dX = dY deq(W_q) + (alpha/r) (dY B) A                (Sec. 3.1, "Implementation Details":
+ *                                                                   the packed weight is consumed transposed,
+ *                                                                   unpack + transpose + matmul in one kernel)
+ *             dA = (alpha/r) (dY B)^T x,   dB = (alpha/r) dY^T (x A^T)
+ *   The quantized weight is frozen: no gradient for codes, scales, zeros (Sec. 3.1).
+ *
+ * Symbols: M tokens, K in-features, N out-features, b bits per code,
+ * G group size along K, r LoRA rank, alpha the "linear stretch" (Appendix B).
+ *
+ *   deq(W_q)[n,k] = s[n, k/G] * (q[n,k] - z[n, k/G])
+ *
+ * Storage (all row-major, dense, no strides):
+ *   packed  uint32 [N, Kw], Kw = K*b/32.  Each row is a little-endian bit stream
+ *           along K: code k occupies stream bits [b*k, b*k+b); stream bit p is
+ *           bit (p mod 32) of word (p div 32).  b in {2,4,8}: 32/b codes per
+ *           word; b = 3: codes straddle word boundaries.
+ *   scales  fp16   [N, K/G]   (fp16 for both activation dtypes)
+ *   zeros   uint8  [N, K/G]   zero-point as an unsigned code in [0, 2^b)
+ *   x, y, dY, dX, A [r,K], B [N,r], t [M,r]: 16-bit floats of `dtype`
+ *   dA [r,K], dB [N,r]: fp32
+ *
+ * Every pointer is a DEVICE pointer (HIP, current device) unless stated
+ * otherwise; the caller owns all buffers; the library allocates nothing and
+ * keeps no state between calls.  Base pointers must be 16-byte aligned.
+ * `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls
+ * enqueue work on `stream` and return without synchronising.
+ *
+ * Errors: every function returning int returns a qlora_status_t.  Arguments
+ * are validated on the host before anything is launched, so a status other
+ * than QLORA_OK / QLORA_E_HIP means no device memory was written.
+ *
+ * Accepted domain: bits in {2,3,4,8}; K % 32 == 0; group_size % 32 == 0 and
+ * K % group_size == 0 (group_size == K is per-row quantisation); N % 8 == 0;
+ * rank in {0, 8, 16, ..., 64}; M >= 1; dtype f16 or bf16.  rank == 0 means the
+ * projection carries no adapter: A, B, t, dA, dB are ignored (may be NULL).
+ */
+#ifndef QLORA_H
+#define QLORA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { QLORA_F16 = 0, QLORA_BF16 = 1 } qlora_dtype_t;
+
+typedef enum {
+    QLORA_OK = 0,
+    QLORA_E_NULL = 1,       /* a required pointer is NULL */
+    QLORA_E_BITS = 2,       /* bits not in {2,3,4,8} */
+    QLORA_E_SHAPE = 3,      /* M < 1, K % 32 != 0, N % 8 != 0, or a size overflows */
+    QLORA_E_GROUP = 4,      /* group_size % 32 != 0 or K % group_size != 0 */
+    QLORA_E_RANK = 5,       /* rank not in {0, 8, ..., 64} */
+    QLORA_E_DTYPE = 6,      /* dtype not QLORA_F16 / QLORA_BF16 */
+    QLORA_E_ALIGN = 7,      /* a pointer is not 16-byte aligned */
+    QLORA_E_WORKSPACE = 8,  /* workspace NULL or smaller than qlora_workspace_bytes() */
+    QLORA_E_HIP = 9         /* the HIP runtime reported an error at launch */
+} qlora_status_t;
+
+/* Host pointer to a static, NUL-terminated description of `status`. */
+const char *qlora_status_string(int status);
+
+/* Number of uint32 words of the packed matrix, N * K*bits/32; 0 if the arguments are invalid. */
+size_t qlora_packed_words(int N, int K, int bits);
+
+/*
+ * Bytes of device scratch qlora_linear_fwd / qlora_linear_bwd need for this
+ * problem (the larger of the two); 0 if the arguments are invalid.  The
+ * workspace holds t = x A^T and u = dY B when they are not passed in, and the
+ * per-slice partial sums of dA and dB (summed in a fixed order, so results are
+ * bitwise reproducible run to run).
+ */
+size_t qlora_workspace_bytes(int M, int N, int K, int bits, int group_size, int rank);
+
+/*
+ * Bit-pack codes [N,K] (uint8, each < 2^bits) into packed [N,Kw] (layout above;
+ * Sec. 3.1: the quantized weight is kept as a bit-packed INT32 matrix).
+ * Done once per projection at load time.  Codes above 2^bits-1 are masked.
+ */
+int qlora_pack(const uint8_t *codes, uint32_t *packed, int N, int K, int bits, void *stream);
+
+/* Inverse of qlora_pack ("standard unpacking", Sec. 3.1): packed [N,Kw] -> codes [N,K]. */
+int qlora_unpack(const uint32_t *packed, uint8_t *codes, int N, int K, int bits, void *stream);
+
+/*
+ * Forward pass (Fig. 1, forward path).  Writes y [M,N] (rounded to `dtype`
+ * from fp32 accumulators).  If t_save is not NULL it receives t = x A^T [M,r]
+ * in `dtype` for later use by qlora_linear_bwd; otherwise t lives in the
+ * workspace only.  Dequantisation is fused into the GEMM: no dequantised copy
+ * of the weight is written to memory.
+ */
+int qlora_linear_fwd(const void *x, const uint32_t *packed, const void *scales, const uint8_t *zeros,
+                     const void *A, const void *B, void *y, void *t_save,
+                     int M, int N, int K, int bits, int group_size, int rank, float alpha, int dtype,
+                     void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Backward pass (Fig. 1, backward path; Sec. 3.1).  Writes dx [M,K] in `dtype`,
+ * and, when rank > 0, dA [r,K] and dB [N,r] in fp32 (overwritten, not
+ * accumulated).  t_saved is the t_save of the matching forward call, or NULL to
+ * have t recomputed from x and A (what gradient checkpointing does).  x is
+ * needed for dA (and for recomputing t); with rank == 0 it may be NULL.
+ */
+int qlora_linear_bwd(const void *dy, const void *x, const uint32_t *packed, const void *scales,
+                     const uint8_t *zeros, const void *A, const void *B, const void *t_saved,
+                     void *dx, float *dA, float *dB,
+                     int M, int N, int K, int bits, int group_size, int rank, float alpha, int dtype,
+                     void *workspace, size_t workspace_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QLORA_H */

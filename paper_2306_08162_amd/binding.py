@@ -1,0 +1,136 @@
+"""Thin ctypes binding of libqlora.so: argument marshalling only.
+
+Function names and argument order mirror `include/qlora.h`.  Tensors are torch
+tensors used as plain device buffers (torch supplies memory and the stream, all
+arithmetic runs in the HIP kernels).  There is no fallback: if the library is
+missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libqlora.so")
+
+QLORA_F16, QLORA_BF16 = 0, 1
+STATUS_NAMES = ["QLORA_OK", "QLORA_E_NULL", "QLORA_E_BITS", "QLORA_E_SHAPE", "QLORA_E_GROUP", "QLORA_E_RANK",
+                "QLORA_E_DTYPE", "QLORA_E_ALIGN", "QLORA_E_WORKSPACE", "QLORA_E_HIP"]
+EXPORTS = ["qlora_status_string", "qlora_packed_words", "qlora_workspace_bytes", "qlora_pack", "qlora_unpack",
+           "qlora_linear_fwd", "qlora_linear_bwd"]
+
+_lib = None
+
+
+class QLoraError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        name = STATUS_NAMES[status] if 0 <= status < len(STATUS_NAMES) else str(status)
+        super().__init__(f"{where}: {name}: {status_string(status)}")
+
+
+def load() -> ctypes.CDLL:
+    """Load libqlora.so (building it first only if it is not there)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        from . import build as _build
+        _build.build()
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2306_08162_amd.build`")
+    lib = ctypes.CDLL(LIB_PATH)
+    c_int, c_sz, vp, f32 = ctypes.c_int, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_float
+    lib.qlora_status_string.restype = ctypes.c_char_p
+    lib.qlora_status_string.argtypes = [c_int]
+    lib.qlora_packed_words.restype = c_sz
+    lib.qlora_packed_words.argtypes = [c_int] * 3
+    lib.qlora_workspace_bytes.restype = c_sz
+    lib.qlora_workspace_bytes.argtypes = [c_int] * 6
+    lib.qlora_pack.restype = c_int
+    lib.qlora_pack.argtypes = [vp, vp, c_int, c_int, c_int, vp]
+    lib.qlora_unpack.restype = c_int
+    lib.qlora_unpack.argtypes = [vp, vp, c_int, c_int, c_int, vp]
+    lib.qlora_linear_fwd.restype = c_int
+    lib.qlora_linear_fwd.argtypes = [vp] * 8 + [c_int] * 6 + [f32, c_int, vp, c_sz, vp]
+    lib.qlora_linear_bwd.restype = c_int
+    lib.qlora_linear_bwd.argtypes = [vp] * 11 + [c_int] * 6 + [f32, c_int, vp, c_sz, vp]
+    _lib = lib
+    return lib
+
+
+def _ptr(t) -> Optional[int]:
+    """Device (or raw integer) pointer of a buffer; None stays NULL."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    if not t.is_contiguous():
+        raise ValueError("qlora buffers must be contiguous")
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream or None
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+def _nbytes(t) -> int:
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def status_string(status: int) -> str:
+    return load().qlora_status_string(int(status)).decode()
+
+
+def qlora_packed_words(N: int, K: int, bits: int) -> int:
+    return int(load().qlora_packed_words(N, K, bits))
+
+
+def qlora_workspace_bytes(M: int, N: int, K: int, bits: int, group_size: int, rank: int) -> int:
+    return int(load().qlora_workspace_bytes(M, N, K, bits, group_size, rank))
+
+
+def qlora_pack(codes, packed, N: int, K: int, bits: int, stream=None, check: bool = True) -> int:
+    st = load().qlora_pack(_ptr(codes), _ptr(packed), N, K, bits, _stream(stream))
+    if check and st != 0:
+        raise QLoraError(st, "qlora_pack")
+    return st
+
+
+def qlora_unpack(packed, codes, N: int, K: int, bits: int, stream=None, check: bool = True) -> int:
+    st = load().qlora_unpack(_ptr(packed), _ptr(codes), N, K, bits, _stream(stream))
+    if check and st != 0:
+        raise QLoraError(st, "qlora_unpack")
+    return st
+
+
+def qlora_linear_fwd(x, packed, scales, zeros, A, B, y, t_save, M: int, N: int, K: int, bits: int, group_size: int,
+                     rank: int, alpha: float, dtype: int, workspace, workspace_bytes: Optional[int] = None,
+                     stream=None, check: bool = True) -> int:
+    if workspace_bytes is None:
+        workspace_bytes = _nbytes(workspace)
+    st = load().qlora_linear_fwd(_ptr(x), _ptr(packed), _ptr(scales), _ptr(zeros), _ptr(A), _ptr(B), _ptr(y),
+                                 _ptr(t_save), M, N, K, bits, group_size, rank, float(alpha), dtype,
+                                 _ptr(workspace), workspace_bytes, _stream(stream))
+    if check and st != 0:
+        raise QLoraError(st, "qlora_linear_fwd")
+    return st
+
+
+def qlora_linear_bwd(dy, x, packed, scales, zeros, A, B, t_saved, dx, dA, dB, M: int, N: int, K: int, bits: int,
+                     group_size: int, rank: int, alpha: float, dtype: int, workspace,
+                     workspace_bytes: Optional[int] = None, stream=None, check: bool = True) -> int:
+    if workspace_bytes is None:
+        workspace_bytes = _nbytes(workspace)
+    st = load().qlora_linear_bwd(_ptr(dy), _ptr(x), _ptr(packed), _ptr(scales), _ptr(zeros), _ptr(A), _ptr(B),
+                                 _ptr(t_saved), _ptr(dx), _ptr(dA), _ptr(dB), M, N, K, bits, group_size, rank,
+                                 float(alpha), dtype, _ptr(workspace), workspace_bytes, _stream(stream))
+    if check and st != 0:
+        raise QLoraError(st, "qlora_linear_bwd")
+    return st

@@ -1,0 +1,180 @@
+// C ABI of the library: argument validation, workspace carve-up, kernel selection.
+// Nothing here touches the device before every argument has been checked.
+#include "../../include/qlora.h"
+#include "kernels.hpp"
+
+#include <hip/hip_runtime.h>
+
+using namespace qlora;
+
+namespace {
+
+constexpr size_t ALIGN = 256;
+
+inline size_t round_up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
+inline bool misaligned(const void *p) { return p != nullptr && (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+int check_weight_shape(int N, int K, int bits)
+{
+    if (bits != 2 && bits != 3 && bits != 4 && bits != 8) return QLORA_E_BITS;
+    if (N < 1 || K < 1 || K % 32 != 0 || N % 8 != 0) return QLORA_E_SHAPE;
+    if ((long long)N * K > (1ll << 40)) return QLORA_E_SHAPE;
+    return QLORA_OK;
+}
+
+int check_problem(int M, int N, int K, int bits, int G, int r, int dtype)
+{
+    int st = check_weight_shape(N, K, bits);
+    if (st != QLORA_OK) return st;
+    if (M < 1) return QLORA_E_SHAPE;
+    // element indices of the activations are kept in 32 bits inside the kernels
+    if ((long long)M * K >= (1ll << 31) || (long long)M * N >= (1ll << 31)) return QLORA_E_SHAPE;
+    if (G < 32 || G % 32 != 0 || K % G != 0) return QLORA_E_GROUP;
+    if (r < 0 || r > 64 || r % 8 != 0) return QLORA_E_RANK;
+    if (dtype != QLORA_F16 && dtype != QLORA_BF16) return QLORA_E_DTYPE;
+    return QLORA_OK;
+}
+
+struct Workspace {
+    size_t t_off, u_off, partial_off, total;
+};
+
+Workspace carve(int M, int N, int K, int r)
+{
+    Workspace w{};
+    size_t off = 0;
+    w.t_off = off;
+    off += round_up((size_t)M * r * 2);
+    w.u_off = off;
+    off += round_up((size_t)M * r * 2);
+    w.partial_off = off;
+    const size_t pa = (size_t)adapter_grad_slices(M, K, r) * K * r * sizeof(float);
+    const size_t pb = (size_t)adapter_grad_slices(M, N, r) * N * r * sizeof(float);
+    off += round_up(pa > pb ? pa : pb);
+    w.total = off < ALIGN ? ALIGN : off;
+    return w;
+}
+
+inline int hip_status()
+{
+    return hipGetLastError() == hipSuccess ? QLORA_OK : QLORA_E_HIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *qlora_status_string(int status)
+{
+    switch (status) {
+    case QLORA_OK: return "ok";
+    case QLORA_E_NULL: return "a required pointer is NULL";
+    case QLORA_E_BITS: return "bits must be 2, 3, 4 or 8";
+    case QLORA_E_SHAPE: return "bad shape: need M >= 1, K % 32 == 0, N % 8 == 0 and sizes below 2^31 elements";
+    case QLORA_E_GROUP: return "bad group size: need group_size % 32 == 0 and K % group_size == 0";
+    case QLORA_E_RANK: return "rank must be 0 or a multiple of 8 up to 64";
+    case QLORA_E_DTYPE: return "dtype must be QLORA_F16 (0) or QLORA_BF16 (1)";
+    case QLORA_E_ALIGN: return "a pointer is not 16-byte aligned";
+    case QLORA_E_WORKSPACE: return "workspace is NULL or smaller than qlora_workspace_bytes()";
+    case QLORA_E_HIP: return "the HIP runtime reported an error";
+    default: return "unknown status";
+    }
+}
+
+size_t qlora_packed_words(int N, int K, int bits)
+{
+    if (check_weight_shape(N, K, bits) != QLORA_OK) return 0;
+    return (size_t)N * ((size_t)K * bits / 32);
+}
+
+size_t qlora_workspace_bytes(int M, int N, int K, int bits, int group_size, int rank)
+{
+    if (check_problem(M, N, K, bits, group_size, rank, QLORA_F16) != QLORA_OK) return 0;
+    return carve(M, N, K, rank).total;
+}
+
+int qlora_pack(const uint8_t *codes, uint32_t *packed, int N, int K, int bits, void *stream)
+{
+    const int st = check_weight_shape(N, K, bits);
+    if (st != QLORA_OK) return st;
+    if (!codes || !packed) return QLORA_E_NULL;
+    if (misaligned(codes) || misaligned(packed)) return QLORA_E_ALIGN;
+    launch_pack(codes, packed, N, K, bits, (hipStream_t)stream);
+    return hip_status();
+}
+
+int qlora_unpack(const uint32_t *packed, uint8_t *codes, int N, int K, int bits, void *stream)
+{
+    const int st = check_weight_shape(N, K, bits);
+    if (st != QLORA_OK) return st;
+    if (!codes || !packed) return QLORA_E_NULL;
+    if (misaligned(codes) || misaligned(packed)) return QLORA_E_ALIGN;
+    launch_unpack(packed, codes, N, K, bits, (hipStream_t)stream);
+    return hip_status();
+}
+
+int qlora_linear_fwd(const void *x, const uint32_t *packed, const void *scales, const uint8_t *zeros, const void *A,
+                     const void *B, void *y, void *t_save, int M, int N, int K, int bits, int group_size, int rank,
+                     float alpha, int dtype, void *workspace, size_t workspace_bytes, void *stream)
+{
+    const int st = check_problem(M, N, K, bits, group_size, rank, dtype);
+    if (st != QLORA_OK) return st;
+    if (!x || !packed || !scales || !zeros || !y) return QLORA_E_NULL;
+    if (rank > 0 && (!A || !B)) return QLORA_E_NULL;
+    if (misaligned(x) || misaligned(packed) || misaligned(scales) || misaligned(zeros) || misaligned(y) ||
+        misaligned(A) || misaligned(B) || misaligned(t_save) || misaligned(workspace))
+        return QLORA_E_ALIGN;
+    const Workspace w = carve(M, N, K, rank);
+    if (!workspace || workspace_bytes < w.total) return QLORA_E_WORKSPACE;
+
+    const hipStream_t s = (hipStream_t)stream;
+    const Problem p{M, N, K, bits, group_size, rank, rank > 0 ? alpha / (float)rank : 0.f, dtype == QLORA_BF16};
+    char *ws = (char *)workspace;
+    void *t = nullptr;
+    if (rank > 0) {
+        t = t_save ? t_save : (void *)(ws + w.t_off);
+        launch_lora_down(x, A, t, M, K, rank, p.bf16, s);
+    }
+    launch_fwd_generic(p, x, packed, scales, zeros, t, B, y, s);
+    return hip_status();
+}
+
+int qlora_linear_bwd(const void *dy, const void *x, const uint32_t *packed, const void *scales, const uint8_t *zeros,
+                     const void *A, const void *B, const void *t_saved, void *dx, float *dA, float *dB, int M, int N,
+                     int K, int bits, int group_size, int rank, float alpha, int dtype, void *workspace,
+                     size_t workspace_bytes, void *stream)
+{
+    const int st = check_problem(M, N, K, bits, group_size, rank, dtype);
+    if (st != QLORA_OK) return st;
+    if (!dy || !packed || !scales || !zeros || !dx) return QLORA_E_NULL;
+    if (rank > 0 && (!x || !A || !B || !dA || !dB)) return QLORA_E_NULL;
+    if (misaligned(dy) || misaligned(x) || misaligned(packed) || misaligned(scales) || misaligned(zeros) ||
+        misaligned(A) || misaligned(B) || misaligned(t_saved) || misaligned(dx) || misaligned(dA) || misaligned(dB) ||
+        misaligned(workspace))
+        return QLORA_E_ALIGN;
+    const Workspace w = carve(M, N, K, rank);
+    if (!workspace || workspace_bytes < w.total) return QLORA_E_WORKSPACE;
+
+    const hipStream_t s = (hipStream_t)stream;
+    const Problem p{M, N, K, bits, group_size, rank, rank > 0 ? alpha / (float)rank : 0.f, dtype == QLORA_BF16};
+    char *ws = (char *)workspace;
+    void *u = nullptr;
+    if (rank > 0) {
+        u = ws + w.u_off;
+        launch_lora_u(dy, B, u, M, N, rank, p.bf16, s);
+    }
+    launch_bwd_dx_generic(p, dy, packed, scales, zeros, u, A, dx, s);
+    if (rank > 0) {
+        const void *t = t_saved;
+        if (!t) {
+            launch_lora_down(x, A, ws + w.t_off, M, K, rank, p.bf16, s);
+            t = ws + w.t_off;
+        }
+        float *partial = (float *)(ws + w.partial_off);
+        launch_adapter_grad(dy, t, dB, partial, M, N, rank, p.sc, /*c_major=*/true, p.bf16, s);
+        launch_adapter_grad(x, u, dA, partial, M, K, rank, p.sc, /*c_major=*/false, p.bf16, s);
+    }
+    return hip_status();
+}
+
+}  // extern "C"

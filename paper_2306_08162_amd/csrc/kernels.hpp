@@ -1,0 +1,38 @@
+// Host-side launchers of the HIP kernels; one translation unit per kernel family.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace qlora {
+
+// One quantized LoRA linear problem, already validated by the C ABI layer.
+struct Problem {
+    int M, N, K;
+    int bits, G, r;
+    float sc;     // alpha / r (0 when r == 0)
+    bool bf16;    // activation / adapter dtype
+};
+
+// pack.hip
+void launch_pack(const uint8_t *codes, uint32_t *packed, int N, int K, int bits, hipStream_t s);
+void launch_unpack(const uint32_t *packed, uint8_t *codes, int N, int K, int bits, hipStream_t s);
+
+// adapters.hip -- the rank-r side products and the adapter gradients
+// t[M,r] = x[M,K] A[r,K]^T
+void launch_lora_down(const void *x, const void *A, void *t, int M, int K, int r, bool bf16, hipStream_t s);
+// u[M,r] = dy[M,N] B[N,r]
+void launch_lora_u(const void *dy, const void *B, void *u, int M, int N, int r, bool bf16, hipStream_t s);
+// Number of token slices the adapter-gradient reductions are cut into (fixed by the shape alone).
+int adapter_grad_slices(int M, int C, int r);
+// out = sc * act[M,C]^T side[M,r]; out is [C,r] (c_major) or [r,C]; partial holds slices*C*r floats.
+void launch_adapter_grad(const void *act, const void *side, float *out, float *partial, int M, int C, int r,
+                         float sc, bool c_major, bool bf16, hipStream_t s);
+
+// generic.hip -- shape-agnostic kernels (any K % 32 == 0), used when no tiled kernel applies
+void launch_fwd_generic(const Problem &p, const void *x, const uint32_t *packed, const void *scales,
+                        const uint8_t *zeros, const void *t, const void *B, void *y, hipStream_t s);
+void launch_bwd_dx_generic(const Problem &p, const void *dy, const uint32_t *packed, const void *scales,
+                           const uint8_t *zeros, const void *u, const void *A, void *dx, hipStream_t s);
+
+}  // namespace qlora

@@ -1,0 +1,94 @@
+"""Device-side plumbing for one layer: torch allocates HBM buffers, the HIP library does all the work.
+
+Used by the tests, the smoke check and the benchmark so that they all call the
+C ABI the same way.  Nothing here computes anything.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding as ql
+from .workloads import LayerConfig, LayerInputs
+
+
+def _dev(a: np.ndarray, device) -> torch.Tensor:
+    """Upload raw bytes; 16-bit patterns travel as int16, words as int32."""
+    if a.dtype == np.uint16:
+        a = a.view(np.int16)
+    elif a.dtype == np.uint32:
+        a = a.view(np.int32)
+    return torch.from_numpy(np.ascontiguousarray(a)).to(device)
+
+
+def _host16(t: torch.Tensor) -> np.ndarray:
+    return t.cpu().numpy().view(np.uint16)
+
+
+class DeviceLayer:
+    """One quantized LoRA projection resident in HBM."""
+
+    def __init__(self, inp: LayerInputs, device: str = "cuda:0", upload_activations: bool = True):
+        c: LayerConfig = inp.cfg
+        self.cfg = c
+        self.device = torch.device(device)
+        self.dtype_flag = ql.QLORA_BF16 if c.dtype == "bf16" else ql.QLORA_F16
+        self.codes = _dev(inp.codes, self.device)
+        self.scales = _dev(inp.scales, self.device)
+        self.zeros = _dev(inp.zeros, self.device)
+        self.A = _dev(inp.A, self.device) if c.rank else None
+        self.B = _dev(inp.B, self.device) if c.rank else None
+        self.packed = torch.empty((c.N, c.words_per_row), dtype=torch.int32, device=self.device)
+        ql.qlora_pack(self.codes, self.packed, c.N, c.K, c.bits)
+        self.x = _dev(inp.x, self.device) if upload_activations else None
+        self.dy = _dev(inp.dy, self.device) if upload_activations else None
+        self.y = torch.empty((c.M, c.N), dtype=torch.int16, device=self.device)
+        self.dx = torch.empty((c.M, c.K), dtype=torch.int16, device=self.device)
+        self.t = torch.empty((c.M, max(c.rank, 1)), dtype=torch.int16, device=self.device)
+        self.dA = torch.empty((max(c.rank, 1), c.K), dtype=torch.float32, device=self.device)
+        self.dB = torch.empty((c.N, max(c.rank, 1)), dtype=torch.float32, device=self.device)
+        nbytes = ql.qlora_workspace_bytes(c.M, c.N, c.K, c.bits, c.group_size, c.rank)
+        if nbytes == 0:
+            raise ValueError(f"shape not accepted by the library: {c}")
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+
+    # -- calls through the C ABI -------------------------------------------------
+    def forward(self, save_t: bool = True, stream=None):
+        c = self.cfg
+        ql.qlora_linear_fwd(self.x, self.packed, self.scales, self.zeros, self.A, self.B, self.y,
+                            self.t if (save_t and c.rank) else None, c.M, c.N, c.K, c.bits, c.group_size, c.rank,
+                            c.alpha, self.dtype_flag, self.workspace, stream=stream)
+
+    def backward(self, use_saved_t: bool = True, stream=None):
+        c = self.cfg
+        ql.qlora_linear_bwd(self.dy, self.x, self.packed, self.scales, self.zeros, self.A, self.B,
+                            self.t if (use_saved_t and c.rank) else None, self.dx,
+                            self.dA if c.rank else None, self.dB if c.rank else None,
+                            c.M, c.N, c.K, c.bits, c.group_size, c.rank, c.alpha, self.dtype_flag, self.workspace,
+                            stream=stream)
+
+    def unpack(self) -> np.ndarray:
+        c = self.cfg
+        out = torch.empty((c.N, c.K), dtype=torch.uint8, device=self.device)
+        ql.qlora_unpack(self.packed, out, c.N, c.K, c.bits)
+        torch.cuda.synchronize()
+        return out.cpu().numpy()
+
+    # -- downloads (raw 16-bit patterns / fp32) ------------------------------------
+    def host_packed(self) -> np.ndarray:
+        return self.packed.cpu().numpy().view(np.uint32)
+
+    def host_y(self) -> np.ndarray:
+        return _host16(self.y)
+
+    def host_dx(self) -> np.ndarray:
+        return _host16(self.dx)
+
+    def host_t(self) -> np.ndarray:
+        return _host16(self.t)
+
+    def host_dA(self) -> np.ndarray:
+        return self.dA.cpu().numpy()
+
+    def host_dB(self) -> np.ndarray:
+        return self.dB.cpu().numpy()

@@ -1,0 +1,131 @@
+"""Host-only checks of the C ABI: the library loads, exports what the header declares,
+and every argument error is reported before anything could reach a device."""
+import os
+import re
+
+import pytest
+
+from paper_2306_08162_amd import binding as ql
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000          # non-NULL, 16-byte aligned; never dereferenced because validation fails first
+ODD = 0x10008           # 8-byte aligned only
+
+
+def test_library_exports_every_declared_symbol():
+    lib = ql.load()
+    header = open(os.path.join(ROOT, "include", "qlora.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = sorted(set(re.findall(r"\b(qlora_[a-z_]+)\s*\(", header)))
+    assert declared == sorted(ql.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_status_strings():
+    assert ql.status_string(0) == "ok"
+    seen = {ql.status_string(i) for i in range(10)}
+    assert len(seen) == 10
+    assert ql.status_string(99) == "unknown status"
+
+
+def test_packed_words():
+    assert ql.qlora_packed_words(4096, 4096, 4) == 4096 * 512
+    assert ql.qlora_packed_words(4096, 11008, 3) == 4096 * 1032
+    assert ql.qlora_packed_words(11008, 4096, 2) == 11008 * 256
+    assert ql.qlora_packed_words(8, 32, 8) == 8 * 8
+    assert ql.qlora_packed_words(8, 32, 5) == 0
+    assert ql.qlora_packed_words(8, 48, 4) == 0
+    assert ql.qlora_packed_words(7, 32, 4) == 0
+
+
+def test_workspace_bytes():
+    w = ql.qlora_workspace_bytes(2048, 4096, 4096, 4, 128, 8)
+    assert w > 0 and w % 256 == 0
+    assert ql.qlora_workspace_bytes(2048, 4096, 4096, 4, 128, 0) > 0
+    assert ql.qlora_workspace_bytes(0, 4096, 4096, 4, 128, 8) == 0
+    assert ql.qlora_workspace_bytes(16, 4096, 4096, 4, 100, 8) == 0
+    assert ql.qlora_workspace_bytes(16, 4096, 4096, 4, 128, 12) == 0
+
+
+def _fwd(**kw):
+    a = dict(x=FAKE, packed=FAKE, scales=FAKE, zeros=FAKE, A=FAKE, B=FAKE, y=FAKE, t_save=None, M=16, N=64, K=128,
+             bits=4, group_size=64, rank=8, alpha=16.0, dtype=0, workspace=FAKE, workspace_bytes=0)
+    a.update(kw)
+    return ql.qlora_linear_fwd(a["x"], a["packed"], a["scales"], a["zeros"], a["A"], a["B"], a["y"], a["t_save"],
+                               a["M"], a["N"], a["K"], a["bits"], a["group_size"], a["rank"], a["alpha"], a["dtype"],
+                               a["workspace"], a["workspace_bytes"], stream=0, check=False)
+
+
+def _bwd(**kw):
+    a = dict(dy=FAKE, x=FAKE, packed=FAKE, scales=FAKE, zeros=FAKE, A=FAKE, B=FAKE, t_saved=None, dx=FAKE, dA=FAKE,
+             dB=FAKE, M=16, N=64, K=128, bits=4, group_size=64, rank=8, alpha=16.0, dtype=0, workspace=FAKE,
+             workspace_bytes=0)
+    a.update(kw)
+    return ql.qlora_linear_bwd(a["dy"], a["x"], a["packed"], a["scales"], a["zeros"], a["A"], a["B"], a["t_saved"],
+                               a["dx"], a["dA"], a["dB"], a["M"], a["N"], a["K"], a["bits"], a["group_size"],
+                               a["rank"], a["alpha"], a["dtype"], a["workspace"], a["workspace_bytes"], stream=0,
+                               check=False)
+
+
+E = {n: i for i, n in enumerate(ql.STATUS_NAMES)}
+
+
+@pytest.mark.parametrize("call", [_fwd, _bwd], ids=["fwd", "bwd"])
+def test_linear_argument_errors(call):
+    assert call(bits=5) == E["QLORA_E_BITS"]
+    assert call(bits=1) == E["QLORA_E_BITS"]
+    assert call(M=0) == E["QLORA_E_SHAPE"]
+    assert call(K=48) == E["QLORA_E_SHAPE"]
+    assert call(N=60) == E["QLORA_E_SHAPE"]
+    assert call(M=1 << 20, K=4096) == E["QLORA_E_SHAPE"]
+    assert call(group_size=48) == E["QLORA_E_GROUP"]
+    assert call(group_size=96) == E["QLORA_E_GROUP"]      # 128 % 96 != 0
+    assert call(group_size=0) == E["QLORA_E_GROUP"]
+    assert call(rank=4) == E["QLORA_E_RANK"]
+    assert call(rank=72) == E["QLORA_E_RANK"]
+    assert call(rank=-8) == E["QLORA_E_RANK"]
+    assert call(dtype=2) == E["QLORA_E_DTYPE"]
+    assert call(packed=None) == E["QLORA_E_NULL"]
+    assert call(scales=None) == E["QLORA_E_NULL"]
+    assert call(zeros=None) == E["QLORA_E_NULL"]
+    assert call(A=None) == E["QLORA_E_NULL"]
+    assert call(B=None) == E["QLORA_E_NULL"]
+    assert call(packed=ODD) == E["QLORA_E_ALIGN"]
+    assert call(A=ODD) == E["QLORA_E_ALIGN"]
+    assert call(workspace=ODD) == E["QLORA_E_ALIGN"]
+    # everything valid except the workspace: still refused before any launch
+    assert call(workspace_bytes=0) == E["QLORA_E_WORKSPACE"]
+    assert call(workspace=None, workspace_bytes=1 << 30) == E["QLORA_E_WORKSPACE"]
+    need = ql.qlora_workspace_bytes(16, 64, 128, 4, 64, 8)
+    assert call(workspace_bytes=need - 1) == E["QLORA_E_WORKSPACE"]
+    # rank 0: adapters may be NULL, the check then moves on to the workspace
+    assert call(rank=0, A=None, B=None) == E["QLORA_E_WORKSPACE"]
+
+
+def test_fwd_bwd_specific_null_checks():
+    assert _fwd(x=None) == E["QLORA_E_NULL"]
+    assert _fwd(y=None) == E["QLORA_E_NULL"]
+    assert _bwd(dy=None) == E["QLORA_E_NULL"]
+    assert _bwd(dx=None) == E["QLORA_E_NULL"]
+    assert _bwd(dA=None) == E["QLORA_E_NULL"]
+    assert _bwd(dB=None) == E["QLORA_E_NULL"]
+    assert _bwd(x=None) == E["QLORA_E_NULL"]
+    assert _bwd(rank=0, x=None, A=None, B=None, dA=None, dB=None) == E["QLORA_E_WORKSPACE"]
+    assert _bwd(dA=ODD) == E["QLORA_E_ALIGN"]
+
+
+def test_pack_unpack_argument_errors():
+    for fn in (ql.qlora_pack, ql.qlora_unpack):
+        assert fn(FAKE, FAKE, 8, 64, 5, stream=0, check=False) == E["QLORA_E_BITS"]
+        assert fn(FAKE, FAKE, 8, 40, 4, stream=0, check=False) == E["QLORA_E_SHAPE"]
+        assert fn(FAKE, FAKE, 0, 64, 4, stream=0, check=False) == E["QLORA_E_SHAPE"]
+        assert fn(None, FAKE, 8, 64, 4, stream=0, check=False) == E["QLORA_E_NULL"]
+        assert fn(FAKE, None, 8, 64, 4, stream=0, check=False) == E["QLORA_E_NULL"]
+        assert fn(ODD, FAKE, 8, 64, 4, stream=0, check=False) == E["QLORA_E_ALIGN"]
+
+
+def test_error_raises_with_check():
+    with pytest.raises(ql.QLoraError) as ei:
+        ql.qlora_pack(FAKE, FAKE, 8, 64, 7, stream=0)
+    assert ei.value.status == E["QLORA_E_BITS"]
