@@ -1,0 +1,177 @@
+#!/usr/bin/env python3
+"""Benchmark of the quantized LoRA linear layer on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+A step is one forward plus one backward of the whole hot path (all kernels the C ABI launches) on the
+LLaMA-7B q_proj workload: K = N = 4096, M = 2048 tokens, INT4 codes, group size 128, LoRA r = 8, fp16.
+Inputs are synthetic, seeded, and resident in HBM before the timed region.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_MFMA_F16_TFLOPS = 2516.6   # 256 CU x 4096 flop/clk/CU x 2.4 GHz, dense fp16/bf16
+PEAK_HBM_GBPS = 8000.0
+
+
+def _mean(v):
+    return sum(v) / len(v)
+
+
+def run_headline(steps: int, warmup: int):
+    import torch
+    from paper_2306_08162_amd import binding as ql
+    from paper_2306_08162_amd import workloads as wl
+    from paper_2306_08162_amd.device import DeviceLayer
+    from paper_2306_08162_amd.hiprt import Event
+
+    cfg = wl.config2()
+    inp = wl.make_inputs(cfg)
+    layer = DeviceLayer(inp, "cuda:0")
+    stream = torch.cuda.current_stream().cuda_stream or None
+
+    for _ in range(warmup):
+        layer.forward()
+        layer.backward()
+    torch.cuda.synchronize()
+
+    ev = [[Event() for _ in range(4)] for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        ql.qlora_profile_gemm(ev[i][0].handle, ev[i][1].handle)
+        layer.forward(stream=stream or 0)
+        ql.qlora_profile_gemm(ev[i][2].handle, ev[i][3].handle)
+        layer.backward(stream=stream or 0)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ql.qlora_profile_gemm(None, None)
+
+    ms_per_step = (t1 - t0) * 1e3 / steps
+    fwd_ms = _mean([e[0].elapsed_ms(e[1]) for e in ev])
+    bwd_ms = _mean([e[2].elapsed_ms(e[3]) for e in ev])
+    return cfg, inp, layer, ms_per_step, fwd_ms, bwd_ms
+
+
+def run_small_m(M: int = 16, iters: int = 3):
+    """Packed-weight GB/s at M tokens: sweep a pool of distinct weight sets (> 1 GB, larger than the
+    256 MB last-level cache) back to back, forward and backward, so every pass streams its weights from HBM."""
+    import torch
+    from paper_2306_08162_amd import workloads as wl
+    from paper_2306_08162_amd.device import DeviceLayer
+    from paper_2306_08162_amd.hiprt import Event
+
+    cfg = wl.config2().with_tokens(M)
+    inp = wl.make_inputs(cfg)
+    base = DeviceLayer(inp, "cuda:0")
+    pool_n = 1 + (1 << 30) // cfg.weight_side_bytes
+    packed = [base.packed] + [base.packed.clone() for _ in range(pool_n - 1)]
+    scales = [base.scales] + [base.scales.clone() for _ in range(pool_n - 1)]
+    zeros = [base.zeros] + [base.zeros.clone() for _ in range(pool_n - 1)]
+    stream = torch.cuda.current_stream().cuda_stream or 0
+
+    def sweep(fn):
+        for i in range(pool_n):
+            base.packed, base.scales, base.zeros = packed[i], scales[i], zeros[i]
+            fn(stream=stream)
+
+    out = {}
+    for name, fn in (("fwd", base.forward), ("bwd", base.backward)):
+        sweep(fn)                       # warm-up (also the first touch of every buffer)
+        torch.cuda.synchronize()
+        e0, e1 = Event(), Event()
+        e0.record(stream or None)
+        for _ in range(iters):
+            sweep(fn)
+        e1.record(stream or None)
+        e1.synchronize()
+        us = e0.elapsed_ms(e1) * 1e3 / (iters * pool_n)
+        out[name] = {"us_per_pass": round(us, 3),
+                     "packed_weight_GBps": round(cfg.weight_side_bytes / us * 1e-3, 1)}
+    out["pool_weight_sets"] = pool_n
+    out["weight_side_bytes"] = cfg.weight_side_bytes
+    both = out["fwd"]["us_per_pass"] + out["bwd"]["us_per_pass"]
+    out["fwd_bwd_packed_weight_GBps"] = round(2 * cfg.weight_side_bytes / both * 1e-3, 1)
+    out["frac_of_hbm_peak"] = round(out["fwd_bwd_packed_weight_GBps"] / PEAK_HBM_GBPS, 4)
+    return out
+
+
+def run_cpu_baseline(inp, max_rows: int):
+    """The fp64 oracle as it stands, on the host cores: forward + backward on the first `max_rows` token rows."""
+    import oracle
+    c = inp.cfg
+    rows = min(c.M, max_rows)
+    t0 = time.perf_counter()
+    lo = oracle.LayerOracle(inp.codes, inp.scales, inp.zeros, inp.A, inp.B, bits=c.bits, group_size=c.group_size,
+                            alpha=c.alpha, dtype=c.dtype)
+    lo.forward(inp.x[:rows])
+    lo.backward_dx(inp.dy[:rows])
+    lo.backward_adapters(inp.dy[:rows], inp.x[:rows])
+    dt = time.perf_counter() - t0
+    flops = 4 * rows * c.N * c.K + 6 * rows * c.rank * (c.K + c.N)
+    return {"value": round(flops / dt / 1e12, 5), "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"fp64 C/OpenMP oracle, unpack+dequant+fwd+bwd on the first {rows} of {c.M} token rows of the "
+                      f"same workload, {dt:.1f} s"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--cpu-rows", type=int, default=2048, help="token rows the CPU oracle baseline is timed on")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-small-m", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (the layer has no multi-GPU path); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    cfg, inp, layer, ms_per_step, fwd_ms, bwd_ms = run_headline(args.steps, args.warmup)
+    flops = cfg.flops_fwd_bwd
+    value = flops / (ms_per_step * 1e-3) / 1e12
+
+    # dominant kernel: the fused dequantise + MFMA GEMM (one launch per pass); take the slower of the two
+    gemm_flops = {"fwd": 2 * cfg.M * cfg.N * cfg.K + 2 * cfg.M * cfg.rank * cfg.N,
+                  "bwd": 2 * cfg.M * cfg.N * cfg.K + 2 * cfg.M * cfg.rank * cfg.K}
+    gemm_ms = {"fwd": fwd_ms, "bwd": bwd_ms}
+    dom = "bwd" if bwd_ms >= fwd_ms else "fwd"
+    achieved = gemm_flops[dom] / (gemm_ms[dom] * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": f"qgemm_kernel ({dom} GEMM, INT4 fp16)", "achieved": round(achieved, 2),
+                "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_MFMA_F16_TFLOPS, 4),
+                "traffic": None,
+                "kernel_us": {k: round(v * 1e3, 2) for k, v in gemm_ms.items()},
+                "kernel_tflops": {k: round(gemm_flops[k] / (gemm_ms[k] * 1e-3) / 1e12, 2) for k in gemm_ms}}
+
+    result = {
+        "metric": "quant-LoRA linear fwd+bwd TFLOP/s (4096^2, M=2048) + packed-weight GB/s @ M=16",
+        "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": cfg.name, "M": cfg.M, "K": cfg.K, "N": cfg.N, "bits": cfg.bits,
+                   "group_size": cfg.group_size, "rank": cfg.rank, "alpha": cfg.alpha,
+                   "flops_per_step": flops},
+        "frac_of_mfma_peak": round(value / PEAK_MFMA_F16_TFLOPS, 4),
+        "roofline": roofline,
+    }
+    if not args.no_small_m:
+        del layer
+        result["small_m"] = {"M": 16, "workload": "c2 weights (INT4 4096x4096, G=128, r=8), M=16", **run_small_m(16)}
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = run_cpu_baseline(inp, args.cpu_rows)
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -116,6 +116,15 @@ int qlora_linear_bwd(const void *dy, const void *x, const uint32_t *packed, cons
                      int M, int N, int K, int bits, int group_size, int rank, float alpha, int dtype,
                      void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Instrumentation for benchmarks (not part of the layer, not thread-safe): while a pair of hipEvent_t
+ * handles is set, every qlora_linear_fwd / qlora_linear_bwd call records ev_before on its stream right
+ * before its GEMM kernel (the fused dequantise + MFMA kernel that dominates the pass) and ev_after right
+ * after it, so a caller can time that kernel alone inside a whole-pass timed region.  Pass NULL, NULL to
+ * clear.  Host pointers (event handles).  Always returns QLORA_OK.
+ */
+int qlora_profile_gemm(void *ev_before, void *ev_after);
+
 #ifdef __cplusplus
 }
 #endif

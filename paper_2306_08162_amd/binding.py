@@ -18,7 +18,7 @@ QLORA_F16, QLORA_BF16 = 0, 1
 STATUS_NAMES = ["QLORA_OK", "QLORA_E_NULL", "QLORA_E_BITS", "QLORA_E_SHAPE", "QLORA_E_GROUP", "QLORA_E_RANK",
                 "QLORA_E_DTYPE", "QLORA_E_ALIGN", "QLORA_E_WORKSPACE", "QLORA_E_HIP"]
 EXPORTS = ["qlora_status_string", "qlora_packed_words", "qlora_workspace_bytes", "qlora_pack", "qlora_unpack",
-           "qlora_linear_fwd", "qlora_linear_bwd"]
+           "qlora_linear_fwd", "qlora_linear_bwd", "qlora_profile_gemm"]
 
 _lib = None
 
@@ -56,6 +56,8 @@ def load() -> ctypes.CDLL:
     lib.qlora_linear_fwd.argtypes = [vp] * 8 + [c_int] * 6 + [f32, c_int, vp, c_sz, vp]
     lib.qlora_linear_bwd.restype = c_int
     lib.qlora_linear_bwd.argtypes = [vp] * 11 + [c_int] * 6 + [f32, c_int, vp, c_sz, vp]
+    lib.qlora_profile_gemm.restype = c_int
+    lib.qlora_profile_gemm.argtypes = [vp, vp]
     _lib = lib
     return lib
 
@@ -94,6 +96,11 @@ def qlora_packed_words(N: int, K: int, bits: int) -> int:
 
 def qlora_workspace_bytes(M: int, N: int, K: int, bits: int, group_size: int, rank: int) -> int:
     return int(load().qlora_workspace_bytes(M, N, K, bits, group_size, rank))
+
+
+def qlora_profile_gemm(ev_before: Optional[int], ev_after: Optional[int]) -> int:
+    """Set (or clear with None, None) the raw hipEvent_t handles recorded around the GEMM kernel."""
+    return int(load().qlora_profile_gemm(ev_before, ev_after))
 
 
 def qlora_pack(codes, packed, N: int, K: int, bits: int, stream=None, check: bool = True) -> int:

@@ -55,6 +55,20 @@ Workspace carve(int M, int N, int K, int r)
     return w;
 }
 
+hipEvent_t g_ev_before = nullptr, g_ev_after = nullptr;   // benchmark instrumentation, see qlora_profile_gemm
+
+struct GemmTimer {   // records the two events around the scope when instrumentation is on
+    hipStream_t s;
+    explicit GemmTimer(hipStream_t st) : s(st)
+    {
+        if (g_ev_before) (void)hipEventRecord(g_ev_before, s);
+    }
+    ~GemmTimer()
+    {
+        if (g_ev_after) (void)hipEventRecord(g_ev_after, s);
+    }
+};
+
 inline int hip_status()
 {
     return hipGetLastError() == hipSuccess ? QLORA_OK : QLORA_E_HIP;
@@ -79,6 +93,13 @@ const char *qlora_status_string(int status)
     case QLORA_E_HIP: return "the HIP runtime reported an error";
     default: return "unknown status";
     }
+}
+
+int qlora_profile_gemm(void *ev_before, void *ev_after)
+{
+    g_ev_before = (hipEvent_t)ev_before;
+    g_ev_after = (hipEvent_t)ev_after;
+    return QLORA_OK;
 }
 
 size_t qlora_packed_words(int N, int K, int bits)
@@ -135,7 +156,10 @@ int qlora_linear_fwd(const void *x, const uint32_t *packed, const void *scales, 
         t = t_save ? t_save : (void *)(ws + w.t_off);
         launch_lora_down(x, A, t, M, K, rank, p.bf16, s);
     }
-    launch_fwd_generic(p, x, packed, scales, zeros, t, B, y, s);
+    {
+        GemmTimer timer(s);
+        launch_fwd_mfma(p, x, packed, scales, zeros, t, B, y, s);
+    }
     return hip_status();
 }
 
@@ -163,7 +187,10 @@ int qlora_linear_bwd(const void *dy, const void *x, const uint32_t *packed, cons
         u = ws + w.u_off;
         launch_lora_u(dy, B, u, M, N, rank, p.bf16, s);
     }
-    launch_bwd_dx_generic(p, dy, packed, scales, zeros, u, A, dx, s);
+    {
+        GemmTimer timer(s);
+        launch_bwd_dx_mfma(p, dy, packed, scales, zeros, u, A, dx, s);
+    }
     if (rank > 0) {
         const void *t = t_saved;
         if (!t) {

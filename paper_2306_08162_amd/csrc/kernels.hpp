@@ -35,4 +35,10 @@ void launch_fwd_generic(const Problem &p, const void *x, const uint32_t *packed,
 void launch_bwd_dx_generic(const Problem &p, const void *dy, const uint32_t *packed, const void *scales,
                            const uint8_t *zeros, const void *u, const void *A, void *dx, hipStream_t s);
 
+// gemm_mfma.hip -- tiled MFMA GEMMs with fused dequantisation (any accepted shape)
+void launch_fwd_mfma(const Problem &p, const void *x, const uint32_t *packed, const void *scales,
+                     const uint8_t *zeros, const void *t, const void *B, void *y, hipStream_t s);
+void launch_bwd_dx_mfma(const Problem &p, const void *dy, const uint32_t *packed, const void *scales,
+                        const uint8_t *zeros, const void *u, const void *A, void *dx, hipStream_t s);
+
 }  // namespace qlora
