@@ -28,7 +28,7 @@
  *
  * Every pointer is a DEVICE pointer (HIP, current device) unless stated
  * otherwise; the caller owns all buffers; the library allocates nothing and
- * keeps no state between calls.  Base pointers must be 16-byte aligned.
+ * keeps no state between calls (apart from the benchmark hook at the end).  Base pointers must be 16-byte aligned.
  * `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls
  * enqueue work on `stream` and return without synchronising.
  *
@@ -36,7 +36,8 @@
  * are validated on the host before anything is launched, so a status other
  * than QLORA_OK / QLORA_E_HIP means no device memory was written.
  *
- * Accepted domain: bits in {2,3,4,8}; K % 32 == 0; group_size % 32 == 0 and
+ * Accepted domain: bits in {2,3,4,8}; K % 32 == 0, K <= 2^20; N <= 2^24;
+ * M*K and M*N below 2^31 elements; group_size % 32 == 0 and
  * K % group_size == 0 (group_size == K is per-row quantisation); N % 8 == 0;
  * rank in {0, 8, 16, ..., 64}; M >= 1; dtype f16 or bf16.  rank == 0 means the
  * projection carries no adapter: A, B, t, dA, dB are ignored (may be NULL).

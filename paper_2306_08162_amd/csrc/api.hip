@@ -18,7 +18,7 @@ int check_weight_shape(int N, int K, int bits)
 {
     if (bits != 2 && bits != 3 && bits != 4 && bits != 8) return QLORA_E_BITS;
     if (N < 1 || K < 1 || K % 32 != 0 || N % 8 != 0) return QLORA_E_SHAPE;
-    if ((long long)N * K > (1ll << 40)) return QLORA_E_SHAPE;
+    if (K > (1 << 20) || N > (1 << 24)) return QLORA_E_SHAPE;   // kernels index groups and rows in 32 bits
     return QLORA_OK;
 }
 

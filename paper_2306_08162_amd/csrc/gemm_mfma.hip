@@ -10,6 +10,7 @@
 // (unpack, s*(q-z), round to 16 bit) -> LDS, and v_mfma_f32_32x32x16 consumes 16-byte fragments from LDS.
 // The dequantised weight never reaches HBM.  The rank-r LoRA term is folded in as extra contraction steps.
 #include "common.hpp"
+#include "dequant.hpp"
 #include "kernels.hpp"
 
 namespace qlora {
@@ -31,6 +32,7 @@ struct GemmArgs {
     int M, N, K, G, r;
     float sc;
     int tiles_m, tiles_n;
+    uint32_t g32_magic;       // see group_magic(): (k/32) / (G/32) == umulhi(k/32, magic), 0 meaning G == 32
 };
 
 template <bool BF16>
@@ -69,35 +71,27 @@ __device__ __forceinline__ void load_unit(const uint32_t *__restrict__ p, uint32
     }
 }
 
-// Code i (compile-time) of a 32-code unit held in BITS words.
-template <int BITS>
-__device__ __forceinline__ uint32_t unit_code(const uint32_t (&w)[BITS], int i)
-{
-    constexpr uint32_t mask = (1u << BITS) - 1u;
-    const int o = BITS * i, wi = o >> 5, sh = o & 31;
-    uint32_t q = w[wi] >> sh;
-    if (sh + BITS > 32) q |= w[wi + 1] << (32 - sh);
-    return q & mask;
-}
-
-// Dequantise one unit: out[i] = round16(s * (q_i - z)).
-template <int BITS, bool BF16>
-__device__ __forceinline__ void dequant_unit(const uint32_t (&w)[BITS], float s, float z, uint16_t (&out)[32])
-{
-#pragma unroll
-    for (int i = 0; i < 32; ++i) out[i] = to16<BF16>(((float)unit_code<BITS>(w, i) - z) * s);
-}
+// What one thread fetches for one 64-deep stage: XCH activation chunks and WU packed units with their group's
+// scale and zero-point.
+template <int BITS, int XCH, int WU>
+struct StageRegs {
+    u32x4_t x[XCH];
+    uint32_t w[WU][BITS];
+    float s[WU], z[WU];
+};
 
 template <int BITS, bool BF16, bool TRANS, int BM, int BN, int WM, int WN>
 __global__ __launch_bounds__(THREADS) void qgemm_kernel(const GemmArgs a)
 {
     static_assert(WM * WN == 4, "four waves per workgroup");
-    static_assert(BN % 128 == 0 && BM % 32 == 0, "tile shape");
+    static_assert(BN % 128 == 0 && BM % 128 == 0, "tile shape");
     constexpr int TM = BM / WM, TN = BN / WN;       // per-wave output tile
     constexpr int MI = TM / 32, NI = TN / 32;       // 32x32 MFMA blocks per wave
     constexpr int XCH = BM * (BK / 8) / THREADS;    // 16-byte activation chunks per thread per stage
     constexpr int WU = BN / 128;                    // 32-code weight units per thread per stage
     constexpr int STAGE = (BM + BN) * LDS_STRIDE;   // halfs per LDS stage
+    constexpr int KSTEPS = BK / 16;                 // MFMA k-steps per stage
+    using Regs = StageRegs<BITS, XCH, WU>;
 
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
 
@@ -130,21 +124,19 @@ __global__ __launch_bounds__(THREADS) void qgemm_kernel(const GemmArgs a)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    u32x4_t xr[XCH];
-    uint32_t wr[WU][BITS];
-    float ws[WU], wz[WU];
-
-    auto load_global = [&](int kt) {
-        const int kbase = kt * BK;
+    // global -> registers for stage kt.  Branch-free: every address is clamped into the valid range and whatever
+    // lies beyond the contraction length (or beyond the weight's rows / columns) is neutralised by a zero scale
+    // on the weight side, so stages past the end may be fetched and staged harmlessly.
+    const uint32_t xkc = (tid & 7) * 8;                 // same k offset for every chunk of this thread
+    uint32_t xrow_off[XCH];                             // element offset of each chunk's row
 #pragma unroll
-        for (int i = 0; i < XCH; ++i) {
-            const int c = tid + THREADS * i, r = c >> 3, kc = (c & 7) * 8;
-            const int gm = min(row0 + r, a.M - 1), k = kbase + kc;
-            if (k < KC)
-                xr[i] = *(const u32x4_t *)(a.act + (long)gm * KC + k);
-            else
-                xr[i] = u32x4_t{0u, 0u, 0u, 0u};
-        }
+    for (int i = 0; i < XCH; ++i) xrow_off[i] = (uint32_t)min(row0 + ((tid + THREADS * i) >> 3), a.M - 1) * (uint32_t)KC;
+
+    auto load_global = [&](int kt, Regs &rg) {
+        const int kbase = kt * BK;
+        const uint32_t k = (uint32_t)min(kbase + (int)xkc, KC - 8);
+#pragma unroll
+        for (int i = 0; i < XCH; ++i) rg.x[i] = *(const u32x4_t *)(a.act + (xrow_off[i] + k));
 #pragma unroll
         for (int i = 0; i < WU; ++i) {
             const int u = tid + THREADS * i;
@@ -158,77 +150,91 @@ __global__ __launch_bounds__(THREADS) void qgemm_kernel(const GemmArgs a)
                 n = col0 + (u >> 1);
                 k0 = kbase + (u & 1) * 32;
                 ok = k0 < a.K;
-                n = min(n, a.N - 1);
             }
-            if (ok) {
-                load_unit<BITS>(a.packed + (long)n * Kw + (k0 >> 5) * BITS, wr[i]);
-                const long gi = (long)n * ng + k0 / a.G;
-                ws[i] = f16_bits_to_f32(a.scales[gi]);
-                wz[i] = (float)a.zeros[gi];
-            } else {
-#pragma unroll
-                for (int j = 0; j < BITS; ++j) wr[i][j] = 0u;
-                ws[i] = 0.f;
-                wz[i] = 0.f;
-            }
+            n = min(n, a.N - 1);
+            k0 = min(k0, a.K - 32);
+            load_unit<BITS>(a.packed + (long)n * Kw + (k0 >> 5) * BITS, rg.w[i]);
+            const long gi = (long)n * ng + (a.g32_magic ? (int)__umulhi((uint32_t)(k0 >> 5), a.g32_magic) : (k0 >> 5));
+            const float sv = f16_bits_to_f32(a.scales[gi]);
+            rg.s[i] = ok ? sv : 0.f;
+            rg.z[i] = (float)a.zeros[gi];
         }
     };
 
-    auto store_lds = [&](int buf) {
+    // registers -> LDS, quarter `part` of a stage: XCH/4 activation chunks, and 8 codes of every unit dequantised
+    auto stage_part = [&](const Regs &rg, const DequantConst<BITS, BF16> (&dq)[WU], int part, int buf) {
         uint16_t *As = smem + buf * STAGE, *Bs = As + BM * LDS_STRIDE;
 #pragma unroll
-        for (int i = 0; i < XCH; ++i) {
+        for (int ii = 0; ii < XCH / KSTEPS; ++ii) {
+            const int i = part * (XCH / KSTEPS) + ii;
             const int c = tid + THREADS * i, r = c >> 3, kc = (c & 7) * 8;
-            *(u32x4_t *)(As + r * LDS_STRIDE + kc) = xr[i];
+            *(u32x4_t *)(As + r * LDS_STRIDE + kc) = rg.x[i];
         }
 #pragma unroll
         for (int i = 0; i < WU; ++i) {
             const int u = tid + THREADS * i;
-            uint16_t v[32];
-            dequant_unit<BITS, BF16>(wr[i], ws[i], wz[i], v);
+            const u16x8_t v = dequant8<BITS, BF16>(rg.w[i], part, dq[i]);
             if constexpr (TRANS) {
-                const int nl = u & 63, kl = (u >> 6) * 32;
+                uint16_t *dst = Bs + ((u >> 6) * 32 + part * 8) * LDS_STRIDE + (u & 63);
 #pragma unroll
-                for (int e = 0; e < 32; ++e) Bs[(kl + e) * LDS_STRIDE + nl] = v[e];
+                for (int e = 0; e < 8; ++e) dst[e * LDS_STRIDE] = v[e];
             } else {
-                uint16_t *dst = Bs + (u >> 1) * LDS_STRIDE + (u & 1) * 32;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    u16x8_t p;
-#pragma unroll
-                    for (int h = 0; h < 8; ++h) p[h] = v[8 * e + h];
-                    *(u16x8_t *)(dst + 8 * e) = p;
-                }
+                *(u16x8_t *)(Bs + (u >> 1) * LDS_STRIDE + (u & 1) * 32 + part * 8) = v;
             }
         }
     };
 
-    auto compute = [&](int buf, int nsteps) {
+    struct Frags {
+        u16x8_t a[MI], b[NI];
+    };
+    const int fr = lane & 31, fk = (lane >> 5) * 8;
+    auto load_frags = [&](int buf, int ks, Frags &f) {
         const uint16_t *As = smem + buf * STAGE, *Bs = As + BM * LDS_STRIDE;
-        const int fr = lane & 31, fk = (lane >> 5) * 8;
-        for (int ks = 0; ks < nsteps; ++ks) {
-            u16x8_t af[MI], bf[NI];
 #pragma unroll
-            for (int i = 0; i < MI; ++i) af[i] = *(const u16x8_t *)(As + (wm * TM + i * 32 + fr) * LDS_STRIDE + ks * 16 + fk);
+        for (int i = 0; i < MI; ++i) f.a[i] = *(const u16x8_t *)(As + (wm * TM + i * 32 + fr) * LDS_STRIDE + ks * 16 + fk);
 #pragma unroll
-            for (int j = 0; j < NI; ++j) bf[j] = *(const u16x8_t *)(Bs + (wn * TN + j * 32 + fr) * LDS_STRIDE + ks * 16 + fk);
+        for (int j = 0; j < NI; ++j) f.b[j] = *(const u16x8_t *)(Bs + (wn * TN + j * 32 + fr) * LDS_STRIDE + ks * 16 + fk);
+    };
+    auto mfma_frags = [&](const Frags &f) {
 #pragma unroll
-            for (int i = 0; i < MI; ++i)
+        for (int i = 0; i < MI; ++i)
 #pragma unroll
-                for (int j = 0; j < NI; ++j) acc[i][j] = mfma32<BF16>(af[i], bf[j], acc[i][j]);
-        }
+            for (int j = 0; j < NI; ++j) acc[i][j] = mfma32<BF16>(f.a[i], f.b[j], acc[i][j]);
     };
 
-    // --- main loop over the contraction, LDS double-buffered, next stage prefetched into registers
+    // One stage of the pipeline: MFMAs on LDS buffer kt&1 interleaved with staging stage kt+1 (held in `next`)
+    // into the other buffer, while stage kt+2 is fetched from memory into `fetch`.  Identical for every kt.
     const int KT = (KC + BK - 1) / BK;
-    load_global(0);
-    store_lds(0);
-    __syncthreads();
-    for (int kt = 0; kt < KT; ++kt) {
-        if (kt + 1 < KT) load_global(kt + 1);
-        compute(kt & 1, BK / 16);
-        if (kt + 1 < KT) store_lds((kt + 1) & 1);
+    auto pipeline_step = [&](int kt, const Regs &next, Regs &fetch) {
+        load_global(kt + 2, fetch);     // `fetch` held stage kt, which was staged during the previous step
+        DequantConst<BITS, BF16> dq[WU];
+#pragma unroll
+        for (int i = 0; i < WU; ++i) dq[i].set(next.s[i], next.z[i]);
+        Frags f[2];
+        load_frags(kt & 1, 0, f[0]);
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks) {
+            if (ks + 1 < KSTEPS) load_frags(kt & 1, ks + 1, f[(ks + 1) & 1]);
+            stage_part(next, dq, ks, (kt + 1) & 1);
+            mfma_frags(f[ks & 1]);
+        }
         __syncthreads();
+    };
+
+    Regs r0, r1;
+    load_global(0, r0);
+    load_global(1, r1);
+    {
+        DequantConst<BITS, BF16> dq[WU];
+#pragma unroll
+        for (int i = 0; i < WU; ++i) dq[i].set(r0.s[i], r0.z[i]);
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks) stage_part(r0, dq, ks, 0);
+    }
+    __syncthreads();
+    for (int kt = 0; kt < KT; kt += 2) {
+        pipeline_step(kt, r1, r0);
+        if (kt + 1 < KT) pipeline_step(kt + 1, r0, r1);
     }
 
     // --- LoRA term as extra contraction steps: Act' = sc * t (or u), W' = B (or A^T), zero-padded to 16
@@ -262,27 +268,46 @@ __global__ __launch_bounds__(THREADS) void qgemm_kernel(const GemmArgs a)
             *(u16x8_t *)(Bs + r * LDS_STRIDE + j) = p;
         }
         __syncthreads();
-        compute(0, nsteps);
+        for (int ks = 0; ks < nsteps; ++ks) {
+            Frags f;
+            load_frags(0, ks, f);
+            mfma_frags(f);
+        }
     }
 
-    // --- epilogue: fp32 accumulators -> 16 bit, rows beyond M and columns beyond NO are dropped
+    // --- epilogue: fp32 accumulators -> 16 bit.  Each wave lays its TM x TN block into its own LDS area in row-major
+    //     order, then streams it out in 16-byte pieces (8 lanes per 128-byte row segment).  Rows beyond M and
+    //     columns beyond NO (always whole 8-element pieces) are dropped.
+    __syncthreads();
+    {
+        constexpr int ESTR = TN + 8;
+        uint16_t *E = smem + wave * (TM * ESTR);
 #pragma unroll
-    for (int i = 0; i < MI; ++i)
+        for (int i = 0; i < MI; ++i)
 #pragma unroll
-        for (int j = 0; j < NI; ++j) {
-            const int col = col0 + wn * TN + j * 32 + (lane & 31);
+            for (int j = 0; j < NI; ++j)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = row0 + wm * TM + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-                if (row < a.M && col < NO) a.out[(long)row * NO + col] = to16<BF16>(acc[i][j][v]);
-            }
+                for (int v = 0; v < 16; ++v)
+                    E[(i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3)) * ESTR + j * 32 + (lane & 31)] =
+                        to16<BF16>(acc[i][j][v]);
+        __syncthreads();
+        constexpr int CPR = TN / 8;                       // 16-byte pieces per row
+        const int rbase = row0 + wm * TM, cbase = col0 + wn * TN;
+#pragma unroll
+        for (int q = 0; q < TM * CPR / 64; ++q) {
+            const int c = lane + 64 * q, r = c / CPR, ch = (c % CPR) * 8;
+            const u32x4_t v = *(const u32x4_t *)(E + r * ESTR + ch);
+            if (rbase + r < a.M && cbase + ch < NO) *(u32x4_t *)(a.out + ((long)(rbase + r) * NO + cbase + ch)) = v;
         }
+    }
 }
 
 template <int BITS, bool BF16, bool TRANS, int BM, int BN, int WM, int WN>
 void launch_variant(const GemmArgs &a, hipStream_t s)
 {
-    constexpr size_t lds = 2 * (size_t)(BM + BN) * LDS_STRIDE * sizeof(uint16_t);
+    constexpr size_t lds_pipe = 2 * (size_t)(BM + BN) * LDS_STRIDE * sizeof(uint16_t);
+    constexpr size_t lds_epi = 4 * (size_t)(BM / WM) * (BN / WN + 8) * sizeof(uint16_t);
+    constexpr size_t lds = lds_pipe > lds_epi ? lds_pipe : lds_epi;
     auto kern = qgemm_kernel<BITS, BF16, TRANS, BM, BN, WM, WN>;
     static bool configured = false;   // raising the dynamic-LDS ceiling is a property of the function, set once
     if (!configured) {
@@ -300,6 +325,14 @@ void launch_tiles(GemmArgs &a, hipStream_t s)
     a.tiles_m = (a.M + BM - 1) / BM;
     a.tiles_n = (NO + BN - 1) / BN;
     launch_variant<BITS, BF16, TRANS, BM, BN, 2, 2>(a, s);
+}
+
+// Multiplier m with umulhi(q, m) == q / (G/32) for every q < 2^16 (q = k/32, K < 2^21): m = floor(2^32 / d) + 1
+// for d = G/32 >= 2.  d = 1 would need m = 2^32; it is encoded as 0 and the kernel then uses q itself.
+inline uint32_t group_magic(int G)
+{
+    const uint32_t d = (uint32_t)(G / 32);
+    return d == 1 ? 0u : (uint32_t)(0x100000000ull / d) + 1u;
 }
 
 template <bool TRANS>
@@ -328,7 +361,7 @@ void launch_fwd_mfma(const Problem &p, const void *x, const uint32_t *packed, co
                      const void *t, const void *B, void *y, hipStream_t s)
 {
     GemmArgs a{(const uint16_t *)x, packed, (const uint16_t *)scales, zeros, (const uint16_t *)t, (const uint16_t *)B,
-               (uint16_t *)y, p.M, p.N, p.K, p.G, p.r, p.sc, 0, 0};
+               (uint16_t *)y, p.M, p.N, p.K, p.G, p.r, p.sc, 0, 0, group_magic(p.G)};
     launch_bits_dtype<false>(p, a, s);
 }
 
@@ -336,7 +369,7 @@ void launch_bwd_dx_mfma(const Problem &p, const void *dy, const uint32_t *packed
                         const uint8_t *zeros, const void *u, const void *A, void *dx, hipStream_t s)
 {
     GemmArgs a{(const uint16_t *)dy, packed, (const uint16_t *)scales, zeros, (const uint16_t *)u, (const uint16_t *)A,
-               (uint16_t *)dx, p.M, p.N, p.K, p.G, p.r, p.sc, 0, 0};
+               (uint16_t *)dx, p.M, p.N, p.K, p.G, p.r, p.sc, 0, 0, group_magic(p.G)};
     launch_bits_dtype<true>(p, a, s);
 }
 
