@@ -12,7 +12,7 @@ import os
 from typing import Optional
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libqlora.so")
+LIB_PATH = os.environ.get("QLORA_LIB", os.path.join(HERE, "libqlora.so"))   # QLORA_LIB: a variant built for tuning
 
 QLORA_F16, QLORA_BF16 = 0, 1
 STATUS_NAMES = ["QLORA_OK", "QLORA_E_NULL", "QLORA_E_BITS", "QLORA_E_SHAPE", "QLORA_E_GROUP", "QLORA_E_RANK",
