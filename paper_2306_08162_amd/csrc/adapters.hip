@@ -1,133 +1,182 @@
-// Rank-r side of the layer (Fig. 1, green LoRA branch): t = x A^T, u = dY B and the gradients of the
-// only trainable parameters, dA and dB (Sec. 3.1).  All of it is HBM-bound on x / dY; fp32 accumulation,
-// fixed summation order (no float atomics), so results are bitwise reproducible.
+// Rank-r side of the layer (Fig. 1, green LoRA branch): t = x A^T, u = dY B and the gradients of the only
+// trainable parameters, dA and dB (Sec. 3.1).  All four are skinny contractions that read x or dY once, so they
+// are HBM-bound; they run on v_mfma_f32_16x16x32 so that their cost does not grow with the rank, accumulate in
+// fp32 and reduce in a fixed order (no float atomics): results are bitwise reproducible.
 #include "common.hpp"
 #include "kernels.hpp"
 
 namespace qlora {
 
-constexpr int ROWS_PER_WAVE = 4;
+namespace {
 
-// t[m,j] = sum_k x[m,k] A[j,k].  One wave owns ROWS_PER_WAVE token rows; lanes stride along K in 16-byte
-// pieces; the rank is walked 8 columns at a time so A is fetched once per row group.
 template <bool BF16>
-__global__ __launch_bounds__(256) void lora_down_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ A,
-                                                        uint16_t *__restrict__ t, int M, int K, int r)
+__device__ __forceinline__ float4_t mfma16(u16x8_t a, u16x8_t b, float4_t c)
 {
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int m0 = (blockIdx.x * 4 + wave) * ROWS_PER_WAVE;
-    if (m0 >= M) return;
-    for (int j0 = 0; j0 < r; j0 += 8) {
-        float acc[ROWS_PER_WAVE][8];
+    if constexpr (BF16)
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b),
+                                                       c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, a), __builtin_bit_cast(half8_t, b), c,
+                                                      0, 0, 0);
+}
+
+// ------------------------------------------------------------------------------------------------------------
+// out[M,r] = act[M,C] * small[r,C]^T        (t = x A^T with small = A;  u = dY B with small = B^T)
+//
+// A workgroup of 8 waves owns 16 token rows; the waves split the contraction into 32-wide chunks (wave w takes
+// chunks w, w+8, ...) and feed them straight from global memory into the MFMA: both operands are contiguous
+// along the contraction, so a lane's fragment is one 16-byte load.  Partial 16 x r tiles meet in LDS.
+// ------------------------------------------------------------------------------------------------------------
+constexpr int SK_WAVES = 8;
+constexpr int SK_UNROLL = 8;
+
+template <bool BF16, int RG>   // RG = ceil(r / 16)
+__global__ __launch_bounds__(SK_WAVES * 64) void skinny_rows_kernel(const uint16_t *__restrict__ act,
+                                                                   const uint16_t *__restrict__ small,
+                                                                   uint16_t *__restrict__ out, int M, int C, int r)
+{
+    __shared__ float red[SK_WAVES][RG][16][17];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int m0 = blockIdx.x * 16;
+    const int li = lane & 15, q = lane >> 4;
+    const uint16_t *arow = act + (long)min(m0 + li, M - 1) * C + q * 8;
+    const uint16_t *srow[RG];
+    bool sval[RG];
 #pragma unroll
-        for (int i = 0; i < ROWS_PER_WAVE; ++i)
+    for (int g = 0; g < RG; ++g) {
+        sval[g] = g * 16 + li < r;
+        srow[g] = small + (long)min(g * 16 + li, r - 1) * C + q * 8;
+    }
+    float4_t acc[RG];
 #pragma unroll
-            for (int jj = 0; jj < 8; ++jj) acc[i][jj] = 0.f;
-        for (int k = lane * 8; k < K; k += WAVE * 8) {
-            float xf[ROWS_PER_WAVE][8];
+    for (int g = 0; g < RG; ++g) acc[g] = float4_t{0.f, 0.f, 0.f, 0.f};
+
+    const int chunks = (C + 31) / 32;   // C % 8 == 0: a chunk may be ragged in whole 8-element pieces
+    for (int c0 = wave; c0 < chunks; c0 += SK_WAVES * SK_UNROLL) {
+        u16x8_t xa[SK_UNROLL], sb[SK_UNROLL][RG];
 #pragma unroll
-            for (int i = 0; i < ROWS_PER_WAVE; ++i) {
-                const int row = min(m0 + i, M - 1);
-                const u16x8_t v = *(const u16x8_t *)(x + (long)row * K + k);
+        for (int uu = 0; uu < SK_UNROLL; ++uu) {
+            const int k = (c0 + uu * SK_WAVES) * 32;
+            const bool in = k + q * 8 < C;
+            const int kk = in ? k : 0;
+            xa[uu] = *(const u16x8_t *)(arow + kk);
+            if (!in) xa[uu] = u16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
-                for (int e = 0; e < 8; ++e) xf[i][e] = cvt16<BF16>(v[e]);
-            }
-#pragma unroll
-            for (int jj = 0; jj < 8; ++jj) {
-                const u16x8_t av = *(const u16x8_t *)(A + (long)(j0 + jj) * K + k);
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float a = cvt16<BF16>(av[e]);
-#pragma unroll
-                    for (int i = 0; i < ROWS_PER_WAVE; ++i) acc[i][jj] += xf[i][e] * a;
-                }
+            for (int g = 0; g < RG; ++g) {
+                sb[uu][g] = *(const u16x8_t *)(srow[g] + kk);
+                if (!sval[g]) sb[uu][g] = u16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
             }
         }
 #pragma unroll
-        for (int i = 0; i < ROWS_PER_WAVE; ++i)
+        for (int uu = 0; uu < SK_UNROLL; ++uu)
 #pragma unroll
-            for (int jj = 0; jj < 8; ++jj) {
-                const float v = wave_sum(acc[i][jj]);
-                if (lane == 0 && m0 + i < M) t[(long)(m0 + i) * r + j0 + jj] = to16<BF16>(v);
-            }
+            for (int g = 0; g < RG; ++g) acc[g] = mfma16<BF16>(xa[uu], sb[uu][g], acc[g]);
+    }
+    // D[row = 4*q + v][col = li]
+#pragma unroll
+    for (int g = 0; g < RG; ++g)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) red[wave][g][4 * q + v][li] = acc[g][v];
+    __syncthreads();
+    for (int e = threadIdx.x; e < RG * 256; e += SK_WAVES * 64) {
+        const int g = e >> 8, row = (e >> 4) & 15, col = e & 15;
+        float s = 0.f;
+#pragma unroll
+        for (int w = 0; w < SK_WAVES; ++w) s += red[w][g][row][col];
+        if (m0 + row < M && g * 16 + col < r) out[(long)(m0 + row) * r + g * 16 + col] = to16<BF16>(s);
     }
 }
 
-// u[m,j] = sum_n dy[m,n] B[n,j].  Same ownership; B rows are r contiguous values, read 8 columns at a time.
-template <bool BF16>
-__global__ __launch_bounds__(256) void lora_u_kernel(const uint16_t *__restrict__ dy, const uint16_t *__restrict__ B,
-                                                     uint16_t *__restrict__ u, int M, int N, int r)
+// bt[r,N] = b[N,r]^T (the small operand of u = dY B must be contiguous along the contraction index n)
+__global__ __launch_bounds__(256) void transpose_small_kernel(const uint16_t *__restrict__ b, uint16_t *__restrict__ bt,
+                                                              int N, int r)
 {
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int m0 = (blockIdx.x * 4 + wave) * ROWS_PER_WAVE;
-    if (m0 >= M) return;
-    for (int j0 = 0; j0 < r; j0 += 8) {
-        float acc[ROWS_PER_WAVE][8];
-#pragma unroll
-        for (int i = 0; i < ROWS_PER_WAVE; ++i)
-#pragma unroll
-            for (int jj = 0; jj < 8; ++jj) acc[i][jj] = 0.f;
-        for (int n = lane * 8; n < N; n += WAVE * 8) {
-            float g[ROWS_PER_WAVE][8];
-#pragma unroll
-            for (int i = 0; i < ROWS_PER_WAVE; ++i) {
-                const int row = min(m0 + i, M - 1);
-                const u16x8_t v = *(const u16x8_t *)(dy + (long)row * N + n);
-#pragma unroll
-                for (int e = 0; e < 8; ++e) g[i][e] = cvt16<BF16>(v[e]);
-            }
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const u16x8_t bv = *(const u16x8_t *)(B + (long)(n + e) * r + j0);
-#pragma unroll
-                for (int jj = 0; jj < 8; ++jj) {
-                    const float b = cvt16<BF16>(bv[jj]);
-#pragma unroll
-                    for (int i = 0; i < ROWS_PER_WAVE; ++i) acc[i][jj] += g[i][e] * b;
-                }
-            }
-        }
-#pragma unroll
-        for (int i = 0; i < ROWS_PER_WAVE; ++i)
-#pragma unroll
-            for (int jj = 0; jj < 8; ++jj) {
-                const float v = wave_sum(acc[i][jj]);
-                if (lane == 0 && m0 + i < M) u[(long)(m0 + i) * r + j0 + jj] = to16<BF16>(v);
-            }
-    }
+    const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (long)N * r) return;
+    const int j = (int)(idx / N), n = (int)(idx % N);
+    bt[idx] = b[(long)n * r + j];
 }
 
-// partial[slice][c][j0..j0+8) = sum over the slice's token rows of act[m,c] * side[m,j].
-// A thread owns two adjacent columns c and eight rank columns; grid = (column blocks, slices, r/8).
-template <bool BF16>
+// ------------------------------------------------------------------------------------------------------------
+// partial[s][c][j] = sum over the token rows m of slice s of act[m,c] * side[m,j]
+//      (dB: act = dY, side = t;  dA: act = x, side = u)
+//
+// The contraction runs over m, the strided index of both operands, so 32-row chunks of act (64 columns wide)
+// and of side are laid into LDS as they come and the MFMA fragments are gathered from there column-wise.
+// A workgroup owns 64 columns x one slice; every global load of the slice is issued before the first MFMA.
+// ------------------------------------------------------------------------------------------------------------
+constexpr int GR_COLS = 64;       // columns per workgroup (16 per wave)
+constexpr int GR_ROWS = 128;      // token rows per slice
+constexpr int GR_CHUNKS = GR_ROWS / 32;
+constexpr int GR_PITCH = GR_COLS + 2;   // halfs; odd dword pitch keeps the column gathers off the same banks
+
+template <bool BF16, int RG>
 __global__ __launch_bounds__(256) void adapter_grad_partial_kernel(const uint16_t *__restrict__ act,
                                                                    const uint16_t *__restrict__ side,
-                                                                   float *__restrict__ partial, int M, int C, int r,
-                                                                   int rows_per_slice)
+                                                                   float *__restrict__ partial, int M, int C, int r)
 {
-    const int c = (blockIdx.x * 256 + threadIdx.x) * 2;
-    const int slice = blockIdx.y, j0 = blockIdx.z * 8;
-    if (c >= C) return;
-    const int m_begin = slice * rows_per_slice, m_end = min(M, m_begin + rows_per_slice);
-    float acc0[8], acc1[8];
+    __shared__ uint16_t As[GR_ROWS * GR_PITCH];
+    constexpr int SP = RG * 16 + 2;         // side pitch in halfs, odd dword pitch as well
+    __shared__ uint16_t Ss[GR_ROWS * SP];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c0 = blockIdx.x * GR_COLS, slice = blockIdx.y, m0 = slice * GR_ROWS;
+
+    // global -> LDS: act rows are 128 bytes wide here (8 lanes x 16 B); rows past M or columns past C become zero
+    {
+        const int rr = tid >> 3, cc = (tid & 7) * 8;
+        u16x8_t v[GR_CHUNKS];
 #pragma unroll
-    for (int jj = 0; jj < 8; ++jj) acc0[jj] = acc1[jj] = 0.f;
-    for (int m = m_begin; m < m_end; ++m) {
-        const uint32_t pair = *(const uint32_t *)(act + (long)m * C + c);
-        const float a0 = cvt16<BF16>((uint16_t)(pair & 0xffffu)), a1 = cvt16<BF16>((uint16_t)(pair >> 16));
-        const u16x8_t sv = *(const u16x8_t *)(side + (long)m * r + j0);   // same address for every lane
+        for (int ch = 0; ch < GR_CHUNKS; ++ch) {
+            const int m = m0 + ch * 32 + rr;
+            const bool in = m < M && c0 + cc < C;
+            v[ch] = *(const u16x8_t *)(act + (in ? (long)m * C + c0 + cc : 0));
+            if (!in) v[ch] = u16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
+        }
 #pragma unroll
-        for (int jj = 0; jj < 8; ++jj) {
-            const float sj = cvt16<BF16>(sv[jj]);
-            acc0[jj] += a0 * sj;
-            acc1[jj] += a1 * sj;
+        for (int ch = 0; ch < GR_CHUNKS; ++ch) {
+            uint32_t *dst = (uint32_t *)(As + (ch * 32 + rr) * GR_PITCH + cc);   // 4-byte aligned: pitch and cc even
+            const u32x4_t w = __builtin_bit_cast(u32x4_t, v[ch]);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) dst[e] = w[e];
+        }
+        for (int e = tid; e < GR_ROWS * RG * 2; e += 256) {     // side rows, padded to RG*16 columns, 8 at a time
+            const int row = e / (RG * 2), j = (e % (RG * 2)) * 8;
+            const bool in = m0 + row < M && j < r;
+            u16x8_t sv = *(const u16x8_t *)(side + (in ? (long)(m0 + row) * r + j : 0));
+            if (!in) sv = u16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
+            uint32_t *sd = (uint32_t *)(Ss + row * SP + j);
+            const u32x4_t sw = __builtin_bit_cast(u32x4_t, sv);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) sd[k] = sw[k];
         }
     }
-    float *dst = partial + ((long)slice * C + c) * r + j0;
+    __syncthreads();
+
+    const int li = lane & 15, q = lane >> 4;
+    float4_t acc[RG];
 #pragma unroll
-    for (int jj = 0; jj < 8; ++jj) {
-        dst[jj] = acc0[jj];
-        dst[r + jj] = acc1[jj];
+    for (int g = 0; g < RG; ++g) acc[g] = float4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 2
+    for (int ch = 0; ch < GR_CHUNKS; ++ch) {
+        const int mb = ch * 32 + q * 8;
+        u16x8_t fb;       // act^T fragment: column c = 16*wave + li, rows mb .. mb+7
+#pragma unroll
+        for (int e = 0; e < 8; ++e) fb[e] = As[(mb + e) * GR_PITCH + wave * 16 + li];
+#pragma unroll
+        for (int g = 0; g < RG; ++g) {
+            u16x8_t fa;   // side^T fragment: column j = 16*g + li
+#pragma unroll
+            for (int e = 0; e < 8; ++e) fa[e] = Ss[(mb + e) * SP + g * 16 + li];
+            acc[g] = mfma16<BF16>(fa, fb, acc[g]);      // D[j = 4*q + v][c = li]
+        }
+    }
+    const int c = c0 + wave * 16 + li;
+    if (c < C) {
+#pragma unroll
+        for (int g = 0; g < RG; ++g) {
+            const int j = g * 16 + 4 * q;
+            if (j < r) *(float4_t *)(partial + ((long)slice * C + c) * r + j) = acc[g];   // r % 8 == 0: j..j+3 < r
+        }
     }
 }
 
@@ -138,56 +187,80 @@ __global__ __launch_bounds__(256) void adapter_grad_reduce_kernel(const float *_
 {
     const long idx = (long)blockIdx.x * 256 + threadIdx.x;
     if (idx >= (long)C * r) return;
+    const long stride = (long)C * r;
     float acc = 0.f;
-    for (int s = 0; s < slices; ++s) acc += partial[(long)s * C * r + idx];
+    int s = 0;
+    for (; s + 4 <= slices; s += 4) {
+        const float a0 = partial[(s + 0) * stride + idx], a1 = partial[(s + 1) * stride + idx];
+        const float a2 = partial[(s + 2) * stride + idx], a3 = partial[(s + 3) * stride + idx];
+        acc = (((acc + a0) + a1) + a2) + a3;
+    }
+    for (; s < slices; ++s) acc += partial[s * stride + idx];
     const int c = (int)(idx / r), j = (int)(idx % r);
     out[c_major ? idx : (long)j * C + c] = sc * acc;
 }
 
-void launch_lora_down(const void *x, const void *A, void *t, int M, int K, int r, bool bf16, hipStream_t s)
+template <bool BF16>
+void launch_skinny(const uint16_t *act, const uint16_t *small, uint16_t *out, int M, int C, int r, hipStream_t s)
 {
-    const dim3 grid((M + 4 * ROWS_PER_WAVE - 1) / (4 * ROWS_PER_WAVE)), block(256);
-    if (bf16)
-        hipLaunchKernelGGL(lora_down_kernel<true>, grid, block, 0, s, (const uint16_t *)x, (const uint16_t *)A,
-                           (uint16_t *)t, M, K, r);
-    else
-        hipLaunchKernelGGL(lora_down_kernel<false>, grid, block, 0, s, (const uint16_t *)x, (const uint16_t *)A,
-                           (uint16_t *)t, M, K, r);
+    const dim3 grid((M + 15) / 16), block(SK_WAVES * 64);
+    switch ((r + 15) / 16) {
+    case 1: hipLaunchKernelGGL((skinny_rows_kernel<BF16, 1>), grid, block, 0, s, act, small, out, M, C, r); break;
+    case 2: hipLaunchKernelGGL((skinny_rows_kernel<BF16, 2>), grid, block, 0, s, act, small, out, M, C, r); break;
+    case 3: hipLaunchKernelGGL((skinny_rows_kernel<BF16, 3>), grid, block, 0, s, act, small, out, M, C, r); break;
+    default: hipLaunchKernelGGL((skinny_rows_kernel<BF16, 4>), grid, block, 0, s, act, small, out, M, C, r); break;
+    }
 }
 
-void launch_lora_u(const void *dy, const void *B, void *u, int M, int N, int r, bool bf16, hipStream_t s)
+template <bool BF16>
+void launch_grad_partial(const uint16_t *act, const uint16_t *side, float *partial, int M, int C, int r, int slices,
+                         hipStream_t s)
 {
-    const dim3 grid((M + 4 * ROWS_PER_WAVE - 1) / (4 * ROWS_PER_WAVE)), block(256);
+    const dim3 grid((C + GR_COLS - 1) / GR_COLS, slices), block(256);
+    switch ((r + 15) / 16) {
+    case 1: hipLaunchKernelGGL((adapter_grad_partial_kernel<BF16, 1>), grid, block, 0, s, act, side, partial, M, C, r); break;
+    case 2: hipLaunchKernelGGL((adapter_grad_partial_kernel<BF16, 2>), grid, block, 0, s, act, side, partial, M, C, r); break;
+    case 3: hipLaunchKernelGGL((adapter_grad_partial_kernel<BF16, 3>), grid, block, 0, s, act, side, partial, M, C, r); break;
+    default: hipLaunchKernelGGL((adapter_grad_partial_kernel<BF16, 4>), grid, block, 0, s, act, side, partial, M, C, r); break;
+    }
+}
+
+}  // namespace
+
+void launch_lora_down(const void *x, const void *A, void *t, int M, int K, int r, bool bf16, hipStream_t s)
+{
     if (bf16)
-        hipLaunchKernelGGL(lora_u_kernel<true>, grid, block, 0, s, (const uint16_t *)dy, (const uint16_t *)B,
-                           (uint16_t *)u, M, N, r);
+        launch_skinny<true>((const uint16_t *)x, (const uint16_t *)A, (uint16_t *)t, M, K, r, s);
     else
-        hipLaunchKernelGGL(lora_u_kernel<false>, grid, block, 0, s, (const uint16_t *)dy, (const uint16_t *)B,
-                           (uint16_t *)u, M, N, r);
+        launch_skinny<false>((const uint16_t *)x, (const uint16_t *)A, (uint16_t *)t, M, K, r, s);
+}
+
+void launch_lora_u(const void *dy, const void *B, void *bt, void *u, int M, int N, int r, bool bf16, hipStream_t s)
+{
+    const long n = (long)N * r;
+    hipLaunchKernelGGL(transpose_small_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (const uint16_t *)B,
+                       (uint16_t *)bt, N, r);
+    if (bf16)
+        launch_skinny<true>((const uint16_t *)dy, (const uint16_t *)bt, (uint16_t *)u, M, N, r, s);
+    else
+        launch_skinny<false>((const uint16_t *)dy, (const uint16_t *)bt, (uint16_t *)u, M, N, r, s);
 }
 
 int adapter_grad_slices(int M, int C, int r)
 {
     (void)C;
     if (r <= 0) return 0;
-    int slices = 512 / r;                       // keeps slices * r, hence the partial buffer, bounded
-    const int by_rows = (M + 31) / 32;          // at least 32 token rows per slice
-    if (slices > by_rows) slices = by_rows;
-    return slices < 1 ? 1 : slices;
+    return (M + GR_ROWS - 1) / GR_ROWS;
 }
 
 void launch_adapter_grad(const void *act, const void *side, float *out, float *partial, int M, int C, int r,
                          float sc, bool c_major, bool bf16, hipStream_t s)
 {
     const int slices = adapter_grad_slices(M, C, r);
-    const int rows_per_slice = (M + slices - 1) / slices;
-    const dim3 grid((C / 2 + 255) / 256, slices, r / 8), block(256);
     if (bf16)
-        hipLaunchKernelGGL(adapter_grad_partial_kernel<true>, grid, block, 0, s, (const uint16_t *)act,
-                           (const uint16_t *)side, partial, M, C, r, rows_per_slice);
+        launch_grad_partial<true>((const uint16_t *)act, (const uint16_t *)side, partial, M, C, r, slices, s);
     else
-        hipLaunchKernelGGL(adapter_grad_partial_kernel<false>, grid, block, 0, s, (const uint16_t *)act,
-                           (const uint16_t *)side, partial, M, C, r, rows_per_slice);
+        launch_grad_partial<false>((const uint16_t *)act, (const uint16_t *)side, partial, M, C, r, slices, s);
     const long n = (long)C * r;
     hipLaunchKernelGGL(adapter_grad_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, partial, out, C,
                        r, slices, sc, c_major ? 1 : 0);

@@ -36,7 +36,7 @@ int check_problem(int M, int N, int K, int bits, int G, int r, int dtype)
 }
 
 struct Workspace {
-    size_t t_off, u_off, partial_off, total;
+    size_t t_off, u_off, bt_off, partial_off, total;
 };
 
 Workspace carve(int M, int N, int K, int r)
@@ -47,6 +47,8 @@ Workspace carve(int M, int N, int K, int r)
     off += round_up((size_t)M * r * 2);
     w.u_off = off;
     off += round_up((size_t)M * r * 2);
+    w.bt_off = off;
+    off += round_up((size_t)N * r * 2);
     w.partial_off = off;
     const size_t pa = (size_t)adapter_grad_slices(M, K, r) * K * r * sizeof(float);
     const size_t pb = (size_t)adapter_grad_slices(M, N, r) * N * r * sizeof(float);
@@ -185,7 +187,7 @@ int qlora_linear_bwd(const void *dy, const void *x, const uint32_t *packed, cons
     void *u = nullptr;
     if (rank > 0) {
         u = ws + w.u_off;
-        launch_lora_u(dy, B, u, M, N, rank, p.bf16, s);
+        launch_lora_u(dy, B, ws + w.bt_off, u, M, N, rank, p.bf16, s);
     }
     {
         GemmTimer timer(s);

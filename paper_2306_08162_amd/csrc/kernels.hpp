@@ -21,8 +21,8 @@ void launch_unpack(const uint32_t *packed, uint8_t *codes, int N, int K, int bit
 // adapters.hip -- the rank-r side products and the adapter gradients
 // t[M,r] = x[M,K] A[r,K]^T
 void launch_lora_down(const void *x, const void *A, void *t, int M, int K, int r, bool bf16, hipStream_t s);
-// u[M,r] = dy[M,N] B[N,r]
-void launch_lora_u(const void *dy, const void *B, void *u, int M, int N, int r, bool bf16, hipStream_t s);
+// u[M,r] = dy[M,N] B[N,r]; bt is scratch for B^T (N*r 16-bit values)
+void launch_lora_u(const void *dy, const void *B, void *bt, void *u, int M, int N, int r, bool bf16, hipStream_t s);
 // Number of token slices the adapter-gradient reductions are cut into (fixed by the shape alone).
 int adapter_grad_slices(int M, int C, int r);
 // out = sc * act[M,C]^T side[M,r]; out is [C,r] (c_major) or [r,C]; partial holds slices*C*r floats.
