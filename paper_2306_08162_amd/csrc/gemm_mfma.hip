@@ -5,10 +5,10 @@
 //             weight is consumed transposed; transpose + unpack + matmul happen inside this one kernel)
 //
 // Both are C[M,NO] = Act[M,KC] * W^T with W viewed as [NO,KC]; only the way a packed tile is fetched and laid
-// into LDS differs.  A workgroup owns a BM x BN output tile and walks the contraction in steps of 64 through a
-// double-buffered LDS stage.  Its eight waves are specialised: four staging waves move activation chunks
-// global -> registers -> LDS unchanged and packed words global -> registers -> (unpack, s*(q-z), round to 16 bit)
-// -> LDS; four MFMA waves read 16-byte fragments from LDS into v_mfma_f32_32x32x16.  One barrier per stage.
+// into LDS differs.  A workgroup owns a BM x BN output tile and walks the contraction in steps of 64.  Its eight
+// waves are specialised: four staging waves move packed words global -> registers -> (unpack, s*(q-z), round to
+// 16 bit) -> LDS (two stages); four MFMA waves pull the activation tile global -> LDS directly (three stages, no
+// registers) and read 16-byte fragments of both operands into v_mfma_f32_32x32x16.  One barrier per stage.
 // The dequantised weight never reaches HBM.  The rank-r LoRA term is folded in as extra contraction steps.
 #include "common.hpp"
 #include "dequant.hpp"
@@ -20,8 +20,7 @@ namespace {
 
 constexpr int BK = 64;               // contraction elements per LDS stage
 constexpr int LDS_STRIDE = BK + 8;   // 144-byte rows: the 16-byte reads of 8 consecutive rows fall in distinct bank groups
-constexpr int THREADS = 512;        // 4 MFMA waves + 4 staging waves
-constexpr int STAGERS = 256;        // staging threads
+constexpr int STAGERS = 256;        // staging threads (4 waves); the MFMA waves come on top
 
 struct GemmArgs {
     const uint16_t *act;      // x (forward) or dY (backward): [M, KC]
@@ -73,39 +72,65 @@ __device__ __forceinline__ void load_unit(const uint32_t *__restrict__ p, uint32
     }
 }
 
-// What one thread fetches for one 64-deep stage: XCH activation chunks and WU packed units with their group's
-// scale and zero-point.
-template <int BITS, int XCH, int WU>
+// What one staging thread fetches for one 64-deep stage of the weight: WU packed units with their group's scale
+// and zero-point, kept exactly as loaded.
+template <int BITS, int WU>
 struct StageRegs {
-    u32x4_t x[XCH];
     uint32_t w[WU][BITS];
     uint16_t s[WU];     // raw fp16 bits: nothing may touch loaded values before they are staged, or the
     uint8_t z[WU];      // in-order memory counter would make that instruction wait for every load issued so far
     bool ok[WU];        // false: the unit lies outside the weight, stage zeros
 };
 
-template <int BITS, bool BF16, bool TRANS, int BM, int BN, int WM, int WN>
-__global__ __launch_bounds__(THREADS) void qgemm_kernel(const GemmArgs a)
+// Direct-to-LDS load: every lane fetches 16 bytes from base + its own 32-bit byte offset, and the 64 pieces land contiguously
+// at the wave-uniform LDS byte address `lds` (1 KB).  Written as assembly so that the compiler does not order it
+// against the LDS fragment reads around it: the stage it fills is never one that is being read (see the stage
+// rotation in the kernel), which the compiler cannot know.  Completion is tracked by the vector-memory counter.
+__device__ __forceinline__ void dma16(const void *base, uint32_t byte_offset, uint32_t lds)
 {
-    static_assert(WM * WN == 4, "four MFMA waves per workgroup");
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 ::"v"(byte_offset), "s"(base), "s"(lds)
+                 : "memory", "m0");
+}
+
+// wait until at most N vector-memory operations of this wave are outstanding, then meet the workgroup
+template <int N>
+__device__ __forceinline__ void wait_vm_and_barrier()
+{
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+
+template <int BITS, bool BF16, bool TRANS, int BM, int BN, int WM, int WN>
+__global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const GemmArgs a)
+{
+    constexpr int MW = WM * WN;                     // MFMA waves
+    constexpr int THREADS = MW * 64 + STAGERS;
+    static_assert(MW == 4 || MW == 8, "one or two MFMA waves per SIMD");
     static_assert(BN % 128 == 0 && BM % 128 == 0, "tile shape");
     constexpr int TM = BM / WM, TN = BN / WN;       // per-wave output tile
     constexpr int MI = TM / 32, NI = TN / 32;       // 32x32 MFMA blocks per wave
-    constexpr int XCH = BM * (BK / 8) / STAGERS;    // 16-byte activation chunks per staging thread per stage
+    constexpr int XDMA = BM / 8 / MW;               // direct-to-LDS loads per MFMA wave per stage (8 rows each)
+    static_assert(XDMA >= 4 && XDMA % 4 == 0, "loads are spread over the four k-steps");
     constexpr int WU = BN / 128;                    // 32-code weight units per staging thread per stage
-    constexpr int STAGE = (BM + BN) * LDS_STRIDE;   // halfs per LDS stage
-    constexpr int KSTEPS = BK / 16;                 // MFMA k-steps per stage
-    using Regs = StageRegs<BITS, XCH, WU>;
+    constexpr int XS = BM * BK;                     // halfs per activation stage (128-byte rows, swizzled)
+    constexpr int NXS = 3;                          // activation stages
+    constexpr int WS = BN * LDS_STRIDE;             // halfs per weight stage (144-byte rows)
+    using Regs = StageRegs<BITS, WU>;
 
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+    uint16_t *const xs = smem;                      // [NXS][BM][64]
+    uint16_t *const wsm = smem + NXS * XS;          // [2][BN][72]
 
-    // Waves 0-3 only feed the matrix cores (LDS fragment reads + MFMA); waves 4-7 only stage operands (global
-    // loads, dequantisation, LDS writes).  Each SIMD hosts one wave of each kind, so the vector ALU work of the
-    // dequantisation issues in the shadow of the other wave's MFMAs instead of competing for its issue slots.
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const bool stager = wave >= 4;
-    const int stid = tid & (STAGERS - 1);           // index among the staging threads
-    const int cw = wave & 3, wm = cw / WN, wn = cw % WN;
+    // The first MW waves feed the matrix cores: LDS fragment reads, MFMAs, and the direct-to-LDS loads of the
+    // activation tile (no registers, no ALU work).  The last four waves stage the weight: packed words global ->
+    // registers -> dequantise -> LDS.  Every SIMD hosts waves of both kinds (and, with MW = 8, two MFMA waves), so
+    // one wave's fragment reads, loads and dequantisation issue in the shadow of another wave's MFMAs: a single
+    // wave cannot hide its own instruction issue behind its MFMAs.
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform, kept in a scalar register
+    const bool stager = wave >= MW;
+    const int stid = tid - MW * 64;                 // index among the staging threads
+    const int cw = wave, wm = cw / WN, wn = cw % WN;
     const int NO = TRANS ? a.K : a.N;    // output columns
     const int KC = TRANS ? a.N : a.K;    // contraction length
     const int ng = a.K / a.G, Kw = a.K * BITS / 32;
@@ -134,16 +159,25 @@ __global__ __launch_bounds__(THREADS) void qgemm_kernel(const GemmArgs a)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
+    // Activation tile in LDS: row r is 128 bytes = eight 16-byte slots; slot s holds the row's chunk
+    // s ^ ((r >> 1) & 7).  A 16-byte LDS read serves 16 lanes per clock out of a 256-byte-wide bank space, i.e. two
+    // rows; with this key the 16 consecutive rows read by 16 lanes fall into 16 different slots of that space.
+    // A direct-to-LDS load lays the 64 lanes' 16 bytes down contiguously (8 rows), so the swizzle is applied by
+    // choosing which global chunk each lane fetches.
     struct Frags {
         u16x8_t a[MI], b[NI];
     };
-    const int fr = lane & 31, fk = (lane >> 5) * 8;
-    auto load_frags = [&](int buf, int ks, Frags &f) {
-        const uint16_t *As = smem + buf * STAGE, *Bs = As + BM * LDS_STRIDE;
+    const int fr = lane & 31, fh = lane >> 5;
+    int aoff[BK / 16];                              // per k-step: this lane's offset into an activation stage
 #pragma unroll
-        for (int i = 0; i < MI; ++i) f.a[i] = *(const u16x8_t *)(As + (wm * TM + i * 32 + fr) * LDS_STRIDE + ks * 16 + fk);
+    for (int ks = 0; ks < BK / 16; ++ks) aoff[ks] = (wm * TM + fr) * BK + ((2 * ks + fh) ^ ((fr >> 1) & 7)) * 8;
+    const int boff = (wn * TN + fr) * LDS_STRIDE + fh * 8;   // and into a weight stage (k-step adds 16)
+    auto load_frags = [&](int xstage, int wstage, int ks, Frags &f) {
+        const uint16_t *As = xs + xstage * XS + aoff[ks], *Bs = wsm + wstage * WS + boff + ks * 16;
 #pragma unroll
-        for (int j = 0; j < NI; ++j) f.b[j] = *(const u16x8_t *)(Bs + (wn * TN + j * 32 + fr) * LDS_STRIDE + ks * 16 + fk);
+        for (int i = 0; i < MI; ++i) f.a[i] = *(const u16x8_t *)(As + i * 32 * BK);
+#pragma unroll
+        for (int j = 0; j < NI; ++j) f.b[j] = *(const u16x8_t *)(Bs + j * 32 * LDS_STRIDE);
     };
     auto mfma_frags = [&](const Frags &f) {
 #pragma unroll
@@ -151,44 +185,75 @@ __global__ __launch_bounds__(THREADS) void qgemm_kernel(const GemmArgs a)
 #pragma unroll
             for (int j = 0; j < NI; ++j) acc[i][j] = mfma32<BF16>(f.a[i], f.b[j], acc[i][j]);
     };
-    // One k-step of the MFMA waves: the fragments of a later k-step are requested from LDS while the MFMAs of the
-    // current one issue, one LDS read slotted behind each MFMA so the matrix pipe never waits on a burst of reads.
-    auto kstep = [&](int rbuf, int rks, Frags &into, const Frags &use) {
-#ifndef QLORA_EXP_NOFRAG
-        load_frags(rbuf, rks, into);
-#endif
-        mfma_frags(use);
-#pragma unroll
-        for (int i = 0; i < MI * NI; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                        // one MFMA
-            if (i < MI + NI) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);       // one LDS read
-        }
-    };
 
-    if (stager) {
+    if (!stager) {
+        // ---- MFMA waves ----
+        // direct-to-LDS loads: this wave's load i covers tile rows (MW i + cw) * 8 .. + 8
+        const int drow = lane >> 3;              // row within the 8-row block; block b starts at tile row 8 b
+        const int dchunk = ((lane & 7) ^ ((4 * cw + (drow >> 1)) & 7)) * 8;   // MW * i * 4 is a multiple of 8
+        const uint32_t xs_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint16_t *)xs;
+        uint32_t xoff[XDMA];                    // byte offset of this lane's row within the activation matrix
+#pragma unroll
+        for (int i = 0; i < XDMA; ++i)
+            xoff[i] = (uint32_t)min(row0 + (MW * i + cw) * 8 + drow, a.M - 1) * (uint32_t)KC * 2u;
+        auto issue_x = [&](int kt, int stage, int i) {
+            // stages past the end and chunks past the contraction length re-read valid data; the weight side is zero there
+            const uint32_t k2 = (uint32_t)min(kt * BK + dchunk, KC - 8) * 2u;
+            const uint32_t dst = xs_lds + (uint32_t)(stage * XS + (MW * i + cw) * 512) * 2u;   // wave-uniform byte address
+            dma16(a.act, xoff[i] + k2, (uint32_t)__builtin_amdgcn_readfirstlane((int)dst));
+        };
+        // One k-step: the fragments of a later k-step are requested from LDS while the MFMAs of the current one
+        // issue, one LDS read slotted behind each MFMA so the matrix pipe never waits on a burst of reads.
+        auto kstep = [&](int xstage, int wstage, int rks, Frags &into, const Frags &use) {
+#ifndef QLORA_EXP_NOFRAG
+            load_frags(xstage, wstage, rks, into);
+#endif
+            mfma_frags(use);
+#pragma unroll
+            for (int i = 0; i < MI * NI; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                        // one MFMA
+                if (i < MI + NI) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);       // one LDS read
+            }
+        };
+
+#pragma unroll
+        for (int i = 0; i < XDMA; ++i) issue_x(0, 0, i);
+#pragma unroll
+        for (int i = 0; i < XDMA; ++i) issue_x(1, 1, i);
+        wait_vm_and_barrier<XDMA>();            // stage 0 of the activations has landed; weights staged by waves 4-7
+        Frags f[2];
+        load_frags(0, 0, 0, f[0]);
+        int xstage = 0;                         // kt % NXS
+        for (int kt = 0; kt < KT; ++kt) {
+            const int wstage = kt & 1;
+            const int xnext = xstage + 1 == NXS ? 0 : xstage + 1, xfill = xnext + 1 == NXS ? 0 : xnext + 1;
+            // the last k-step of a stage runs from registers after the barrier, overlapping the LDS latency of the
+            // next stage's first fragments; the activation loads for stage kt+2 are spread over the k-steps
+            auto issue_quarter = [&](int qtr) {
+#ifndef QLORA_EXP_NOLOAD
+#pragma unroll
+                for (int i = qtr * (XDMA / 4); i < (qtr + 1) * (XDMA / 4); ++i) issue_x(kt + 2, xfill, i);
+#endif
+            };
+            issue_quarter(0);
+            kstep(xstage, wstage, 1, f[1], f[0]);
+            issue_quarter(1);
+            kstep(xstage, wstage, 2, f[0], f[1]);
+            issue_quarter(2);
+            kstep(xstage, wstage, 3, f[1], f[0]);
+            issue_quarter(3);
+            wait_vm_and_barrier<XDMA>();        // stage kt+1 has landed (only this step's loads may be pending)
+            kstep(xnext, wstage ^ 1, 0, f[0], f[1]);
+            xstage = xnext;
+        }
+        wait_vm_and_barrier<0>();               // the loads issued past the last stage have landed: LDS is quiet
+    } else {
+        // ---- weight staging waves ----
         // global -> registers for stage kt.  Branch-free: every address is clamped into the valid range and
         // whatever lies beyond the contraction length (or beyond the weight's rows / columns) is neutralised by a
-        // zero scale on the weight side, so stages past the end may be fetched and staged harmlessly.
-        const uint32_t xkc = (stid & 7) * 8;                // same k offset for every chunk of this thread
-        uint32_t xrow_off[XCH];                             // element offset of each chunk's row
-#pragma unroll
-        for (int i = 0; i < XCH; ++i)
-            xrow_off[i] = (uint32_t)min(row0 + ((stid + STAGERS * i) >> 3), a.M - 1) * (uint32_t)KC;
-
-#ifndef QLORA_PHASE_MODE
-#define QLORA_PHASE_MODE 0
-#endif
-        const int phase = QLORA_PHASE_MODE == 0 ? 0
-                          : QLORA_PHASE_MODE == 1 ? (pm * KT) / a.tiles_m
-                          : QLORA_PHASE_MODE == 2 ? ((pm * KT) / a.tiles_m + pn) % KT
-                                                  : (pn * 5 + pm * 3) % KT;
-        auto load_global = [&](int kt_seq, Regs &rg) {
-            int kt = kt_seq + phase;
-            kt = kt >= KT ? kt - KT : kt;               // stages are visited in a rotated order (see above)
+        // zero scale, so stages past the end may be fetched and staged harmlessly.
+        auto load_global = [&](int kt, Regs &rg) {
             const int kbase = kt * BK;
-            const uint32_t k = (uint32_t)min(kbase + (int)xkc, KC - 8);
-#pragma unroll
-            for (int i = 0; i < XCH; ++i) rg.x[i] = *(const u32x4_t *)(a.act + (xrow_off[i] + k));
 #pragma unroll
             for (int i = 0; i < WU; ++i) {
                 const int u = stid + STAGERS * i;
@@ -205,43 +270,17 @@ __global__ __launch_bounds__(THREADS) void qgemm_kernel(const GemmArgs a)
                 }
                 n = min(n, a.N - 1);
                 k0 = min(k0, a.K - 32);
-#ifdef QLORA_EXP_NOWLOAD
-                for (int j = 0; j < BITS; ++j) rg.w[i][j] = 0x12345678u + n;
-#else
                 load_unit<BITS>(a.packed + (long)n * Kw + (k0 >> 5) * BITS, rg.w[i]);
-#endif
                 const long gi = (long)n * ng + (a.g32_magic ? (int)__umulhi((uint32_t)(k0 >> 5), a.g32_magic) : (k0 >> 5));
-#ifdef QLORA_EXP_NOSZLOAD
-                rg.s[i] = (uint16_t)gi;
-                rg.z[i] = (uint8_t)gi;
-#else
                 rg.s[i] = a.scales[gi];
                 rg.z[i] = a.zeros[gi];
-#endif
                 rg.ok[i] = ok;
             }
         };
 
-        // registers -> LDS: activation chunks unchanged, every unit dequantised 8 codes at a time
+        // registers -> LDS: every unit dequantised 8 codes at a time
         auto stage = [&](const Regs &rg, int buf) {
-            uint16_t *As = smem + buf * STAGE, *Bs = As + BM * LDS_STRIDE;
-#ifdef QLORA_EXP_NOXW
-            {
-                u32x4_t t = rg.x[0];
-                for (int i = 1; i < XCH; ++i) t ^= rg.x[i];
-                if (t[0] == 0x12345678u) *(u32x4_t *)(As + stid * 8) = t;
-            }
-#else
-#pragma unroll
-            for (int i = 0; i < XCH; ++i) {
-                const int c = stid + STAGERS * i, r = c >> 3, kc = (c & 7) * 8;
-                *(u32x4_t *)(As + r * LDS_STRIDE + kc) = rg.x[i];
-            }
-#endif
-#ifdef QLORA_EXP_NOWW
-            if (rg.w[0][0] == 0x12345678u && rg.s[0] == 77 && rg.z[0] == 3) Bs[stid] = 1;
-            return;
-#endif
+            uint16_t *Bs = wsm + buf * WS;
 #pragma unroll
             for (int i = 0; i < WU; ++i) {
                 const int u = stid + STAGERS * i;
@@ -249,12 +288,7 @@ __global__ __launch_bounds__(THREADS) void qgemm_kernel(const GemmArgs a)
                 dq.set(rg.ok[i] ? f16_bits_to_f32(rg.s[i]) : 0.f, (float)rg.z[i]);
 #pragma unroll
                 for (int part = 0; part < 4; ++part) {
-#ifdef QLORA_EXP_NODEQ
-                    u16x8_t v;
-                    for (int e = 0; e < 8; ++e) v[e] = (uint16_t)(rg.w[i][0] + e);
-#else
                     const u16x8_t v = dequant8<BITS, BF16>(rg.w[i], part, dq);
-#endif
                     if constexpr (TRANS) {
                         uint16_t *dst = Bs + ((u >> 6) * 32 + part * 8) * LDS_STRIDE + (u & 63);
 #pragma unroll
@@ -267,7 +301,7 @@ __global__ __launch_bounds__(THREADS) void qgemm_kernel(const GemmArgs a)
         };
 
         // stage kt+1 is written while the MFMA waves work on stage kt; NSETS later stages are in flight from
-        // memory (one register set each), enough to cover the L2 / HBM round trip with a full stream of loads
+        // memory (one register set each)
         constexpr int NSETS = 3;
         Regs rs[NSETS];
 #pragma unroll
@@ -275,18 +309,12 @@ __global__ __launch_bounds__(THREADS) void qgemm_kernel(const GemmArgs a)
         stage(rs[0], 0);
         load_global(NSETS, rs[0]);
         __syncthreads();
-        // One step: the MFMA waves work on stage kt while stage kt+1 (held in set (i+1) % NSETS) goes to LDS and
-        // that set is refilled with stage kt+1+NSETS.
         auto step = [&](int kt, Regs &rg) {
 #ifndef QLORA_EXP_NOSTAGE
             stage(rg, (kt + 1) & 1);
 #endif
-#ifndef QLORA_EXP_NOLOAD
             load_global(kt + 1 + NSETS, rg);
-#endif
-#ifndef QLORA_EXP_NOBAR
             __syncthreads();
-#endif
         };
         // Whole rotations run without any condition inside: the compiler derives how many loads may stay in flight
         // from the static paths through the loop, and a skippable step would make it assume the shortest one.
@@ -298,37 +326,17 @@ __global__ __launch_bounds__(THREADS) void qgemm_kernel(const GemmArgs a)
 #pragma unroll
         for (int i = 0; i < NSETS - 1; ++i)
             if (kt0 + i < KT) step(kt0 + i, rs[(i + 1) % NSETS]);
-    } else {
-        // MFMA waves.  The last k-step of a stage runs from registers after the barrier, overlapping the LDS
-        // latency of the next stage's first fragments.
-        Frags f[2];
-        __syncthreads();
-        load_frags(0, 0, f[0]);
-        for (int kt = 0; kt < KT; ++kt) {
-            const int buf = kt & 1;
-#ifndef QLORA_EXP_NOMFMA
-            kstep(buf, 1, f[1], f[0]);
-            kstep(buf, 2, f[0], f[1]);
-            kstep(buf, 3, f[1], f[0]);
-#ifndef QLORA_EXP_NOBAR
-            __syncthreads();
-#endif
-            kstep(buf ^ 1, 0, f[0], f[1]);
-#else
-            __syncthreads();
-#endif
-        }
+        __syncthreads();                        // pairs with the MFMA waves' final wait-and-barrier
     }
 
     // --- LoRA term as extra contraction steps: Act' = sc * t (or u), W' = B (or A^T), zero-padded to 16.
-    //     Every wave is past the last barrier of the main loop, so both LDS stages are free.
+    //     Every wave is past the last barrier of the main loop, so every LDS stage is free.
     if (a.r > 0) {
         const int nsteps = (a.r + 15) / 16, width = nsteps * 16;
         if (stager) {
-            uint16_t *As = smem, *Bs = As + BM * LDS_STRIDE;
             const int cpr = width / 8;                      // 8-element chunks per row
             for (int c = stid; c < BM * cpr; c += STAGERS) {
-                const int r = c / cpr, j = (c % cpr) * 8;
+                const int r = c / cpr, jc = c % cpr, j = jc * 8;
                 u16x8_t p = {0, 0, 0, 0, 0, 0, 0, 0};
                 if (j < a.r) {
                     const int gm = min(row0 + r, a.M - 1);
@@ -336,7 +344,7 @@ __global__ __launch_bounds__(THREADS) void qgemm_kernel(const GemmArgs a)
 #pragma unroll
                     for (int h = 0; h < 8; ++h) p[h] = to16<BF16>(a.sc * cvt16<BF16>(v[h]));
                 }
-                *(u16x8_t *)(As + r * LDS_STRIDE + j) = p;
+                *(u16x8_t *)(xs + r * BK + ((jc ^ ((r >> 1) & 7)) * 8)) = p;  // same swizzle as the main loop
             }
             for (int c = stid; c < BN * cpr; c += STAGERS) {
                 const int r = c / cpr, j = (c % cpr) * 8;
@@ -350,14 +358,14 @@ __global__ __launch_bounds__(THREADS) void qgemm_kernel(const GemmArgs a)
                         p = *(const u16x8_t *)(a.ext_w + (long)col * a.r + j);
                     }
                 }
-                *(u16x8_t *)(Bs + r * LDS_STRIDE + j) = p;
+                *(u16x8_t *)(wsm + r * LDS_STRIDE + j) = p;
             }
         }
         __syncthreads();
         if (!stager) {
             for (int ks = 0; ks < nsteps; ++ks) {
                 Frags fx;
-                load_frags(0, ks, fx);
+                load_frags(0, 0, ks, fx);
                 mfma_frags(fx);
             }
         }
@@ -365,7 +373,7 @@ __global__ __launch_bounds__(THREADS) void qgemm_kernel(const GemmArgs a)
     }
 
     // --- epilogue: fp32 accumulators -> 16 bit.  Each MFMA wave lays its TM x TN block into its own LDS area in
-    //     row-major order; then all eight waves stream the areas out in 16-byte pieces (8 lanes per 128-byte row
+    //     row-major order; then all waves stream the areas out in 16-byte pieces (8 lanes per 128-byte row
     //     segment).  Rows beyond M and columns beyond NO (always whole 8-element pieces) are dropped.
     constexpr int ESTR = TN + 8;
     if (!stager) {
@@ -383,9 +391,8 @@ __global__ __launch_bounds__(THREADS) void qgemm_kernel(const GemmArgs a)
     {
         constexpr int CPR = TN / 8;                       // 16-byte pieces per row of one wave's area
         constexpr int PER_AREA = TM * CPR;
-#pragma unroll
-        for (int q = 0; q < 4 * PER_AREA / THREADS; ++q) {
-            const int c = tid + THREADS * q, w = c / PER_AREA, cc = c % PER_AREA;
+        for (int c = tid; c < MW * PER_AREA; c += THREADS) {
+            const int w = c / PER_AREA, cc = c % PER_AREA;
             const int r = cc / CPR, ch = (cc % CPR) * 8;
             const int grow = row0 + (w / WN) * TM + r, gcol = col0 + (w % WN) * TN + ch;
             const u32x4_t v = *(const u32x4_t *)(smem + w * (TM * ESTR) + r * ESTR + ch);
@@ -397,8 +404,8 @@ __global__ __launch_bounds__(THREADS) void qgemm_kernel(const GemmArgs a)
 template <int BITS, bool BF16, bool TRANS, int BM, int BN, int WM, int WN>
 void launch_variant(const GemmArgs &a, hipStream_t s)
 {
-    constexpr size_t lds_pipe = 2 * (size_t)(BM + BN) * LDS_STRIDE * sizeof(uint16_t);
-    constexpr size_t lds_epi = 4 * (size_t)(BM / WM) * (BN / WN + 8) * sizeof(uint16_t);
+    constexpr size_t lds_pipe = (3 * (size_t)BM * BK + 2 * (size_t)BN * LDS_STRIDE) * sizeof(uint16_t);
+    constexpr size_t lds_epi = (size_t)WM * WN * (BM / WM) * (BN / WN + 8) * sizeof(uint16_t);
     constexpr size_t lds = lds_pipe > lds_epi ? lds_pipe : lds_epi;
     auto kern = qgemm_kernel<BITS, BF16, TRANS, BM, BN, WM, WN>;
     static bool configured = false;   // raising the dynamic-LDS ceiling is a property of the function, set once
@@ -406,7 +413,7 @@ void launch_variant(const GemmArgs &a, hipStream_t s)
         (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         configured = true;
     }
-    hipLaunchKernelGGL(kern, dim3(a.tiles_m * a.tiles_n), dim3(THREADS), lds, s, a);
+    hipLaunchKernelGGL(kern, dim3(a.tiles_m * a.tiles_n), dim3(WM * WN * 64 + STAGERS), lds, s, a);
 }
 
 template <int BITS, bool BF16, bool TRANS>
@@ -420,7 +427,11 @@ void launch_tiles(GemmArgs &a, hipStream_t s)
     const int NO = TRANS ? a.K : a.N;
     a.tiles_m = (a.M + BM - 1) / BM;
     a.tiles_n = (NO + BN - 1) / BN;
-    launch_variant<BITS, BF16, TRANS, BM, BN, 2, 2>(a, s);
+#ifndef QLORA_WM
+#define QLORA_WM 2
+#define QLORA_WN 2
+#endif
+    launch_variant<BITS, BF16, TRANS, BM, BN, QLORA_WM, QLORA_WN>(a, s);
 }
 
 // Multiplier m with umulhi(q, m) == q / (G/32) for every q < 2^16 (q = k/32, K < 2^21): m = floor(2^32 / d) + 1
