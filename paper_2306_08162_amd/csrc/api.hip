@@ -52,7 +52,12 @@ Workspace carve(int M, int N, int K, int r)
     w.partial_off = off;
     const size_t pa = (size_t)adapter_grad_slices(M, K, r) * K * r * sizeof(float);
     const size_t pb = (size_t)adapter_grad_slices(M, N, r) * N * r * sizeof(float);
-    off += round_up(pa > pb ? pa : pb);
+    size_t pmax = pa > pb ? pa : pb;
+    if (M <= SMALL_M_MAX) {     // the small-M backward kernel sums row slices of dX through the same buffer
+        const size_t pg = (size_t)gemv_bwd_slices(N, K) * M * K * sizeof(float);
+        pmax = pg > pmax ? pg : pmax;
+    }
+    off += round_up(pmax);
     w.total = off < ALIGN ? ALIGN : off;
     return w;
 }
@@ -160,7 +165,10 @@ int qlora_linear_fwd(const void *x, const uint32_t *packed, const void *scales, 
     }
     {
         GemmTimer timer(s);
-        launch_fwd_mfma(p, x, packed, scales, zeros, t, B, y, s);
+        if (M <= SMALL_M_MAX)
+            launch_fwd_small(p, x, packed, scales, zeros, t, B, y, s);
+        else
+            launch_fwd_mfma(p, x, packed, scales, zeros, t, B, y, s);
     }
     return hip_status();
 }
@@ -191,7 +199,10 @@ int qlora_linear_bwd(const void *dy, const void *x, const uint32_t *packed, cons
     }
     {
         GemmTimer timer(s);
-        launch_bwd_dx_mfma(p, dy, packed, scales, zeros, u, A, dx, s);
+        if (M <= SMALL_M_MAX)
+            launch_bwd_dx_small(p, dy, packed, scales, zeros, u, A, dx, (float *)(ws + w.partial_off), s);
+        else
+            launch_bwd_dx_mfma(p, dy, packed, scales, zeros, u, A, dx, s);
     }
     if (rank > 0) {
         const void *t = t_saved;

@@ -41,4 +41,12 @@ void launch_fwd_mfma(const Problem &p, const void *x, const uint32_t *packed, co
 void launch_bwd_dx_mfma(const Problem &p, const void *dy, const uint32_t *packed, const void *scales,
                         const uint8_t *zeros, const void *u, const void *A, void *dx, hipStream_t s);
 
+// gemv.hip -- small token counts (M <= SMALL_M_MAX): weight-streaming kernels, one pass over the packed weight
+constexpr int SMALL_M_MAX = 64;
+int gemv_bwd_slices(int N, int K);   // row slices of the backward kernel; partial holds slices*M*K floats
+void launch_fwd_small(const Problem &p, const void *x, const uint32_t *packed, const void *scales,
+                      const uint8_t *zeros, const void *t, const void *B, void *y, hipStream_t s);
+void launch_bwd_dx_small(const Problem &p, const void *dy, const uint32_t *packed, const void *scales,
+                         const uint8_t *zeros, const void *u, const void *A, void *dx, float *partial, hipStream_t s);
+
 }  // namespace qlora

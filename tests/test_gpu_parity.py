@@ -60,6 +60,14 @@ SMALL_CASES = [
     (129, 256, 1000, 4, 64, 0, "f16"),        # no adapter on this projection
     (33, 1376, 512, 3, 32, 16, "f16"),
     (513, 512, 512, 4, 128, 8, "bf16"),
+    # small token counts (weight-streaming kernels), every width and both dtypes
+    (16, 512, 264, 8, 128, 8, "f16"),
+    (9, 256, 72, 8, 64, 16, "bf16"),
+    (64, 512, 128, 2, 64, 8, "bf16"),
+    (48, 256, 200, 4, 32, 8, "bf16"),
+    (2, 4096, 4096, 4, 128, 8, "f16"),
+    (17, 1376, 520, 2, 32, 32, "f16"),
+    (65, 256, 136, 4, 64, 8, "f16"),           # first M on the tiled path
 ]
 
 
