@@ -36,10 +36,10 @@ int check_problem(int M, int N, int K, int bits, int G, int r, int dtype)
 }
 
 struct Workspace {
-    size_t t_off, u_off, bt_off, partial_off, total;
+    size_t t_off, u_off, bt_off, upartial_off, partial_off, total;
 };
 
-Workspace carve(int M, int N, int K, int r)
+Workspace carve(int M, int N, int K, int r, int bits)
 {
     Workspace w{};
     size_t off = 0;
@@ -49,12 +49,14 @@ Workspace carve(int M, int N, int K, int r)
     off += round_up((size_t)M * r * 2);
     w.bt_off = off;
     off += round_up((size_t)N * r * 2);
+    w.upartial_off = off;
+    off += round_up((size_t)gemv_bwd_slices(N, K, bits) * 1024 * sizeof(float));
     w.partial_off = off;
     const size_t pa = (size_t)adapter_grad_slices(M, K, r) * K * r * sizeof(float);
     const size_t pb = (size_t)adapter_grad_slices(M, N, r) * N * r * sizeof(float);
     size_t pmax = pa > pb ? pa : pb;
-    if (M <= SMALL_M_MAX) {     // the small-M backward kernel sums row slices of dX through the same buffer
-        const size_t pg = (size_t)gemv_bwd_slices(N, K) * M * K * sizeof(float);
+    if (M <= SMALL_M_BWD_MAX) {     // the small-M backward kernel sums row slices of dX through the same buffer
+        const size_t pg = (size_t)gemv_bwd_slices(N, K, bits) * M * K * sizeof(float);
         pmax = pg > pmax ? pg : pmax;
     }
     off += round_up(pmax);
@@ -118,7 +120,7 @@ size_t qlora_packed_words(int N, int K, int bits)
 size_t qlora_workspace_bytes(int M, int N, int K, int bits, int group_size, int rank)
 {
     if (check_problem(M, N, K, bits, group_size, rank, QLORA_F16) != QLORA_OK) return 0;
-    return carve(M, N, K, rank).total;
+    return carve(M, N, K, rank, bits).total;
 }
 
 int qlora_pack(const uint8_t *codes, uint32_t *packed, int N, int K, int bits, void *stream)
@@ -152,23 +154,26 @@ int qlora_linear_fwd(const void *x, const uint32_t *packed, const void *scales, 
     if (misaligned(x) || misaligned(packed) || misaligned(scales) || misaligned(zeros) || misaligned(y) ||
         misaligned(A) || misaligned(B) || misaligned(t_save) || misaligned(workspace))
         return QLORA_E_ALIGN;
-    const Workspace w = carve(M, N, K, rank);
+    const Workspace w = carve(M, N, K, rank, bits);
     if (!workspace || workspace_bytes < w.total) return QLORA_E_WORKSPACE;
 
     const hipStream_t s = (hipStream_t)stream;
     const Problem p{M, N, K, bits, group_size, rank, rank > 0 ? alpha / (float)rank : 0.f, dtype == QLORA_BF16};
     char *ws = (char *)workspace;
-    void *t = nullptr;
-    if (rank > 0) {
-        t = t_save ? t_save : (void *)(ws + w.t_off);
-        launch_lora_down(x, A, t, M, K, rank, p.bf16, s);
-    }
-    {
+    if (M <= SMALL_M_FWD_MAX) {
+        // one launch: the weight-streaming kernel also forms t (ranks up to 32)
+        void *t = rank > 0 ? (t_save ? t_save : (void *)(ws + w.t_off)) : nullptr;
+        if (rank > 0 && !fwd_small_computes_t(rank)) launch_lora_down(x, A, t, M, K, rank, p.bf16, s);
         GemmTimer timer(s);
-        if (M <= SMALL_M_MAX)
-            launch_fwd_small(p, x, packed, scales, zeros, t, B, y, s);
-        else
-            launch_fwd_mfma(p, x, packed, scales, zeros, t, B, y, s);
+        launch_fwd_small(p, x, packed, scales, zeros, A, B, t, t, y, s);
+    } else {
+        void *t = nullptr;
+        if (rank > 0) {
+            t = t_save ? t_save : (void *)(ws + w.t_off);
+            launch_lora_down(x, A, t, M, K, rank, p.bf16, s);
+        }
+        GemmTimer timer(s);
+        launch_fwd_mfma(p, x, packed, scales, zeros, t, B, y, s);
     }
     return hip_status();
 }
@@ -186,12 +191,24 @@ int qlora_linear_bwd(const void *dy, const void *x, const uint32_t *packed, cons
         misaligned(A) || misaligned(B) || misaligned(t_saved) || misaligned(dx) || misaligned(dA) || misaligned(dB) ||
         misaligned(workspace))
         return QLORA_E_ALIGN;
-    const Workspace w = carve(M, N, K, rank);
+    const Workspace w = carve(M, N, K, rank, bits);
     if (!workspace || workspace_bytes < w.total) return QLORA_E_WORKSPACE;
 
     const hipStream_t s = (hipStream_t)stream;
     const Problem p{M, N, K, bits, group_size, rank, rank > 0 ? alpha / (float)rank : 0.f, dtype == QLORA_BF16};
     char *ws = (char *)workspace;
+    if (M <= SMALL_M_BWD_MAX) {
+        // two launches: partial dX and u over row slices of the weight, then the sums, dA and dB
+        const void *t = t_saved;
+        if (rank > 0 && !t) {
+            launch_lora_down(x, A, ws + w.t_off, M, K, rank, p.bf16, s);
+            t = ws + w.t_off;
+        }
+        GemmTimer timer(s);
+        launch_bwd_small(p, dy, x, packed, scales, zeros, A, B, t, dx, dA, dB, (float *)(ws + w.partial_off),
+                         (float *)(ws + w.upartial_off), s);
+        return hip_status();
+    }
     void *u = nullptr;
     if (rank > 0) {
         u = ws + w.u_off;
@@ -199,10 +216,7 @@ int qlora_linear_bwd(const void *dy, const void *x, const uint32_t *packed, cons
     }
     {
         GemmTimer timer(s);
-        if (M <= SMALL_M_MAX)
-            launch_bwd_dx_small(p, dy, packed, scales, zeros, u, A, dx, (float *)(ws + w.partial_off), s);
-        else
-            launch_bwd_dx_mfma(p, dy, packed, scales, zeros, u, A, dx, s);
+        launch_bwd_dx_mfma(p, dy, packed, scales, zeros, u, A, dx, s);
     }
     if (rank > 0) {
         const void *t = t_saved;

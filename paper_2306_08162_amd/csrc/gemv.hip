@@ -1,12 +1,15 @@
-// Small token counts (M <= 64): the pass is bound by streaming the packed weight once from HBM, so every lane
-// fetches its own MFMA fragment of packed words straight from global memory, dequantises it in registers and
-// feeds v_mfma_f32_16x16x32; nothing but partial sums goes through LDS.  (Limitations of the paper: the compressed
-// weight cuts the memory traffic of both passes; this is the regime where that shows.)
+// Small token counts: the pass is bound by streaming the packed weight once from HBM (Limitations of the paper:
+// the compressed weight cuts the memory traffic of both passes; this is the regime where that shows).  Every lane
+// fetches its own MFMA fragment of packed words straight from global memory, dequantises it in registers and feeds
+// v_mfma_f32_16x16x32; only partial sums go through LDS.  Launches are what the pass is made of at this size, so
+// the rank-r products ride along: one launch forward, two backward.
 //
-//   forward   y [M,N] = x  Wd^T + sc * t B^T     one workgroup per 16 weight rows, its 4 waves split K
-//   backward  dX[M,K] = dY Wd   + sc * u A       one workgroup per 128 weight columns and slice of rows;
-//             the contraction runs over rows n, so a lane gathers one word from each of 8 rows and transposes
-//             the 8 x 8 block of codes in registers (Sec. 3.1: transpose + unpack + matmul in one kernel)
+//   forward  (M <= 64)  y = x Wd^T + sc * t B^T with t = x A^T computed by the same MFMAs (one extra fragment of
+//            A per k-step); one workgroup per 16 weight rows, its 4 waves split K.
+//   backward (M <= 16)  kernel 1: partial dX = dY Wd over row slices of the weight, and partial u = dY B.  The
+//            contraction runs over the weight's rows n, so a lane gathers the same few words from 8 consecutive
+//            rows and transposes the 8 x CL block of codes in registers (Sec. 3.1: transpose + unpack + matmul in one
+//            kernel).  kernel 2: sums the slices, adds sc * u A, and forms dA = sc u^T x and dB = sc dY^T t.
 #include "common.hpp"
 #include "dequant.hpp"
 #include "kernels.hpp"
@@ -52,49 +55,79 @@ __device__ __forceinline__ void load_words(const uint32_t *__restrict__ p, uint3
 
 __device__ __forceinline__ int group_of(int k, uint32_t magic) { return magic ? (int)__umulhi((uint32_t)(k >> 5), magic) : (k >> 5); }
 
+constexpr u16x8_t ZERO8 = {0, 0, 0, 0, 0, 0, 0, 0};
+
 // ------------------------------------------------------------------------------------------------- forward
 constexpr int FW_U = 4;   // iterations (128 codes per row each) whose loads are in flight together
 
-template <int BITS, bool BF16, int MB>
-__global__ __launch_bounds__(256) void gemv_fwd_kernel(const uint16_t *__restrict__ x, const uint32_t *__restrict__ packed,
-                                                       const uint16_t *__restrict__ scales, const uint8_t *__restrict__ zeros,
-                                                       const uint16_t *__restrict__ t, const uint16_t *__restrict__ B,
-                                                       uint16_t *__restrict__ y, int M, int N, int K, int r, float sc,
-                                                       uint32_t magic, int ng)
+struct FwdArgs {
+    const uint16_t *x;
+    const uint32_t *packed;
+    const uint16_t *scales;
+    const uint8_t *zeros;
+    const uint16_t *A, *B;
+    const uint16_t *t_in;     // t computed elsewhere (ranks above 32), else NULL: computed here
+    uint16_t *y, *t_out;      // t_out may be NULL
+    int M, N, K, r, ng;
+    float sc;
+    uint32_t magic;
+};
+
+template <int BITS, bool BF16, int MB, int RG, int NW>   // RG = 16-column groups of t formed here (0: none); NW waves
+__global__ __launch_bounds__(NW * 64) void gemv_fwd_kernel(const FwdArgs a)
 {
-    __shared__ float red[4][MB][16][17];
+    constexpr int RGS = RG > 0 ? RG : 1, NT = NW * 64;
+    __shared__ float red[NW][MB][16][17];
+    __shared__ float tred[NW][MB][RGS][16][17];
+    constexpr int TC = RG > 0 ? RG * 16 : 64;      // columns of t kept in LDS
+    __shared__ float tfull[MB * 16][TC + 1];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, li = lane & 15, q = lane >> 4;
-    const int n0 = blockIdx.x * 16, n = min(n0 + li, N - 1);
-    const int Kw = K * BITS / 32;
-    const uint32_t *wrow = packed + (long)n * Kw;
-    const uint16_t *xrow[MB];
+    const int n0 = blockIdx.x * 16, n = min(n0 + li, a.N - 1);
+    const int K = a.K, Kw = K * BITS / 32, r = a.r;
+    const uint32_t *wrow = a.packed + (long)n * Kw;
+    const uint16_t *xrow[MB], *arow[RGS];
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb) xrow[mb] = x + (long)min(mb * 16 + li, M - 1) * K;
-
-    float4_t acc[MB];
+    for (int mb = 0; mb < MB; ++mb) xrow[mb] = a.x + (long)min(mb * 16 + li, a.M - 1) * K;
+    bool aval[RGS];
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb) acc[mb] = float4_t{0.f, 0.f, 0.f, 0.f};
+    for (int g = 0; g < RGS; ++g) {
+        aval[g] = RG > 0 && g * 16 + li < r;
+        arow[g] = a.A + (long)(RG > 0 ? min(g * 16 + li, r - 1) : 0) * K;
+    }
 
-    const int iters = (K + 127) / 128;          // wave w takes iterations w, w+4, ...: neighbours read neighbouring bytes
-    for (int it0 = wave; it0 < iters; it0 += 4 * FW_U) {
+    float4_t acc[MB], tacc[MB][RGS];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+        acc[mb] = float4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int g = 0; g < RGS; ++g) tacc[mb][g] = float4_t{0.f, 0.f, 0.f, 0.f};
+    }
+
+    const int iters = (K + 127) / 128;          // wave w takes iterations w, w+NW, ...: neighbours read neighbouring bytes
+    for (int it0 = wave; it0 < iters; it0 += NW * FW_U) {
         uint32_t w[FW_U][BITS];
         uint16_t sraw[FW_U];
         uint8_t zraw[FW_U];
         bool ok[FW_U];
-        u16x8_t xf[FW_U][MB][4];
+        u16x8_t xf[FW_U][MB][4], af[FW_U][RGS][4];
 #pragma unroll
         for (int u = 0; u < FW_U; ++u) {
-            const int kb = (it0 + 4 * u) * 128 + 32 * q;
+            const int kb = (it0 + NW * u) * 128 + 32 * q;
             ok[u] = kb < K;
             const int kc = ok[u] ? kb : 0;
             load_words<BITS>(wrow + (kc >> 5) * BITS, w[u]);
-            const long gi = (long)n * ng + group_of(kc, magic);
-            sraw[u] = scales[gi];
-            zraw[u] = zeros[gi];
+            const long gi = (long)n * a.ng + group_of(kc, a.magic);
+            sraw[u] = a.scales[gi];
+            zraw[u] = a.zeros[gi];
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
+            for (int s = 0; s < 4; ++s) {
 #pragma unroll
-                for (int s = 0; s < 4; ++s) xf[u][mb][s] = *(const u16x8_t *)(xrow[mb] + kc + 8 * s);
+                for (int mb = 0; mb < MB; ++mb) xf[u][mb][s] = *(const u16x8_t *)(xrow[mb] + kc + 8 * s);
+                if constexpr (RG > 0) {
+#pragma unroll
+                    for (int g = 0; g < RG; ++g) af[u][g][s] = *(const u16x8_t *)(arow[g] + kc + 8 * s);
+                }
+            }
         }
 #pragma unroll
         for (int u = 0; u < FW_U; ++u) {
@@ -105,199 +138,285 @@ __global__ __launch_bounds__(256) void gemv_fwd_kernel(const uint16_t *__restric
                 const u16x8_t wf = dequant8<BITS, BF16>(w[u], s, dq);
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb) acc[mb] = mfma16<BF16>(xf[u][mb][s], wf, acc[mb]);   // D[m = 4q+v][n = li]
+                if constexpr (RG > 0) {
+#pragma unroll
+                    for (int g = 0; g < RG; ++g) {
+                        const u16x8_t afz = (aval[g] && ok[u]) ? af[u][g][s] : ZERO8;
+#pragma unroll
+                        for (int mb = 0; mb < MB; ++mb) tacc[mb][g] = mfma16<BF16>(xf[u][mb][s], afz, tacc[mb][g]);   // D[m][j = li]
+                    }
+                }
             }
         }
     }
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) red[wave][mb][4 * q + v][li] = acc[mb][v];
+        for (int v = 0; v < 4; ++v) {
+            red[wave][mb][4 * q + v][li] = acc[mb][v];
+            if constexpr (RG > 0) {
+#pragma unroll
+                for (int g = 0; g < RG; ++g) tred[wave][mb][g][4 * q + v][li] = tacc[mb][g][v];
+            }
+        }
     __syncthreads();
-    for (int e = threadIdx.x; e < MB * 256; e += 256) {
+    // t for all token rows of the call (every workgroup computes the same t; workgroup 0 hands it out)
+    if constexpr (RG > 0) {
+        for (int e = threadIdx.x; e < MB * 16 * RG * 16; e += NT) {
+            const int m = e / (RG * 16), j = e % (RG * 16);
+            float tv = 0.f;
+            if (j < r && m < a.M) {
+                const int mb = m >> 4, ml = m & 15, g = j >> 4, jl = j & 15;
+#pragma unroll
+                for (int w = 0; w < NW; ++w) tv += tred[w][mb][g][ml][jl];
+                tv = cvt16<BF16>(to16<BF16>(tv));          // the value every consumer of t sees
+                if (blockIdx.x == 0 && a.t_out) a.t_out[(long)m * r + j] = to16<BF16>(tv);
+            }
+            tfull[m][j] = tv;
+        }
+    } else {
+        for (int e = threadIdx.x; e < a.M * r; e += NT) tfull[e / r][e % r] = cvt16<BF16>(a.t_in[e]);
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < MB * 256; e += NT) {
         const int mb = e >> 8, ml = (e >> 4) & 15, nl = e & 15;
         const int m = mb * 16 + ml, nn = n0 + nl;
-        if (m >= M || nn >= N) continue;
-        float v = ((red[0][mb][ml][nl] + red[1][mb][ml][nl]) + red[2][mb][ml][nl]) + red[3][mb][ml][nl];
+        if (m >= a.M || nn >= a.N) continue;
+        float v = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) v += red[w][mb][ml][nl];
         float lo = 0.f;
-        for (int j = 0; j < r; ++j) lo += cvt16<BF16>(t[(long)m * r + j]) * cvt16<BF16>(B[(long)nn * r + j]);
-        y[(long)m * N + nn] = to16<BF16>(v + sc * lo);
+        for (int j0 = 0; j0 < r; j0 += 8) {
+            const u16x8_t bv = *(const u16x8_t *)(a.B + (long)nn * r + j0);
+#pragma unroll
+            for (int h = 0; h < 8; ++h) lo += tfull[m][j0 + h] * cvt16<BF16>(bv[h]);
+        }
+        a.y[(long)m * a.N + nn] = to16<BF16>(v + a.sc * lo);
     }
 }
 
 // ------------------------------------------------------------------------------------------------ backward
-// Workgroup (cb, sp): weight columns [128 cb, +128), rows n of slice sp; wave w takes 32-row chunks w, w+4, ...
-// Lane (wc = lane % 16, q = lane / 16) loads the word holding columns 128 cb + 8 wc .. + 8 from rows
-// chunk*32 + 8 q + e, e = 0..7.  MFMA number c of a chunk multiplies dY[m, 32 rows] with the codes at column
-// 8 wc + c of those rows: D_c[m][k = 128 cb + 8 wc + c].
-constexpr int BW_COLS = 128;
+// Workgroup (cb, sp): weight columns [CB cb, +CB), CB = 16 * CL, rows n of slice sp; wave w takes 32-row chunks
+// w, w+4, ...  Lane (wc = lane % 16, q = lane / 16) holds the CL codes of columns CB cb + CL wc .. of rows
+// chunk + 8 q + e, e = 0..7.  MFMA number c of a chunk multiplies dY[m, 32 rows] with the codes at column
+// CL wc + c of those rows: D_c[m][k = CB cb + CL wc + c].
+template <int BITS>
+struct BwdShape {
+    static constexpr int CL = BITS == 3 ? 32 : (BITS == 2 ? 16 : 8);   // columns per lane: 4, 8 or 12 bytes of codes
+    static constexpr int WORDS = CL * BITS / 32;
+    static constexpr int CB = 16 * CL;
+};
 
-// Column c (compile-time) of an 8-row block of words holding 8 codes each, as eight 16-bit floats
-// s_e * (q_e - z_e), rows e = 0..7.  Only widths whose 8 codes fill a whole number of bytes go through here.
-template <int BITS, bool BF16>
-__device__ __forceinline__ u16x8_t column8(const uint32_t (&w)[8], int c, const float (&s)[8], const float (&z)[8])
+struct BwdArgs {
+    const uint16_t *dy;
+    const uint32_t *packed;
+    const uint16_t *scales;
+    const uint8_t *zeros;
+    const uint16_t *B;
+    float *partial;       // [slices][M][K]
+    float *upartial;      // [slices][16][64]
+    int M, N, K, r, ng, rows_per_slice;
+    uint32_t magic;
+};
+
+// code c (compile-time) of a lane's CL codes held in WORDS words
+template <int BITS, int WORDS>
+__device__ __forceinline__ uint32_t code_of(const uint32_t (&w)[WORDS], int c)
 {
-    u16x8_t out;
     constexpr uint32_t mask = (1u << BITS) - 1u;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const float v = ((float)((w[e] >> (BITS * c)) & mask) - z[e]) * s[e];
-        out[e] = to16<BF16>(v);
-    }
-    return out;
+    const int o = BITS * c, wi = o >> 5, sh = o & 31;
+    uint32_t v = w[wi] >> sh;
+    if (sh + BITS > 32) v |= w[wi + 1] << (32 - sh);
+    return v & mask;
 }
 
-template <int BITS, bool BF16, int MB>
-__global__ __launch_bounds__(256) void gemv_bwd_kernel(const uint16_t *__restrict__ dy, const uint32_t *__restrict__ packed,
-                                                       const uint16_t *__restrict__ scales, const uint8_t *__restrict__ zeros,
-                                                       float *__restrict__ partial, int M, int N, int K, uint32_t magic,
-                                                       int ng, int rows_per_slice)
+template <int BITS, bool BF16>
+__global__ __launch_bounds__(256) void gemv_bwd_kernel(const BwdArgs a)
 {
-    // 8 codes of a row = BITS bytes; a lane's "word" is the 32-bit window starting at that byte
-    __shared__ float red[4][16][BW_COLS + 1];
+    using S = BwdShape<BITS>;
+    constexpr int CL = S::CL, WORDS = S::WORDS, CB = S::CB;
+    __shared__ float red[4][16][128 + 1];   // the column block is reduced 128 columns at a time
+    __shared__ float ured[4][16][64 + 1];
+    __shared__ uint16_t sz_s[4][32];        // per wave: scales of its 32 rows (this lane's group is fetched by lane row)
+    __shared__ uint8_t sz_z[4][32];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wc = lane & 15, q = lane >> 4;
-    const int kcol = blockIdx.x * BW_COLS + 8 * wc;          // first of this lane's 8 columns
+    const int N = a.N, K = a.K, r = a.r;
+    const int kcol = blockIdx.x * CB + CL * wc;             // first of this lane's CL columns (all in one group: CL | 32)
     const bool kok = kcol < K;
     const int kc = kok ? kcol : 0;
     const int Kw = K * BITS / 32;
-    const int g = group_of(kc, magic);
-    const int nbeg = blockIdx.y * rows_per_slice, nend = min(N, nbeg + rows_per_slice);
-    const uint8_t *pbytes = (const uint8_t *)packed;
+    const int g = group_of(kc, a.magic);
+    const bool uniform_group = group_of(blockIdx.x * CB, a.magic) == group_of(min(blockIdx.x * CB + CB, K) - 1, a.magic);
+    const int nbeg = blockIdx.y * a.rows_per_slice, nend = min(N, nbeg + a.rows_per_slice);
+    const bool do_u = blockIdx.x == 0 && r > 0;
 
-    float4_t acc[MB][8];
+    float4_t acc[CL], uacc[4];
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb)
+    for (int c = 0; c < CL; ++c) acc[c] = float4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int c = 0; c < 8; ++c) acc[mb][c] = float4_t{0.f, 0.f, 0.f, 0.f};
+    for (int gg = 0; gg < 4; ++gg) uacc[gg] = float4_t{0.f, 0.f, 0.f, 0.f};
 
     for (int n0 = nbeg + wave * 32; n0 < nend; n0 += 128) {
-        uint32_t w[8];
+        uint32_t w[8][WORDS];
         float s[8], z[8];
-        u16x8_t df[MB];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            const int n = n0 + 8 * q + e;
-            const bool ok = kok && n < nend;
-            const int nc = min(n, N - 1);
-            const uint8_t *src = pbytes + (long)nc * Kw * 4 + (long)(kc >> 3) * BITS;   // byte address of 8 codes
-            if constexpr (BITS == 4) {
-                w[e] = *(const uint32_t *)src;
-            } else if constexpr (BITS == 8) {
-                w[e] = 0;   // handled below with two words
-            } else if constexpr (BITS == 2) {
-                w[e] = *(const uint16_t *)src;
-            } else {        // 3 bits: 3 bytes, not word aligned
-                uint32_t v = 0;
+            const int nc = min(n0 + 8 * q + e, N - 1);
+            const uint32_t *src = a.packed + (long)nc * Kw + (kc / CL) * WORDS;
+            if constexpr (WORDS == 2) {
+                const u32x2_t v = *(const u32x2_t *)src;
+                w[e][0] = v[0];
+                w[e][1] = v[1];
+            } else if constexpr (WORDS == 0) {     // unreachable, keeps WORDS >= 1 visible to the compiler
+            } else {
 #pragma unroll
-                for (int b = 0; b < BITS; ++b) v |= (uint32_t)src[b] << (8 * b);
-                w[e] = v;
+                for (int i = 0; i < WORDS; ++i) w[e][i] = src[i];
             }
-            const long gi = (long)nc * ng + g;
-            s[e] = ok ? f16_bits_to_f32(scales[gi]) : 0.f;
-            z[e] = (float)zeros[gi];
         }
-        uint32_t w2[8];     // second word for 8-bit codes (columns 4..7)
-        if constexpr (BITS == 8) {
+        const int mrow = min(wc, a.M - 1), nn = n0 + 8 * q;   // dY fragment: token row wc, 8 consecutive rows n
+        const bool in = nn < nend;                            // N % 8 == 0, slices are multiples of 32: all or nothing
+        u16x8_t df = *(const u16x8_t *)(a.dy + (long)mrow * N + (in ? nn : 0));
+        if (!in) df = ZERO8;
+
+        if (uniform_group) {
+            // one scale / zero-point per row for the whole column block: 32 loads per wave, shared through LDS
+            if (lane < 32) {
+                const long gi = (long)min(n0 + lane, N - 1) * a.ng + g;
+                sz_s[wave][lane] = a.scales[gi];
+                sz_z[wave][lane] = a.zeros[gi];
+            }
+            __builtin_amdgcn_wave_barrier();
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const int nc = min(n0 + 8 * q + e, N - 1);
-                const u32x2_t v = *(const u32x2_t *)(pbytes + (long)nc * Kw * 4 + (long)(kc >> 3) * 8);
-                w[e] = v[0];
-                w2[e] = v[1];
+                const bool ok = kok && n0 + 8 * q + e < nend;
+                s[e] = ok ? f16_bits_to_f32(sz_s[wave][8 * q + e]) : 0.f;
+                z[e] = (float)sz_z[wave][8 * q + e];
+            }
+            __builtin_amdgcn_wave_barrier();
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int n = n0 + 8 * q + e;
+                const bool ok = kok && n < nend;
+                const long gi = (long)min(n, N - 1) * a.ng + g;
+                s[e] = ok ? f16_bits_to_f32(a.scales[gi]) : 0.f;
+                z[e] = (float)a.zeros[gi];
+            }
+        }
+        if (do_u) {     // u = dY B over this chunk: B^T fragment gathered column-wise (only the first column block)
+#pragma unroll
+            for (int gg = 0; gg < 4; ++gg) {
+                if (gg * 16 < r) {
+                    u16x8_t bf = ZERO8;
+                    const int j = gg * 16 + wc;
+                    if (in && j < r) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) bf[e] = a.B[(long)(nn + e) * r + j];
+                    }
+                    uacc[gg] = mfma16<BF16>(df, bf, uacc[gg]);      // D[m = 4q+v][j = 16 gg + wc]
+                }
             }
         }
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
-            const int m = min(mb * 16 + wc, M - 1);
-            const int nn = n0 + 8 * q;                       // 8 consecutive rows n = contraction indices of this lane
-            const bool in = nn < nend;                       // N % 8 == 0 and slices are multiples of 32: all or nothing
-            df[mb] = *(const u16x8_t *)(dy + (long)m * N + (in ? nn : 0));
-            if (!in) df[mb] = u16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
-        }
-#pragma unroll
-        for (int c = 0; c < 8; ++c) {
+        for (int c = 0; c < CL; ++c) {
             u16x8_t wf;
-            if constexpr (BITS == 8)
-                wf = c < 4 ? column8<8, BF16>(w, c, s, z) : column8<8, BF16>(w2, c - 4, s, z);
-            else
-                wf = column8<BITS, BF16>(w, c, s, z);
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb) acc[mb][c] = mfma16<BF16>(df[mb], wf, acc[mb][c]);   // D[m = 4q+v][col wc]
+            for (int e = 0; e < 8; ++e) wf[e] = to16<BF16>(((float)code_of<BITS, WORDS>(w[e], c) - z[e]) * s[e]);
+            acc[c] = mfma16<BF16>(df, wf, acc[c]);                  // D[m = 4q+v][column CL wc + c]
         }
     }
+    if (do_u) {
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb) {
-        if (mb) __syncthreads();
+        for (int gg = 0; gg < 4; ++gg)
 #pragma unroll
-        for (int c = 0; c < 8; ++c)
+            for (int v = 0; v < 4; ++v) ured[wave][4 * q + v][16 * gg + wc] = uacc[gg][v];
+    }
+    for (int cp = 0; cp < CB / 128; ++cp) {
+        if (cp) __syncthreads();
+        if ((CL * wc) / 128 == cp) {
 #pragma unroll
-            for (int v = 0; v < 4; ++v) red[wave][4 * q + v][8 * wc + c] = acc[mb][c][v];
+            for (int c = 0; c < CL; ++c)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) red[wave][4 * q + v][(CL * wc + c) & 127] = acc[c][v];
+        }
         __syncthreads();
-        for (int e = threadIdx.x; e < 16 * BW_COLS; e += 256) {
-            const int ml = e / BW_COLS, kl = e % BW_COLS;
-            const int m = mb * 16 + ml, k = blockIdx.x * BW_COLS + kl;
-            if (m >= M || k >= K) continue;
-            const float v = ((red[0][ml][kl] + red[1][ml][kl]) + red[2][ml][kl]) + red[3][ml][kl];
-            partial[((long)blockIdx.y * M + m) * K + k] = v;
+        for (int e = threadIdx.x; e < 16 * 128; e += 256) {
+            const int m = e >> 7, kl = e & 127, k = blockIdx.x * CB + cp * 128 + kl;
+            if (m >= a.M || k >= K) continue;
+            a.partial[((long)blockIdx.y * a.M + m) * K + k] = ((red[0][m][kl] + red[1][m][kl]) + red[2][m][kl]) + red[3][m][kl];
+        }
+    }
+    if (do_u) {
+        for (int e = threadIdx.x; e < 16 * 64; e += 256) {
+            const int m = e >> 6, j = e & 63;
+            a.upartial[(long)blockIdx.y * 1024 + e] = ((ured[0][m][j] + ured[1][m][j]) + ured[2][m][j]) + ured[3][m][j];
         }
     }
 }
 
-// dx[m,k] = sum over slices (in order) of partial + sc * sum_j u[m,j] A[j,k]
+// Second backward kernel (M <= 16), one thread per output element:
+//   blocks [0, xb)        dX[m,k] = sum over slices of partial + sc * sum_j u[m,j] A[j,k]
+//   blocks [xb, xb+ab)    dA[j,k] = sc * sum_m u[m,j] x[m,k]
+//   blocks [xb+ab, ...)   dB[n,j] = sc * sum_m dY[m,n] t[m,j]
+// u = sum over slices of the partial u; every block that needs it sums the few entries itself.
+struct FinishArgs {
+    const float *partial, *upartial;
+    const uint16_t *A, *x, *dy, *t;
+    uint16_t *dx;
+    float *dA, *dB;
+    int M, N, K, r, slices, xb, ab;
+    float sc;
+};
+
 template <bool BF16>
-__global__ __launch_bounds__(256) void gemv_bwd_finish_kernel(const float *__restrict__ partial, const uint16_t *__restrict__ u,
-                                                              const uint16_t *__restrict__ A, uint16_t *__restrict__ dx,
-                                                              int M, int K, int r, float sc, int slices)
+__global__ __launch_bounds__(256) void gemv_bwd_finish_kernel(const FinishArgs a)
 {
-    const long idx = (long)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= (long)M * K) return;
-    const int m = (int)(idx / K), k = (int)(idx % K);
-    float v = 0.f;
-    for (int s = 0; s < slices; ++s) v += partial[(long)s * M * K + idx];
-    float lo = 0.f;
-    for (int j = 0; j < r; ++j) lo += cvt16<BF16>(u[(long)m * r + j]) * cvt16<BF16>(A[(long)j * K + k]);
-    dx[idx] = to16<BF16>(v + sc * lo);
-}
-
-template <int BITS, bool BF16>
-void launch_fwd_mb(const Problem &p, const void *x, const uint32_t *packed, const void *scales, const uint8_t *zeros,
-                   const void *t, const void *B, void *y, uint32_t magic, hipStream_t s)
-{
-    const dim3 grid((p.N + 15) / 16), block(256);
-    const int ng = p.K / p.G;
-#define QLORA_FWD(MBV)                                                                                              \
-    hipLaunchKernelGGL((gemv_fwd_kernel<BITS, BF16, MBV>), grid, block, 0, s, (const uint16_t *)x, packed,           \
-                       (const uint16_t *)scales, zeros, (const uint16_t *)t, (const uint16_t *)B, (uint16_t *)y, p.M, \
-                       p.N, p.K, p.r, p.sc, magic, ng)
-    switch ((p.M + 15) / 16) {
-    case 1: QLORA_FWD(1); break;
-    case 2: QLORA_FWD(2); break;
-    case 3: QLORA_FWD(3); break;
-    default: QLORA_FWD(4); break;
+    __shared__ float side[16][64 + 1];       // u (dX and dA blocks) or t (dB blocks), as the 16-bit values they round to
+    const int M = a.M, r = a.r, K = a.K, N = a.N;
+    const int b = blockIdx.x;
+    if (b < a.xb + a.ab) {
+        for (int e = threadIdx.x; e < M * r; e += 256) {
+            const int m = e / r, j = e % r;
+            float v = 0.f;
+            for (int s = 0; s < a.slices; ++s) v += a.upartial[(long)s * 1024 + m * 64 + j];
+            side[m][j] = cvt16<BF16>(to16<BF16>(v));
+        }
+    } else {
+        for (int e = threadIdx.x; e < M * r; e += 256) side[e / r][e % r] = cvt16<BF16>(a.t[e]);
     }
-#undef QLORA_FWD
-}
-
-template <int BITS, bool BF16>
-void launch_bwd_mb(const Problem &p, const void *dy, const uint32_t *packed, const void *scales, const uint8_t *zeros,
-                   const void *u, const void *A, void *dx, float *partial, uint32_t magic, hipStream_t s)
-{
-    const int slices = gemv_bwd_slices(p.N, p.K);
-    const int rows_per_slice = ((p.N + slices - 1) / slices + 31) / 32 * 32;
-    const dim3 grid((p.K + BW_COLS - 1) / BW_COLS, slices), block(256);
-    const int ng = p.K / p.G;
-#define QLORA_BWD(MBV)                                                                                         \
-    hipLaunchKernelGGL((gemv_bwd_kernel<BITS, BF16, MBV>), grid, block, 0, s, (const uint16_t *)dy, packed,     \
-                       (const uint16_t *)scales, zeros, partial, p.M, p.N, p.K, magic, ng, rows_per_slice)
-    switch ((p.M + 15) / 16) {
-    case 1: QLORA_BWD(1); break;
-    case 2: QLORA_BWD(2); break;
-    case 3: QLORA_BWD(3); break;
-    default: QLORA_BWD(4); break;
+    __syncthreads();
+    if (b < a.xb) {
+        const long idx = (long)b * 256 + threadIdx.x;
+        if (idx >= (long)M * K) return;
+        const int m = (int)(idx / K), k = (int)(idx % K);
+        const long stride = (long)M * K;
+        float v = 0.f;
+        int s = 0;
+        for (; s + 4 <= a.slices; s += 4) {
+            const float p0 = a.partial[(s + 0) * stride + idx], p1 = a.partial[(s + 1) * stride + idx];
+            const float p2 = a.partial[(s + 2) * stride + idx], p3 = a.partial[(s + 3) * stride + idx];
+            v = (((v + p0) + p1) + p2) + p3;
+        }
+        for (; s < a.slices; ++s) v += a.partial[s * stride + idx];
+        float lo = 0.f;
+        for (int j = 0; j < r; ++j) lo += side[m][j] * cvt16<BF16>(a.A[(long)j * K + k]);
+        a.dx[idx] = to16<BF16>(v + a.sc * lo);
+    } else if (b < a.xb + a.ab) {
+        const long idx = (long)(b - a.xb) * 256 + threadIdx.x;
+        if (idx >= (long)r * K) return;
+        const int j = (int)(idx / K), k = (int)(idx % K);
+        float v = 0.f;
+        for (int m = 0; m < M; ++m) v += side[m][j] * cvt16<BF16>(a.x[(long)m * K + k]);
+        a.dA[idx] = a.sc * v;
+    } else {
+        const long idx = (long)(b - a.xb - a.ab) * 256 + threadIdx.x;
+        if (idx >= (long)r * N) return;
+        const int j = (int)(idx / N), n = (int)(idx % N);
+        float v = 0.f;
+        for (int m = 0; m < M; ++m) v += cvt16<BF16>(a.dy[(long)m * N + n]) * side[m][j];
+        a.dB[(long)n * r + j] = a.sc * v;
     }
-#undef QLORA_BWD
-    const long n = (long)p.M * p.K;
-    hipLaunchKernelGGL((gemv_bwd_finish_kernel<BF16>), dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, partial,
-                       (const uint16_t *)u, (const uint16_t *)A, (uint16_t *)dx, p.M, p.K, p.r, p.sc, slices);
 }
 
 inline uint32_t group_magic(int G)
@@ -306,12 +425,45 @@ inline uint32_t group_magic(int G)
     return d == 1 ? 0u : (uint32_t)(0x100000000ull / d) + 1u;
 }
 
+template <int BITS, bool BF16, int MB>
+void launch_fwd_rg(const FwdArgs &a, int rg, hipStream_t s)
+{
+    constexpr int NW = MB == 1 ? 8 : 4;     // one 16-row token block: more waves, so each has fewer loads to wait for
+    const dim3 grid((a.N + 15) / 16), block(NW * 64);
+    switch (rg) {
+    case 0: hipLaunchKernelGGL((gemv_fwd_kernel<BITS, BF16, MB, 0, NW>), grid, block, 0, s, a); break;
+    case 1: hipLaunchKernelGGL((gemv_fwd_kernel<BITS, BF16, MB, 1, NW>), grid, block, 0, s, a); break;
+    default: hipLaunchKernelGGL((gemv_fwd_kernel<BITS, BF16, MB, 2, NW>), grid, block, 0, s, a); break;
+    }
+}
+
+template <int BITS, bool BF16>
+void launch_fwd_mb(const FwdArgs &a, int rg, hipStream_t s)
+{
+    switch ((a.M + 15) / 16) {
+    case 1: launch_fwd_rg<BITS, BF16, 1>(a, rg, s); break;
+    case 2: launch_fwd_rg<BITS, BF16, 2>(a, rg, s); break;
+    case 3: launch_fwd_rg<BITS, BF16, 3>(a, rg, s); break;
+    default: launch_fwd_rg<BITS, BF16, 4>(a, rg, s); break;
+    }
+}
+
+template <int BITS, bool BF16>
+void launch_bwd_bits(const BwdArgs &a, int slices, hipStream_t s)
+{
+    const dim3 grid((a.K + BwdShape<BITS>::CB - 1) / BwdShape<BITS>::CB, slices), block(256);
+    hipLaunchKernelGGL((gemv_bwd_kernel<BITS, BF16>), grid, block, 0, s, a);
+}
+
+int bwd_cb(int bits) { return bits == 3 ? 512 : (bits == 2 ? 256 : 128); }
+
 }  // namespace
 
-int gemv_bwd_slices(int N, int K)
+int gemv_bwd_slices(int N, int K, int bits)
 {
-    const int colblocks = (K + BW_COLS - 1) / BW_COLS;
-    int slices = (512 + colblocks - 1) / colblocks;      // aim at >= 512 workgroups
+    const int colblocks = (K + bwd_cb(bits) - 1) / bwd_cb(bits);
+    int slices = (256 + colblocks - 1) / colblocks;      // aim at one workgroup per compute unit: every extra slice
+                                                         // costs another M x K block of partial sums
     const int max_slices = (N + 127) / 128;              // at least one 32-row chunk per wave
     if (slices > max_slices) slices = max_slices;
     return slices < 1 ? 1 : slices;
@@ -336,18 +488,36 @@ int gemv_bwd_slices(int N, int K)
         }                                                      \
     } while (0)
 
+bool fwd_small_computes_t(int rank) { return rank > 0 && rank <= 32; }
+
 void launch_fwd_small(const Problem &p, const void *x, const uint32_t *packed, const void *scales, const uint8_t *zeros,
-                      const void *t, const void *B, void *y, hipStream_t s)
+                      const void *A, const void *B, const void *t_in, void *t_out, void *y, hipStream_t s)
 {
-    const uint32_t magic = group_magic(p.G);
-    QLORA_BITS_DTYPE(launch_fwd_mb, p, x, packed, scales, zeros, t, B, y, magic, s);
+    const bool fused = fwd_small_computes_t(p.r);
+    const FwdArgs a{(const uint16_t *)x, packed, (const uint16_t *)scales, zeros, (const uint16_t *)A,
+                    (const uint16_t *)B, fused ? nullptr : (const uint16_t *)t_in, (uint16_t *)y,
+                    fused ? (uint16_t *)t_out : nullptr, p.M, p.N, p.K, p.r, p.K / p.G, p.sc, group_magic(p.G)};
+    const int rg = fused ? (p.r + 15) / 16 : 0;
+    QLORA_BITS_DTYPE(launch_fwd_mb, a, rg, s);
 }
 
-void launch_bwd_dx_small(const Problem &p, const void *dy, const uint32_t *packed, const void *scales,
-                         const uint8_t *zeros, const void *u, const void *A, void *dx, float *partial, hipStream_t s)
+void launch_bwd_small(const Problem &p, const void *dy, const void *x, const uint32_t *packed, const void *scales,
+                      const uint8_t *zeros, const void *A, const void *B, const void *t, void *dx, float *dA, float *dB,
+                      float *partial, float *upartial, hipStream_t s)
 {
-    const uint32_t magic = group_magic(p.G);
-    QLORA_BITS_DTYPE(launch_bwd_mb, p, dy, packed, scales, zeros, u, A, dx, partial, magic, s);
+    const int slices = gemv_bwd_slices(p.N, p.K, p.bits);
+    const int rows_per_slice = ((p.N + slices - 1) / slices + 31) / 32 * 32;
+    const BwdArgs a{(const uint16_t *)dy, packed, (const uint16_t *)scales, zeros, (const uint16_t *)B, partial,
+                    upartial, p.M, p.N, p.K, p.r, p.K / p.G, rows_per_slice, group_magic(p.G)};
+    QLORA_BITS_DTYPE(launch_bwd_bits, a, slices, s);
+    const int xb = (int)(((long)p.M * p.K + 255) / 256);
+    const int ab = (int)(((long)p.r * p.K + 255) / 256), bb = (int)(((long)p.r * p.N + 255) / 256);
+    const FinishArgs f{partial, upartial, (const uint16_t *)A, (const uint16_t *)x, (const uint16_t *)dy,
+                       (const uint16_t *)t, (uint16_t *)dx, dA, dB, p.M, p.N, p.K, p.r, slices, xb, ab, p.sc};
+    if (p.bf16)
+        hipLaunchKernelGGL((gemv_bwd_finish_kernel<true>), dim3(xb + ab + bb), dim3(256), 0, s, f);
+    else
+        hipLaunchKernelGGL((gemv_bwd_finish_kernel<false>), dim3(xb + ab + bb), dim3(256), 0, s, f);
 }
 
 }  // namespace qlora

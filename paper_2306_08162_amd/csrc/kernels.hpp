@@ -41,12 +41,18 @@ void launch_fwd_mfma(const Problem &p, const void *x, const uint32_t *packed, co
 void launch_bwd_dx_mfma(const Problem &p, const void *dy, const uint32_t *packed, const void *scales,
                         const uint8_t *zeros, const void *u, const void *A, void *dx, hipStream_t s);
 
-// gemv.hip -- small token counts (M <= SMALL_M_MAX): weight-streaming kernels, one pass over the packed weight
-constexpr int SMALL_M_MAX = 64;
-int gemv_bwd_slices(int N, int K);   // row slices of the backward kernel; partial holds slices*M*K floats
+// gemv.hip -- small token counts: weight-streaming kernels, one pass over the packed weight
+constexpr int SMALL_M_FWD_MAX = 64;   // forward kernel handles up to four 16-row token blocks
+constexpr int SMALL_M_BWD_MAX = 16;   // backward kernel keeps one 16-row token block
+int gemv_bwd_slices(int N, int K, int bits);   // row slices of the backward kernel
+bool fwd_small_computes_t(int rank);           // true: the forward kernel forms t = x A^T itself
+// y (and t_out, if not NULL and the kernel forms t) from one launch; t_in is used when the kernel does not form t
 void launch_fwd_small(const Problem &p, const void *x, const uint32_t *packed, const void *scales,
-                      const uint8_t *zeros, const void *t, const void *B, void *y, hipStream_t s);
-void launch_bwd_dx_small(const Problem &p, const void *dy, const uint32_t *packed, const void *scales,
-                         const uint8_t *zeros, const void *u, const void *A, void *dx, float *partial, hipStream_t s);
+                      const uint8_t *zeros, const void *A, const void *B, const void *t_in, void *t_out, void *y,
+                      hipStream_t s);
+// dx, dA, dB from two launches; partial holds slices*M*K floats, upartial slices*1024 floats; t may be NULL if r == 0
+void launch_bwd_small(const Problem &p, const void *dy, const void *x, const uint32_t *packed, const void *scales,
+                      const uint8_t *zeros, const void *A, const void *B, const void *t, void *dx, float *dA, float *dB,
+                      float *partial, float *upartial, hipStream_t s);
 
 }  // namespace qlora
