@@ -58,7 +58,10 @@ __device__ __forceinline__ int group_of(int k, uint32_t magic) { return magic ? 
 constexpr u16x8_t ZERO8 = {0, 0, 0, 0, 0, 0, 0, 0};
 
 // ------------------------------------------------------------------------------------------------- forward
-constexpr int FW_U = 4;   // iterations (128 codes per row each) whose loads are in flight together
+#ifndef QLORA_FW_U
+#define QLORA_FW_U 4
+#endif
+constexpr int FW_U = QLORA_FW_U;   // iterations (128 codes per row each) whose loads are in flight together
 
 struct FwdArgs {
     const uint16_t *x;
@@ -125,7 +128,8 @@ __global__ __launch_bounds__(NW * 64) void gemv_fwd_kernel(const FwdArgs a)
                 for (int mb = 0; mb < MB; ++mb) xf[u][mb][s] = *(const u16x8_t *)(xrow[mb] + kc + 8 * s);
                 if constexpr (RG > 0) {
 #pragma unroll
-                    for (int g = 0; g < RG; ++g) af[u][g][s] = *(const u16x8_t *)(arow[g] + kc + 8 * s);
+                    for (int g = 0; g < RG; ++g)
+                        af[u][g][s] = aval[g] ? *(const u16x8_t *)(arow[g] + kc + 8 * s) : ZERO8;
                 }
             }
         }
@@ -141,7 +145,7 @@ __global__ __launch_bounds__(NW * 64) void gemv_fwd_kernel(const FwdArgs a)
                 if constexpr (RG > 0) {
 #pragma unroll
                     for (int g = 0; g < RG; ++g) {
-                        const u16x8_t afz = (aval[g] && ok[u]) ? af[u][g][s] : ZERO8;
+                        const u16x8_t afz = ok[u] ? af[u][g][s] : ZERO8;
 #pragma unroll
                         for (int mb = 0; mb < MB; ++mb) tacc[mb][g] = mfma16<BF16>(xf[u][mb][s], afz, tacc[mb][g]);   // D[m][j = li]
                     }
@@ -207,6 +211,8 @@ struct BwdShape {
     static constexpr int CB = 16 * CL;
 };
 
+constexpr int BW_U = 4;   // 32-row chunks per wave whose loads are in flight together
+
 struct BwdArgs {
     const uint16_t *dy;
     const uint32_t *packed;
@@ -256,74 +262,95 @@ __global__ __launch_bounds__(256) void gemv_bwd_kernel(const BwdArgs a)
 #pragma unroll
     for (int gg = 0; gg < 4; ++gg) uacc[gg] = float4_t{0.f, 0.f, 0.f, 0.f};
 
-    for (int n0 = nbeg + wave * 32; n0 < nend; n0 += 128) {
-        uint32_t w[8][WORDS];
-        float s[8], z[8];
+    // A wave's chunks are fetched BW_U at a time before any of them is used: the pass is a handful of dependent
+    // memory round trips long, so every load that can be in flight together must be.
+    for (int nb = nbeg + wave * 32; nb < nend; nb += 128 * BW_U) {
+        uint32_t w[BW_U][8][WORDS];
+        u16x8_t df[BW_U];
+        uint16_t sraw[BW_U][8];
+        uint8_t zraw[BW_U][8];
+        const int mrow = min(wc, a.M - 1);                    // dY fragment: token row wc, 8 consecutive rows n
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int nc = min(n0 + 8 * q + e, N - 1);
-            const uint32_t *src = a.packed + (long)nc * Kw + (kc / CL) * WORDS;
-            if constexpr (WORDS == 2) {
-                const u32x2_t v = *(const u32x2_t *)src;
-                w[e][0] = v[0];
-                w[e][1] = v[1];
-            } else if constexpr (WORDS == 0) {     // unreachable, keeps WORDS >= 1 visible to the compiler
+        for (int u = 0; u < BW_U; ++u) {
+            const int n0 = nb + 128 * u;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int nc = min(n0 + 8 * q + e, N - 1);
+                const uint32_t *src = a.packed + (long)nc * Kw + (kc / CL) * WORDS;
+                if constexpr (WORDS == 2) {
+                    const u32x2_t v = *(const u32x2_t *)src;
+                    w[u][e][0] = v[0];
+                    w[u][e][1] = v[1];
+                } else {
+#pragma unroll
+                    for (int i = 0; i < WORDS; ++i) w[u][e][i] = src[i];
+                }
+            }
+            const int nn = n0 + 8 * q;
+            df[u] = *(const u16x8_t *)(a.dy + (long)mrow * N + (nn < nend ? nn : 0));
+            if (uniform_group) {
+                // one scale / zero-point per row for the whole column block: lane l < 32 fetches row n0 + l
+                const long gi = (long)min(n0 + (lane & 31), N - 1) * a.ng + g;
+                sraw[u][0] = a.scales[gi];
+                zraw[u][0] = a.zeros[gi];
             } else {
 #pragma unroll
-                for (int i = 0; i < WORDS; ++i) w[e][i] = src[i];
-            }
-        }
-        const int mrow = min(wc, a.M - 1), nn = n0 + 8 * q;   // dY fragment: token row wc, 8 consecutive rows n
-        const bool in = nn < nend;                            // N % 8 == 0, slices are multiples of 32: all or nothing
-        u16x8_t df = *(const u16x8_t *)(a.dy + (long)mrow * N + (in ? nn : 0));
-        if (!in) df = ZERO8;
-
-        if (uniform_group) {
-            // one scale / zero-point per row for the whole column block: 32 loads per wave, shared through LDS
-            if (lane < 32) {
-                const long gi = (long)min(n0 + lane, N - 1) * a.ng + g;
-                sz_s[wave][lane] = a.scales[gi];
-                sz_z[wave][lane] = a.zeros[gi];
-            }
-            __builtin_amdgcn_wave_barrier();
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const bool ok = kok && n0 + 8 * q + e < nend;
-                s[e] = ok ? f16_bits_to_f32(sz_s[wave][8 * q + e]) : 0.f;
-                z[e] = (float)sz_z[wave][8 * q + e];
-            }
-            __builtin_amdgcn_wave_barrier();
-        } else {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int n = n0 + 8 * q + e;
-                const bool ok = kok && n < nend;
-                const long gi = (long)min(n, N - 1) * a.ng + g;
-                s[e] = ok ? f16_bits_to_f32(a.scales[gi]) : 0.f;
-                z[e] = (float)a.zeros[gi];
-            }
-        }
-        if (do_u) {     // u = dY B over this chunk: B^T fragment gathered column-wise (only the first column block)
-#pragma unroll
-            for (int gg = 0; gg < 4; ++gg) {
-                if (gg * 16 < r) {
-                    u16x8_t bf = ZERO8;
-                    const int j = gg * 16 + wc;
-                    if (in && j < r) {
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) bf[e] = a.B[(long)(nn + e) * r + j];
-                    }
-                    uacc[gg] = mfma16<BF16>(df, bf, uacc[gg]);      // D[m = 4q+v][j = 16 gg + wc]
+                for (int e = 0; e < 8; ++e) {
+                    const long gi = (long)min(n0 + 8 * q + e, N - 1) * a.ng + g;
+                    sraw[u][e] = a.scales[gi];
+                    zraw[u][e] = a.zeros[gi];
                 }
             }
         }
 #pragma unroll
-        for (int c = 0; c < CL; ++c) {
-            u16x8_t wf;
+        for (int u = 0; u < BW_U; ++u) {
+            const int n0 = nb + 128 * u, nn = n0 + 8 * q;
+            const bool in = nn < nend;                        // N % 8 == 0, slices are multiples of 32: all or nothing
+            const u16x8_t dfu = in ? df[u] : ZERO8;
+            float s[8], z[8];
+            if (uniform_group) {
+                // hand the 32 rows' values round through LDS (wave-private; LDS operations of a wave complete in order)
+                if (lane < 32) {
+                    sz_s[wave][lane] = sraw[u][0];
+                    sz_z[wave][lane] = zraw[u][0];
+                }
+                __builtin_amdgcn_wave_barrier();
 #pragma unroll
-            for (int e = 0; e < 8; ++e) wf[e] = to16<BF16>(((float)code_of<BITS, WORDS>(w[e], c) - z[e]) * s[e]);
-            acc[c] = mfma16<BF16>(df, wf, acc[c]);                  // D[m = 4q+v][column CL wc + c]
+                for (int e = 0; e < 8; ++e) {
+                    const bool ok = kok && n0 + 8 * q + e < nend;
+                    s[e] = ok ? f16_bits_to_f32(sz_s[wave][8 * q + e]) : 0.f;
+                    z[e] = (float)sz_z[wave][8 * q + e];
+                }
+                __builtin_amdgcn_wave_barrier();
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const bool ok = kok && n0 + 8 * q + e < nend;
+                    s[e] = ok ? f16_bits_to_f32(sraw[u][e]) : 0.f;
+                    z[e] = (float)zraw[u][e];
+                }
+            }
+            if (do_u) {     // u = dY B over this chunk: B^T fragment gathered column-wise (only the first column block)
+#pragma unroll
+                for (int gg = 0; gg < 4; ++gg) {
+                    if (gg * 16 < r) {
+                        u16x8_t bf = ZERO8;
+                        const int j = gg * 16 + wc;
+                        if (in && j < r) {
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) bf[e] = a.B[(long)(nn + e) * r + j];
+                        }
+                        uacc[gg] = mfma16<BF16>(dfu, bf, uacc[gg]);      // D[m = 4q+v][j = 16 gg + wc]
+                    }
+                }
+            }
+#pragma unroll
+            for (int c = 0; c < CL; ++c) {
+                u16x8_t wf;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) wf[e] = to16<BF16>(((float)code_of<BITS, WORDS>(w[u][e], c) - z[e]) * s[e]);
+                acc[c] = mfma16<BF16>(dfu, wf, acc[c]);                  // D[m = 4q+v][column CL wc + c]
+            }
         }
     }
     if (do_u) {
@@ -428,7 +455,10 @@ inline uint32_t group_magic(int G)
 template <int BITS, bool BF16, int MB>
 void launch_fwd_rg(const FwdArgs &a, int rg, hipStream_t s)
 {
-    constexpr int NW = MB == 1 ? 8 : 4;     // one 16-row token block: more waves, so each has fewer loads to wait for
+#ifndef QLORA_FW_NW
+#define QLORA_FW_NW 8
+#endif
+    constexpr int NW = MB == 1 ? QLORA_FW_NW : 4;     // one 16-row token block: more waves, so each has fewer loads to wait for
     const dim3 grid((a.N + 15) / 16), block(NW * 64);
     switch (rg) {
     case 0: hipLaunchKernelGGL((gemv_fwd_kernel<BITS, BF16, MB, 0, NW>), grid, block, 0, s, a); break;

@@ -1,0 +1,79 @@
+"""GPU parity at the full workload sizes, in the launch configuration bench.py times.
+
+The oracle computes dA and dB in full (they are cheap) and y / dX on a seeded sample of complete token rows:
+rows are independent, so row-sampled parity is exact, not statistical.  Inputs come from the same seeded
+generators as everywhere else; the LLaMA-7B shapes stand in for the paper's fine-tuning workloads.
+"""
+import dataclasses
+
+import numpy as np
+import pytest
+
+from paper_2306_08162_amd import workloads as wl
+from parity import check_layer
+
+pytestmark = pytest.mark.gpu
+
+
+def _sample_rows(M: int, count: int, seed: int) -> np.ndarray:
+    """`count` distinct rows: first, last, a tile boundary, and seeded picks in between."""
+    fixed = [0, M - 1, min(M - 1, 255), min(M - 1, 256)]
+    extra = (wl.splitmix64(seed, 0, count) % np.uint64(M)).astype(np.int64).tolist()
+    rows = sorted(set(fixed + extra))[:count]
+    return np.array(rows, dtype=np.int64)
+
+
+def test_config2_qproj_int4_full():
+    """The headline workload, every output row."""
+    inp = wl.make_inputs(wl.config2())
+    check_layer(inp)
+
+
+def test_config3_gateup_int2_bf16_sampled_rows():
+    inp = wl.make_inputs(wl.config3())
+    check_layer(inp, rows=_sample_rows(inp.cfg.M, 64, 3))
+
+
+def test_config4_down_int3_sampled_rows():
+    inp = wl.make_inputs(wl.config4())
+    check_layer(inp, rows=_sample_rows(inp.cfg.M, 64, 4))
+
+
+_BLOCK_WEIGHTS = {}
+
+
+def _block_inputs(bits: int, M: int):
+    """The seven projections of one decoder block at M tokens.  Weights are generated once per (shape, bits):
+    projections of equal shape (q/k/v/o, gate/up) share their synthetic weights, activations differ."""
+    out = []
+    for cfg in wl.config5(bits, M):
+        key = (cfg.K, cfg.N, bits)
+        if key not in _BLOCK_WEIGHTS:
+            w = wl.make_inputs(dataclasses.replace(cfg, M=1))
+            _BLOCK_WEIGHTS[key] = (w.codes, w.scales, w.zeros, w.A, w.B)
+        codes, scales, zeros, A, B = _BLOCK_WEIGHTS[key]
+        x = wl.to_bits(wl.normal(cfg.seed + wl.T_X + 1000 * M, cfg.M * cfg.K), cfg.dtype).reshape(cfg.M, cfg.K)
+        dy = wl.to_bits(wl.normal(cfg.seed + wl.T_DY + 1000 * M, cfg.M * cfg.N), cfg.dtype).reshape(cfg.M, cfg.N)
+        out.append(wl.LayerInputs(cfg, codes, scales, zeros, A, B, x, dy))
+    return out
+
+
+@pytest.mark.parametrize("bits", [2, 8])
+@pytest.mark.parametrize("M", [1, 16])
+def test_config5_block_small_token_counts(bits, M):
+    """All seven projections, forward + backward, every row (the weight-streaming kernels)."""
+    for inp in _block_inputs(bits, M):
+        check_layer(inp)
+
+
+@pytest.mark.parametrize("bits", [2, 8])
+def test_config5_block_M256_and_M4096(bits):
+    """The tiled kernels on the block's three distinct shapes: M = 256 on all rows of a sample, M = 4096 sampled."""
+    for M, count in ((256, 32), (4096, 32)):
+        seen = set()
+        for inp in _block_inputs(bits, M):
+            shape = (inp.cfg.K, inp.cfg.N)
+            if shape in seen:
+                continue
+            seen.add(shape)
+            check_layer(inp, rows=_sample_rows(M, count, bits * 100 + M))
