@@ -21,6 +21,9 @@ if ROOT not in sys.path:
 
 PEAK_MFMA_F16_TFLOPS = 2516.6   # 256 CU x 4096 flop/clk/CU x 2.4 GHz, dense fp16/bf16
 PEAK_HBM_GBPS = 8000.0
+# HBM bytes per launch of the two GEMM kernels on the headline workload, from rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE runs of this script, scaled by a 1 GiB copy in the same runs (profiles/qgemm_c2_hbm_traffic.md).
+GEMM_TRAFFIC_BYTES = {"fwd": 101.9e6, "bwd": 104.3e6}
 
 
 def _mean(v):
@@ -186,12 +189,22 @@ def main() -> int:
     ap.add_argument("--cpu-rows", type=int, default=2048, help="token rows the CPU oracle baseline is timed on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-small-m", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy, so a rocprofv3 --pmc run of this command holds a kernel of "
+                         "known HBM traffic to scale FETCH_SIZE / WRITE_SIZE by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (the layer has no multi-GPU path); use --gpus 1",
               file=sys.stderr)
         return 2
 
+    if args.calibrate_copy:
+        import torch
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)              # reads 1 GiB, writes 1 GiB: far larger than every cache
+        torch.cuda.synchronize()
+        del src, dst
     cfg, inp, layer, ms_per_step, fwd_ms, bwd_ms = run_headline(args.steps, args.warmup)
     flops = cfg.flops_fwd_bwd
     value = flops / (ms_per_step * 1e-3) / 1e12
@@ -204,7 +217,7 @@ def main() -> int:
     achieved = gemm_flops[dom] / (gemm_ms[dom] * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": f"qgemm_kernel ({dom} GEMM, INT4 fp16)", "achieved": round(achieved, 2),
                 "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_MFMA_F16_TFLOPS, 4),
-                "traffic": None,
+                "traffic": GEMM_TRAFFIC_BYTES[dom], "traffic_unit": "bytes per launch (rocprofv3 pmc, see profiles/)",
                 "kernel_us": {k: round(v * 1e3, 2) for k, v in gemm_ms.items()},
                 "kernel_tflops": {k: round(gemm_flops[k] / (gemm_ms[k] * 1e-3) / 1e12, 2) for k in gemm_ms}}
 
