@@ -90,7 +90,7 @@ __device__ __forceinline__ void dma16(const void *base, uint32_t byte_offset, ui
 {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                  ::"v"(byte_offset), "s"(base), "s"(lds)
-                 : "memory", "m0");
+                 : "memory");   // m0 is reserved by the compiler: it never keeps a value there across other code
 }
 
 // wait until at most N vector-memory operations of this wave are outstanding, then meet the workgroup
@@ -205,9 +205,7 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
         // One k-step: the fragments of a later k-step are requested from LDS while the MFMAs of the current one
         // issue, one LDS read slotted behind each MFMA so the matrix pipe never waits on a burst of reads.
         auto kstep = [&](int xstage, int wstage, int rks, Frags &into, const Frags &use) {
-#ifndef QLORA_EXP_NOFRAG
             load_frags(xstage, wstage, rks, into);
-#endif
             mfma_frags(use);
 #pragma unroll
             for (int i = 0; i < MI * NI; ++i) {
@@ -230,10 +228,8 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
             // the last k-step of a stage runs from registers after the barrier, overlapping the LDS latency of the
             // next stage's first fragments; the activation loads for stage kt+2 are spread over the k-steps
             auto issue_quarter = [&](int qtr) {
-#ifndef QLORA_EXP_NOLOAD
 #pragma unroll
                 for (int i = qtr * (XDMA / 4); i < (qtr + 1) * (XDMA / 4); ++i) issue_x(kt + 2, xfill, i);
-#endif
             };
             issue_quarter(0);
             kstep(xstage, wstage, 1, f[1], f[0]);
@@ -310,9 +306,7 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
         load_global(NSETS, rs[0]);
         __syncthreads();
         auto step = [&](int kt, Regs &rg) {
-#ifndef QLORA_EXP_NOSTAGE
             stage(rg, (kt + 1) & 1);
-#endif
             load_global(kt + 1 + NSETS, rg);
             __syncthreads();
         };
@@ -419,7 +413,7 @@ void launch_variant(const GemmArgs &a, hipStream_t s)
 template <int BITS, bool BF16, bool TRANS>
 void launch_tiles(GemmArgs &a, hipStream_t s)
 {
-#ifndef QLORA_BM
+#ifndef QLORA_BM          // tile shape and MFMA-wave grid can be overridden at build time for tuning runs
 #define QLORA_BM 256
 #define QLORA_BN 128
 #endif

@@ -29,12 +29,6 @@ int adapter_grad_slices(int M, int C, int r);
 void launch_adapter_grad(const void *act, const void *side, float *out, float *partial, int M, int C, int r,
                          float sc, bool c_major, bool bf16, hipStream_t s);
 
-// generic.hip -- shape-agnostic kernels (any K % 32 == 0), used when no tiled kernel applies
-void launch_fwd_generic(const Problem &p, const void *x, const uint32_t *packed, const void *scales,
-                        const uint8_t *zeros, const void *t, const void *B, void *y, hipStream_t s);
-void launch_bwd_dx_generic(const Problem &p, const void *dy, const uint32_t *packed, const void *scales,
-                           const uint8_t *zeros, const void *u, const void *A, void *dx, hipStream_t s);
-
 // gemm_mfma.hip -- tiled MFMA GEMMs with fused dequantisation (any accepted shape)
 void launch_fwd_mfma(const Problem &p, const void *x, const uint32_t *packed, const void *scales,
                      const uint8_t *zeros, const void *t, const void *B, void *y, hipStream_t s);
