@@ -76,18 +76,27 @@ struct FwdArgs {
     uint32_t magic;
 };
 
-template <int BITS, bool BF16, int MB, int RG, int NW>   // RG = 16-column groups of t formed here (0: none); NW waves
+template <int BITS, bool BF16, int MB, int RG, int NW, int NB>   // RG: 16-column groups of t formed here (0: none);
+                                                                  // NW waves; NB 16-row weight blocks per workgroup
 __global__ __launch_bounds__(NW * 64) void gemv_fwd_kernel(const FwdArgs a)
 {
     constexpr int RGS = RG > 0 ? RG : 1, NT = NW * 64;
-    __shared__ float red[NW][MB][16][17];
+    __shared__ float red[NW][MB][NB][16][17];
     __shared__ float tred[NW][MB][RGS][16][17];
     constexpr int TC = RG > 0 ? RG * 16 : 64;      // columns of t kept in LDS
     __shared__ float tfull[MB * 16][TC + 1];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, li = lane & 15, q = lane >> 4;
-    const int n0 = blockIdx.x * 16, n = min(n0 + li, a.N - 1);
+    const int n0 = blockIdx.x * 16 * NB;
     const int K = a.K, Kw = K * BITS / 32, r = a.r;
-    const uint32_t *wrow = a.packed + (long)n * Kw;
+    // the activation (and A) fragments of a k-step are fetched once and used for all NB weight blocks: they, not the
+    // packed weight, are most of what a workgroup pulls through its L1
+    int nrow[NB];
+    const uint32_t *wrow[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        nrow[nb] = min(n0 + nb * 16 + li, a.N - 1);
+        wrow[nb] = a.packed + (long)nrow[nb] * Kw;
+    }
     const uint16_t *xrow[MB], *arow[RGS];
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) xrow[mb] = a.x + (long)min(mb * 16 + li, a.M - 1) * K;
@@ -98,19 +107,20 @@ __global__ __launch_bounds__(NW * 64) void gemv_fwd_kernel(const FwdArgs a)
         arow[g] = a.A + (long)(RG > 0 ? min(g * 16 + li, r - 1) : 0) * K;
     }
 
-    float4_t acc[MB], tacc[MB][RGS];
+    float4_t acc[MB][NB], tacc[MB][RGS];
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
-        acc[mb] = float4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = float4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int g = 0; g < RGS; ++g) tacc[mb][g] = float4_t{0.f, 0.f, 0.f, 0.f};
     }
 
     const int iters = (K + 127) / 128;          // wave w takes iterations w, w+NW, ...: neighbours read neighbouring bytes
     for (int it0 = wave; it0 < iters; it0 += NW * FW_U) {
-        uint32_t w[FW_U][BITS];
-        uint16_t sraw[FW_U];
-        uint8_t zraw[FW_U];
+        uint32_t w[FW_U][NB][BITS];
+        uint16_t sraw[FW_U][NB];
+        uint8_t zraw[FW_U][NB];
         bool ok[FW_U];
         u16x8_t xf[FW_U][MB][4], af[FW_U][RGS][4];
 #pragma unroll
@@ -118,10 +128,14 @@ __global__ __launch_bounds__(NW * 64) void gemv_fwd_kernel(const FwdArgs a)
             const int kb = (it0 + NW * u) * 128 + 32 * q;
             ok[u] = kb < K;
             const int kc = ok[u] ? kb : 0;
-            load_words<BITS>(wrow + (kc >> 5) * BITS, w[u]);
-            const long gi = (long)n * a.ng + group_of(kc, a.magic);
-            sraw[u] = a.scales[gi];
-            zraw[u] = a.zeros[gi];
+            const int grp = group_of(kc, a.magic);
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                load_words<BITS>(wrow[nb] + (kc >> 5) * BITS, w[u][nb]);
+                const long gi = (long)nrow[nb] * a.ng + grp;
+                sraw[u][nb] = a.scales[gi];
+                zraw[u][nb] = a.zeros[gi];
+            }
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
 #pragma unroll
@@ -135,21 +149,27 @@ __global__ __launch_bounds__(NW * 64) void gemv_fwd_kernel(const FwdArgs a)
         }
 #pragma unroll
         for (int u = 0; u < FW_U; ++u) {
-            DequantConst<BITS, BF16> dq;
-            dq.set(ok[u] ? f16_bits_to_f32(sraw[u]) : 0.f, (float)zraw[u]);
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                const u16x8_t wf = dequant8<BITS, BF16>(w[u], s, dq);
+            for (int nb = 0; nb < NB; ++nb) {
+                DequantConst<BITS, BF16> dq;
+                dq.set(ok[u] ? f16_bits_to_f32(sraw[u][nb]) : 0.f, (float)zraw[u][nb]);
 #pragma unroll
-                for (int mb = 0; mb < MB; ++mb) acc[mb] = mfma16<BF16>(xf[u][mb][s], wf, acc[mb]);   // D[m = 4q+v][n = li]
-                if constexpr (RG > 0) {
+                for (int s = 0; s < 4; ++s) {
+                    const u16x8_t wf = dequant8<BITS, BF16>(w[u][nb], s, dq);
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb)
+                        acc[mb][nb] = mfma16<BF16>(xf[u][mb][s], wf, acc[mb][nb]);    // D[m = 4q+v][n = li]
+                }
+            }
+            if constexpr (RG > 0) {
+#pragma unroll
+                for (int s = 0; s < 4; ++s)
 #pragma unroll
                     for (int g = 0; g < RG; ++g) {
                         const u16x8_t afz = ok[u] ? af[u][g][s] : ZERO8;
 #pragma unroll
                         for (int mb = 0; mb < MB; ++mb) tacc[mb][g] = mfma16<BF16>(xf[u][mb][s], afz, tacc[mb][g]);   // D[m][j = li]
                     }
-                }
             }
         }
     }
@@ -157,7 +177,8 @@ __global__ __launch_bounds__(NW * 64) void gemv_fwd_kernel(const FwdArgs a)
     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-            red[wave][mb][4 * q + v][li] = acc[mb][v];
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) red[wave][mb][nb][4 * q + v][li] = acc[mb][nb][v];
             if constexpr (RG > 0) {
 #pragma unroll
                 for (int g = 0; g < RG; ++g) tred[wave][mb][g][4 * q + v][li] = tacc[mb][g][v];
@@ -182,13 +203,13 @@ __global__ __launch_bounds__(NW * 64) void gemv_fwd_kernel(const FwdArgs a)
         for (int e = threadIdx.x; e < a.M * r; e += NT) tfull[e / r][e % r] = cvt16<BF16>(a.t_in[e]);
     }
     __syncthreads();
-    for (int e = threadIdx.x; e < MB * 256; e += NT) {
-        const int mb = e >> 8, ml = (e >> 4) & 15, nl = e & 15;
-        const int m = mb * 16 + ml, nn = n0 + nl;
+    for (int e = threadIdx.x; e < MB * NB * 256; e += NT) {
+        const int mb = e / (NB * 256), nb = (e >> 8) % NB, ml = (e >> 4) & 15, nl = e & 15;
+        const int m = mb * 16 + ml, nn = n0 + nb * 16 + nl;
         if (m >= a.M || nn >= a.N) continue;
         float v = 0.f;
 #pragma unroll
-        for (int w = 0; w < NW; ++w) v += red[w][mb][ml][nl];
+        for (int w = 0; w < NW; ++w) v += red[w][mb][nb][ml][nl];
         float lo = 0.f;
         for (int j0 = 0; j0 < r; j0 += 8) {
             const u16x8_t bv = *(const u16x8_t *)(a.B + (long)nn * r + j0);
@@ -458,12 +479,16 @@ void launch_fwd_rg(const FwdArgs &a, int rg, hipStream_t s)
 #ifndef QLORA_FW_NW
 #define QLORA_FW_NW 8
 #endif
-    constexpr int NW = MB == 1 ? QLORA_FW_NW : 4;     // one 16-row token block: more waves, so each has fewer loads to wait for
-    const dim3 grid((a.N + 15) / 16), block(NW * 64);
+#ifndef QLORA_FW_NB
+#define QLORA_FW_NB 1
+#endif
+    // one 16-row token block: more waves (each has fewer loads to wait for) and several weight blocks per workgroup
+    constexpr int NW = MB == 1 ? QLORA_FW_NW : 4, NB = MB == 1 ? QLORA_FW_NB : 1;
+    const dim3 grid((a.N + 16 * NB - 1) / (16 * NB)), block(NW * 64);
     switch (rg) {
-    case 0: hipLaunchKernelGGL((gemv_fwd_kernel<BITS, BF16, MB, 0, NW>), grid, block, 0, s, a); break;
-    case 1: hipLaunchKernelGGL((gemv_fwd_kernel<BITS, BF16, MB, 1, NW>), grid, block, 0, s, a); break;
-    default: hipLaunchKernelGGL((gemv_fwd_kernel<BITS, BF16, MB, 2, NW>), grid, block, 0, s, a); break;
+    case 0: hipLaunchKernelGGL((gemv_fwd_kernel<BITS, BF16, MB, 0, NW, NB>), grid, block, 0, s, a); break;
+    case 1: hipLaunchKernelGGL((gemv_fwd_kernel<BITS, BF16, MB, 1, NW, NB>), grid, block, 0, s, a); break;
+    default: hipLaunchKernelGGL((gemv_fwd_kernel<BITS, BF16, MB, 2, NW, NB>), grid, block, 0, s, a); break;
     }
 }
 
