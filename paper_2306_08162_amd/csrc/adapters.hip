@@ -28,7 +28,7 @@ __device__ __forceinline__ float4_t mfma16(u16x8_t a, u16x8_t b, float4_t c)
 // along the contraction, so a lane's fragment is one 16-byte load.  Partial 16 x r tiles meet in LDS.
 // ------------------------------------------------------------------------------------------------------------
 constexpr int SK_WAVES = 8;
-constexpr int SK_UNROLL = 8;
+constexpr int SK_UNROLL = 16;
 
 template <bool BF16, int RG>   // RG = ceil(r / 16)
 __global__ __launch_bounds__(SK_WAVES * 64) void skinny_rows_kernel(const uint16_t *__restrict__ act,
@@ -106,8 +106,7 @@ __global__ __launch_bounds__(256) void transpose_small_kernel(const uint16_t *__
 // A workgroup owns 64 columns x one slice; every global load of the slice is issued before the first MFMA.
 // ------------------------------------------------------------------------------------------------------------
 constexpr int GR_COLS = 64;       // columns per workgroup (16 per wave)
-constexpr int GR_ROWS = 128;      // token rows per slice
-constexpr int GR_CHUNKS = GR_ROWS / 32;
+constexpr int grad_rows(int rg) { return rg <= 2 ? 256 : 128; }   // token rows per slice (LDS budget: 64 KB)
 constexpr int GR_PITCH = GR_COLS + 2;   // halfs; odd dword pitch keeps the column gathers off the same banks
 
 template <bool BF16, int RG>
@@ -115,6 +114,7 @@ __global__ __launch_bounds__(256) void adapter_grad_partial_kernel(const uint16_
                                                                    const uint16_t *__restrict__ side,
                                                                    float *__restrict__ partial, int M, int C, int r)
 {
+    constexpr int GR_ROWS = grad_rows(RG), GR_CHUNKS = GR_ROWS / 32;
     __shared__ uint16_t As[GR_ROWS * GR_PITCH];
     constexpr int SP = RG * 16 + 2;         // side pitch in halfs, odd dword pitch as well
     __shared__ uint16_t Ss[GR_ROWS * SP];
@@ -250,7 +250,8 @@ int adapter_grad_slices(int M, int C, int r)
 {
     (void)C;
     if (r <= 0) return 0;
-    return (M + GR_ROWS - 1) / GR_ROWS;
+    const int rows = grad_rows((r + 15) / 16);
+    return (M + rows - 1) / rows;
 }
 
 void launch_adapter_grad(const void *act, const void *side, float *out, float *partial, int M, int C, int r,

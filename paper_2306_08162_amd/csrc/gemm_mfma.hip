@@ -188,6 +188,7 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
 
     if (!stager) {
         // ---- MFMA waves ----
+        __builtin_amdgcn_s_setprio(1);          // when both kinds of wave are ready, the matrix pipe's feeder goes first
         // direct-to-LDS loads: this wave's load i covers tile rows (MW i + cw) * 8 .. + 8
         const int drow = lane >> 3;              // row within the 8-row block; block b starts at tile row 8 b
         const int dchunk = ((lane & 7) ^ ((4 * cw + (drow >> 1)) & 7)) * 8;   // MW * i * 4 is a multiple of 8
