@@ -100,6 +100,7 @@ __global__ __launch_bounds__(256) void transpose_small_kernel(const uint16_t *__
 // ------------------------------------------------------------------------------------------------------------
 // partial[s][c][j] = sum over the token rows m of slice s of act[m,c] * side[m,j]
 //      (dB: act = dY, side = t;  dA: act = x, side = u)
+// Both gradients go out in one launch: column blocks [0, nb0) belong to the first problem, the rest to the second.
 //
 // The contraction runs over m, the strided index of both operands, so 32-row chunks of act (64 columns wide)
 // and of side are laid into LDS as they come and the MFMA fragments are gathered from there column-wise.
@@ -109,17 +110,30 @@ constexpr int GR_COLS = 64;       // columns per workgroup (16 per wave)
 constexpr int grad_rows(int rg) { return rg <= 2 ? 256 : 128; }   // token rows per slice (LDS budget: 64 KB)
 constexpr int GR_PITCH = GR_COLS + 2;   // halfs; odd dword pitch keeps the column gathers off the same banks
 
+struct GradArgs {
+    const uint16_t *act[2], *side[2];
+    float *partial[2];      // [slices][C][r] each
+    float *out[2];          // dB [C0, r] and dA [r, C1]
+    int C[2];
+    int nb0;                // column blocks of the first problem
+    int M, r, slices;
+    float sc;
+};
+
 template <bool BF16, int RG>
-__global__ __launch_bounds__(256) void adapter_grad_partial_kernel(const uint16_t *__restrict__ act,
-                                                                   const uint16_t *__restrict__ side,
-                                                                   float *__restrict__ partial, int M, int C, int r)
+__global__ __launch_bounds__(256) void adapter_grad_partial_kernel(const GradArgs a)
 {
     constexpr int GR_ROWS = grad_rows(RG), GR_CHUNKS = GR_ROWS / 32;
+    const int which = (int)blockIdx.x >= a.nb0 ? 1 : 0;
+    const uint16_t *__restrict__ act = a.act[which];
+    const uint16_t *__restrict__ side = a.side[which];
+    float *__restrict__ partial = a.partial[which];
+    const int M = a.M, C = a.C[which], r = a.r;
     __shared__ uint16_t As[GR_ROWS * GR_PITCH];
     constexpr int SP = RG * 16 + 2;         // side pitch in halfs, odd dword pitch as well
     __shared__ uint16_t Ss[GR_ROWS * SP];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int c0 = blockIdx.x * GR_COLS, slice = blockIdx.y, m0 = slice * GR_ROWS;
+    const int c0 = ((int)blockIdx.x - (which ? a.nb0 : 0)) * GR_COLS, slice = blockIdx.y, m0 = slice * GR_ROWS;
 
     // global -> LDS: act rows are 128 bytes wide here (8 lanes x 16 B); rows past M or columns past C become zero
     {
@@ -180,24 +194,28 @@ __global__ __launch_bounds__(256) void adapter_grad_partial_kernel(const uint16_
     }
 }
 
-// out = sc * sum over slices (in slice order) of partial; out is [C,r] or [r,C].
-__global__ __launch_bounds__(256) void adapter_grad_reduce_kernel(const float *__restrict__ partial,
-                                                                  float *__restrict__ out, int C, int r, int slices,
-                                                                  float sc, int c_major)
+// out = sc * sum over slices (in slice order) of partial, both problems in one launch: the first C0*r threads
+// write dB as [C0, r], the next C1*r threads dA as [r, C1].
+__global__ __launch_bounds__(256) void adapter_grad_reduce_kernel(const GradArgs a)
 {
-    const long idx = (long)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= (long)C * r) return;
+    long idx = (long)blockIdx.x * 256 + threadIdx.x;
+    const long n0 = (long)a.C[0] * a.r;
+    const int which = idx >= n0 ? 1 : 0;
+    if (which) idx -= n0;
+    const int C = a.C[which], r = a.r;
     const long stride = (long)C * r;
+    if (idx >= stride) return;
+    const float *__restrict__ partial = a.partial[which];
     float acc = 0.f;
     int s = 0;
-    for (; s + 4 <= slices; s += 4) {
+    for (; s + 4 <= a.slices; s += 4) {
         const float a0 = partial[(s + 0) * stride + idx], a1 = partial[(s + 1) * stride + idx];
         const float a2 = partial[(s + 2) * stride + idx], a3 = partial[(s + 3) * stride + idx];
         acc = (((acc + a0) + a1) + a2) + a3;
     }
-    for (; s < slices; ++s) acc += partial[s * stride + idx];
+    for (; s < a.slices; ++s) acc += partial[s * stride + idx];
     const int c = (int)(idx / r), j = (int)(idx % r);
-    out[c_major ? idx : (long)j * C + c] = sc * acc;
+    a.out[which][which ? (long)j * C + c : idx] = a.sc * acc;
 }
 
 template <bool BF16>
@@ -213,15 +231,15 @@ void launch_skinny(const uint16_t *act, const uint16_t *small, uint16_t *out, in
 }
 
 template <bool BF16>
-void launch_grad_partial(const uint16_t *act, const uint16_t *side, float *partial, int M, int C, int r, int slices,
-                         hipStream_t s)
+void launch_grad_partial(const GradArgs &a, hipStream_t s)
 {
-    const dim3 grid((C + GR_COLS - 1) / GR_COLS, slices), block(256);
-    switch ((r + 15) / 16) {
-    case 1: hipLaunchKernelGGL((adapter_grad_partial_kernel<BF16, 1>), grid, block, 0, s, act, side, partial, M, C, r); break;
-    case 2: hipLaunchKernelGGL((adapter_grad_partial_kernel<BF16, 2>), grid, block, 0, s, act, side, partial, M, C, r); break;
-    case 3: hipLaunchKernelGGL((adapter_grad_partial_kernel<BF16, 3>), grid, block, 0, s, act, side, partial, M, C, r); break;
-    default: hipLaunchKernelGGL((adapter_grad_partial_kernel<BF16, 4>), grid, block, 0, s, act, side, partial, M, C, r); break;
+    const int nb1 = (a.C[1] + GR_COLS - 1) / GR_COLS;
+    const dim3 grid(a.nb0 + nb1, a.slices), block(256);
+    switch ((a.r + 15) / 16) {
+    case 1: hipLaunchKernelGGL((adapter_grad_partial_kernel<BF16, 1>), grid, block, 0, s, a); break;
+    case 2: hipLaunchKernelGGL((adapter_grad_partial_kernel<BF16, 2>), grid, block, 0, s, a); break;
+    case 3: hipLaunchKernelGGL((adapter_grad_partial_kernel<BF16, 3>), grid, block, 0, s, a); break;
+    default: hipLaunchKernelGGL((adapter_grad_partial_kernel<BF16, 4>), grid, block, 0, s, a); break;
     }
 }
 
@@ -246,25 +264,39 @@ void launch_lora_u(const void *dy, const void *B, void *bt, void *u, int M, int 
         launch_skinny<false>((const uint16_t *)dy, (const uint16_t *)bt, (uint16_t *)u, M, N, r, s);
 }
 
-int adapter_grad_slices(int M, int C, int r)
+int adapter_grad_slices(int M, int r)
 {
-    (void)C;
     if (r <= 0) return 0;
     const int rows = grad_rows((r + 15) / 16);
     return (M + rows - 1) / rows;
 }
 
-void launch_adapter_grad(const void *act, const void *side, float *out, float *partial, int M, int C, int r,
-                         float sc, bool c_major, bool bf16, hipStream_t s)
+void launch_adapter_grads(const void *dy, const void *t, const void *x, const void *u, float *dB, float *dA,
+                          float *partial, int M, int N, int K, int r, float sc, bool bf16, hipStream_t s)
 {
-    const int slices = adapter_grad_slices(M, C, r);
+    const int slices = adapter_grad_slices(M, r);
+    GradArgs a;
+    a.act[0] = (const uint16_t *)dy;
+    a.side[0] = (const uint16_t *)t;
+    a.act[1] = (const uint16_t *)x;
+    a.side[1] = (const uint16_t *)u;
+    a.partial[0] = partial;
+    a.partial[1] = partial + (size_t)slices * N * r;
+    a.out[0] = dB;
+    a.out[1] = dA;
+    a.C[0] = N;
+    a.C[1] = K;
+    a.nb0 = (N + GR_COLS - 1) / GR_COLS;
+    a.M = M;
+    a.r = r;
+    a.slices = slices;
+    a.sc = sc;
     if (bf16)
-        launch_grad_partial<true>((const uint16_t *)act, (const uint16_t *)side, partial, M, C, r, slices, s);
+        launch_grad_partial<true>(a, s);
     else
-        launch_grad_partial<false>((const uint16_t *)act, (const uint16_t *)side, partial, M, C, r, slices, s);
-    const long n = (long)C * r;
-    hipLaunchKernelGGL(adapter_grad_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, partial, out, C,
-                       r, slices, sc, c_major ? 1 : 0);
+        launch_grad_partial<false>(a, s);
+    const long n = (long)(N + K) * r;
+    hipLaunchKernelGGL(adapter_grad_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, a);
 }
 
 }  // namespace qlora

@@ -52,9 +52,7 @@ Workspace carve(int M, int N, int K, int r, int bits)
     w.upartial_off = off;
     off += round_up((size_t)gemv_bwd_slices(N, K, bits) * 1024 * sizeof(float));
     w.partial_off = off;
-    const size_t pa = (size_t)adapter_grad_slices(M, K, r) * K * r * sizeof(float);
-    const size_t pb = (size_t)adapter_grad_slices(M, N, r) * N * r * sizeof(float);
-    size_t pmax = pa > pb ? pa : pb;
+    size_t pmax = (size_t)adapter_grad_slices(M, r) * ((size_t)N + K) * r * sizeof(float);   // dB and dA slices
     if (M <= SMALL_M_BWD_MAX) {     // the small-M backward kernel sums row slices of dX through the same buffer
         const size_t pg = (size_t)gemv_bwd_slices(N, K, bits) * M * K * sizeof(float);
         pmax = pg > pmax ? pg : pmax;
@@ -225,8 +223,7 @@ int qlora_linear_bwd(const void *dy, const void *x, const uint32_t *packed, cons
             t = ws + w.t_off;
         }
         float *partial = (float *)(ws + w.partial_off);
-        launch_adapter_grad(dy, t, dB, partial, M, N, rank, p.sc, /*c_major=*/true, p.bf16, s);
-        launch_adapter_grad(x, u, dA, partial, M, K, rank, p.sc, /*c_major=*/false, p.bf16, s);
+        launch_adapter_grads(dy, t, x, u, dB, dA, partial, M, N, K, rank, p.sc, p.bf16, s);
     }
     return hip_status();
 }

@@ -24,10 +24,11 @@ void launch_lora_down(const void *x, const void *A, void *t, int M, int K, int r
 // u[M,r] = dy[M,N] B[N,r]; bt is scratch for B^T (N*r 16-bit values)
 void launch_lora_u(const void *dy, const void *B, void *bt, void *u, int M, int N, int r, bool bf16, hipStream_t s);
 // Number of token slices the adapter-gradient reductions are cut into (fixed by the shape alone).
-int adapter_grad_slices(int M, int C, int r);
-// out = sc * act[M,C]^T side[M,r]; out is [C,r] (c_major) or [r,C]; partial holds slices*C*r floats.
-void launch_adapter_grad(const void *act, const void *side, float *out, float *partial, int M, int C, int r,
-                         float sc, bool c_major, bool bf16, hipStream_t s);
+int adapter_grad_slices(int M, int r);
+// dB[N,r] = sc * dy[M,N]^T t[M,r] and dA[r,K] = sc * u[M,r]^T x[M,K], two launches for both (slice partial sums,
+// then their fixed-order reduction); partial holds slices*(N+K)*r floats.
+void launch_adapter_grads(const void *dy, const void *t, const void *x, const void *u, float *dB, float *dA,
+                          float *partial, int M, int N, int K, int r, float sc, bool bf16, hipStream_t s);
 
 // gemm_mfma.hip -- tiled MFMA GEMMs with fused dequantisation (any accepted shape)
 void launch_fwd_mfma(const Problem &p, const void *x, const uint32_t *packed, const void *scales,
