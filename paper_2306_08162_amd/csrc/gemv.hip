@@ -220,6 +220,236 @@ __global__ __launch_bounds__(NW * 64) void gemv_fwd_kernel(const FwdArgs a)
     }
 }
 
+// ------------------------------------------------------------------------------- forward, staged activations
+// Same products as gemv_fwd_kernel for up to two 16-row token blocks, with a different route for x and A.  A lane's
+// MFMA fragment of x is 16 bytes out of each of 16 different rows: fetched as such, a wave touches 64 separate
+// 64-byte pieces per instruction and the pass is bound by that, not by the packed weight.  Here every wave copies
+// its 128-column slice of x and A straight into LDS with row-contiguous requests (global_load_lds, 16 lanes per
+// 256-byte row segment, no registers in between) and takes the fragments from there.  The slices are private to
+// the wave, two deep, so the loop has no workgroup barrier; the packed words still go from global memory to
+// registers, a batch of iterations ahead.
+//
+// LDS slice of one 16-row block: 16 rows x 16 pieces of 16 bytes; piece c of row w sits in slot 16 w + (c ^ w), so
+// the fragment reads of 16 rows at one piece index fall on 16 different bank groups.
+constexpr int ST_BLOCK = 4096;      // bytes of one 16-row x 128-column block
+#ifndef QLORA_ST_U
+#define QLORA_ST_U 4
+#endif
+constexpr int ST_U = QLORA_ST_U;    // iterations whose packed words are requested together
+
+__device__ __forceinline__ void dma16(const void *base, uint32_t byte_offset, uint32_t lds)
+{
+    // lane l of the wave writes its 16 bytes to LDS byte address lds + 16 l; completion counts on vmcnt
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(byte_offset), "s"(base), "s"(lds)
+                 : "memory");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vm()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+__device__ __forceinline__ void wait_lds() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+
+template <int BITS, bool BF16, int MB, int RG, int NW>
+__global__ __launch_bounds__(NW * 64) void gemv_fwd_staged_kernel(const FwdArgs a)
+{
+    constexpr int RGS = RG > 0 ? RG : 1, NT = NW * 64, NB = 1;
+    constexpr int BLOCKS = MB + RG;                 // 16-row blocks per slice: x blocks, then A blocks
+    constexpr int ND = 4 * BLOCKS;                  // LDS-DMA instructions per slice
+    extern __shared__ __attribute__((aligned(16))) uint8_t stage[];   // [NW][2][BLOCKS][ST_BLOCK]
+    __shared__ float red[NW][MB][NB][16][17];
+    __shared__ float tred[NW][MB][RGS][16][17];
+    constexpr int TC = RG > 0 ? RG * 16 : 64;
+    __shared__ float tfull[MB * 16][TC + 1];
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int li = lane & 15, q = lane >> 4;
+    const int n0 = blockIdx.x * 16 * NB;
+    const int K = a.K, Kw = K * BITS / 32, r = a.r;
+    int nrow[NB];
+    const uint32_t *wrow[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        nrow[nb] = min(n0 + nb * 16 + li, a.N - 1);
+        wrow[nb] = a.packed + (long)nrow[nb] * Kw;
+    }
+    // this lane's part of a slice copy: instruction j of a block moves rows 4j + lane/16; the lane fetches the
+    // piece that belongs in its slot
+    uint32_t src_off[BLOCKS][4];                    // byte offset of (row, piece) at column 0 of the slice
+#pragma unroll
+    for (int b = 0; b < BLOCKS; ++b)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int w16 = 4 * j + (lane >> 4), piece = (lane & 15) ^ w16;
+            const int row = b < MB ? min(b * 16 + w16, a.M - 1) : min((b - MB) * 16 + w16, r - 1);   // clamped rows
+            src_off[b][j] = (uint32_t)(((long)row * K + 8 * piece) * 2);                             // repeat a valid one
+        }
+    const uint32_t my_stage = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)stage +
+                              (uint32_t)wave * (2 * BLOCKS * ST_BLOCK);
+    const int iters = (K + 127) / 128;
+    const int n_it = wave < iters ? (iters - wave + NW - 1) / NW : 0;      // this wave's iterations: wave, wave+NW, ..
+    auto issue_slice = [&](int i, int buf) {
+        const int k0 = (wave + NW * i) * 128;
+#pragma unroll
+        for (int b = 0; b < BLOCKS; ++b)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                // pieces past K (last iteration of a K that is not a multiple of 128) re-read column 0: their
+                // weights are scaled by zero and their A fragments replaced by zero below
+                const int piece = (lane & 15) ^ (4 * j + (lane >> 4));
+                const uint32_t kb = k0 + 8 * piece < K ? (uint32_t)k0 * 2u : (uint32_t)(-(8 * piece)) * 2u;
+                dma16(b < MB ? (const void *)a.x : (const void *)a.A, src_off[b][j] + kb,
+                      my_stage + (uint32_t)((buf * BLOCKS + b) * ST_BLOCK + j * 1024));
+            }
+    };
+
+    // the rows of B this thread's outputs need at the very end: requested now, so they are not one more round trip then
+    constexpr int EPT = (MB * 256 + NT - 1) / NT;
+    u16x8_t bpre[EPT][2 * RGS];
+    if constexpr (RG > 0) {
+#pragma unroll
+        for (int x = 0; x < EPT; ++x) {
+            const int e = threadIdx.x + x * NT, nn = n0 + (e & 15);
+            const bool live = e < MB * 256 && nn < a.N;
+#pragma unroll
+            for (int h = 0; h < 2 * RG; ++h)
+                bpre[x][h] = (live && 8 * h < r) ? *(const u16x8_t *)(a.B + (long)nn * r + 8 * h) : ZERO8;
+        }
+    }
+
+    float4_t acc[MB][NB], tacc[MB][RGS];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = float4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int g = 0; g < RGS; ++g) tacc[mb][g] = float4_t{0.f, 0.f, 0.f, 0.f};
+    }
+
+    for (int i0 = 0; i0 < n_it; i0 += ST_U) {
+        uint32_t w[ST_U][NB][BITS];
+        uint16_t sraw[ST_U][NB];
+        uint8_t zraw[ST_U][NB];
+        bool ok[ST_U];
+#pragma unroll
+        for (int u = 0; u < ST_U; ++u) {
+            const int kb = (wave + NW * (i0 + u)) * 128 + 32 * q;
+            ok[u] = kb < K;                           // also false for iterations past the wave's last
+            const int kc = ok[u] ? kb : 0;
+            const int grp = group_of(kc, a.magic);
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                load_words<BITS>(wrow[nb] + (kc >> 5) * BITS, w[u][nb]);
+                const long gi = (long)nrow[nb] * a.ng + grp;
+                sraw[u][nb] = a.scales[gi];
+                zraw[u][nb] = a.zeros[gi];
+            }
+        }
+        if (i0 == 0) {      // the first two slices go out behind the first batch of packed words, not ahead of it
+            issue_slice(0, 0);
+            if (n_it > 1) issue_slice(1, 1);
+        }
+#pragma unroll
+        for (int u = 0; u < ST_U; ++u) {
+            const int i = i0 + u;
+            if (i >= n_it) break;
+            // slice i has landed when at most the ND copies of slice i+1 (issued after it) are still in flight
+            if (i + 1 < n_it) wait_vm<ND>(); else wait_vm<0>();
+            const uint8_t *buf = stage + (size_t)(wave * 2 + (u & 1)) * (BLOCKS * ST_BLOCK);
+            u16x8_t xf[MB][4], af[RGS][4];
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const int slot = li * 16 + ((4 * q + s) ^ li);
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) xf[mb][s] = *(const u16x8_t *)(buf + mb * ST_BLOCK + slot * 16);
+                if constexpr (RG > 0) {
+#pragma unroll
+                    for (int g = 0; g < RG; ++g) {
+                        const u16x8_t v = *(const u16x8_t *)(buf + (MB + g) * ST_BLOCK + slot * 16);
+                        af[g][s] = (ok[u] && g * 16 + li < r) ? v : ZERO8;
+                    }
+                }
+            }
+            wait_lds();                               // the fragments are in registers: the slice may be overwritten
+            if (i + 2 < n_it) issue_slice(i + 2, u & 1);
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                DequantConst<BITS, BF16> dq;
+                dq.set(ok[u] ? f16_bits_to_f32(sraw[u][nb]) : 0.f, (float)zraw[u][nb]);
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    const u16x8_t wf = dequant8<BITS, BF16>(w[u][nb], s, dq);
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb)
+                        acc[mb][nb] = mfma16<BF16>(xf[mb][s], wf, acc[mb][nb]);       // D[m = 4q+v][n = li]
+                }
+            }
+            if constexpr (RG > 0) {
+#pragma unroll
+                for (int s = 0; s < 4; ++s)
+#pragma unroll
+                    for (int g = 0; g < RG; ++g)
+#pragma unroll
+                        for (int mb = 0; mb < MB; ++mb) tacc[mb][g] = mfma16<BF16>(xf[mb][s], af[g][s], tacc[mb][g]);
+            }
+        }
+    }
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) red[wave][mb][nb][4 * q + v][li] = acc[mb][nb][v];
+            if constexpr (RG > 0) {
+#pragma unroll
+                for (int g = 0; g < RG; ++g) tred[wave][mb][g][4 * q + v][li] = tacc[mb][g][v];
+            }
+        }
+    __syncthreads();
+    if constexpr (RG > 0) {
+        for (int e = threadIdx.x; e < MB * 16 * RG * 16; e += NT) {
+            const int m = e / (RG * 16), j = e % (RG * 16);
+            float tv = 0.f;
+            if (j < r && m < a.M) {
+                const int mb = m >> 4, ml = m & 15, g = j >> 4, jl = j & 15;
+#pragma unroll
+                for (int w = 0; w < NW; ++w) tv += tred[w][mb][g][ml][jl];
+                tv = cvt16<BF16>(to16<BF16>(tv));          // the value every consumer of t sees
+                if (blockIdx.x == 0 && a.t_out) a.t_out[(long)m * r + j] = to16<BF16>(tv);
+            }
+            tfull[m][j] = tv;
+        }
+    } else {
+        for (int e = threadIdx.x; e < a.M * r; e += NT) tfull[e / r][e % r] = cvt16<BF16>(a.t_in[e]);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int x = 0; x < EPT; ++x) {
+        const int e = threadIdx.x + x * NT;
+        const int mb = e >> 8, ml = (e >> 4) & 15, nl = e & 15;
+        const int m = mb * 16 + ml, nn = n0 + nl;
+        if (e >= MB * 256 || m >= a.M || nn >= a.N) continue;
+        float v = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) v += red[w][mb][0][ml][nl];
+        float lo = 0.f;
+        if constexpr (RG > 0) {
+#pragma unroll
+            for (int h = 0; h < 2 * RG; ++h)
+#pragma unroll
+                for (int c = 0; c < 8; ++c) lo += tfull[m][8 * h + c] * cvt16<BF16>(bpre[x][h][c]);   // zero past r
+        } else {
+            for (int j0 = 0; j0 < r; j0 += 8) {
+                const u16x8_t bv = *(const u16x8_t *)(a.B + (long)nn * r + j0);
+#pragma unroll
+                for (int h = 0; h < 8; ++h) lo += tfull[m][j0 + h] * cvt16<BF16>(bv[h]);
+            }
+        }
+        a.y[(long)m * a.N + nn] = to16<BF16>(v + a.sc * lo);
+    }
+}
+
 // ------------------------------------------------------------------------------------------------ backward
 // Workgroup (cb, sp): weight columns [CB cb, +CB), CB = 16 * CL, rows n of slice sp; wave w takes 32-row chunks
 // w, w+4, ...  Lane (wc = lane % 16, q = lane / 16) holds the CL codes of columns CB cb + CL wc .. of rows
@@ -255,6 +485,38 @@ __device__ __forceinline__ uint32_t code_of(const uint32_t (&w)[WORDS], int c)
     uint32_t v = w[wi] >> sh;
     if (sh + BITS > 32) v |= w[wi + 1] << (32 - sh);
     return v & mask;
+}
+
+// fp16: column c of eight consecutive weight rows as one MFMA fragment (element e = row e).  Rows are handled in
+// pairs: one byte permute drops the code of both rows into the mantissas of (1024.0, 1024.0), at bit p of each
+// half; a packed fma with (2^-p, -(1024 * 2^-p + z)) leaves the exact integers q - z and a packed multiply applies
+// the two rows' scales, so every weight is rounded once from its exact value.
+template <int BITS, int WORDS>
+__device__ __forceinline__ u16x8_t dequant_rows8_f16(const uint32_t (&w)[8][WORDS], int c, const half2_t (&s2)[4],
+                                                     const half2_t (&nz2)[4])
+{
+    const int o = BITS * c, wi = o >> 5, sh = o & 31;
+    const bool straddle = sh + BITS > 32;                 // the code runs into the next word (3-bit codes only)
+    const int bb = straddle ? 0 : (sh >> 3), p = straddle ? 0 : (sh & 7);
+    const bool two = p + BITS > 8;                        // ... or into the next byte
+    const uint32_t sel = (uint32_t)bb | ((two ? (uint32_t)(bb + 1) : 0x0Cu) << 8) | ((uint32_t)(4 + bb) << 16) |
+                         ((two ? (uint32_t)(5 + bb) : 0x0Cu) << 24);
+    const uint32_t m1 = ((1u << BITS) - 1u) << p, mask2 = m1 | (m1 << 16);
+    const half_t mulv = (half_t)(1.f / (float)(1 << p)), offc = (half_t)(-1024.f / (float)(1 << p));
+    const half2_t mul2 = {mulv, mulv}, off2 = {offc, offc};
+    u32x4_t out;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        uint32_t lo = w[2 * i][wi], hi = w[2 * i + 1][wi];
+        if (straddle) {
+            lo = __builtin_amdgcn_alignbit(w[2 * i][wi + 1 < WORDS ? wi + 1 : wi], lo, (uint32_t)sh);
+            hi = __builtin_amdgcn_alignbit(w[2 * i + 1][wi + 1 < WORDS ? wi + 1 : wi], hi, (uint32_t)sh);
+        }
+        const uint32_t bits = (__builtin_amdgcn_perm(hi, lo, sel) & mask2) | 0x64006400u;
+        const half2_t h = __builtin_bit_cast(half2_t, bits);
+        out[i] = __builtin_bit_cast(uint32_t, (h * mul2 + (nz2[i] + off2)) * s2[i]);
+    }
+    return __builtin_bit_cast(u16x8_t, out);
 }
 
 template <int BITS, bool BF16>
@@ -365,12 +627,25 @@ __global__ __launch_bounds__(256) void gemv_bwd_kernel(const BwdArgs a)
                     }
                 }
             }
+            if constexpr (BF16) {
 #pragma unroll
-            for (int c = 0; c < CL; ++c) {
-                u16x8_t wf;
+                for (int c = 0; c < CL; ++c) {
+                    u16x8_t wf;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) wf[e] = to16<BF16>(((float)code_of<BITS, WORDS>(w[u][e], c) - z[e]) * s[e]);
-                acc[c] = mfma16<BF16>(dfu, wf, acc[c]);                  // D[m = 4q+v][column CL wc + c]
+                    for (int e = 0; e < 8; ++e)
+                        wf[e] = to16<BF16>(((float)code_of<BITS, WORDS>(w[u][e], c) - z[e]) * s[e]);
+                    acc[c] = mfma16<BF16>(dfu, wf, acc[c]);              // D[m = 4q+v][column CL wc + c]
+                }
+            } else {
+                half2_t s2[4], nz2[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    s2[i] = half2_t{(half_t)s[2 * i], (half_t)s[2 * i + 1]};          // exact: they were fp16
+                    nz2[i] = half2_t{(half_t)(-z[2 * i]), (half_t)(-z[2 * i + 1])};
+                }
+#pragma unroll
+                for (int c = 0; c < CL; ++c)
+                    acc[c] = mfma16<BF16>(dfu, dequant_rows8_f16<BITS, WORDS>(w[u], c, s2, nz2), acc[c]);
             }
         }
     }
@@ -476,19 +751,49 @@ inline uint32_t group_magic(int G)
 template <int BITS, bool BF16, int MB>
 void launch_fwd_rg(const FwdArgs &a, int rg, hipStream_t s)
 {
-#ifndef QLORA_FW_NW
-#define QLORA_FW_NW 8
-#endif
-#ifndef QLORA_FW_NB
-#define QLORA_FW_NB 1
-#endif
-    // one 16-row token block: more waves (each has fewer loads to wait for) and several weight blocks per workgroup
-    constexpr int NW = MB == 1 ? QLORA_FW_NW : 4, NB = MB == 1 ? QLORA_FW_NB : 1;
-    const dim3 grid((a.N + 16 * NB - 1) / (16 * NB)), block(NW * 64);
+    constexpr int NW = 4;
+    const dim3 grid((a.N + 15) / 16), block(NW * 64);
     switch (rg) {
-    case 0: hipLaunchKernelGGL((gemv_fwd_kernel<BITS, BF16, MB, 0, NW, NB>), grid, block, 0, s, a); break;
-    case 1: hipLaunchKernelGGL((gemv_fwd_kernel<BITS, BF16, MB, 1, NW, NB>), grid, block, 0, s, a); break;
-    default: hipLaunchKernelGGL((gemv_fwd_kernel<BITS, BF16, MB, 2, NW, NB>), grid, block, 0, s, a); break;
+    case 0: hipLaunchKernelGGL((gemv_fwd_kernel<BITS, BF16, MB, 0, NW, 1>), grid, block, 0, s, a); break;
+    case 1: hipLaunchKernelGGL((gemv_fwd_kernel<BITS, BF16, MB, 1, NW, 1>), grid, block, 0, s, a); break;
+    default: hipLaunchKernelGGL((gemv_fwd_kernel<BITS, BF16, MB, 2, NW, 1>), grid, block, 0, s, a); break;
+    }
+}
+
+template <int BITS, bool BF16, int MB, int RG, int NW>
+void launch_fwd_staged_one(const FwdArgs &a, hipStream_t s)
+{
+    constexpr int lds = NW * 2 * (MB + RG) * ST_BLOCK;            // 128 KB of slices at most
+    auto kern = gemv_fwd_staged_kernel<BITS, BF16, MB, RG, NW>;
+    static bool configured = false;   // raising the dynamic-LDS ceiling is a property of the function, set once
+    if (!configured) {
+        (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        configured = true;
+    }
+    hipLaunchKernelGGL(kern, dim3((a.N + 15) / 16), dim3(NW * 64), lds, s, a);
+}
+
+template <int BITS, bool BF16, int MB, int RG>
+void launch_fwd_staged_rg(const FwdArgs &a, hipStream_t s)
+{
+    // Eight waves per workgroup when there is one workgroup per compute unit or less; with more weight rows than
+    // that, four-wave workgroups, two to a compute unit, so that one's first loads overlap the other's tail.
+    if constexpr (MB + RG <= 2) {
+        if ((a.N + 15) / 16 < 512) {
+            launch_fwd_staged_one<BITS, BF16, MB, RG, 8>(a, s);
+            return;
+        }
+    }
+    launch_fwd_staged_one<BITS, BF16, MB, RG, 4>(a, s);
+}
+
+template <int BITS, bool BF16, int MB>
+void launch_fwd_staged(const FwdArgs &a, int rg, hipStream_t s)
+{
+    switch (rg) {
+    case 0: launch_fwd_staged_rg<BITS, BF16, MB, 0>(a, s); break;
+    case 1: launch_fwd_staged_rg<BITS, BF16, MB, 1>(a, s); break;
+    default: launch_fwd_staged_rg<BITS, BF16, MB, 2>(a, s); break;
     }
 }
 
@@ -496,8 +801,8 @@ template <int BITS, bool BF16>
 void launch_fwd_mb(const FwdArgs &a, int rg, hipStream_t s)
 {
     switch ((a.M + 15) / 16) {
-    case 1: launch_fwd_rg<BITS, BF16, 1>(a, rg, s); break;
-    case 2: launch_fwd_rg<BITS, BF16, 2>(a, rg, s); break;
+    case 1: launch_fwd_staged<BITS, BF16, 1>(a, rg, s); break;
+    case 2: launch_fwd_staged<BITS, BF16, 2>(a, rg, s); break;
     case 3: launch_fwd_rg<BITS, BF16, 3>(a, rg, s); break;
     default: launch_fwd_rg<BITS, BF16, 4>(a, rg, s); break;
     }

@@ -68,6 +68,11 @@ SMALL_CASES = [
     (2, 4096, 4096, 4, 128, 8, "f16"),
     (17, 1376, 520, 2, 32, 32, "f16"),
     (65, 256, 136, 4, 64, 8, "f16"),           # first M on the tiled path
+    (12, 1120, 72, 3, 32, 24, "f16"),          # rank between two 16-column groups, K not a multiple of 128
+    (8, 256, 8200, 4, 64, 8, "f16"),           # enough weight rows for two 16-row blocks per workgroup, ragged
+    (3, 512, 96, 8, 64, 0, "f16"),             # no adapter, small M
+    (30, 256, 64, 4, 32, 64, "bf16"),          # rank 64 at small M: t comes from its own launch
+    (32, 128, 48, 3, 128, 16, "bf16"),
 ]
 
 
