@@ -457,12 +457,17 @@ __global__ __launch_bounds__(NW * 64) void gemv_fwd_staged_kernel(const FwdArgs 
 // CL wc + c of those rows: D_c[m][k = CB cb + CL wc + c].
 template <int BITS>
 struct BwdShape {
-    static constexpr int CL = BITS == 3 ? 32 : (BITS == 2 ? 16 : 8);   // columns per lane: 4, 8 or 12 bytes of codes
+#ifndef QLORA_BW_CL2
+#define QLORA_BW_CL2 16
+#endif
+#ifndef QLORA_BW_CL4
+#define QLORA_BW_CL4 8
+#endif
+    static constexpr int CL = BITS == 3 ? 32 : (BITS == 2 ? QLORA_BW_CL2 : (BITS == 4 ? QLORA_BW_CL4 : 8));   // columns per lane
     static constexpr int WORDS = CL * BITS / 32;
     static constexpr int CB = 16 * CL;
 };
 
-constexpr int BW_U = 4;   // 32-row chunks per wave whose loads are in flight together
 
 struct BwdArgs {
     const uint16_t *dy;
@@ -519,25 +524,30 @@ __device__ __forceinline__ u16x8_t dequant_rows8_f16(const uint32_t (&w)[8][WORD
     return __builtin_bit_cast(u16x8_t, out);
 }
 
-template <int BITS, bool BF16>
-__global__ __launch_bounds__(256) void gemv_bwd_kernel(const BwdArgs a)
+template <int BITS, bool BF16, int NW, int BW_U>   // NW waves; BW_U 32-row chunks per wave in flight together
+__global__ __launch_bounds__(NW * 64) void gemv_bwd_kernel(const BwdArgs a)
 {
     using S = BwdShape<BITS>;
     constexpr int CL = S::CL, WORDS = S::WORDS, CB = S::CB;
-    __shared__ float red[4][16][128 + 1];   // the column block is reduced 128 columns at a time
-    __shared__ float ured[4][16][64 + 1];
-    __shared__ uint16_t sz_s[4][32];        // per wave: scales of its 32 rows (this lane's group is fetched by lane row)
-    __shared__ uint8_t sz_z[4][32];
+    constexpr int NT = NW * 64;
+    __shared__ float red[NW][16][128 + 1];   // the column block is reduced 128 columns at a time
+    __shared__ float ured[NW][16][64 + 1];
+    __shared__ uint16_t sz_s[NW][32];        // per wave: scales of its 32 rows (this lane's group is fetched by lane row)
+    __shared__ uint8_t sz_z[NW][32];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wc = lane & 15, q = lane >> 4;
     const int N = a.N, K = a.K, r = a.r;
-    const int kcol = blockIdx.x * CB + CL * wc;             // first of this lane's CL columns (all in one group: CL | 32)
+    // Workgroups are dealt to the 8 dies round-robin by their linear index.  A 64-byte piece of a weight row is half
+    // a cache line: neighbouring column blocks go to the same die, so that the line is fetched into one L2 only.
+    const int ncb = (int)gridDim.x, die = (int)blockIdx.x & 7;
+    const int cb = die * (ncb >> 3) + min(die, ncb & 7) + ((int)blockIdx.x >> 3);
+    const int kcol = cb * CB + CL * wc;                     // first of this lane's CL columns (all in one group: CL | 32)
     const bool kok = kcol < K;
     const int kc = kok ? kcol : 0;
     const int Kw = K * BITS / 32;
     const int g = group_of(kc, a.magic);
-    const bool uniform_group = group_of(blockIdx.x * CB, a.magic) == group_of(min(blockIdx.x * CB + CB, K) - 1, a.magic);
+    const bool uniform_group = group_of(cb * CB, a.magic) == group_of(min(cb * CB + CB, K) - 1, a.magic);
     const int nbeg = blockIdx.y * a.rows_per_slice, nend = min(N, nbeg + a.rows_per_slice);
-    const bool do_u = blockIdx.x == 0 && r > 0;
+    const bool do_u = cb == 0 && r > 0;
 
     float4_t acc[CL], uacc[4];
 #pragma unroll
@@ -547,15 +557,19 @@ __global__ __launch_bounds__(256) void gemv_bwd_kernel(const BwdArgs a)
 
     // A wave's chunks are fetched BW_U at a time before any of them is used: the pass is a handful of dependent
     // memory round trips long, so every load that can be in flight together must be.
-    for (int nb = nbeg + wave * 32; nb < nend; nb += 128 * BW_U) {
+    for (int nb = nbeg + wave * 32; nb < nend; nb += 32 * NW * BW_U) {
         uint32_t w[BW_U][8][WORDS];
-        u16x8_t df[BW_U];
+        u16x8_t df[BW_U], bfr[BW_U][4];        // bfr: B^T fragments for u = dY B (first column block only)
+#pragma unroll
+        for (int u = 0; u < BW_U; ++u)
+#pragma unroll
+            for (int gg = 0; gg < 4; ++gg) bfr[u][gg] = ZERO8;
         uint16_t sraw[BW_U][8];
         uint8_t zraw[BW_U][8];
         const int mrow = min(wc, a.M - 1);                    // dY fragment: token row wc, 8 consecutive rows n
 #pragma unroll
         for (int u = 0; u < BW_U; ++u) {
-            const int n0 = nb + 128 * u;
+            const int n0 = nb + 32 * NW * u;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const int nc = min(n0 + 8 * q + e, N - 1);
@@ -571,6 +585,16 @@ __global__ __launch_bounds__(256) void gemv_bwd_kernel(const BwdArgs a)
             }
             const int nn = n0 + 8 * q;
             df[u] = *(const u16x8_t *)(a.dy + (long)mrow * N + (nn < nend ? nn : 0));
+            if (do_u) {     // gathered column-wise, in flight together with the packed words
+#pragma unroll
+                for (int gg = 0; gg < 4; ++gg) {
+                    const int j = gg * 16 + wc;
+                    if (nn < nend && j < r) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) bfr[u][gg][e] = a.B[(long)(nn + e) * r + j];
+                    }
+                }
+            }
             if (uniform_group) {
                 // one scale / zero-point per row for the whole column block: lane l < 32 fetches row n0 + l
                 const long gi = (long)min(n0 + (lane & 31), N - 1) * a.ng + g;
@@ -587,7 +611,7 @@ __global__ __launch_bounds__(256) void gemv_bwd_kernel(const BwdArgs a)
         }
 #pragma unroll
         for (int u = 0; u < BW_U; ++u) {
-            const int n0 = nb + 128 * u, nn = n0 + 8 * q;
+            const int n0 = nb + 32 * NW * u, nn = n0 + 8 * q;
             const bool in = nn < nend;                        // N % 8 == 0, slices are multiples of 32: all or nothing
             const u16x8_t dfu = in ? df[u] : ZERO8;
             float s[8], z[8];
@@ -613,19 +637,10 @@ __global__ __launch_bounds__(256) void gemv_bwd_kernel(const BwdArgs a)
                     z[e] = (float)zraw[u][e];
                 }
             }
-            if (do_u) {     // u = dY B over this chunk: B^T fragment gathered column-wise (only the first column block)
+            if (do_u) {     // u = dY B over this chunk
 #pragma unroll
-                for (int gg = 0; gg < 4; ++gg) {
-                    if (gg * 16 < r) {
-                        u16x8_t bf = ZERO8;
-                        const int j = gg * 16 + wc;
-                        if (in && j < r) {
-#pragma unroll
-                            for (int e = 0; e < 8; ++e) bf[e] = a.B[(long)(nn + e) * r + j];
-                        }
-                        uacc[gg] = mfma16<BF16>(dfu, bf, uacc[gg]);      // D[m = 4q+v][j = 16 gg + wc]
-                    }
-                }
+                for (int gg = 0; gg < 4; ++gg)
+                    if (gg * 16 < r) uacc[gg] = mfma16<BF16>(dfu, bfr[u][gg], uacc[gg]);      // D[m = 4q+v][j = 16 gg + wc]
             }
             if constexpr (BF16) {
 #pragma unroll
@@ -664,16 +679,22 @@ __global__ __launch_bounds__(256) void gemv_bwd_kernel(const BwdArgs a)
                 for (int v = 0; v < 4; ++v) red[wave][4 * q + v][(CL * wc + c) & 127] = acc[c][v];
         }
         __syncthreads();
-        for (int e = threadIdx.x; e < 16 * 128; e += 256) {
-            const int m = e >> 7, kl = e & 127, k = blockIdx.x * CB + cp * 128 + kl;
+        for (int e = threadIdx.x; e < 16 * 128; e += NT) {
+            const int m = e >> 7, kl = e & 127, k = cb * CB + cp * 128 + kl;
             if (m >= a.M || k >= K) continue;
-            a.partial[((long)blockIdx.y * a.M + m) * K + k] = ((red[0][m][kl] + red[1][m][kl]) + red[2][m][kl]) + red[3][m][kl];
+            float v = 0.f;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) v += red[w][m][kl];
+            a.partial[((long)blockIdx.y * a.M + m) * K + k] = v;
         }
     }
     if (do_u) {
-        for (int e = threadIdx.x; e < 16 * 64; e += 256) {
+        for (int e = threadIdx.x; e < 16 * 64; e += NT) {
             const int m = e >> 6, j = e & 63;
-            a.upartial[(long)blockIdx.y * 1024 + e] = ((ured[0][m][j] + ured[1][m][j]) + ured[2][m][j]) + ured[3][m][j];
+            float v = 0.f;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) v += ured[w][m][j];
+            a.upartial[(long)blockIdx.y * 1024 + e] = v;
         }
     }
 }
@@ -811,11 +832,16 @@ void launch_fwd_mb(const FwdArgs &a, int rg, hipStream_t s)
 template <int BITS, bool BF16>
 void launch_bwd_bits(const BwdArgs &a, int slices, hipStream_t s)
 {
-    const dim3 grid((a.K + BwdShape<BITS>::CB - 1) / BwdShape<BITS>::CB, slices), block(256);
-    hipLaunchKernelGGL((gemv_bwd_kernel<BITS, BF16>), grid, block, 0, s, a);
+    const dim3 grid((a.K + BwdShape<BITS>::CB - 1) / BwdShape<BITS>::CB, slices);
+    // Two chunks per wave in flight (more would not fit the register file at eight waves); eight waves share out the
+    // arithmetic of a slice, four are enough when the slice has no more than eight chunks.
+    if (a.rows_per_slice / 32 > 8)
+        hipLaunchKernelGGL((gemv_bwd_kernel<BITS, BF16, 8, 2>), grid, dim3(512), 0, s, a);
+    else
+        hipLaunchKernelGGL((gemv_bwd_kernel<BITS, BF16, 4, 2>), grid, dim3(256), 0, s, a);
 }
 
-int bwd_cb(int bits) { return bits == 3 ? 512 : (bits == 2 ? 256 : 128); }
+int bwd_cb(int bits) { return bits == 3 ? BwdShape<3>::CB : (bits == 2 ? BwdShape<2>::CB : (bits == 4 ? BwdShape<4>::CB : BwdShape<8>::CB)); }
 
 }  // namespace
 
@@ -824,7 +850,7 @@ int gemv_bwd_slices(int N, int K, int bits)
     const int colblocks = (K + bwd_cb(bits) - 1) / bwd_cb(bits);
     int slices = (256 + colblocks - 1) / colblocks;      // aim at one workgroup per compute unit: every extra slice
                                                          // costs another M x K block of partial sums
-    const int max_slices = (N + 127) / 128;              // at least one 32-row chunk per wave
+    const int max_slices = (N + 127) / 128;              // at least four 32-row chunks per workgroup
     if (slices > max_slices) slices = max_slices;
     return slices < 1 ? 1 : slices;
 }
