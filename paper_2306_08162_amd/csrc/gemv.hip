@@ -252,15 +252,22 @@ __device__ __forceinline__ void wait_vm()
 
 __device__ __forceinline__ void wait_lds() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
-template <int BITS, bool BF16, int MB, int RG, int NW>
+template <int BITS, bool BF16, int MB, int RG, int NW, int NB>   // NB: 16-row weight blocks per workgroup
 __global__ __launch_bounds__(NW * 64) void gemv_fwd_staged_kernel(const FwdArgs a)
 {
-    constexpr int RGS = RG > 0 ? RG : 1, NT = NW * 64, NB = 1;
+    constexpr int RGS = RG > 0 ? RG : 1, NT = NW * 64;
     constexpr int BLOCKS = MB + RG;                 // 16-row blocks per slice: x blocks, then A blocks
     constexpr int ND = 4 * BLOCKS;                  // LDS-DMA instructions per slice
     extern __shared__ __attribute__((aligned(16))) uint8_t stage[];   // [NW][2][BLOCKS][ST_BLOCK]
-    __shared__ float red[NW][MB][NB][16][17];
-    __shared__ float tred[NW][MB][RGS][16][17];
+    // a wave's partial sums go where its slices were, once it has used the last of them
+    constexpr int WAVE_STAGE = 2 * BLOCKS * ST_BLOCK;
+    static_assert((MB * NB + MB * RGS) * 16 * 17 * 4 <= WAVE_STAGE, "partial sums fit in the wave's slices");
+    auto red = [&](int w, int mb, int nb, int row, int col) -> float & {
+        return ((float *)(stage + (size_t)w * WAVE_STAGE))[((mb * NB + nb) * 16 + row) * 17 + col];
+    };
+    auto tred = [&](int w, int mb, int g, int row, int col) -> float & {
+        return ((float *)(stage + (size_t)w * WAVE_STAGE))[((MB * NB + mb * RGS + g) * 16 + row) * 17 + col];
+    };
     constexpr int TC = RG > 0 ? RG * 16 : 64;
     __shared__ float tfull[MB * 16][TC + 1];
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -286,7 +293,7 @@ __global__ __launch_bounds__(NW * 64) void gemv_fwd_staged_kernel(const FwdArgs 
             src_off[b][j] = (uint32_t)(((long)row * K + 8 * piece) * 2);                             // repeat a valid one
         }
     const uint32_t my_stage = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)stage +
-                              (uint32_t)wave * (2 * BLOCKS * ST_BLOCK);
+                              (uint32_t)wave * WAVE_STAGE;
     const int iters = (K + 127) / 128;
     const int n_it = wave < iters ? (iters - wave + NW - 1) / NW : 0;      // this wave's iterations: wave, wave+NW, ..
     auto issue_slice = [&](int i, int buf) {
@@ -305,13 +312,13 @@ __global__ __launch_bounds__(NW * 64) void gemv_fwd_staged_kernel(const FwdArgs 
     };
 
     // the rows of B this thread's outputs need at the very end: requested now, so they are not one more round trip then
-    constexpr int EPT = (MB * 256 + NT - 1) / NT;
+    constexpr int EPT = (MB * NB * 256 + NT - 1) / NT;
     u16x8_t bpre[EPT][2 * RGS];
     if constexpr (RG > 0) {
 #pragma unroll
         for (int x = 0; x < EPT; ++x) {
-            const int e = threadIdx.x + x * NT, nn = n0 + (e & 15);
-            const bool live = e < MB * 256 && nn < a.N;
+            const int e = threadIdx.x + x * NT, nn = n0 + ((e >> 8) % NB) * 16 + (e & 15);
+            const bool live = e < MB * NB * 256 && nn < a.N;
 #pragma unroll
             for (int h = 0; h < 2 * RG; ++h)
                 bpre[x][h] = (live && 8 * h < r) ? *(const u16x8_t *)(a.B + (long)nn * r + 8 * h) : ZERO8;
@@ -356,7 +363,7 @@ __global__ __launch_bounds__(NW * 64) void gemv_fwd_staged_kernel(const FwdArgs 
             if (i >= n_it) break;
             // slice i has landed when at most the ND copies of slice i+1 (issued after it) are still in flight
             if (i + 1 < n_it) wait_vm<ND>(); else wait_vm<0>();
-            const uint8_t *buf = stage + (size_t)(wave * 2 + (u & 1)) * (BLOCKS * ST_BLOCK);
+            const uint8_t *buf = stage + (size_t)wave * WAVE_STAGE + (size_t)(u & 1) * (BLOCKS * ST_BLOCK);
             u16x8_t xf[MB][4], af[RGS][4];
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
@@ -400,10 +407,10 @@ __global__ __launch_bounds__(NW * 64) void gemv_fwd_staged_kernel(const FwdArgs 
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) red[wave][mb][nb][4 * q + v][li] = acc[mb][nb][v];
+            for (int nb = 0; nb < NB; ++nb) red(wave, mb, nb, 4 * q + v, li) = acc[mb][nb][v];
             if constexpr (RG > 0) {
 #pragma unroll
-                for (int g = 0; g < RG; ++g) tred[wave][mb][g][4 * q + v][li] = tacc[mb][g][v];
+                for (int g = 0; g < RG; ++g) tred(wave, mb, g, 4 * q + v, li) = tacc[mb][g][v];
             }
         }
     __syncthreads();
@@ -414,7 +421,7 @@ __global__ __launch_bounds__(NW * 64) void gemv_fwd_staged_kernel(const FwdArgs 
             if (j < r && m < a.M) {
                 const int mb = m >> 4, ml = m & 15, g = j >> 4, jl = j & 15;
 #pragma unroll
-                for (int w = 0; w < NW; ++w) tv += tred[w][mb][g][ml][jl];
+                for (int w = 0; w < NW; ++w) tv += tred(w, mb, g, ml, jl);
                 tv = cvt16<BF16>(to16<BF16>(tv));          // the value every consumer of t sees
                 if (blockIdx.x == 0 && a.t_out) a.t_out[(long)m * r + j] = to16<BF16>(tv);
             }
@@ -427,12 +434,12 @@ __global__ __launch_bounds__(NW * 64) void gemv_fwd_staged_kernel(const FwdArgs 
 #pragma unroll
     for (int x = 0; x < EPT; ++x) {
         const int e = threadIdx.x + x * NT;
-        const int mb = e >> 8, ml = (e >> 4) & 15, nl = e & 15;
-        const int m = mb * 16 + ml, nn = n0 + nl;
-        if (e >= MB * 256 || m >= a.M || nn >= a.N) continue;
+        const int mb = e / (NB * 256), nb = (e >> 8) % NB, ml = (e >> 4) & 15, nl = e & 15;
+        const int m = mb * 16 + ml, nn = n0 + nb * 16 + nl;
+        if (e >= MB * NB * 256 || m >= a.M || nn >= a.N) continue;
         float v = 0.f;
 #pragma unroll
-        for (int w = 0; w < NW; ++w) v += red[w][mb][0][ml][nl];
+        for (int w = 0; w < NW; ++w) v += red(w, mb, nb, ml, nl);
         float lo = 0.f;
         if constexpr (RG > 0) {
 #pragma unroll
@@ -781,31 +788,37 @@ void launch_fwd_rg(const FwdArgs &a, int rg, hipStream_t s)
     }
 }
 
-template <int BITS, bool BF16, int MB, int RG, int NW>
+template <int BITS, bool BF16, int MB, int RG, int NW, int NB>
 void launch_fwd_staged_one(const FwdArgs &a, hipStream_t s)
 {
     constexpr int lds = NW * 2 * (MB + RG) * ST_BLOCK;            // 128 KB of slices at most
-    auto kern = gemv_fwd_staged_kernel<BITS, BF16, MB, RG, NW>;
+    auto kern = gemv_fwd_staged_kernel<BITS, BF16, MB, RG, NW, NB>;
     static bool configured = false;   // raising the dynamic-LDS ceiling is a property of the function, set once
     if (!configured) {
         (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         configured = true;
     }
-    hipLaunchKernelGGL(kern, dim3((a.N + 15) / 16), dim3(NW * 64), lds, s, a);
+    hipLaunchKernelGGL(kern, dim3((a.N + 16 * NB - 1) / (16 * NB)), dim3(NW * 64), lds, s, a);
 }
 
 template <int BITS, bool BF16, int MB, int RG>
 void launch_fwd_staged_rg(const FwdArgs &a, hipStream_t s)
 {
-    // Eight waves per workgroup when there is one workgroup per compute unit or less; with more weight rows than
-    // that, four-wave workgroups, two to a compute unit, so that one's first loads overlap the other's tail.
-    if constexpr (MB + RG <= 2) {
-        if ((a.N + 15) / 16 < 512) {
-            launch_fwd_staged_one<BITS, BF16, MB, RG, 8>(a, s);
-            return;
+    // Every workgroup pulls all of x and A through its compute unit once, however many weight rows it owns: with
+    // more 16-row blocks than compute units a workgroup takes up to four of them (one token block only: the
+    // registers are needed for the packed words).
+    constexpr int NW = MB + RG <= 2 ? 8 : 4;
+    const int blocks = (a.N + 15) / 16;
+    if constexpr (MB == 1) {
+        constexpr int NBMAX = BITS == 8 ? 3 : 4;              // 8-bit words: four blocks' worth would spill
+        switch (blocks > 256 * (NBMAX - 1) ? NBMAX : (blocks + 255) / 256) {
+        case 4: launch_fwd_staged_one<BITS, BF16, MB, RG, NW, NBMAX>(a, s); return;
+        case 3: launch_fwd_staged_one<BITS, BF16, MB, RG, NW, 3>(a, s); return;
+        case 2: launch_fwd_staged_one<BITS, BF16, MB, RG, NW, 2>(a, s); return;
+        default: break;
         }
     }
-    launch_fwd_staged_one<BITS, BF16, MB, RG, 4>(a, s);
+    launch_fwd_staged_one<BITS, BF16, MB, RG, NW, 1>(a, s);
 }
 
 template <int BITS, bool BF16, int MB>
@@ -835,10 +848,13 @@ void launch_bwd_bits(const BwdArgs &a, int slices, hipStream_t s)
     const dim3 grid((a.K + BwdShape<BITS>::CB - 1) / BwdShape<BITS>::CB, slices);
     // Two chunks per wave in flight (more would not fit the register file at eight waves); eight waves share out the
     // arithmetic of a slice, four are enough when the slice has no more than eight chunks.
-    if (a.rows_per_slice / 32 > 8)
-        hipLaunchKernelGGL((gemv_bwd_kernel<BITS, BF16, 8, 2>), grid, dim3(512), 0, s, a);
-    else
-        hipLaunchKernelGGL((gemv_bwd_kernel<BITS, BF16, 4, 2>), grid, dim3(256), 0, s, a);
+    if constexpr (BITS != 3) {      // 3-bit: 32 columns per lane, the accumulators need the four-wave register budget
+        if (a.rows_per_slice / 32 > 8) {
+            hipLaunchKernelGGL((gemv_bwd_kernel<BITS, BF16, 8, 2>), grid, dim3(512), 0, s, a);
+            return;
+        }
+    }
+    hipLaunchKernelGGL((gemv_bwd_kernel<BITS, BF16, 4, 2>), grid, dim3(256), 0, s, a);
 }
 
 int bwd_cb(int bits) { return bits == 3 ? BwdShape<3>::CB : (bits == 2 ? BwdShape<2>::CB : (bits == 4 ? BwdShape<4>::CB : BwdShape<8>::CB)); }
