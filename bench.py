@@ -192,8 +192,8 @@ def run_cpu_baseline(inp, max_rows: int):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=200)   # 35 ms of timed work: the clocks settle over the first ~20 ms
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--cpu-rows", type=int, default=2048, help="token rows the CPU oracle baseline is timed on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-small-m", action="store_true")

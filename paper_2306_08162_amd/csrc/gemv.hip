@@ -1,11 +1,12 @@
 // Small token counts: the pass is bound by streaming the packed weight once from HBM (Limitations of the paper:
 // the compressed weight cuts the memory traffic of both passes; this is the regime where that shows).  Every lane
 // fetches its own MFMA fragment of packed words straight from global memory, dequantises it in registers and feeds
-// v_mfma_f32_16x16x32; only partial sums go through LDS.  Launches are what the pass is made of at this size, so
-// the rank-r products ride along: one launch forward, two backward.
+// v_mfma_f32_16x16x32; partial sums go through LDS (and, up to 32 token rows, so do x and A: see the staged
+// forward kernel).  Launches are what the pass is made of at this size, so the rank-r products ride along: one
+// launch forward, two backward.
 //
 //   forward  (M <= 64)  y = x Wd^T + sc * t B^T with t = x A^T computed by the same MFMAs (one extra fragment of
-//            A per k-step); one workgroup per 16 weight rows, its 4 waves split K.
+//            A per k-step); one workgroup per 16 weight rows (up to four such blocks), its waves split K.
 //   backward (M <= 16)  kernel 1: partial dX = dY Wd over row slices of the weight, and partial u = dY B.  The
 //            contraction runs over the weight's rows n, so a lane gathers the same few words from 8 consecutive
 //            rows and transposes the 8 x CL block of codes in registers (Sec. 3.1: transpose + unpack + matmul in one
@@ -552,7 +553,8 @@ __global__ __launch_bounds__(NW * 64) void gemv_bwd_kernel(const BwdArgs a)
     const int kc = kok ? kcol : 0;
     const int Kw = K * BITS / 32;
     const int g = group_of(kc, a.magic);
-    const bool uniform_group = group_of(cb * CB, a.magic) == group_of(min(cb * CB + CB, K) - 1, a.magic);
+    const int g_block = group_of(cb * CB, a.magic);        // group of the block's first column (lanes past K hold g of column 0)
+    const bool uniform_group = g_block == group_of(min(cb * CB + CB, K) - 1, a.magic);
     const int nbeg = blockIdx.y * a.rows_per_slice, nend = min(N, nbeg + a.rows_per_slice);
     const bool do_u = cb == 0 && r > 0;
 
@@ -604,7 +606,7 @@ __global__ __launch_bounds__(NW * 64) void gemv_bwd_kernel(const BwdArgs a)
             }
             if (uniform_group) {
                 // one scale / zero-point per row for the whole column block: lane l < 32 fetches row n0 + l
-                const long gi = (long)min(n0 + (lane & 31), N - 1) * a.ng + g;
+                const long gi = (long)min(n0 + (lane & 31), N - 1) * a.ng + g_block;
                 sraw[u][0] = a.scales[gi];
                 zraw[u][0] = a.zeros[gi];
             } else {
@@ -729,8 +731,15 @@ __global__ __launch_bounds__(256) void gemv_bwd_finish_kernel(const FinishArgs a
     if (b < a.xb + a.ab) {
         for (int e = threadIdx.x; e < M * r; e += 256) {
             const int m = e / r, j = e % r;
+            const float *up = a.upartial + m * 64 + j;
             float v = 0.f;
-            for (int s = 0; s < a.slices; ++s) v += a.upartial[(long)s * 1024 + m * 64 + j];
+            for (int s0 = 0; s0 < a.slices; s0 += 8) {       // eight slices requested together, summed in slice order
+                float pv[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) pv[i] = s0 + i < a.slices ? up[(long)(s0 + i) * 1024] : 0.f;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) v += pv[i];
+            }
             side[m][j] = cvt16<BF16>(to16<BF16>(v));
         }
     } else {

@@ -3,6 +3,8 @@
 Integer work (packed words, unpacked codes) must match bit for bit; y, dX, dA, dB
 must be within 5e-3 relative Frobenius error.
 """
+import os
+
 import numpy as np
 import pytest
 
@@ -73,6 +75,9 @@ SMALL_CASES = [
     (3, 512, 96, 8, 64, 0, "f16"),             # no adapter, small M
     (30, 256, 64, 4, 32, 64, "bf16"),          # rank 64 at small M: t comes from its own launch
     (32, 128, 48, 3, 128, 16, "bf16"),
+    (4, 160, 4200, 8, 32, 8, "f16"),           # two 16-row weight blocks per workgroup, last workgroup half empty
+    (16, 96, 12312, 2, 32, 8, "bf16"),         # four blocks per workgroup, ragged; backward with many row slices
+    (11, 2048, 1544, 4, 128, 16, "f16"),       # backward: 8-wave workgroups, slices that do not divide the rows
 ]
 
 
@@ -83,6 +88,35 @@ def test_small_shapes(case):
     check_layer(inp)
     if r:
         check_layer(inp, recompute_t=True)
+
+
+def _random_cases(count, seed):
+    """Seeded random legal shapes: every dimension ragged against every tile size somewhere in the set."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(count):
+        bits = int(rng.choice([2, 3, 4, 8]))
+        K = 32 * int(rng.integers(1, 41))                         # 32 .. 1280
+        divisors = [g for g in range(32, K + 1, 32) if K % g == 0]
+        G = int(rng.choice(divisors))
+        M = int(rng.choice([1, 2, 7, 15, 16, 17, 31, 33, 48, 64, 65, 100, 257]))
+        N = 8 * int(rng.integers(1, 90))                          # 8 .. 712
+        if rng.random() < 0.25:
+            N = 8 * int(rng.integers(500, 1100))                  # enough rows for several row slices / weight blocks
+        r = int(rng.choice([0, 8, 8, 16, 24, 32, 40, 64]))
+        dtype = "f16" if rng.random() < 0.5 else "bf16"
+        cases.append((M, K, N, bits, G, r, dtype))
+    return cases
+
+
+# more cases, or other ones: QLORA_FUZZ_CASES=300 QLORA_FUZZ_SEED=7 python -m pytest tests/test_gpu_parity.py -m gpu -k random
+@pytest.mark.parametrize("case", _random_cases(int(os.environ.get("QLORA_FUZZ_CASES", "40")),
+                                               int(os.environ.get("QLORA_FUZZ_SEED", "20230608"))),
+                         ids=lambda c: "M{}_K{}_N{}_b{}_G{}_r{}_{}".format(*c))
+def test_random_shapes(case):
+    M, K, N, bits, G, r, dtype = case
+    inp = small_inputs(13 * M + 3 * K + N + bits, M, K, N, bits, G, r, dtype)
+    check_layer(inp, recompute_t=bool(r) and (M + N) % 2 == 0)
 
 
 def test_results_are_bitwise_reproducible():
