@@ -118,6 +118,43 @@ int qlora_linear_bwd(const void *dy, const void *x, const uint32_t *packed, cons
                      void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Sibling projections at small token counts.  Projections that read the same
+ * input (q/k/v of an attention block, gate/up of an MLP; the paper adapts "every
+ * linear projection", Appendix C) can be handed over together: one launch
+ * streams all their packed weights and fetches x once per workgroup instead of
+ * once per projection, and their contributions to dX are summed by the same
+ * reduction that sums the row slices.  Results equal those of the per-layer
+ * calls (y_i, dA_i, dB_i as above; dX = sum over i of the per-layer dX_i).
+ *
+ * count in [1, QLORA_MAX_SIBLINGS]; M <= QLORA_SIBLINGS_MAX_M (the
+ * weight-streaming regime: larger M is what the per-layer calls are for).  The
+ * siblings share M, K, bits, group_size, rank, alpha and dtype; projection i has
+ * N[i] out-features and its own packed[i], scales[i], zeros[i], A[i], B[i],
+ * y[i] / dy[i], dA[i], dB[i].  N and the pointer arrays are HOST arrays of `count`
+ * entries (the entries are device pointers); they are read before the call
+ * returns.  t_save / t_saved may be NULL, or hold NULL entries, meaning "not
+ * saved" / "recompute" for that projection.  Validation and errors as above.
+ */
+#define QLORA_MAX_SIBLINGS 4
+#define QLORA_SIBLINGS_MAX_M 16
+
+/* Bytes of scratch the two sibling calls need (the larger of the two); 0 if the arguments are invalid. */
+size_t qlora_siblings_workspace_bytes(int count, const int *N, int M, int K, int bits, int group_size, int rank);
+
+int qlora_linear_fwd_siblings(int count, const void *x, const uint32_t *const *packed, const void *const *scales,
+                              const uint8_t *const *zeros, const void *const *A, const void *const *B,
+                              void *const *y, void *const *t_save, const int *N,
+                              int M, int K, int bits, int group_size, int rank, float alpha, int dtype,
+                              void *workspace, size_t workspace_bytes, void *stream);
+
+int qlora_linear_bwd_siblings(int count, const void *const *dy, const void *x, const uint32_t *const *packed,
+                              const void *const *scales, const uint8_t *const *zeros, const void *const *A,
+                              const void *const *B, const void *const *t_saved,
+                              void *dx, float *const *dA, float *const *dB, const int *N,
+                              int M, int K, int bits, int group_size, int rank, float alpha, int dtype,
+                              void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Instrumentation for benchmarks (not part of the layer, not thread-safe): while a pair of hipEvent_t
  * handles is set, every qlora_linear_fwd / qlora_linear_bwd call records ev_before on its stream right
  * before its GEMM kernel (the fused dequantise + MFMA kernel that dominates the pass) and ev_after right

@@ -18,7 +18,9 @@ QLORA_F16, QLORA_BF16 = 0, 1
 STATUS_NAMES = ["QLORA_OK", "QLORA_E_NULL", "QLORA_E_BITS", "QLORA_E_SHAPE", "QLORA_E_GROUP", "QLORA_E_RANK",
                 "QLORA_E_DTYPE", "QLORA_E_ALIGN", "QLORA_E_WORKSPACE", "QLORA_E_HIP"]
 EXPORTS = ["qlora_status_string", "qlora_packed_words", "qlora_workspace_bytes", "qlora_pack", "qlora_unpack",
-           "qlora_linear_fwd", "qlora_linear_bwd", "qlora_profile_gemm"]
+           "qlora_linear_fwd", "qlora_linear_bwd", "qlora_siblings_workspace_bytes", "qlora_linear_fwd_siblings",
+           "qlora_linear_bwd_siblings", "qlora_profile_gemm"]
+MAX_SIBLINGS, SIBLINGS_MAX_M = 4, 16
 
 _lib = None
 
@@ -58,6 +60,12 @@ def load() -> ctypes.CDLL:
     lib.qlora_linear_bwd.argtypes = [vp] * 11 + [c_int] * 6 + [f32, c_int, vp, c_sz, vp]
     lib.qlora_profile_gemm.restype = c_int
     lib.qlora_profile_gemm.argtypes = [vp, vp]
+    lib.qlora_siblings_workspace_bytes.restype = c_sz
+    lib.qlora_siblings_workspace_bytes.argtypes = [c_int, vp] + [c_int] * 5
+    lib.qlora_linear_fwd_siblings.restype = c_int
+    lib.qlora_linear_fwd_siblings.argtypes = [c_int] + [vp] * 9 + [c_int] * 5 + [f32, c_int, vp, c_sz, vp]
+    lib.qlora_linear_bwd_siblings.restype = c_int
+    lib.qlora_linear_bwd_siblings.argtypes = [c_int] + [vp] * 12 + [c_int] * 5 + [f32, c_int, vp, c_sz, vp]
     _lib = lib
     return lib
 
@@ -140,4 +148,53 @@ def qlora_linear_bwd(dy, x, packed, scales, zeros, A, B, t_saved, dx, dA, dB, M:
                                  float(alpha), dtype, _ptr(workspace), workspace_bytes, _stream(stream))
     if check and st != 0:
         raise QLoraError(st, "qlora_linear_bwd")
+    return st
+
+
+def _ptr_array(items, count: int):
+    """Host array of `count` device pointers (None entries are NULL); None stays a NULL array."""
+    if items is None:
+        return None
+    if len(items) != count:
+        raise ValueError("one entry per sibling projection is needed")
+    return (ctypes.c_void_p * count)(*[_ptr(t) for t in items])
+
+
+def _int_array(values):
+    return (ctypes.c_int * len(values))(*[int(v) for v in values])
+
+
+def qlora_siblings_workspace_bytes(N, M: int, K: int, bits: int, group_size: int, rank: int) -> int:
+    return int(load().qlora_siblings_workspace_bytes(len(N), _int_array(N), M, K, bits, group_size, rank))
+
+
+def qlora_linear_fwd_siblings(x, packed, scales, zeros, A, B, y, t_save, N, M: int, K: int, bits: int,
+                              group_size: int, rank: int, alpha: float, dtype: int, workspace,
+                              workspace_bytes: Optional[int] = None, stream=None, check: bool = True) -> int:
+    """packed, scales, zeros, A, B, y, t_save: sequences with one buffer per sibling projection; N: their out-features."""
+    n = len(N)
+    if workspace_bytes is None:
+        workspace_bytes = _nbytes(workspace)
+    st = load().qlora_linear_fwd_siblings(n, _ptr(x), _ptr_array(packed, n), _ptr_array(scales, n),
+                                          _ptr_array(zeros, n), _ptr_array(A, n), _ptr_array(B, n), _ptr_array(y, n),
+                                          _ptr_array(t_save, n), _int_array(N), M, K, bits, group_size, rank,
+                                          float(alpha), dtype, _ptr(workspace), workspace_bytes, _stream(stream))
+    if check and st != 0:
+        raise QLoraError(st, "qlora_linear_fwd_siblings")
+    return st
+
+
+def qlora_linear_bwd_siblings(dy, x, packed, scales, zeros, A, B, t_saved, dx, dA, dB, N, M: int, K: int, bits: int,
+                              group_size: int, rank: int, alpha: float, dtype: int, workspace,
+                              workspace_bytes: Optional[int] = None, stream=None, check: bool = True) -> int:
+    n = len(N)
+    if workspace_bytes is None:
+        workspace_bytes = _nbytes(workspace)
+    st = load().qlora_linear_bwd_siblings(n, _ptr_array(dy, n), _ptr(x), _ptr_array(packed, n), _ptr_array(scales, n),
+                                          _ptr_array(zeros, n), _ptr_array(A, n), _ptr_array(B, n),
+                                          _ptr_array(t_saved, n), _ptr(dx), _ptr_array(dA, n), _ptr_array(dB, n),
+                                          _int_array(N), M, K, bits, group_size, rank, float(alpha), dtype,
+                                          _ptr(workspace), workspace_bytes, _stream(stream))
+    if check and st != 0:
+        raise QLoraError(st, "qlora_linear_bwd_siblings")
     return st

@@ -163,7 +163,8 @@ int qlora_linear_fwd(const void *x, const uint32_t *packed, const void *scales, 
         void *t = rank > 0 ? (t_save ? t_save : (void *)(ws + w.t_off)) : nullptr;
         if (rank > 0 && !fwd_small_computes_t(rank)) launch_lora_down(x, A, t, M, K, rank, p.bf16, s);
         GemmTimer timer(s);
-        launch_fwd_small(p, x, packed, scales, zeros, A, B, t, t, y, s);
+        const void *tc = t;
+        launch_fwd_small(p, 1, x, &packed, &scales, &zeros, &A, &B, &tc, &t, &y, &N, s);
     } else {
         void *t = nullptr;
         if (rank > 0) {
@@ -203,8 +204,8 @@ int qlora_linear_bwd(const void *dy, const void *x, const uint32_t *packed, cons
             t = ws + w.t_off;
         }
         GemmTimer timer(s);
-        launch_bwd_small(p, dy, x, packed, scales, zeros, A, B, t, dx, dA, dB, (float *)(ws + w.partial_off),
-                         (float *)(ws + w.upartial_off), s);
+        launch_bwd_small(p, 1, &dy, x, &packed, &scales, &zeros, &A, &B, &t, dx, &dA, &dB, &N,
+                         (float *)(ws + w.partial_off), (float *)(ws + w.upartial_off), s);
         return hip_status();
     }
     void *u = nullptr;
@@ -225,6 +226,126 @@ int qlora_linear_bwd(const void *dy, const void *x, const uint32_t *packed, cons
         float *partial = (float *)(ws + w.partial_off);
         launch_adapter_grads(dy, t, x, u, dB, dA, partial, M, N, K, rank, p.sc, p.bf16, s);
     }
+    return hip_status();
+}
+
+namespace {
+
+struct SiblingWorkspace {
+    size_t t_off[MAX_SIBLINGS], upartial_off, partial_off, total;
+};
+
+SiblingWorkspace carve_siblings(int count, const int *N, int M, int K, int r, int bits)
+{
+    SiblingWorkspace w{};
+    size_t off = 0;
+    for (int i = 0; i < count; ++i) {
+        w.t_off[i] = off;
+        off += round_up((size_t)M * r * 2);
+    }
+    int slices[MAX_SIBLINGS];
+    const size_t total_slices = (size_t)gemv_bwd_slices_siblings(count, N, K, bits, slices);
+    w.upartial_off = off;
+    off += round_up(total_slices * 1024 * sizeof(float));
+    w.partial_off = off;
+    off += round_up(total_slices * M * K * sizeof(float));
+    w.total = off < ALIGN ? ALIGN : off;
+    return w;
+}
+
+int check_siblings(int count, const int *N, int M, int K, int bits, int G, int r, int dtype)
+{
+    if (!N) return QLORA_E_NULL;
+    if (count < 1 || count > QLORA_MAX_SIBLINGS || M > QLORA_SIBLINGS_MAX_M) return QLORA_E_SHAPE;
+    for (int i = 0; i < count; ++i) {
+        const int st = check_problem(M, N[i], K, bits, G, r, dtype);
+        if (st != QLORA_OK) return st;
+    }
+    return QLORA_OK;
+}
+
+}  // namespace
+
+static_assert(QLORA_MAX_SIBLINGS == MAX_SIBLINGS && QLORA_SIBLINGS_MAX_M == SMALL_M_BWD_MAX, "header and kernels agree");
+
+size_t qlora_siblings_workspace_bytes(int count, const int *N, int M, int K, int bits, int group_size, int rank)
+{
+    if (check_siblings(count, N, M, K, bits, group_size, rank, QLORA_F16) != QLORA_OK) return 0;
+    return carve_siblings(count, N, M, K, rank, bits).total;
+}
+
+int qlora_linear_fwd_siblings(int count, const void *x, const uint32_t *const *packed, const void *const *scales,
+                              const uint8_t *const *zeros, const void *const *A, const void *const *B,
+                              void *const *y, void *const *t_save, const int *N, int M, int K, int bits,
+                              int group_size, int rank, float alpha, int dtype, void *workspace,
+                              size_t workspace_bytes, void *stream)
+{
+    const int st = check_siblings(count, N, M, K, bits, group_size, rank, dtype);
+    if (st != QLORA_OK) return st;
+    if (!x || !packed || !scales || !zeros || !y) return QLORA_E_NULL;
+    if (rank > 0 && (!A || !B)) return QLORA_E_NULL;
+    if (misaligned(x) || misaligned(workspace)) return QLORA_E_ALIGN;
+    for (int i = 0; i < count; ++i) {
+        if (!packed[i] || !scales[i] || !zeros[i] || !y[i]) return QLORA_E_NULL;
+        if (rank > 0 && (!A[i] || !B[i])) return QLORA_E_NULL;
+        if (misaligned(packed[i]) || misaligned(scales[i]) || misaligned(zeros[i]) || misaligned(y[i]) ||
+            (rank > 0 && (misaligned(A[i]) || misaligned(B[i]))) || (t_save && misaligned(t_save[i])))
+            return QLORA_E_ALIGN;
+    }
+    const SiblingWorkspace w = carve_siblings(count, N, M, K, rank, bits);
+    if (!workspace || workspace_bytes < w.total) return QLORA_E_WORKSPACE;
+
+    const hipStream_t s = (hipStream_t)stream;
+    const Problem p{M, 0, K, bits, group_size, rank, rank > 0 ? alpha / (float)rank : 0.f, dtype == QLORA_BF16};
+    char *ws = (char *)workspace;
+    void *t[MAX_SIBLINGS] = {};
+    const void *tc[MAX_SIBLINGS] = {};
+    for (int i = 0; i < count && rank > 0; ++i) {
+        t[i] = (t_save && t_save[i]) ? t_save[i] : (void *)(ws + w.t_off[i]);
+        tc[i] = t[i];
+        if (!fwd_small_computes_t(rank)) launch_lora_down(x, A[i], t[i], M, K, rank, p.bf16, s);
+    }
+    GemmTimer timer(s);
+    launch_fwd_small(p, count, x, packed, scales, zeros, A, B, tc, t, y, N, s);
+    return hip_status();
+}
+
+int qlora_linear_bwd_siblings(int count, const void *const *dy, const void *x, const uint32_t *const *packed,
+                              const void *const *scales, const uint8_t *const *zeros, const void *const *A,
+                              const void *const *B, const void *const *t_saved, void *dx, float *const *dA,
+                              float *const *dB, const int *N, int M, int K, int bits, int group_size, int rank,
+                              float alpha, int dtype, void *workspace, size_t workspace_bytes, void *stream)
+{
+    const int st = check_siblings(count, N, M, K, bits, group_size, rank, dtype);
+    if (st != QLORA_OK) return st;
+    if (!dy || !packed || !scales || !zeros || !dx) return QLORA_E_NULL;
+    if (rank > 0 && (!x || !A || !B || !dA || !dB)) return QLORA_E_NULL;
+    if (misaligned(x) || misaligned(dx) || misaligned(workspace)) return QLORA_E_ALIGN;
+    for (int i = 0; i < count; ++i) {
+        if (!dy[i] || !packed[i] || !scales[i] || !zeros[i]) return QLORA_E_NULL;
+        if (rank > 0 && (!A[i] || !B[i] || !dA[i] || !dB[i])) return QLORA_E_NULL;
+        if (misaligned(dy[i]) || misaligned(packed[i]) || misaligned(scales[i]) || misaligned(zeros[i]) ||
+            (rank > 0 && (misaligned(A[i]) || misaligned(B[i]) || misaligned(dA[i]) || misaligned(dB[i]))) ||
+            (t_saved && misaligned(t_saved[i])))
+            return QLORA_E_ALIGN;
+    }
+    const SiblingWorkspace w = carve_siblings(count, N, M, K, rank, bits);
+    if (!workspace || workspace_bytes < w.total) return QLORA_E_WORKSPACE;
+
+    const hipStream_t s = (hipStream_t)stream;
+    const Problem p{M, 0, K, bits, group_size, rank, rank > 0 ? alpha / (float)rank : 0.f, dtype == QLORA_BF16};
+    char *ws = (char *)workspace;
+    const void *t[MAX_SIBLINGS] = {};
+    for (int i = 0; i < count && rank > 0; ++i) {
+        t[i] = t_saved ? t_saved[i] : nullptr;
+        if (!t[i]) {
+            launch_lora_down(x, A[i], ws + w.t_off[i], M, K, rank, p.bf16, s);
+            t[i] = ws + w.t_off[i];
+        }
+    }
+    GemmTimer timer(s);
+    launch_bwd_small(p, count, dy, x, packed, scales, zeros, A, B, t, dx, dA, dB, N, (float *)(ws + w.partial_off),
+                     (float *)(ws + w.upartial_off), s);
     return hip_status();
 }
 

@@ -77,6 +77,14 @@ struct FwdArgs {
     uint32_t magic;
 };
 
+// Sibling projections (q/k/v, gate/up) read the same x: one launch serves up to four of them.  They share M, K, the
+// code width, the grouping and the rank; workgroups [wg_end[i-1], wg_end[i]) belong to projection i.
+struct FwdMulti {
+    FwdArgs p[MAX_SIBLINGS];
+    int wg_end[MAX_SIBLINGS];
+    int count;
+};
+
 template <int BITS, bool BF16, int MB, int RG, int NW, int NB>   // RG: 16-column groups of t formed here (0: none);
                                                                   // NW waves; NB 16-row weight blocks per workgroup
 __global__ __launch_bounds__(NW * 64) void gemv_fwd_kernel(const FwdArgs a)
@@ -254,7 +262,7 @@ __device__ __forceinline__ void wait_vm()
 __device__ __forceinline__ void wait_lds() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
 template <int BITS, bool BF16, int MB, int RG, int NW, int NB>   // NB: 16-row weight blocks per workgroup
-__global__ __launch_bounds__(NW * 64) void gemv_fwd_staged_kernel(const FwdArgs a)
+__device__ __forceinline__ void gemv_fwd_staged_body(const FwdArgs &a, const int wg)   // wg: workgroup index inside the projection
 {
     constexpr int RGS = RG > 0 ? RG : 1, NT = NW * 64;
     constexpr int BLOCKS = MB + RG;                 // 16-row blocks per slice: x blocks, then A blocks
@@ -273,7 +281,7 @@ __global__ __launch_bounds__(NW * 64) void gemv_fwd_staged_kernel(const FwdArgs 
     __shared__ float tfull[MB * 16][TC + 1];
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int li = lane & 15, q = lane >> 4;
-    const int n0 = blockIdx.x * 16 * NB;
+    const int n0 = wg * 16 * NB;
     const int K = a.K, Kw = K * BITS / 32, r = a.r;
     int nrow[NB];
     const uint32_t *wrow[NB];
@@ -424,7 +432,7 @@ __global__ __launch_bounds__(NW * 64) void gemv_fwd_staged_kernel(const FwdArgs 
 #pragma unroll
                 for (int w = 0; w < NW; ++w) tv += tred(w, mb, g, ml, jl);
                 tv = cvt16<BF16>(to16<BF16>(tv));          // the value every consumer of t sees
-                if (blockIdx.x == 0 && a.t_out) a.t_out[(long)m * r + j] = to16<BF16>(tv);
+                if (wg == 0 && a.t_out) a.t_out[(long)m * r + j] = to16<BF16>(tv);
             }
             tfull[m][j] = tv;
         }
@@ -456,6 +464,22 @@ __global__ __launch_bounds__(NW * 64) void gemv_fwd_staged_kernel(const FwdArgs 
         }
         a.y[(long)m * a.N + nn] = to16<BF16>(v + a.sc * lo);
     }
+}
+
+template <int BITS, bool BF16, int MB, int RG, int NW, int NB>
+__global__ __launch_bounds__(NW * 64) void gemv_fwd_staged_kernel(const FwdArgs a)
+{
+    gemv_fwd_staged_body<BITS, BF16, MB, RG, NW, NB>(a, (int)blockIdx.x);
+}
+
+// several sibling projections in one launch: the workgroup first finds the projection it belongs to
+template <int BITS, bool BF16, int MB, int RG, int NW, int NB>
+__global__ __launch_bounds__(NW * 64) void gemv_fwd_staged_siblings_kernel(const FwdMulti ma)
+{
+    int pi = 0;
+    while (pi + 1 < ma.count && (int)blockIdx.x >= ma.wg_end[pi]) ++pi;          // wave-uniform
+    const FwdArgs a = ma.p[pi];
+    gemv_fwd_staged_body<BITS, BF16, MB, RG, NW, NB>(a, (int)blockIdx.x - (pi ? ma.wg_end[pi - 1] : 0));
 }
 
 // ------------------------------------------------------------------------------------------------ backward
@@ -532,8 +556,9 @@ __device__ __forceinline__ u16x8_t dequant_rows8_f16(const uint32_t (&w)[8][WORD
     return __builtin_bit_cast(u16x8_t, out);
 }
 
+// sp_local: row slice inside the projection; sp: slice among all slices of the launch (where its partial sums go)
 template <int BITS, bool BF16, int NW, int BW_U>   // NW waves; BW_U 32-row chunks per wave in flight together
-__global__ __launch_bounds__(NW * 64) void gemv_bwd_kernel(const BwdArgs a)
+__device__ __forceinline__ void gemv_bwd_body(const BwdArgs &a, const int sp_local, const int sp)
 {
     using S = BwdShape<BITS>;
     constexpr int CL = S::CL, WORDS = S::WORDS, CB = S::CB;
@@ -555,7 +580,7 @@ __global__ __launch_bounds__(NW * 64) void gemv_bwd_kernel(const BwdArgs a)
     const int g = group_of(kc, a.magic);
     const int g_block = group_of(cb * CB, a.magic);        // group of the block's first column (lanes past K hold g of column 0)
     const bool uniform_group = g_block == group_of(min(cb * CB + CB, K) - 1, a.magic);
-    const int nbeg = blockIdx.y * a.rows_per_slice, nend = min(N, nbeg + a.rows_per_slice);
+    const int nbeg = sp_local * a.rows_per_slice, nend = min(N, nbeg + a.rows_per_slice);
     const bool do_u = cb == 0 && r > 0;
 
     float4_t acc[CL], uacc[4];
@@ -694,7 +719,7 @@ __global__ __launch_bounds__(NW * 64) void gemv_bwd_kernel(const BwdArgs a)
             float v = 0.f;
 #pragma unroll
             for (int w = 0; w < NW; ++w) v += red[w][m][kl];
-            a.partial[((long)blockIdx.y * a.M + m) * K + k] = v;
+            a.partial[((long)sp * a.M + m) * K + k] = v;
         }
     }
     if (do_u) {
@@ -703,9 +728,32 @@ __global__ __launch_bounds__(NW * 64) void gemv_bwd_kernel(const BwdArgs a)
             float v = 0.f;
 #pragma unroll
             for (int w = 0; w < NW; ++w) v += ured[w][m][j];
-            a.upartial[(long)blockIdx.y * 1024 + e] = v;
+            a.upartial[(long)sp * 1024 + e] = v;
         }
     }
+}
+
+struct BwdMulti {
+    BwdArgs p[MAX_SIBLINGS];
+    int slice_end[MAX_SIBLINGS];      // projection i owns the slices [slice_end[i-1], slice_end[i])
+    int count;
+};
+
+template <int BITS, bool BF16, int NW, int BW_U>
+__global__ __launch_bounds__(NW * 64) void gemv_bwd_kernel(const BwdArgs a)
+{
+    gemv_bwd_body<BITS, BF16, NW, BW_U>(a, (int)blockIdx.y, (int)blockIdx.y);
+}
+
+// sibling projections (same x, so their dX add up): the slices of all of them in one launch
+template <int BITS, bool BF16, int NW, int BW_U>
+__global__ __launch_bounds__(NW * 64) void gemv_bwd_siblings_kernel(const BwdMulti ma)
+{
+    const int sp = (int)blockIdx.y;
+    int pi = 0;
+    while (pi + 1 < ma.count && sp >= ma.slice_end[pi]) ++pi;      // wave-uniform
+    const BwdArgs a = ma.p[pi];
+    gemv_bwd_body<BITS, BF16, NW, BW_U>(a, sp - (pi ? ma.slice_end[pi - 1] : 0), sp);
 }
 
 // Second backward kernel (M <= 16), one thread per output element:
@@ -779,6 +827,92 @@ __global__ __launch_bounds__(256) void gemv_bwd_finish_kernel(const FinishArgs a
     }
 }
 
+// The same for sibling projections: dX sums the slices of all of them and every projection's sc * u_i A_i.
+//   blocks [0, xb)                 dX
+//   blocks [xb, xb + count*ab)     dA of projection (b - xb) / ab
+//   then, per projection           dB (its block range ends at bb_end)
+struct FinishProj {
+    const uint16_t *A, *dy, *t;
+    float *dA, *dB;
+    int N, slice_begin, slice_end, bb_end;
+};
+struct FinishMulti {
+    FinishProj p[MAX_SIBLINGS];
+    const float *partial, *upartial;
+    const uint16_t *x;
+    uint16_t *dx;
+    int M, K, r, slices, xb, ab, count;
+    float sc;
+};
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void gemv_bwd_finish_siblings_kernel(const FinishMulti a)
+{
+    __shared__ float side[MAX_SIBLINGS][16][64 + 1];
+    const int M = a.M, r = a.r, K = a.K;
+    const int b = blockIdx.x;
+    // u of projection i, as the 16-bit values it rounds to, into side[slot]
+    auto sum_u = [&](int i, int slot) {
+        const int sb = a.p[i].slice_begin, se = a.p[i].slice_end;
+        for (int e = threadIdx.x; e < M * r; e += 256) {
+            const int m = e / r, j = e % r;
+            const float *up = a.upartial + m * 64 + j;
+            float v = 0.f;
+            for (int s0 = sb; s0 < se; s0 += 8) {
+                float pv[8];
+#pragma unroll
+                for (int i8 = 0; i8 < 8; ++i8) pv[i8] = s0 + i8 < se ? up[(long)(s0 + i8) * 1024] : 0.f;
+#pragma unroll
+                for (int i8 = 0; i8 < 8; ++i8) v += pv[i8];
+            }
+            side[slot][m][j] = cvt16<BF16>(to16<BF16>(v));
+        }
+    };
+    if (b < a.xb) {
+        for (int i = 0; i < a.count; ++i) sum_u(i, i);
+        __syncthreads();
+        const long idx = (long)b * 256 + threadIdx.x;
+        if (idx >= (long)M * K) return;
+        const int m = (int)(idx / K), k = (int)(idx % K);
+        const long stride = (long)M * K;
+        float v = 0.f;
+        int s = 0;
+        for (; s + 4 <= a.slices; s += 4) {
+            const float p0 = a.partial[(s + 0) * stride + idx], p1 = a.partial[(s + 1) * stride + idx];
+            const float p2 = a.partial[(s + 2) * stride + idx], p3 = a.partial[(s + 3) * stride + idx];
+            v = (((v + p0) + p1) + p2) + p3;
+        }
+        for (; s < a.slices; ++s) v += a.partial[s * stride + idx];
+        float lo = 0.f;
+        for (int i = 0; i < a.count; ++i)
+            for (int j = 0; j < r; ++j) lo += side[i][m][j] * cvt16<BF16>(a.p[i].A[(long)j * K + k]);
+        a.dx[idx] = to16<BF16>(v + a.sc * lo);
+    } else if (b < a.xb + a.count * a.ab) {
+        const int i = (b - a.xb) / a.ab;
+        sum_u(i, 0);
+        __syncthreads();
+        const long idx = (long)((b - a.xb) % a.ab) * 256 + threadIdx.x;
+        if (idx >= (long)r * K) return;
+        const int j = (int)(idx / K), k = (int)(idx % K);
+        float v = 0.f;
+        for (int m = 0; m < M; ++m) v += side[0][m][j] * cvt16<BF16>(a.x[(long)m * K + k]);
+        a.p[i].dA[idx] = a.sc * v;
+    } else {
+        const int bb = b - a.xb - a.count * a.ab;
+        int i = 0;
+        while (i + 1 < a.count && bb >= a.p[i].bb_end) ++i;
+        const FinishProj pr = a.p[i];
+        for (int e = threadIdx.x; e < M * r; e += 256) side[0][e / r][e % r] = cvt16<BF16>(pr.t[e]);
+        __syncthreads();
+        const long idx = (long)(bb - (i ? a.p[i - 1].bb_end : 0)) * 256 + threadIdx.x;
+        if (idx >= (long)r * pr.N) return;
+        const int j = (int)(idx / pr.N), n = (int)(idx % pr.N);
+        float v = 0.f;
+        for (int m = 0; m < M; ++m) v += cvt16<BF16>(pr.dy[(long)m * pr.N + n]) * side[0][m][j];
+        pr.dB[(long)n * r + j] = a.sc * v;
+    }
+}
+
 inline uint32_t group_magic(int G)
 {
     const uint32_t d = (uint32_t)(G / 32);
@@ -797,73 +931,133 @@ void launch_fwd_rg(const FwdArgs &a, int rg, hipStream_t s)
     }
 }
 
+inline int blocks16(int N) { return (N + 15) / 16; }
+
 template <int BITS, bool BF16, int MB, int RG, int NW, int NB>
-void launch_fwd_staged_one(const FwdArgs &a, hipStream_t s)
+void launch_fwd_staged_one(FwdMulti m, hipStream_t s)
 {
     constexpr int lds = NW * 2 * (MB + RG) * ST_BLOCK;            // 128 KB of slices at most
-    auto kern = gemv_fwd_staged_kernel<BITS, BF16, MB, RG, NW, NB>;
-    static bool configured = false;   // raising the dynamic-LDS ceiling is a property of the function, set once
-    if (!configured) {
-        (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        configured = true;
+    int wgs = 0;
+    for (int i = 0; i < m.count; ++i) {
+        wgs += (blocks16(m.p[i].N) + NB - 1) / NB;
+        m.wg_end[i] = wgs;
     }
-    hipLaunchKernelGGL(kern, dim3((a.N + 16 * NB - 1) / (16 * NB)), dim3(NW * 64), lds, s, a);
+    if (m.count == 1) {
+        auto kern = gemv_fwd_staged_kernel<BITS, BF16, MB, RG, NW, NB>;
+        static bool configured = false;   // raising the dynamic-LDS ceiling is a property of the function, set once
+        if (!configured) {
+            (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+            configured = true;
+        }
+        hipLaunchKernelGGL(kern, dim3(wgs), dim3(NW * 64), lds, s, m.p[0]);
+        return;
+    }
+    if constexpr (MB == 1) {          // the callers hand siblings over together only up to 16 token rows
+        auto kern = gemv_fwd_staged_siblings_kernel<BITS, BF16, MB, RG, NW, NB>;
+        static bool configured = false;
+        if (!configured) {
+            (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+            configured = true;
+        }
+        hipLaunchKernelGGL(kern, dim3(wgs), dim3(NW * 64), lds, s, m);
+    }
 }
 
 template <int BITS, bool BF16, int MB, int RG>
-void launch_fwd_staged_rg(const FwdArgs &a, hipStream_t s)
+void launch_fwd_staged_rg(const FwdMulti &m, hipStream_t s)
 {
-    // Every workgroup pulls all of x and A through its compute unit once, however many weight rows it owns: with
-    // more 16-row blocks than compute units a workgroup takes up to four of them (one token block only: the
-    // registers are needed for the packed words).
+    // Every workgroup pulls all of x and A through its compute unit once, however many weight rows it owns, and the
+    // slices leave room for one workgroup per compute unit: the launch should be a single round of the 256 units.
+    // So a workgroup takes as many 16-row blocks (up to four; one token block only: the registers are needed for the
+    // packed words) as it takes to get there.  Siblings that do not fit one round together go out one by one.
     constexpr int NW = MB + RG <= 2 ? 8 : 4;
-    const int blocks = (a.N + 15) / 16;
     if constexpr (MB == 1) {
         constexpr int NBMAX = BITS == 8 ? 3 : 4;              // 8-bit words: four blocks' worth would spill
-        switch (blocks > 256 * (NBMAX - 1) ? NBMAX : (blocks + 255) / 256) {
-        case 4: launch_fwd_staged_one<BITS, BF16, MB, RG, NW, NBMAX>(a, s); return;
-        case 3: launch_fwd_staged_one<BITS, BF16, MB, RG, NW, 3>(a, s); return;
-        case 2: launch_fwd_staged_one<BITS, BF16, MB, RG, NW, 2>(a, s); return;
+        int nb = 0;
+        for (int cand = 1; cand <= NBMAX && nb == 0; ++cand) {
+            int wgs = 0;
+            for (int i = 0; i < m.count; ++i) wgs += (blocks16(m.p[i].N) + cand - 1) / cand;
+            if (wgs <= 256) nb = cand;
+        }
+        if (nb == 0 && m.count > 1) {
+            for (int i = 0; i < m.count; ++i) {
+                FwdMulti one{};
+                one.count = 1;
+                one.p[0] = m.p[i];
+                launch_fwd_staged_rg<BITS, BF16, MB, RG>(one, s);
+            }
+            return;
+        }
+        switch (nb == 0 ? NBMAX : nb) {
+        case 4: launch_fwd_staged_one<BITS, BF16, MB, RG, NW, NBMAX>(m, s); return;
+        case 3: launch_fwd_staged_one<BITS, BF16, MB, RG, NW, 3>(m, s); return;
+        case 2: launch_fwd_staged_one<BITS, BF16, MB, RG, NW, 2>(m, s); return;
         default: break;
         }
     }
-    launch_fwd_staged_one<BITS, BF16, MB, RG, NW, 1>(a, s);
+    launch_fwd_staged_one<BITS, BF16, MB, RG, NW, 1>(m, s);
 }
 
 template <int BITS, bool BF16, int MB>
-void launch_fwd_staged(const FwdArgs &a, int rg, hipStream_t s)
+void launch_fwd_staged(const FwdMulti &m, int rg, hipStream_t s)
 {
     switch (rg) {
-    case 0: launch_fwd_staged_rg<BITS, BF16, MB, 0>(a, s); break;
-    case 1: launch_fwd_staged_rg<BITS, BF16, MB, 1>(a, s); break;
-    default: launch_fwd_staged_rg<BITS, BF16, MB, 2>(a, s); break;
+    case 0: launch_fwd_staged_rg<BITS, BF16, MB, 0>(m, s); break;
+    case 1: launch_fwd_staged_rg<BITS, BF16, MB, 1>(m, s); break;
+    default: launch_fwd_staged_rg<BITS, BF16, MB, 2>(m, s); break;
     }
 }
 
 template <int BITS, bool BF16>
-void launch_fwd_mb(const FwdArgs &a, int rg, hipStream_t s)
+void launch_fwd_mb(const FwdMulti &m, int rg, hipStream_t s)
 {
-    switch ((a.M + 15) / 16) {
-    case 1: launch_fwd_staged<BITS, BF16, 1>(a, rg, s); break;
-    case 2: launch_fwd_staged<BITS, BF16, 2>(a, rg, s); break;
-    case 3: launch_fwd_rg<BITS, BF16, 3>(a, rg, s); break;
-    default: launch_fwd_rg<BITS, BF16, 4>(a, rg, s); break;
+    switch ((m.p[0].M + 15) / 16) {
+    case 1: launch_fwd_staged<BITS, BF16, 1>(m, rg, s); break;
+    case 2:
+        for (int i = 0; i < m.count; ++i) {
+            FwdMulti one{};
+            one.count = 1;
+            one.p[0] = m.p[i];
+            launch_fwd_staged<BITS, BF16, 2>(one, rg, s);
+        }
+        break;
+    case 3:
+        for (int i = 0; i < m.count; ++i) launch_fwd_rg<BITS, BF16, 3>(m.p[i], rg, s);
+        break;
+    default:
+        for (int i = 0; i < m.count; ++i) launch_fwd_rg<BITS, BF16, 4>(m.p[i], rg, s);
+        break;
     }
 }
 
 template <int BITS, bool BF16>
-void launch_bwd_bits(const BwdArgs &a, int slices, hipStream_t s)
+void launch_bwd_bits(const BwdMulti &m, hipStream_t s)
 {
-    const dim3 grid((a.K + BwdShape<BITS>::CB - 1) / BwdShape<BITS>::CB, slices);
+    const int slices = m.slice_end[m.count - 1];
+    int max_rows = 0;
+    for (int i = 0; i < m.count; ++i) max_rows = m.p[i].rows_per_slice > max_rows ? m.p[i].rows_per_slice : max_rows;
+    const dim3 grid((m.p[0].K + BwdShape<BITS>::CB - 1) / BwdShape<BITS>::CB, slices);
     // Two chunks per wave in flight (more would not fit the register file at eight waves); eight waves share out the
     // arithmetic of a slice, four are enough when the slice has no more than eight chunks.
-    if constexpr (BITS != 3) {      // 3-bit: 32 columns per lane, the accumulators need the four-wave register budget
-        if (a.rows_per_slice / 32 > 8) {
-            hipLaunchKernelGGL((gemv_bwd_kernel<BITS, BF16, 8, 2>), grid, dim3(512), 0, s, a);
+    bool eight = false;
+    if constexpr (BITS != 3) eight = max_rows / 32 > 8;   // 3-bit: 32 columns per lane, the accumulators need the four-wave register budget
+    if (m.count == 1) {
+        if constexpr (BITS != 3) {
+            if (eight) {
+                hipLaunchKernelGGL((gemv_bwd_kernel<BITS, BF16, 8, 2>), grid, dim3(512), 0, s, m.p[0]);
+                return;
+            }
+        }
+        hipLaunchKernelGGL((gemv_bwd_kernel<BITS, BF16, 4, 2>), grid, dim3(256), 0, s, m.p[0]);
+        return;
+    }
+    if constexpr (BITS != 3) {
+        if (eight) {
+            hipLaunchKernelGGL((gemv_bwd_siblings_kernel<BITS, BF16, 8, 2>), grid, dim3(512), 0, s, m);
             return;
         }
     }
-    hipLaunchKernelGGL((gemv_bwd_kernel<BITS, BF16, 4, 2>), grid, dim3(256), 0, s, a);
+    hipLaunchKernelGGL((gemv_bwd_siblings_kernel<BITS, BF16, 4, 2>), grid, dim3(256), 0, s, m);
 }
 
 int bwd_cb(int bits) { return bits == 3 ? BwdShape<3>::CB : (bits == 2 ? BwdShape<2>::CB : (bits == 4 ? BwdShape<4>::CB : BwdShape<8>::CB)); }
@@ -878,6 +1072,36 @@ int gemv_bwd_slices(int N, int K, int bits)
     const int max_slices = (N + 127) / 128;              // at least four 32-row chunks per workgroup
     if (slices > max_slices) slices = max_slices;
     return slices < 1 ? 1 : slices;
+}
+
+int gemv_bwd_slices_siblings(int count, const int *N, int K, int bits, int *slices)
+{
+    if (count == 1) {
+        slices[0] = gemv_bwd_slices(N[0], K, bits);
+        return slices[0];
+    }
+    const int colblocks = (K + bwd_cb(bits) - 1) / bwd_cb(bits);
+    const int target = (256 + colblocks - 1) / colblocks;
+    long rows = 0;
+    for (int i = 0; i < count; ++i) rows += N[i];
+    int total = 0;
+    for (int i = 0; i < count; ++i) {       // the launch's slices are shared out in proportion to the rows
+        int sl = (int)(((long)target * N[i] + rows / 2) / rows);
+        const int max_slices = (N[i] + 127) / 128;
+        if (sl > max_slices) sl = max_slices;
+        if (sl < 1) sl = 1;
+        slices[i] = sl;
+        total += sl;
+    }
+    while (total > target) {                // rounding must not push the launch into a second round of workgroups
+        int big = 0;
+        for (int i = 1; i < count; ++i)
+            if ((long)slices[i] * N[big] > (long)slices[big] * N[i] || (slices[big] == 1 && slices[i] > 1)) big = i;
+        if (slices[big] == 1) break;        // one slice each is the least there is
+        --slices[big];
+        --total;
+    }
+    return total;
 }
 
 #define QLORA_BITS_DTYPE(FN, ...)                              \
@@ -901,34 +1125,92 @@ int gemv_bwd_slices(int N, int K, int bits)
 
 bool fwd_small_computes_t(int rank) { return rank > 0 && rank <= 32; }
 
-void launch_fwd_small(const Problem &p, const void *x, const uint32_t *packed, const void *scales, const uint8_t *zeros,
-                      const void *A, const void *B, const void *t_in, void *t_out, void *y, hipStream_t s)
+void launch_fwd_small(const Problem &p, int count, const void *x, const uint32_t *const *packed,
+                      const void *const *scales, const uint8_t *const *zeros, const void *const *A,
+                      const void *const *B, const void *const *t_in, void *const *t_out, void *const *y, const int *N,
+                      hipStream_t s)
 {
     const bool fused = fwd_small_computes_t(p.r);
-    const FwdArgs a{(const uint16_t *)x, packed, (const uint16_t *)scales, zeros, (const uint16_t *)A,
-                    (const uint16_t *)B, fused ? nullptr : (const uint16_t *)t_in, (uint16_t *)y,
-                    fused ? (uint16_t *)t_out : nullptr, p.M, p.N, p.K, p.r, p.K / p.G, p.sc, group_magic(p.G)};
+    FwdMulti m{};
+    m.count = count;
+    for (int i = 0; i < count; ++i)
+        m.p[i] = FwdArgs{(const uint16_t *)x,
+                         packed[i],
+                         (const uint16_t *)scales[i],
+                         zeros[i],
+                         (const uint16_t *)(A ? A[i] : nullptr),
+                         (const uint16_t *)(B ? B[i] : nullptr),
+                         fused ? nullptr : (const uint16_t *)(t_in ? t_in[i] : nullptr),
+                         (uint16_t *)y[i],
+                         fused ? (uint16_t *)(t_out ? t_out[i] : nullptr) : nullptr,
+                         p.M,
+                         N[i],
+                         p.K,
+                         p.r,
+                         p.K / p.G,
+                         p.sc,
+                         group_magic(p.G)};
     const int rg = fused ? (p.r + 15) / 16 : 0;
-    QLORA_BITS_DTYPE(launch_fwd_mb, a, rg, s);
+    QLORA_BITS_DTYPE(launch_fwd_mb, m, rg, s);
 }
 
-void launch_bwd_small(const Problem &p, const void *dy, const void *x, const uint32_t *packed, const void *scales,
-                      const uint8_t *zeros, const void *A, const void *B, const void *t, void *dx, float *dA, float *dB,
-                      float *partial, float *upartial, hipStream_t s)
+void launch_bwd_small(const Problem &p, int count, const void *const *dy, const void *x,
+                      const uint32_t *const *packed, const void *const *scales, const uint8_t *const *zeros,
+                      const void *const *A, const void *const *B, const void *const *t, void *dx, float *const *dA,
+                      float *const *dB, const int *N, float *partial, float *upartial, hipStream_t s)
 {
-    const int slices = gemv_bwd_slices(p.N, p.K, p.bits);
-    const int rows_per_slice = ((p.N + slices - 1) / slices + 31) / 32 * 32;
-    const BwdArgs a{(const uint16_t *)dy, packed, (const uint16_t *)scales, zeros, (const uint16_t *)B, partial,
-                    upartial, p.M, p.N, p.K, p.r, p.K / p.G, rows_per_slice, group_magic(p.G)};
-    QLORA_BITS_DTYPE(launch_bwd_bits, a, slices, s);
-    const int xb = (int)(((long)p.M * p.K + 255) / 256);
-    const int ab = (int)(((long)p.r * p.K + 255) / 256), bb = (int)(((long)p.r * p.N + 255) / 256);
-    const FinishArgs f{partial, upartial, (const uint16_t *)A, (const uint16_t *)x, (const uint16_t *)dy,
-                       (const uint16_t *)t, (uint16_t *)dx, dA, dB, p.M, p.N, p.K, p.r, slices, xb, ab, p.sc};
+    int slices[MAX_SIBLINGS];
+    const int total = gemv_bwd_slices_siblings(count, N, p.K, p.bits, slices);
+    BwdMulti m{};
+    m.count = count;
+    int end = 0;
+    for (int i = 0; i < count; ++i) {
+        const int rows_per_slice = ((N[i] + slices[i] - 1) / slices[i] + 31) / 32 * 32;
+        m.p[i] = BwdArgs{(const uint16_t *)dy[i], packed[i], (const uint16_t *)scales[i], zeros[i],
+                         (const uint16_t *)(B ? B[i] : nullptr), partial, upartial, p.M, N[i], p.K, p.r, p.K / p.G,
+                         rows_per_slice, group_magic(p.G)};
+        end += slices[i];
+        m.slice_end[i] = end;
+    }
+    QLORA_BITS_DTYPE(launch_bwd_bits, m, s);
+    const int xb = (int)(((long)p.M * p.K + 255) / 256), ab = (int)(((long)p.r * p.K + 255) / 256);
+    if (count == 1) {
+        const int bb = (int)(((long)p.r * N[0] + 255) / 256);
+        const FinishArgs f{partial, upartial, (const uint16_t *)(A ? A[0] : nullptr), (const uint16_t *)x,
+                           (const uint16_t *)dy[0], (const uint16_t *)(t ? t[0] : nullptr), (uint16_t *)dx,
+                           dA ? dA[0] : nullptr, dB ? dB[0] : nullptr, p.M, N[0], p.K, p.r, total, xb, ab, p.sc};
+        if (p.bf16)
+            hipLaunchKernelGGL((gemv_bwd_finish_kernel<true>), dim3(xb + ab + bb), dim3(256), 0, s, f);
+        else
+            hipLaunchKernelGGL((gemv_bwd_finish_kernel<false>), dim3(xb + ab + bb), dim3(256), 0, s, f);
+        return;
+    }
+    FinishMulti f{};
+    f.partial = partial;
+    f.upartial = upartial;
+    f.x = (const uint16_t *)x;
+    f.dx = (uint16_t *)dx;
+    f.M = p.M;
+    f.K = p.K;
+    f.r = p.r;
+    f.slices = total;
+    f.xb = xb;
+    f.ab = ab;
+    f.count = count;
+    f.sc = p.sc;
+    int bb_end = 0, sb = 0;
+    for (int i = 0; i < count; ++i) {
+        bb_end += (int)(((long)p.r * N[i] + 255) / 256);
+        f.p[i] = FinishProj{(const uint16_t *)(A ? A[i] : nullptr), (const uint16_t *)dy[i],
+                            (const uint16_t *)(t ? t[i] : nullptr), dA ? dA[i] : nullptr, dB ? dB[i] : nullptr,
+                            N[i], sb, sb + slices[i], bb_end};
+        sb += slices[i];
+    }
+    const int blocks = xb + count * ab + bb_end;
     if (p.bf16)
-        hipLaunchKernelGGL((gemv_bwd_finish_kernel<true>), dim3(xb + ab + bb), dim3(256), 0, s, f);
+        hipLaunchKernelGGL((gemv_bwd_finish_siblings_kernel<true>), dim3(blocks), dim3(256), 0, s, f);
     else
-        hipLaunchKernelGGL((gemv_bwd_finish_kernel<false>), dim3(xb + ab + bb), dim3(256), 0, s, f);
+        hipLaunchKernelGGL((gemv_bwd_finish_siblings_kernel<false>), dim3(blocks), dim3(256), 0, s, f);
 }
 
 }  // namespace qlora

@@ -41,13 +41,22 @@ constexpr int SMALL_M_FWD_MAX = 64;   // forward kernel handles up to four 16-ro
 constexpr int SMALL_M_BWD_MAX = 16;   // backward kernel keeps one 16-row token block
 int gemv_bwd_slices(int N, int K, int bits);   // row slices of the backward kernel
 bool fwd_small_computes_t(int rank);           // true: the forward kernel forms t = x A^T itself
-// y (and t_out, if not NULL and the kernel forms t) from one launch; t_in is used when the kernel does not form t
-void launch_fwd_small(const Problem &p, const void *x, const uint32_t *packed, const void *scales,
-                      const uint8_t *zeros, const void *A, const void *B, const void *t_in, void *t_out, void *y,
+constexpr int MAX_SIBLINGS = 4;                // projections that read the same x, served by one launch
+// `count` sibling projections (same x, M, K, code width, grouping, rank; own weights, adapters, N and outputs):
+// y[i] (and t_out[i], if not NULL and the kernel forms t) from one launch up to 16 token rows, one launch each above;
+// t_in[i] is used when the kernel does not form t.  The arrays are host arrays of `count` device pointers.
+void launch_fwd_small(const Problem &p, int count, const void *x, const uint32_t *const *packed,
+                      const void *const *scales, const uint8_t *const *zeros, const void *const *A,
+                      const void *const *B, const void *const *t_in, void *const *t_out, void *const *y, const int *N,
                       hipStream_t s);
-// dx, dA, dB from two launches; partial holds slices*M*K floats, upartial slices*1024 floats; t may be NULL if r == 0
-void launch_bwd_small(const Problem &p, const void *dy, const void *x, const uint32_t *packed, const void *scales,
-                      const uint8_t *zeros, const void *A, const void *B, const void *t, void *dx, float *dA, float *dB,
-                      float *partial, float *upartial, hipStream_t s);
+// Row slices of the backward kernel for `count` sibling projections launched together: slices[i] for each, the
+// total returned (count == 1: gemv_bwd_slices).
+int gemv_bwd_slices_siblings(int count, const int *N, int K, int bits, int *slices);
+// dx (the sum over the siblings), dA[i], dB[i] from two launches; partial holds total_slices*M*K floats, upartial
+// total_slices*1024 floats; t may be NULL if r == 0.  The arrays are host arrays of `count` device pointers.
+void launch_bwd_small(const Problem &p, int count, const void *const *dy, const void *x,
+                      const uint32_t *const *packed, const void *const *scales, const uint8_t *const *zeros,
+                      const void *const *A, const void *const *B, const void *const *t, void *dx, float *const *dA,
+                      float *const *dB, const int *N, float *partial, float *upartial, hipStream_t s);
 
 }  // namespace qlora

@@ -92,3 +92,52 @@ class DeviceLayer:
 
     def host_dB(self) -> np.ndarray:
         return self.dB.cpu().numpy()
+
+
+class DeviceSiblings:
+    """Several projections that read the same x (q/k/v, gate/up), called together through the sibling entry points.
+
+    Built from DeviceLayer objects of equal M, K, bits, group size, rank, alpha and dtype; the first one's x is the
+    shared input.  dx receives the sum of the projections' dX.
+    """
+
+    def __init__(self, layers):
+        c0 = layers[0].cfg
+        for l in layers[1:]:
+            c = l.cfg
+            if (c.M, c.K, c.bits, c.group_size, c.rank, c.alpha, c.dtype) != (c0.M, c0.K, c0.bits, c0.group_size,
+                                                                              c0.rank, c0.alpha, c0.dtype):
+                raise ValueError("sibling projections must share everything but N")
+        self.layers = list(layers)
+        self.cfg = c0
+        self.N = [l.cfg.N for l in layers]
+        self.x = layers[0].x
+        self.dx = torch.empty((c0.M, c0.K), dtype=torch.int16, device=layers[0].device)
+        nbytes = ql.qlora_siblings_workspace_bytes(self.N, c0.M, c0.K, c0.bits, c0.group_size, c0.rank)
+        if nbytes == 0:
+            raise ValueError(f"shapes not accepted by the sibling entry points: {self.N}, {c0}")
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=layers[0].device)
+
+    def _each(self, name):
+        return [getattr(l, name) for l in self.layers]
+
+    def forward(self, save_t: bool = True, stream=None):
+        c = self.cfg
+        ql.qlora_linear_fwd_siblings(self.x, self._each("packed"), self._each("scales"), self._each("zeros"),
+                                     self._each("A") if c.rank else None, self._each("B") if c.rank else None,
+                                     self._each("y"), self._each("t") if (save_t and c.rank) else None, self.N,
+                                     c.M, c.K, c.bits, c.group_size, c.rank, c.alpha, self.layers[0].dtype_flag,
+                                     self.workspace, stream=stream)
+
+    def backward(self, use_saved_t: bool = True, stream=None):
+        c = self.cfg
+        ql.qlora_linear_bwd_siblings(self._each("dy"), self.x, self._each("packed"), self._each("scales"),
+                                     self._each("zeros"), self._each("A") if c.rank else None,
+                                     self._each("B") if c.rank else None,
+                                     self._each("t") if (use_saved_t and c.rank) else None, self.dx,
+                                     self._each("dA") if c.rank else None, self._each("dB") if c.rank else None,
+                                     self.N, c.M, c.K, c.bits, c.group_size, c.rank, c.alpha,
+                                     self.layers[0].dtype_flag, self.workspace, stream=stream)
+
+    def host_dx(self) -> np.ndarray:
+        return _host16(self.dx)

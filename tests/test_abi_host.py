@@ -115,6 +115,57 @@ def test_fwd_bwd_specific_null_checks():
     assert _bwd(dA=ODD) == E["QLORA_E_ALIGN"]
 
 
+def _sib(which, count=2, N=(64, 40), M=4, K=128, bits=4, G=64, rank=8, dtype=0, ws=FAKE, ws_bytes=1 << 30, **over):
+    """A sibling call with fake pointers; `over` replaces one argument (a list, a pointer or None)."""
+    a = dict(x=FAKE, packed=[FAKE] * count, scales=[FAKE] * count, zeros=[FAKE] * count, A=[FAKE] * count,
+             B=[FAKE] * count, y=[FAKE] * count, t=None, dy=[FAKE] * count, dx=FAKE, dA=[FAKE] * count,
+             dB=[FAKE] * count)
+    a.update(over)
+    N = list(N)[:count] if len(N) >= count else list(N) + [64] * (count - len(N))
+    if which == "fwd":
+        return ql.qlora_linear_fwd_siblings(a["x"], a["packed"], a["scales"], a["zeros"], a["A"], a["B"], a["y"],
+                                            a["t"], N, M, K, bits, G, rank, 16.0, dtype, ws, ws_bytes, stream=0,
+                                            check=False)
+    return ql.qlora_linear_bwd_siblings(a["dy"], a["x"], a["packed"], a["scales"], a["zeros"], a["A"], a["B"], a["t"],
+                                        a["dx"], a["dA"], a["dB"], N, M, K, bits, G, rank, 16.0, dtype, ws, ws_bytes,
+                                        stream=0, check=False)
+
+
+@pytest.mark.parametrize("which", ["fwd", "bwd"])
+def test_sibling_argument_errors(which):
+    assert _sib(which, M=17) == E["QLORA_E_SHAPE"]                 # only the weight-streaming regime
+    assert _sib(which, count=5, N=(64,) * 5) == E["QLORA_E_SHAPE"]
+    assert _sib(which, N=(64, 44)) == E["QLORA_E_SHAPE"]           # N % 8
+    assert _sib(which, bits=5) == E["QLORA_E_BITS"]
+    assert _sib(which, G=48) == E["QLORA_E_GROUP"]
+    assert _sib(which, rank=12) == E["QLORA_E_RANK"]
+    assert _sib(which, dtype=2) == E["QLORA_E_DTYPE"]
+    assert _sib(which, packed=[FAKE, None]) == E["QLORA_E_NULL"]
+    assert _sib(which, B=[None, FAKE]) == E["QLORA_E_NULL"]
+    assert _sib(which, scales=None) == E["QLORA_E_NULL"]
+    assert _sib(which, zeros=[FAKE, ODD]) == E["QLORA_E_ALIGN"]
+    assert _sib(which, x=None) == E["QLORA_E_NULL"]
+    need = ql.qlora_siblings_workspace_bytes([64, 40], 4, 128, 4, 64, 8)
+    assert need > 0
+    assert _sib(which, ws_bytes=need - 1) == E["QLORA_E_WORKSPACE"]
+    assert _sib(which, ws=None) == E["QLORA_E_WORKSPACE"]
+    assert _sib(which, rank=0, A=None, B=None, dA=None, dB=None, ws_bytes=0) == E["QLORA_E_WORKSPACE"]
+    if which == "bwd":
+        assert _sib(which, dA=[FAKE, None]) == E["QLORA_E_NULL"]
+        assert _sib(which, dx=None) == E["QLORA_E_NULL"]
+        assert _sib(which, dy=[None, FAKE]) == E["QLORA_E_NULL"]
+    else:
+        assert _sib(which, y=[FAKE, None]) == E["QLORA_E_NULL"]
+
+
+def test_sibling_workspace_bytes():
+    assert ql.qlora_siblings_workspace_bytes([64, 40], 17, 128, 4, 64, 8) == 0
+    assert ql.qlora_siblings_workspace_bytes([64, 44], 4, 128, 4, 64, 8) == 0
+    one = ql.qlora_siblings_workspace_bytes([4096], 16, 4096, 4, 128, 8)
+    three = ql.qlora_siblings_workspace_bytes([4096] * 3, 16, 4096, 4, 128, 8)
+    assert 0 < one < three
+
+
 def test_pack_unpack_argument_errors():
     for fn in (ql.qlora_pack, ql.qlora_unpack):
         assert fn(FAKE, FAKE, 8, 64, 5, stream=0, check=False) == E["QLORA_E_BITS"]

@@ -291,6 +291,25 @@ def test_backward_finite_differences():
             assert abs(fd - grad[idx]) <= 1e-8 * max(1.0, abs(fd)), (name, idx, fd, grad[idx])
 
 
+def test_sibling_projections_dx_is_the_sum_of_their_dx():
+    # Projections that read the same x (q/k/v, gate/up): the gradient of L = sum_i <dY_i, y_i(x)> w.r.t. x is what the
+    # sibling entry points must return.  Central differences on the oracle's forward (L is linear in x) pin the rule
+    # "dX = sum of the per-layer dX" that the GPU parity test of those entry points relies on.
+    ps = [_small_problem(610 + i, M=4, N=n, K=64, r=4, b=b, G=32) for i, (n, b) in enumerate(((9, 3), (16, 4), (7, 2)))]
+    x = ps[0]["x"]
+    L = lambda xx: sum(float(np.sum(p["dy"] * oracle.forward(xx, p["Wd"], p["A"], p["B"], p["alpha"])[0])) for p in ps)
+    dx = sum(oracle.backward_dx(p["dy"], p["Wd"], p["A"], p["B"], p["alpha"]) for p in ps)
+    h = 1e-3
+    rng = np.random.RandomState(1)
+    for _ in range(16):
+        idx = tuple(rng.randint(0, s) for s in x.shape)
+        xp, xm = x.copy(), x.copy()
+        xp[idx] += h
+        xm[idx] -= h
+        fd = (L(xp) - L(xm)) / (2 * h)
+        assert abs(fd - dx[idx]) <= 1e-8 * max(1.0, abs(fd)), (idx, fd, dx[idx])
+
+
 def test_backward_adjoint_identities():
     p = _small_problem(700, M=11, N=24, K=128, r=8, b=4, G=64)
     fwd = lambda x, A, B: oracle.forward(x, p["Wd"], A, B, p["alpha"])[0]
