@@ -188,6 +188,62 @@ def run_small_m(M: int = 16, iters: int = 5):
     return results
 
 
+def run_lrec_loss(M: int = 2048, V: int = 32000, iters: int = 20):
+    """The LREC objective + gradient over M token rows of a LLaMA vocabulary (widened row of the scope table).
+
+    HBM-bound: both logit rows are read once and the gradient written once, 6 bytes per logit.  Four input sets are
+    rotated so that no launch finds its rows in the 256 MB last-level cache (a set is 262 MB).
+    """
+    import numpy as np
+    import torch
+    from paper_2306_08162_amd import binding as ql
+    from paper_2306_08162_amd import workloads as wl
+    from paper_2306_08162_amd.hiprt import Event
+    dev = torch.device("cuda:0")
+    rows = 64                                   # seeded rows generated on the host, tiled over the M tokens
+    zt = wl.normal(0x10551, rows * V).reshape(rows, V) * 4.0
+    zs = 0.7 * zt + wl.normal(0x10552, rows * V).reshape(rows, V) * 1.2
+    up = lambda a: torch.from_numpy(wl.to_bits(a.ravel(), "f16").view(np.int16).reshape(rows, V)).to(dev)
+    sets = []
+    for i in range(4):
+        sets.append((up(zs).roll(i, 0).repeat(M // rows, 1).contiguous(), up(zt).roll(i, 0).repeat(M // rows, 1).contiguous()))
+    labels = torch.from_numpy((wl.splitmix64(0x10553, 0, M) % np.uint64(V)).astype(np.int32)).to(dev)
+    kl = torch.empty(M, dtype=torch.float32, device=dev)
+    ce = torch.empty_like(kl)
+    mean = torch.empty(1, dtype=torch.float32, device=dev)
+    grad = torch.empty((M, V), dtype=torch.int16, device=dev)
+    ws = torch.empty(ql.qlora_lrec_workspace_bytes(M), dtype=torch.uint8, device=dev)
+    call = lambda i: ql.qlora_lrec_loss(sets[i % 4][0], sets[i % 4][1], labels, 1.0, 120.0, kl, ce, mean, grad, M, V,
+                                        ql.QLORA_F16, ws)
+    for i in range(4):
+        call(i)
+    torch.cuda.synchronize()
+    stream = torch.cuda.current_stream().cuda_stream or None
+    e0, e1 = Event(), Event()
+    e0.record(stream)
+    for i in range(iters):
+        call(i)
+    e1.record(stream)
+    e1.synchronize()
+    us = e0.elapsed_ms(e1) * 1e3 / iters
+    nbytes = 6 * M * V
+    # for scale: what a plain device-to-device copy of the same volume reaches on this box (reads + writes counted)
+    src = grad.view(-1)
+    dst = torch.empty_like(src)
+    for _ in range(2):
+        dst.copy_(src)
+    e0.record(stream)
+    for _ in range(10):
+        dst.copy_(src)
+    e1.record(stream)
+    e1.synchronize()
+    copy_gbps = 2 * src.numel() * 2 / (e0.elapsed_ms(e1) * 1e-3 / 10) * 1e-9
+    return {"workload": f"M={M} tokens x V={V} logits, fp16, lambda_kl=1 lambda_ce=120", "us_per_call": round(us, 2),
+            "algorithmic_bytes": nbytes, "GBps": round(nbytes / us * 1e-3, 1),
+            "frac_of_hbm_peak": round(nbytes / us * 1e-3 / PEAK_HBM_GBPS, 4),
+            "plain_copy_GBps_same_box": round(copy_gbps, 1), "loss_mean": float(mean.cpu()[0])}
+
+
 def run_cpu_baseline(inp, max_rows: int):
     """The fp64 oracle as it stands, on the host cores: forward + backward on the first `max_rows` token rows."""
     import oracle
@@ -261,6 +317,7 @@ def main() -> int:
         del layer
         result["small_m"] = {"M": 16, "timing": "HIP-graph replays over a >1 GB pool of distinct weight sets",
                              **run_small_m(16)}
+        result["lrec_loss"] = run_lrec_loss()
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = run_cpu_baseline(inp, args.cpu_rows)
     print(json.dumps(result))

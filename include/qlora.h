@@ -155,6 +155,25 @@ int qlora_linear_bwd_siblings(int count, const void *const *dy, const void *x, c
                               void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The LREC objective (Sec. 3.2 "Optimization", Eq. 1 and 2) and its gradient with respect to the student logits:
+ *   per token  y_hat = softmax(student_logits[m,:]),  y = softmax(teacher_logits[m,:])
+ *              KL = sum_i y_hat_i log(y_hat_i / y_i)          (student first, as Eq. 1 is written)
+ *              CE = -log y_hat[labels[m]]                      (next-token cross entropy; no CE term where the label
+ *                                                               is negative or not below V)
+ *   *loss_mean = mean over the M tokens of lambda_kl*KL + lambda_ce*CE      (Eq. 2; factors of Appendix C)
+ *   dlogits    = d loss_mean / d student_logits, in `dtype`
+ * student_logits, teacher_logits, dlogits: [M,V] of `dtype` (the teacher's are its cached logits); labels int32 [M];
+ * kl, ce: fp32 [M], each may be NULL; dlogits may be NULL (objective only); loss_mean: fp32 [1].  V % 8 == 0,
+ * M*V below 2^40.  workspace: qlora_lrec_workspace_bytes(M) bytes.  Sums run in a fixed order: results are
+ * bitwise reproducible.  Validation and errors as for the other calls.
+ */
+size_t qlora_lrec_workspace_bytes(int M);
+
+int qlora_lrec_loss(const void *student_logits, const void *teacher_logits, const int32_t *labels,
+                    float lambda_kl, float lambda_ce, float *kl, float *ce, float *loss_mean, void *dlogits,
+                    int M, int V, int dtype, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Instrumentation for benchmarks (not part of the layer, not thread-safe): while a pair of hipEvent_t
  * handles is set, every qlora_linear_fwd / qlora_linear_bwd call records ev_before on its stream right
  * before its GEMM kernel (the fused dequantise + MFMA kernel that dominates the pass) and ev_after right

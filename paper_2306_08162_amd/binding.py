@@ -19,7 +19,7 @@ STATUS_NAMES = ["QLORA_OK", "QLORA_E_NULL", "QLORA_E_BITS", "QLORA_E_SHAPE", "QL
                 "QLORA_E_DTYPE", "QLORA_E_ALIGN", "QLORA_E_WORKSPACE", "QLORA_E_HIP"]
 EXPORTS = ["qlora_status_string", "qlora_packed_words", "qlora_workspace_bytes", "qlora_pack", "qlora_unpack",
            "qlora_linear_fwd", "qlora_linear_bwd", "qlora_siblings_workspace_bytes", "qlora_linear_fwd_siblings",
-           "qlora_linear_bwd_siblings", "qlora_profile_gemm"]
+           "qlora_linear_bwd_siblings", "qlora_lrec_workspace_bytes", "qlora_lrec_loss", "qlora_profile_gemm"]
 MAX_SIBLINGS, SIBLINGS_MAX_M = 4, 16
 
 _lib = None
@@ -66,6 +66,10 @@ def load() -> ctypes.CDLL:
     lib.qlora_linear_fwd_siblings.argtypes = [c_int] + [vp] * 9 + [c_int] * 5 + [f32, c_int, vp, c_sz, vp]
     lib.qlora_linear_bwd_siblings.restype = c_int
     lib.qlora_linear_bwd_siblings.argtypes = [c_int] + [vp] * 12 + [c_int] * 5 + [f32, c_int, vp, c_sz, vp]
+    lib.qlora_lrec_workspace_bytes.restype = c_sz
+    lib.qlora_lrec_workspace_bytes.argtypes = [c_int]
+    lib.qlora_lrec_loss.restype = c_int
+    lib.qlora_lrec_loss.argtypes = [vp] * 3 + [f32, f32] + [vp] * 4 + [c_int] * 3 + [vp, c_sz, vp]
     _lib = lib
     return lib
 
@@ -197,4 +201,21 @@ def qlora_linear_bwd_siblings(dy, x, packed, scales, zeros, A, B, t_saved, dx, d
                                           _ptr(workspace), workspace_bytes, _stream(stream))
     if check and st != 0:
         raise QLoraError(st, "qlora_linear_bwd_siblings")
+    return st
+
+
+def qlora_lrec_workspace_bytes(M: int) -> int:
+    return int(load().qlora_lrec_workspace_bytes(M))
+
+
+def qlora_lrec_loss(student_logits, teacher_logits, labels, lambda_kl: float, lambda_ce: float, kl, ce, loss_mean,
+                    dlogits, M: int, V: int, dtype: int, workspace, workspace_bytes: Optional[int] = None,
+                    stream=None, check: bool = True) -> int:
+    if workspace_bytes is None:
+        workspace_bytes = _nbytes(workspace)
+    st = load().qlora_lrec_loss(_ptr(student_logits), _ptr(teacher_logits), _ptr(labels), float(lambda_kl),
+                                float(lambda_ce), _ptr(kl), _ptr(ce), _ptr(loss_mean), _ptr(dlogits), M, V, dtype,
+                                _ptr(workspace), workspace_bytes, _stream(stream))
+    if check and st != 0:
+        raise QLoraError(st, "qlora_lrec_loss")
     return st

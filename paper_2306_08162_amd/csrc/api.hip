@@ -349,4 +349,26 @@ int qlora_linear_bwd_siblings(int count, const void *const *dy, const void *x, c
     return hip_status();
 }
 
+size_t qlora_lrec_workspace_bytes(int M)
+{
+    return M < 1 ? 0 : round_up((size_t)M * sizeof(float));
+}
+
+int qlora_lrec_loss(const void *student_logits, const void *teacher_logits, const int32_t *labels, float lambda_kl,
+                    float lambda_ce, float *kl, float *ce, float *loss_mean, void *dlogits, int M, int V, int dtype,
+                    void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (M < 1 || V < 8 || V % 8 != 0 || (long long)M * V >= (1ll << 40)) return QLORA_E_SHAPE;
+    if (dtype != QLORA_F16 && dtype != QLORA_BF16) return QLORA_E_DTYPE;
+    if (!student_logits || !teacher_logits || !labels || !loss_mean) return QLORA_E_NULL;
+    if (misaligned(student_logits) || misaligned(teacher_logits) || misaligned(dlogits) || misaligned(workspace) ||
+        (reinterpret_cast<uintptr_t>(labels) & 3u) || (reinterpret_cast<uintptr_t>(kl) & 3u) ||
+        (reinterpret_cast<uintptr_t>(ce) & 3u) || (reinterpret_cast<uintptr_t>(loss_mean) & 3u))
+        return QLORA_E_ALIGN;
+    if (!workspace || workspace_bytes < qlora_lrec_workspace_bytes(M)) return QLORA_E_WORKSPACE;
+    launch_lrec_loss(student_logits, teacher_logits, labels, lambda_kl, lambda_ce, kl, ce, (float *)workspace,
+                     loss_mean, dlogits, M, V, dtype == QLORA_BF16, (hipStream_t)stream);
+    return hip_status();
+}
+
 }  // extern "C"

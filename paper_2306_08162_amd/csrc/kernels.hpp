@@ -59,4 +59,10 @@ void launch_bwd_small(const Problem &p, int count, const void *const *dy, const 
                       const void *const *A, const void *const *B, const void *const *t, void *dx, float *const *dA,
                       float *const *dB, const int *N, float *partial, float *upartial, hipStream_t s);
 
+// loss.hip -- the LREC objective (KL student || teacher + next-token CE, mean over tokens) and its gradient
+// kl, ce (per token) and grad may be NULL; tok receives lambda_kl*KL + lambda_ce*CE per token, loss_mean their mean
+void launch_lrec_loss(const void *student, const void *teacher, const int32_t *labels, float lambda_kl,
+                      float lambda_ce, float *kl, float *ce, float *tok, float *loss_mean, void *grad, int M, int V,
+                      bool bf16, hipStream_t s);
+
 }  // namespace qlora

@@ -166,6 +166,25 @@ def test_sibling_workspace_bytes():
     assert 0 < one < three
 
 
+def test_lrec_loss_argument_errors():
+    def call(M=4, V=64, dtype=0, zs=FAKE, zt=FAKE, lab=FAKE, kl=FAKE, ce=FAKE, mean=FAKE, grad=FAKE, ws=FAKE, wsb=1 << 20):
+        return ql.qlora_lrec_loss(zs, zt, lab, 1.0, 120.0, kl, ce, mean, grad, M, V, dtype, ws, wsb, stream=0, check=False)
+    assert call(M=0) == E["QLORA_E_SHAPE"]
+    assert call(V=60) == E["QLORA_E_SHAPE"]             # V % 8
+    assert call(V=0) == E["QLORA_E_SHAPE"]
+    assert call(dtype=3) == E["QLORA_E_DTYPE"]
+    assert call(zs=None) == E["QLORA_E_NULL"]
+    assert call(zt=None) == E["QLORA_E_NULL"]
+    assert call(lab=None) == E["QLORA_E_NULL"]
+    assert call(mean=None) == E["QLORA_E_NULL"]
+    assert call(zs=ODD) == E["QLORA_E_ALIGN"]
+    assert call(grad=ODD) == E["QLORA_E_ALIGN"]
+    assert call(kl=0x10002) == E["QLORA_E_ALIGN"]
+    assert call(ws=None) == E["QLORA_E_WORKSPACE"]
+    assert call(wsb=ql.qlora_lrec_workspace_bytes(4) - 1) == E["QLORA_E_WORKSPACE"]
+    assert ql.qlora_lrec_workspace_bytes(0) == 0 and ql.qlora_lrec_workspace_bytes(2048) >= 2048 * 4
+
+
 def test_pack_unpack_argument_errors():
     for fn in (ql.qlora_pack, ql.qlora_unpack):
         assert fn(FAKE, FAKE, 8, 64, 5, stream=0, check=False) == E["QLORA_E_BITS"]
