@@ -7,9 +7,14 @@
 //   gradient    d objective / d z_k = (lambda_KL y_hat_k (d_k - KL) + lambda_CE (y_hat_k - [k = label])) / M,
 //               d_k = log y_hat_k - log y_k
 //
-// The work is a reduction over a 32000-wide vocabulary per token: three sweeps over the row (log-sum-exp of both
-// rows, KL, gradient).  It is bound by HBM: both rows are read once (a workgroup keeps its token's two rows in
-// registers, 16-bit, for all three sweeps) and the gradient is written once, 6 bytes per logit in all.
+// The work is a reduction over a 32000-wide vocabulary per token and is bound by HBM: both rows are read once and
+// the gradient is written once, 6 bytes per logit in all.  Two sweeps over registers do it.  With e_i =
+// exp(zs_i - m), m any upper bound of the row, and S = sum e_i:  y_hat_i = e_i / S  and
+//     KL = sum_i y_hat_i ((zs_i - zt_i) - delta) = Q / S - delta,   Q = sum_i e_i (zs_i - zt_i),
+//     delta = lse(zs) - lse(zt),
+// so one sweep with one exponential per logit yields (m, S, Q) of the student row and (m, S) of the teacher row,
+// merged over the threads like any running softmax; the second sweep forms the gradient from e_i and zs_i - zt_i,
+// which the first one left behind in the registers the logits came in (as fp16).
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -34,21 +39,23 @@ struct LossArgs {
     float lkl, lce;
 };
 
-// (max, sum of exp(v - max)) pairs are merged; the neutral element is (-inf, 0)
-struct MaxSum {
-    float m, s;
+// Running softmax state: m an upper bound of the values seen, s = sum exp(v - m), q = sum exp(v - m) w for a weight
+// w per value (the student row carries w = zs - zt; the teacher row carries none).  The neutral element is (-inf, 0, 0).
+struct SoftState {
+    float m, s, q;
 };
-__device__ __forceinline__ MaxSum merge(MaxSum a, MaxSum b)
+__device__ __forceinline__ SoftState merge(SoftState a, SoftState b)
 {
     const float m = fmaxf(a.m, b.m);
-    if (m == -INFINITY) return MaxSum{m, 0.f};
-    return MaxSum{m, a.s * fast_exp2((a.m - m) * LOG2E) + b.s * fast_exp2((b.m - m) * LOG2E)};
+    if (m == -INFINITY) return SoftState{m, 0.f, 0.f};
+    const float fa = fast_exp2((a.m - m) * LOG2E), fb = fast_exp2((b.m - m) * LOG2E);
+    return SoftState{m, a.s * fa + b.s * fb, a.q * fa + b.q * fb};
 }
-__device__ __forceinline__ MaxSum wave_merge(MaxSum v)
+__device__ __forceinline__ SoftState wave_merge(SoftState v)
 {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) {
-        MaxSum o{__shfl_xor(v.m, off, WAVE), __shfl_xor(v.s, off, WAVE)};
+        SoftState o{__shfl_xor(v.m, off, WAVE), __shfl_xor(v.s, off, WAVE), __shfl_xor(v.q, off, WAVE)};
         v = merge(v, o);
     }
     return v;
@@ -58,9 +65,8 @@ __device__ __forceinline__ MaxSum wave_merge(MaxSum v)
 template <bool BF16, int CH>
 __global__ __launch_bounds__(LT) void lrec_loss_kernel(const LossArgs a)
 {
-    __shared__ MaxSum red_ms[2][LT / 64];
-    __shared__ float red_f[LT / 64];
-    __shared__ float bc[4];              // lse of the student row, lse of the teacher row, KL
+    __shared__ SoftState red[2][LT / 64];
+    __shared__ float bc[4];              // max and sum of the student row, delta, KL
     const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int pieces = a.V / 8;
     const uint16_t *zs = a.zs + (long)row * a.V, *zt = a.zt + (long)row * a.V;
@@ -95,8 +101,11 @@ __global__ __launch_bounds__(LT) void lrec_loss_kernel(const LossArgs a)
             return (float)__builtin_bit_cast(half8_t, v)[e];
     };
 
-    // sweep 1: log-sum-exp of both rows.  The thread's own maxima first (fp16: packed, exact), so that every logit
-    // costs one exponential and the (max, sum) pairs are merged once per thread, not once per piece.
+    // sweep 1.  The thread's own maxima first (fp16: packed, exact), then one exponential per logit.  `one` is 1.0
+    // the compiler cannot see through: zs * one - zt then stays one mixed-precision fma on the two halves instead of
+    // two conversions and a subtraction.
+    float one = 1.f, zero = 0.f;
+    asm volatile("" : "+v"(one), "+v"(zero));
     float ls = -INFINITY, lt = -INFINITY;
     if constexpr (BF16) {
 #pragma unroll CH > 0 ? CH : 1
@@ -118,95 +127,80 @@ __global__ __launch_bounds__(LT) void lrec_loss_kernel(const LossArgs a)
             if (piece_of(i) >= pieces) break;
             u16x8_t s8, t8;
             get(i, s8, t8);
-            const u32x4_t sw = __builtin_bit_cast(u32x4_t, s8), tw = __builtin_bit_cast(u32x4_t, t8);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                hs = __builtin_elementwise_max(hs, __builtin_bit_cast(half2_t, sw[e]));
-                ht = __builtin_elementwise_max(ht, __builtin_bit_cast(half2_t, tw[e]));
-            }
+            // (written out pair by pair: a loop over the four 32-bit words, bit-cast one at a time, was compiled
+            // down to its first iteration by this toolchain)
+            const half8_t sh = __builtin_bit_cast(half8_t, s8), th = __builtin_bit_cast(half8_t, t8);
+            const half2_t s01 = {sh[0], sh[1]}, s23 = {sh[2], sh[3]}, s45 = {sh[4], sh[5]}, s67 = {sh[6], sh[7]};
+            const half2_t t01 = {th[0], th[1]}, t23 = {th[2], th[3]}, t45 = {th[4], th[5]}, t67 = {th[6], th[7]};
+            hs = __builtin_elementwise_max(hs, __builtin_elementwise_max(__builtin_elementwise_max(s01, s23),
+                                                                         __builtin_elementwise_max(s45, s67)));
+            ht = __builtin_elementwise_max(ht, __builtin_elementwise_max(__builtin_elementwise_max(t01, t23),
+                                                                         __builtin_elementwise_max(t45, t67)));
         }
         ls = fmaxf((float)hs[0], (float)hs[1]);
         lt = fmaxf((float)ht[0], (float)ht[1]);
     }
-    float ss = 0.f, st = 0.f;
-    {
-        const float os = -ls * LOG2E, ot = -lt * LOG2E;       // exp(v - max) = exp2(v log2e - max log2e)
-#pragma unroll CH > 0 ? CH : 1
-        for (int i = 0; i < my_pieces; ++i) {
-            if (piece_of(i) >= pieces) break;
-            u16x8_t s8, t8;
-            get(i, s8, t8);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                ss += fast_exp2(fmaf(val(s8, e), LOG2E, os));
-                st += fast_exp2(fmaf(val(t8, e), LOG2E, ot));
-            }
-        }
-    }
-    MaxSum ms = wave_merge(MaxSum{ls, ss}), mt = wave_merge(MaxSum{lt, st});
-    if (lane == 0) {
-        red_ms[0][wave] = ms;
-        red_ms[1][wave] = mt;
-    }
-    __syncthreads();
-    if (tid < 2) {
-        MaxSum v = red_ms[tid][0];
-#pragma unroll
-        for (int w = 1; w < LT / 64; ++w) v = merge(v, red_ms[tid][w]);
-        bc[tid] = v.m + __builtin_amdgcn_logf(v.s) * LN2;     // the hardware's log2
-    }
-    __syncthreads();
-    const float lse_s = bc[0], lse_t = bc[1];
-    const float delta = lse_s - lse_t;                        // d_i = log y_hat_i - log y_i = (zs_i - zt_i) - delta
-    const float off_s = -lse_s * LOG2E;                       // y_hat_i = exp2(zs_i log2e + off_s)
-
-    // sweep 2: KL = sum_i y_hat_i d_i = sum_i y_hat_i (zs_i - zt_i) - delta sum_i y_hat_i; the last sum is carried
-    // along (it is 1 up to rounding).  y_hat and zs - zt are kept, as fp16 pairs (2^-11 relative), for the gradient
-    // sweep: they take the registers of the piece they were computed from.  `one` is 1.0 the compiler cannot see through: zs * one - zt then stays one mixed-precision fma on the
-    // two halves instead of two conversions and a subtraction.
-    float one = 1.f, zero = 0.f;
-    asm volatile("" : "+v"(one), "+v"(zero));
-    float kl = 0.f, psum = 0.f;
+    float ss = 0.f, st = 0.f, qs = 0.f;
+    const float os = -ls * LOG2E, ot = -lt * LOG2E;           // exp(v - max) = exp2(v log2e - max log2e)
 #pragma unroll CH > 0 ? CH : 1
     for (int i = 0; i < my_pieces; ++i) {
         if (piece_of(i) >= pieces) break;
         u16x8_t s8, t8;
         get(i, s8, t8);
-        half8_t ph, dh;
+        half8_t eh, dh;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            const float pe = fast_exp2(fmaf(val(s8, e), LOG2E, off_s));
-            const float de = fmaf(val(s8, e), one, -val(t8, e));
-            kl = fmaf(pe, de, kl);
-            psum += pe;
-            ph[e] = (half_t)pe;
-            dh[e] = (half_t)de;
+            const float es = fast_exp2(fmaf(val(s8, e), LOG2E, os));
+            const float dz = fmaf(val(s8, e), one, -val(t8, e));
+            ss += es;
+            qs = fmaf(es, dz, qs);
+            st += fast_exp2(fmaf(val(t8, e), LOG2E, ot));
+            eh[e] = (half_t)es;
+            dh[e] = (half_t)dz;
         }
-        if constexpr (CH > 0) {
-            rs[i] = __builtin_bit_cast(u16x8_t, ph);
+        if constexpr (CH > 0) {       // e_i and zs_i - zt_i (2^-11 relative) take the place of the logits
+            rs[i] = __builtin_bit_cast(u16x8_t, eh);
             rt[i] = __builtin_bit_cast(u16x8_t, dh);
         }
     }
-    kl = wave_sum(fmaf(-delta, psum, kl));
-    if (lane == 0) red_f[wave] = kl;
+    const SoftState ws = wave_merge(SoftState{ls, ss, qs}), wt = wave_merge(SoftState{lt, st, 0.f});
+    if (lane == 0) {
+        red[0][wave] = ws;
+        red[1][wave] = wt;
+    }
     __syncthreads();
     const int label = a.labels[row];
     const bool has = label >= 0 && label < a.V;
     if (tid == 0) {
-        float v = 0.f;
+        SoftState vs = red[0][0], vt = red[1][0];
 #pragma unroll
-        for (int w = 0; w < LT / 64; ++w) v += red_f[w];
-        bc[2] = v;
+        for (int w = 1; w < LT / 64; ++w) {
+            vs = merge(vs, red[0][w]);
+            vt = merge(vt, red[1][w]);
+        }
+        const float lse_s = vs.m + __builtin_amdgcn_logf(vs.s) * LN2;      // the hardware's log2
+        const float lse_t = vt.m + __builtin_amdgcn_logf(vt.s) * LN2;
+        const float delta = lse_s - lse_t;
+        const float klv = vs.q / vs.s - delta;
         const float ce = has ? lse_s - cvt16<BF16>(zs[label]) : 0.f;
-        if (a.kl) a.kl[row] = v;
+        bc[0] = vs.m;
+        bc[1] = vs.s;
+        bc[2] = delta;
+        bc[3] = klv;
+        if (a.kl) a.kl[row] = klv;
         if (a.ce) a.ce[row] = ce;
-        a.tok[row] = a.lkl * v + a.lce * ce;
+        a.tok[row] = a.lkl * klv + a.lce * ce;
     }
     if (!a.grad) return;
     __syncthreads();
-    // sweep 3: the gradient row, g_i = y_hat_i (c1 (zs_i - zt_i) + c2) - [i = label] lce / M
+    // sweep 2: the gradient row, g_i = y_hat_i (c1 (zs_i - zt_i) + c2) - [i = label] lce / M, with
+    // y_hat_i = e_i phi, phi = exp(ls - m) / S the thread's share of the normalisation
+    const float row_m = bc[0], row_s = bc[1], delta = bc[2], klv = bc[3];
     const float inv_m = 1.f / (float)a.M, lce = has ? a.lce : 0.f;
-    const float c1 = a.lkl * inv_m, c2 = (lce - a.lkl * (bc[2] + delta)) * inv_m;
+    const float c1 = a.lkl * inv_m, c2 = (lce - a.lkl * (klv + delta)) * inv_m;
+    const float phi = fast_exp2((ls - row_m) * LOG2E) / row_s;
+    const float c1p = c1 * phi, c2p = c2 * phi;
+    const float off_s = -(row_m + __builtin_amdgcn_logf(row_s) * LN2) * LOG2E;   // y_hat_i = exp2(zs_i log2e + off_s)
     uint16_t *grow = a.grad + (long)row * a.V;
 #pragma unroll CH > 0 ? CH : 1
     for (int i = 0; i < my_pieces; ++i) {
@@ -219,7 +213,7 @@ __global__ __launch_bounds__(LT) void lrec_loss_kernel(const LossArgs a)
         for (int e = 0; e < 8; ++e) {
             if constexpr (CH > 0)
                 g[e] = fmaf((float)__builtin_bit_cast(half8_t, rs[i])[e],
-                            fmaf((float)__builtin_bit_cast(half8_t, rt[i])[e], c1, c2), zero);
+                            fmaf((float)__builtin_bit_cast(half8_t, rt[i])[e], c1p, c2p), zero);
             else
                 g[e] = fast_exp2(fmaf(val(s8, e), LOG2E, off_s)) * fmaf(fmaf(val(s8, e), one, -val(t8, e)), c1, c2);
         }
@@ -231,15 +225,12 @@ __global__ __launch_bounds__(LT) void lrec_loss_kernel(const LossArgs a)
     // stores to that address stay in order) computes it again in full and overwrites it
     if (has && ((label >> 3) % LT) == tid) {
         const float z = cvt16<BF16>(zs[label]), t = cvt16<BF16>(zt[label]);
-        float p, d;
-        if constexpr (CH > 0) {       // the values the sweep used: y_hat and zs - zt as the fp16 they were kept in
-            p = (float)(half_t)fast_exp2(fmaf(z, LOG2E, off_s));
-            d = (float)(half_t)(z - t);
-        } else {
-            p = fast_exp2(fmaf(z, LOG2E, off_s));
-            d = z - t;
-        }
-        grow[label] = to16<BF16>(fmaf(p, fmaf(d, c1, c2), zero) - lce * inv_m);
+        float gl;
+        if constexpr (CH > 0)         // from the values the sweep used: e and zs - zt as the fp16 they were kept in
+            gl = fmaf((float)(half_t)fast_exp2(fmaf(z, LOG2E, os)), fmaf((float)(half_t)(z - t), c1p, c2p), zero);
+        else
+            gl = fast_exp2(fmaf(z, LOG2E, off_s)) * fmaf(z - t, c1, c2);
+        grow[label] = to16<BF16>(gl - lce * inv_m);
     }
 }
 
