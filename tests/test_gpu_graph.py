@@ -1,0 +1,59 @@
+"""The library's calls captured in a HIP graph (how bench.py times the small-token passes): every replay must give the
+bits the eager calls give, with eager work and synchronisations between the replays."""
+import numpy as np
+import pytest
+
+from parity import announce, small_inputs
+
+pytestmark = pytest.mark.gpu
+
+
+def _snapshot(layer, sib=None):
+    out = [layer.host_y().copy(), layer.host_dx().copy(), layer.host_dA().copy(), layer.host_dB().copy()]
+    if sib is not None:
+        out.append(sib.host_dx().copy())
+    return out
+
+
+@pytest.mark.parametrize("M", [16, 300], ids=["weight_streaming", "tiled"])
+def test_graph_replays_match_eager(M):
+    import torch
+    from paper_2306_08162_amd.device import DeviceLayer, DeviceSiblings
+    announce(f"graph replay M={M}")
+    inp = small_inputs(123 + M, M, 512, 264, 4, 128, 8, "f16")
+    layer = DeviceLayer(inp)
+    other = DeviceLayer(small_inputs(124 + M, M, 512, 136, 4, 128, 8, "f16"))
+    other.x = layer.x
+    sib = DeviceSiblings([layer, other]) if M <= 16 else None
+
+    def run():
+        layer.forward()
+        layer.backward()
+        if sib is not None:
+            sib.forward()
+            sib.backward()
+
+    run()
+    torch.cuda.synchronize()
+    eager = _snapshot(layer, sib)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run()                                   # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run()
+    for rep in range(4):
+        # scribble over the outputs, do some eager work of the same kind, then replay
+        for t in (layer.y, layer.dx, layer.dA, layer.dB):
+            t.fill_(7)
+        other.forward()
+        other.backward()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(eager, _snapshot(layer, sib)):
+            assert np.array_equal(a, b), f"replay {rep} differs from the eager result"
