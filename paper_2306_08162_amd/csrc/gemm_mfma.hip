@@ -143,7 +143,10 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
         const int nt = a.tiles_m * a.tiles_n, bid = blockIdx.x;
         const int xcd = bid & 7, loc = bid >> 3, per = nt >> 3, rem = nt & 7;
         const int t = xcd * per + min(xcd, rem) + loc;
-        constexpr int GM = 4;
+#ifndef QLORA_GM
+#define QLORA_GM 4
+#endif
+        constexpr int GM = QLORA_GM;
         const int in_group = GM * a.tiles_n, group = t / in_group, first_m = group * GM;
         const int gsz = min(a.tiles_m - first_m, GM), o = t % in_group;
         pm = first_m + o % gsz;

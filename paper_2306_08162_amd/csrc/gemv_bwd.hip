@@ -1,0 +1,574 @@
+// Small token counts, backward pass (M <= 16): see gemv_fwd.hip for the regime.  Two launches: row-sliced partial
+// dX = dY Wd with the 8-row in-register transposition of the packed codes (Sec. 3.1: transpose + unpack + matmul in
+// one kernel) and partial u = dY B; then the slice sums, sc u A, dA = sc u^T x and dB = sc dY^T t.
+#include "gemv_common.hpp"
+
+namespace qlora {
+
+namespace {
+
+// ------------------------------------------------------------------------------------------------ backward
+// Workgroup (cb, sp): weight columns [CB cb, +CB), CB = 16 * CL, rows n of slice sp; wave w takes 32-row chunks
+// w, w+4, ...  Lane (wc = lane % 16, q = lane / 16) holds the CL codes of columns CB cb + CL wc .. of rows
+// chunk + 8 q + e, e = 0..7.  MFMA number c of a chunk multiplies dY[m, 32 rows] with the codes at column
+// CL wc + c of those rows: D_c[m][k = CB cb + CL wc + c].
+template <int BITS>
+struct BwdShape {
+#ifndef QLORA_BW_CL2
+#define QLORA_BW_CL2 16
+#endif
+#ifndef QLORA_BW_CL4
+#define QLORA_BW_CL4 8
+#endif
+    static constexpr int CL = BITS == 3 ? 32 : (BITS == 2 ? QLORA_BW_CL2 : (BITS == 4 ? QLORA_BW_CL4 : 8));   // columns per lane
+    static constexpr int WORDS = CL * BITS / 32;
+    static constexpr int CB = 16 * CL;
+};
+
+
+struct BwdArgs {
+    const uint16_t *dy;
+    const uint32_t *packed;
+    const uint16_t *scales;
+    const uint8_t *zeros;
+    const uint16_t *B;
+    float *partial;       // [slices][M][K]
+    float *upartial;      // [slices][16][64]
+    int M, N, K, r, ng, rows_per_slice;
+    uint32_t magic;
+};
+
+// code c (compile-time) of a lane's CL codes held in WORDS words
+template <int BITS, int WORDS>
+__device__ __forceinline__ uint32_t code_of(const uint32_t (&w)[WORDS], int c)
+{
+    constexpr uint32_t mask = (1u << BITS) - 1u;
+    const int o = BITS * c, wi = o >> 5, sh = o & 31;
+    uint32_t v = w[wi] >> sh;
+    if (sh + BITS > 32) v |= w[wi + 1] << (32 - sh);
+    return v & mask;
+}
+
+// fp16: column c of eight consecutive weight rows as one MFMA fragment (element e = row e).  Rows are handled in
+// pairs: one byte permute drops the code of both rows into the mantissas of (1024.0, 1024.0), at bit p of each
+// half; a packed fma with (2^-p, -(1024 * 2^-p + z)) leaves the exact integers q - z and a packed multiply applies
+// the two rows' scales, so every weight is rounded once from its exact value.
+template <int BITS, int WORDS>
+__device__ __forceinline__ u16x8_t dequant_rows8_f16(const uint32_t (&w)[8][WORDS], int c, const half2_t (&s2)[4],
+                                                     const half2_t (&nz2)[4])
+{
+    const int o = BITS * c, wi = o >> 5, sh = o & 31;
+    const bool straddle = sh + BITS > 32;                 // the code runs into the next word (3-bit codes only)
+    const int bb = straddle ? 0 : (sh >> 3), p = straddle ? 0 : (sh & 7);
+    const bool two = p + BITS > 8;                        // ... or into the next byte
+    const uint32_t sel = (uint32_t)bb | ((two ? (uint32_t)(bb + 1) : 0x0Cu) << 8) | ((uint32_t)(4 + bb) << 16) |
+                         ((two ? (uint32_t)(5 + bb) : 0x0Cu) << 24);
+    const uint32_t m1 = ((1u << BITS) - 1u) << p, mask2 = m1 | (m1 << 16);
+    const half_t mulv = (half_t)(1.f / (float)(1 << p)), offc = (half_t)(-1024.f / (float)(1 << p));
+    const half2_t mul2 = {mulv, mulv}, off2 = {offc, offc};
+    u32x4_t out;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        uint32_t lo = w[2 * i][wi], hi = w[2 * i + 1][wi];
+        if (straddle) {
+            lo = __builtin_amdgcn_alignbit(w[2 * i][wi + 1 < WORDS ? wi + 1 : wi], lo, (uint32_t)sh);
+            hi = __builtin_amdgcn_alignbit(w[2 * i + 1][wi + 1 < WORDS ? wi + 1 : wi], hi, (uint32_t)sh);
+        }
+        const uint32_t bits = (__builtin_amdgcn_perm(hi, lo, sel) & mask2) | 0x64006400u;
+        const half2_t h = __builtin_bit_cast(half2_t, bits);
+        out[i] = __builtin_bit_cast(uint32_t, (h * mul2 + (nz2[i] + off2)) * s2[i]);
+    }
+    return __builtin_bit_cast(u16x8_t, out);
+}
+
+// sp_local: row slice inside the projection; sp: slice among all slices of the launch (where its partial sums go)
+template <int BITS, bool BF16, int NW, int BW_U>   // NW waves; BW_U 32-row chunks per wave in flight together
+__device__ __forceinline__ void gemv_bwd_body(const BwdArgs &a, const int sp_local, const int sp)
+{
+    using S = BwdShape<BITS>;
+    constexpr int CL = S::CL, WORDS = S::WORDS, CB = S::CB;
+    constexpr int NT = NW * 64;
+    __shared__ float red[NW][16][128 + 1];   // the column block is reduced 128 columns at a time
+    __shared__ float ured[NW][16][64 + 1];
+    __shared__ uint16_t sz_s[NW][32];        // per wave: scales of its 32 rows (this lane's group is fetched by lane row)
+    __shared__ uint8_t sz_z[NW][32];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wc = lane & 15, q = lane >> 4;
+    const int N = a.N, K = a.K, r = a.r;
+    // Workgroups are dealt to the 8 dies round-robin by their linear index.  A 64-byte piece of a weight row is half
+    // a cache line: neighbouring column blocks go to the same die, so that the line is fetched into one L2 only.
+    const int ncb = (int)gridDim.x, die = (int)blockIdx.x & 7;
+    const int cb = die * (ncb >> 3) + min(die, ncb & 7) + ((int)blockIdx.x >> 3);
+    const int kcol = cb * CB + CL * wc;                     // first of this lane's CL columns (all in one group: CL | 32)
+    const bool kok = kcol < K;
+    const int kc = kok ? kcol : 0;
+    const int Kw = K * BITS / 32;
+    const int g = group_of(kc, a.magic);
+    const int g_block = group_of(cb * CB, a.magic);        // group of the block's first column (lanes past K hold g of column 0)
+    const bool uniform_group = g_block == group_of(min(cb * CB + CB, K) - 1, a.magic);
+    const int nbeg = sp_local * a.rows_per_slice, nend = min(N, nbeg + a.rows_per_slice);
+    const bool do_u = cb == 0 && r > 0;
+
+    float4_t acc[CL], uacc[4];
+#pragma unroll
+    for (int c = 0; c < CL; ++c) acc[c] = float4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int gg = 0; gg < 4; ++gg) uacc[gg] = float4_t{0.f, 0.f, 0.f, 0.f};
+
+    // A wave's chunks are fetched BW_U at a time before any of them is used: the pass is a handful of dependent
+    // memory round trips long, so every load that can be in flight together must be.
+    for (int nb = nbeg + wave * 32; nb < nend; nb += 32 * NW * BW_U) {
+        uint32_t w[BW_U][8][WORDS];
+        u16x8_t df[BW_U], bfr[BW_U][4];        // bfr: B^T fragments for u = dY B (first column block only)
+#pragma unroll
+        for (int u = 0; u < BW_U; ++u)
+#pragma unroll
+            for (int gg = 0; gg < 4; ++gg) bfr[u][gg] = ZERO8;
+        uint16_t sraw[BW_U][8];
+        uint8_t zraw[BW_U][8];
+        const int mrow = min(wc, a.M - 1);                    // dY fragment: token row wc, 8 consecutive rows n
+#pragma unroll
+        for (int u = 0; u < BW_U; ++u) {
+            const int n0 = nb + 32 * NW * u;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int nc = min(n0 + 8 * q + e, N - 1);
+                const uint32_t *src = a.packed + (long)nc * Kw + (kc / CL) * WORDS;
+                if constexpr (WORDS == 2) {
+                    const u32x2_t v = *(const u32x2_t *)src;
+                    w[u][e][0] = v[0];
+                    w[u][e][1] = v[1];
+                } else {
+#pragma unroll
+                    for (int i = 0; i < WORDS; ++i) w[u][e][i] = src[i];
+                }
+            }
+            const int nn = n0 + 8 * q;
+            df[u] = *(const u16x8_t *)(a.dy + (long)mrow * N + (nn < nend ? nn : 0));
+            if (do_u) {     // gathered column-wise, in flight together with the packed words
+#pragma unroll
+                for (int gg = 0; gg < 4; ++gg) {
+                    const int j = gg * 16 + wc;
+                    if (nn < nend && j < r) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) bfr[u][gg][e] = a.B[(long)(nn + e) * r + j];
+                    }
+                }
+            }
+            if (uniform_group) {
+                // one scale / zero-point per row for the whole column block: lane l < 32 fetches row n0 + l
+                const long gi = (long)min(n0 + (lane & 31), N - 1) * a.ng + g_block;
+                sraw[u][0] = a.scales[gi];
+                zraw[u][0] = a.zeros[gi];
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const long gi = (long)min(n0 + 8 * q + e, N - 1) * a.ng + g;
+                    sraw[u][e] = a.scales[gi];
+                    zraw[u][e] = a.zeros[gi];
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < BW_U; ++u) {
+            const int n0 = nb + 32 * NW * u, nn = n0 + 8 * q;
+            const bool in = nn < nend;                        // N % 8 == 0, slices are multiples of 32: all or nothing
+            const u16x8_t dfu = in ? df[u] : ZERO8;
+            float s[8], z[8];
+            if (uniform_group) {
+                // hand the 32 rows' values round through LDS (wave-private; LDS operations of a wave complete in order)
+                if (lane < 32) {
+                    sz_s[wave][lane] = sraw[u][0];
+                    sz_z[wave][lane] = zraw[u][0];
+                }
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const bool ok = kok && n0 + 8 * q + e < nend;
+                    s[e] = ok ? f16_bits_to_f32(sz_s[wave][8 * q + e]) : 0.f;
+                    z[e] = (float)sz_z[wave][8 * q + e];
+                }
+                __builtin_amdgcn_wave_barrier();
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const bool ok = kok && n0 + 8 * q + e < nend;
+                    s[e] = ok ? f16_bits_to_f32(sraw[u][e]) : 0.f;
+                    z[e] = (float)zraw[u][e];
+                }
+            }
+            if (do_u) {     // u = dY B over this chunk
+#pragma unroll
+                for (int gg = 0; gg < 4; ++gg)
+                    if (gg * 16 < r) uacc[gg] = mfma16<BF16>(dfu, bfr[u][gg], uacc[gg]);      // D[m = 4q+v][j = 16 gg + wc]
+            }
+            if constexpr (BF16) {
+#pragma unroll
+                for (int c = 0; c < CL; ++c) {
+                    u16x8_t wf;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        wf[e] = to16<BF16>(((float)code_of<BITS, WORDS>(w[u][e], c) - z[e]) * s[e]);
+                    acc[c] = mfma16<BF16>(dfu, wf, acc[c]);              // D[m = 4q+v][column CL wc + c]
+                }
+            } else {
+                half2_t s2[4], nz2[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    s2[i] = half2_t{(half_t)s[2 * i], (half_t)s[2 * i + 1]};          // exact: they were fp16
+                    nz2[i] = half2_t{(half_t)(-z[2 * i]), (half_t)(-z[2 * i + 1])};
+                }
+#pragma unroll
+                for (int c = 0; c < CL; ++c)
+                    acc[c] = mfma16<BF16>(dfu, dequant_rows8_f16<BITS, WORDS>(w[u], c, s2, nz2), acc[c]);
+            }
+        }
+    }
+    if (do_u) {
+#pragma unroll
+        for (int gg = 0; gg < 4; ++gg)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) ured[wave][4 * q + v][16 * gg + wc] = uacc[gg][v];
+    }
+    for (int cp = 0; cp < CB / 128; ++cp) {
+        if (cp) __syncthreads();
+        if ((CL * wc) / 128 == cp) {
+#pragma unroll
+            for (int c = 0; c < CL; ++c)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) red[wave][4 * q + v][(CL * wc + c) & 127] = acc[c][v];
+        }
+        __syncthreads();
+        for (int e = threadIdx.x; e < 16 * 128; e += NT) {
+            const int m = e >> 7, kl = e & 127, k = cb * CB + cp * 128 + kl;
+            if (m >= a.M || k >= K) continue;
+            float v = 0.f;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) v += red[w][m][kl];
+            a.partial[((long)sp * a.M + m) * K + k] = v;
+        }
+    }
+    if (do_u) {
+        for (int e = threadIdx.x; e < 16 * 64; e += NT) {
+            const int m = e >> 6, j = e & 63;
+            float v = 0.f;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) v += ured[w][m][j];
+            a.upartial[(long)sp * 1024 + e] = v;
+        }
+    }
+}
+
+struct BwdMulti {
+    BwdArgs p[MAX_SIBLINGS];
+    int slice_end[MAX_SIBLINGS];      // projection i owns the slices [slice_end[i-1], slice_end[i])
+    int count;
+};
+
+template <int BITS, bool BF16, int NW, int BW_U>
+__global__ __launch_bounds__(NW * 64) void gemv_bwd_kernel(const BwdArgs a)
+{
+    gemv_bwd_body<BITS, BF16, NW, BW_U>(a, (int)blockIdx.y, (int)blockIdx.y);
+}
+
+// sibling projections (same x, so their dX add up): the slices of all of them in one launch
+template <int BITS, bool BF16, int NW, int BW_U>
+__global__ __launch_bounds__(NW * 64) void gemv_bwd_siblings_kernel(const BwdMulti ma)
+{
+    const int sp = (int)blockIdx.y;
+    int pi = 0;
+    while (pi + 1 < ma.count && sp >= ma.slice_end[pi]) ++pi;      // wave-uniform
+    const BwdArgs a = ma.p[pi];
+    gemv_bwd_body<BITS, BF16, NW, BW_U>(a, sp - (pi ? ma.slice_end[pi - 1] : 0), sp);
+}
+
+// Second backward kernel (M <= 16), one thread per output element:
+//   blocks [0, xb)        dX[m,k] = sum over slices of partial + sc * sum_j u[m,j] A[j,k]
+//   blocks [xb, xb+ab)    dA[j,k] = sc * sum_m u[m,j] x[m,k]
+//   blocks [xb+ab, ...)   dB[n,j] = sc * sum_m dY[m,n] t[m,j]
+// u = sum over slices of the partial u; every block that needs it sums the few entries itself.
+struct FinishArgs {
+    const float *partial, *upartial;
+    const uint16_t *A, *x, *dy, *t;
+    uint16_t *dx;
+    float *dA, *dB;
+    int M, N, K, r, slices, xb, ab;
+    float sc;
+};
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void gemv_bwd_finish_kernel(const FinishArgs a)
+{
+    __shared__ float side[16][64 + 1];       // u (dX and dA blocks) or t (dB blocks), as the 16-bit values they round to
+    const int M = a.M, r = a.r, K = a.K, N = a.N;
+    const int b = blockIdx.x;
+    if (b < a.xb + a.ab) {
+        for (int e = threadIdx.x; e < M * r; e += 256) {
+            const int m = e / r, j = e % r;
+            const float *up = a.upartial + m * 64 + j;
+            float v = 0.f;
+            for (int s0 = 0; s0 < a.slices; s0 += 8) {       // eight slices requested together, summed in slice order
+                float pv[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) pv[i] = s0 + i < a.slices ? up[(long)(s0 + i) * 1024] : 0.f;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) v += pv[i];
+            }
+            side[m][j] = cvt16<BF16>(to16<BF16>(v));
+        }
+    } else {
+        for (int e = threadIdx.x; e < M * r; e += 256) side[e / r][e % r] = cvt16<BF16>(a.t[e]);
+    }
+    __syncthreads();
+    if (b < a.xb) {
+        const long idx = (long)b * 256 + threadIdx.x;
+        if (idx >= (long)M * K) return;
+        const int m = (int)(idx / K), k = (int)(idx % K);
+        const long stride = (long)M * K;
+        float v = 0.f;
+        int s = 0;
+        for (; s + 4 <= a.slices; s += 4) {
+            const float p0 = a.partial[(s + 0) * stride + idx], p1 = a.partial[(s + 1) * stride + idx];
+            const float p2 = a.partial[(s + 2) * stride + idx], p3 = a.partial[(s + 3) * stride + idx];
+            v = (((v + p0) + p1) + p2) + p3;
+        }
+        for (; s < a.slices; ++s) v += a.partial[s * stride + idx];
+        float lo = 0.f;
+        for (int j = 0; j < r; ++j) lo += side[m][j] * cvt16<BF16>(a.A[(long)j * K + k]);
+        a.dx[idx] = to16<BF16>(v + a.sc * lo);
+    } else if (b < a.xb + a.ab) {
+        const long idx = (long)(b - a.xb) * 256 + threadIdx.x;
+        if (idx >= (long)r * K) return;
+        const int j = (int)(idx / K), k = (int)(idx % K);
+        float v = 0.f;
+        for (int m = 0; m < M; ++m) v += side[m][j] * cvt16<BF16>(a.x[(long)m * K + k]);
+        a.dA[idx] = a.sc * v;
+    } else {
+        const long idx = (long)(b - a.xb - a.ab) * 256 + threadIdx.x;
+        if (idx >= (long)r * N) return;
+        const int j = (int)(idx / N), n = (int)(idx % N);
+        float v = 0.f;
+        for (int m = 0; m < M; ++m) v += cvt16<BF16>(a.dy[(long)m * N + n]) * side[m][j];
+        a.dB[(long)n * r + j] = a.sc * v;
+    }
+}
+
+// The same for sibling projections: dX sums the slices of all of them and every projection's sc * u_i A_i.
+//   blocks [0, xb)                 dX
+//   blocks [xb, xb + count*ab)     dA of projection (b - xb) / ab
+//   then, per projection           dB (its block range ends at bb_end)
+struct FinishProj {
+    const uint16_t *A, *dy, *t;
+    float *dA, *dB;
+    int N, slice_begin, slice_end, bb_end;
+};
+struct FinishMulti {
+    FinishProj p[MAX_SIBLINGS];
+    const float *partial, *upartial;
+    const uint16_t *x;
+    uint16_t *dx;
+    int M, K, r, slices, xb, ab, count;
+    float sc;
+};
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void gemv_bwd_finish_siblings_kernel(const FinishMulti a)
+{
+    __shared__ float side[MAX_SIBLINGS][16][64 + 1];
+    const int M = a.M, r = a.r, K = a.K;
+    const int b = blockIdx.x;
+    // u of projection i, as the 16-bit values it rounds to, into side[slot]
+    auto sum_u = [&](int i, int slot) {
+        const int sb = a.p[i].slice_begin, se = a.p[i].slice_end;
+        for (int e = threadIdx.x; e < M * r; e += 256) {
+            const int m = e / r, j = e % r;
+            const float *up = a.upartial + m * 64 + j;
+            float v = 0.f;
+            for (int s0 = sb; s0 < se; s0 += 8) {
+                float pv[8];
+#pragma unroll
+                for (int i8 = 0; i8 < 8; ++i8) pv[i8] = s0 + i8 < se ? up[(long)(s0 + i8) * 1024] : 0.f;
+#pragma unroll
+                for (int i8 = 0; i8 < 8; ++i8) v += pv[i8];
+            }
+            side[slot][m][j] = cvt16<BF16>(to16<BF16>(v));
+        }
+    };
+    if (b < a.xb) {
+        for (int i = 0; i < a.count; ++i) sum_u(i, i);
+        __syncthreads();
+        const long idx = (long)b * 256 + threadIdx.x;
+        if (idx >= (long)M * K) return;
+        const int m = (int)(idx / K), k = (int)(idx % K);
+        const long stride = (long)M * K;
+        float v = 0.f;
+        int s = 0;
+        for (; s + 4 <= a.slices; s += 4) {
+            const float p0 = a.partial[(s + 0) * stride + idx], p1 = a.partial[(s + 1) * stride + idx];
+            const float p2 = a.partial[(s + 2) * stride + idx], p3 = a.partial[(s + 3) * stride + idx];
+            v = (((v + p0) + p1) + p2) + p3;
+        }
+        for (; s < a.slices; ++s) v += a.partial[s * stride + idx];
+        float lo = 0.f;
+        for (int i = 0; i < a.count; ++i)
+            for (int j = 0; j < r; ++j) lo += side[i][m][j] * cvt16<BF16>(a.p[i].A[(long)j * K + k]);
+        a.dx[idx] = to16<BF16>(v + a.sc * lo);
+    } else if (b < a.xb + a.count * a.ab) {
+        const int i = (b - a.xb) / a.ab;
+        sum_u(i, 0);
+        __syncthreads();
+        const long idx = (long)((b - a.xb) % a.ab) * 256 + threadIdx.x;
+        if (idx >= (long)r * K) return;
+        const int j = (int)(idx / K), k = (int)(idx % K);
+        float v = 0.f;
+        for (int m = 0; m < M; ++m) v += side[0][m][j] * cvt16<BF16>(a.x[(long)m * K + k]);
+        a.p[i].dA[idx] = a.sc * v;
+    } else {
+        const int bb = b - a.xb - a.count * a.ab;
+        int i = 0;
+        while (i + 1 < a.count && bb >= a.p[i].bb_end) ++i;
+        const FinishProj pr = a.p[i];
+        for (int e = threadIdx.x; e < M * r; e += 256) side[0][e / r][e % r] = cvt16<BF16>(pr.t[e]);
+        __syncthreads();
+        const long idx = (long)(bb - (i ? a.p[i - 1].bb_end : 0)) * 256 + threadIdx.x;
+        if (idx >= (long)r * pr.N) return;
+        const int j = (int)(idx / pr.N), n = (int)(idx % pr.N);
+        float v = 0.f;
+        for (int m = 0; m < M; ++m) v += cvt16<BF16>(pr.dy[(long)m * pr.N + n]) * side[0][m][j];
+        pr.dB[(long)n * r + j] = a.sc * v;
+    }
+}
+
+template <int BITS, bool BF16>
+void launch_bwd_bits(const BwdMulti &m, hipStream_t s)
+{
+    const int slices = m.slice_end[m.count - 1];
+    int max_rows = 0;
+    for (int i = 0; i < m.count; ++i) max_rows = m.p[i].rows_per_slice > max_rows ? m.p[i].rows_per_slice : max_rows;
+    const dim3 grid((m.p[0].K + BwdShape<BITS>::CB - 1) / BwdShape<BITS>::CB, slices);
+    // Two chunks per wave in flight (more would not fit the register file at eight waves); eight waves share out the
+    // arithmetic of a slice, four are enough when the slice has no more than eight chunks.
+    bool eight = false;
+    if constexpr (BITS != 3) eight = max_rows / 32 > 8;   // 3-bit: 32 columns per lane, the accumulators need the four-wave register budget
+    if (m.count == 1) {
+        if constexpr (BITS != 3) {
+            if (eight) {
+                hipLaunchKernelGGL((gemv_bwd_kernel<BITS, BF16, 8, 2>), grid, dim3(512), 0, s, m.p[0]);
+                return;
+            }
+        }
+        hipLaunchKernelGGL((gemv_bwd_kernel<BITS, BF16, 4, 2>), grid, dim3(256), 0, s, m.p[0]);
+        return;
+    }
+    if constexpr (BITS != 3) {
+        if (eight) {
+            hipLaunchKernelGGL((gemv_bwd_siblings_kernel<BITS, BF16, 8, 2>), grid, dim3(512), 0, s, m);
+            return;
+        }
+    }
+    hipLaunchKernelGGL((gemv_bwd_siblings_kernel<BITS, BF16, 4, 2>), grid, dim3(256), 0, s, m);
+}
+
+int bwd_cb(int bits) { return bits == 3 ? BwdShape<3>::CB : (bits == 2 ? BwdShape<2>::CB : (bits == 4 ? BwdShape<4>::CB : BwdShape<8>::CB)); }
+
+}  // namespace
+
+int gemv_bwd_slices(int N, int K, int bits)
+{
+    const int colblocks = (K + bwd_cb(bits) - 1) / bwd_cb(bits);
+    int slices = (256 + colblocks - 1) / colblocks;      // aim at one workgroup per compute unit: every extra slice
+                                                         // costs another M x K block of partial sums
+    const int max_slices = (N + 127) / 128;              // at least four 32-row chunks per workgroup
+    if (slices > max_slices) slices = max_slices;
+    return slices < 1 ? 1 : slices;
+}
+
+int gemv_bwd_slices_siblings(int count, const int *N, int K, int bits, int *slices)
+{
+    if (count == 1) {
+        slices[0] = gemv_bwd_slices(N[0], K, bits);
+        return slices[0];
+    }
+    const int colblocks = (K + bwd_cb(bits) - 1) / bwd_cb(bits);
+    const int target = (256 + colblocks - 1) / colblocks;
+    long rows = 0;
+    for (int i = 0; i < count; ++i) rows += N[i];
+    int total = 0;
+    for (int i = 0; i < count; ++i) {       // the launch's slices are shared out in proportion to the rows
+        int sl = (int)(((long)target * N[i] + rows / 2) / rows);
+        const int max_slices = (N[i] + 127) / 128;
+        if (sl > max_slices) sl = max_slices;
+        if (sl < 1) sl = 1;
+        slices[i] = sl;
+        total += sl;
+    }
+    while (total > target) {                // rounding must not push the launch into a second round of workgroups
+        int big = 0;
+        for (int i = 1; i < count; ++i)
+            if ((long)slices[i] * N[big] > (long)slices[big] * N[i] || (slices[big] == 1 && slices[i] > 1)) big = i;
+        if (slices[big] == 1) break;        // one slice each is the least there is
+        --slices[big];
+        --total;
+    }
+    return total;
+}
+
+void launch_bwd_small(const Problem &p, int count, const void *const *dy, const void *x,
+                      const uint32_t *const *packed, const void *const *scales, const uint8_t *const *zeros,
+                      const void *const *A, const void *const *B, const void *const *t, void *dx, float *const *dA,
+                      float *const *dB, const int *N, float *partial, float *upartial, hipStream_t s)
+{
+    int slices[MAX_SIBLINGS];
+    const int total = gemv_bwd_slices_siblings(count, N, p.K, p.bits, slices);
+    BwdMulti m{};
+    m.count = count;
+    int end = 0;
+    for (int i = 0; i < count; ++i) {
+        const int rows_per_slice = ((N[i] + slices[i] - 1) / slices[i] + 31) / 32 * 32;
+        m.p[i] = BwdArgs{(const uint16_t *)dy[i], packed[i], (const uint16_t *)scales[i], zeros[i],
+                         (const uint16_t *)(B ? B[i] : nullptr), partial, upartial, p.M, N[i], p.K, p.r, p.K / p.G,
+                         rows_per_slice, group_magic(p.G)};
+        end += slices[i];
+        m.slice_end[i] = end;
+    }
+    QLORA_BITS_DTYPE(launch_bwd_bits, m, s);
+    const int xb = (int)(((long)p.M * p.K + 255) / 256), ab = (int)(((long)p.r * p.K + 255) / 256);
+    if (count == 1) {
+        const int bb = (int)(((long)p.r * N[0] + 255) / 256);
+        const FinishArgs f{partial, upartial, (const uint16_t *)(A ? A[0] : nullptr), (const uint16_t *)x,
+                           (const uint16_t *)dy[0], (const uint16_t *)(t ? t[0] : nullptr), (uint16_t *)dx,
+                           dA ? dA[0] : nullptr, dB ? dB[0] : nullptr, p.M, N[0], p.K, p.r, total, xb, ab, p.sc};
+        if (p.bf16)
+            hipLaunchKernelGGL((gemv_bwd_finish_kernel<true>), dim3(xb + ab + bb), dim3(256), 0, s, f);
+        else
+            hipLaunchKernelGGL((gemv_bwd_finish_kernel<false>), dim3(xb + ab + bb), dim3(256), 0, s, f);
+        return;
+    }
+    FinishMulti f{};
+    f.partial = partial;
+    f.upartial = upartial;
+    f.x = (const uint16_t *)x;
+    f.dx = (uint16_t *)dx;
+    f.M = p.M;
+    f.K = p.K;
+    f.r = p.r;
+    f.slices = total;
+    f.xb = xb;
+    f.ab = ab;
+    f.count = count;
+    f.sc = p.sc;
+    int bb_end = 0, sb = 0;
+    for (int i = 0; i < count; ++i) {
+        bb_end += (int)(((long)p.r * N[i] + 255) / 256);
+        f.p[i] = FinishProj{(const uint16_t *)(A ? A[i] : nullptr), (const uint16_t *)dy[i],
+                            (const uint16_t *)(t ? t[i] : nullptr), dA ? dA[i] : nullptr, dB ? dB[i] : nullptr,
+                            N[i], sb, sb + slices[i], bb_end};
+        sb += slices[i];
+    }
+    const int blocks = xb + count * ab + bb_end;
+    if (p.bf16)
+        hipLaunchKernelGGL((gemv_bwd_finish_siblings_kernel<true>), dim3(blocks), dim3(256), 0, s, f);
+    else
+        hipLaunchKernelGGL((gemv_bwd_finish_siblings_kernel<false>), dim3(blocks), dim3(256), 0, s, f);
+}
+
+}  // namespace qlora

@@ -1,0 +1,53 @@
+// Small token counts: the pass is bound by streaming the packed weight once from HBM (Limitations of the paper:
+// the compressed weight cuts the memory traffic of both passes; this is the regime where that shows).  Every lane
+// fetches its own MFMA fragment of packed words straight from global memory, dequantises it in registers and feeds
+// v_mfma_f32_16x16x32; partial sums go through LDS (and, up to 32 token rows, so do x and A: see the staged
+// forward kernel in gemv_fwd_impl.hpp).  Launches are what the pass is made of at this size, so the rank-r products
+// ride along: one launch forward, two backward (gemv_bwd.hip).
+//
+//   forward  (M <= 64)  y = x Wd^T + sc * t B^T with t = x A^T computed by the same MFMAs (one extra fragment of
+//            A per k-step); one workgroup per 16 weight rows (up to four such blocks), its waves split K.
+//
+// This file holds the host side of the forward pass; the kernels are instantiated per code width in
+// gemv_fwd_b{2,3,4,8}.hip.
+#include "gemv_common.hpp"
+
+namespace qlora {
+
+bool fwd_small_computes_t(int rank) { return rank > 0 && rank <= 32; }
+
+void launch_fwd_small(const Problem &p, int count, const void *x, const uint32_t *const *packed,
+                      const void *const *scales, const uint8_t *const *zeros, const void *const *A,
+                      const void *const *B, const void *const *t_in, void *const *t_out, void *const *y, const int *N,
+                      hipStream_t s)
+{
+    const bool fused = fwd_small_computes_t(p.r);
+    FwdMulti m{};
+    m.count = count;
+    for (int i = 0; i < count; ++i)
+        m.p[i] = FwdArgs{(const uint16_t *)x,
+                         packed[i],
+                         (const uint16_t *)scales[i],
+                         zeros[i],
+                         (const uint16_t *)(A ? A[i] : nullptr),
+                         (const uint16_t *)(B ? B[i] : nullptr),
+                         fused ? nullptr : (const uint16_t *)(t_in ? t_in[i] : nullptr),
+                         (uint16_t *)y[i],
+                         fused ? (uint16_t *)(t_out ? t_out[i] : nullptr) : nullptr,
+                         p.M,
+                         N[i],
+                         p.K,
+                         p.r,
+                         p.K / p.G,
+                         p.sc,
+                         group_magic(p.G)};
+    const int rg = fused ? (p.r + 15) / 16 : 0;
+    switch (p.bits) {
+    case 2: launch_fwd_small_bits<2>(m, rg, p.bf16, s); break;
+    case 3: launch_fwd_small_bits<3>(m, rg, p.bf16, s); break;
+    case 4: launch_fwd_small_bits<4>(m, rg, p.bf16, s); break;
+    default: launch_fwd_small_bits<8>(m, rg, p.bf16, s); break;
+    }
+}
+
+}  // namespace qlora

@@ -1,0 +1,8 @@
+// Small-token-count forward kernels for 8-bit codes (see gemv_fwd_impl.hpp).
+#include "gemv_fwd_impl.hpp"
+
+namespace qlora {
+
+template void launch_fwd_small_bits<8>(const FwdMulti &, int, bool, hipStream_t);
+
+}  // namespace qlora
