@@ -113,7 +113,11 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
     static_assert(XDMA >= 4 && XDMA % 4 == 0, "loads are spread over the four k-steps");
     constexpr int WU = BN / 128;                    // 32-code weight units per staging thread per stage
     constexpr int XS = BM * BK;                     // halfs per activation stage (128-byte rows, swizzled)
-    constexpr int NXS = 3;                          // activation stages
+#ifndef QLORA_NXS
+#define QLORA_NXS 3
+#endif
+    constexpr int NXS = QLORA_NXS;                  // activation stages (3, or 2 when two workgroups share a CU's LDS)
+    static_assert(NXS == 2 || NXS == 3, "activation stages");
     constexpr int WS = BN * LDS_STRIDE;             // halfs per weight stage (144-byte rows)
     using Regs = StageRegs<BITS, WU>;
 
@@ -220,20 +224,24 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
 
 #pragma unroll
         for (int i = 0; i < XDMA; ++i) issue_x(0, 0, i);
+        if constexpr (NXS == 3) {
 #pragma unroll
-        for (int i = 0; i < XDMA; ++i) issue_x(1, 1, i);
-        wait_vm_and_barrier<XDMA>();            // stage 0 of the activations has landed; weights staged by waves 4-7
+            for (int i = 0; i < XDMA; ++i) issue_x(1, 1, i);
+        }
+        constexpr int AHEAD = NXS == 3 ? XDMA : 0;   // loads that may still be in flight when a stage is needed
+        wait_vm_and_barrier<AHEAD>();           // stage 0 of the activations has landed; weights staged by waves 4-7
         Frags f[2];
         load_frags(0, 0, 0, f[0]);
         int xstage = 0;                         // kt % NXS
         for (int kt = 0; kt < KT; ++kt) {
             const int wstage = kt & 1;
-            const int xnext = xstage + 1 == NXS ? 0 : xstage + 1, xfill = xnext + 1 == NXS ? 0 : xnext + 1;
+            const int xnext = xstage + 1 == NXS ? 0 : xstage + 1;
+            const int xfill = NXS == 3 ? (xnext + 1 == NXS ? 0 : xnext + 1) : xnext;   // the stage NXS-1 ahead
             // the last k-step of a stage runs from registers after the barrier, overlapping the LDS latency of the
             // next stage's first fragments; the activation loads for stage kt+2 are spread over the k-steps
             auto issue_quarter = [&](int qtr) {
 #pragma unroll
-                for (int i = qtr * (XDMA / 4); i < (qtr + 1) * (XDMA / 4); ++i) issue_x(kt + 2, xfill, i);
+                for (int i = qtr * (XDMA / 4); i < (qtr + 1) * (XDMA / 4); ++i) issue_x(kt + NXS - 1, xfill, i);
             };
             issue_quarter(0);
             kstep(xstage, wstage, 1, f[1], f[0]);
@@ -242,7 +250,7 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
             issue_quarter(2);
             kstep(xstage, wstage, 3, f[1], f[0]);
             issue_quarter(3);
-            wait_vm_and_barrier<XDMA>();        // stage kt+1 has landed (only this step's loads may be pending)
+            wait_vm_and_barrier<AHEAD>();       // stage kt+1 has landed (only loads for a later stage may be pending)
             kstep(xnext, wstage ^ 1, 0, f[0], f[1]);
             xstage = xnext;
         }
@@ -402,7 +410,7 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
 template <int BITS, bool BF16, bool TRANS, int BM, int BN, int WM, int WN>
 void launch_variant(const GemmArgs &a, hipStream_t s)
 {
-    constexpr size_t lds_pipe = (3 * (size_t)BM * BK + 2 * (size_t)BN * LDS_STRIDE) * sizeof(uint16_t);
+    constexpr size_t lds_pipe = (QLORA_NXS * (size_t)BM * BK + 2 * (size_t)BN * LDS_STRIDE) * sizeof(uint16_t);
     constexpr size_t lds_epi = (size_t)WM * WN * (BM / WM) * (BN / WN + 8) * sizeof(uint16_t);
     constexpr size_t lds = lds_pipe > lds_epi ? lds_pipe : lds_epi;
     auto kern = qgemm_kernel<BITS, BF16, TRANS, BM, BN, WM, WN>;
