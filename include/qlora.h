@@ -118,6 +118,17 @@ int qlora_linear_bwd(const void *dy, const void *x, const uint32_t *packed, cons
                      void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The same with accumulation into the adapter gradients, for training steps that sum micro-batches (Appendix B:
+ * a batch of 144 from micro-batches of 1, 24 or 48):  dA = beta * dA + (this call's dA), dB likewise; dx is
+ * overwritten as before.  beta == 0 is qlora_linear_bwd (dA and dB are then not read).
+ */
+int qlora_linear_bwd_accumulate(const void *dy, const void *x, const uint32_t *packed, const void *scales,
+                                const uint8_t *zeros, const void *A, const void *B, const void *t_saved,
+                                void *dx, float *dA, float *dB, float beta,
+                                int M, int N, int K, int bits, int group_size, int rank, float alpha, int dtype,
+                                void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Sibling projections at small token counts.  Projections that read the same
  * input (q/k/v of an attention block, gate/up of an MLP; the paper adapts "every
  * linear projection", Appendix C) can be handed over together: one launch

@@ -117,7 +117,7 @@ struct GradArgs {
     int C[2];
     int nb0;                // column blocks of the first problem
     int M, r, slices;
-    float sc;
+    float sc, beta;         // out = beta * out + sc * sum (beta == 0: out is not read)
 };
 
 template <bool BF16, int RG>
@@ -215,7 +215,8 @@ __global__ __launch_bounds__(256) void adapter_grad_reduce_kernel(const GradArgs
     }
     for (; s < a.slices; ++s) acc += partial[s * stride + idx];
     const int c = (int)(idx / r), j = (int)(idx % r);
-    a.out[which][which ? (long)j * C + c : idx] = a.sc * acc;
+    float *dst = a.out[which] + (which ? (long)j * C + c : idx);
+    *dst = a.beta == 0.f ? a.sc * acc : fmaf(a.beta, *dst, a.sc * acc);
 }
 
 template <bool BF16>
@@ -272,7 +273,7 @@ int adapter_grad_slices(int M, int r)
 }
 
 void launch_adapter_grads(const void *dy, const void *t, const void *x, const void *u, float *dB, float *dA,
-                          float *partial, int M, int N, int K, int r, float sc, bool bf16, hipStream_t s)
+                          float *partial, int M, int N, int K, int r, float sc, float beta, bool bf16, hipStream_t s)
 {
     const int slices = adapter_grad_slices(M, r);
     GradArgs a;
@@ -291,6 +292,7 @@ void launch_adapter_grads(const void *dy, const void *t, const void *x, const vo
     a.r = r;
     a.slices = slices;
     a.sc = sc;
+    a.beta = beta;
     if (bf16)
         launch_grad_partial<true>(a, s);
     else

@@ -182,6 +182,15 @@ int qlora_linear_bwd(const void *dy, const void *x, const uint32_t *packed, cons
                      int K, int bits, int group_size, int rank, float alpha, int dtype, void *workspace,
                      size_t workspace_bytes, void *stream)
 {
+    return qlora_linear_bwd_accumulate(dy, x, packed, scales, zeros, A, B, t_saved, dx, dA, dB, 0.f, M, N, K, bits,
+                                       group_size, rank, alpha, dtype, workspace, workspace_bytes, stream);
+}
+
+int qlora_linear_bwd_accumulate(const void *dy, const void *x, const uint32_t *packed, const void *scales,
+                                const uint8_t *zeros, const void *A, const void *B, const void *t_saved, void *dx,
+                                float *dA, float *dB, float beta, int M, int N, int K, int bits, int group_size,
+                                int rank, float alpha, int dtype, void *workspace, size_t workspace_bytes, void *stream)
+{
     const int st = check_problem(M, N, K, bits, group_size, rank, dtype);
     if (st != QLORA_OK) return st;
     if (!dy || !packed || !scales || !zeros || !dx) return QLORA_E_NULL;
@@ -205,7 +214,7 @@ int qlora_linear_bwd(const void *dy, const void *x, const uint32_t *packed, cons
         }
         GemmTimer timer(s);
         launch_bwd_small(p, 1, &dy, x, &packed, &scales, &zeros, &A, &B, &t, dx, &dA, &dB, &N,
-                         (float *)(ws + w.partial_off), (float *)(ws + w.upartial_off), s);
+                         (float *)(ws + w.partial_off), (float *)(ws + w.upartial_off), beta, s);
         return hip_status();
     }
     void *u = nullptr;
@@ -224,7 +233,7 @@ int qlora_linear_bwd(const void *dy, const void *x, const uint32_t *packed, cons
             t = ws + w.t_off;
         }
         float *partial = (float *)(ws + w.partial_off);
-        launch_adapter_grads(dy, t, x, u, dB, dA, partial, M, N, K, rank, p.sc, p.bf16, s);
+        launch_adapter_grads(dy, t, x, u, dB, dA, partial, M, N, K, rank, p.sc, beta, p.bf16, s);
     }
     return hip_status();
 }
@@ -345,7 +354,7 @@ int qlora_linear_bwd_siblings(int count, const void *const *dy, const void *x, c
     }
     GemmTimer timer(s);
     launch_bwd_small(p, count, dy, x, packed, scales, zeros, A, B, t, dx, dA, dB, N, (float *)(ws + w.partial_off),
-                     (float *)(ws + w.upartial_off), s);
+                     (float *)(ws + w.upartial_off), 0.f, s);
     return hip_status();
 }
 

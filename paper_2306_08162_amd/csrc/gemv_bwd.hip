@@ -292,7 +292,7 @@ struct FinishArgs {
     uint16_t *dx;
     float *dA, *dB;
     int M, N, K, r, slices, xb, ab;
-    float sc;
+    float sc, beta;      // dA = beta * dA + ..., dB likewise (beta == 0: they are not read)
 };
 
 template <bool BF16>
@@ -341,14 +341,15 @@ __global__ __launch_bounds__(256) void gemv_bwd_finish_kernel(const FinishArgs a
         const int j = (int)(idx / K), k = (int)(idx % K);
         float v = 0.f;
         for (int m = 0; m < M; ++m) v += side[m][j] * cvt16<BF16>(a.x[(long)m * K + k]);
-        a.dA[idx] = a.sc * v;
+        a.dA[idx] = a.beta == 0.f ? a.sc * v : fmaf(a.beta, a.dA[idx], a.sc * v);
     } else {
         const long idx = (long)(b - a.xb - a.ab) * 256 + threadIdx.x;
         if (idx >= (long)r * N) return;
         const int j = (int)(idx / N), n = (int)(idx % N);
         float v = 0.f;
         for (int m = 0; m < M; ++m) v += cvt16<BF16>(a.dy[(long)m * N + n]) * side[m][j];
-        a.dB[(long)n * r + j] = a.sc * v;
+        float *dst = a.dB + (long)n * r + j;
+        *dst = a.beta == 0.f ? a.sc * v : fmaf(a.beta, *dst, a.sc * v);
     }
 }
 
@@ -367,7 +368,7 @@ struct FinishMulti {
     const uint16_t *x;
     uint16_t *dx;
     int M, K, r, slices, xb, ab, count;
-    float sc;
+    float sc, beta;
 };
 
 template <bool BF16>
@@ -421,7 +422,7 @@ __global__ __launch_bounds__(256) void gemv_bwd_finish_siblings_kernel(const Fin
         const int j = (int)(idx / K), k = (int)(idx % K);
         float v = 0.f;
         for (int m = 0; m < M; ++m) v += side[0][m][j] * cvt16<BF16>(a.x[(long)m * K + k]);
-        a.p[i].dA[idx] = a.sc * v;
+        a.p[i].dA[idx] = a.beta == 0.f ? a.sc * v : fmaf(a.beta, a.p[i].dA[idx], a.sc * v);
     } else {
         const int bb = b - a.xb - a.count * a.ab;
         int i = 0;
@@ -434,7 +435,8 @@ __global__ __launch_bounds__(256) void gemv_bwd_finish_siblings_kernel(const Fin
         const int j = (int)(idx / pr.N), n = (int)(idx % pr.N);
         float v = 0.f;
         for (int m = 0; m < M; ++m) v += cvt16<BF16>(pr.dy[(long)m * pr.N + n]) * side[0][m][j];
-        pr.dB[(long)n * r + j] = a.sc * v;
+        float *dst = pr.dB + (long)n * r + j;
+        *dst = a.beta == 0.f ? a.sc * v : fmaf(a.beta, *dst, a.sc * v);
     }
 }
 
@@ -515,7 +517,7 @@ int gemv_bwd_slices_siblings(int count, const int *N, int K, int bits, int *slic
 void launch_bwd_small(const Problem &p, int count, const void *const *dy, const void *x,
                       const uint32_t *const *packed, const void *const *scales, const uint8_t *const *zeros,
                       const void *const *A, const void *const *B, const void *const *t, void *dx, float *const *dA,
-                      float *const *dB, const int *N, float *partial, float *upartial, hipStream_t s)
+                      float *const *dB, const int *N, float *partial, float *upartial, float beta, hipStream_t s)
 {
     int slices[MAX_SIBLINGS];
     const int total = gemv_bwd_slices_siblings(count, N, p.K, p.bits, slices);
@@ -536,7 +538,7 @@ void launch_bwd_small(const Problem &p, int count, const void *const *dy, const 
         const int bb = (int)(((long)p.r * N[0] + 255) / 256);
         const FinishArgs f{partial, upartial, (const uint16_t *)(A ? A[0] : nullptr), (const uint16_t *)x,
                            (const uint16_t *)dy[0], (const uint16_t *)(t ? t[0] : nullptr), (uint16_t *)dx,
-                           dA ? dA[0] : nullptr, dB ? dB[0] : nullptr, p.M, N[0], p.K, p.r, total, xb, ab, p.sc};
+                           dA ? dA[0] : nullptr, dB ? dB[0] : nullptr, p.M, N[0], p.K, p.r, total, xb, ab, p.sc, beta};
         if (p.bf16)
             hipLaunchKernelGGL((gemv_bwd_finish_kernel<true>), dim3(xb + ab + bb), dim3(256), 0, s, f);
         else
@@ -556,6 +558,7 @@ void launch_bwd_small(const Problem &p, int count, const void *const *dy, const 
     f.ab = ab;
     f.count = count;
     f.sc = p.sc;
+    f.beta = beta;
     int bb_end = 0, sb = 0;
     for (int i = 0; i < count; ++i) {
         bb_end += (int)(((long)p.r * N[i] + 255) / 256);

@@ -26,9 +26,9 @@ void launch_lora_u(const void *dy, const void *B, void *bt, void *u, int M, int 
 // Number of token slices the adapter-gradient reductions are cut into (fixed by the shape alone).
 int adapter_grad_slices(int M, int r);
 // dB[N,r] = sc * dy[M,N]^T t[M,r] and dA[r,K] = sc * u[M,r]^T x[M,K], two launches for both (slice partial sums,
-// then their fixed-order reduction); partial holds slices*(N+K)*r floats.
+// then their fixed-order reduction); partial holds slices*(N+K)*r floats.  beta != 0: dB = beta*dB + ..., dA likewise.
 void launch_adapter_grads(const void *dy, const void *t, const void *x, const void *u, float *dB, float *dA,
-                          float *partial, int M, int N, int K, int r, float sc, bool bf16, hipStream_t s);
+                          float *partial, int M, int N, int K, int r, float sc, float beta, bool bf16, hipStream_t s);
 
 // gemm_mfma.hip -- tiled MFMA GEMMs with fused dequantisation (any accepted shape)
 void launch_fwd_mfma(const Problem &p, const void *x, const uint32_t *packed, const void *scales,
@@ -53,11 +53,12 @@ void launch_fwd_small(const Problem &p, int count, const void *x, const uint32_t
 // total returned (count == 1: gemv_bwd_slices).
 int gemv_bwd_slices_siblings(int count, const int *N, int K, int bits, int *slices);
 // dx (the sum over the siblings), dA[i], dB[i] from two launches; partial holds total_slices*M*K floats, upartial
-// total_slices*1024 floats; t may be NULL if r == 0.  The arrays are host arrays of `count` device pointers.
+// total_slices*1024 floats; t may be NULL if r == 0; beta != 0 accumulates into dA[i], dB[i] (beta*old + new).  The
+// arrays are host arrays of `count` device pointers.
 void launch_bwd_small(const Problem &p, int count, const void *const *dy, const void *x,
                       const uint32_t *const *packed, const void *const *scales, const uint8_t *const *zeros,
                       const void *const *A, const void *const *B, const void *const *t, void *dx, float *const *dA,
-                      float *const *dB, const int *N, float *partial, float *upartial, hipStream_t s);
+                      float *const *dB, const int *N, float *partial, float *upartial, float beta, hipStream_t s);
 
 // loss.hip -- the LREC objective (KL student || teacher + next-token CE, mean over tokens) and its gradient
 // kl, ce (per token) and grad may be NULL; tok receives lambda_kl*KL + lambda_ce*CE per token, loss_mean their mean

@@ -67,6 +67,14 @@ class DeviceLayer:
                             c.M, c.N, c.K, c.bits, c.group_size, c.rank, c.alpha, self.dtype_flag, self.workspace,
                             stream=stream)
 
+    def backward_accumulate(self, beta: float, use_saved_t: bool = True, stream=None):
+        c = self.cfg
+        ql.qlora_linear_bwd_accumulate(self.dy, self.x, self.packed, self.scales, self.zeros, self.A, self.B,
+                                       self.t if (use_saved_t and c.rank) else None, self.dx,
+                                       self.dA if c.rank else None, self.dB if c.rank else None, beta,
+                                       c.M, c.N, c.K, c.bits, c.group_size, c.rank, c.alpha, self.dtype_flag,
+                                       self.workspace, stream=stream)
+
     def unpack(self) -> np.ndarray:
         c = self.cfg
         out = torch.empty((c.N, c.K), dtype=torch.uint8, device=self.device)

@@ -158,6 +158,19 @@ def test_sibling_argument_errors(which):
         assert _sib(which, y=[FAKE, None]) == E["QLORA_E_NULL"]
 
 
+def test_bwd_accumulate_argument_errors():
+    args = [FAKE] * 11
+    def call(beta=1.0, M=16, N=64, K=128, bits=4, G=64, rank=8, dtype=0, dA=FAKE, wsb=1 << 30):
+        a = list(args)
+        a[9] = dA
+        return ql.qlora_linear_bwd_accumulate(*a, beta, M, N, K, bits, G, rank, 16.0, dtype, FAKE, wsb, stream=0,
+                                              check=False)
+    assert call(bits=5) == E["QLORA_E_BITS"]
+    assert call(rank=12) == E["QLORA_E_RANK"]
+    assert call(dA=None) == E["QLORA_E_NULL"]
+    assert call(wsb=0) == E["QLORA_E_WORKSPACE"]
+
+
 def test_sibling_workspace_bytes():
     assert ql.qlora_siblings_workspace_bytes([64, 40], 17, 128, 4, 64, 8) == 0
     assert ql.qlora_siblings_workspace_bytes([64, 44], 4, 128, 4, 64, 8) == 0

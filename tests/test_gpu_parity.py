@@ -206,3 +206,32 @@ def test_zero_adapter_A_gives_zero_dB():
     torch.cuda.synchronize()
     assert np.all(layer.host_dB() == 0.0)
     assert np.all(layer.host_t() == 0)
+
+
+@pytest.mark.parametrize("M", [9, 300], ids=["weight_streaming", "tiled"])
+def test_backward_accumulates_into_adapter_gradients(M):
+    """Micro-batch accumulation: dA = beta * dA + new, dB likewise, dX overwritten; beta = 0 must not read dA / dB."""
+    import torch
+    from paper_2306_08162_amd.device import DeviceLayer
+    inp = small_inputs(55 + M, M, 384, 264, 3, 128, 16, "f16")
+    announce(f"accumulate M={M}")
+    layer = DeviceLayer(inp)
+    layer.forward()
+    layer.backward()
+    torch.cuda.synchronize()
+    dA1, dB1, dx1 = layer.host_dA().copy(), layer.host_dB().copy(), layer.host_dx().copy()
+    # accumulate the same gradients twice more on top, with beta = 1 and then beta = 0.5
+    layer.backward_accumulate(1.0)
+    layer.backward_accumulate(0.5)
+    torch.cuda.synchronize()
+    assert np.array_equal(layer.host_dx(), dx1)
+    lo = make_oracle(inp)
+    dA_ref, dB_ref = lo.backward_adapters(inp.dy, inp.x)
+    assert rel_fro(layer.host_dA(), 2.0 * dA_ref) <= TOL and rel_fro(layer.host_dB(), 2.0 * dB_ref) <= TOL
+    assert np.allclose(layer.host_dA(), 0.5 * (2.0 * dA1) + dA1, rtol=1e-6, atol=0)
+    # beta = 0 over poisoned buffers: the old contents (NaN) must not leak in
+    layer.dA.fill_(float("nan"))
+    layer.dB.fill_(float("nan"))
+    layer.backward_accumulate(0.0)
+    torch.cuda.synchronize()
+    assert np.array_equal(layer.host_dA(), dA1) and np.array_equal(layer.host_dB(), dB1)
