@@ -175,6 +175,34 @@ def backward_adapters(dy, x, A, B, alpha: float) -> Tuple[np.ndarray, np.ndarray
     return dA, dB
 
 
+# ------------------------------------------------------------ LoRA dropout
+# Appendix B trains with a dropout rate of 0.05.  Reading: as in the LoRA method the paper builds on, dropout acts on
+# the input of the low-rank branch only, with inverted scaling; the frozen quantized path sees x itself:
+#     x~ = x * keep * keep_scale   (keep in {0,1} per element of x, keep_scale = 1 / (1 - p))
+#     y  = x Wd^T + sc (x~ A^T) B^T
+#     dX = dY Wd + (sc (dY B) A) * keep * keep_scale,   dA = sc (dY B)^T x~,   dB = sc dY^T (x~ A^T)
+# The mask is an input (the caller draws it); the functions below are the plain ones applied to x~ where x~ stands.
+
+def forward_dropout(x, Wd, A, B, alpha: float, keep, keep_scale: float) -> Tuple[np.ndarray, np.ndarray]:
+    x = _c(x, np.float64)
+    xt = x * _c(keep, np.float64) * float(keep_scale)
+    base, _ = forward(x, Wd, np.zeros_like(_c(A, np.float64)), B, alpha)          # x Wd^T
+    lora, t = forward(xt, np.zeros_like(_c(Wd, np.float64)), A, B, alpha)         # sc (x~ A^T) B^T
+    return base + lora, t
+
+
+def backward_dx_dropout(dy, Wd, A, B, alpha: float, keep, keep_scale: float) -> np.ndarray:
+    Wd = _c(Wd, np.float64)
+    base = backward_dx(dy, Wd, A, np.zeros_like(_c(B, np.float64)), alpha)        # dY Wd
+    lora = backward_dx(dy, np.zeros_like(Wd), A, B, alpha)                         # sc (dY B) A
+    return base + lora * _c(keep, np.float64) * float(keep_scale)
+
+
+def backward_adapters_dropout(dy, x, A, B, alpha: float, keep, keep_scale: float) -> Tuple[np.ndarray, np.ndarray]:
+    xt = _c(x, np.float64) * _c(keep, np.float64) * float(keep_scale)
+    return backward_adapters(dy, xt, A, B, alpha)
+
+
 class LayerOracle:
     """The layer on one set of stored inputs (raw 16-bit patterns + codes).
 
@@ -206,3 +234,18 @@ class LayerOracle:
     def backward_adapters(self, dy_bits, x_bits):
         return backward_adapters(widen(dy_bits, self.dtype), widen(x_bits, self.dtype),
                                  self.A, self.B, self.alpha)
+
+    # the same with LoRA dropout (keep: {0,1} [M,K] for the rows asked for, keep_scale = 1 / (1 - p))
+    def forward_dropout(self, x_bits, keep, keep_scale: float, rows: Optional[np.ndarray] = None):
+        x = widen(x_bits if rows is None else np.asarray(x_bits)[rows], self.dtype)
+        k = keep if rows is None else np.asarray(keep)[rows]
+        return forward_dropout(x, self.Wd, self.A, self.B, self.alpha, k, keep_scale)
+
+    def backward_dx_dropout(self, dy_bits, keep, keep_scale: float, rows: Optional[np.ndarray] = None):
+        dy = widen(dy_bits if rows is None else np.asarray(dy_bits)[rows], self.dtype)
+        k = keep if rows is None else np.asarray(keep)[rows]
+        return backward_dx_dropout(dy, self.Wd, self.A, self.B, self.alpha, k, keep_scale)
+
+    def backward_adapters_dropout(self, dy_bits, x_bits, keep, keep_scale: float):
+        return backward_adapters_dropout(widen(dy_bits, self.dtype), widen(x_bits, self.dtype), self.A, self.B,
+                                         self.alpha, keep, keep_scale)

@@ -310,6 +310,54 @@ def test_sibling_projections_dx_is_the_sum_of_their_dx():
         assert abs(fd - dx[idx]) <= 1e-8 * max(1.0, abs(fd)), (idx, fd, dx[idx])
 
 
+def test_lora_dropout_reduces_to_the_plain_layer_and_to_no_adapter():
+    p = _small_problem(620, M=6, N=10, K=64, r=4, b=4, G=32)
+    ones, zeros = np.ones_like(p["x"]), np.zeros_like(p["x"])
+    y0, t0 = oracle.forward(p["x"], p["Wd"], p["A"], p["B"], p["alpha"])
+    y1, t1 = oracle.forward_dropout(p["x"], p["Wd"], p["A"], p["B"], p["alpha"], ones, 1.0)
+    assert np.allclose(y0, y1, rtol=0, atol=1e-12) and np.allclose(t0, t1, rtol=0, atol=1e-13)
+    assert np.allclose(oracle.backward_dx(p["dy"], p["Wd"], p["A"], p["B"], p["alpha"]),
+                       oracle.backward_dx_dropout(p["dy"], p["Wd"], p["A"], p["B"], p["alpha"], ones, 1.0), atol=1e-12)
+    # everything dropped: the adapter is gone from y, dX and dA (dB = sc dY^T t with t = 0)
+    y2, t2 = oracle.forward_dropout(p["x"], p["Wd"], p["A"], p["B"], p["alpha"], zeros, 1.0 / 0.95)
+    assert _rel(y2, p["x"] @ p["Wd"].T) < RTOL and np.all(t2 == 0)
+    assert _rel(oracle.backward_dx_dropout(p["dy"], p["Wd"], p["A"], p["B"], p["alpha"], zeros, 1.0 / 0.95),
+                p["dy"] @ p["Wd"]) < RTOL
+    dA, dB = oracle.backward_adapters_dropout(p["dy"], p["x"], p["A"], p["B"], p["alpha"], zeros, 1.0 / 0.95)
+    assert np.all(dA == 0) and np.all(dB == 0)
+    # against the formulas written with numpy
+    rng = np.random.RandomState(2)
+    keep = (rng.rand(*p["x"].shape) > 0.3).astype(np.float64)
+    ks, sc = 1.0 / 0.7, p["alpha"] / 4
+    xt = p["x"] * keep * ks
+    y3, _ = oracle.forward_dropout(p["x"], p["Wd"], p["A"], p["B"], p["alpha"], keep, ks)
+    assert _rel(y3, p["x"] @ p["Wd"].T + sc * (xt @ p["A"].T) @ p["B"].T) < RTOL
+    dx3 = oracle.backward_dx_dropout(p["dy"], p["Wd"], p["A"], p["B"], p["alpha"], keep, ks)
+    assert _rel(dx3, p["dy"] @ p["Wd"] + sc * ((p["dy"] @ p["B"]) @ p["A"]) * keep * ks) < RTOL
+
+
+def test_lora_dropout_gradients_by_finite_differences():
+    # with the mask fixed, L = <dY, y> is still linear in each of x, A, B
+    p = _small_problem(630, M=5, N=9, K=64, r=4, b=3, G=32)
+    rng = np.random.RandomState(3)
+    keep = (rng.rand(*p["x"].shape) > 0.25).astype(np.float64)
+    ks = 1.0 / 0.75
+    L = lambda x, A, B: float(np.sum(p["dy"] * oracle.forward_dropout(x, p["Wd"], A, B, p["alpha"], keep, ks)[0]))
+    dx = oracle.backward_dx_dropout(p["dy"], p["Wd"], p["A"], p["B"], p["alpha"], keep, ks)
+    dA, dB = oracle.backward_adapters_dropout(p["dy"], p["x"], p["A"], p["B"], p["alpha"], keep, ks)
+    h = 1e-3
+    for name, grad in (("x", dx), ("A", dA), ("B", dB)):
+        for _ in range(12):
+            idx = tuple(rng.randint(0, s) for s in grad.shape)
+            args = {k: p[k].copy() for k in ("x", "A", "B")}
+            args[name][idx] += h
+            up = L(args["x"], args["A"], args["B"])
+            args[name][idx] -= 2 * h
+            dn = L(args["x"], args["A"], args["B"])
+            fd = (up - dn) / (2 * h)
+            assert abs(fd - grad[idx]) <= 1e-8 * max(1.0, abs(fd)), (name, idx, fd, grad[idx])
+
+
 def test_backward_adjoint_identities():
     p = _small_problem(700, M=11, N=24, K=128, r=8, b=4, G=64)
     fwd = lambda x, A, B: oracle.forward(x, p["Wd"], A, B, p["alpha"])[0]
