@@ -129,6 +129,28 @@ int qlora_linear_bwd_accumulate(const void *dy, const void *x, const uint32_t *p
                                 void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * LoRA dropout (Appendix B trains with a dropout rate of 0.05).  Reading: as in the LoRA method the paper builds on,
+ * dropout acts on the input of the low-rank branch only, with inverted scaling; the frozen quantized path sees x:
+ *     x~ = x * keep * keep_scale,  keep_scale = 1 / (1 - p)
+ *     y  = x deq(W_q)^T + (alpha/r) (x~ A^T) B^T
+ *     dX = dY deq(W_q) + ((alpha/r) (dY B) A) * keep * keep_scale,   dA = (alpha/r) (dY B)^T x~,  dB unchanged in form
+ * keep_mask: uint32 [M, K/32], drawn by the caller; element (m,k) is kept where bit k % 32 of word [m, k/32] is set.
+ * The same mask goes to the forward and to the backward call; t_save / t_saved then hold t = x~ A^T.  keep_mask ==
+ * NULL is no dropout: the calls are then qlora_linear_fwd and qlora_linear_bwd_accumulate.
+ */
+int qlora_linear_fwd_dropout(const void *x, const uint32_t *packed, const void *scales, const uint8_t *zeros,
+                             const void *A, const void *B, const uint32_t *keep_mask, float keep_scale,
+                             void *y, void *t_save,
+                             int M, int N, int K, int bits, int group_size, int rank, float alpha, int dtype,
+                             void *workspace, size_t workspace_bytes, void *stream);
+
+int qlora_linear_bwd_dropout(const void *dy, const void *x, const uint32_t *packed, const void *scales,
+                             const uint8_t *zeros, const void *A, const void *B, const uint32_t *keep_mask,
+                             float keep_scale, const void *t_saved, void *dx, float *dA, float *dB, float beta,
+                             int M, int N, int K, int bits, int group_size, int rank, float alpha, int dtype,
+                             void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Sibling projections at small token counts.  Projections that read the same
  * input (q/k/v of an attention block, gate/up of an MLP; the paper adapts "every
  * linear projection", Appendix C) can be handed over together: one launch

@@ -18,7 +18,8 @@ QLORA_F16, QLORA_BF16 = 0, 1
 STATUS_NAMES = ["QLORA_OK", "QLORA_E_NULL", "QLORA_E_BITS", "QLORA_E_SHAPE", "QLORA_E_GROUP", "QLORA_E_RANK",
                 "QLORA_E_DTYPE", "QLORA_E_ALIGN", "QLORA_E_WORKSPACE", "QLORA_E_HIP"]
 EXPORTS = ["qlora_status_string", "qlora_packed_words", "qlora_workspace_bytes", "qlora_pack", "qlora_unpack",
-           "qlora_linear_fwd", "qlora_linear_bwd", "qlora_linear_bwd_accumulate", "qlora_siblings_workspace_bytes", "qlora_linear_fwd_siblings",
+           "qlora_linear_fwd", "qlora_linear_bwd", "qlora_linear_bwd_accumulate", "qlora_linear_fwd_dropout",
+           "qlora_linear_bwd_dropout", "qlora_siblings_workspace_bytes", "qlora_linear_fwd_siblings",
            "qlora_linear_bwd_siblings", "qlora_lrec_workspace_bytes", "qlora_lrec_loss", "qlora_profile_gemm"]
 MAX_SIBLINGS, SIBLINGS_MAX_M = 4, 16
 
@@ -62,6 +63,10 @@ def load() -> ctypes.CDLL:
     lib.qlora_profile_gemm.argtypes = [vp, vp]
     lib.qlora_linear_bwd_accumulate.restype = c_int
     lib.qlora_linear_bwd_accumulate.argtypes = [vp] * 11 + [f32] + [c_int] * 6 + [f32, c_int, vp, c_sz, vp]
+    lib.qlora_linear_fwd_dropout.restype = c_int
+    lib.qlora_linear_fwd_dropout.argtypes = [vp] * 7 + [f32] + [vp] * 2 + [c_int] * 6 + [f32, c_int, vp, c_sz, vp]
+    lib.qlora_linear_bwd_dropout.restype = c_int
+    lib.qlora_linear_bwd_dropout.argtypes = [vp] * 8 + [f32] + [vp] * 4 + [f32] + [c_int] * 6 + [f32, c_int, vp, c_sz, vp]
     lib.qlora_siblings_workspace_bytes.restype = c_sz
     lib.qlora_siblings_workspace_bytes.argtypes = [c_int, vp] + [c_int] * 5
     lib.qlora_linear_fwd_siblings.restype = c_int
@@ -234,4 +239,33 @@ def qlora_linear_bwd_accumulate(dy, x, packed, scales, zeros, A, B, t_saved, dx,
                                             workspace_bytes, _stream(stream))
     if check and st != 0:
         raise QLoraError(st, "qlora_linear_bwd_accumulate")
+    return st
+
+
+def qlora_linear_fwd_dropout(x, packed, scales, zeros, A, B, keep_mask, keep_scale: float, y, t_save, M: int, N: int,
+                             K: int, bits: int, group_size: int, rank: int, alpha: float, dtype: int, workspace,
+                             workspace_bytes: Optional[int] = None, stream=None, check: bool = True) -> int:
+    if workspace_bytes is None:
+        workspace_bytes = _nbytes(workspace)
+    st = load().qlora_linear_fwd_dropout(_ptr(x), _ptr(packed), _ptr(scales), _ptr(zeros), _ptr(A), _ptr(B),
+                                         _ptr(keep_mask), float(keep_scale), _ptr(y), _ptr(t_save), M, N, K, bits,
+                                         group_size, rank, float(alpha), dtype, _ptr(workspace), workspace_bytes,
+                                         _stream(stream))
+    if check and st != 0:
+        raise QLoraError(st, "qlora_linear_fwd_dropout")
+    return st
+
+
+def qlora_linear_bwd_dropout(dy, x, packed, scales, zeros, A, B, keep_mask, keep_scale: float, t_saved, dx, dA, dB,
+                             beta: float, M: int, N: int, K: int, bits: int, group_size: int, rank: int, alpha: float,
+                             dtype: int, workspace, workspace_bytes: Optional[int] = None, stream=None,
+                             check: bool = True) -> int:
+    if workspace_bytes is None:
+        workspace_bytes = _nbytes(workspace)
+    st = load().qlora_linear_bwd_dropout(_ptr(dy), _ptr(x), _ptr(packed), _ptr(scales), _ptr(zeros), _ptr(A), _ptr(B),
+                                         _ptr(keep_mask), float(keep_scale), _ptr(t_saved), _ptr(dx), _ptr(dA),
+                                         _ptr(dB), float(beta), M, N, K, bits, group_size, rank, float(alpha), dtype,
+                                         _ptr(workspace), workspace_bytes, _stream(stream))
+    if check and st != 0:
+        raise QLoraError(st, "qlora_linear_bwd_dropout")
     return st

@@ -20,6 +20,19 @@ __device__ __forceinline__ float4_t mfma16(u16x8_t a, u16x8_t b, float4_t c)
                                                       0, 0, 0);
 }
 
+// LoRA dropout (Appendix B trains with a rate of 0.05; it acts on the input of the low-rank branch only): the keep
+// mask is one bit per element of x, bit k % 32 of word k / 32 of the row, i.e. one byte per 8-element fragment.
+__device__ __forceinline__ u16x8_t keep_halves(u16x8_t v, uint32_t keep_byte)
+{
+    u32x4_t w = __builtin_bit_cast(u32x4_t, v);
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        const uint32_t lo = (keep_byte >> (2 * d)) & 1u, hi = (keep_byte >> (2 * d + 1)) & 1u;
+        w[d] &= lo * 0xFFFFu + hi * 0xFFFF0000u;
+    }
+    return __builtin_bit_cast(u16x8_t, w);
+}
+
 // ------------------------------------------------------------------------------------------------------------
 // out[M,r] = act[M,C] * small[r,C]^T        (t = x A^T with small = A;  u = dY B with small = B^T)
 //
@@ -30,16 +43,19 @@ __device__ __forceinline__ float4_t mfma16(u16x8_t a, u16x8_t b, float4_t c)
 constexpr int SK_WAVES = 8;
 constexpr int SK_UNROLL = 16;
 
-template <bool BF16, int RG>   // RG = ceil(r / 16)
+// MASKED: act is x under LoRA dropout: out = keep_scale * (x * keep) small^T, keep one byte per fragment [M, C/8]
+template <bool BF16, int RG, bool MASKED>   // RG = ceil(r / 16)
 __global__ __launch_bounds__(SK_WAVES * 64) void skinny_rows_kernel(const uint16_t *__restrict__ act,
                                                                    const uint16_t *__restrict__ small,
-                                                                   uint16_t *__restrict__ out, int M, int C, int r)
+                                                                   uint16_t *__restrict__ out, int M, int C, int r,
+                                                                   const uint8_t *__restrict__ keep, float keep_scale)
 {
     __shared__ float red[SK_WAVES][RG][16][17];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m0 = blockIdx.x * 16;
     const int li = lane & 15, q = lane >> 4;
     const uint16_t *arow = act + (long)min(m0 + li, M - 1) * C + q * 8;
+    const uint8_t *krow = MASKED ? keep + (long)min(m0 + li, M - 1) * (C / 8) + q : nullptr;
     const uint16_t *srow[RG];
     bool sval[RG];
 #pragma unroll
@@ -60,6 +76,7 @@ __global__ __launch_bounds__(SK_WAVES * 64) void skinny_rows_kernel(const uint16
             const bool in = k + q * 8 < C;
             const int kk = in ? k : 0;
             xa[uu] = *(const u16x8_t *)(arow + kk);
+            if constexpr (MASKED) xa[uu] = keep_halves(xa[uu], krow[(kk >> 3)]);
             if (!in) xa[uu] = u16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
             for (int g = 0; g < RG; ++g) {
@@ -83,6 +100,7 @@ __global__ __launch_bounds__(SK_WAVES * 64) void skinny_rows_kernel(const uint16
         float s = 0.f;
 #pragma unroll
         for (int w = 0; w < SK_WAVES; ++w) s += red[w][g][row][col];
+        if constexpr (MASKED) s *= keep_scale;
         if (m0 + row < M && g * 16 + col < r) out[(long)(m0 + row) * r + g * 16 + col] = to16<BF16>(s);
     }
 }
@@ -117,7 +135,8 @@ struct GradArgs {
     int C[2];
     int nb0;                // column blocks of the first problem
     int M, r, slices;
-    float sc, beta;         // out = beta * out + sc * sum (beta == 0: out is not read)
+    float sc[2], beta;      // out = beta * out + sc * sum (beta == 0: out is not read)
+    const uint8_t *keep;    // LoRA dropout: keep bits of x (the second problem's act), [M, C1/8] bytes, or NULL
 };
 
 template <bool BF16, int RG>
@@ -144,6 +163,7 @@ __global__ __launch_bounds__(256) void adapter_grad_partial_kernel(const GradArg
             const int m = m0 + ch * 32 + rr;
             const bool in = m < M && c0 + cc < C;
             v[ch] = *(const u16x8_t *)(act + (in ? (long)m * C + c0 + cc : 0));
+            if (which && a.keep) v[ch] = keep_halves(v[ch], a.keep[in ? (long)m * (C / 8) + ((c0 + cc) >> 3) : 0]);
             if (!in) v[ch] = u16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
         }
 #pragma unroll
@@ -216,18 +236,19 @@ __global__ __launch_bounds__(256) void adapter_grad_reduce_kernel(const GradArgs
     for (; s < a.slices; ++s) acc += partial[s * stride + idx];
     const int c = (int)(idx / r), j = (int)(idx % r);
     float *dst = a.out[which] + (which ? (long)j * C + c : idx);
-    *dst = a.beta == 0.f ? a.sc * acc : fmaf(a.beta, *dst, a.sc * acc);
+    *dst = a.beta == 0.f ? a.sc[which] * acc : fmaf(a.beta, *dst, a.sc[which] * acc);
 }
 
-template <bool BF16>
-void launch_skinny(const uint16_t *act, const uint16_t *small, uint16_t *out, int M, int C, int r, hipStream_t s)
+template <bool BF16, bool MASKED>
+void launch_skinny(const uint16_t *act, const uint16_t *small, uint16_t *out, int M, int C, int r, const uint8_t *keep,
+                   float keep_scale, hipStream_t s)
 {
     const dim3 grid((M + 15) / 16), block(SK_WAVES * 64);
     switch ((r + 15) / 16) {
-    case 1: hipLaunchKernelGGL((skinny_rows_kernel<BF16, 1>), grid, block, 0, s, act, small, out, M, C, r); break;
-    case 2: hipLaunchKernelGGL((skinny_rows_kernel<BF16, 2>), grid, block, 0, s, act, small, out, M, C, r); break;
-    case 3: hipLaunchKernelGGL((skinny_rows_kernel<BF16, 3>), grid, block, 0, s, act, small, out, M, C, r); break;
-    default: hipLaunchKernelGGL((skinny_rows_kernel<BF16, 4>), grid, block, 0, s, act, small, out, M, C, r); break;
+    case 1: hipLaunchKernelGGL((skinny_rows_kernel<BF16, 1, MASKED>), grid, block, 0, s, act, small, out, M, C, r, keep, keep_scale); break;
+    case 2: hipLaunchKernelGGL((skinny_rows_kernel<BF16, 2, MASKED>), grid, block, 0, s, act, small, out, M, C, r, keep, keep_scale); break;
+    case 3: hipLaunchKernelGGL((skinny_rows_kernel<BF16, 3, MASKED>), grid, block, 0, s, act, small, out, M, C, r, keep, keep_scale); break;
+    default: hipLaunchKernelGGL((skinny_rows_kernel<BF16, 4, MASKED>), grid, block, 0, s, act, small, out, M, C, r, keep, keep_scale); break;
     }
 }
 
@@ -246,12 +267,19 @@ void launch_grad_partial(const GradArgs &a, hipStream_t s)
 
 }  // namespace
 
-void launch_lora_down(const void *x, const void *A, void *t, int M, int K, int r, bool bf16, hipStream_t s)
+void launch_lora_down(const void *x, const void *A, void *t, int M, int K, int r, bool bf16, const uint32_t *keep,
+                      float keep_scale, hipStream_t s)
 {
-    if (bf16)
-        launch_skinny<true>((const uint16_t *)x, (const uint16_t *)A, (uint16_t *)t, M, K, r, s);
-    else
-        launch_skinny<false>((const uint16_t *)x, (const uint16_t *)A, (uint16_t *)t, M, K, r, s);
+    const uint16_t *xp = (const uint16_t *)x, *Ap = (const uint16_t *)A;
+    uint16_t *tp = (uint16_t *)t;
+    const uint8_t *kb = (const uint8_t *)keep;
+    if (keep) {
+        if (bf16) launch_skinny<true, true>(xp, Ap, tp, M, K, r, kb, keep_scale, s);
+        else launch_skinny<false, true>(xp, Ap, tp, M, K, r, kb, keep_scale, s);
+    } else {
+        if (bf16) launch_skinny<true, false>(xp, Ap, tp, M, K, r, nullptr, 1.f, s);
+        else launch_skinny<false, false>(xp, Ap, tp, M, K, r, nullptr, 1.f, s);
+    }
 }
 
 void launch_lora_u(const void *dy, const void *B, void *bt, void *u, int M, int N, int r, bool bf16, hipStream_t s)
@@ -260,9 +288,66 @@ void launch_lora_u(const void *dy, const void *B, void *bt, void *u, int M, int 
     hipLaunchKernelGGL(transpose_small_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (const uint16_t *)B,
                        (uint16_t *)bt, N, r);
     if (bf16)
-        launch_skinny<true>((const uint16_t *)dy, (const uint16_t *)bt, (uint16_t *)u, M, N, r, s);
+        launch_skinny<true, false>((const uint16_t *)dy, (const uint16_t *)bt, (uint16_t *)u, M, N, r, nullptr, 1.f, s);
     else
-        launch_skinny<false>((const uint16_t *)dy, (const uint16_t *)bt, (uint16_t *)u, M, N, r, s);
+        launch_skinny<false, false>((const uint16_t *)dy, (const uint16_t *)bt, (uint16_t *)u, M, N, r, nullptr, 1.f, s);
+}
+
+// dX[m,k] += f[m,k] * sum_j u[m,j] A[j,k],  f = sc * keep_scale where the keep bit of (m,k) is set, else 0:
+// the adapter's share of dX under LoRA dropout, added to the base product the GEMM left in dX (which then carried
+// no adapter steps).  A workgroup owns 64 rows x 256 columns; u and the A columns are staged in LDS.
+template <bool BF16>
+__global__ __launch_bounds__(256) void lora_dx_masked_kernel(uint16_t *__restrict__ dx, const uint16_t *__restrict__ u,
+                                                             const uint16_t *__restrict__ A,
+                                                             const uint8_t *__restrict__ keep, int M, int K, int r,
+                                                             float f)
+{
+    __shared__ float us[64][64 + 1];
+    __shared__ uint16_t As[64][256 + 8];
+    const int m0 = blockIdx.y * 64, k0 = blockIdx.x * 256, tid = threadIdx.x;
+    for (int e = tid; e < 64 * r; e += 256) {
+        const int m = e / r, j = e % r;
+        us[m][j] = m0 + m < M ? cvt16<BF16>(u[(long)(m0 + m) * r + j]) : 0.f;
+    }
+    for (int e = tid; e < r * 32; e += 256) {              // A rows of this column block, 8 columns at a time
+        const int j = e >> 5, c = (e & 31) * 8;
+        u16x8_t v = u16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
+        if (k0 + c < K) v = *(const u16x8_t *)(A + (long)j * K + k0 + c);
+        *(u16x8_t *)&As[j][c] = v;
+    }
+    __syncthreads();
+    const int c = (tid & 31) * 8;                          // this thread's 8 columns; rows tid/32, +8, ...
+    if (k0 + c >= K) return;
+    for (int m = tid >> 5; m < 64 && m0 + m < M; m += 8) {
+        uint16_t *p = dx + (long)(m0 + m) * K + k0 + c;
+        u16x8_t d = *(const u16x8_t *)p;
+        const uint32_t kb = keep[(long)(m0 + m) * (K / 8) + ((k0 + c) >> 3)];
+        float lo[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) lo[e] = 0.f;
+        for (int j = 0; j < r; ++j) {
+            const float uj = us[m][j];
+            const u16x8_t av = *(const u16x8_t *)&As[j][c];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) lo[e] = fmaf(uj, cvt16<BF16>(av[e]), lo[e]);
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            if ((kb >> e) & 1u) d[e] = to16<BF16>(fmaf(f, lo[e], cvt16<BF16>(d[e])));
+        *(u16x8_t *)p = d;
+    }
+}
+
+void launch_lora_dx_masked(void *dx, const void *u, const void *A, const uint32_t *keep, int M, int K, int r, float f,
+                           bool bf16, hipStream_t s)
+{
+    const dim3 grid((K + 255) / 256, (M + 63) / 64), block(256);
+    if (bf16)
+        hipLaunchKernelGGL(lora_dx_masked_kernel<true>, grid, block, 0, s, (uint16_t *)dx, (const uint16_t *)u,
+                           (const uint16_t *)A, (const uint8_t *)keep, M, K, r, f);
+    else
+        hipLaunchKernelGGL(lora_dx_masked_kernel<false>, grid, block, 0, s, (uint16_t *)dx, (const uint16_t *)u,
+                           (const uint16_t *)A, (const uint8_t *)keep, M, K, r, f);
 }
 
 int adapter_grad_slices(int M, int r)
@@ -273,7 +358,8 @@ int adapter_grad_slices(int M, int r)
 }
 
 void launch_adapter_grads(const void *dy, const void *t, const void *x, const void *u, float *dB, float *dA,
-                          float *partial, int M, int N, int K, int r, float sc, float beta, bool bf16, hipStream_t s)
+                          float *partial, int M, int N, int K, int r, float sc, float beta, const uint32_t *keep,
+                          float keep_scale, bool bf16, hipStream_t s)
 {
     const int slices = adapter_grad_slices(M, r);
     GradArgs a;
@@ -291,8 +377,10 @@ void launch_adapter_grads(const void *dy, const void *t, const void *x, const vo
     a.M = M;
     a.r = r;
     a.slices = slices;
-    a.sc = sc;
+    a.sc[0] = sc;
+    a.sc[1] = keep ? sc * keep_scale : sc;
     a.beta = beta;
+    a.keep = (const uint8_t *)keep;
     if (bf16)
         launch_grad_partial<true>(a, s);
     else

@@ -145,31 +145,42 @@ int qlora_linear_fwd(const void *x, const uint32_t *packed, const void *scales, 
                      const void *B, void *y, void *t_save, int M, int N, int K, int bits, int group_size, int rank,
                      float alpha, int dtype, void *workspace, size_t workspace_bytes, void *stream)
 {
+    return qlora_linear_fwd_dropout(x, packed, scales, zeros, A, B, nullptr, 1.f, y, t_save, M, N, K, bits, group_size,
+                                    rank, alpha, dtype, workspace, workspace_bytes, stream);
+}
+
+int qlora_linear_fwd_dropout(const void *x, const uint32_t *packed, const void *scales, const uint8_t *zeros,
+                             const void *A, const void *B, const uint32_t *keep_mask, float keep_scale, void *y,
+                             void *t_save, int M, int N, int K, int bits, int group_size, int rank, float alpha,
+                             int dtype, void *workspace, size_t workspace_bytes, void *stream)
+{
     const int st = check_problem(M, N, K, bits, group_size, rank, dtype);
     if (st != QLORA_OK) return st;
     if (!x || !packed || !scales || !zeros || !y) return QLORA_E_NULL;
     if (rank > 0 && (!A || !B)) return QLORA_E_NULL;
     if (misaligned(x) || misaligned(packed) || misaligned(scales) || misaligned(zeros) || misaligned(y) ||
-        misaligned(A) || misaligned(B) || misaligned(t_save) || misaligned(workspace))
+        misaligned(A) || misaligned(B) || misaligned(t_save) || misaligned(workspace) || misaligned(keep_mask))
         return QLORA_E_ALIGN;
     const Workspace w = carve(M, N, K, rank, bits);
     if (!workspace || workspace_bytes < w.total) return QLORA_E_WORKSPACE;
+    if (rank == 0) keep_mask = nullptr;         // no adapter branch: nothing is dropped
 
     const hipStream_t s = (hipStream_t)stream;
     const Problem p{M, N, K, bits, group_size, rank, rank > 0 ? alpha / (float)rank : 0.f, dtype == QLORA_BF16};
     char *ws = (char *)workspace;
     if (M <= SMALL_M_FWD_MAX) {
-        // one launch: the weight-streaming kernel also forms t (ranks up to 32)
+        // one launch: the weight-streaming kernel also forms t (ranks up to 32, no dropout)
         void *t = rank > 0 ? (t_save ? t_save : (void *)(ws + w.t_off)) : nullptr;
-        if (rank > 0 && !fwd_small_computes_t(rank)) launch_lora_down(x, A, t, M, K, rank, p.bf16, s);
+        const bool t_first = rank > 0 && (keep_mask || !fwd_small_computes_t(rank));
+        if (t_first) launch_lora_down(x, A, t, M, K, rank, p.bf16, keep_mask, keep_scale, s);
         GemmTimer timer(s);
         const void *tc = t;
-        launch_fwd_small(p, 1, x, &packed, &scales, &zeros, &A, &B, &tc, &t, &y, &N, s);
+        launch_fwd_small(p, 1, x, &packed, &scales, &zeros, &A, &B, &tc, &t, &y, &N, t_first, s);
     } else {
         void *t = nullptr;
         if (rank > 0) {
             t = t_save ? t_save : (void *)(ws + w.t_off);
-            launch_lora_down(x, A, t, M, K, rank, p.bf16, s);
+            launch_lora_down(x, A, t, M, K, rank, p.bf16, keep_mask, keep_scale, s);
         }
         GemmTimer timer(s);
         launch_fwd_mfma(p, x, packed, scales, zeros, t, B, y, s);
@@ -191,16 +202,27 @@ int qlora_linear_bwd_accumulate(const void *dy, const void *x, const uint32_t *p
                                 float *dA, float *dB, float beta, int M, int N, int K, int bits, int group_size,
                                 int rank, float alpha, int dtype, void *workspace, size_t workspace_bytes, void *stream)
 {
+    return qlora_linear_bwd_dropout(dy, x, packed, scales, zeros, A, B, nullptr, 1.f, t_saved, dx, dA, dB, beta, M, N,
+                                    K, bits, group_size, rank, alpha, dtype, workspace, workspace_bytes, stream);
+}
+
+int qlora_linear_bwd_dropout(const void *dy, const void *x, const uint32_t *packed, const void *scales,
+                             const uint8_t *zeros, const void *A, const void *B, const uint32_t *keep_mask,
+                             float keep_scale, const void *t_saved, void *dx, float *dA, float *dB, float beta, int M,
+                             int N, int K, int bits, int group_size, int rank, float alpha, int dtype,
+                             void *workspace, size_t workspace_bytes, void *stream)
+{
     const int st = check_problem(M, N, K, bits, group_size, rank, dtype);
     if (st != QLORA_OK) return st;
     if (!dy || !packed || !scales || !zeros || !dx) return QLORA_E_NULL;
     if (rank > 0 && (!x || !A || !B || !dA || !dB)) return QLORA_E_NULL;
     if (misaligned(dy) || misaligned(x) || misaligned(packed) || misaligned(scales) || misaligned(zeros) ||
         misaligned(A) || misaligned(B) || misaligned(t_saved) || misaligned(dx) || misaligned(dA) || misaligned(dB) ||
-        misaligned(workspace))
+        misaligned(workspace) || misaligned(keep_mask))
         return QLORA_E_ALIGN;
     const Workspace w = carve(M, N, K, rank, bits);
     if (!workspace || workspace_bytes < w.total) return QLORA_E_WORKSPACE;
+    if (rank == 0) keep_mask = nullptr;
 
     const hipStream_t s = (hipStream_t)stream;
     const Problem p{M, N, K, bits, group_size, rank, rank > 0 ? alpha / (float)rank : 0.f, dtype == QLORA_BF16};
@@ -209,12 +231,12 @@ int qlora_linear_bwd_accumulate(const void *dy, const void *x, const uint32_t *p
         // two launches: partial dX and u over row slices of the weight, then the sums, dA and dB
         const void *t = t_saved;
         if (rank > 0 && !t) {
-            launch_lora_down(x, A, ws + w.t_off, M, K, rank, p.bf16, s);
+            launch_lora_down(x, A, ws + w.t_off, M, K, rank, p.bf16, keep_mask, keep_scale, s);
             t = ws + w.t_off;
         }
         GemmTimer timer(s);
         launch_bwd_small(p, 1, &dy, x, &packed, &scales, &zeros, &A, &B, &t, dx, &dA, &dB, &N,
-                         (float *)(ws + w.partial_off), (float *)(ws + w.upartial_off), beta, s);
+                         (float *)(ws + w.partial_off), (float *)(ws + w.upartial_off), beta, keep_mask, keep_scale, s);
         return hip_status();
     }
     void *u = nullptr;
@@ -224,16 +246,24 @@ int qlora_linear_bwd_accumulate(const void *dy, const void *x, const uint32_t *p
     }
     {
         GemmTimer timer(s);
-        launch_bwd_dx_mfma(p, dy, packed, scales, zeros, u, A, dx, s);
+        if (keep_mask) {        // the GEMM leaves the base product; the adapter's masked share is added afterwards
+            Problem base = p;
+            base.r = 0;
+            base.sc = 0.f;
+            launch_bwd_dx_mfma(base, dy, packed, scales, zeros, nullptr, nullptr, dx, s);
+        } else {
+            launch_bwd_dx_mfma(p, dy, packed, scales, zeros, u, A, dx, s);
+        }
     }
+    if (keep_mask) launch_lora_dx_masked(dx, u, A, keep_mask, M, K, rank, p.sc * keep_scale, p.bf16, s);
     if (rank > 0) {
         const void *t = t_saved;
         if (!t) {
-            launch_lora_down(x, A, ws + w.t_off, M, K, rank, p.bf16, s);
+            launch_lora_down(x, A, ws + w.t_off, M, K, rank, p.bf16, keep_mask, keep_scale, s);
             t = ws + w.t_off;
         }
         float *partial = (float *)(ws + w.partial_off);
-        launch_adapter_grads(dy, t, x, u, dB, dA, partial, M, N, K, rank, p.sc, beta, p.bf16, s);
+        launch_adapter_grads(dy, t, x, u, dB, dA, partial, M, N, K, rank, p.sc, beta, keep_mask, keep_scale, p.bf16, s);
     }
     return hip_status();
 }
@@ -312,10 +342,10 @@ int qlora_linear_fwd_siblings(int count, const void *x, const uint32_t *const *p
     for (int i = 0; i < count && rank > 0; ++i) {
         t[i] = (t_save && t_save[i]) ? t_save[i] : (void *)(ws + w.t_off[i]);
         tc[i] = t[i];
-        if (!fwd_small_computes_t(rank)) launch_lora_down(x, A[i], t[i], M, K, rank, p.bf16, s);
+        if (!fwd_small_computes_t(rank)) launch_lora_down(x, A[i], t[i], M, K, rank, p.bf16, nullptr, 1.f, s);
     }
     GemmTimer timer(s);
-    launch_fwd_small(p, count, x, packed, scales, zeros, A, B, tc, t, y, N, s);
+    launch_fwd_small(p, count, x, packed, scales, zeros, A, B, tc, t, y, N, false, s);
     return hip_status();
 }
 
@@ -348,13 +378,13 @@ int qlora_linear_bwd_siblings(int count, const void *const *dy, const void *x, c
     for (int i = 0; i < count && rank > 0; ++i) {
         t[i] = t_saved ? t_saved[i] : nullptr;
         if (!t[i]) {
-            launch_lora_down(x, A[i], ws + w.t_off[i], M, K, rank, p.bf16, s);
+            launch_lora_down(x, A[i], ws + w.t_off[i], M, K, rank, p.bf16, nullptr, 1.f, s);
             t[i] = ws + w.t_off[i];
         }
     }
     GemmTimer timer(s);
     launch_bwd_small(p, count, dy, x, packed, scales, zeros, A, B, t, dx, dA, dB, N, (float *)(ws + w.partial_off),
-                     (float *)(ws + w.upartial_off), 0.f, s);
+                     (float *)(ws + w.upartial_off), 0.f, nullptr, 1.f, s);
     return hip_status();
 }
 

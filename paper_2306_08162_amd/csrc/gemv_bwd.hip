@@ -293,6 +293,8 @@ struct FinishArgs {
     float *dA, *dB;
     int M, N, K, r, slices, xb, ab;
     float sc, beta;      // dA = beta * dA + ..., dB likewise (beta == 0: they are not read)
+    const uint8_t *keep; // LoRA dropout: keep bits of x as bytes [M, K/8], or NULL
+    float keep_scale;
 };
 
 template <bool BF16>
@@ -334,13 +336,18 @@ __global__ __launch_bounds__(256) void gemv_bwd_finish_kernel(const FinishArgs a
         for (; s < a.slices; ++s) v += a.partial[s * stride + idx];
         float lo = 0.f;
         for (int j = 0; j < r; ++j) lo += side[m][j] * cvt16<BF16>(a.A[(long)j * K + k]);
+        if (a.keep) lo = ((a.keep[(long)m * (K / 8) + (k >> 3)] >> (k & 7)) & 1) ? lo * a.keep_scale : 0.f;
         a.dx[idx] = to16<BF16>(v + a.sc * lo);
     } else if (b < a.xb + a.ab) {
         const long idx = (long)(b - a.xb) * 256 + threadIdx.x;
         if (idx >= (long)r * K) return;
         const int j = (int)(idx / K), k = (int)(idx % K);
         float v = 0.f;
-        for (int m = 0; m < M; ++m) v += side[m][j] * cvt16<BF16>(a.x[(long)m * K + k]);
+        for (int m = 0; m < M; ++m) {
+            float xv = cvt16<BF16>(a.x[(long)m * K + k]);
+            if (a.keep) xv = ((a.keep[(long)m * (K / 8) + (k >> 3)] >> (k & 7)) & 1) ? xv * a.keep_scale : 0.f;
+            v += side[m][j] * xv;
+        }
         a.dA[idx] = a.beta == 0.f ? a.sc * v : fmaf(a.beta, a.dA[idx], a.sc * v);
     } else {
         const long idx = (long)(b - a.xb - a.ab) * 256 + threadIdx.x;
@@ -517,7 +524,8 @@ int gemv_bwd_slices_siblings(int count, const int *N, int K, int bits, int *slic
 void launch_bwd_small(const Problem &p, int count, const void *const *dy, const void *x,
                       const uint32_t *const *packed, const void *const *scales, const uint8_t *const *zeros,
                       const void *const *A, const void *const *B, const void *const *t, void *dx, float *const *dA,
-                      float *const *dB, const int *N, float *partial, float *upartial, float beta, hipStream_t s)
+                      float *const *dB, const int *N, float *partial, float *upartial, float beta, const uint32_t *keep,
+                      float keep_scale, hipStream_t s)
 {
     int slices[MAX_SIBLINGS];
     const int total = gemv_bwd_slices_siblings(count, N, p.K, p.bits, slices);
@@ -538,7 +546,8 @@ void launch_bwd_small(const Problem &p, int count, const void *const *dy, const 
         const int bb = (int)(((long)p.r * N[0] + 255) / 256);
         const FinishArgs f{partial, upartial, (const uint16_t *)(A ? A[0] : nullptr), (const uint16_t *)x,
                            (const uint16_t *)dy[0], (const uint16_t *)(t ? t[0] : nullptr), (uint16_t *)dx,
-                           dA ? dA[0] : nullptr, dB ? dB[0] : nullptr, p.M, N[0], p.K, p.r, total, xb, ab, p.sc, beta};
+                           dA ? dA[0] : nullptr, dB ? dB[0] : nullptr, p.M, N[0], p.K, p.r, total, xb, ab, p.sc, beta,
+                           (const uint8_t *)keep, keep_scale};
         if (p.bf16)
             hipLaunchKernelGGL((gemv_bwd_finish_kernel<true>), dim3(xb + ab + bb), dim3(256), 0, s, f);
         else

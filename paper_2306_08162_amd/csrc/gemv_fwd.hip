@@ -19,9 +19,9 @@ bool fwd_small_computes_t(int rank) { return rank > 0 && rank <= 32; }
 void launch_fwd_small(const Problem &p, int count, const void *x, const uint32_t *const *packed,
                       const void *const *scales, const uint8_t *const *zeros, const void *const *A,
                       const void *const *B, const void *const *t_in, void *const *t_out, void *const *y, const int *N,
-                      hipStream_t s)
+                      bool t_given, hipStream_t s)
 {
-    const bool fused = fwd_small_computes_t(p.r);
+    const bool fused = fwd_small_computes_t(p.r) && !t_given;
     FwdMulti m{};
     m.count = count;
     for (int i = 0; i < count; ++i)

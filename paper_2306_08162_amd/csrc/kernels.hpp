@@ -19,16 +19,23 @@ void launch_pack(const uint8_t *codes, uint32_t *packed, int N, int K, int bits,
 void launch_unpack(const uint32_t *packed, uint8_t *codes, int N, int K, int bits, hipStream_t s);
 
 // adapters.hip -- the rank-r side products and the adapter gradients
-// t[M,r] = x[M,K] A[r,K]^T
-void launch_lora_down(const void *x, const void *A, void *t, int M, int K, int r, bool bf16, hipStream_t s);
+// t[M,r] = x[M,K] A[r,K]^T; with a keep mask (LoRA dropout, one bit per element of x, bit k % 32 of word k / 32 of
+// the row) t = keep_scale * (x * keep) A^T
+void launch_lora_down(const void *x, const void *A, void *t, int M, int K, int r, bool bf16, const uint32_t *keep,
+                      float keep_scale, hipStream_t s);
+// dx[m,k] += f * keep[m,k] * sum_j u[m,j] A[j,k]: the adapter's share of dX under dropout, on top of the base product
+void launch_lora_dx_masked(void *dx, const void *u, const void *A, const uint32_t *keep, int M, int K, int r, float f,
+                           bool bf16, hipStream_t s);
 // u[M,r] = dy[M,N] B[N,r]; bt is scratch for B^T (N*r 16-bit values)
 void launch_lora_u(const void *dy, const void *B, void *bt, void *u, int M, int N, int r, bool bf16, hipStream_t s);
 // Number of token slices the adapter-gradient reductions are cut into (fixed by the shape alone).
 int adapter_grad_slices(int M, int r);
 // dB[N,r] = sc * dy[M,N]^T t[M,r] and dA[r,K] = sc * u[M,r]^T x[M,K], two launches for both (slice partial sums,
 // then their fixed-order reduction); partial holds slices*(N+K)*r floats.  beta != 0: dB = beta*dB + ..., dA likewise.
+// keep != NULL (LoRA dropout): x stands for keep_scale * x * keep in dA.
 void launch_adapter_grads(const void *dy, const void *t, const void *x, const void *u, float *dB, float *dA,
-                          float *partial, int M, int N, int K, int r, float sc, float beta, bool bf16, hipStream_t s);
+                          float *partial, int M, int N, int K, int r, float sc, float beta, const uint32_t *keep,
+                          float keep_scale, bool bf16, hipStream_t s);
 
 // gemm_mfma.hip -- tiled MFMA GEMMs with fused dequantisation (any accepted shape)
 void launch_fwd_mfma(const Problem &p, const void *x, const uint32_t *packed, const void *scales,
@@ -40,25 +47,28 @@ void launch_bwd_dx_mfma(const Problem &p, const void *dy, const uint32_t *packed
 constexpr int SMALL_M_FWD_MAX = 64;   // forward kernel handles up to four 16-row token blocks
 constexpr int SMALL_M_BWD_MAX = 16;   // backward kernel keeps one 16-row token block
 int gemv_bwd_slices(int N, int K, int bits);   // row slices of the backward kernel
-bool fwd_small_computes_t(int rank);           // true: the forward kernel forms t = x A^T itself
+bool fwd_small_computes_t(int rank);           // true: the forward kernel forms t = x A^T itself (unless t is handed in)
 constexpr int MAX_SIBLINGS = 4;                // projections that read the same x, served by one launch
 // `count` sibling projections (same x, M, K, code width, grouping, rank; own weights, adapters, N and outputs):
 // y[i] (and t_out[i], if not NULL and the kernel forms t) from one launch up to 16 token rows, one launch each above;
-// t_in[i] is used when the kernel does not form t.  The arrays are host arrays of `count` device pointers.
+// t_in[i] is used when the kernel does not form t (ranks above 32, or t_given: t was computed beforehand, e.g. under
+// dropout).  The arrays are host arrays of `count` device pointers.
 void launch_fwd_small(const Problem &p, int count, const void *x, const uint32_t *const *packed,
                       const void *const *scales, const uint8_t *const *zeros, const void *const *A,
                       const void *const *B, const void *const *t_in, void *const *t_out, void *const *y, const int *N,
-                      hipStream_t s);
+                      bool t_given, hipStream_t s);
 // Row slices of the backward kernel for `count` sibling projections launched together: slices[i] for each, the
 // total returned (count == 1: gemv_bwd_slices).
 int gemv_bwd_slices_siblings(int count, const int *N, int K, int bits, int *slices);
 // dx (the sum over the siblings), dA[i], dB[i] from two launches; partial holds total_slices*M*K floats, upartial
 // total_slices*1024 floats; t may be NULL if r == 0; beta != 0 accumulates into dA[i], dB[i] (beta*old + new).  The
-// arrays are host arrays of `count` device pointers.
+// arrays are host arrays of `count` device pointers.  keep != NULL (LoRA dropout, single projection only): the
+// adapter's share of dX is multiplied by keep_scale * keep and x stands for keep_scale * x * keep in dA.
 void launch_bwd_small(const Problem &p, int count, const void *const *dy, const void *x,
                       const uint32_t *const *packed, const void *const *scales, const uint8_t *const *zeros,
                       const void *const *A, const void *const *B, const void *const *t, void *dx, float *const *dA,
-                      float *const *dB, const int *N, float *partial, float *upartial, float beta, hipStream_t s);
+                      float *const *dB, const int *N, float *partial, float *upartial, float beta, const uint32_t *keep,
+                      float keep_scale, hipStream_t s);
 
 // loss.hip -- the LREC objective (KL student || teacher + next-token CE, mean over tokens) and its gradient
 // kl, ce (per token) and grad may be NULL; tok receives lambda_kl*KL + lambda_ce*CE per token, loss_mean their mean

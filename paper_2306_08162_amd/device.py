@@ -75,6 +75,22 @@ class DeviceLayer:
                                        c.M, c.N, c.K, c.bits, c.group_size, c.rank, c.alpha, self.dtype_flag,
                                        self.workspace, stream=stream)
 
+    def forward_dropout(self, keep_mask, keep_scale: float, save_t: bool = True, stream=None):
+        """keep_mask: int32 tensor [M, K/32] of keep bits (bit k % 32 of word k / 32)."""
+        c = self.cfg
+        ql.qlora_linear_fwd_dropout(self.x, self.packed, self.scales, self.zeros, self.A, self.B, keep_mask,
+                                    keep_scale, self.y, self.t if (save_t and c.rank) else None, c.M, c.N, c.K,
+                                    c.bits, c.group_size, c.rank, c.alpha, self.dtype_flag, self.workspace,
+                                    stream=stream)
+
+    def backward_dropout(self, keep_mask, keep_scale: float, use_saved_t: bool = True, beta: float = 0.0, stream=None):
+        c = self.cfg
+        ql.qlora_linear_bwd_dropout(self.dy, self.x, self.packed, self.scales, self.zeros, self.A, self.B, keep_mask,
+                                    keep_scale, self.t if (use_saved_t and c.rank) else None, self.dx,
+                                    self.dA if c.rank else None, self.dB if c.rank else None, beta,
+                                    c.M, c.N, c.K, c.bits, c.group_size, c.rank, c.alpha, self.dtype_flag,
+                                    self.workspace, stream=stream)
+
     def unpack(self) -> np.ndarray:
         c = self.cfg
         out = torch.empty((c.N, c.K), dtype=torch.uint8, device=self.device)

@@ -171,6 +171,29 @@ def test_bwd_accumulate_argument_errors():
     assert call(wsb=0) == E["QLORA_E_WORKSPACE"]
 
 
+def test_dropout_argument_errors():
+    def fwd(mask=FAKE, **kw):
+        d = dict(M=16, N=64, K=128, bits=4, G=64, rank=8, dtype=0, wsb=1 << 30)
+        d.update(kw)
+        return ql.qlora_linear_fwd_dropout(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, mask, 1.0 / 0.95, FAKE, FAKE, d["M"],
+                                           d["N"], d["K"], d["bits"], d["G"], d["rank"], 16.0, d["dtype"], FAKE,
+                                           d["wsb"], stream=0, check=False)
+
+    def bwd(mask=FAKE, **kw):
+        d = dict(M=16, N=64, K=128, bits=4, G=64, rank=8, dtype=0, wsb=1 << 30)
+        d.update(kw)
+        return ql.qlora_linear_bwd_dropout(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, mask, 1.0 / 0.95, FAKE, FAKE, FAKE,
+                                           FAKE, 0.0, d["M"], d["N"], d["K"], d["bits"], d["G"], d["rank"], 16.0,
+                                           d["dtype"], FAKE, d["wsb"], stream=0, check=False)
+
+    for call in (fwd, bwd):
+        assert call(bits=7) == E["QLORA_E_BITS"]
+        assert call(K=100) == E["QLORA_E_SHAPE"]
+        assert call(mask=ODD) == E["QLORA_E_ALIGN"]
+        assert call(wsb=0) == E["QLORA_E_WORKSPACE"]
+        assert call(mask=None, wsb=0) == E["QLORA_E_WORKSPACE"]       # no mask is allowed: plain layer
+
+
 def test_sibling_workspace_bytes():
     assert ql.qlora_siblings_workspace_bytes([64, 40], 17, 128, 4, 64, 8) == 0
     assert ql.qlora_siblings_workspace_bytes([64, 44], 4, 128, 4, 64, 8) == 0
