@@ -97,6 +97,32 @@ def dequant(P: np.ndarray, scales: np.ndarray, zeros: np.ndarray, K: int, bits: 
     return Wd
 
 
+# ------------------------------------------- activation-order checkpoints
+
+def dequant_actorder(codes: np.ndarray, scales: np.ndarray, zeros: np.ndarray, g_idx: np.ndarray) -> np.ndarray:
+    """Wd[n,k] = s[n, g_idx[k]] * (q[n,k] - z[n, g_idx[k]]) in float64.
+
+    Eq. 1 with the per-column group index a GPTQ checkpoint quantized with the
+    "activation order" option carries (App. A): the columns of one group are no
+    longer a run of consecutive columns.  Plain definition, numpy indexing only.
+    """
+    q = _c(codes, np.uint8).astype(np.float64)
+    s = _c(scales, np.float64)
+    z = _c(zeros, np.uint8).astype(np.float64)
+    g = _c(g_idx, np.int64)
+    assert q.shape[1] == g.shape[0] and s.shape == z.shape and s.shape[0] == q.shape[0]
+    return s[:, g] * (q - z[:, g])
+
+
+def actorder_perm(g_idx: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """Stable sort of the columns by group: perm[j] = column that moves to place j, and its inverse."""
+    g = _c(g_idx, np.int64)
+    perm = np.argsort(g, kind="stable").astype(np.int32)
+    inv = np.empty_like(perm)
+    inv[perm] = np.arange(perm.size, dtype=np.int32)
+    return perm, inv
+
+
 # ------------------------------------------------------------ layer passes
 
 def lora_down(x: np.ndarray, A: np.ndarray) -> np.ndarray:

@@ -31,6 +31,7 @@ BASE_SEED = 0x230608162000
 
 # tensor ids (added to the per-config seed)
 T_CODES, T_SCALES, T_ZEROS, T_A, T_B, T_X, T_DY = range(7)
+T_GIDX = 11
 
 
 def splitmix64(seed: int, start: int, count: int) -> np.ndarray:
@@ -162,6 +163,16 @@ def make_inputs(cfg: LayerConfig) -> LayerInputs:
         x=x.reshape(cfg.M, cfg.K),
         dy=dy.reshape(cfg.M, cfg.N),
     )
+
+
+def actorder_g_idx(seed: int, K: int, G: int) -> np.ndarray:
+    """Per-column group index of a checkpoint quantized in activation order (App. A): the columns are visited in a
+    data-dependent order (here a seeded random one) and every G consecutive visits form a group.  int32 [K]."""
+    keys = splitmix64(seed + T_GIDX, 0, K)
+    order = np.argsort(keys, kind="stable")          # order[i] = column visited i-th
+    g_idx = np.empty(K, dtype=np.int32)
+    g_idx[order] = (np.arange(K) // G).astype(np.int32)
+    return g_idx
 
 
 # --- the named workloads ---------------------------------------------------

@@ -403,3 +403,55 @@ def test_layer_oracle_row_subsets_equal_full_rows():
     X = oracle.widen(inp.x, "f16")
     ref = X @ W.T + 2.0 * (X @ oracle.widen(inp.A, "f16").T) @ oracle.widen(inp.B, "f16").T
     assert _rel(y, ref) < RTOL
+
+
+# ------------------------------------------------- activation-order checkpoints (App. A)
+
+def _actorder_case(b=4, N=5, K=192, G=32, seed=901):
+    codes = wl.uniform_ints(seed, N * K, 1 << b).reshape(N, K)
+    s = wl.uniform_range(seed + 1, N * (K // G), 0.002, 0.05).reshape(N, K // G)
+    z = wl.uniform_ints(seed + 2, N * (K // G), 1 << b).reshape(N, K // G)
+    g_idx = wl.actorder_g_idx(seed + 3, K, G)
+    return codes, s, z, g_idx
+
+
+def test_actorder_generator_gives_full_groups_in_scattered_columns():
+    g_idx = wl.actorder_g_idx(5, 256, 32)
+    assert g_idx.dtype == np.int32 and np.array_equal(np.bincount(g_idx), np.full(8, 32))
+    assert not np.array_equal(g_idx, np.arange(256) // 32)          # really out of order
+
+
+def test_actorder_dequant_by_python_loops():
+    codes, s, z, g_idx = _actorder_case()
+    Wd = oracle.dequant_actorder(codes, s, z, g_idx)
+    for n in range(codes.shape[0]):
+        for k in range(codes.shape[1]):
+            g = int(g_idx[k])
+            assert Wd[n, k] == s[n, g] * (float(codes[n, k]) - float(z[n, g]))
+
+
+def test_actorder_with_consecutive_groups_is_the_plain_dequant():
+    codes, s, z, _ = _actorder_case()
+    K, G = codes.shape[1], 32
+    plain = oracle.dequant(oracle.pack(codes, 4), s, z, K, 4, G)
+    assert np.array_equal(oracle.dequant_actorder(codes, s, z, np.arange(K) // G), plain)
+
+
+def test_actorder_perm_sorts_columns_into_consecutive_groups_and_keeps_the_product():
+    b, G = 3, 32
+    codes, s, z, g_idx = _actorder_case(b=b, N=6, K=256, G=G, seed=911)
+    K = codes.shape[1]
+    perm, inv = oracle.actorder_perm(g_idx)
+    assert np.array_equal(np.sort(perm), np.arange(K))                       # a permutation
+    assert np.array_equal(g_idx[perm], np.arange(K) // G)                    # groups become runs of G columns
+    assert np.array_equal(perm[inv], np.arange(K)) and np.array_equal(inv[perm], np.arange(K))
+    for g in range(K // G):                                                  # stable: original order inside a group
+        assert np.all(np.diff(perm[g * G:(g + 1) * G]) > 0)
+    # the layer in sorted coordinates: same weight entries, so the same product up to summation order
+    W_act = oracle.dequant_actorder(codes, s, z, g_idx)
+    W_sorted = oracle.dequant(oracle.pack(codes[:, perm], b), s, z, K, b, G)
+    assert np.array_equal(W_sorted, W_act[:, perm])
+    x = wl.normal(912, 4 * K).reshape(4, K)
+    np.testing.assert_allclose(x[:, perm] @ W_sorted.T, x @ W_act.T, rtol=1e-12, atol=1e-12)
+    dy = wl.normal(913, 4 * 6).reshape(4, 6)
+    np.testing.assert_allclose((dy @ W_sorted)[:, inv], dy @ W_act, rtol=1e-12, atol=1e-12)
