@@ -244,6 +244,34 @@ def run_lrec_loss(M: int = 2048, V: int = 32000, iters: int = 20):
             "plain_copy_GBps_same_box": round(copy_gbps, 1), "loss_mean": float(mean.cpu()[0])}
 
 
+def run_actorder_gather(M: int = 2048, K: int = 4096, G: int = 128, iters: int = 20):
+    """The run-time cost of an activation-order checkpoint: one column gather of x before the forward call and one
+    of dX after the backward call (4 bytes per element each: read once, written once).  Eight buffers are rotated."""
+    import numpy as np
+    import torch
+    from paper_2306_08162_amd import binding as ql
+    from paper_2306_08162_amd import workloads as wl
+    dev = torch.device("cuda:0")
+    perm = np.empty(K, dtype=np.int32)
+    ql.qlora_actorder_perm(wl.actorder_g_idx(0xAC7, K, G), perm, None, K, G)
+    idx = torch.from_numpy(perm).to(dev)
+    src = [torch.zeros((M, K), dtype=torch.int16, device=dev) for _ in range(8)]
+    dst = [torch.empty((M, K), dtype=torch.int16, device=dev) for _ in range(8)]
+    def burst():
+        for i in range(8):
+            ql.qlora_gather_columns(src[i], idx, dst[i], M, K)
+    us = _graph_time(burst, iters) / 8
+    def copies():
+        for i in range(8):
+            dst[i].copy_(src[i])
+    copy_us = _graph_time(copies, iters) / 8
+    nbytes = 4 * M * K
+    return {"workload": f"gather of {M} x {K} 16-bit columns by a seeded activation order (G={G})",
+            "us_per_call": round(us, 2), "algorithmic_bytes": nbytes, "GBps": round(nbytes / us * 1e-3, 1),
+            "frac_of_hbm_peak": round(nbytes / us * 1e-3 / PEAK_HBM_GBPS, 4),
+            "plain_copy_us_same_box": round(copy_us, 2), "calls_per_fwd_bwd": 2}
+
+
 def run_cpu_baseline(inp, max_rows: int):
     """The fp64 oracle as it stands, on the host cores: forward + backward on the first `max_rows` token rows."""
     import oracle
@@ -318,6 +346,7 @@ def main() -> int:
         result["small_m"] = {"M": 16, "timing": "HIP-graph replays over a >1 GB pool of distinct weight sets",
                              **run_small_m(16)}
         result["lrec_loss"] = run_lrec_loss()
+        result["actorder_gather"] = run_actorder_gather()
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = run_cpu_baseline(inp, args.cpu_rows)
     print(json.dumps(result))

@@ -64,7 +64,8 @@ typedef enum {
     QLORA_E_DTYPE = 6,      /* dtype not QLORA_F16 / QLORA_BF16 */
     QLORA_E_ALIGN = 7,      /* a pointer is not 16-byte aligned */
     QLORA_E_WORKSPACE = 8,  /* workspace NULL or smaller than qlora_workspace_bytes() */
-    QLORA_E_HIP = 9         /* the HIP runtime reported an error at launch */
+    QLORA_E_HIP = 9,        /* the HIP runtime reported an error at launch */
+    QLORA_E_GIDX = 10       /* a group index is out of range, or a group does not own exactly group_size columns */
 } qlora_status_t;
 
 /* Host pointer to a static, NUL-terminated description of `status`. */
@@ -91,6 +92,42 @@ int qlora_pack(const uint8_t *codes, uint32_t *packed, int N, int K, int bits, v
 
 /* Inverse of qlora_pack ("standard unpacking", Sec. 3.1): packed [N,Kw] -> codes [N,K]. */
 int qlora_unpack(const uint32_t *packed, uint8_t *codes, int N, int K, int bits, void *stream);
+
+/*
+ * Checkpoints quantized in activation order (App. A: the columns are quantized
+ * in order of decreasing activation size, so the G columns that share a scale
+ * and zero-point are scattered over the row and the checkpoint carries a group
+ * index g_idx[k] per column).  The layer entry points keep consecutive groups,
+ * which is what lets one K-slice use one scale: such a checkpoint is brought
+ * to that form once at load time by sorting its columns by group, and at run
+ * time x is gathered into, and dX scattered out of, the sorted column order.
+ * The adapter A lives in the sorted order throughout (it is trained from a
+ * random start, so its column order carries no meaning); projections that read
+ * the same x share one activation order and so one gather.
+ *
+ * qlora_actorder_perm: HOST pointers.  From g_idx [K] (each in [0, K/group_size))
+ * writes perm [K], the stable sort of the columns by group (perm[j] = original
+ * column that moves to place j), and, if not NULL, inv_perm [K] with
+ * inv_perm[perm[j]] = j.  QLORA_E_GIDX if a group index is out of range or a
+ * group does not own exactly group_size columns.  No device work.
+ */
+int qlora_actorder_perm(const int32_t *g_idx, int32_t *perm, int32_t *inv_perm, int K, int group_size);
+
+/*
+ * qlora_pack with a column gather: packs codes[:, perm[j]] as column j.  codes
+ * [N,K] uint8, perm [K] int32, both DEVICE.  An entry of perm outside [0, K)
+ * packs a zero code for that column (no out-of-bounds read).
+ */
+int qlora_pack_permuted(const uint8_t *codes, const int32_t *perm, uint32_t *packed, int N, int K, int bits,
+                        void *stream);
+
+/*
+ * dst[m, j] = src[m, index[j]] for 16-bit elements, src and dst [M,K] row-major
+ * DEVICE buffers that do not overlap, index [K] int32 DEVICE.  With index =
+ * perm it brings x into the sorted column order; with index = inv_perm it
+ * brings dX back to the checkpoint's.  An index outside [0, K) yields 0.
+ */
+int qlora_gather_columns(const void *src, const int32_t *index, void *dst, int M, int K, void *stream);
 
 /*
  * Forward pass (Fig. 1, forward path).  Writes y [M,N] (rounded to `dtype`

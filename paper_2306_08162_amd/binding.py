@@ -16,8 +16,9 @@ LIB_PATH = os.environ.get("QLORA_LIB", os.path.join(HERE, "libqlora.so"))   # QL
 
 QLORA_F16, QLORA_BF16 = 0, 1
 STATUS_NAMES = ["QLORA_OK", "QLORA_E_NULL", "QLORA_E_BITS", "QLORA_E_SHAPE", "QLORA_E_GROUP", "QLORA_E_RANK",
-                "QLORA_E_DTYPE", "QLORA_E_ALIGN", "QLORA_E_WORKSPACE", "QLORA_E_HIP"]
+                "QLORA_E_DTYPE", "QLORA_E_ALIGN", "QLORA_E_WORKSPACE", "QLORA_E_HIP", "QLORA_E_GIDX"]
 EXPORTS = ["qlora_status_string", "qlora_packed_words", "qlora_workspace_bytes", "qlora_pack", "qlora_unpack",
+           "qlora_actorder_perm", "qlora_pack_permuted", "qlora_gather_columns",
            "qlora_linear_fwd", "qlora_linear_bwd", "qlora_linear_bwd_accumulate", "qlora_linear_fwd_dropout",
            "qlora_linear_bwd_dropout", "qlora_siblings_workspace_bytes", "qlora_linear_fwd_siblings",
            "qlora_linear_bwd_siblings", "qlora_lrec_workspace_bytes", "qlora_lrec_loss", "qlora_profile_gemm"]
@@ -55,6 +56,12 @@ def load() -> ctypes.CDLL:
     lib.qlora_pack.argtypes = [vp, vp, c_int, c_int, c_int, vp]
     lib.qlora_unpack.restype = c_int
     lib.qlora_unpack.argtypes = [vp, vp, c_int, c_int, c_int, vp]
+    lib.qlora_actorder_perm.restype = c_int
+    lib.qlora_actorder_perm.argtypes = [vp, vp, vp, c_int, c_int]
+    lib.qlora_pack_permuted.restype = c_int
+    lib.qlora_pack_permuted.argtypes = [vp, vp, vp, c_int, c_int, c_int, vp]
+    lib.qlora_gather_columns.restype = c_int
+    lib.qlora_gather_columns.argtypes = [vp, vp, vp, c_int, c_int, vp]
     lib.qlora_linear_fwd.restype = c_int
     lib.qlora_linear_fwd.argtypes = [vp] * 8 + [c_int] * 6 + [f32, c_int, vp, c_sz, vp]
     lib.qlora_linear_bwd.restype = c_int
@@ -133,6 +140,30 @@ def qlora_unpack(packed, codes, N: int, K: int, bits: int, stream=None, check: b
     st = load().qlora_unpack(_ptr(packed), _ptr(codes), N, K, bits, _stream(stream))
     if check and st != 0:
         raise QLoraError(st, "qlora_unpack")
+    return st
+
+
+def qlora_actorder_perm(g_idx, perm, inv_perm, K: int, group_size: int, check: bool = True) -> int:
+    """Host arrays (numpy int32, or None): stable sort of the columns by group and its inverse."""
+    def host(a):
+        return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+    st = load().qlora_actorder_perm(host(g_idx), host(perm), host(inv_perm), K, group_size)
+    if check and st != 0:
+        raise QLoraError(st, "qlora_actorder_perm")
+    return st
+
+
+def qlora_pack_permuted(codes, perm, packed, N: int, K: int, bits: int, stream=None, check: bool = True) -> int:
+    st = load().qlora_pack_permuted(_ptr(codes), _ptr(perm), _ptr(packed), N, K, bits, _stream(stream))
+    if check and st != 0:
+        raise QLoraError(st, "qlora_pack_permuted")
+    return st
+
+
+def qlora_gather_columns(src, index, dst, M: int, K: int, stream=None, check: bool = True) -> int:
+    st = load().qlora_gather_columns(_ptr(src), _ptr(index), _ptr(dst), M, K, _stream(stream))
+    if check and st != 0:
+        raise QLoraError(st, "qlora_gather_columns")
     return st
 
 

@@ -5,6 +5,9 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+#include <vector>
+
 using namespace qlora;
 
 namespace {
@@ -98,6 +101,7 @@ const char *qlora_status_string(int status)
     case QLORA_E_ALIGN: return "a pointer is not 16-byte aligned";
     case QLORA_E_WORKSPACE: return "workspace is NULL or smaller than qlora_workspace_bytes()";
     case QLORA_E_HIP: return "the HIP runtime reported an error";
+    case QLORA_E_GIDX: return "group index out of range, or a group without exactly group_size columns";
     default: return "unknown status";
     }
 }
@@ -138,6 +142,49 @@ int qlora_unpack(const uint32_t *packed, uint8_t *codes, int N, int K, int bits,
     if (!codes || !packed) return QLORA_E_NULL;
     if (misaligned(codes) || misaligned(packed)) return QLORA_E_ALIGN;
     launch_unpack(packed, codes, N, K, bits, (hipStream_t)stream);
+    return hip_status();
+}
+
+int qlora_actorder_perm(const int32_t *g_idx, int32_t *perm, int32_t *inv_perm, int K, int group_size)
+{
+    if (K < 32 || K % 32 != 0 || K > (1 << 20)) return QLORA_E_SHAPE;
+    if (group_size < 32 || group_size % 32 != 0 || K % group_size != 0) return QLORA_E_GROUP;
+    if (!g_idx || !perm) return QLORA_E_NULL;
+    const int groups = K / group_size;
+    // counting sort with a fixed capacity of group_size per group: place = g * group_size + (columns of g seen so far)
+    std::vector<int> seen((size_t)groups, 0);
+    for (int k = 0; k < K; ++k) {
+        const int g = g_idx[k];
+        if (g < 0 || g >= groups || seen[(size_t)g] >= group_size) return QLORA_E_GIDX;
+        ++seen[(size_t)g];
+    }
+    std::fill(seen.begin(), seen.end(), 0);
+    for (int k = 0; k < K; ++k) {
+        const int g = g_idx[k];
+        const int place = g * group_size + seen[(size_t)g]++;
+        perm[place] = k;
+        if (inv_perm) inv_perm[k] = place;
+    }
+    return QLORA_OK;
+}
+
+int qlora_pack_permuted(const uint8_t *codes, const int32_t *perm, uint32_t *packed, int N, int K, int bits,
+                        void *stream)
+{
+    const int st = check_weight_shape(N, K, bits);
+    if (st != QLORA_OK) return st;
+    if (!codes || !perm || !packed) return QLORA_E_NULL;
+    if (misaligned(codes) || misaligned(packed)) return QLORA_E_ALIGN;
+    launch_pack_permuted(codes, perm, packed, N, K, bits, (hipStream_t)stream);
+    return hip_status();
+}
+
+int qlora_gather_columns(const void *src, const int32_t *index, void *dst, int M, int K, void *stream)
+{
+    if (M < 1 || K < 32 || K % 32 != 0 || K > (1 << 20) || (long)M * K >= (1L << 31)) return QLORA_E_SHAPE;
+    if (!src || !index || !dst) return QLORA_E_NULL;
+    if (misaligned(src) || misaligned(dst)) return QLORA_E_ALIGN;
+    launch_gather_columns(src, index, dst, M, K, (hipStream_t)stream);
     return hip_status();
 }
 

@@ -17,6 +17,11 @@ struct Problem {
 // pack.hip
 void launch_pack(const uint8_t *codes, uint32_t *packed, int N, int K, int bits, hipStream_t s);
 void launch_unpack(const uint32_t *packed, uint8_t *codes, int N, int K, int bits, hipStream_t s);
+// column j of the packed matrix takes the codes of column perm[j] (zero codes where perm[j] is outside [0, K))
+void launch_pack_permuted(const uint8_t *codes, const int32_t *perm, uint32_t *packed, int N, int K, int bits,
+                          hipStream_t s);
+// dst[m, j] = src[m, index[j]], 16-bit elements, K % 8 == 0 (0 where index[j] is outside [0, K))
+void launch_gather_columns(const void *src, const int32_t *index, void *dst, int M, int K, hipStream_t s);
 
 // adapters.hip -- the rank-r side products and the adapter gradients
 // t[M,r] = x[M,K] A[r,K]^T; with a keep mask (LoRA dropout, one bit per element of x, bit k % 32 of word k / 32 of

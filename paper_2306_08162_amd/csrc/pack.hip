@@ -27,6 +27,110 @@ __global__ __launch_bounds__(256) void pack_kernel(const uint8_t *__restrict__ c
     packed[idx] = word;
 }
 
+// The same with a column gather (checkpoints quantized in activation order, App. A, sorted by group at load time).
+template <int BITS>
+__global__ __launch_bounds__(256) void pack_permuted_kernel(const uint8_t *__restrict__ codes,
+                                                            const int32_t *__restrict__ perm,
+                                                            uint32_t *__restrict__ packed, int N, int K)
+{
+    const int Kw = K * BITS / 32;
+    const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (long)N * Kw) return;
+    const int n = (int)(idx / Kw), w = (int)(idx % Kw);
+    const uint8_t *row = codes + (long)n * K;
+    constexpr uint32_t mask = (1u << BITS) - 1u;
+    const int bit0 = 32 * w;
+    uint32_t word = 0;
+    for (int k = bit0 / BITS; BITS * k < bit0 + 32; ++k) {
+        const int src = perm[k];
+        const uint32_t q = (unsigned)src < (unsigned)K ? (row[src] & mask) : 0u;
+        const int sh = BITS * k - bit0;
+        word |= sh >= 0 ? (q << sh) : (q >> (-sh));
+    }
+    packed[idx] = word;
+}
+
+// Column gather of a 16-bit matrix.  A workgroup copies GATHER_ROWS whole rows into LDS with row-contiguous 16-byte
+// loads (scattered 2-byte reads from global memory move a fraction of what contiguous requests do), then every thread
+// builds eight neighbouring output columns per row from LDS and writes them with one 16-byte store.  The index is read
+// once per thread and row block.  A workgroup takes as many rows as fit GATHER_LDS_BYTES (at most GATHER_ROWS); rows
+// longer than that take the direct kernel below.
+#ifndef QLORA_GATHER_ROWS
+#define QLORA_GATHER_ROWS 2
+#endif
+#ifndef QLORA_GATHER_LDS_BYTES
+#define QLORA_GATHER_LDS_BYTES 16384
+#endif
+constexpr int GATHER_ROWS = QLORA_GATHER_ROWS;
+constexpr int GATHER_LDS_BYTES = QLORA_GATHER_LDS_BYTES;
+constexpr int GATHER_LDS_K = 32768;      // one row of 64 KB: the most a launch gets without asking for more
+__global__ __launch_bounds__(256) void gather_columns_lds_kernel(const uint16_t *__restrict__ src,
+                                                                 const int32_t *__restrict__ index,
+                                                                 uint16_t *__restrict__ dst, int M, int K, int R)
+{
+    extern __shared__ uint16_t rows[];   // R x K
+    const int m0 = blockIdx.x * R;
+    const int nrows = m0 + R <= M ? R : M - m0;
+    const int pieces = nrows * (K / 8);                        // the rows are adjacent in memory: one flat copy
+    const u32x4_t *from = reinterpret_cast<const u32x4_t *>(src + (long)m0 * K);
+    for (int p = threadIdx.x; p < pieces; p += 256) reinterpret_cast<u32x4_t *>(rows)[p] = from[p];
+    __syncthreads();
+    for (int j0 = threadIdx.x * 8; j0 < K; j0 += 256 * 8) {
+        int col[8];
+        bool ok[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int v = index[j0 + e];
+            ok[e] = (unsigned)v < (unsigned)K;
+            col[e] = ok[e] ? v : 0;
+        }
+        for (int i = 0; i < nrows; ++i) {
+            const uint16_t *row = rows + i * K;
+            uint16_t v[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = ok[e] ? row[col[e]] : (uint16_t)0;
+            u32x4_t out;
+            out[0] = v[0] | ((uint32_t)v[1] << 16);
+            out[1] = v[2] | ((uint32_t)v[3] << 16);
+            out[2] = v[4] | ((uint32_t)v[5] << 16);
+            out[3] = v[6] | ((uint32_t)v[7] << 16);
+            *reinterpret_cast<u32x4_t *>(dst + (long)(m0 + i) * K + j0) = out;
+        }
+    }
+}
+
+// The same without LDS, for rows too long to stage: a thread owns eight neighbouring output columns and walks
+// GATHER_ROWS rows with the same eight source columns.
+__global__ __launch_bounds__(256) void gather_columns_kernel(const uint16_t *__restrict__ src,
+                                                             const int32_t *__restrict__ index,
+                                                             uint16_t *__restrict__ dst, int M, int K)
+{
+    const int j0 = (blockIdx.y * 256 + threadIdx.x) * 8;
+    if (j0 >= K) return;
+    int from[8];
+    bool ok[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const int v = index[j0 + e];
+        ok[e] = (unsigned)v < (unsigned)K;
+        from[e] = ok[e] ? v : 0;
+    }
+    const int m0 = blockIdx.x * GATHER_ROWS;
+    const int m1 = m0 + GATHER_ROWS < M ? m0 + GATHER_ROWS : M;
+    for (int m = m0; m < m1; ++m) {
+        const uint16_t *row = src + (long)m * K;
+        uint16_t v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = ok[e] ? row[from[e]] : (uint16_t)0;
+        u32x4_t out;
+        out[0] = v[0] | ((uint32_t)v[1] << 16);
+        out[1] = v[2] | ((uint32_t)v[3] << 16);
+        out[2] = v[4] | ((uint32_t)v[5] << 16);
+        out[3] = v[6] | ((uint32_t)v[7] << 16);
+        *reinterpret_cast<u32x4_t *>(dst + (long)m * K + j0) = out;
+    }
+}
+
 // One thread recovers one code.
 template <int BITS>
 __global__ __launch_bounds__(256) void unpack_kernel(const uint32_t *__restrict__ packed, uint8_t *__restrict__ codes,
@@ -49,6 +153,33 @@ void launch_pack(const uint8_t *codes, uint32_t *packed, int N, int K, int bits,
     case 4: hipLaunchKernelGGL(pack_kernel<4>, grid, block, 0, s, codes, packed, N, K); break;
     default: hipLaunchKernelGGL(pack_kernel<8>, grid, block, 0, s, codes, packed, N, K); break;
     }
+}
+
+void launch_pack_permuted(const uint8_t *codes, const int32_t *perm, uint32_t *packed, int N, int K, int bits,
+                          hipStream_t s)
+{
+    const long words = (long)N * (K * bits / 32);
+    const dim3 grid((unsigned)((words + 255) / 256)), block(256);
+    switch (bits) {
+    case 2: hipLaunchKernelGGL(pack_permuted_kernel<2>, grid, block, 0, s, codes, perm, packed, N, K); break;
+    case 3: hipLaunchKernelGGL(pack_permuted_kernel<3>, grid, block, 0, s, codes, perm, packed, N, K); break;
+    case 4: hipLaunchKernelGGL(pack_permuted_kernel<4>, grid, block, 0, s, codes, perm, packed, N, K); break;
+    default: hipLaunchKernelGGL(pack_permuted_kernel<8>, grid, block, 0, s, codes, perm, packed, N, K); break;
+    }
+}
+
+void launch_gather_columns(const void *src, const int32_t *index, void *dst, int M, int K, hipStream_t s)
+{
+    if (K <= GATHER_LDS_K) {
+        int R = GATHER_LDS_BYTES / (K * 2);
+        R = R < 1 ? 1 : (R > GATHER_ROWS ? GATHER_ROWS : R);
+        hipLaunchKernelGGL(gather_columns_lds_kernel, dim3((unsigned)((M + R - 1) / R)), dim3(256), (size_t)R * K * 2, s,
+                           (const uint16_t *)src, index, (uint16_t *)dst, M, K, R);
+        return;
+    }
+    const unsigned row_blocks = (unsigned)((M + GATHER_ROWS - 1) / GATHER_ROWS);
+    const dim3 grid(row_blocks, (unsigned)((K / 8 + 255) / 256)), block(256);
+    hipLaunchKernelGGL(gather_columns_kernel, grid, block, 0, s, (const uint16_t *)src, index, (uint16_t *)dst, M, K);
 }
 
 void launch_unpack(const uint32_t *packed, uint8_t *codes, int N, int K, int bits, hipStream_t s)

@@ -118,6 +118,42 @@ class DeviceLayer:
         return self.dB.cpu().numpy()
 
 
+class ActOrderLayer(DeviceLayer):
+    """A projection whose checkpoint was quantized in activation order (per-column group index g_idx).
+
+    `inp.codes`, `inp.x` and the returned dX are in the checkpoint's column order; scales and zeros are indexed by
+    group as always; the adapter A is held in the sorted column order.  Load time: columns sorted by group and packed.
+    Run time: x gathered into the sorted order before the forward call, dX gathered back after the backward call.
+    """
+
+    def __init__(self, inp: LayerInputs, g_idx: np.ndarray, device: str = "cuda:0"):
+        super().__init__(inp, device=device)
+        c = self.cfg
+        g_idx = np.ascontiguousarray(g_idx, dtype=np.int32)
+        perm = np.empty(c.K, dtype=np.int32)
+        inv = np.empty(c.K, dtype=np.int32)
+        ql.qlora_actorder_perm(g_idx, perm, inv, c.K, c.group_size)
+        self.perm = _dev(perm, self.device)
+        self.inv_perm = _dev(inv, self.device)
+        ql.qlora_pack_permuted(self.codes, self.perm, self.packed, c.N, c.K, c.bits)
+        self.x_checkpoint_order = self.x
+        self.x = torch.empty_like(self.x_checkpoint_order)
+        self.dx_checkpoint_order = torch.empty_like(self.dx)
+
+    def forward(self, save_t: bool = True, stream=None):
+        c = self.cfg
+        ql.qlora_gather_columns(self.x_checkpoint_order, self.perm, self.x, c.M, c.K, stream=stream)
+        super().forward(save_t=save_t, stream=stream)
+
+    def backward(self, use_saved_t: bool = True, stream=None):
+        c = self.cfg
+        super().backward(use_saved_t=use_saved_t, stream=stream)
+        ql.qlora_gather_columns(self.dx, self.inv_perm, self.dx_checkpoint_order, c.M, c.K, stream=stream)
+
+    def host_dx(self) -> np.ndarray:
+        return _host16(self.dx_checkpoint_order)
+
+
 class DeviceSiblings:
     """Several projections that read the same x (q/k/v, gate/up), called together through the sibling entry points.
 

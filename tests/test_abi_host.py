@@ -3,6 +3,8 @@ and every argument error is reported before anything could reach a device."""
 import os
 import re
 
+import numpy as np
+
 import pytest
 
 from paper_2306_08162_amd import binding as ql
@@ -235,3 +237,30 @@ def test_error_raises_with_check():
     with pytest.raises(ql.QLoraError) as ei:
         ql.qlora_pack(FAKE, FAKE, 8, 64, 7, stream=0)
     assert ei.value.status == E["QLORA_E_BITS"]
+
+
+def test_actorder_perm_host_function_and_its_errors():
+    """qlora_actorder_perm is pure host work: checked here against numpy's stable sort, plus its error paths."""
+    from paper_2306_08162_amd import workloads as wl
+    K, G = 384, 32
+    g_idx = wl.actorder_g_idx(17, K, G)
+    perm = np.empty(K, dtype=np.int32)
+    inv = np.empty(K, dtype=np.int32)
+    assert ql.qlora_actorder_perm(g_idx, perm, inv, K, G, check=False) == 0
+    ref = np.argsort(g_idx, kind="stable")
+    assert np.array_equal(perm, ref) and np.array_equal(inv[ref], np.arange(K))
+    assert ql.qlora_actorder_perm(g_idx, perm, None, K, G, check=False) == 0          # inverse is optional
+    bad = g_idx.copy()
+    bad[5] = K // G
+    assert ql.qlora_actorder_perm(bad, perm, inv, K, G, check=False) == ql.STATUS_NAMES.index("QLORA_E_GIDX")
+    bad = g_idx.copy()
+    bad[5] = (bad[5] + 1) % (K // G)                                                  # one group too full
+    assert ql.qlora_actorder_perm(bad, perm, inv, K, G, check=False) == ql.STATUS_NAMES.index("QLORA_E_GIDX")
+    assert ql.qlora_actorder_perm(None, perm, inv, K, G, check=False) == ql.STATUS_NAMES.index("QLORA_E_NULL")
+    assert ql.qlora_actorder_perm(g_idx, perm, inv, K, 48, check=False) == ql.STATUS_NAMES.index("QLORA_E_GROUP")
+    assert ql.qlora_actorder_perm(g_idx, perm, inv, 40, 32, check=False) == ql.STATUS_NAMES.index("QLORA_E_SHAPE")
+    assert ql.qlora_pack_permuted(None, None, None, 8, 64, 4, stream=0, check=False) == ql.STATUS_NAMES.index("QLORA_E_NULL")
+    assert ql.qlora_pack_permuted(None, None, None, 8, 64, 5, stream=0, check=False) == ql.STATUS_NAMES.index("QLORA_E_BITS")
+    assert ql.qlora_gather_columns(None, None, None, 4, 64, stream=0, check=False) == ql.STATUS_NAMES.index("QLORA_E_NULL")
+    assert ql.qlora_gather_columns(None, None, None, 0, 64, stream=0, check=False) == ql.STATUS_NAMES.index("QLORA_E_SHAPE")
+    assert ql.qlora_gather_columns(None, None, None, 4, 40, stream=0, check=False) == ql.STATUS_NAMES.index("QLORA_E_SHAPE")

@@ -1,0 +1,97 @@
+"""GPU parity for checkpoints quantized in activation order (App. A): the host sort, the permuted pack and the
+column gather are exact integer / byte work; the layer called in sorted coordinates is compared with the oracle's
+plain per-column-group definition in the checkpoint's own column order."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2306_08162_amd import binding as ql
+from paper_2306_08162_amd import workloads as wl
+from parity import TOL, announce, rel_fro, small_inputs
+
+pytestmark = pytest.mark.gpu
+
+CASES = [
+    # (M, K, N, bits, G, r, dtype): weight-streaming, forward-only streaming, tiled paths; ragged everywhere
+    (5, 256, 72, 4, 32, 8, "f16"),
+    (16, 1376, 520, 2, 32, 16, "bf16"),
+    (40, 384, 264, 3, 128, 16, "f16"),
+    (300, 640, 392, 4, 128, 8, "f16"),
+    (131, 1024, 136, 8, 64, 64, "bf16"),
+    (77, 2080, 200, 3, 32, 0, "f16"),
+]
+
+
+@pytest.mark.parametrize("case", CASES, ids=lambda c: "M{}_K{}_N{}_b{}_G{}_r{}_{}".format(*c))
+def test_actorder_layer(case):
+    import torch
+    from paper_2306_08162_amd.device import ActOrderLayer
+    M, K, N, bits, G, r, dtype = case
+    inp = small_inputs(11 * M + K + bits, M, K, N, bits, G, r, dtype)
+    c = inp.cfg
+    g_idx = wl.actorder_g_idx(c.seed, K, G)
+    announce(f"act-order {c.name}")
+    layer = ActOrderLayer(inp, g_idx)
+    layer.forward()
+    layer.backward()
+    torch.cuda.synchronize()
+
+    # integer and byte work: bit-exact
+    perm_ref, inv_ref = oracle.actorder_perm(g_idx)
+    assert np.array_equal(layer.perm.cpu().numpy(), perm_ref)
+    assert np.array_equal(layer.inv_perm.cpu().numpy(), inv_ref)
+    assert np.array_equal(layer.host_packed(), oracle.pack(inp.codes[:, perm_ref], bits))
+    assert np.array_equal(layer.x.cpu().numpy().view(np.uint16), inp.x[:, perm_ref])
+
+    # the layer, against the per-column-group definition in checkpoint order (A is held in sorted order)
+    s = oracle.widen(inp.scales, "f16")
+    Wd = oracle.dequant_actorder(inp.codes, s, inp.zeros, g_idx)
+    x, dy = oracle.widen(inp.x, dtype), oracle.widen(inp.dy, dtype)
+    A_sorted, B = oracle.widen(inp.A, dtype), oracle.widen(inp.B, dtype)
+    A_ckpt = A_sorted[:, inv_ref] if r else A_sorted
+    y_ref, _ = oracle.forward(x, Wd, A_ckpt, B, c.alpha)
+    dx_ref = oracle.backward_dx(dy, Wd, A_ckpt, B, c.alpha)
+    errs = {"y": rel_fro(oracle.widen(layer.host_y(), dtype), y_ref),
+            "dx": rel_fro(oracle.widen(layer.host_dx(), dtype), dx_ref)}
+    if r:
+        dA_ref, dB_ref = oracle.backward_adapters(dy, x, A_ckpt, B, c.alpha)
+        errs["dA"] = rel_fro(layer.host_dA(), dA_ref[:, perm_ref])
+        errs["dB"] = rel_fro(layer.host_dB(), dB_ref)
+    announce(" ".join(f"{k}={v:.2e}" for k, v in errs.items()))
+    for k, v in errs.items():
+        assert np.isfinite(v) and v <= TOL, f"{c.name}: rel. Frobenius error of {k} = {v:.3e} > {TOL}"
+
+
+def test_gather_columns_out_of_range_index_gives_zero():
+    import torch
+    M, K = 9, 64
+    src = torch.arange(1, M * K + 1, dtype=torch.int16, device="cuda:0").reshape(M, K)
+    index = np.arange(K, dtype=np.int32)[::-1].copy()
+    index[3], index[40] = -1, K
+    idx = torch.from_numpy(index).to("cuda:0")
+    dst = torch.full((M, K), 77, dtype=torch.int16, device="cuda:0")
+    ql.qlora_gather_columns(src, idx, dst, M, K)
+    torch.cuda.synchronize()
+    ref = src.cpu().numpy()[:, np.clip(index, 0, K - 1)]
+    ref[:, [3, 40]] = 0
+    assert np.array_equal(dst.cpu().numpy(), ref)
+
+
+def test_gather_full_size_is_exact():
+    """The headline shape (2048 x 4096), sorted and back: the round trip returns the input bit for bit."""
+    import torch
+    M, K, G = 2048, 4096, 128
+    g_idx = wl.actorder_g_idx(4242, K, G)
+    perm = np.empty(K, dtype=np.int32)
+    inv = np.empty(K, dtype=np.int32)
+    ql.qlora_actorder_perm(g_idx, perm, inv, K, G)
+    p_ref, i_ref = oracle.actorder_perm(g_idx)
+    assert np.array_equal(perm, p_ref) and np.array_equal(inv, i_ref)
+    x = wl.to_f16_bits(wl.normal(4243, M * K)).reshape(M, K)
+    xd = torch.from_numpy(x.view(np.int16)).to("cuda:0")
+    xs, xb = torch.empty_like(xd), torch.empty_like(xd)
+    ql.qlora_gather_columns(xd, torch.from_numpy(perm).to("cuda:0"), xs, M, K)
+    ql.qlora_gather_columns(xs, torch.from_numpy(inv).to("cuda:0"), xb, M, K)
+    torch.cuda.synchronize()
+    assert np.array_equal(xs.cpu().numpy().view(np.uint16), x[:, p_ref])
+    assert np.array_equal(xb.cpu().numpy().view(np.uint16), x)
