@@ -97,6 +97,32 @@ def dequant(P: np.ndarray, scales: np.ndarray, zeros: np.ndarray, K: int, bits: 
     return Wd
 
 
+def zero_words(groups: int, bits: int) -> int:
+    """Words per row of the packed zero-points: the row's bit stream rounded up to whole 32-bit words."""
+    return (groups * bits + 31) // 32
+
+
+def pack_zeros(zeros: np.ndarray, bits: int) -> np.ndarray:
+    """Zero-points [N, groups] (uint8, each < 2^bits) as checkpoints store them: `bits` wide, bit-packed per row in
+    group order with the same little-endian stream as the codes (Sec. 3.1), the last word zero-padded."""
+    z = _c(zeros, np.uint8)
+    N, groups = z.shape
+    per_word_run = 32                      # 32 fields of any width fill whole words
+    padded = (groups + per_word_run - 1) // per_word_run * per_word_run
+    zp = np.zeros((N, padded), dtype=np.uint8)
+    zp[:, :groups] = z
+    return np.ascontiguousarray(pack(zp, bits)[:, :zero_words(groups, bits)])
+
+
+def unpack_zeros(packed_zeros: np.ndarray, groups: int, bits: int) -> np.ndarray:
+    P = _c(packed_zeros, np.uint32)
+    N = P.shape[0]
+    padded = (groups + 31) // 32 * 32
+    full = np.zeros((N, padded * bits // 32), dtype=np.uint32)
+    full[:, :P.shape[1]] = P
+    return np.ascontiguousarray(unpack(full, padded, bits)[:, :groups])
+
+
 # ------------------------------------------- activation-order checkpoints
 
 def dequant_actorder(codes: np.ndarray, scales: np.ndarray, zeros: np.ndarray, g_idx: np.ndarray) -> np.ndarray:

@@ -455,3 +455,32 @@ def test_actorder_perm_sorts_columns_into_consecutive_groups_and_keeps_the_produ
     np.testing.assert_allclose(x[:, perm] @ W_sorted.T, x @ W_act.T, rtol=1e-12, atol=1e-12)
     dy = wl.normal(913, 4 * 6).reshape(4, 6)
     np.testing.assert_allclose((dy @ W_sorted)[:, inv], dy @ W_act, rtol=1e-12, atol=1e-12)
+
+
+# ------------------------------------------------- packed zero-points
+
+def test_packed_zero_points_hand_derived():
+    # INT4, 5 groups: fields 0x3, 0xA, 0xF, 0x0, 0x7 from bit 0 upwards -> 0x000 7 0 F A 3
+    P = oracle.pack_zeros(np.array([[3, 10, 15, 0, 7]], np.uint8), 4)
+    assert P.shape == (1, 1) and P[0, 0] == 0x00070FA3
+    # INT3, 11 groups = 33 bits: the eleventh field (value 5 = 0b101) straddles the word boundary at bit 30
+    z = np.array([[1, 2, 3, 4, 5, 6, 7, 0, 1, 2, 5]], np.uint8)
+    P = oracle.pack_zeros(z, 3)
+    stream = sum(int(v) << (3 * i) for i, v in enumerate(z[0]))
+    assert P.shape == (1, 2) and P[0, 0] == stream & 0xFFFFFFFF and P[0, 1] == stream >> 32 == 0b1
+    # INT2: 0b11, 0b00, 0b10 -> 0b10_00_11 ; INT8: bytes in order
+    assert oracle.pack_zeros(np.array([[3, 0, 2]], np.uint8), 2)[0, 0] == 0b100011
+    assert oracle.pack_zeros(np.array([[0x12, 0x34, 0x56, 0x78, 0x9A]], np.uint8), 8).tolist() == [[0x78563412, 0x9A]]
+
+
+@pytest.mark.parametrize("b", [2, 3, 4, 8])
+@pytest.mark.parametrize("groups", [1, 7, 32, 33, 86, 344])
+def test_packed_zero_points_match_bigint_stream_and_roundtrip(b, groups):
+    N = 6
+    z = wl.uniform_ints(4321 + 10 * b + groups, N * groups, 1 << b).reshape(N, groups)
+    P = oracle.pack_zeros(z, b)
+    assert P.shape == (N, oracle.zero_words(groups, b)) == (N, -(-groups * b // 32))
+    for n in range(N):
+        stream = sum(int(v) << (b * i) for i, v in enumerate(z[n]))
+        assert P[n].tolist() == [(stream >> (32 * w)) & 0xFFFFFFFF for w in range(P.shape[1])]
+    assert np.array_equal(oracle.unpack_zeros(P, groups, b), z)
