@@ -94,6 +94,20 @@ int qlora_pack(const uint8_t *codes, uint32_t *packed, int N, int K, int bits, v
 int qlora_unpack(const uint32_t *packed, uint8_t *codes, int N, int K, int bits, void *stream);
 
 /*
+ * Zero-points as quantized checkpoints store them (Sec. 2.2 / App. A: the
+ * GPTQ-format files keep them bit-packed like the codes): packed_zeros
+ * [N, Zw] uint32 with Zw = ceil(groups*bits/32), row n holding the zero-points
+ * of its groups in order as one little-endian stream of `bits`-wide fields,
+ * the last word zero-padded.  The layer entry points take unpacked uint8
+ * zero-points; these two convert at load time (packing them in the kernels
+ * would save under 2 % of the weight-side bytes).  groups >= 1, N >= 1,
+ * N * groups < 2^31.  qlora_packed_zero_words returns N * Zw, 0 on bad arguments.
+ */
+size_t qlora_packed_zero_words(int N, int groups, int bits);
+int qlora_pack_zeros(const uint8_t *zeros, uint32_t *packed_zeros, int N, int groups, int bits, void *stream);
+int qlora_unpack_zeros(const uint32_t *packed_zeros, uint8_t *zeros, int N, int groups, int bits, void *stream);
+
+/*
  * Checkpoints quantized in activation order (App. A: the columns are quantized
  * in order of decreasing activation size, so the G columns that share a scale
  * and zero-point are scattered over the row and the checkpoint carries a group

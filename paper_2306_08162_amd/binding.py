@@ -19,6 +19,7 @@ STATUS_NAMES = ["QLORA_OK", "QLORA_E_NULL", "QLORA_E_BITS", "QLORA_E_SHAPE", "QL
                 "QLORA_E_DTYPE", "QLORA_E_ALIGN", "QLORA_E_WORKSPACE", "QLORA_E_HIP", "QLORA_E_GIDX"]
 EXPORTS = ["qlora_status_string", "qlora_packed_words", "qlora_workspace_bytes", "qlora_pack", "qlora_unpack",
            "qlora_actorder_perm", "qlora_pack_permuted", "qlora_gather_columns",
+           "qlora_packed_zero_words", "qlora_pack_zeros", "qlora_unpack_zeros",
            "qlora_linear_fwd", "qlora_linear_bwd", "qlora_linear_bwd_accumulate", "qlora_linear_fwd_dropout",
            "qlora_linear_bwd_dropout", "qlora_siblings_workspace_bytes", "qlora_linear_fwd_siblings",
            "qlora_linear_bwd_siblings", "qlora_lrec_workspace_bytes", "qlora_lrec_loss", "qlora_profile_gemm"]
@@ -56,6 +57,12 @@ def load() -> ctypes.CDLL:
     lib.qlora_pack.argtypes = [vp, vp, c_int, c_int, c_int, vp]
     lib.qlora_unpack.restype = c_int
     lib.qlora_unpack.argtypes = [vp, vp, c_int, c_int, c_int, vp]
+    lib.qlora_packed_zero_words.restype = c_sz
+    lib.qlora_packed_zero_words.argtypes = [c_int, c_int, c_int]
+    lib.qlora_pack_zeros.restype = c_int
+    lib.qlora_pack_zeros.argtypes = [vp, vp, c_int, c_int, c_int, vp]
+    lib.qlora_unpack_zeros.restype = c_int
+    lib.qlora_unpack_zeros.argtypes = [vp, vp, c_int, c_int, c_int, vp]
     lib.qlora_actorder_perm.restype = c_int
     lib.qlora_actorder_perm.argtypes = [vp, vp, vp, c_int, c_int]
     lib.qlora_pack_permuted.restype = c_int
@@ -140,6 +147,24 @@ def qlora_unpack(packed, codes, N: int, K: int, bits: int, stream=None, check: b
     st = load().qlora_unpack(_ptr(packed), _ptr(codes), N, K, bits, _stream(stream))
     if check and st != 0:
         raise QLoraError(st, "qlora_unpack")
+    return st
+
+
+def qlora_packed_zero_words(N: int, groups: int, bits: int) -> int:
+    return int(load().qlora_packed_zero_words(N, groups, bits))
+
+
+def qlora_pack_zeros(zeros, packed_zeros, N: int, groups: int, bits: int, stream=None, check: bool = True) -> int:
+    st = load().qlora_pack_zeros(_ptr(zeros), _ptr(packed_zeros), N, groups, bits, _stream(stream))
+    if check and st != 0:
+        raise QLoraError(st, "qlora_pack_zeros")
+    return st
+
+
+def qlora_unpack_zeros(packed_zeros, zeros, N: int, groups: int, bits: int, stream=None, check: bool = True) -> int:
+    st = load().qlora_unpack_zeros(_ptr(packed_zeros), _ptr(zeros), N, groups, bits, _stream(stream))
+    if check and st != 0:
+        raise QLoraError(st, "qlora_unpack_zeros")
     return st
 
 

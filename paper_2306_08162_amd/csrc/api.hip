@@ -25,6 +25,13 @@ int check_weight_shape(int N, int K, int bits)
     return QLORA_OK;
 }
 
+int check_zero_shape(int N, int groups, int bits)
+{
+    if (bits != 2 && bits != 3 && bits != 4 && bits != 8) return QLORA_E_BITS;
+    if (N < 1 || groups < 1 || (long long)N * groups >= (1ll << 31)) return QLORA_E_SHAPE;
+    return QLORA_OK;
+}
+
 int check_problem(int M, int N, int K, int bits, int G, int r, int dtype)
 {
     int st = check_weight_shape(N, K, bits);
@@ -142,6 +149,30 @@ int qlora_unpack(const uint32_t *packed, uint8_t *codes, int N, int K, int bits,
     if (!codes || !packed) return QLORA_E_NULL;
     if (misaligned(codes) || misaligned(packed)) return QLORA_E_ALIGN;
     launch_unpack(packed, codes, N, K, bits, (hipStream_t)stream);
+    return hip_status();
+}
+
+size_t qlora_packed_zero_words(int N, int groups, int bits)
+{
+    if (check_zero_shape(N, groups, bits) != QLORA_OK) return 0;
+    return (size_t)N * (((size_t)groups * bits + 31) / 32);
+}
+
+int qlora_pack_zeros(const uint8_t *zeros, uint32_t *packed_zeros, int N, int groups, int bits, void *stream)
+{
+    const int st = check_zero_shape(N, groups, bits);
+    if (st != QLORA_OK) return st;
+    if (!zeros || !packed_zeros) return QLORA_E_NULL;
+    launch_pack_zeros(zeros, packed_zeros, N, groups, bits, (hipStream_t)stream);
+    return hip_status();
+}
+
+int qlora_unpack_zeros(const uint32_t *packed_zeros, uint8_t *zeros, int N, int groups, int bits, void *stream)
+{
+    const int st = check_zero_shape(N, groups, bits);
+    if (st != QLORA_OK) return st;
+    if (!zeros || !packed_zeros) return QLORA_E_NULL;
+    launch_unpack_zeros(packed_zeros, zeros, N, groups, bits, (hipStream_t)stream);
     return hip_status();
 }
 

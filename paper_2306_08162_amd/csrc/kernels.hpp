@@ -17,6 +17,9 @@ struct Problem {
 // pack.hip
 void launch_pack(const uint8_t *codes, uint32_t *packed, int N, int K, int bits, hipStream_t s);
 void launch_unpack(const uint32_t *packed, uint8_t *codes, int N, int K, int bits, hipStream_t s);
+// zero-points [N, groups] <-> their bit-packed form [N, ceil(groups*bits/32)] (same stream convention as the codes)
+void launch_pack_zeros(const uint8_t *zeros, uint32_t *packed, int N, int groups, int bits, hipStream_t s);
+void launch_unpack_zeros(const uint32_t *packed, uint8_t *zeros, int N, int groups, int bits, hipStream_t s);
 // column j of the packed matrix takes the codes of column perm[j] (zero codes where perm[j] is outside [0, K))
 void launch_pack_permuted(const uint8_t *codes, const int32_t *perm, uint32_t *packed, int N, int K, int bits,
                           hipStream_t s);

@@ -143,6 +143,37 @@ __global__ __launch_bounds__(256) void unpack_kernel(const uint32_t *__restrict_
     codes[idx] = (uint8_t)code_at<BITS>(packed + (long)n * Kw, k);
 }
 
+// Zero-points as checkpoints store them: BITS wide, bit-packed per weight row in group order (the codes' stream
+// convention), each row rounded up to whole words.  One thread builds one word / recovers one zero-point.
+template <int BITS>
+__global__ __launch_bounds__(256) void pack_zeros_kernel(const uint8_t *__restrict__ zeros, uint32_t *__restrict__ packed,
+                                                         int N, int groups, int zw)
+{
+    const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (long)N * zw) return;
+    const int n = (int)(idx / zw), w = (int)(idx % zw);
+    const uint8_t *row = zeros + (long)n * groups;
+    constexpr uint32_t mask = (1u << BITS) - 1u;
+    const int bit0 = 32 * w;
+    uint32_t word = 0;
+    for (int g = bit0 / BITS; BITS * g < bit0 + 32 && g < groups; ++g) {
+        const uint32_t q = row[g] & mask;
+        const int sh = BITS * g - bit0;
+        word |= sh >= 0 ? (q << sh) : (q >> (-sh));
+    }
+    packed[idx] = word;
+}
+
+template <int BITS>
+__global__ __launch_bounds__(256) void unpack_zeros_kernel(const uint32_t *__restrict__ packed, uint8_t *__restrict__ zeros,
+                                                           int N, int groups, int zw)
+{
+    const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (long)N * groups) return;
+    const int n = (int)(idx / groups), g = (int)(idx % groups);
+    zeros[idx] = (uint8_t)code_at<BITS>(packed + (long)n * zw, g);   // a straddling field ends inside the padded row
+}
+
 void launch_pack(const uint8_t *codes, uint32_t *packed, int N, int K, int bits, hipStream_t s)
 {
     const long words = (long)N * (K * bits / 32);
@@ -191,6 +222,30 @@ void launch_unpack(const uint32_t *packed, uint8_t *codes, int N, int K, int bit
     case 3: hipLaunchKernelGGL(unpack_kernel<3>, grid, block, 0, s, packed, codes, N, K); break;
     case 4: hipLaunchKernelGGL(unpack_kernel<4>, grid, block, 0, s, packed, codes, N, K); break;
     default: hipLaunchKernelGGL(unpack_kernel<8>, grid, block, 0, s, packed, codes, N, K); break;
+    }
+}
+
+void launch_pack_zeros(const uint8_t *zeros, uint32_t *packed, int N, int groups, int bits, hipStream_t s)
+{
+    const int zw = (groups * bits + 31) / 32;
+    const dim3 grid((unsigned)(((long)N * zw + 255) / 256)), block(256);
+    switch (bits) {
+    case 2: hipLaunchKernelGGL(pack_zeros_kernel<2>, grid, block, 0, s, zeros, packed, N, groups, zw); break;
+    case 3: hipLaunchKernelGGL(pack_zeros_kernel<3>, grid, block, 0, s, zeros, packed, N, groups, zw); break;
+    case 4: hipLaunchKernelGGL(pack_zeros_kernel<4>, grid, block, 0, s, zeros, packed, N, groups, zw); break;
+    default: hipLaunchKernelGGL(pack_zeros_kernel<8>, grid, block, 0, s, zeros, packed, N, groups, zw); break;
+    }
+}
+
+void launch_unpack_zeros(const uint32_t *packed, uint8_t *zeros, int N, int groups, int bits, hipStream_t s)
+{
+    const int zw = (groups * bits + 31) / 32;
+    const dim3 grid((unsigned)(((long)N * groups + 255) / 256)), block(256);
+    switch (bits) {
+    case 2: hipLaunchKernelGGL(unpack_zeros_kernel<2>, grid, block, 0, s, packed, zeros, N, groups, zw); break;
+    case 3: hipLaunchKernelGGL(unpack_zeros_kernel<3>, grid, block, 0, s, packed, zeros, N, groups, zw); break;
+    case 4: hipLaunchKernelGGL(unpack_zeros_kernel<4>, grid, block, 0, s, packed, zeros, N, groups, zw); break;
+    default: hipLaunchKernelGGL(unpack_zeros_kernel<8>, grid, block, 0, s, packed, zeros, N, groups, zw); break;
     }
 }
 

@@ -264,3 +264,14 @@ def test_actorder_perm_host_function_and_its_errors():
     assert ql.qlora_gather_columns(None, None, None, 4, 64, stream=0, check=False) == ql.STATUS_NAMES.index("QLORA_E_NULL")
     assert ql.qlora_gather_columns(None, None, None, 0, 64, stream=0, check=False) == ql.STATUS_NAMES.index("QLORA_E_SHAPE")
     assert ql.qlora_gather_columns(None, None, None, 4, 40, stream=0, check=False) == ql.STATUS_NAMES.index("QLORA_E_SHAPE")
+
+
+def test_packed_zero_words_and_errors():
+    assert ql.qlora_packed_zero_words(4096, 32, 4) == 4096 * 4
+    assert ql.qlora_packed_zero_words(8, 11, 3) == 8 * 2
+    assert ql.qlora_packed_zero_words(8, 1, 2) == 8
+    assert ql.qlora_packed_zero_words(8, 11, 5) == 0 and ql.qlora_packed_zero_words(0, 11, 4) == 0
+    E = ql.STATUS_NAMES.index
+    assert ql.qlora_pack_zeros(None, None, 8, 4, 4, stream=0, check=False) == E("QLORA_E_NULL")
+    assert ql.qlora_unpack_zeros(None, None, 8, 4, 6, stream=0, check=False) == E("QLORA_E_BITS")
+    assert ql.qlora_unpack_zeros(None, None, 8, 0, 4, stream=0, check=False) == E("QLORA_E_SHAPE")

@@ -95,3 +95,28 @@ def test_gather_full_size_is_exact():
     torch.cuda.synchronize()
     assert np.array_equal(xs.cpu().numpy().view(np.uint16), x[:, p_ref])
     assert np.array_equal(xb.cpu().numpy().view(np.uint16), x)
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4, 8])
+@pytest.mark.parametrize("groups", [1, 11, 32, 86, 344])
+def test_packed_zero_points_bit_exact(bits, groups):
+    """Zero-points in their checkpoint storage form: pack and unpack against the oracle, bit for bit."""
+    import torch
+    N = 136
+    z = wl.uniform_ints(77 + bits + groups, N * groups, 1 << bits).reshape(N, groups)
+    zd = torch.from_numpy(z).to("cuda:0")
+    words = ql.qlora_packed_zero_words(N, groups, bits)
+    assert words == N * oracle.zero_words(groups, bits)
+    pd = torch.full((N, words // N), -1, dtype=torch.int32, device="cuda:0")
+    ql.qlora_pack_zeros(zd, pd, N, groups, bits)
+    back = torch.full((N, groups), 255, dtype=torch.uint8, device="cuda:0")
+    ql.qlora_unpack_zeros(pd, back, N, groups, bits)
+    torch.cuda.synchronize()
+    ref = oracle.pack_zeros(z, bits)
+    assert np.array_equal(pd.cpu().numpy().view(np.uint32), ref)
+    assert np.array_equal(back.cpu().numpy(), z)
+    # and from the oracle's words, as a loader would hand them over
+    pd2 = torch.from_numpy(ref.view(np.int32)).to("cuda:0")
+    ql.qlora_unpack_zeros(pd2, back.fill_(255), N, groups, bits)
+    torch.cuda.synchronize()
+    assert np.array_equal(back.cpu().numpy(), oracle.unpack_zeros(ref, groups, bits))
