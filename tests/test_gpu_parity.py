@@ -78,6 +78,8 @@ SMALL_CASES = [
     (4, 160, 4200, 8, 32, 8, "f16"),           # two 16-row weight blocks per workgroup, last workgroup half empty
     (16, 96, 12312, 2, 32, 8, "bf16"),         # four blocks per workgroup, ragged; backward with many row slices
     (11, 2048, 1544, 4, 128, 16, "f16"),       # backward: 8-wave workgroups, slices that do not divide the rows
+    (7, 512, 136, 4, 512, 8, "f16"),           # per-row grouping on the weight-streaming path
+    (150, 1024, 264, 2, 1024, 8, "f16"),       # and on the tiled path, both passes
 ]
 
 
