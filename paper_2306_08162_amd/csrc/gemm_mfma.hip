@@ -118,12 +118,17 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
 #endif
     constexpr int NXS = QLORA_NXS;                  // activation stages (3, or 2 when two workgroups share a CU's LDS)
     static_assert(NXS == 2 || NXS == 3, "activation stages");
-    constexpr int WS = BN * LDS_STRIDE;             // halfs per weight stage (144-byte rows)
+    // Weight stage.  Forward: [BN rows n][64 k + 8] (144-byte rows), fragments are 16-byte reads.  Backward: the
+    // staging threads own rows n of the contraction, so the stage is kept as they produce it, [64 rows n][BN k + 32]
+    // (320-byte rows: four consecutive rows start 16 banks apart), and the fragments are gathered with the
+    // transposing LDS read (ds_read_b64_tr_b16), two per fragment.
+    constexpr int WPITCH = TRANS ? BN + 32 : LDS_STRIDE;
+    constexpr int WS = TRANS ? BK * WPITCH : BN * LDS_STRIDE;   // halfs per weight stage
     using Regs = StageRegs<BITS, WU>;
 
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
     uint16_t *const xs = smem;                      // [NXS][BM][64]
-    uint16_t *const wsm = smem + NXS * XS;          // [2][BN][72]
+    uint16_t *const wsm = smem + NXS * XS;          // [2] weight stages
 
     // The first MW waves feed the matrix cores: LDS fragment reads, MFMAs, and the direct-to-LDS loads of the
     // activation tile (no registers, no ALU work).  The last four waves stage the weight: packed words global ->
@@ -178,13 +183,33 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
     int aoff[BK / 16];                              // per k-step: this lane's offset into an activation stage
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) aoff[ks] = (wm * TM + fr) * BK + ((2 * ks + fh) ^ ((fr >> 1) & 7)) * 8;
-    const int boff = (wn * TN + fr) * LDS_STRIDE + fh * 8;   // and into a weight stage (k-step adds 16)
+    // and into a weight stage (a k-step adds 16 contraction elements).  Transposing read: in every block of 16
+    // lanes, lane 4e+g supplies the address of four consecutive 16-bit columns of one row, and lane i receives, as
+    // element e, column i%4 of the row supplied by lane 4e + i/4.  Lane (e, g) of block b therefore points at row
+    // 8 (b/2) + e, columns 16 (b%2) + 4g .. +4 of the 16 x 32 k-step slab, and lane l ends up with contraction
+    // elements 8 (l/32) .. +4 of column l % 32: half an MFMA operand; the second read starts four rows further down.
+    const int boff = TRANS ? (8 * (lane >> 5) + ((lane & 15) >> 2)) * WPITCH + wn * TN + 16 * ((lane >> 4) & 1) + 4 * (lane & 3)
+                           : (wn * TN + fr) * LDS_STRIDE + fh * 8;
     auto load_frags = [&](int xstage, int wstage, int ks, Frags &f) {
-        const uint16_t *As = xs + xstage * XS + aoff[ks], *Bs = wsm + wstage * WS + boff + ks * 16;
+        const uint16_t *As = xs + xstage * XS + aoff[ks];
 #pragma unroll
         for (int i = 0; i < MI; ++i) f.a[i] = *(const u16x8_t *)(As + i * 32 * BK);
+        if constexpr (TRANS) {
+            const uint16_t *Bs = wsm + wstage * WS + boff + ks * 16 * WPITCH;
 #pragma unroll
-        for (int j = 0; j < NI; ++j) f.b[j] = *(const u16x8_t *)(Bs + j * 32 * LDS_STRIDE);
+            for (int j = 0; j < NI; ++j) {
+                typedef short s16x4_t __attribute__((ext_vector_type(4)));
+                typedef __attribute__((address_space(3))) s16x4_t *lds4_t;
+                const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds4_t)(Bs + j * 32));
+                const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds4_t)(Bs + j * 32 + 4 * WPITCH));
+                f.b[j] = u16x8_t{(uint16_t)lo[0], (uint16_t)lo[1], (uint16_t)lo[2], (uint16_t)lo[3],
+                                 (uint16_t)hi[0], (uint16_t)hi[1], (uint16_t)hi[2], (uint16_t)hi[3]};
+            }
+        } else {
+            const uint16_t *Bs = wsm + wstage * WS + boff + ks * 16;
+#pragma unroll
+            for (int j = 0; j < NI; ++j) f.b[j] = *(const u16x8_t *)(Bs + j * 32 * LDS_STRIDE);
+        }
     };
     auto mfma_frags = [&](const Frags &f) {
 #pragma unroll
@@ -218,7 +243,7 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
 #pragma unroll
             for (int i = 0; i < MI * NI; ++i) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                        // one MFMA
-                if (i < MI + NI) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);       // one LDS read
+                if (i < MI + (TRANS ? 2 * NI : NI)) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
             }
         };
 
@@ -298,9 +323,7 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
                 for (int part = 0; part < 4; ++part) {
                     const u16x8_t v = dequant8<BITS, BF16>(rg.w[i], part, dq);
                     if constexpr (TRANS) {
-                        uint16_t *dst = Bs + ((u >> 6) * 32 + part * 8) * LDS_STRIDE + (u & 63);
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) dst[e * LDS_STRIDE] = v[e];
+                        *(u16x8_t *)(Bs + (u & 63) * WPITCH + (u >> 6) * 32 + part * 8) = v;
                     } else {
                         *(u16x8_t *)(Bs + (u >> 1) * LDS_STRIDE + (u & 1) * 32 + part * 8) = v;
                     }
@@ -352,19 +375,21 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
                 }
                 *(u16x8_t *)(xs + r * BK + ((jc ^ ((r >> 1) & 7)) * 8)) = p;  // same swizzle as the main loop
             }
-            for (int c = stid; c < BN * cpr; c += STAGERS) {
-                const int r = c / cpr, j = (c % cpr) * 8;
-                const int col = col0 + r;
-                u16x8_t p = {0, 0, 0, 0, 0, 0, 0, 0};
-                if (j < a.r && col < NO) {
-                    if constexpr (TRANS) {
-#pragma unroll
-                        for (int h = 0; h < 8; ++h) p[h] = a.ext_w[(long)(j + h) * a.K + col];
-                    } else {
-                        p = *(const u16x8_t *)(a.ext_w + (long)col * a.r + j);
-                    }
+            if constexpr (TRANS) {          // rows j of A, the tile's columns contiguous: the stage's own layout
+                for (int c = stid; c < width * (BN / 8); c += STAGERS) {
+                    const int j = c / (BN / 8), col = col0 + (c % (BN / 8)) * 8;
+                    u16x8_t p = {0, 0, 0, 0, 0, 0, 0, 0};
+                    if (j < a.r && col < NO) p = *(const u16x8_t *)(a.ext_w + (long)j * a.K + col);
+                    *(u16x8_t *)(wsm + j * WPITCH + (c % (BN / 8)) * 8) = p;
                 }
-                *(u16x8_t *)(wsm + r * LDS_STRIDE + j) = p;
+            } else {
+                for (int c = stid; c < BN * cpr; c += STAGERS) {
+                    const int r = c / cpr, j = (c % cpr) * 8;
+                    const int col = col0 + r;
+                    u16x8_t p = {0, 0, 0, 0, 0, 0, 0, 0};
+                    if (j < a.r && col < NO) p = *(const u16x8_t *)(a.ext_w + (long)col * a.r + j);
+                    *(u16x8_t *)(wsm + r * LDS_STRIDE + j) = p;
+                }
             }
         }
         __syncthreads();
@@ -410,7 +435,8 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
 template <int BITS, bool BF16, bool TRANS, int BM, int BN, int WM, int WN>
 void launch_variant(const GemmArgs &a, hipStream_t s)
 {
-    constexpr size_t lds_pipe = (QLORA_NXS * (size_t)BM * BK + 2 * (size_t)BN * LDS_STRIDE) * sizeof(uint16_t);
+    constexpr size_t wstage = TRANS ? (size_t)BK * (BN + 32) : (size_t)BN * LDS_STRIDE;
+    constexpr size_t lds_pipe = (QLORA_NXS * (size_t)BM * BK + 2 * wstage) * sizeof(uint16_t);
     constexpr size_t lds_epi = (size_t)WM * WN * (BM / WM) * (BN / WN + 8) * sizeof(uint16_t);
     constexpr size_t lds = lds_pipe > lds_epi ? lds_pipe : lds_epi;
     auto kern = qgemm_kernel<BITS, BF16, TRANS, BM, BN, WM, WN>;
