@@ -111,6 +111,74 @@ __global__ __launch_bounds__(SK_WAVES * 64) void skinny_rows_kernel(const uint16
     }
 }
 
+// u = act * small with `small` [C, r] taken as it lies in memory (r contiguous, r <= 16; u = dY B): the contraction
+// index is the strided one, so blocks of rows of `small` are copied into LDS unchanged and the MFMA operand is
+// gathered with the transposing LDS read (in a block of 16 lanes, lane 4e+g supplies the address of four columns of
+// one row; lane i receives column i%4 of the rows supplied by lanes i/4, 4 + i/4, 8 + i/4, 12 + i/4).  Saves the
+// separate transposition of B and its launch.
+constexpr int SKN_BYTES = 65536;   // LDS block of `small`
+template <bool BF16, int SK_ROWS>
+__global__ __launch_bounds__(SK_WAVES * 64) void skinny_rows_natural_kernel(const uint16_t *__restrict__ act,
+                                                                           const uint16_t *__restrict__ small,
+                                                                           uint16_t *__restrict__ out, int M, int C, int r)
+{
+    extern __shared__ __attribute__((aligned(16))) uint16_t sm[];
+    __shared__ float red[SK_WAVES][16][17];
+    typedef short s16x4_t __attribute__((ext_vector_type(4)));
+    typedef __attribute__((address_space(3))) s16x4_t *lds4_t;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int m0 = blockIdx.x * SK_ROWS;
+    const int li = lane & 15, q = lane >> 4;
+    const bool rowin = li < SK_ROWS, sval = li < r;
+    const uint16_t *arow = act + (long)min(m0 + li, M - 1) * C + q * 8;
+    const int NB = SKN_BYTES / 2 / r;                               // rows of `small` per block: a multiple of 32
+    const int toff = (8 * q + (li >> 2)) * r + min(4 * (li & 3), r - 4);   // this lane's address within a 32-row chunk
+    float4_t acc = {0.f, 0.f, 0.f, 0.f};
+
+    for (int nb = 0; nb < C; nb += NB) {
+        const int rows_here = min(NB, C - nb);
+        __syncthreads();                                            // the previous block has been read
+        {
+            const u32x4_t *src = (const u32x4_t *)(small + (long)nb * r);
+            for (int p = threadIdx.x; p < rows_here * r / 8; p += SK_WAVES * 64) ((u32x4_t *)sm)[p] = src[p];
+        }
+        __syncthreads();
+        const int ce = (nb + rows_here + 31) / 32;                  // chunks of 32 contraction elements, this block's end
+        for (int c0 = nb / 32 + wave; c0 < ce; c0 += SK_WAVES * SK_UNROLL) {
+            u16x8_t xa[SK_UNROLL], sb[SK_UNROLL];
+#pragma unroll
+            for (int uu = 0; uu < SK_UNROLL; ++uu) {
+                const int c = c0 + uu * SK_WAVES;
+                const int k = c * 32;
+                const bool in = c < ce && k + q * 8 < C;
+                xa[uu] = u16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
+                sb[uu] = xa[uu];
+                if (in && rowin) xa[uu] = *(const u16x8_t *)(arow + k);
+                if (c < ce) {                                       // wave-uniform: every lane supplies its address
+                    const uint16_t *ch = sm + (k - nb) * r + toff;  // rows up to the chunk's 32nd lie inside the block
+                    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds4_t)ch);
+                    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds4_t)(ch + 4 * r));
+                    if (in && sval)                                 // rows past C hold stale LDS contents
+                        sb[uu] = u16x8_t{(uint16_t)lo[0], (uint16_t)lo[1], (uint16_t)lo[2], (uint16_t)lo[3],
+                                         (uint16_t)hi[0], (uint16_t)hi[1], (uint16_t)hi[2], (uint16_t)hi[3]};
+                }
+            }
+#pragma unroll
+            for (int uu = 0; uu < SK_UNROLL; ++uu) acc = mfma16<BF16>(xa[uu], sb[uu], acc);
+        }
+    }
+#pragma unroll
+    for (int v = 0; v < 4; ++v) red[wave][4 * q + v][li] = acc[v];
+    __syncthreads();
+    if (threadIdx.x < 256) {
+        const int row = threadIdx.x >> 4, col = threadIdx.x & 15;
+        float s = 0.f;
+#pragma unroll
+        for (int w = 0; w < SK_WAVES; ++w) s += red[w][row][col];
+        if (row < SK_ROWS && m0 + row < M && col < r) out[(long)(m0 + row) * r + col] = to16<BF16>(s);
+    }
+}
+
 // bt[r,N] = b[N,r]^T (the small operand of u = dY B must be contiguous along the contraction index n)
 __global__ __launch_bounds__(256) void transpose_small_kernel(const uint16_t *__restrict__ b, uint16_t *__restrict__ bt,
                                                               int N, int r)
@@ -296,8 +364,32 @@ void launch_lora_down(const void *x, const void *A, void *t, int M, int K, int r
     }
 }
 
+template <bool BF16, int SK_ROWS>
+void launch_skinny_natural(const uint16_t *act, const uint16_t *small, uint16_t *out, int M, int C, int r, hipStream_t s)
+{
+    auto kern = skinny_rows_natural_kernel<BF16, SK_ROWS>;
+    static bool configured = false;   // the static reduction buffer plus this block exceed the default LDS ceiling
+    if (!configured) {
+        (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SKN_BYTES);
+        configured = true;
+    }
+    hipLaunchKernelGGL(kern, dim3((M + SK_ROWS - 1) / SK_ROWS), dim3(SK_WAVES * 64), SKN_BYTES, s, act, small, out, M, C, r);
+}
+
 void launch_lora_u(const void *dy, const void *B, void *bt, void *u, int M, int N, int r, bool bf16, hipStream_t s)
 {
+    if (r <= 16) {      // B is read as it lies in memory
+        const uint16_t *a = (const uint16_t *)dy, *b = (const uint16_t *)B;
+        uint16_t *o = (uint16_t *)u;
+        if (M >= 16 * 256) {
+            if (bf16) launch_skinny_natural<true, 16>(a, b, o, M, N, r, s);
+            else launch_skinny_natural<false, 16>(a, b, o, M, N, r, s);
+        } else {
+            if (bf16) launch_skinny_natural<true, 8>(a, b, o, M, N, r, s);
+            else launch_skinny_natural<false, 8>(a, b, o, M, N, r, s);
+        }
+        return;
+    }
     const long n = (long)N * r;
     hipLaunchKernelGGL(transpose_small_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (const uint16_t *)B,
                        (uint16_t *)bt, N, r);

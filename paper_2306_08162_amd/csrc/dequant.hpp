@@ -47,10 +47,12 @@ struct DequantConst<BITS, true> {
     }
 };
 
-// (byte b of x) -> [b, 0, b, 0]
+// (byte b of x) -> [b, 0x64, b, 0x64]: the byte in the low byte of both 16-bit lanes, the exponent byte of 1024.0
+// above it, picked from the first source of the byte permute (selector 5 = its byte 1).  Masking the unwanted code
+// bits away (with the 0x64 bytes kept by the mask) leaves the two fp16 values 1024 + c * 2^p.
 __device__ __forceinline__ uint32_t spread_byte(uint32_t x, int b)
 {
-    return __builtin_amdgcn_perm(0u, x, 0x0C000C00u | ((uint32_t)b << 16) | (uint32_t)b);
+    return __builtin_amdgcn_perm(0x64006400u, x, 0x05000500u | ((uint32_t)b << 16) | (uint32_t)b);
 }
 
 __device__ __forceinline__ uint32_t h2_bits(half2_t v) { return __builtin_bit_cast(uint32_t, v); }
@@ -82,30 +84,30 @@ __device__ __forceinline__ u16x8_t dequant8(const uint32_t (&w)[BITS], int part,
             const half2_t mul = {(half_t)1.f, (half_t)0.0625f};
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                out[i] = fp16_pair((spread_byte(x, i) & 0x00F0000Fu) | MAGIC, mul, c.off[0], c.s2);
+                out[i] = fp16_pair(spread_byte(x, i) & (0x00F0000Fu | MAGIC), mul, c.off[0], c.s2);
         } else if constexpr (BITS == 2) {
             const uint32_t x = w[part >> 1];
             const half2_t mul0 = {(half_t)1.f, (half_t)0.25f}, mul1 = {(half_t)0.0625f, (half_t)0.015625f};
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
                 const uint32_t p = spread_byte(x, 2 * (part & 1) + i);
-                out[2 * i] = fp16_pair((p & 0x000C0003u) | MAGIC, mul0, c.off[0], c.s2);
-                out[2 * i + 1] = fp16_pair((p & 0x00C00030u) | MAGIC, mul1, c.off[1], c.s2);
+                out[2 * i] = fp16_pair(p & (0x000C0003u | MAGIC), mul0, c.off[0], c.s2);
+                out[2 * i + 1] = fp16_pair(p & (0x00C00030u | MAGIC), mul1, c.off[1], c.s2);
             }
         } else if constexpr (BITS == 8) {
             const half2_t one = {(half_t)1.f, (half_t)1.f};
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const uint32_t x = w[2 * part + (i >> 1)];
-                const uint32_t sel = (i & 1) ? 0x0C030C02u : 0x0C010C00u;   // [b0,0,b1,0] or [b2,0,b3,0]
-                out[i] = fp16_pair(__builtin_amdgcn_perm(0u, x, sel) | MAGIC, one, c.off[0], c.s2);
+                const uint32_t sel = (i & 1) ? 0x05030502u : 0x05010500u;   // [b0,0x64,b1,0x64] or [b2,0x64,b3,0x64]
+                out[i] = fp16_pair(__builtin_amdgcn_perm(MAGIC, x, sel), one, c.off[0], c.s2);
             }
         } else {   // BITS == 3: eight codes = 24 bits starting at bit 24*part
             const uint32_t x = window<BITS>(w, 24 * part);
             const half2_t mul = {(half_t)1.f, (half_t)0.125f};
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                out[i] = fp16_pair((spread_byte(x >> (6 * i), 0) & 0x00380007u) | MAGIC, mul, c.off[0], c.s2);
+                out[i] = fp16_pair(spread_byte(x >> (6 * i), 0) & (0x00380007u | MAGIC), mul, c.off[0], c.s2);
         }
     } else {
         constexpr uint32_t mask = (1u << BITS) - 1u;
