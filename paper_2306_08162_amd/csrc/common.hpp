@@ -87,4 +87,15 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
+// Direct-to-LDS load: every lane fetches 16 bytes from base + its own 32-bit byte offset, and the 64 pieces land
+// contiguously at the wave-uniform LDS byte address `lds` (1 KB, lane l at lds + 16 l).  Written as assembly so that
+// the compiler does not order it against the LDS reads around it; completion is tracked by the vector-memory
+// counter, which the caller waits on itself (the compiler does not see these loads).
+__device__ __forceinline__ void dma16(const void *base, uint32_t byte_offset, uint32_t lds)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 ::"v"(byte_offset), "s"(base), "s"(lds)
+                 : "memory");   // m0 is reserved by the compiler: it never keeps a value there across other code
+}
+
 }  // namespace qlora

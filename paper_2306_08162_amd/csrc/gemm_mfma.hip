@@ -82,17 +82,6 @@ struct StageRegs {
     bool ok[WU];        // false: the unit lies outside the weight, stage zeros
 };
 
-// Direct-to-LDS load: every lane fetches 16 bytes from base + its own 32-bit byte offset, and the 64 pieces land contiguously
-// at the wave-uniform LDS byte address `lds` (1 KB).  Written as assembly so that the compiler does not order it
-// against the LDS fragment reads around it: the stage it fills is never one that is being read (see the stage
-// rotation in the kernel), which the compiler cannot know.  Completion is tracked by the vector-memory counter.
-__device__ __forceinline__ void dma16(const void *base, uint32_t byte_offset, uint32_t lds)
-{
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 ::"v"(byte_offset), "s"(base), "s"(lds)
-                 : "memory");   // m0 is reserved by the compiler: it never keeps a value there across other code
-}
-
 // wait until at most N vector-memory operations of this wave are outstanding, then meet the workgroup
 template <int N>
 __device__ __forceinline__ void wait_vm_and_barrier()

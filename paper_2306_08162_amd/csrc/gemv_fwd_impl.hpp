@@ -179,13 +179,6 @@ constexpr int ST_BLOCK = 4096;      // bytes of one 16-row x 128-column block
 #endif
 constexpr int ST_U = QLORA_ST_U;    // iterations whose packed words are requested together
 
-__device__ __forceinline__ void dma16(const void *base, uint32_t byte_offset, uint32_t lds)
-{
-    // lane l of the wave writes its 16 bytes to LDS byte address lds + 16 l; completion counts on vmcnt
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(byte_offset), "s"(base), "s"(lds)
-                 : "memory");
-}
-
 template <int N>
 __device__ __forceinline__ void wait_vm()
 {
