@@ -213,7 +213,7 @@ struct GradArgs {
     const uint8_t *keep;    // LoRA dropout: keep bits of x (the second problem's act), [M, C1/8] bytes, or NULL
 };
 
-template <bool BF16, int RG>
+template <bool BF16, int RG, bool MASKED>   // MASKED: a.keep != NULL (kept out of the load loop as a template argument)
 __global__ __launch_bounds__(256) void adapter_grad_partial_kernel(const GradArgs a)
 {
     constexpr int GR_ROWS = grad_rows(RG), GR_CHUNKS = GR_ROWS / 32;
@@ -237,7 +237,7 @@ __global__ __launch_bounds__(256) void adapter_grad_partial_kernel(const GradArg
             const int m = m0 + ch * 32 + rr;
             const bool in = m < M && c0 + cc < C;
             v[ch] = *(const u16x8_t *)(act + (in ? (long)m * C + c0 + cc : 0));
-            if (which && a.keep) v[ch] = keep_halves(v[ch], a.keep[in ? (long)m * (C / 8) + ((c0 + cc) >> 3) : 0]);
+            if (MASKED && which) v[ch] = keep_halves(v[ch], a.keep[in ? (long)m * (C / 8) + ((c0 + cc) >> 3) : 0]);
             if (!in) v[ch] = u16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
         }
 #pragma unroll
@@ -339,12 +339,17 @@ void launch_grad_partial(const GradArgs &a, hipStream_t s)
 {
     const int nb1 = (a.C[1] + GR_COLS - 1) / GR_COLS;
     const dim3 grid(a.nb0 + nb1, a.slices), block(256);
+#define QLORA_GRAD_CASE(RG)                                                                                   \
+    if (a.keep) hipLaunchKernelGGL((adapter_grad_partial_kernel<BF16, RG, true>), grid, block, 0, s, a);        \
+    else hipLaunchKernelGGL((adapter_grad_partial_kernel<BF16, RG, false>), grid, block, 0, s, a);              \
+    break
     switch ((a.r + 15) / 16) {
-    case 1: hipLaunchKernelGGL((adapter_grad_partial_kernel<BF16, 1>), grid, block, 0, s, a); break;
-    case 2: hipLaunchKernelGGL((adapter_grad_partial_kernel<BF16, 2>), grid, block, 0, s, a); break;
-    case 3: hipLaunchKernelGGL((adapter_grad_partial_kernel<BF16, 3>), grid, block, 0, s, a); break;
-    default: hipLaunchKernelGGL((adapter_grad_partial_kernel<BF16, 4>), grid, block, 0, s, a); break;
+    case 1: QLORA_GRAD_CASE(1);
+    case 2: QLORA_GRAD_CASE(2);
+    case 3: QLORA_GRAD_CASE(3);
+    default: QLORA_GRAD_CASE(4);
     }
+#undef QLORA_GRAD_CASE
 }
 
 }  // namespace
