@@ -227,6 +227,16 @@ def backward_adapters(dy, x, A, B, alpha: float) -> Tuple[np.ndarray, np.ndarray
     return dA, dB
 
 
+def backward_adapters_stacked(dy, x, A, B, alpha: float, frozen_rank: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Stacked adapters (App. D: a recovery adapter trained by LREC stays on the layer, frozen, while a second pair is
+    trained on the task): A = [A_frozen; A_train] (r rows), B = [B_frozen, B_train] (r columns), scaling alpha / r
+    for the whole stack.  Only the trainable pair has gradients: the rows frozen_rank.. of dA and the columns
+    frozen_rank.. of dB of the full-stack gradient; dX is that of the full stack.  Returns (dA_train [r-f, K],
+    dB_train [N, r-f])."""
+    dA, dB = backward_adapters(dy, x, A, B, alpha)
+    return np.ascontiguousarray(dA[frozen_rank:, :]), np.ascontiguousarray(dB[:, frozen_rank:])
+
+
 # ------------------------------------------------------------ LoRA dropout
 # Appendix B trains with a dropout rate of 0.05.  Reading: as in the LoRA method the paper builds on, dropout acts on
 # the input of the low-rank branch only, with inverted scaling; the frozen quantized path sees x itself:

@@ -484,3 +484,39 @@ def test_packed_zero_points_match_bigint_stream_and_roundtrip(b, groups):
         stream = sum(int(v) << (b * i) for i, v in enumerate(z[n]))
         assert P[n].tolist() == [(stream >> (32 * w)) & 0xFFFFFFFF for w in range(P.shape[1])]
     assert np.array_equal(oracle.unpack_zeros(P, groups, b), z)
+
+
+# ------------------------------------------------- stacked adapters (App. D)
+
+def test_stacked_adapters_forward_is_the_sum_of_the_two_branches_and_gradients_by_finite_differences():
+    p = _small_problem(640, M=4, N=10, K=64, r=8, b=4, G=32)
+    f = 6                                                       # frozen rows / columns of the stack
+    A, B, x, dy, Wd, alpha = p["A"], p["B"], p["x"], p["dy"], p["Wd"], p["alpha"]
+    sc = alpha / A.shape[0]
+    # the stack is the sum of its two pairs, both scaled by alpha / (total rank)
+    y, _ = oracle.forward(x, Wd, A, B, alpha)
+    y_two = x @ Wd.T + sc * (x @ A[:f].T) @ B[:, :f].T + sc * (x @ A[f:].T) @ B[:, f:].T
+    np.testing.assert_allclose(y, y_two, rtol=1e-12, atol=1e-12)
+    dA_t, dB_t = oracle.backward_adapters_stacked(dy, x, A, B, alpha, f)
+    assert dA_t.shape == (2, 64) and dB_t.shape == (10, 2)
+    # central differences on trainable entries only (L = <dY, y> is linear in each of A and B)
+    L = lambda A_, B_: float(np.sum(dy * oracle.forward(x, Wd, A_, B_, alpha)[0]))
+    h = 1e-3
+    rng = np.random.RandomState(3)
+    for _ in range(10):
+        j, k = rng.randint(f, 8), rng.randint(0, 64)
+        Ap, Am = A.copy(), A.copy()
+        Ap[j, k] += h
+        Am[j, k] -= h
+        fd = (L(Ap, B) - L(Am, B)) / (2 * h)
+        assert abs(fd - dA_t[j - f, k]) <= 1e-8 * max(1.0, abs(fd))
+        n = rng.randint(0, 10)
+        Bp, Bm = B.copy(), B.copy()
+        Bp[n, j] += h
+        Bm[n, j] -= h
+        fd = (L(A, Bp) - L(A, Bm)) / (2 * h)
+        assert abs(fd - dB_t[n, j - f]) <= 1e-8 * max(1.0, abs(fd))
+    # nothing frozen: the plain gradients
+    dA, dB = oracle.backward_adapters(dy, x, A, B, alpha)
+    dA0, dB0 = oracle.backward_adapters_stacked(dy, x, A, B, alpha, 0)
+    assert np.array_equal(dA0, dA) and np.array_equal(dB0, dB)
