@@ -272,6 +272,35 @@ def run_actorder_gather(M: int = 2048, K: int = 4096, G: int = 128, iters: int =
             "plain_copy_us_same_box": round(copy_us, 2), "calls_per_fwd_bwd": 2}
 
 
+def run_stacked(iters: int = 20):
+    """Stacked adapters on the headline projection (App. D: a frozen rank-32 recovery pair plus a trainable rank-8
+    pair): the backward pass with gradients for all 40 adapter columns against the one that forms them for the
+    trainable 8 only.  HIP events around `iters` back-to-back calls."""
+    import dataclasses
+    import torch
+    from paper_2306_08162_amd import workloads as wl
+    from paper_2306_08162_amd.device import DeviceLayer
+    from paper_2306_08162_amd.hiprt import Event
+    cfg = dataclasses.replace(wl.config2(), rank=40, alpha=80.0, name="c2_qproj_int4_rank32+8")
+    layer = DeviceLayer(wl.make_inputs(cfg))
+    layer.forward()
+    stream = torch.cuda.current_stream().cuda_stream or None
+    out = {}
+    for label, call in (("all_40_columns", lambda: layer.backward()), ("trainable_8_only", lambda: layer.backward_stacked(32))):
+        for _ in range(5):
+            call()
+        torch.cuda.synchronize()
+        e0, e1 = Event(), Event()
+        e0.record(stream)
+        for _ in range(iters):
+            call()
+        e1.record(stream)
+        e1.synchronize()
+        out[label + "_bwd_us"] = round(e0.elapsed_ms(e1) * 1e3 / iters, 2)
+    out["workload"] = f"{cfg.name}: M={cfg.M} K={cfg.K} N={cfg.N} INT{cfg.bits} fp16, backward pass"
+    return out
+
+
 def run_cpu_baseline(inp, max_rows: int):
     """The fp64 oracle as it stands, on the host cores: forward + backward on the first `max_rows` token rows."""
     import oracle
@@ -347,6 +376,7 @@ def main() -> int:
                              **run_small_m(16)}
         result["lrec_loss"] = run_lrec_loss()
         result["actorder_gather"] = run_actorder_gather()
+        result["stacked_adapters"] = run_stacked()
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = run_cpu_baseline(inp, args.cpu_rows)
     print(json.dumps(result))

@@ -202,6 +202,24 @@ int qlora_linear_bwd_dropout(const void *dy, const void *x, const uint32_t *pack
                              void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Backward pass for stacked adapters (App. D: the recovery adapter that LREC
+ * trained stays on the layer, frozen, while a second pair is trained on the
+ * task).  The stack is passed as one adapter of `rank` columns, A = [A_frozen;
+ * A_train] [rank, K], B = [B_frozen, B_train] [N, rank], scaled by alpha / rank
+ * as a whole; the forward pass is qlora_linear_fwd with that rank.  dx is the
+ * gradient through the whole stack; gradients are formed for the trainable
+ * pair only: dA_train [rank - frozen_rank, K], dB_train [N, rank - frozen_rank]
+ * (beta as in qlora_linear_bwd_accumulate).  frozen_rank is a multiple of 8,
+ * 0 <= frozen_rank < rank (0: the same as qlora_linear_bwd_accumulate), else
+ * QLORA_E_RANK.  Workspace as for qlora_linear_bwd.
+ */
+int qlora_linear_bwd_stacked(const void *dy, const void *x, const uint32_t *packed, const void *scales,
+                             const uint8_t *zeros, const void *A, const void *B, const void *t_saved, void *dx,
+                             float *dA_train, float *dB_train, float beta, int frozen_rank,
+                             int M, int N, int K, int bits, int group_size, int rank, float alpha, int dtype,
+                             void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Sibling projections at small token counts.  Projections that read the same
  * input (q/k/v of an attention block, gate/up of an MLP; the paper adapts "every
  * linear projection", Appendix C) can be handed over together: one launch

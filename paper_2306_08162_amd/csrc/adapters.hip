@@ -208,7 +208,9 @@ struct GradArgs {
     float *out[2];          // dB [C0, r] and dA [r, C1]
     int C[2];
     int nb0;                // column blocks of the first problem
-    int M, r, slices;
+    int M, r, slices;       // r: adapter columns the gradients are formed for
+    int side_pitch, side_c0;   // side is [M, side_pitch]; its columns side_c0 .. side_c0 + r are used (stacked adapters:
+                               // the leading side_c0 columns belong to a frozen pair)
     float sc[2], beta;      // out = beta * out + sc * sum (beta == 0: out is not read)
     const uint8_t *keep;    // LoRA dropout: keep bits of x (the second problem's act), [M, C1/8] bytes, or NULL
 };
@@ -250,7 +252,7 @@ __global__ __launch_bounds__(256) void adapter_grad_partial_kernel(const GradArg
         for (int e = tid; e < GR_ROWS * RG * 2; e += 256) {     // side rows, padded to RG*16 columns, 8 at a time
             const int row = e / (RG * 2), j = (e % (RG * 2)) * 8;
             const bool in = m0 + row < M && j < r;
-            u16x8_t sv = *(const u16x8_t *)(side + (in ? (long)(m0 + row) * r + j : 0));
+            u16x8_t sv = *(const u16x8_t *)(side + (in ? (long)(m0 + row) * a.side_pitch + a.side_c0 + j : 0));
             if (!in) sv = u16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
             uint32_t *sd = (uint32_t *)(Ss + row * SP + j);
             const u32x4_t sw = __builtin_bit_cast(u32x4_t, sv);
@@ -469,9 +471,10 @@ int adapter_grad_slices(int M, int r)
 }
 
 void launch_adapter_grads(const void *dy, const void *t, const void *x, const void *u, float *dB, float *dA,
-                          float *partial, int M, int N, int K, int r, float sc, float beta, const uint32_t *keep,
-                          float keep_scale, bool bf16, hipStream_t s)
+                          float *partial, int M, int N, int K, int r_all, int frozen, float sc, float beta,
+                          const uint32_t *keep, float keep_scale, bool bf16, hipStream_t s)
 {
+    const int r = r_all - frozen;
     const int slices = adapter_grad_slices(M, r);
     GradArgs a;
     a.act[0] = (const uint16_t *)dy;
@@ -487,6 +490,8 @@ void launch_adapter_grads(const void *dy, const void *t, const void *x, const vo
     a.nb0 = (N + GR_COLS - 1) / GR_COLS;
     a.M = M;
     a.r = r;
+    a.side_pitch = r_all;
+    a.side_c0 = frozen;
     a.slices = slices;
     a.sc[0] = sc;
     a.sc[1] = keep ? sc * keep_scale : sc;

@@ -284,14 +284,16 @@ int qlora_linear_bwd_accumulate(const void *dy, const void *x, const uint32_t *p
                                     K, bits, group_size, rank, alpha, dtype, workspace, workspace_bytes, stream);
 }
 
-int qlora_linear_bwd_dropout(const void *dy, const void *x, const uint32_t *packed, const void *scales,
-                             const uint8_t *zeros, const void *A, const void *B, const uint32_t *keep_mask,
-                             float keep_scale, const void *t_saved, void *dx, float *dA, float *dB, float beta, int M,
-                             int N, int K, int bits, int group_size, int rank, float alpha, int dtype,
-                             void *workspace, size_t workspace_bytes, void *stream)
+// The backward pass behind every single-projection entry point.  frozen: leading adapter columns without gradients.
+static int backward(const void *dy, const void *x, const uint32_t *packed, const void *scales, const uint8_t *zeros,
+                    const void *A, const void *B, const uint32_t *keep_mask, float keep_scale, const void *t_saved,
+                    void *dx, float *dA, float *dB, float beta, int frozen, int M, int N, int K, int bits,
+                    int group_size, int rank, float alpha, int dtype, void *workspace, size_t workspace_bytes,
+                    void *stream)
 {
     const int st = check_problem(M, N, K, bits, group_size, rank, dtype);
     if (st != QLORA_OK) return st;
+    if (frozen < 0 || frozen % 8 != 0 || (frozen > 0 && frozen >= rank)) return QLORA_E_RANK;
     if (!dy || !packed || !scales || !zeros || !dx) return QLORA_E_NULL;
     if (rank > 0 && (!x || !A || !B || !dA || !dB)) return QLORA_E_NULL;
     if (misaligned(dy) || misaligned(x) || misaligned(packed) || misaligned(scales) || misaligned(zeros) ||
@@ -314,7 +316,8 @@ int qlora_linear_bwd_dropout(const void *dy, const void *x, const uint32_t *pack
         }
         GemmTimer timer(s);
         launch_bwd_small(p, 1, &dy, x, &packed, &scales, &zeros, &A, &B, &t, dx, &dA, &dB, &N,
-                         (float *)(ws + w.partial_off), (float *)(ws + w.upartial_off), beta, keep_mask, keep_scale, s);
+                         (float *)(ws + w.partial_off), (float *)(ws + w.upartial_off), beta, keep_mask, keep_scale, frozen,
+                         s);
         return hip_status();
     }
     void *u = nullptr;
@@ -341,9 +344,30 @@ int qlora_linear_bwd_dropout(const void *dy, const void *x, const uint32_t *pack
             t = ws + w.t_off;
         }
         float *partial = (float *)(ws + w.partial_off);
-        launch_adapter_grads(dy, t, x, u, dB, dA, partial, M, N, K, rank, p.sc, beta, keep_mask, keep_scale, p.bf16, s);
+        launch_adapter_grads(dy, t, x, u, dB, dA, partial, M, N, K, rank, frozen, p.sc, beta, keep_mask, keep_scale,
+                             p.bf16, s);
     }
     return hip_status();
+}
+
+int qlora_linear_bwd_dropout(const void *dy, const void *x, const uint32_t *packed, const void *scales,
+                             const uint8_t *zeros, const void *A, const void *B, const uint32_t *keep_mask,
+                             float keep_scale, const void *t_saved, void *dx, float *dA, float *dB, float beta, int M,
+                             int N, int K, int bits, int group_size, int rank, float alpha, int dtype,
+                             void *workspace, size_t workspace_bytes, void *stream)
+{
+    return backward(dy, x, packed, scales, zeros, A, B, keep_mask, keep_scale, t_saved, dx, dA, dB, beta, 0, M, N, K,
+                    bits, group_size, rank, alpha, dtype, workspace, workspace_bytes, stream);
+}
+
+int qlora_linear_bwd_stacked(const void *dy, const void *x, const uint32_t *packed, const void *scales,
+                             const uint8_t *zeros, const void *A, const void *B, const void *t_saved, void *dx,
+                             float *dA_train, float *dB_train, float beta, int frozen_rank, int M, int N, int K,
+                             int bits, int group_size, int rank, float alpha, int dtype, void *workspace,
+                             size_t workspace_bytes, void *stream)
+{
+    return backward(dy, x, packed, scales, zeros, A, B, nullptr, 1.f, t_saved, dx, dA_train, dB_train, beta,
+                    frozen_rank, M, N, K, bits, group_size, rank, alpha, dtype, workspace, workspace_bytes, stream);
 }
 
 namespace {
@@ -462,7 +486,7 @@ int qlora_linear_bwd_siblings(int count, const void *const *dy, const void *x, c
     }
     GemmTimer timer(s);
     launch_bwd_small(p, count, dy, x, packed, scales, zeros, A, B, t, dx, dA, dB, N, (float *)(ws + w.partial_off),
-                     (float *)(ws + w.upartial_off), 0.f, nullptr, 1.f, s);
+                     (float *)(ws + w.upartial_off), 0.f, nullptr, 1.f, 0, s);
     return hip_status();
 }
 

@@ -295,6 +295,7 @@ struct FinishArgs {
     float sc, beta;      // dA = beta * dA + ..., dB likewise (beta == 0: they are not read)
     const uint8_t *keep; // LoRA dropout: keep bits of x as bytes [M, K/8], or NULL
     float keep_scale;
+    int r0;              // stacked adapters: adapter columns below r0 are frozen; dA is [r - r0, K], dB [N, r - r0]
 };
 
 // MASKED (a.keep != NULL) is a template argument: a test of the pointer inside the token loop kept the compiler from
@@ -342,8 +343,8 @@ __global__ __launch_bounds__(256) void gemv_bwd_finish_kernel(const FinishArgs a
         a.dx[idx] = to16<BF16>(v + a.sc * lo);
     } else if (b < a.xb + a.ab) {
         const long idx = (long)(b - a.xb) * 256 + threadIdx.x;
-        if (idx >= (long)r * K) return;
-        const int j = (int)(idx / K), k = (int)(idx % K);
+        if (idx >= (long)(r - a.r0) * K) return;
+        const int j = a.r0 + (int)(idx / K), k = (int)(idx % K);
         float v = 0.f;
         for (int m = 0; m < M; ++m) {
             float xv = cvt16<BF16>(a.x[(long)m * K + k]);
@@ -353,11 +354,11 @@ __global__ __launch_bounds__(256) void gemv_bwd_finish_kernel(const FinishArgs a
         a.dA[idx] = a.beta == 0.f ? a.sc * v : fmaf(a.beta, a.dA[idx], a.sc * v);
     } else {
         const long idx = (long)(b - a.xb - a.ab) * 256 + threadIdx.x;
-        if (idx >= (long)r * N) return;
-        const int j = (int)(idx / N), n = (int)(idx % N);
+        if (idx >= (long)(r - a.r0) * N) return;
+        const int j = a.r0 + (int)(idx / N), n = (int)(idx % N);
         float v = 0.f;
         for (int m = 0; m < M; ++m) v += cvt16<BF16>(a.dy[(long)m * N + n]) * side[m][j];
-        float *dst = a.dB + (long)n * r + j;
+        float *dst = a.dB + (long)n * (r - a.r0) + (j - a.r0);
         *dst = a.beta == 0.f ? a.sc * v : fmaf(a.beta, *dst, a.sc * v);
     }
 }
@@ -527,7 +528,7 @@ void launch_bwd_small(const Problem &p, int count, const void *const *dy, const 
                       const uint32_t *const *packed, const void *const *scales, const uint8_t *const *zeros,
                       const void *const *A, const void *const *B, const void *const *t, void *dx, float *const *dA,
                       float *const *dB, const int *N, float *partial, float *upartial, float beta, const uint32_t *keep,
-                      float keep_scale, hipStream_t s)
+                      float keep_scale, int frozen, hipStream_t s)
 {
     int slices[MAX_SIBLINGS];
     const int total = gemv_bwd_slices_siblings(count, N, p.K, p.bits, slices);
@@ -543,13 +544,14 @@ void launch_bwd_small(const Problem &p, int count, const void *const *dy, const 
         m.slice_end[i] = end;
     }
     QLORA_BITS_DTYPE(launch_bwd_bits, m, s);
-    const int xb = (int)(((long)p.M * p.K + 255) / 256), ab = (int)(((long)p.r * p.K + 255) / 256);
+    const int rt = count == 1 ? p.r - frozen : p.r;     // adapter columns with gradients (siblings: no frozen part)
+    const int xb = (int)(((long)p.M * p.K + 255) / 256), ab = (int)(((long)rt * p.K + 255) / 256);
     if (count == 1) {
-        const int bb = (int)(((long)p.r * N[0] + 255) / 256);
+        const int bb = (int)(((long)rt * N[0] + 255) / 256);
         const FinishArgs f{partial, upartial, (const uint16_t *)(A ? A[0] : nullptr), (const uint16_t *)x,
                            (const uint16_t *)dy[0], (const uint16_t *)(t ? t[0] : nullptr), (uint16_t *)dx,
                            dA ? dA[0] : nullptr, dB ? dB[0] : nullptr, p.M, N[0], p.K, p.r, total, xb, ab, p.sc, beta,
-                           (const uint8_t *)keep, keep_scale};
+                           (const uint8_t *)keep, keep_scale, frozen};
         const dim3 grid(xb + ab + bb), block(256);
         if (keep) {
             if (p.bf16) hipLaunchKernelGGL((gemv_bwd_finish_kernel<true, true>), grid, block, 0, s, f);

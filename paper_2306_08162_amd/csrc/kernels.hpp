@@ -40,10 +40,11 @@ void launch_lora_u(const void *dy, const void *B, void *bt, void *u, int M, int 
 int adapter_grad_slices(int M, int r);
 // dB[N,r] = sc * dy[M,N]^T t[M,r] and dA[r,K] = sc * u[M,r]^T x[M,K], two launches for both (slice partial sums,
 // then their fixed-order reduction); partial holds slices*(N+K)*r floats.  beta != 0: dB = beta*dB + ..., dA likewise.
-// keep != NULL (LoRA dropout): x stands for keep_scale * x * keep in dA.
+// keep != NULL (LoRA dropout): x stands for keep_scale * x * keep in dA.  Stacked adapters: t and u are [M, r_all],
+// the first `frozen` adapter columns have no gradient, r = r_all - frozen, dB is [N, r], dA [r, K].
 void launch_adapter_grads(const void *dy, const void *t, const void *x, const void *u, float *dB, float *dA,
-                          float *partial, int M, int N, int K, int r, float sc, float beta, const uint32_t *keep,
-                          float keep_scale, bool bf16, hipStream_t s);
+                          float *partial, int M, int N, int K, int r_all, int frozen, float sc, float beta,
+                          const uint32_t *keep, float keep_scale, bool bf16, hipStream_t s);
 
 // gemm_mfma.hip -- tiled MFMA GEMMs with fused dequantisation (any accepted shape)
 void launch_fwd_mfma(const Problem &p, const void *x, const uint32_t *packed, const void *scales,
@@ -72,11 +73,13 @@ int gemv_bwd_slices_siblings(int count, const int *N, int K, int bits, int *slic
 // total_slices*1024 floats; t may be NULL if r == 0; beta != 0 accumulates into dA[i], dB[i] (beta*old + new).  The
 // arrays are host arrays of `count` device pointers.  keep != NULL (LoRA dropout, single projection only): the
 // adapter's share of dX is multiplied by keep_scale * keep and x stands for keep_scale * x * keep in dA.
+// frozen (single projection only): the first `frozen` adapter columns have no gradient; dA is [r - frozen, K], dB
+// [N, r - frozen].
 void launch_bwd_small(const Problem &p, int count, const void *const *dy, const void *x,
                       const uint32_t *const *packed, const void *const *scales, const uint8_t *const *zeros,
                       const void *const *A, const void *const *B, const void *const *t, void *dx, float *const *dA,
                       float *const *dB, const int *N, float *partial, float *upartial, float beta, const uint32_t *keep,
-                      float keep_scale, hipStream_t s);
+                      float keep_scale, int frozen, hipStream_t s);
 
 // loss.hip -- the LREC objective (KL student || teacher + next-token CE, mean over tokens) and its gradient
 // kl, ce (per token) and grad may be NULL; tok receives lambda_kl*KL + lambda_ce*CE per token, loss_mean their mean

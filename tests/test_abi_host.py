@@ -275,3 +275,14 @@ def test_packed_zero_words_and_errors():
     assert ql.qlora_pack_zeros(None, None, 8, 4, 4, stream=0, check=False) == E("QLORA_E_NULL")
     assert ql.qlora_unpack_zeros(None, None, 8, 4, 6, stream=0, check=False) == E("QLORA_E_BITS")
     assert ql.qlora_unpack_zeros(None, None, 8, 0, 4, stream=0, check=False) == E("QLORA_E_SHAPE")
+
+
+def test_stacked_backward_rejects_bad_frozen_rank():
+    E = ql.STATUS_NAMES.index
+    args = lambda frozen, rank: ql.qlora_linear_bwd_stacked(None, None, None, None, None, None, None, None, None, None, None,
+                                                             0.0, frozen, 32, 64, 128, 4, 64, rank, 16.0, ql.QLORA_F16, None, 0,
+                                                             stream=0, check=False)
+    assert args(4, 16) == E("QLORA_E_RANK")          # not a multiple of 8
+    assert args(16, 16) == E("QLORA_E_RANK")         # nothing left to train
+    assert args(-8, 16) == E("QLORA_E_RANK")
+    assert args(8, 16) == E("QLORA_E_NULL")          # accepted, then the NULL buffers are caught
