@@ -290,6 +290,132 @@ __global__ __launch_bounds__(256) void adapter_grad_partial_kernel(const GradArg
     }
 }
 
+// ------------------------------------------------------------------------------------------------------------
+// dB and dA in one pass, without slice partial sums (ranks <= 16, no dropout mask): a workgroup owns 32 columns of
+// dY (for dB) or x (for dA) and walks all token rows.  Each of its eight waves takes 64-row stretches (wave w the
+// stretches w, w + 8, ...): it pulls the stretch of its 32 columns (64 bytes per row) and of the side operand (t or
+// u, its trainable columns) into one of two wave-private LDS buffers with direct-to-LDS loads -- the next stretch is
+// in flight while this one is multiplied, the wave waits on its own loads, no workgroup barrier in the loop -- and
+// gathers both MFMA operands (the contraction runs over the row index, the strided one) with the transposing LDS
+// read.  The eight partial results are added in wave order at the end and written as out = beta * out + sc * sum.
+// Measured at 2048 x (4096 + 4096), rank 8: 8.2 us against 9.9 + 4.7 us for the slice sums and their reduction.
+// ------------------------------------------------------------------------------------------------------------
+constexpr int GO_COLS = 32, GO_ROWS = 64, GO_WAVES = 8;
+constexpr int GO_ACT_BYTES = GO_ROWS * GO_COLS * 2;          // 8 KB: 8 loads of 16 rows x 64 bytes
+constexpr int GO_SIDE_BYTES = GO_ROWS * 16 * 2;              // up to 16 side columns per row
+constexpr int GO_BUF_BYTES = GO_ACT_BYTES + GO_SIDE_BYTES;   // one stretch; every wave has two such buffers
+template <bool BF16, int R>                                  // R: side columns, 8 or 16
+__global__ __launch_bounds__(GO_WAVES * 64) void adapter_grad_onepass_kernel(const GradArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) char go_lds[];   // [GO_WAVES][2] buffers, then reused for the final sum
+    typedef short s16x4_t __attribute__((ext_vector_type(4)));
+    typedef __attribute__((address_space(3))) s16x4_t *lds4_t;
+    constexpr int PR = R / 8, S_ROWS = 64 / PR;              // 16-byte pieces per side row; side rows per load
+    constexpr int LOADS = GO_ROWS / 16 + GO_ROWS / S_ROWS;   // direct-to-LDS loads per stretch
+    // Consecutive workgroup ids land on different XCDs; a 32-column block is half a 128-byte line per row, so each
+    // XCD is handed a contiguous run of column blocks: both halves of a line are then fetched through the same L2.
+    int blk;
+    {
+        const int nt = gridDim.x, bid = blockIdx.x;
+        const int xcd = bid & 7, loc = bid >> 3, per = nt >> 3, rem = nt & 7;
+        blk = xcd * per + min(xcd, rem) + loc;
+    }
+    const int which = blk >= a.nb0 ? 1 : 0;
+    const uint16_t *__restrict__ act = a.act[which];
+    const uint16_t *__restrict__ side = a.side[which];
+    const int M = a.M, C = a.C[which];
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int c0 = (blk - (which ? a.nb0 : 0)) * GO_COLS;
+    const int li = lane & 15, q = lane >> 4;
+    char *mine = go_lds + wave * (2 * GO_BUF_BYTES);
+    const uint32_t mine_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)mine;
+
+    // what this lane fetches: of the activations, piece lane % 4 (8 columns) of row lane / 4 of every 16-row block;
+    // of the side operand, piece lane % PR of row lane / PR of every S_ROWS-row block
+    const int a_row = lane >> 2, a_col = min(c0 + 8 * (lane & 3), C - 8);
+    const int s_row = lane / PR, s_col = a.side_c0 + 8 * (lane % PR);
+    // transposing reads (see skinny_rows_natural_kernel): lane (e = li / 4, g = li % 4) of block q points at row
+    // 8 q + e, columns 4 g .. + 4 of a 32-row chunk; the second read of a fragment starts four rows further down
+    const int t_row = 8 * q + (li >> 2);
+    const int act_rd = t_row * (GO_COLS * 2) + 8 * (li & 3);                      // + 32 for the second 16 columns
+    const int side_rd = GO_ACT_BYTES + t_row * (R * 2) + 2 * min(4 * (li & 3), R - 4);
+    const bool jval = li < R;
+
+    // this wave's stretches: rows (GO_WAVES i + wave) * GO_ROWS .. + GO_ROWS, i = 0, 1, ...; two are in flight
+    auto fetch = [&](int m0, int buf) {
+        const uint32_t base = mine_lds + buf * GO_BUF_BYTES;
+#pragma unroll
+        for (int b = 0; b < GO_ROWS / 16; ++b) {
+            const uint32_t row = (uint32_t)min(m0 + 16 * b + a_row, M - 1);     // past the end: copies of the last row
+            dma16(act, (row * (uint32_t)C + (uint32_t)a_col) * 2u,
+                  (uint32_t)__builtin_amdgcn_readfirstlane((int)(base + b * 1024)));
+        }
+#pragma unroll
+        for (int b = 0; b < GO_ROWS / S_ROWS; ++b) {
+            const uint32_t row = (uint32_t)min(m0 + S_ROWS * b + s_row, M - 1);
+            dma16(side, (row * (uint32_t)a.side_pitch + (uint32_t)s_col) * 2u,
+                  (uint32_t)__builtin_amdgcn_readfirstlane((int)(base + GO_ACT_BYTES + b * 1024)));
+        }
+    };
+    float4_t acc[2] = {float4_t{0.f, 0.f, 0.f, 0.f}, float4_t{0.f, 0.f, 0.f, 0.f}};
+    auto consume = [&](int m0, int buf) {
+        const char *bp = mine + buf * GO_BUF_BYTES;
+        const int rows_here = min(GO_ROWS, M - m0);
+#pragma unroll
+        for (int ch = 0; ch < GO_ROWS / 32; ++ch) {
+            const s16x4_t s_lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds4_t)(bp + side_rd + ch * 32 * (R * 2)));
+            const s16x4_t s_hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds4_t)(bp + side_rd + (ch * 32 + 4) * (R * 2)));
+            u16x8_t fa = {(uint16_t)s_lo[0], (uint16_t)s_lo[1], (uint16_t)s_lo[2], (uint16_t)s_lo[3],
+                          (uint16_t)s_hi[0], (uint16_t)s_hi[1], (uint16_t)s_hi[2], (uint16_t)s_hi[3]};
+            // rows past M were fetched as copies of the last row: their side values count as zero; so do the
+            // columns past R of the 16-column operand
+            const int left = rows_here - (ch * 32 + 8 * q);         // valid rows among this lane's eight
+            if (!jval || left < 8) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (!jval || e >= left) fa[e] = 0;
+            }
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const s16x4_t x_lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds4_t)(bp + act_rd + ch * 32 * (GO_COLS * 2) + 32 * h));
+                const s16x4_t x_hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds4_t)(bp + act_rd + (ch * 32 + 4) * (GO_COLS * 2) + 32 * h));
+                const u16x8_t fb = {(uint16_t)x_lo[0], (uint16_t)x_lo[1], (uint16_t)x_lo[2], (uint16_t)x_lo[3],
+                                    (uint16_t)x_hi[0], (uint16_t)x_hi[1], (uint16_t)x_hi[2], (uint16_t)x_hi[3]};
+                acc[h] = mfma16<BF16>(fa, fb, acc[h]);              // D[j = 4 q + v][c = 16 h + li]
+            }
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");          // the buffer is read out before it is refilled
+    };
+    constexpr int STEP = GO_WAVES * GO_ROWS;
+    int m0 = wave * GO_ROWS, buf = 0;
+    if (m0 < M) fetch(m0, 0);
+    if (m0 + STEP < M) fetch(m0 + STEP, 1);
+    for (; m0 < M; m0 += STEP, buf ^= 1) {
+        // the stretch in `buf` was requested before the one in the other buffer (if there is one)
+        if (m0 + STEP < M) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LOADS) : "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        consume(m0, buf);
+        if (m0 + 2 * STEP < M) fetch(m0 + 2 * STEP, buf);
+    }
+    __syncthreads();                                                // every wave is done with its buffers
+    float *red = reinterpret_cast<float *>(go_lds);                 // [GO_WAVES][16 j][32 c]
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) red[(wave * 16 + 4 * q + v) * GO_COLS + 16 * h + li] = acc[h][v];
+    __syncthreads();
+    for (int e = threadIdx.x; e < R * GO_COLS; e += GO_WAVES * 64) {
+        const int j = e / GO_COLS, c = e % GO_COLS;
+        float sum = 0.f;
+#pragma unroll
+        for (int w = 0; w < GO_WAVES; ++w) sum += red[(w * 16 + j) * GO_COLS + c];
+        if (c0 + c < C) {
+            float *dst = a.out[which] + (which ? (long)j * C + c0 + c : (long)(c0 + c) * R + j);
+            *dst = a.beta == 0.f ? a.sc[which] * sum : fmaf(a.beta, *dst, a.sc[which] * sum);
+        }
+    }
+}
+
 // out = sc * sum over slices (in slice order) of partial, both problems in one launch: the first C0*r threads
 // write dB as [C0, r], the next C1*r threads dA as [r, C1].
 __global__ __launch_bounds__(256) void adapter_grad_reduce_kernel(const GradArgs a)
@@ -497,6 +623,29 @@ void launch_adapter_grads(const void *dy, const void *t, const void *x, const vo
     a.sc[1] = keep ? sc * keep_scale : sc;
     a.beta = beta;
     a.keep = (const uint8_t *)keep;
+    // one pass, no partial sums: ranks up to 16 without a dropout mask, byte offsets of the staged loads in 32 bits
+    if (!keep && r <= 16 && (long)M * N * 2 < (1L << 32) && (long)M * K * 2 < (1L << 32) && (long)M * r_all * 2 < (1L << 32)) {
+        a.nb0 = (N + GO_COLS - 1) / GO_COLS;
+        const int blocks = a.nb0 + (K + GO_COLS - 1) / GO_COLS;
+        constexpr int lds = GO_WAVES * 2 * GO_BUF_BYTES;
+        static bool configured = false;
+        if (!configured) {
+            (void)hipFuncSetAttribute((const void *)adapter_grad_onepass_kernel<true, 8>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+            (void)hipFuncSetAttribute((const void *)adapter_grad_onepass_kernel<true, 16>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+            (void)hipFuncSetAttribute((const void *)adapter_grad_onepass_kernel<false, 8>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+            (void)hipFuncSetAttribute((const void *)adapter_grad_onepass_kernel<false, 16>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+            configured = true;
+        }
+        const dim3 grid(blocks), block(GO_WAVES * 64);
+        if (r == 8) {
+            if (bf16) hipLaunchKernelGGL((adapter_grad_onepass_kernel<true, 8>), grid, block, lds, s, a);
+            else hipLaunchKernelGGL((adapter_grad_onepass_kernel<false, 8>), grid, block, lds, s, a);
+        } else {
+            if (bf16) hipLaunchKernelGGL((adapter_grad_onepass_kernel<true, 16>), grid, block, lds, s, a);
+            else hipLaunchKernelGGL((adapter_grad_onepass_kernel<false, 16>), grid, block, lds, s, a);
+        }
+        return;
+    }
     if (bf16)
         launch_grad_partial<true>(a, s);
     else
