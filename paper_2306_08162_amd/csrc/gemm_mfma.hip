@@ -207,6 +207,9 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
             for (int j = 0; j < NI; ++j) acc[i][j] = mfma32<BF16>(f.a[i], f.b[j], acc[i][j]);
     };
 
+    constexpr int EXT_A = BM * 2 / STAGERS, EXT_W = BN * 2 / STAGERS;   // pieces per staging thread, one LoRA step
+    u16x8_t ext_a[EXT_A], ext_w[EXT_W];
+
     if (!stager) {
         // ---- MFMA waves ----
         __builtin_amdgcn_s_setprio(1);          // when both kinds of wave are ready, the matrix pipe's feeder goes first
@@ -271,6 +274,28 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
         wait_vm_and_barrier<0>();               // the loads issued past the last stage have landed: LDS is quiet
     } else {
         // ---- weight staging waves ----
+        // The operands of the LoRA steps that follow the main loop (one step, ranks up to 16) are requested now, so
+        // their memory latency is long gone when they are needed: 8-element pieces of sc * t (or u) and of B (or A).
+        if (a.r > 0 && a.r <= 16) {
+#pragma unroll
+            for (int i = 0; i < EXT_A; ++i) {
+                const int c = stid + STAGERS * i, r = c >> 1, j = (c & 1) * 8;
+                ext_a[i] = u16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
+                if (j < a.r) ext_a[i] = *(const u16x8_t *)(a.ext_act + (long)min(row0 + r, a.M - 1) * a.r + j);
+            }
+#pragma unroll
+            for (int i = 0; i < EXT_W; ++i) {
+                const int c = stid + STAGERS * i;
+                ext_w[i] = u16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
+                if constexpr (TRANS) {
+                    const int j = c / (BN / 8), col = col0 + (c % (BN / 8)) * 8;
+                    if (j < a.r && col < NO) ext_w[i] = *(const u16x8_t *)(a.ext_w + (long)j * a.K + col);
+                } else {
+                    const int r = c >> 1, j = (c & 1) * 8, col = col0 + r;
+                    if (j < a.r && col < NO) ext_w[i] = *(const u16x8_t *)(a.ext_w + (long)col * a.r + j);
+                }
+            }
+        }
         // global -> registers for stage kt.  Branch-free: every address is clamped into the valid range and
         // whatever lies beyond the contraction length (or beyond the weight's rows / columns) is neutralised by a
         // zero scale, so stages past the end may be fetched and staged harmlessly.
@@ -351,7 +376,22 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
     //     Every wave is past the last barrier of the main loop, so every LDS stage is free.
     if (a.r > 0) {
         const int nsteps = (a.r + 15) / 16, width = nsteps * 16;
-        if (stager) {
+        if (stager && nsteps == 1) {                        // operands already in registers
+#pragma unroll
+            for (int i = 0; i < EXT_A; ++i) {
+                const int c = stid + STAGERS * i, r = c >> 1, jc = c & 1;
+                u16x8_t p;
+#pragma unroll
+                for (int h = 0; h < 8; ++h) p[h] = to16<BF16>(a.sc * cvt16<BF16>(ext_a[i][h]));
+                *(u16x8_t *)(xs + r * BK + ((jc ^ ((r >> 1) & 7)) * 8)) = p;  // same swizzle as the main loop
+            }
+#pragma unroll
+            for (int i = 0; i < EXT_W; ++i) {
+                const int c = stid + STAGERS * i;
+                if constexpr (TRANS) *(u16x8_t *)(wsm + (c / (BN / 8)) * WPITCH + (c % (BN / 8)) * 8) = ext_w[i];
+                else *(u16x8_t *)(wsm + (c >> 1) * LDS_STRIDE + (c & 1) * 8) = ext_w[i];
+            }
+        } else if (stager) {
             const int cpr = width / 8;                      // 8-element chunks per row
             for (int c = stid; c < BM * cpr; c += STAGERS) {
                 const int r = c / cpr, jc = c % cpr, j = jc * 8;
