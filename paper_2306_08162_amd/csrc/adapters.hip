@@ -72,10 +72,11 @@ __global__ __launch_bounds__(SK_WAVES * 64) void skinny_rows_kernel(const uint16
     for (int g = 0; g < RG; ++g) acc[g] = float4_t{0.f, 0.f, 0.f, 0.f};
 
     const int chunks = (C + 31) / 32;   // C % 8 == 0: a chunk may be ragged in whole 8-element pieces
-    for (int c0 = wave; c0 < chunks; c0 += SK_WAVES * SK_UNROLL) {
-        u16x8_t xa[SK_UNROLL], sb[SK_UNROLL][RG];
+    constexpr int UNROLL = RG == 1 ? SK_UNROLL : SK_UNROLL / 2;   // registers: two workgroups per CU at every rank
+    for (int c0 = wave; c0 < chunks; c0 += SK_WAVES * UNROLL) {
+        u16x8_t xa[UNROLL], sb[UNROLL][RG];
 #pragma unroll
-        for (int uu = 0; uu < SK_UNROLL; ++uu) {
+        for (int uu = 0; uu < UNROLL; ++uu) {
             const int k = (c0 + uu * SK_WAVES) * 32;
             const bool in = k + q * 8 < C;
             const int kk = in ? k : 0;
@@ -91,7 +92,7 @@ __global__ __launch_bounds__(SK_WAVES * 64) void skinny_rows_kernel(const uint16
             }
         }
 #pragma unroll
-        for (int uu = 0; uu < SK_UNROLL; ++uu)
+        for (int uu = 0; uu < UNROLL; ++uu)
 #pragma unroll
             for (int g = 0; g < RG; ++g) acc[g] = mfma16<BF16>(xa[uu], sb[uu][g], acc[g]);
     }
@@ -111,82 +112,147 @@ __global__ __launch_bounds__(SK_WAVES * 64) void skinny_rows_kernel(const uint16
     }
 }
 
-// u = act * small with `small` [C, r] taken as it lies in memory (r contiguous, r <= 16; u = dY B): the contraction
-// index is the strided one, so blocks of rows of `small` are copied into LDS unchanged and the MFMA operand is
-// gathered with the transposing LDS read (in a block of 16 lanes, lane 4e+g supplies the address of four columns of
-// one row; lane i receives column i%4 of the rows supplied by lanes i/4, 4 + i/4, 8 + i/4, 12 + i/4).  Saves the
-// separate transposition of B and its launch.
-constexpr int SKN_BYTES = 65536;   // LDS block of `small`
-template <bool BF16, int SK_ROWS>
-__global__ __launch_bounds__(SK_WAVES * 64) void skinny_rows_natural_kernel(const uint16_t *__restrict__ act,
-                                                                           const uint16_t *__restrict__ small,
-                                                                           uint16_t *__restrict__ out, int M, int C, int r)
+// The same product with both operands staged through LDS, the form every unmasked call takes: every wave walks
+// 64-column stretches of the contraction (wave w the stretches w, w + 8, ...) and pulls the stretch of its token rows
+// and of `small` into one of two private LDS buffers with direct-to-LDS loads, the next stretch in flight while this
+// one is multiplied; no workgroup barrier in the loop.  (Fragment loads straight from global memory are 16 bytes out
+// of each of 16 rows per instruction: at rank 32 that kernel took 12.9 us at 2048 x 4096, this one 7.3; at rank 8
+// 6.9 against 6.0.)
+//   token rows: 8 rows x 128 bytes per load, the 16-byte pieces of a row XOR-swizzled by the row number so that
+//               the fragment reads of 16 rows collide at most pairwise;
+//   NATURAL = false (t = x A^T): `small` is [r, C], its rows are staged like token rows;
+//   NATURAL = true  (u = dY B):  `small` is [C, r], the contraction index is the strided one; the stretch's 64 rows
+//               are one contiguous block, copied as it lies, and the MFMA operand is gathered with the transposing
+//               LDS read (in a block of 16 lanes, lane 4e+g supplies the address of four columns of one row; lane i
+//               receives column i%4 of the rows supplied by lanes i/4, 4 + i/4, 8 + i/4, 12 + i/4).
+constexpr int SS_COLS = 64;
+template <int RG, int SK_ROWS, bool NATURAL>
+constexpr int ss_buf_bytes() { return NATURAL ? SK_ROWS * 128 + SS_COLS * RG * 16 * 2 : (SK_ROWS + 16 * RG) * 128; }
+template <bool BF16, int RG, int SK_ROWS, bool NATURAL>
+__global__ __launch_bounds__(SK_WAVES * 64) void skinny_rows_staged_kernel(const uint16_t *__restrict__ act,
+                                                                          const uint16_t *__restrict__ small,
+                                                                          uint16_t *__restrict__ out, int M, int C, int r)
 {
-    extern __shared__ __attribute__((aligned(16))) uint16_t sm[];
-    __shared__ float red[SK_WAVES][16][17];
+    extern __shared__ __attribute__((aligned(16))) char ss_lds[];   // [SK_WAVES][2] buffers; then the final sum
     typedef short s16x4_t __attribute__((ext_vector_type(4)));
     typedef __attribute__((address_space(3))) s16x4_t *lds4_t;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    constexpr int BUF = ss_buf_bytes<RG, SK_ROWS, NATURAL>();
+    constexpr int XDMA = SK_ROWS / 8;                // loads of token rows per stretch
+    constexpr int SDMA_MAX = 2 * RG;                 // loads of `small` per stretch, at most (16 RG rows or 64 x 16 RG columns)
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int m0 = blockIdx.x * SK_ROWS;
     const int li = lane & 15, q = lane >> 4;
-    const bool rowin = li < SK_ROWS, sval = li < r;
-    const uint16_t *arow = act + (long)min(m0 + li, M - 1) * C + q * 8;
-    const int NB = SKN_BYTES / 2 / r;                               // rows of `small` per block: a multiple of 32
-    const int toff = (8 * q + (li >> 2)) * r + min(4 * (li & 3), r - 4);   // this lane's address within a 32-row chunk
-    float4_t acc = {0.f, 0.f, 0.f, 0.f};
+    const bool rowin = li < SK_ROWS;
+    char *mine = ss_lds + wave * (2 * BUF);
+    const uint32_t mine_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)mine;
+    const int sdma = NATURAL ? r / 8 : 2 * RG;       // NATURAL: 64 rows x 2 r bytes = r / 8 KB
 
-    for (int nb = 0; nb < C; nb += NB) {
-        const int rows_here = min(NB, C - nb);
-        __syncthreads();                                            // the previous block has been read
-        {
-            const u32x4_t *src = (const u32x4_t *)(small + (long)nb * r);
-            for (int p = threadIdx.x; p < rows_here * r / 8; p += SK_WAVES * 64) ((u32x4_t *)sm)[p] = src[p];
-        }
-        __syncthreads();
-        const int ce = (nb + rows_here + 31) / 32;                  // chunks of 32 contraction elements, this block's end
-        for (int c0 = nb / 32 + wave; c0 < ce; c0 += SK_WAVES * SK_UNROLL) {
-            u16x8_t xa[SK_UNROLL], sb[SK_UNROLL];
+    // a row-wise load covers staged rows 8 d .. 8 d + 7; this lane: row 8 d + lane / 8, LDS slot lane % 8, which
+    // receives piece slot ^ (row % 8) of the stretch
+    const int d_row = lane >> 3, d_piece = (lane & 7) ^ d_row;
+    uint32_t xoff[XDMA], soff[SDMA_MAX];
 #pragma unroll
-            for (int uu = 0; uu < SK_UNROLL; ++uu) {
-                const int c = c0 + uu * SK_WAVES;
-                const int k = c * 32;
-                const bool in = c < ce && k + q * 8 < C;
-                xa[uu] = u16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
-                sb[uu] = xa[uu];
-                if (in && rowin) xa[uu] = *(const u16x8_t *)(arow + k);
-                if (c < ce) {                                       // wave-uniform: every lane supplies its address
-                    const uint16_t *ch = sm + (k - nb) * r + toff;  // rows up to the chunk's 32nd lie inside the block
-                    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds4_t)ch);
-                    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds4_t)(ch + 4 * r));
-                    if (in && sval)                                 // rows past C hold stale LDS contents
-                        sb[uu] = u16x8_t{(uint16_t)lo[0], (uint16_t)lo[1], (uint16_t)lo[2], (uint16_t)lo[3],
-                                         (uint16_t)hi[0], (uint16_t)hi[1], (uint16_t)hi[2], (uint16_t)hi[3]};
-                }
-            }
+    for (int d = 0; d < XDMA; ++d) xoff[d] = (uint32_t)min(m0 + 8 * d + d_row, M - 1) * (uint32_t)C * 2u;
 #pragma unroll
-            for (int uu = 0; uu < SK_UNROLL; ++uu) acc = mfma16<BF16>(xa[uu], sb[uu], acc);
+    for (int d = 0; d < SDMA_MAX; ++d)
+        soff[d] = NATURAL ? (uint32_t)(d * 1024 + lane * 16)                               // within the 64-row block
+                          : (uint32_t)min(8 * d + d_row, r - 1) * (uint32_t)C * 2u;        // row 8 d + lane / 8 of small
+    auto fetch = [&](int col0, int buf) {
+        const uint32_t cb = (uint32_t)min(col0 + 8 * d_piece, C - 8) * 2u;       // past the end: the last piece again
+        const uint32_t base = mine_lds + buf * BUF;
+#pragma unroll
+        for (int d = 0; d < XDMA; ++d)
+            dma16(act, xoff[d] + cb, (uint32_t)__builtin_amdgcn_readfirstlane((int)(base + d * 1024)));
+        if constexpr (NATURAL) {
+            const uint32_t blk = (uint32_t)col0 * (uint32_t)r * 2u, last = (uint32_t)C * (uint32_t)r * 2u - 16u;
+#pragma unroll
+            for (int d = 0; d < SDMA_MAX; ++d)
+                if (d < sdma)       // wave-uniform
+                    dma16(small, min(blk + soff[d], last),
+                          (uint32_t)__builtin_amdgcn_readfirstlane((int)(base + SK_ROWS * 128 + d * 1024)));
+        } else {
+#pragma unroll
+            for (int d = 0; d < SDMA_MAX; ++d)
+                dma16(small, soff[d] + cb, (uint32_t)__builtin_amdgcn_readfirstlane((int)(base + (XDMA + d) * 1024)));
         }
+    };
+    float4_t acc[RG];
+    bool sval[RG];
+#pragma unroll
+    for (int g = 0; g < RG; ++g) {
+        acc[g] = float4_t{0.f, 0.f, 0.f, 0.f};
+        sval[g] = g * 16 + li < r;
     }
+    // NATURAL: this lane's address within a 32-row chunk of the block, 16-column group 0 (see above)
+    const int t_off = (8 * q + (li >> 2)) * (r * 2);
+    auto consume = [&](int col0, int buf) {
+        const char *bp = mine + buf * BUF;
 #pragma unroll
-    for (int v = 0; v < 4; ++v) red[wave][4 * q + v][li] = acc[v];
+        for (int cc = 0; cc < SS_COLS / 32; ++cc) {
+            const int slot = (4 * cc + q) ^ (li & 7);
+            const bool in = col0 + 32 * cc + 8 * q < C;
+            u16x8_t xa = *(const u16x8_t *)(bp + (rowin ? li : 0) * 128 + slot * 16);
+            if (!(in && rowin)) xa = u16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+            for (int g = 0; g < RG; ++g) {
+                u16x8_t sb;
+                if constexpr (NATURAL) {
+                    const char *ch = bp + SK_ROWS * 128 + cc * 32 * (r * 2) + t_off + 2 * min(16 * g + 4 * (li & 3), r - 4);
+                    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds4_t)ch);
+                    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds4_t)(ch + 4 * (r * 2)));
+                    sb = u16x8_t{(uint16_t)lo[0], (uint16_t)lo[1], (uint16_t)lo[2], (uint16_t)lo[3],
+                                 (uint16_t)hi[0], (uint16_t)hi[1], (uint16_t)hi[2], (uint16_t)hi[3]};
+                    if (!(in && sval[g])) sb = u16x8_t{0, 0, 0, 0, 0, 0, 0, 0};   // rows past C hold copies of valid data
+                } else {
+                    sb = *(const u16x8_t *)(bp + (SK_ROWS + 16 * g + li) * 128 + slot * 16);
+                    if (!sval[g]) sb = u16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
+                }
+                acc[g] = mfma16<BF16>(xa, sb, acc[g]);
+            }
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");          // the buffer is read out before it is refilled
+    };
+    constexpr int STEP = SK_WAVES * SS_COLS;
+    const int loads = XDMA + sdma;                                  // per stretch
+    int col0 = wave * SS_COLS, buf = 0;
+    if (col0 < C) fetch(col0, 0);
+    if (col0 + STEP < C) fetch(col0 + STEP, 1);
+    for (; col0 < C; col0 += STEP, buf ^= 1) {
+        // the stretch in `buf` was requested before the one in the other buffer (if there is one): leave only the
+        // younger stretch's loads in flight (the count is wave-uniform; the instruction needs it as an immediate)
+        if (col0 + STEP < C) {
+            switch (loads) {
+            case 2: asm volatile("s_waitcnt vmcnt(2)" ::: "memory"); break;
+            case 3: asm volatile("s_waitcnt vmcnt(3)" ::: "memory"); break;
+            case 4: asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); break;
+            case 5: asm volatile("s_waitcnt vmcnt(5)" ::: "memory"); break;
+            case 6: asm volatile("s_waitcnt vmcnt(6)" ::: "memory"); break;
+            case 7: asm volatile("s_waitcnt vmcnt(7)" ::: "memory"); break;
+            case 8: asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); break;
+            case 9: asm volatile("s_waitcnt vmcnt(9)" ::: "memory"); break;
+            case 10: asm volatile("s_waitcnt vmcnt(10)" ::: "memory"); break;
+            default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;   // stricter than needed, never laxer
+            }
+        } else {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        }
+        consume(col0, buf);
+        if (col0 + 2 * STEP < C) fetch(col0 + 2 * STEP, buf);
+    }
+    __syncthreads();                                                // every wave is done with its buffers
+    float(*red)[RG][16][17] = reinterpret_cast<float(*)[RG][16][17]>(ss_lds);   // [SK_WAVES][RG][16][17]
+#pragma unroll
+    for (int g = 0; g < RG; ++g)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) red[wave][g][4 * q + v][li] = acc[g][v];
     __syncthreads();
-    if (threadIdx.x < 256) {
-        const int row = threadIdx.x >> 4, col = threadIdx.x & 15;
+    for (int e = threadIdx.x; e < RG * 256; e += SK_WAVES * 64) {
+        const int g = e >> 8, row = (e >> 4) & 15, col = e & 15;
         float s = 0.f;
 #pragma unroll
-        for (int w = 0; w < SK_WAVES; ++w) s += red[w][row][col];
-        if (row < SK_ROWS && m0 + row < M && col < r) out[(long)(m0 + row) * r + col] = to16<BF16>(s);
+        for (int w = 0; w < SK_WAVES; ++w) s += red[w][g][row][col];
+        if (row < SK_ROWS && m0 + row < M && g * 16 + col < r) out[(long)(m0 + row) * r + g * 16 + col] = to16<BF16>(s);
     }
-}
-
-// bt[r,N] = b[N,r]^T (the small operand of u = dY B must be contiguous along the contraction index n)
-__global__ __launch_bounds__(256) void transpose_small_kernel(const uint16_t *__restrict__ b, uint16_t *__restrict__ bt,
-                                                              int N, int r)
-{
-    const long idx = (long)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= (long)N * r) return;
-    const int j = (int)(idx / N), n = (int)(idx % N);
-    bt[idx] = b[(long)n * r + j];
 }
 
 // ------------------------------------------------------------------------------------------------------------
@@ -300,18 +366,25 @@ __global__ __launch_bounds__(256) void adapter_grad_partial_kernel(const GradArg
 // read.  The eight partial results are added in wave order at the end and written as out = beta * out + sc * sum.
 // Measured at 2048 x (4096 + 4096), rank 8: 8.2 us against 9.9 + 4.7 us for the slice sums and their reduction.
 // ------------------------------------------------------------------------------------------------------------
-constexpr int GO_COLS = 32, GO_ROWS = 64, GO_WAVES = 8;
-constexpr int GO_ACT_BYTES = GO_ROWS * GO_COLS * 2;          // 8 KB: 8 loads of 16 rows x 64 bytes
-constexpr int GO_SIDE_BYTES = GO_ROWS * 16 * 2;              // up to 16 side columns per row
-constexpr int GO_BUF_BYTES = GO_ACT_BYTES + GO_SIDE_BYTES;   // one stretch; every wave has two such buffers
-template <bool BF16, int R>                                  // R: side columns, 8 or 16
+constexpr int GO_COLS = 32, GO_WAVES = 8;
+constexpr int go_rows(int R) { return R <= 32 ? 64 : 32; }                   // rows per stretch
+constexpr int go_buf_bytes(int R) { return go_rows(R) * (GO_COLS + (R < 16 ? 16 : R)) * 2; }   // activations + side
+constexpr int go_lds_bytes(int R)
+{
+    const int pipe = GO_WAVES * 2 * go_buf_bytes(R), sum = GO_WAVES * ((R + 15) / 16 * 16) * GO_COLS * 4;
+    return pipe > sum ? pipe : sum;
+}
+template <bool BF16, int R>                                  // R: side columns, 8, 16, 32 or 64
 __global__ __launch_bounds__(GO_WAVES * 64) void adapter_grad_onepass_kernel(const GradArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) char go_lds[];   // [GO_WAVES][2] buffers, then reused for the final sum
     typedef short s16x4_t __attribute__((ext_vector_type(4)));
     typedef __attribute__((address_space(3))) s16x4_t *lds4_t;
+    constexpr int GO_ROWS = go_rows(R), GO_ACT_BYTES = GO_ROWS * GO_COLS * 2, GO_BUF_BYTES = go_buf_bytes(R);
+    constexpr int RG = (R + 15) / 16;                        // 16-column groups of the side operand
     constexpr int PR = R / 8, S_ROWS = 64 / PR;              // 16-byte pieces per side row; side rows per load
     constexpr int LOADS = GO_ROWS / 16 + GO_ROWS / S_ROWS;   // direct-to-LDS loads per stretch
+    static_assert(GO_ROWS % S_ROWS == 0 && GO_ROWS % 32 == 0, "whole loads and whole chunks per stretch");
     // Consecutive workgroup ids land on different XCDs; a 32-column block is half a 128-byte line per row, so each
     // XCD is handed a contiguous run of column blocks: both halves of a line are then fetched through the same L2.
     int blk;
@@ -338,7 +411,7 @@ __global__ __launch_bounds__(GO_WAVES * 64) void adapter_grad_onepass_kernel(con
     // 8 q + e, columns 4 g .. + 4 of a 32-row chunk; the second read of a fragment starts four rows further down
     const int t_row = 8 * q + (li >> 2);
     const int act_rd = t_row * (GO_COLS * 2) + 8 * (li & 3);                      // + 32 for the second 16 columns
-    const int side_rd = GO_ACT_BYTES + t_row * (R * 2) + 2 * min(4 * (li & 3), R - 4);
+    const int side_rd = GO_ACT_BYTES + t_row * (R * 2) + 2 * min(4 * (li & 3), R - 4);   // + 32 per 16-column group
     const bool jval = li < R;
 
     // this wave's stretches: rows (GO_WAVES i + wave) * GO_ROWS .. + GO_ROWS, i = 0, 1, ...; two are in flight
@@ -357,31 +430,38 @@ __global__ __launch_bounds__(GO_WAVES * 64) void adapter_grad_onepass_kernel(con
                   (uint32_t)__builtin_amdgcn_readfirstlane((int)(base + GO_ACT_BYTES + b * 1024)));
         }
     };
-    float4_t acc[2] = {float4_t{0.f, 0.f, 0.f, 0.f}, float4_t{0.f, 0.f, 0.f, 0.f}};
+    float4_t acc[RG][2];
+#pragma unroll
+    for (int g = 0; g < RG; ++g) acc[g][0] = acc[g][1] = float4_t{0.f, 0.f, 0.f, 0.f};
     auto consume = [&](int m0, int buf) {
         const char *bp = mine + buf * GO_BUF_BYTES;
         const int rows_here = min(GO_ROWS, M - m0);
 #pragma unroll
         for (int ch = 0; ch < GO_ROWS / 32; ++ch) {
-            const s16x4_t s_lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds4_t)(bp + side_rd + ch * 32 * (R * 2)));
-            const s16x4_t s_hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds4_t)(bp + side_rd + (ch * 32 + 4) * (R * 2)));
-            u16x8_t fa = {(uint16_t)s_lo[0], (uint16_t)s_lo[1], (uint16_t)s_lo[2], (uint16_t)s_lo[3],
-                          (uint16_t)s_hi[0], (uint16_t)s_hi[1], (uint16_t)s_hi[2], (uint16_t)s_hi[3]};
-            // rows past M were fetched as copies of the last row: their side values count as zero; so do the
-            // columns past R of the 16-column operand
-            const int left = rows_here - (ch * 32 + 8 * q);         // valid rows among this lane's eight
-            if (!jval || left < 8) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    if (!jval || e >= left) fa[e] = 0;
-            }
+            u16x8_t fb[2];
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 const s16x4_t x_lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds4_t)(bp + act_rd + ch * 32 * (GO_COLS * 2) + 32 * h));
                 const s16x4_t x_hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds4_t)(bp + act_rd + (ch * 32 + 4) * (GO_COLS * 2) + 32 * h));
-                const u16x8_t fb = {(uint16_t)x_lo[0], (uint16_t)x_lo[1], (uint16_t)x_lo[2], (uint16_t)x_lo[3],
-                                    (uint16_t)x_hi[0], (uint16_t)x_hi[1], (uint16_t)x_hi[2], (uint16_t)x_hi[3]};
-                acc[h] = mfma16<BF16>(fa, fb, acc[h]);              // D[j = 4 q + v][c = 16 h + li]
+                fb[h] = u16x8_t{(uint16_t)x_lo[0], (uint16_t)x_lo[1], (uint16_t)x_lo[2], (uint16_t)x_lo[3],
+                                (uint16_t)x_hi[0], (uint16_t)x_hi[1], (uint16_t)x_hi[2], (uint16_t)x_hi[3]};
+            }
+            const int left = rows_here - (ch * 32 + 8 * q);         // valid rows among this lane's eight
+#pragma unroll
+            for (int g = 0; g < RG; ++g) {
+                const s16x4_t s_lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds4_t)(bp + side_rd + ch * 32 * (R * 2) + 32 * g));
+                const s16x4_t s_hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds4_t)(bp + side_rd + (ch * 32 + 4) * (R * 2) + 32 * g));
+                u16x8_t fa = {(uint16_t)s_lo[0], (uint16_t)s_lo[1], (uint16_t)s_lo[2], (uint16_t)s_lo[3],
+                              (uint16_t)s_hi[0], (uint16_t)s_hi[1], (uint16_t)s_hi[2], (uint16_t)s_hi[3]};
+                // rows past M were fetched as copies of the last row: their side values count as zero; so do the
+                // columns past R of the 16-column operand
+                if (!jval || left < 8) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (!jval || e >= left) fa[e] = 0;
+                }
+#pragma unroll
+                for (int h = 0; h < 2; ++h) acc[g][h] = mfma16<BF16>(fa, fb[h], acc[g][h]);   // D[j = 16 g + 4 q + v][c = 16 h + li]
             }
         }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");          // the buffer is read out before it is refilled
@@ -398,22 +478,38 @@ __global__ __launch_bounds__(GO_WAVES * 64) void adapter_grad_onepass_kernel(con
         if (m0 + 2 * STEP < M) fetch(m0 + 2 * STEP, buf);
     }
     __syncthreads();                                                // every wave is done with its buffers
-    float *red = reinterpret_cast<float *>(go_lds);                 // [GO_WAVES][16 j][32 c]
+    float *red = reinterpret_cast<float *>(go_lds);                 // [GO_WAVES][16 RG rows j][32 c]
 #pragma unroll
-    for (int h = 0; h < 2; ++h)
+    for (int g = 0; g < RG; ++g)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) red[(wave * 16 + 4 * q + v) * GO_COLS + 16 * h + li] = acc[h][v];
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                red[(wave * (16 * RG) + 16 * g + 4 * q + v) * GO_COLS + 16 * h + li] = acc[g][h][v];
     __syncthreads();
     for (int e = threadIdx.x; e < R * GO_COLS; e += GO_WAVES * 64) {
         const int j = e / GO_COLS, c = e % GO_COLS;
         float sum = 0.f;
 #pragma unroll
-        for (int w = 0; w < GO_WAVES; ++w) sum += red[(w * 16 + j) * GO_COLS + c];
+        for (int w = 0; w < GO_WAVES; ++w) sum += red[(w * (16 * RG) + j) * GO_COLS + c];
         if (c0 + c < C) {
             float *dst = a.out[which] + (which ? (long)j * C + c0 + c : (long)(c0 + c) * R + j);
             *dst = a.beta == 0.f ? a.sc[which] * sum : fmaf(a.beta, *dst, a.sc[which] * sum);
         }
     }
+}
+
+template <bool BF16, int R>
+void launch_grad_onepass(const GradArgs &a, int blocks, hipStream_t s)
+{
+    constexpr int lds = go_lds_bytes(R);
+    auto kern = adapter_grad_onepass_kernel<BF16, R>;
+    static bool configured = false;
+    if (!configured) {
+        (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        configured = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(GO_WAVES * 64), lds, s, a);
 }
 
 // out = sc * sum over slices (in slice order) of partial, both problems in one launch: the first C0*r threads
@@ -441,10 +537,41 @@ __global__ __launch_bounds__(256) void adapter_grad_reduce_kernel(const GradArgs
     *dst = a.beta == 0.f ? a.sc[which] * acc : fmaf(a.beta, *dst, a.sc[which] * acc);
 }
 
+template <bool BF16, int RG, int SK_ROWS, bool NATURAL>
+void launch_skinny_staged(const uint16_t *act, const uint16_t *small, uint16_t *out, int M, int C, int r, hipStream_t s)
+{
+    constexpr int pipe = SK_WAVES * 2 * ss_buf_bytes<RG, SK_ROWS, NATURAL>(), sum = SK_WAVES * RG * 16 * 17 * 4;
+    constexpr int lds = pipe > sum ? pipe : sum;
+    auto kern = skinny_rows_staged_kernel<BF16, RG, SK_ROWS, NATURAL>;
+    static bool configured = false;
+    if (!configured) {
+        (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        configured = true;
+    }
+    hipLaunchKernelGGL(kern, dim3((M + SK_ROWS - 1) / SK_ROWS), dim3(SK_WAVES * 64), lds, s, act, small, out, M, C, r);
+}
+
+template <bool BF16, int SK_ROWS, bool NATURAL>
+void launch_skinny_staged_rank(const uint16_t *act, const uint16_t *small, uint16_t *out, int M, int C, int r, hipStream_t s)
+{
+    switch ((r + 15) / 16) {
+    case 1: launch_skinny_staged<BF16, 1, SK_ROWS, NATURAL>(act, small, out, M, C, r, s); break;
+    case 2: launch_skinny_staged<BF16, 2, SK_ROWS, NATURAL>(act, small, out, M, C, r, s); break;
+    case 3: launch_skinny_staged<BF16, 3, SK_ROWS, NATURAL>(act, small, out, M, C, r, s); break;
+    default: launch_skinny_staged<BF16, 4, SK_ROWS, NATURAL>(act, small, out, M, C, r, s); break;
+    }
+}
+
 template <bool BF16, bool MASKED, int SK_ROWS>
 void launch_skinny_rows(const uint16_t *act, const uint16_t *small, uint16_t *out, int M, int C, int r,
                         const uint8_t *keep, float keep_scale, hipStream_t s)
 {
+    if constexpr (!MASKED) {    // operands staged through LDS (byte offsets of the loads in 32 bits)
+        if ((long)M * C * 2 < (1L << 32) && (long)r * C * 2 < (1L << 32)) {
+            launch_skinny_staged_rank<BF16, SK_ROWS, false>(act, small, out, M, C, r, s);
+            return;
+        }
+    }
     const dim3 grid((M + SK_ROWS - 1) / SK_ROWS), block(SK_WAVES * 64);
     switch ((r + 15) / 16) {
     case 1: hipLaunchKernelGGL((skinny_rows_kernel<BF16, 1, MASKED, SK_ROWS>), grid, block, 0, s, act, small, out, M, C, r, keep, keep_scale); break;
@@ -497,39 +624,34 @@ void launch_lora_down(const void *x, const void *A, void *t, int M, int K, int r
     }
 }
 
-template <bool BF16, int SK_ROWS>
-void launch_skinny_natural(const uint16_t *act, const uint16_t *small, uint16_t *out, int M, int C, int r, hipStream_t s)
+// bt[r,N] = b[N,r]^T, for the rare call whose byte offsets do not fit the staged kernel
+__global__ __launch_bounds__(256) void transpose_small_kernel(const uint16_t *__restrict__ b, uint16_t *__restrict__ bt,
+                                                              int N, int r)
 {
-    auto kern = skinny_rows_natural_kernel<BF16, SK_ROWS>;
-    static bool configured = false;   // the static reduction buffer plus this block exceed the default LDS ceiling
-    if (!configured) {
-        (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SKN_BYTES);
-        configured = true;
-    }
-    hipLaunchKernelGGL(kern, dim3((M + SK_ROWS - 1) / SK_ROWS), dim3(SK_WAVES * 64), SKN_BYTES, s, act, small, out, M, C, r);
+    const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (long)N * r) return;
+    const int j = (int)(idx / N), n = (int)(idx % N);
+    bt[idx] = b[(long)n * r + j];
 }
 
 void launch_lora_u(const void *dy, const void *B, void *bt, void *u, int M, int N, int r, bool bf16, hipStream_t s)
 {
-    if (r <= 16) {      // B is read as it lies in memory
-        const uint16_t *a = (const uint16_t *)dy, *b = (const uint16_t *)B;
-        uint16_t *o = (uint16_t *)u;
+    const uint16_t *a = (const uint16_t *)dy, *b = (const uint16_t *)B;
+    uint16_t *o = (uint16_t *)u;
+    if ((long)M * N * 2 < (1L << 32) && (long)N * r * 2 < (1L << 32)) {     // B is read as it lies in memory
         if (M >= 16 * 256) {
-            if (bf16) launch_skinny_natural<true, 16>(a, b, o, M, N, r, s);
-            else launch_skinny_natural<false, 16>(a, b, o, M, N, r, s);
+            if (bf16) launch_skinny_staged_rank<true, 16, true>(a, b, o, M, N, r, s);
+            else launch_skinny_staged_rank<false, 16, true>(a, b, o, M, N, r, s);
         } else {
-            if (bf16) launch_skinny_natural<true, 8>(a, b, o, M, N, r, s);
-            else launch_skinny_natural<false, 8>(a, b, o, M, N, r, s);
+            if (bf16) launch_skinny_staged_rank<true, 8, true>(a, b, o, M, N, r, s);
+            else launch_skinny_staged_rank<false, 8, true>(a, b, o, M, N, r, s);
         }
         return;
     }
     const long n = (long)N * r;
-    hipLaunchKernelGGL(transpose_small_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (const uint16_t *)B,
-                       (uint16_t *)bt, N, r);
-    if (bf16)
-        launch_skinny<true, false>((const uint16_t *)dy, (const uint16_t *)bt, (uint16_t *)u, M, N, r, nullptr, 1.f, s);
-    else
-        launch_skinny<false, false>((const uint16_t *)dy, (const uint16_t *)bt, (uint16_t *)u, M, N, r, nullptr, 1.f, s);
+    hipLaunchKernelGGL(transpose_small_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, b, (uint16_t *)bt, N, r);
+    if (bf16) launch_skinny<true, false>(a, (const uint16_t *)bt, o, M, N, r, nullptr, 1.f, s);
+    else launch_skinny<false, false>(a, (const uint16_t *)bt, o, M, N, r, nullptr, 1.f, s);
 }
 
 // dX[m,k] += f[m,k] * sum_j u[m,j] A[j,k],  f = sc * keep_scale where the keep bit of (m,k) is set, else 0:
@@ -623,28 +745,20 @@ void launch_adapter_grads(const void *dy, const void *t, const void *x, const vo
     a.sc[1] = keep ? sc * keep_scale : sc;
     a.beta = beta;
     a.keep = (const uint8_t *)keep;
-    // one pass, no partial sums: ranks up to 16 without a dropout mask, byte offsets of the staged loads in 32 bits
-    if (!keep && r <= 16 && (long)M * N * 2 < (1L << 32) && (long)M * K * 2 < (1L << 32) && (long)M * r_all * 2 < (1L << 32)) {
+    // one pass, no partial sums: ranks 8, 16, 32, 64 without a dropout mask, byte offsets of the staged loads in 32 bits
+    if (!keep && (r == 8 || r == 16 || r == 32 || r == 64) && (long)M * N * 2 < (1L << 32) && (long)M * K * 2 < (1L << 32) &&
+        (long)M * r_all * 2 < (1L << 32)) {
         a.nb0 = (N + GO_COLS - 1) / GO_COLS;
         const int blocks = a.nb0 + (K + GO_COLS - 1) / GO_COLS;
-        constexpr int lds = GO_WAVES * 2 * GO_BUF_BYTES;
-        static bool configured = false;
-        if (!configured) {
-            (void)hipFuncSetAttribute((const void *)adapter_grad_onepass_kernel<true, 8>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-            (void)hipFuncSetAttribute((const void *)adapter_grad_onepass_kernel<true, 16>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-            (void)hipFuncSetAttribute((const void *)adapter_grad_onepass_kernel<false, 8>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-            (void)hipFuncSetAttribute((const void *)adapter_grad_onepass_kernel<false, 16>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-            configured = true;
-        }
-        const dim3 grid(blocks), block(GO_WAVES * 64);
-        if (r == 8) {
-            if (bf16) hipLaunchKernelGGL((adapter_grad_onepass_kernel<true, 8>), grid, block, lds, s, a);
-            else hipLaunchKernelGGL((adapter_grad_onepass_kernel<false, 8>), grid, block, lds, s, a);
-        } else {
-            if (bf16) hipLaunchKernelGGL((adapter_grad_onepass_kernel<true, 16>), grid, block, lds, s, a);
-            else hipLaunchKernelGGL((adapter_grad_onepass_kernel<false, 16>), grid, block, lds, s, a);
-        }
-        return;
+#define QLORA_ONEPASS(R)                                       \
+    if (bf16) launch_grad_onepass<true, R>(a, blocks, s);      \
+    else launch_grad_onepass<false, R>(a, blocks, s);          \
+    return
+        if (r == 8) { QLORA_ONEPASS(8); }
+        if (r == 16) { QLORA_ONEPASS(16); }
+        if (r == 32) { QLORA_ONEPASS(32); }
+        QLORA_ONEPASS(64);
+#undef QLORA_ONEPASS
     }
     if (bf16)
         launch_grad_partial<true>(a, s);

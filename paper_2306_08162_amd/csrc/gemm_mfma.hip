@@ -207,8 +207,9 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
             for (int j = 0; j < NI; ++j) acc[i][j] = mfma32<BF16>(f.a[i], f.b[j], acc[i][j]);
     };
 
-    constexpr int EXT_A = BM * 2 / STAGERS, EXT_W = BN * 2 / STAGERS;   // pieces per staging thread, one LoRA step
-    u16x8_t ext_a[EXT_A], ext_w[EXT_W];
+    constexpr int EXT_STEPS = 2;                                        // LoRA steps whose operands are prefetched
+    constexpr int EXT_A = BM * 2 / STAGERS, EXT_W = BN * 2 / STAGERS;   // pieces per staging thread and LoRA step
+    u16x8_t ext_a[EXT_STEPS][EXT_A], ext_w[EXT_STEPS][EXT_W];
 
     if (!stager) {
         // ---- MFMA waves ----
@@ -274,25 +275,30 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
         wait_vm_and_barrier<0>();               // the loads issued past the last stage have landed: LDS is quiet
     } else {
         // ---- weight staging waves ----
-        // The operands of the LoRA steps that follow the main loop (one step, ranks up to 16) are requested now, so
-        // their memory latency is long gone when they are needed: 8-element pieces of sc * t (or u) and of B (or A).
-        if (a.r > 0 && a.r <= 16) {
+        // The operands of the LoRA steps that follow the main loop (up to two steps, ranks up to 32) are requested
+        // now, so their memory latency is long gone when they are needed: 8-element pieces of t (or u) and of B (or A);
+        // piece (row, half h) of step st holds adapter columns 16 st + 8 h .. + 8.
+        const int ext_steps = (a.r + 15) / 16;
+        if (a.r > 0 && ext_steps <= EXT_STEPS) {
 #pragma unroll
-            for (int i = 0; i < EXT_A; ++i) {
-                const int c = stid + STAGERS * i, r = c >> 1, j = (c & 1) * 8;
-                ext_a[i] = u16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
-                if (j < a.r) ext_a[i] = *(const u16x8_t *)(a.ext_act + (long)min(row0 + r, a.M - 1) * a.r + j);
-            }
+            for (int st = 0; st < EXT_STEPS; ++st) {
 #pragma unroll
-            for (int i = 0; i < EXT_W; ++i) {
-                const int c = stid + STAGERS * i;
-                ext_w[i] = u16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
-                if constexpr (TRANS) {
-                    const int j = c / (BN / 8), col = col0 + (c % (BN / 8)) * 8;
-                    if (j < a.r && col < NO) ext_w[i] = *(const u16x8_t *)(a.ext_w + (long)j * a.K + col);
-                } else {
-                    const int r = c >> 1, j = (c & 1) * 8, col = col0 + r;
-                    if (j < a.r && col < NO) ext_w[i] = *(const u16x8_t *)(a.ext_w + (long)col * a.r + j);
+                for (int i = 0; i < EXT_A; ++i) {
+                    const int c = stid + STAGERS * i, r = c >> 1, j = 16 * st + (c & 1) * 8;
+                    ext_a[st][i] = u16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
+                    if (j < a.r) ext_a[st][i] = *(const u16x8_t *)(a.ext_act + (long)min(row0 + r, a.M - 1) * a.r + j);
+                }
+#pragma unroll
+                for (int i = 0; i < EXT_W; ++i) {
+                    const int c = stid + STAGERS * i;
+                    ext_w[st][i] = u16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
+                    if constexpr (TRANS) {
+                        const int j = 16 * st + c / (BN / 8), col = col0 + (c % (BN / 8)) * 8;
+                        if (j < a.r && col < NO) ext_w[st][i] = *(const u16x8_t *)(a.ext_w + (long)j * a.K + col);
+                    } else {
+                        const int r = c >> 1, j = 16 * st + (c & 1) * 8, col = col0 + r;
+                        if (j < a.r && col < NO) ext_w[st][i] = *(const u16x8_t *)(a.ext_w + (long)col * a.r + j);
+                    }
                 }
             }
         }
@@ -376,20 +382,26 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
     //     Every wave is past the last barrier of the main loop, so every LDS stage is free.
     if (a.r > 0) {
         const int nsteps = (a.r + 15) / 16, width = nsteps * 16;
-        if (stager && nsteps == 1) {                        // operands already in registers
+        if (stager && nsteps <= EXT_STEPS) {                // operands already in registers
 #pragma unroll
-            for (int i = 0; i < EXT_A; ++i) {
-                const int c = stid + STAGERS * i, r = c >> 1, jc = c & 1;
-                u16x8_t p;
+            for (int st = 0; st < EXT_STEPS; ++st) {
+                if (st >= nsteps) break;
 #pragma unroll
-                for (int h = 0; h < 8; ++h) p[h] = to16<BF16>(a.sc * cvt16<BF16>(ext_a[i][h]));
-                *(u16x8_t *)(xs + r * BK + ((jc ^ ((r >> 1) & 7)) * 8)) = p;  // same swizzle as the main loop
-            }
+                for (int i = 0; i < EXT_A; ++i) {
+                    const int c = stid + STAGERS * i, r = c >> 1, jc = 2 * st + (c & 1);
+                    u16x8_t p;
 #pragma unroll
-            for (int i = 0; i < EXT_W; ++i) {
-                const int c = stid + STAGERS * i;
-                if constexpr (TRANS) *(u16x8_t *)(wsm + (c / (BN / 8)) * WPITCH + (c % (BN / 8)) * 8) = ext_w[i];
-                else *(u16x8_t *)(wsm + (c >> 1) * LDS_STRIDE + (c & 1) * 8) = ext_w[i];
+                    for (int h = 0; h < 8; ++h) p[h] = to16<BF16>(a.sc * cvt16<BF16>(ext_a[st][i][h]));
+                    *(u16x8_t *)(xs + r * BK + ((jc ^ ((r >> 1) & 7)) * 8)) = p;  // same swizzle as the main loop
+                }
+#pragma unroll
+                for (int i = 0; i < EXT_W; ++i) {
+                    const int c = stid + STAGERS * i;
+                    if constexpr (TRANS)
+                        *(u16x8_t *)(wsm + (16 * st + c / (BN / 8)) * WPITCH + (c % (BN / 8)) * 8) = ext_w[st][i];
+                    else
+                        *(u16x8_t *)(wsm + (c >> 1) * LDS_STRIDE + 16 * st + (c & 1) * 8) = ext_w[st][i];
+                }
             }
         } else if (stager) {
             const int cpr = width / 8;                      // 8-element chunks per row
