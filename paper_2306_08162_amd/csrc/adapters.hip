@@ -36,9 +36,11 @@ __device__ __forceinline__ u16x8_t keep_halves(u16x8_t v, uint32_t keep_byte)
 // ------------------------------------------------------------------------------------------------------------
 // out[M,r] = act[M,C] * small[r,C]^T        (t = x A^T with small = A;  u = dY B with small = B^T)
 //
-// A workgroup of 8 waves owns 16 token rows; the waves split the contraction into 32-wide chunks (wave w takes
-// chunks w, w+8, ...) and feed them straight from global memory into the MFMA: both operands are contiguous
-// along the contraction, so a lane's fragment is one 16-byte load.  Partial 16 x r tiles meet in LDS.
+// First form, kept for calls with a dropout mask (and for byte offsets beyond 32 bits): a workgroup of 8 waves owns
+// 8 or 16 token rows; the waves split the contraction into 32-wide chunks (wave w takes chunks w, w+8, ...) and
+// feed them straight from global memory into the MFMA: both operands are contiguous along the contraction, so a
+// lane's fragment is one 16-byte load.  Partial 16 x r tiles meet in LDS.  Every other call takes
+// skinny_rows_staged_kernel below.
 // ------------------------------------------------------------------------------------------------------------
 constexpr int SK_WAVES = 8;
 constexpr int SK_UNROLL = 16;
@@ -407,7 +409,7 @@ __global__ __launch_bounds__(GO_WAVES * 64) void adapter_grad_onepass_kernel(con
     // of the side operand, piece lane % PR of row lane / PR of every S_ROWS-row block
     const int a_row = lane >> 2, a_col = min(c0 + 8 * (lane & 3), C - 8);
     const int s_row = lane / PR, s_col = a.side_c0 + 8 * (lane % PR);
-    // transposing reads (see skinny_rows_natural_kernel): lane (e = li / 4, g = li % 4) of block q points at row
+    // transposing reads (see skinny_rows_staged_kernel): lane (e = li / 4, g = li % 4) of block q points at row
     // 8 q + e, columns 4 g .. + 4 of a 32-row chunk; the second read of a fragment starts four rows further down
     const int t_row = 8 * q + (li >> 2);
     const int act_rd = t_row * (GO_COLS * 2) + 8 * (li & 3);                      // + 32 for the second 16 columns
