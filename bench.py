@@ -298,6 +298,25 @@ def run_stacked(iters: int = 20):
         e1.synchronize()
         out[label + "_bwd_us"] = round(e0.elapsed_ms(e1) * 1e3 / iters, 2)
     out["workload"] = f"{cfg.name}: M={cfg.M} K={cfg.K} N={cfg.N} INT{cfg.bits} fp16, backward pass"
+    # the rank LREC trains at (App. C: r = 32 on every layer), whole step
+    cfg32 = dataclasses.replace(wl.config2(), rank=32, alpha=64.0, name="c2_qproj_int4_rank32")
+    del layer
+    layer = DeviceLayer(wl.make_inputs(cfg32))
+    def step():
+        layer.forward()
+        layer.backward()
+    for _ in range(100):                 # as for the headline: the clocks settle over the first ~20 ms
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = Event(), Event()
+    e0.record(stream)
+    for _ in range(200):
+        step()
+    e1.record(stream)
+    e1.synchronize()
+    us = e0.elapsed_ms(e1) * 1e3 / 200
+    out["rank32_fwd_bwd_us"] = round(us, 2)
+    out["rank32_fwd_bwd_TFLOPs"] = round(cfg32.flops_fwd_bwd / us * 1e-6, 1)
     return out
 
 
