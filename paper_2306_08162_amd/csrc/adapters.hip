@@ -36,7 +36,7 @@ __device__ __forceinline__ u16x8_t keep_halves(u16x8_t v, uint32_t keep_byte)
 // ------------------------------------------------------------------------------------------------------------
 // out[M,r] = act[M,C] * small[r,C]^T        (t = x A^T with small = A;  u = dY B with small = B^T)
 //
-// First form, kept for calls with a dropout mask (and for byte offsets beyond 32 bits): a workgroup of 8 waves owns
+// First form, kept for byte offsets beyond 32 bits: a workgroup of 8 waves owns
 // 8 or 16 token rows; the waves split the contraction into 32-wide chunks (wave w takes chunks w, w+8, ...) and
 // feed them straight from global memory into the MFMA: both operands are contiguous along the contraction, so a
 // lane's fragment is one 16-byte load.  Partial 16 x r tiles meet in LDS.  Every other call takes
@@ -128,17 +128,24 @@ __global__ __launch_bounds__(SK_WAVES * 64) void skinny_rows_kernel(const uint16
 //               LDS read (in a block of 16 lanes, lane 4e+g supplies the address of four columns of one row; lane i
 //               receives column i%4 of the rows supplied by lanes i/4, 4 + i/4, 8 + i/4, 12 + i/4).
 constexpr int SS_COLS = 64;
-template <int RG, int SK_ROWS, bool NATURAL>
-constexpr int ss_buf_bytes() { return NATURAL ? SK_ROWS * 128 + SS_COLS * RG * 16 * 2 : (SK_ROWS + 16 * RG) * 128; }
-template <bool BF16, int RG, int SK_ROWS, bool NATURAL>
+//   MASKED (t under LoRA dropout, out = keep_scale * (x * keep) A^T): the keep bits of the stretch, 8 bytes per token
+//               row, come in with one 4-byte-per-lane load and are applied to the fragments as they are read.
+template <int RG, int SK_ROWS, bool NATURAL, bool MASKED>
+constexpr int ss_buf_bytes()      // operands of one stretch (+ 256 bytes for keep bits)
+{
+    return (NATURAL ? SK_ROWS * 128 + SS_COLS * RG * 16 * 2 : (SK_ROWS + 16 * RG) * 128) + (MASKED ? 256 : 0);
+}
+template <bool BF16, int RG, int SK_ROWS, bool NATURAL, bool MASKED>
 __global__ __launch_bounds__(SK_WAVES * 64) void skinny_rows_staged_kernel(const uint16_t *__restrict__ act,
                                                                           const uint16_t *__restrict__ small,
-                                                                          uint16_t *__restrict__ out, int M, int C, int r)
+                                                                          uint16_t *__restrict__ out, int M, int C, int r,
+                                                                          const uint8_t *__restrict__ keep, float keep_scale)
 {
+    static_assert(!(NATURAL && MASKED), "the mask belongs to x, the activation operand of t = x A^T");
     extern __shared__ __attribute__((aligned(16))) char ss_lds[];   // [SK_WAVES][2] buffers; then the final sum
     typedef short s16x4_t __attribute__((ext_vector_type(4)));
     typedef __attribute__((address_space(3))) s16x4_t *lds4_t;
-    constexpr int BUF = ss_buf_bytes<RG, SK_ROWS, NATURAL>();
+    constexpr int BUF = ss_buf_bytes<RG, SK_ROWS, NATURAL, MASKED>(), MASK_OFF = BUF - 256;
     constexpr int XDMA = SK_ROWS / 8;                // loads of token rows per stretch
     constexpr int SDMA_MAX = 2 * RG;                 // loads of `small` per stretch, at most (16 RG rows or 64 x 16 RG columns)
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -177,6 +184,11 @@ __global__ __launch_bounds__(SK_WAVES * 64) void skinny_rows_staged_kernel(const
             for (int d = 0; d < SDMA_MAX; ++d)
                 dma16(small, soff[d] + cb, (uint32_t)__builtin_amdgcn_readfirstlane((int)(base + (XDMA + d) * 1024)));
         }
+        if constexpr (MASKED) {     // lane l: dword l % 2 of the 8 keep bytes of token row l / 2 (rows past the tile: copies)
+            const uint32_t row = (uint32_t)min(m0 + min(lane >> 1, SK_ROWS - 1), M - 1);
+            dma4(keep, row * (uint32_t)(C / 8) + (uint32_t)min(col0 / 8 + 4 * (lane & 1), C / 8 - 4),
+                 (uint32_t)__builtin_amdgcn_readfirstlane((int)(base + MASK_OFF)));
+        }
     };
     float4_t acc[RG];
     bool sval[RG];
@@ -194,6 +206,7 @@ __global__ __launch_bounds__(SK_WAVES * 64) void skinny_rows_staged_kernel(const
             const int slot = (4 * cc + q) ^ (li & 7);
             const bool in = col0 + 32 * cc + 8 * q < C;
             u16x8_t xa = *(const u16x8_t *)(bp + (rowin ? li : 0) * 128 + slot * 16);
+            if constexpr (MASKED) xa = keep_halves(xa, *(const uint8_t *)(bp + MASK_OFF + (rowin ? li : 0) * 8 + 4 * cc + q));
             if (!(in && rowin)) xa = u16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
             for (int g = 0; g < RG; ++g) {
@@ -215,7 +228,7 @@ __global__ __launch_bounds__(SK_WAVES * 64) void skinny_rows_staged_kernel(const
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");          // the buffer is read out before it is refilled
     };
     constexpr int STEP = SK_WAVES * SS_COLS;
-    const int loads = XDMA + sdma;                                  // per stretch
+    const int loads = XDMA + sdma + (MASKED ? 1 : 0);               // per stretch
     int col0 = wave * SS_COLS, buf = 0;
     if (col0 < C) fetch(col0, 0);
     if (col0 + STEP < C) fetch(col0 + STEP, 1);
@@ -233,6 +246,7 @@ __global__ __launch_bounds__(SK_WAVES * 64) void skinny_rows_staged_kernel(const
             case 8: asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); break;
             case 9: asm volatile("s_waitcnt vmcnt(9)" ::: "memory"); break;
             case 10: asm volatile("s_waitcnt vmcnt(10)" ::: "memory"); break;
+            case 11: asm volatile("s_waitcnt vmcnt(11)" ::: "memory"); break;
             default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;   // stricter than needed, never laxer
             }
         } else {
@@ -253,6 +267,7 @@ __global__ __launch_bounds__(SK_WAVES * 64) void skinny_rows_staged_kernel(const
         float s = 0.f;
 #pragma unroll
         for (int w = 0; w < SK_WAVES; ++w) s += red[w][g][row][col];
+        if constexpr (MASKED) s *= keep_scale;
         if (row < SK_ROWS && m0 + row < M && g * 16 + col < r) out[(long)(m0 + row) * r + g * 16 + col] = to16<BF16>(s);
     }
 }
@@ -370,19 +385,20 @@ __global__ __launch_bounds__(256) void adapter_grad_partial_kernel(const GradArg
 // ------------------------------------------------------------------------------------------------------------
 constexpr int GO_COLS = 32, GO_WAVES = 8;
 constexpr int go_rows(int R) { return R <= 32 ? 64 : 32; }                   // rows per stretch
-constexpr int go_buf_bytes(int R) { return go_rows(R) * (GO_COLS + (R < 16 ? 16 : R)) * 2; }   // activations + side
+constexpr int go_buf_bytes(int R) { return go_rows(R) * (GO_COLS + (R < 16 ? 16 : R)) * 2 + 256; }   // activations + side + mask
 constexpr int go_lds_bytes(int R)
 {
     const int pipe = GO_WAVES * 2 * go_buf_bytes(R), sum = GO_WAVES * ((R + 15) / 16 * 16) * GO_COLS * 4;
     return pipe > sum ? pipe : sum;
 }
-template <bool BF16, int R>                                  // R: side columns, 8, 16, 32 or 64
+template <bool BF16, int R, bool MASKED>                     // R: side columns, 8, 16, 32 or 64; MASKED: a.keep != NULL
 __global__ __launch_bounds__(GO_WAVES * 64) void adapter_grad_onepass_kernel(const GradArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) char go_lds[];   // [GO_WAVES][2] buffers, then reused for the final sum
     typedef short s16x4_t __attribute__((ext_vector_type(4)));
     typedef __attribute__((address_space(3))) s16x4_t *lds4_t;
     constexpr int GO_ROWS = go_rows(R), GO_ACT_BYTES = GO_ROWS * GO_COLS * 2, GO_BUF_BYTES = go_buf_bytes(R);
+    constexpr int GO_MASK_OFF = GO_BUF_BYTES - 256;          // LoRA dropout: the 32 keep bits of each row of the stretch
     constexpr int RG = (R + 15) / 16;                        // 16-column groups of the side operand
     constexpr int PR = R / 8, S_ROWS = 64 / PR;              // 16-byte pieces per side row; side rows per load
     constexpr int LOADS = GO_ROWS / 16 + GO_ROWS / S_ROWS;   // direct-to-LDS loads per stretch
@@ -431,6 +447,11 @@ __global__ __launch_bounds__(GO_WAVES * 64) void adapter_grad_onepass_kernel(con
             dma16(side, (row * (uint32_t)a.side_pitch + (uint32_t)s_col) * 2u,
                   (uint32_t)__builtin_amdgcn_readfirstlane((int)(base + GO_ACT_BYTES + b * 1024)));
         }
+        if (MASKED && which) {      // dA sees keep_scale * x * keep: lane l fetches the keep bits of row l, columns c0 .. c0 + 32
+            const uint32_t row = (uint32_t)min(m0 + lane, M - 1);
+            dma4(a.keep, row * (uint32_t)(C / 8) + (uint32_t)(c0 / 8),
+                 (uint32_t)__builtin_amdgcn_readfirstlane((int)(base + GO_MASK_OFF)));
+        }
     };
     float4_t acc[RG][2];
 #pragma unroll
@@ -447,6 +468,15 @@ __global__ __launch_bounds__(GO_WAVES * 64) void adapter_grad_onepass_kernel(con
                 const s16x4_t x_hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds4_t)(bp + act_rd + (ch * 32 + 4) * (GO_COLS * 2) + 32 * h));
                 fb[h] = u16x8_t{(uint16_t)x_lo[0], (uint16_t)x_lo[1], (uint16_t)x_lo[2], (uint16_t)x_lo[3],
                                 (uint16_t)x_hi[0], (uint16_t)x_hi[1], (uint16_t)x_hi[2], (uint16_t)x_hi[3]};
+            }
+            if (MASKED && which) {  // this lane holds column 16 h + li of rows 8 q .. 8 q + 7 of the chunk
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const uint32_t bits = *(const uint32_t *)(bp + GO_MASK_OFF + (ch * 32 + 8 * q + e) * 4);
+#pragma unroll
+                    for (int h = 0; h < 2; ++h)
+                        if (!((bits >> (16 * h + li)) & 1u)) fb[h][e] = 0;
+                }
             }
             const int left = rows_here - (ch * 32 + 8 * q);         // valid rows among this lane's eight
 #pragma unroll
@@ -474,8 +504,9 @@ __global__ __launch_bounds__(GO_WAVES * 64) void adapter_grad_onepass_kernel(con
     if (m0 + STEP < M) fetch(m0 + STEP, 1);
     for (; m0 < M; m0 += STEP, buf ^= 1) {
         // the stretch in `buf` was requested before the one in the other buffer (if there is one)
-        if (m0 + STEP < M) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LOADS) : "memory");
-        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        if (m0 + STEP >= M) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        else if (MASKED && which) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LOADS + 1) : "memory");   // + the keep bits
+        else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LOADS) : "memory");
         consume(m0, buf);
         if (m0 + 2 * STEP < M) fetch(m0 + 2 * STEP, buf);
     }
@@ -501,17 +532,24 @@ __global__ __launch_bounds__(GO_WAVES * 64) void adapter_grad_onepass_kernel(con
     }
 }
 
-template <bool BF16, int R>
-void launch_grad_onepass(const GradArgs &a, int blocks, hipStream_t s)
+template <bool BF16, int R, bool MASKED>
+void launch_grad_onepass_masked(const GradArgs &a, int blocks, hipStream_t s)
 {
     constexpr int lds = go_lds_bytes(R);
-    auto kern = adapter_grad_onepass_kernel<BF16, R>;
+    auto kern = adapter_grad_onepass_kernel<BF16, R, MASKED>;
     static bool configured = false;
     if (!configured) {
         (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         configured = true;
     }
     hipLaunchKernelGGL(kern, dim3(blocks), dim3(GO_WAVES * 64), lds, s, a);
+}
+
+template <bool BF16, int R>
+void launch_grad_onepass(const GradArgs &a, int blocks, hipStream_t s)
+{
+    if (a.keep) launch_grad_onepass_masked<BF16, R, true>(a, blocks, s);
+    else launch_grad_onepass_masked<BF16, R, false>(a, blocks, s);
 }
 
 // out = sc * sum over slices (in slice order) of partial, both problems in one launch: the first C0*r threads
@@ -539,28 +577,35 @@ __global__ __launch_bounds__(256) void adapter_grad_reduce_kernel(const GradArgs
     *dst = a.beta == 0.f ? a.sc[which] * acc : fmaf(a.beta, *dst, a.sc[which] * acc);
 }
 
-template <bool BF16, int RG, int SK_ROWS, bool NATURAL>
-void launch_skinny_staged(const uint16_t *act, const uint16_t *small, uint16_t *out, int M, int C, int r, hipStream_t s)
+template <bool BF16, int RG, int SK_ROWS, bool NATURAL, bool MASKED>
+void launch_skinny_staged(const uint16_t *act, const uint16_t *small, uint16_t *out, int M, int C, int r,
+                          const uint8_t *keep, float keep_scale, hipStream_t s)
 {
-    constexpr int pipe = SK_WAVES * 2 * ss_buf_bytes<RG, SK_ROWS, NATURAL>(), sum = SK_WAVES * RG * 16 * 17 * 4;
+    constexpr int pipe = SK_WAVES * 2 * ss_buf_bytes<RG, SK_ROWS, NATURAL, MASKED>(), sum = SK_WAVES * RG * 16 * 17 * 4;
+    static_assert(pipe <= 160 * 1024, "fits the LDS of a CU");
     constexpr int lds = pipe > sum ? pipe : sum;
-    auto kern = skinny_rows_staged_kernel<BF16, RG, SK_ROWS, NATURAL>;
+    auto kern = skinny_rows_staged_kernel<BF16, RG, SK_ROWS, NATURAL, MASKED>;
     static bool configured = false;
     if (!configured) {
         (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         configured = true;
     }
-    hipLaunchKernelGGL(kern, dim3((M + SK_ROWS - 1) / SK_ROWS), dim3(SK_WAVES * 64), lds, s, act, small, out, M, C, r);
+    hipLaunchKernelGGL(kern, dim3((M + SK_ROWS - 1) / SK_ROWS), dim3(SK_WAVES * 64), lds, s, act, small, out, M, C, r, keep,
+                       keep_scale);
 }
 
-template <bool BF16, int SK_ROWS, bool NATURAL>
-void launch_skinny_staged_rank(const uint16_t *act, const uint16_t *small, uint16_t *out, int M, int C, int r, hipStream_t s)
+template <bool BF16, int SK_ROWS, bool NATURAL, bool MASKED>
+void launch_skinny_staged_rank(const uint16_t *act, const uint16_t *small, uint16_t *out, int M, int C, int r,
+                               const uint8_t *keep, float keep_scale, hipStream_t s)
 {
     switch ((r + 15) / 16) {
-    case 1: launch_skinny_staged<BF16, 1, SK_ROWS, NATURAL>(act, small, out, M, C, r, s); break;
-    case 2: launch_skinny_staged<BF16, 2, SK_ROWS, NATURAL>(act, small, out, M, C, r, s); break;
-    case 3: launch_skinny_staged<BF16, 3, SK_ROWS, NATURAL>(act, small, out, M, C, r, s); break;
-    default: launch_skinny_staged<BF16, 4, SK_ROWS, NATURAL>(act, small, out, M, C, r, s); break;
+    case 1: launch_skinny_staged<BF16, 1, SK_ROWS, NATURAL, MASKED>(act, small, out, M, C, r, keep, keep_scale, s); break;
+    case 2: launch_skinny_staged<BF16, 2, SK_ROWS, NATURAL, MASKED>(act, small, out, M, C, r, keep, keep_scale, s); break;
+    case 3: launch_skinny_staged<BF16, 3, SK_ROWS, NATURAL, MASKED>(act, small, out, M, C, r, keep, keep_scale, s); break;
+    default:    // (masked, 16 rows, four rank groups do not fit the LDS: the caller keeps that case away)
+        if constexpr (!(MASKED && SK_ROWS == 16))
+            launch_skinny_staged<BF16, 4, SK_ROWS, NATURAL, MASKED>(act, small, out, M, C, r, keep, keep_scale, s);
+        break;
     }
 }
 
@@ -568,11 +613,10 @@ template <bool BF16, bool MASKED, int SK_ROWS>
 void launch_skinny_rows(const uint16_t *act, const uint16_t *small, uint16_t *out, int M, int C, int r,
                         const uint8_t *keep, float keep_scale, hipStream_t s)
 {
-    if constexpr (!MASKED) {    // operands staged through LDS (byte offsets of the loads in 32 bits)
-        if ((long)M * C * 2 < (1L << 32) && (long)r * C * 2 < (1L << 32)) {
-            launch_skinny_staged_rank<BF16, SK_ROWS, false>(act, small, out, M, C, r, s);
-            return;
-        }
+    // staged: byte offsets of the loads in 32 bits; masked, 16 rows and ranks above 48 together exceed the LDS
+    if ((long)M * C * 2 < (1L << 32) && (long)r * C * 2 < (1L << 32) && !(MASKED && SK_ROWS == 16 && r > 48)) {
+        launch_skinny_staged_rank<BF16, SK_ROWS, false, MASKED>(act, small, out, M, C, r, keep, keep_scale, s);
+        return;
     }
     const dim3 grid((M + SK_ROWS - 1) / SK_ROWS), block(SK_WAVES * 64);
     switch ((r + 15) / 16) {
@@ -642,11 +686,11 @@ void launch_lora_u(const void *dy, const void *B, void *bt, void *u, int M, int 
     uint16_t *o = (uint16_t *)u;
     if ((long)M * N * 2 < (1L << 32) && (long)N * r * 2 < (1L << 32)) {     // B is read as it lies in memory
         if (M >= 16 * 256) {
-            if (bf16) launch_skinny_staged_rank<true, 16, true>(a, b, o, M, N, r, s);
-            else launch_skinny_staged_rank<false, 16, true>(a, b, o, M, N, r, s);
+            if (bf16) launch_skinny_staged_rank<true, 16, true, false>(a, b, o, M, N, r, nullptr, 1.f, s);
+            else launch_skinny_staged_rank<false, 16, true, false>(a, b, o, M, N, r, nullptr, 1.f, s);
         } else {
-            if (bf16) launch_skinny_staged_rank<true, 8, true>(a, b, o, M, N, r, s);
-            else launch_skinny_staged_rank<false, 8, true>(a, b, o, M, N, r, s);
+            if (bf16) launch_skinny_staged_rank<true, 8, true, false>(a, b, o, M, N, r, nullptr, 1.f, s);
+            else launch_skinny_staged_rank<false, 8, true, false>(a, b, o, M, N, r, nullptr, 1.f, s);
         }
         return;
     }
@@ -747,8 +791,8 @@ void launch_adapter_grads(const void *dy, const void *t, const void *x, const vo
     a.sc[1] = keep ? sc * keep_scale : sc;
     a.beta = beta;
     a.keep = (const uint8_t *)keep;
-    // one pass, no partial sums: ranks 8, 16, 32, 64 without a dropout mask, byte offsets of the staged loads in 32 bits
-    if (!keep && (r == 8 || r == 16 || r == 32 || r == 64) && (long)M * N * 2 < (1L << 32) && (long)M * K * 2 < (1L << 32) &&
+    // one pass, no partial sums: ranks 8, 16, 32, 64, byte offsets of the staged loads in 32 bits
+    if ((r == 8 || r == 16 || r == 32 || r == 64) && (long)M * N * 2 < (1L << 32) && (long)M * K * 2 < (1L << 32) &&
         (long)M * r_all * 2 < (1L << 32)) {
         a.nb0 = (N + GO_COLS - 1) / GO_COLS;
         const int blocks = a.nb0 + (K + GO_COLS - 1) / GO_COLS;

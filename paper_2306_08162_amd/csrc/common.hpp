@@ -98,4 +98,12 @@ __device__ __forceinline__ void dma16(const void *base, uint32_t byte_offset, ui
                  : "memory");   // m0 is reserved by the compiler: it never keeps a value there across other code
 }
 
+// The 4-byte form: lane l's dword lands at lds + 4 l (256 bytes per instruction).
+__device__ __forceinline__ void dma4(const void *base, uint32_t byte_offset, uint32_t lds)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
+                 ::"v"(byte_offset), "s"(base), "s"(lds)
+                 : "memory");
+}
+
 }  // namespace qlora
