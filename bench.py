@@ -273,7 +273,7 @@ def run_actorder_gather(M: int = 2048, K: int = 4096, G: int = 128, iters: int =
 
 
 def run_stacked(iters: int = 20):
-    """Stacked adapters on the headline projection (App. D: a frozen rank-32 recovery pair plus a trainable rank-8
+    """Variants of the headline layer that training runs of the paper use.  Stacked adapters on the headline projection (App. D: a frozen rank-32 recovery pair plus a trainable rank-8
     pair): the backward pass with gradients for all 40 adapter columns against the one that forms them for the
     trainable 8 only.  HIP events around `iters` back-to-back calls."""
     import dataclasses
@@ -317,6 +317,28 @@ def run_stacked(iters: int = 20):
     us = e0.elapsed_ms(e1) * 1e3 / 200
     out["rank32_fwd_bwd_us"] = round(us, 2)
     out["rank32_fwd_bwd_TFLOPs"] = round(cfg32.flops_fwd_bwd / us * 1e-6, 1)
+    # the headline layer with LoRA dropout (App. B: rate 0.05), mask drawn by a seeded generator on the host
+    import numpy as np
+    del layer
+    cfg = wl.config2()
+    layer = DeviceLayer(wl.make_inputs(cfg))
+    u01 = wl.splitmix64(0xD809, 0, cfg.M * cfg.K).astype(np.float64) / 2.0 ** 64
+    bits = (u01 >= 0.05).astype(np.uint64).reshape(cfg.M, cfg.K // 32, 32)
+    words = (bits << np.arange(32, dtype=np.uint64)).sum(axis=2).astype(np.uint32)
+    km = torch.from_numpy(words.view(np.int32)).to(layer.device)
+    def dstep():
+        layer.forward_dropout(km, 1.0 / 0.95)
+        layer.backward_dropout(km, 1.0 / 0.95)
+    for _ in range(100):
+        dstep()
+    torch.cuda.synchronize()
+    e0, e1 = Event(), Event()
+    e0.record(stream)
+    for _ in range(200):
+        dstep()
+    e1.record(stream)
+    e1.synchronize()
+    out["dropout_0.05_fwd_bwd_us"] = round(e0.elapsed_ms(e1) * 1e3 / 200, 2)
     return out
 
 
