@@ -537,11 +537,7 @@ void launch_grad_onepass_masked(const GradArgs &a, int blocks, hipStream_t s)
 {
     constexpr int lds = go_lds_bytes(R);
     auto kern = adapter_grad_onepass_kernel<BF16, R, MASKED>;
-    static bool configured = false;
-    if (!configured) {
-        (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        configured = true;
-    }
+    ensure_dynamic_lds((const void *)kern, (int)(lds));
     hipLaunchKernelGGL(kern, dim3(blocks), dim3(GO_WAVES * 64), lds, s, a);
 }
 
@@ -585,11 +581,7 @@ void launch_skinny_staged(const uint16_t *act, const uint16_t *small, uint16_t *
     static_assert(pipe <= 160 * 1024, "fits the LDS of a CU");
     constexpr int lds = pipe > sum ? pipe : sum;
     auto kern = skinny_rows_staged_kernel<BF16, RG, SK_ROWS, NATURAL, MASKED>;
-    static bool configured = false;
-    if (!configured) {
-        (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        configured = true;
-    }
+    ensure_dynamic_lds((const void *)kern, (int)(lds));
     hipLaunchKernelGGL(kern, dim3((M + SK_ROWS - 1) / SK_ROWS), dim3(SK_WAVES * 64), lds, s, act, small, out, M, C, r, keep,
                        keep_scale);
 }

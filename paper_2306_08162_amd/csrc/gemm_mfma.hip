@@ -481,11 +481,7 @@ void launch_variant(const GemmArgs &a, hipStream_t s)
     constexpr size_t lds_epi = (size_t)WM * WN * (BM / WM) * (BN / WN + 8) * sizeof(uint16_t);
     constexpr size_t lds = lds_pipe > lds_epi ? lds_pipe : lds_epi;
     auto kern = qgemm_kernel<BITS, BF16, TRANS, BM, BN, WM, WN>;
-    static bool configured = false;   // raising the dynamic-LDS ceiling is a property of the function, set once
-    if (!configured) {
-        (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        configured = true;
-    }
+    ensure_dynamic_lds((const void *)kern, (int)(lds));
     hipLaunchKernelGGL(kern, dim3(a.tiles_m * a.tiles_n), dim3(WM * WN * 64 + STAGERS), lds, s, a);
 }
 

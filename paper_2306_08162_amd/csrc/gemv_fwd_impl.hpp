@@ -433,21 +433,13 @@ void launch_fwd_staged_one(FwdMulti m, hipStream_t s)
     }
     if (m.count == 1) {
         auto kern = gemv_fwd_staged_kernel<BITS, BF16, MB, RG, NW, NB>;
-        static bool configured = false;   // raising the dynamic-LDS ceiling is a property of the function, set once
-        if (!configured) {
-            (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-            configured = true;
-        }
+        ensure_dynamic_lds((const void *)kern, (int)(lds));
         hipLaunchKernelGGL(kern, dim3(wgs), dim3(NW * 64), lds, s, m.p[0]);
         return;
     }
     if constexpr (MB == 1) {          // the callers hand siblings over together only up to 16 token rows
         auto kern = gemv_fwd_staged_siblings_kernel<BITS, BF16, MB, RG, NW, NB>;
-        static bool configured = false;
-        if (!configured) {
-            (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-            configured = true;
-        }
+        ensure_dynamic_lds((const void *)kern, (int)(lds));
         hipLaunchKernelGGL(kern, dim3(wgs), dim3(NW * 64), lds, s, m);
     }
 }

@@ -14,6 +14,10 @@ struct Problem {
     bool bf16;    // activation / adapter dtype
 };
 
+// Kernels that use more than 64 KB of dynamic LDS must have that ceiling raised once per function and device; safe to
+// call from several host threads.
+void ensure_dynamic_lds(const void *kernel, int bytes);
+
 // pack.hip
 void launch_pack(const uint8_t *codes, uint32_t *packed, int N, int K, int bits, hipStream_t s);
 void launch_unpack(const uint32_t *packed, uint8_t *codes, int N, int K, int bits, hipStream_t s);

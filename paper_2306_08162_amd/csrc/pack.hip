@@ -3,7 +3,24 @@
 #include "common.hpp"
 #include "kernels.hpp"
 
+#include <mutex>
+#include <unordered_map>
+
 namespace qlora {
+
+void ensure_dynamic_lds(const void *kernel, int bytes)
+{
+    static std::mutex mu;
+    static std::unordered_map<const void *, uint64_t> done;     // kernel -> devices it has been configured on
+    int dev = 0;
+    (void)hipGetDevice(&dev);
+    const uint64_t bit = 1ull << (dev & 63);
+    std::lock_guard<std::mutex> guard(mu);
+    uint64_t &mask = done[kernel];
+    if (mask & bit) return;
+    (void)hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    mask |= bit;
+}
 
 // One thread builds one 32-bit word of the row's little-endian bit stream.
 template <int BITS>
