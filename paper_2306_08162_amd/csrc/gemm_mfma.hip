@@ -492,14 +492,22 @@ void launch_tiles(GemmArgs &a, hipStream_t s)
 #define QLORA_BM 256
 #define QLORA_BN 128
 #endif
-    constexpr int BM = QLORA_BM, BN = QLORA_BN;
-    const int NO = TRANS ? a.K : a.N;
-    a.tiles_m = (a.M + BM - 1) / BM;
-    a.tiles_n = (NO + BN - 1) / BN;
 #ifndef QLORA_WM
 #define QLORA_WM 2
 #define QLORA_WN 2
 #endif
+    constexpr int BM = QLORA_BM, BN = QLORA_BN;
+    const int NO = TRANS ? a.K : a.N;
+    a.tiles_n = (NO + BN - 1) / BN;
+    // fewer tiles than CUs: halve the tile height, so that (up to) twice as many CUs work
+    if constexpr (BM == 256) {
+        if (((a.M + 255) / 256) * a.tiles_n < 256 && a.M > 128) {
+            a.tiles_m = (a.M + 127) / 128;
+            launch_variant<BITS, BF16, TRANS, 128, BN, QLORA_WM, QLORA_WN>(a, s);
+            return;
+        }
+    }
+    a.tiles_m = (a.M + BM - 1) / BM;
     launch_variant<BITS, BF16, TRANS, BM, BN, QLORA_WM, QLORA_WN>(a, s);
 }
 
