@@ -490,10 +490,14 @@ void launch_tiles(GemmArgs &a, hipStream_t s)
 {
 #ifndef QLORA_BM          // tile shape and MFMA-wave grid can be overridden at build time for tuning runs
 #define QLORA_BM 256
+#endif
+#ifndef QLORA_BN
 #define QLORA_BN 128
 #endif
 #ifndef QLORA_WM
 #define QLORA_WM 2
+#endif
+#ifndef QLORA_WN
 #define QLORA_WN 2
 #endif
     constexpr int BM = QLORA_BM, BN = QLORA_BN;
