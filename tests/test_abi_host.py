@@ -286,3 +286,12 @@ def test_stacked_backward_rejects_bad_frozen_rank():
     assert args(16, 16) == E("QLORA_E_RANK")         # nothing left to train
     assert args(-8, 16) == E("QLORA_E_RANK")
     assert args(8, 16) == E("QLORA_E_NULL")          # accepted, then the NULL buffers are caught
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The layer has no multi-GPU path: bench.py says so and exits before touching a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
