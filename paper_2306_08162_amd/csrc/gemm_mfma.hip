@@ -89,6 +89,10 @@ __device__ __forceinline__ void wait_vm_and_barrier()
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 
+// Swizzle key of a row of the backward weight stage: a permutation of 0..15 over any 16 consecutive rows whose
+// upper two bits run through 0..3 over any 4 consecutive rows starting at a multiple of 4.
+__device__ __forceinline__ constexpr int wswz(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
+
 template <int BITS, bool BF16, bool TRANS, int BM, int BN, int WM, int WN>
 __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const GemmArgs a)
 {
@@ -108,10 +112,13 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
     constexpr int NXS = QLORA_NXS;                  // activation stages (3, or 2 when two workgroups share a CU's LDS)
     static_assert(NXS == 2 || NXS == 3, "activation stages");
     // Weight stage.  Forward: [BN rows n][64 k + 8] (144-byte rows), fragments are 16-byte reads.  Backward: the
-    // staging threads own rows n of the contraction, so the stage is kept as they produce it, [64 rows n][BN k + 32]
-    // (320-byte rows: four consecutive rows start 16 banks apart), and the fragments are gathered with the
-    // transposing LDS read (ds_read_b64_tr_b16), two per fragment.
-    constexpr int WPITCH = TRANS ? BN + 32 : LDS_STRIDE;
+    // staging threads own rows n of the contraction, so the stage is kept as they produce it, [64 rows n][BN k],
+    // and the fragments are gathered with the transposing LDS read (ds_read_b64_tr_b16), two per fragment.  The
+    // 16-byte pieces of a row are XOR-swizzled with wswz(row): sixteen consecutive rows put the same piece into
+    // sixteen different bank quads (the stagers' 16-byte writes, one row per lane), and four consecutive rows put
+    // four consecutive pieces into disjoint runs of 16 banks (the transposing reads: 4 rows x 64 bytes per half
+    // wave).  Unpadded 320-byte rows served the reads equally well but made the writes collide four ways.
+    constexpr int WPITCH = TRANS ? BN : LDS_STRIDE;
     constexpr int WS = TRANS ? BK * WPITCH : BN * LDS_STRIDE;   // halfs per weight stage
     using Regs = StageRegs<BITS, WU>;
 
@@ -177,20 +184,31 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
     // element e, column i%4 of the row supplied by lane 4e + i/4.  Lane (e, g) of block b therefore points at row
     // 8 (b/2) + e, columns 16 (b%2) + 4g .. +4 of the 16 x 32 k-step slab, and lane l ends up with contraction
     // elements 8 (l/32) .. +4 of column l % 32: half an MFMA operand; the second read starts four rows further down.
-    const int boff = TRANS ? (8 * (lane >> 5) + ((lane & 15) >> 2)) * WPITCH + wn * TN + 16 * ((lane >> 4) & 1) + 4 * (lane & 3)
-                           : (wn * TN + fr) * LDS_STRIDE + fh * 8;
+    // The row's swizzle key is 4 e + 2 (l/32) + (second read), so each of the 2 NI reads has its own offset.
+    const int boff = TRANS ? 0 : (wn * TN + fr) * LDS_STRIDE + fh * 8;
+    int toff[TRANS ? NI : 1][2];
+    if constexpr (TRANS) {
+        const int e = (lane & 15) >> 2, row = 8 * (lane >> 5) + e;
+        const int piece = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);     // 16-byte piece within the 64-byte run
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int hi = 0; hi < 2; ++hi)
+                toff[j][hi] = (row + 4 * hi) * WPITCH
+                            + (((wn * TN / 8 + 4 * j + piece) ^ wswz(row + 4 * hi)) * 8) + 4 * (lane & 1);
+    }
     auto load_frags = [&](int xstage, int wstage, int ks, Frags &f) {
         const uint16_t *As = xs + xstage * XS + aoff[ks];
 #pragma unroll
         for (int i = 0; i < MI; ++i) f.a[i] = *(const u16x8_t *)(As + i * 32 * BK);
         if constexpr (TRANS) {
-            const uint16_t *Bs = wsm + wstage * WS + boff + ks * 16 * WPITCH;
+            const uint16_t *Bs = wsm + wstage * WS + ks * 16 * WPITCH;   // 16 rows further: same swizzle keys
 #pragma unroll
             for (int j = 0; j < NI; ++j) {
                 typedef short s16x4_t __attribute__((ext_vector_type(4)));
                 typedef __attribute__((address_space(3))) s16x4_t *lds4_t;
-                const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds4_t)(Bs + j * 32));
-                const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds4_t)(Bs + j * 32 + 4 * WPITCH));
+                const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds4_t)(Bs + toff[j][0]));
+                const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds4_t)(Bs + toff[j][1]));
                 f.b[j] = u16x8_t{(uint16_t)lo[0], (uint16_t)lo[1], (uint16_t)lo[2], (uint16_t)lo[3],
                                  (uint16_t)hi[0], (uint16_t)hi[1], (uint16_t)hi[2], (uint16_t)hi[3]};
             }
@@ -343,7 +361,7 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
                 for (int part = 0; part < 4; ++part) {
                     const u16x8_t v = dequant8<BITS, BF16>(rg.w[i], part, dq);
                     if constexpr (TRANS) {
-                        *(u16x8_t *)(Bs + (u & 63) * WPITCH + (u >> 6) * 32 + part * 8) = v;
+                        *(u16x8_t *)(Bs + (u & 63) * WPITCH + ((((u >> 6) * 4 + part) ^ wswz(u & 63)) * 8)) = v;
                     } else {
                         *(u16x8_t *)(Bs + (u >> 1) * LDS_STRIDE + (u & 1) * 32 + part * 8) = v;
                     }
@@ -398,7 +416,8 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
                 for (int i = 0; i < EXT_W; ++i) {
                     const int c = stid + STAGERS * i;
                     if constexpr (TRANS)
-                        *(u16x8_t *)(wsm + (16 * st + c / (BN / 8)) * WPITCH + (c % (BN / 8)) * 8) = ext_w[st][i];
+                        *(u16x8_t *)(wsm + (16 * st + c / (BN / 8)) * WPITCH
+                                     + (((c % (BN / 8)) ^ wswz(c / (BN / 8))) * 8)) = ext_w[st][i];
                     else
                         *(u16x8_t *)(wsm + (c >> 1) * LDS_STRIDE + 16 * st + (c & 1) * 8) = ext_w[st][i];
                 }
@@ -421,7 +440,7 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
                     const int j = c / (BN / 8), col = col0 + (c % (BN / 8)) * 8;
                     u16x8_t p = {0, 0, 0, 0, 0, 0, 0, 0};
                     if (j < a.r && col < NO) p = *(const u16x8_t *)(a.ext_w + (long)j * a.K + col);
-                    *(u16x8_t *)(wsm + j * WPITCH + (c % (BN / 8)) * 8) = p;
+                    *(u16x8_t *)(wsm + j * WPITCH + (((c % (BN / 8)) ^ wswz(j)) * 8)) = p;
                 }
             } else {
                 for (int c = stid; c < BN * cpr; c += STAGERS) {
@@ -476,7 +495,7 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
 template <int BITS, bool BF16, bool TRANS, int BM, int BN, int WM, int WN>
 void launch_variant(const GemmArgs &a, hipStream_t s)
 {
-    constexpr size_t wstage = TRANS ? (size_t)BK * (BN + 32) : (size_t)BN * LDS_STRIDE;
+    constexpr size_t wstage = TRANS ? (size_t)BK * BN : (size_t)BN * LDS_STRIDE;
     constexpr size_t lds_pipe = (QLORA_NXS * (size_t)BM * BK + 2 * wstage) * sizeof(uint16_t);
     constexpr size_t lds_epi = (size_t)WM * WN * (BM / WM) * (BN / WN + 8) * sizeof(uint16_t);
     constexpr size_t lds = lds_pipe > lds_epi ? lds_pipe : lds_epi;
