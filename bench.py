@@ -342,6 +342,30 @@ def run_stacked(iters: int = 20):
     return out
 
 
+def run_dense_library_context(M: int, K: int, N: int, iters: int = 200):
+    """CONTEXT ONLY, never part of `value`: the vendor library's dense fp16 GEMM (torch.matmul) on already
+    dequantised weights of the headline shape, in the two operand orders of the layer's passes.  It reads four
+    times the weight bytes, has no LoRA term, and shares nothing with this library's kernels."""
+    import torch
+    x = torch.randn(M, K, device="cuda:0", dtype=torch.float16)
+    dy = torch.randn(M, N, device="cuda:0", dtype=torch.float16)
+    w = torch.randn(N, K, device="cuda:0", dtype=torch.float16)
+    out = {}
+    for name, fn in (("fwd_x_wT_us", lambda: x @ w.t()), ("bwd_dy_w_us", lambda: dy @ w)):
+        for _ in range(50):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        out[name] = round(e0.elapsed_time(e1) / iters * 1e3, 2)
+    out["note"] = "vendor dense fp16 GEMM of the same shape on fp16 weights: context, not this library"
+    return out
+
+
 def run_cpu_baseline(inp, max_rows: int):
     """The fp64 oracle as it stands, on the host cores: forward + backward on the first `max_rows` token rows."""
     import oracle
@@ -371,6 +395,8 @@ def main() -> int:
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy, so a rocprofv3 --pmc run of this command holds a kernel of "
                          "known HBM traffic to scale FETCH_SIZE / WRITE_SIZE by")
+    ap.add_argument("--library-context", action="store_true",
+                    help="also time the vendor library's dense fp16 GEMM of the headline shape (context only)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (the layer has no multi-GPU path); use --gpus 1",
@@ -418,6 +444,8 @@ def main() -> int:
         result["lrec_loss"] = run_lrec_loss()
         result["actorder_gather"] = run_actorder_gather()
         result["stacked_adapters"] = run_stacked()
+    if args.library_context:
+        result["dense_library_context"] = run_dense_library_context(cfg.M, cfg.K, cfg.N)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = run_cpu_baseline(inp, args.cpu_rows)
     print(json.dumps(result))
