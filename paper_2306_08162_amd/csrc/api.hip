@@ -46,7 +46,7 @@ int check_problem(int M, int N, int K, int bits, int G, int r, int dtype)
 }
 
 struct Workspace {
-    size_t t_off, u_off, bt_off, upartial_off, partial_off, total;
+    size_t t_off, u_off, bt_off, upartial_off, partial_off, split_off, total;
 };
 
 Workspace carve(int M, int N, int K, int r, int bits)
@@ -68,6 +68,10 @@ Workspace carve(int M, int N, int K, int r, int bits)
         pmax = pg > pmax ? pg : pmax;
     }
     off += round_up(pmax);
+    w.split_off = off;              // fp32 planes of a GEMM whose contraction is split over workgroups
+    const size_t sf = (size_t)gemm_splits(M, N, K), sb = (size_t)gemm_splits(M, K, N);
+    const size_t pf = sf > 1 ? sf * M * N * sizeof(float) : 0, pb = sb > 1 ? sb * M * K * sizeof(float) : 0;
+    off += round_up(pf > pb ? pf : pb);
     w.total = off < ALIGN ? ALIGN : off;
     return w;
 }
@@ -261,7 +265,7 @@ int qlora_linear_fwd_dropout(const void *x, const uint32_t *packed, const void *
             launch_lora_down(x, A, t, M, K, rank, p.bf16, keep_mask, keep_scale, s);
         }
         GemmTimer timer(s);
-        launch_fwd_mfma(p, x, packed, scales, zeros, t, B, y, s);
+        launch_fwd_mfma(p, x, packed, scales, zeros, t, B, y, (float *)(ws + w.split_off), s);
     }
     return hip_status();
 }
@@ -331,9 +335,9 @@ static int backward(const void *dy, const void *x, const uint32_t *packed, const
             Problem base = p;
             base.r = 0;
             base.sc = 0.f;
-            launch_bwd_dx_mfma(base, dy, packed, scales, zeros, nullptr, nullptr, dx, s);
+            launch_bwd_dx_mfma(base, dy, packed, scales, zeros, nullptr, nullptr, dx, (float *)(ws + w.split_off), s);
         } else {
-            launch_bwd_dx_mfma(p, dy, packed, scales, zeros, u, A, dx, s);
+            launch_bwd_dx_mfma(p, dy, packed, scales, zeros, u, A, dx, (float *)(ws + w.split_off), s);
         }
     }
     if (keep_mask) launch_lora_dx_masked(dx, u, A, keep_mask, M, K, rank, p.sc * keep_scale, p.bf16, s);

@@ -34,6 +34,8 @@ struct GemmArgs {
     float sc;
     int tiles_m, tiles_n;
     uint32_t g32_magic;       // see group_magic(): (k/32) / (G/32) == umulhi(k/32, magic), 0 meaning G == 32
+    float *part;              // splits > 1: fp32 partial products [splits][M][NO], summed by splitk_sum_kernel
+    int splits, kt_split;     // workgroups per tile along the contraction, 64-deep stages per workgroup
 };
 
 template <bool BF16>
@@ -139,13 +141,18 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
     const int NO = TRANS ? a.K : a.N;    // output columns
     const int KC = TRANS ? a.N : a.K;    // contraction length
     const int ng = a.K / a.G, Kw = a.K * BITS / 32;
-    const int KT = (KC + BK - 1) / BK;
+    // a workgroup owns the stages kt_first .. kt_first + KT of its tile's contraction (all of them unless the
+    // contraction is split over several workgroups)
+    const int nt = a.tiles_m * a.tiles_n;
+    const int split = __builtin_amdgcn_readfirstlane(a.splits > 1 ? (int)blockIdx.x / nt : 0);
+    const int kt_first = split * a.kt_split;
+    const int KT = min((KC + BK - 1) / BK - kt_first, a.kt_split);
 
     // --- which tile: consecutive workgroups land on different XCDs, so hand each XCD a contiguous run of tile
     //     ids, and order ids so that a run covers a compact block of tiles (shared rows and columns hit in L2)
     int pm, pn;
     {
-        const int nt = a.tiles_m * a.tiles_n, bid = blockIdx.x;
+        const int bid = a.splits > 1 ? (int)blockIdx.x % nt : (int)blockIdx.x;
         const int xcd = bid & 7, loc = bid >> 3, per = nt >> 3, rem = nt & 7;
         const int t = xcd * per + min(xcd, rem) + loc;
 #ifndef QLORA_GM
@@ -242,7 +249,7 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
             xoff[i] = (uint32_t)min(row0 + (MW * i + cw) * 8 + drow, a.M - 1) * (uint32_t)KC * 2u;
         auto issue_x = [&](int kt, int stage, int i) {
             // stages past the end and chunks past the contraction length re-read valid data; the weight side is zero there
-            const uint32_t k2 = (uint32_t)min(kt * BK + dchunk, KC - 8) * 2u;
+            const uint32_t k2 = (uint32_t)min((kt_first + kt) * BK + dchunk, KC - 8) * 2u;
             const uint32_t dst = xs_lds + (uint32_t)(stage * XS + (MW * i + cw) * 512) * 2u;   // wave-uniform byte address
             dma16(a.act, xoff[i] + k2, (uint32_t)__builtin_amdgcn_readfirstlane((int)dst));
         };
@@ -297,7 +304,7 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
         // now, so their memory latency is long gone when they are needed: 8-element pieces of t (or u) and of B (or A);
         // piece (row, half h) of step st holds adapter columns 16 st + 8 h .. + 8.
         const int ext_steps = (a.r + 15) / 16;
-        if (a.r > 0 && ext_steps <= EXT_STEPS) {
+        if (a.r > 0 && split == 0 && ext_steps <= EXT_STEPS) {
 #pragma unroll
             for (int st = 0; st < EXT_STEPS; ++st) {
 #pragma unroll
@@ -324,7 +331,7 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
         // whatever lies beyond the contraction length (or beyond the weight's rows / columns) is neutralised by a
         // zero scale, so stages past the end may be fetched and staged harmlessly.
         auto load_global = [&](int kt, Regs &rg) {
-            const int kbase = kt * BK;
+            const int kbase = (kt_first + kt) * BK;
 #pragma unroll
             for (int i = 0; i < WU; ++i) {
                 const int u = stid + STAGERS * i;
@@ -398,7 +405,7 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
 
     // --- LoRA term as extra contraction steps: Act' = sc * t (or u), W' = B (or A^T), zero-padded to 16.
     //     Every wave is past the last barrier of the main loop, so every LDS stage is free.
-    if (a.r > 0) {
+    if (a.r > 0 && split == 0) {                            // the first workgroup of a split contraction adds it
         const int nsteps = (a.r + 15) / 16, width = nsteps * 16;
         if (stager && nsteps <= EXT_STEPS) {                // operands already in registers
 #pragma unroll
@@ -466,6 +473,25 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
     // --- epilogue: fp32 accumulators -> 16 bit.  Each MFMA wave lays its TM x TN block into its own LDS area in
     //     row-major order; then all waves stream the areas out in 16-byte pieces (8 lanes per 128-byte row
     //     segment).  Rows beyond M and columns beyond NO (always whole 8-element pieces) are dropped.
+    if (a.splits > 1) {
+        // split contraction: the fp32 accumulators go to this split's plane as they are (a lane's 32 neighbours
+        // write 128 consecutive bytes of a row); a second kernel sums the planes in order and rounds once
+        if (!stager) {
+            float *P = a.part + (size_t)split * a.M * NO;
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int j = 0; j < NI; ++j) {
+                    const int gcol = col0 + wn * TN + j * 32 + (lane & 31);
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int grow = row0 + wm * TM + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+                        if (grow < a.M && gcol < NO) P[(size_t)grow * NO + gcol] = acc[i][j][v];
+                    }
+                }
+        }
+        return;
+    }
     constexpr int ESTR = TN + 8;
     if (!stager) {
         uint16_t *E = smem + cw * (TM * ESTR);
@@ -501,7 +527,31 @@ void launch_variant(const GemmArgs &a, hipStream_t s)
     constexpr size_t lds = lds_pipe > lds_epi ? lds_pipe : lds_epi;
     auto kern = qgemm_kernel<BITS, BF16, TRANS, BM, BN, WM, WN>;
     ensure_dynamic_lds((const void *)kern, (int)(lds));
-    hipLaunchKernelGGL(kern, dim3(a.tiles_m * a.tiles_n), dim3(WM * WN * 64 + STAGERS), lds, s, a);
+    hipLaunchKernelGGL(kern, dim3(a.tiles_m * a.tiles_n * a.splits), dim3(WM * WN * 64 + STAGERS), lds, s, a);
+}
+
+// out = round16(sum over the split planes, in order): 8 elements per thread
+template <bool BF16>
+__global__ __launch_bounds__(256) void splitk_sum_kernel(const float *__restrict__ part, uint16_t *__restrict__ out,
+                                                         size_t plane, int splits)
+{
+    const size_t e = ((size_t)blockIdx.x * 256 + threadIdx.x) * 8;
+    if (e >= plane) return;                             // plane is a multiple of 8
+    float acc[8];
+#pragma unroll
+    for (int h = 0; h < 8; ++h) acc[h] = 0.f;
+    for (int sp = 0; sp < splits; ++sp) {
+        const float4_t lo = *(const float4_t *)(part + sp * plane + e), hi = *(const float4_t *)(part + sp * plane + e + 4);
+#pragma unroll
+        for (int h = 0; h < 4; ++h) {
+            acc[h] += lo[h];
+            acc[4 + h] += hi[h];
+        }
+    }
+    u16x8_t o;
+#pragma unroll
+    for (int h = 0; h < 8; ++h) o[h] = to16<BF16>(acc[h]);
+    *(u16x8_t *)(out + e) = o;
 }
 
 template <int BITS, bool BF16, bool TRANS>
@@ -520,13 +570,27 @@ void launch_tiles(GemmArgs &a, hipStream_t s)
 #define QLORA_WN 2
 #endif
     constexpr int BM = QLORA_BM, BN = QLORA_BN;
-    const int NO = TRANS ? a.K : a.N;
+    static_assert(BN == GEMM_SPLIT_BN, "gemm_splits() counts tiles of this width");
+    const int NO = TRANS ? a.K : a.N, KC = TRANS ? a.N : a.K;
     a.tiles_n = (NO + BN - 1) / BN;
-    // fewer tiles than CUs: halve the tile height, so that (up to) twice as many CUs work
+    a.splits = 1;
+    a.kt_split = (KC + BK - 1) / BK;
+    // fewer tiles than CUs: halve the tile height, so that (up to) twice as many CUs work; far fewer: also split
+    // the contraction over several workgroups per tile
     if constexpr (BM == 256) {
-        if (((a.M + 255) / 256) * a.tiles_n < 256 && a.M > 128) {
+        if (((a.M + 255) / 256) * a.tiles_n < 256) {
             a.tiles_m = (a.M + 127) / 128;
+            const int splits = a.part ? gemm_splits(a.M, NO, KC) : 1;
+            if (splits > 1) {
+                a.splits = splits;
+                a.kt_split = (a.kt_split + splits - 1) / splits;
+            }
             launch_variant<BITS, BF16, TRANS, 128, BN, QLORA_WM, QLORA_WN>(a, s);
+            if (splits > 1) {
+                const size_t plane = (size_t)a.M * NO;
+                hipLaunchKernelGGL(splitk_sum_kernel<BF16>, dim3((unsigned)((plane / 8 + 255) / 256)), dim3(256), 0, s,
+                                   a.part, a.out, plane, splits);
+            }
             return;
         }
     }
@@ -565,18 +629,18 @@ void launch_bits_dtype(const Problem &p, GemmArgs &a, hipStream_t s)
 }  // namespace
 
 void launch_fwd_mfma(const Problem &p, const void *x, const uint32_t *packed, const void *scales, const uint8_t *zeros,
-                     const void *t, const void *B, void *y, hipStream_t s)
+                     const void *t, const void *B, void *y, float *part, hipStream_t s)
 {
     GemmArgs a{(const uint16_t *)x, packed, (const uint16_t *)scales, zeros, (const uint16_t *)t, (const uint16_t *)B,
-               (uint16_t *)y, p.M, p.N, p.K, p.G, p.r, p.sc, 0, 0, group_magic(p.G)};
+               (uint16_t *)y, p.M, p.N, p.K, p.G, p.r, p.sc, 0, 0, group_magic(p.G), part, 1, 0};
     launch_bits_dtype<false>(p, a, s);
 }
 
 void launch_bwd_dx_mfma(const Problem &p, const void *dy, const uint32_t *packed, const void *scales,
-                        const uint8_t *zeros, const void *u, const void *A, void *dx, hipStream_t s)
+                        const uint8_t *zeros, const void *u, const void *A, void *dx, float *part, hipStream_t s)
 {
     GemmArgs a{(const uint16_t *)dy, packed, (const uint16_t *)scales, zeros, (const uint16_t *)u, (const uint16_t *)A,
-               (uint16_t *)dx, p.M, p.N, p.K, p.G, p.r, p.sc, 0, 0, group_magic(p.G)};
+               (uint16_t *)dx, p.M, p.N, p.K, p.G, p.r, p.sc, 0, 0, group_magic(p.G), part, 1, 0};
     launch_bits_dtype<true>(p, a, s);
 }
 

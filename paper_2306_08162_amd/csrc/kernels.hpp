@@ -51,10 +51,25 @@ void launch_adapter_grads(const void *dy, const void *t, const void *x, const vo
                           const uint32_t *keep, float keep_scale, bool bf16, hipStream_t s);
 
 // gemm_mfma.hip -- tiled MFMA GEMMs with fused dequantisation (any accepted shape)
+// Workgroups per output tile along the contraction.  An [M, NO] output with a contraction of length KC that makes
+// at most 128 tiles of 128 x 128 would leave half of the 256 CUs idle: the contraction is then cut into up to 8
+// runs of at least 8 stages (64 deep each), every run one workgroup, and the fp32 partial products are summed in a
+// fixed order by a second kernel.  1: no split.  Depends on the shape alone.
+constexpr int GEMM_SPLIT_BN = 128;
+inline int gemm_splits(int M, int NO, int KC)
+{
+    const long tiles = (long)((M + 127) / 128) * ((NO + GEMM_SPLIT_BN - 1) / GEMM_SPLIT_BN);
+    if (tiles > 128) return 1;
+    const int by_cus = (int)(256 / tiles), by_depth = ((KC + 63) / 64) / 8;
+    const int s = by_cus < by_depth ? by_cus : by_depth;
+    return s > 8 ? 8 : (s < 1 ? 1 : s);
+}
+// part: gemm_splits(M, NO, KC) * M * NO floats when that count exceeds 1 (NO = N, KC = K forward; NO = K, KC = N
+// backward); NULL switches splitting off
 void launch_fwd_mfma(const Problem &p, const void *x, const uint32_t *packed, const void *scales,
-                     const uint8_t *zeros, const void *t, const void *B, void *y, hipStream_t s);
+                     const uint8_t *zeros, const void *t, const void *B, void *y, float *part, hipStream_t s);
 void launch_bwd_dx_mfma(const Problem &p, const void *dy, const uint32_t *packed, const void *scales,
-                        const uint8_t *zeros, const void *u, const void *A, void *dx, hipStream_t s);
+                        const uint8_t *zeros, const void *u, const void *A, void *dx, float *part, hipStream_t s);
 
 // gemv.hip -- small token counts: weight-streaming kernels, one pass over the packed weight
 constexpr int SMALL_M_FWD_MAX = 64;   // forward kernel handles up to four 16-row token blocks
