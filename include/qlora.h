@@ -77,9 +77,11 @@ size_t qlora_packed_words(int N, int K, int bits);
 /*
  * Bytes of device scratch qlora_linear_fwd / qlora_linear_bwd need for this
  * problem (the larger of the two); 0 if the arguments are invalid.  The
- * workspace holds t = x A^T and u = dY B when they are not passed in, and the
- * per-slice partial sums of dA and dB (summed in a fixed order, so results are
- * bitwise reproducible run to run).
+ * workspace holds t = x A^T and u = dY B when they are not passed in, the
+ * per-slice partial sums of dA and dB, and, for token counts whose output
+ * makes too few tiles to occupy the chip, the fp32 partial products of a GEMM
+ * whose contraction is split over several workgroups (all summed in a fixed
+ * order, so results are bitwise reproducible run to run).
  */
 size_t qlora_workspace_bytes(int M, int N, int K, int bits, int group_size, int rank);
 
