@@ -117,3 +117,48 @@ def test_decoder_block_siblings_full_size(bits):
         inps = [wl.make_inputs(block[n]) for n in names]
         x = inps[0].x
         _check([dataclasses.replace(i, x=x) for i in inps])
+
+
+@pytest.mark.parametrize("case", [(100, 512, (264, 136), 4, 128, 8, "f16"), (300, 1024, (520, 264, 72), 2, 64, 8, "bf16")],
+                         ids=["two_f16", "three_bf16"])
+def test_siblings_above_16_rows_as_one_concatenated_layer(case):
+    """Above 16 token rows siblings need no entry point of their own: packed rows, scales and zeros of the siblings
+    laid one after the other along N are themselves a valid weight, the stacked A with a block-structured B a valid
+    adapter of rank (count * r), so one call of the ordinary entry points serves them all.  Checked per projection
+    against the single-layer oracle (dX against the sum of the layers' dX)."""
+    import torch
+    from paper_2306_08162_amd.device import DeviceLayer
+
+    M, K, Ns, bits, G, r, dtype = case
+    inps = _siblings(11 * M + K, M, K, Ns, bits, G, r, dtype)
+    c0, count, Ntot = inps[0].cfg, len(Ns), sum(Ns)
+    B = np.zeros((Ntot, count * r), dtype=np.uint16)            # bit pattern 0 is +0.0 in both formats
+    row = 0
+    for i, inp in enumerate(inps):
+        B[row:row + inp.cfg.N, i * r:(i + 1) * r] = inp.B
+        row += inp.cfg.N
+    cat = wl.LayerInputs(
+        cfg=dataclasses.replace(c0, name="concatenated", N=Ntot, rank=count * r, alpha=c0.alpha * count),  # same alpha/r
+        codes=np.concatenate([i.codes for i in inps]), scales=np.concatenate([i.scales for i in inps]),
+        zeros=np.concatenate([i.zeros for i in inps]), A=np.concatenate([i.A for i in inps]), B=B, x=inps[0].x,
+        dy=np.ascontiguousarray(np.concatenate([i.dy for i in inps], axis=1)))
+    announce(f"concatenated siblings N={Ns} M={M} K={K} bits={bits} G={G} r={r} {dtype}")
+    layer = DeviceLayer(cat)
+    layer.forward()
+    layer.backward()
+    torch.cuda.synchronize()
+    y, dA, dB = oracle.widen(layer.host_y(), dtype), layer.host_dA(), layer.host_dB()
+    errs, dx_ref, row = {}, 0.0, 0
+    for i, inp in enumerate(inps):
+        lo, n = make_oracle(inp), inp.cfg.N
+        y_ref, _ = lo.forward(inp.x)
+        dx_ref = dx_ref + lo.backward_dx(inp.dy)
+        dA_ref, dB_ref = lo.backward_adapters(inp.dy, inp.x)
+        errs[f"y{i}"] = rel_fro(y[:, row:row + n], y_ref)
+        errs[f"dA{i}"] = rel_fro(dA[i * r:(i + 1) * r], dA_ref)
+        errs[f"dB{i}"] = rel_fro(dB[row:row + n, i * r:(i + 1) * r], dB_ref)
+        row += n
+    errs["dx"] = rel_fro(oracle.widen(layer.host_dx(), dtype), dx_ref)
+    announce(" ".join(f"{k}={v:.2e}" for k, v in errs.items()))
+    for k, v in errs.items():
+        assert np.isfinite(v) and v <= TOL, f"rel. Frobenius error of {k} = {v:.3e} > {TOL}"
