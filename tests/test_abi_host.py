@@ -48,6 +48,11 @@ def test_workspace_bytes():
     assert ql.qlora_workspace_bytes(0, 4096, 4096, 4, 128, 8) == 0
     assert ql.qlora_workspace_bytes(16, 4096, 4096, 4, 100, 8) == 0
     assert ql.qlora_workspace_bytes(16, 4096, 4096, 4, 128, 12) == 0
+    # token counts whose output makes few tiles: room for the fp32 planes of a GEMM split along its contraction
+    # (256 x 4096 output = 64 tiles of 128 x 128 -> 4 planes; 512 rows -> 2 planes; 1024 rows: no split)
+    assert ql.qlora_workspace_bytes(256, 4096, 4096, 4, 128, 0) >= 4 * 256 * 4096 * 4
+    assert ql.qlora_workspace_bytes(512, 4096, 4096, 4, 128, 0) >= 2 * 512 * 4096 * 4
+    assert ql.qlora_workspace_bytes(1024, 4096, 4096, 4, 128, 0) < 1024 * 4096 * 4
 
 
 def _fwd(**kw):
