@@ -391,7 +391,9 @@ constexpr int go_lds_bytes(int R)
     const int pipe = GO_WAVES * 2 * go_buf_bytes(R), sum = GO_WAVES * ((R + 15) / 16 * 16) * GO_COLS * 4;
     return pipe > sum ? pipe : sum;
 }
-template <bool BF16, int R, bool MASKED>                     // R: side columns, 8, 16, 32 or 64; MASKED: a.keep != NULL
+// R: side columns staged per row, 8, 16, 32 or 64; the rank a.r may be smaller (24 in 32; 40, 48, 56 in 64): the
+// missing 8-column pieces are fetched as copies of the last one and count as zero.  MASKED: a.keep != NULL
+template <bool BF16, int R, bool MASKED>
 __global__ __launch_bounds__(GO_WAVES * 64) void adapter_grad_onepass_kernel(const GradArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) char go_lds[];   // [GO_WAVES][2] buffers, then reused for the final sum
@@ -424,13 +426,13 @@ __global__ __launch_bounds__(GO_WAVES * 64) void adapter_grad_onepass_kernel(con
     // what this lane fetches: of the activations, piece lane % 4 (8 columns) of row lane / 4 of every 16-row block;
     // of the side operand, piece lane % PR of row lane / PR of every S_ROWS-row block
     const int a_row = lane >> 2, a_col = min(c0 + 8 * (lane & 3), C - 8);
-    const int s_row = lane / PR, s_col = a.side_c0 + 8 * (lane % PR);
+    const int r = a.r;                                       // r <= R, r % 8 == 0
+    const int s_row = lane / PR, s_col = a.side_c0 + 8 * min(lane % PR, r / 8 - 1);
     // transposing reads (see skinny_rows_staged_kernel): lane (e = li / 4, g = li % 4) of block q points at row
     // 8 q + e, columns 4 g .. + 4 of a 32-row chunk; the second read of a fragment starts four rows further down
     const int t_row = 8 * q + (li >> 2);
     const int act_rd = t_row * (GO_COLS * 2) + 8 * (li & 3);                      // + 32 for the second 16 columns
     const int side_rd = GO_ACT_BYTES + t_row * (R * 2) + 2 * min(4 * (li & 3), R - 4);   // + 32 per 16-column group
-    const bool jval = li < R;
 
     // this wave's stretches: rows (GO_WAVES i + wave) * GO_ROWS .. + GO_ROWS, i = 0, 1, ...; two are in flight
     auto fetch = [&](int m0, int buf) {
@@ -486,7 +488,8 @@ __global__ __launch_bounds__(GO_WAVES * 64) void adapter_grad_onepass_kernel(con
                 u16x8_t fa = {(uint16_t)s_lo[0], (uint16_t)s_lo[1], (uint16_t)s_lo[2], (uint16_t)s_lo[3],
                               (uint16_t)s_hi[0], (uint16_t)s_hi[1], (uint16_t)s_hi[2], (uint16_t)s_hi[3]};
                 // rows past M were fetched as copies of the last row: their side values count as zero; so do the
-                // columns past R of the 16-column operand
+                // columns past the rank
+                const bool jval = 16 * g + li < r;
                 if (!jval || left < 8) {
 #pragma unroll
                     for (int e = 0; e < 8; ++e)
@@ -520,13 +523,13 @@ __global__ __launch_bounds__(GO_WAVES * 64) void adapter_grad_onepass_kernel(con
             for (int v = 0; v < 4; ++v)
                 red[(wave * (16 * RG) + 16 * g + 4 * q + v) * GO_COLS + 16 * h + li] = acc[g][h][v];
     __syncthreads();
-    for (int e = threadIdx.x; e < R * GO_COLS; e += GO_WAVES * 64) {
+    for (int e = threadIdx.x; e < r * GO_COLS; e += GO_WAVES * 64) {
         const int j = e / GO_COLS, c = e % GO_COLS;
         float sum = 0.f;
 #pragma unroll
         for (int w = 0; w < GO_WAVES; ++w) sum += red[(w * (16 * RG) + j) * GO_COLS + c];
         if (c0 + c < C) {
-            float *dst = a.out[which] + (which ? (long)j * C + c0 + c : (long)(c0 + c) * R + j);
+            float *dst = a.out[which] + (which ? (long)j * C + c0 + c : (long)(c0 + c) * r + j);
             *dst = a.beta == 0.f ? a.sc[which] * sum : fmaf(a.beta, *dst, a.sc[which] * sum);
         }
     }
@@ -783,9 +786,9 @@ void launch_adapter_grads(const void *dy, const void *t, const void *x, const vo
     a.sc[1] = keep ? sc * keep_scale : sc;
     a.beta = beta;
     a.keep = (const uint8_t *)keep;
-    // one pass, no partial sums: ranks 8, 16, 32, 64, byte offsets of the staged loads in 32 bits
-    if ((r == 8 || r == 16 || r == 32 || r == 64) && (long)M * N * 2 < (1L << 32) && (long)M * K * 2 < (1L << 32) &&
-        (long)M * r_all * 2 < (1L << 32)) {
+    // one pass, no partial sums: byte offsets of the staged loads in 32 bits (ranks 24, 40, 48 and 56 run in the next
+    // larger of the kernel's side widths 8, 16, 32, 64)
+    if ((long)M * N * 2 < (1L << 32) && (long)M * K * 2 < (1L << 32) && (long)M * r_all * 2 < (1L << 32)) {
         a.nb0 = (N + GO_COLS - 1) / GO_COLS;
         const int blocks = a.nb0 + (K + GO_COLS - 1) / GO_COLS;
 #define QLORA_ONEPASS(R)                                       \
@@ -794,7 +797,7 @@ void launch_adapter_grads(const void *dy, const void *t, const void *x, const vo
     return
         if (r == 8) { QLORA_ONEPASS(8); }
         if (r == 16) { QLORA_ONEPASS(16); }
-        if (r == 32) { QLORA_ONEPASS(32); }
+        if (r <= 32) { QLORA_ONEPASS(32); }
         QLORA_ONEPASS(64);
 #undef QLORA_ONEPASS
     }

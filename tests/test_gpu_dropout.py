@@ -58,6 +58,8 @@ CASES = [
     (300, 640, 392, 4, 128, 8, "f16", 0.05),
     (257, 1024, 520, 2, 128, 32, "bf16", 0.5),
     (130, 96, 40, 8, 32, 64, "bf16", 0.05),
+    (200, 384, 264, 4, 128, 24, "f16", 0.3),             # rank 24 in the 32-wide one-pass gradient kernel, masked
+    (90, 512, 136, 2, 128, 56, "bf16", 0.05),            # rank 56 in the 64-wide one
     (65, 256, 1000, 4, 64, 0, "f16", 0.05),              # no adapter: the mask has nothing to act on
 ]
 

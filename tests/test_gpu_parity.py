@@ -80,6 +80,9 @@ SMALL_CASES = [
     (11, 2048, 1544, 4, 128, 16, "f16"),       # backward: 8-wave workgroups, slices that do not divide the rows
     (7, 512, 136, 4, 512, 8, "f16"),           # per-row grouping on the weight-streaming path
     (150, 1024, 264, 2, 1024, 8, "f16"),       # and on the tiled path, both passes
+    (130, 256, 264, 4, 64, 48, "f16"),         # ranks 40, 48, 56: gradients by the 64-wide one-pass kernel
+    (90, 512, 136, 2, 128, 56, "bf16"),
+    (200, 384, 520, 8, 128, 40, "bf16"),
     (100, 2048, 512, 4, 128, 8, "f16"),        # forward contraction split over 4 workgroups per tile
     (200, 1056, 2048, 3, 32, 16, "bf16"),      # forward split in 9 + 8 stages (the last one half empty), backward in 4
     (70, 4096, 4096, 2, 128, 8, "f16"),        # both passes split 8 ways
