@@ -87,8 +87,10 @@ __global__ __launch_bounds__(LT) void lrec_loss_kernel(const LossArgs a)
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
             const int p = piece_of(i) < pieces ? piece_of(i) : 0;          // the row's first piece stands in past the end
-            rs[i] = *(const u16x8_t *)(zs + 8 * (long)p);
-            rt[i] = *(const u16x8_t *)(zt + 8 * (long)p);
+            // read once, never again: the non-temporal hint keeps the 393 MB of a call from displacing each other
+            // in the caches on their way through (83 -> 76 us at 2048 x 32000)
+            rs[i] = __builtin_nontemporal_load((const u16x8_t *)(zs + 8 * (long)p));
+            rt[i] = __builtin_nontemporal_load((const u16x8_t *)(zt + 8 * (long)p));
         }
     }
 
@@ -219,7 +221,7 @@ __global__ __launch_bounds__(LT) void lrec_loss_kernel(const LossArgs a)
         }
 #pragma unroll
         for (int e = 0; e < 8; ++e) g8[e] = to16<BF16>(g[e]);
-        *(u16x8_t *)(grow + k0) = g8;
+        __builtin_nontemporal_store(g8, (u16x8_t *)(grow + k0));
     }
     // the target's own entry carries one more term, -lce / M: the thread that wrote it (same thread, so the two
     // stores to that address stay in order) computes it again in full and overwrites it
