@@ -331,16 +331,20 @@ static int backward(const void *dy, const void *x, const uint32_t *packed, const
     }
     {
         GemmTimer timer(s);
-        if (keep_mask) {        // the GEMM leaves the base product; the adapter's masked share is added afterwards
+        if (keep_mask && rank > GEMM_MASKED_MAX_RANK) {
+            // the GEMM leaves the base product; the adapter's masked share is added afterwards
             Problem base = p;
             base.r = 0;
             base.sc = 0.f;
-            launch_bwd_dx_mfma(base, dy, packed, scales, zeros, nullptr, nullptr, dx, (float *)(ws + w.split_off), s);
-        } else {
-            launch_bwd_dx_mfma(p, dy, packed, scales, zeros, u, A, dx, (float *)(ws + w.split_off), s);
+            launch_bwd_dx_mfma(base, dy, packed, scales, zeros, nullptr, nullptr, dx, (float *)(ws + w.split_off), nullptr,
+                               1.f, s);
+        } else {                // keep_mask: the GEMM's epilogue adds the adapter's share masked per element
+            launch_bwd_dx_mfma(p, dy, packed, scales, zeros, u, A, dx, (float *)(ws + w.split_off), keep_mask, keep_scale,
+                               s);
         }
     }
-    if (keep_mask) launch_lora_dx_masked(dx, u, A, keep_mask, M, K, rank, p.sc * keep_scale, p.bf16, s);
+    if (keep_mask && rank > GEMM_MASKED_MAX_RANK)
+        launch_lora_dx_masked(dx, u, A, keep_mask, M, K, rank, p.sc * keep_scale, p.bf16, s);
     if (rank > 0) {
         const void *t = t_saved;
         if (!t) {

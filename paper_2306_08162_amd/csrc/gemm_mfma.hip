@@ -36,6 +36,8 @@ struct GemmArgs {
     uint32_t g32_magic;       // see group_magic(): (k/32) / (G/32) == umulhi(k/32, magic), 0 meaning G == 32
     float *part;              // splits > 1: fp32 partial products [splits][M][NO], summed by splitk_sum_kernel
     int splits, kt_split;     // workgroups per tile along the contraction, 64-deep stages per workgroup
+    const uint8_t *keep;      // LoRA dropout (backward only): keep bit of x[m, k] is bit k % 8 of keep[m * K/8 + k/8]
+    float keep_sc;            // sc * keep_scale
 };
 
 template <bool BF16>
@@ -95,9 +97,14 @@ __device__ __forceinline__ void wait_vm_and_barrier()
 // upper two bits run through 0..3 over any 4 consecutive rows starting at a multiple of 4.
 __device__ __forceinline__ constexpr int wswz(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
 
-template <int BITS, bool BF16, bool TRANS, int BM, int BN, int WM, int WN>
+// MASKED (backward under LoRA dropout, ranks up to 32, no split): the adapter's share of dX is masked per element,
+// dX = dY Wd + keep_sc * keep (.) (u A), so it cannot ride in the accumulators.  The LoRA steps are left out; the
+// staging waves lay the tile's rows of u and columns of A (both fetched at kernel start) beside the epilogue area, and
+// the copy-out adds the masked product to every 8-element piece before it is stored.
+template <int BITS, bool BF16, bool TRANS, int BM, int BN, int WM, int WN, bool MASKED = false>
 __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const GemmArgs a)
 {
+    static_assert(!MASKED || TRANS, "the dropout mask acts on dX only");
     constexpr int MW = WM * WN;                     // MFMA waves
     constexpr int THREADS = MW * 64 + STAGERS;
     static_assert(MW == 4 || MW == 8, "one or two MFMA waves per SIMD");
@@ -405,7 +412,28 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
 
     // --- LoRA term as extra contraction steps: Act' = sc * t (or u), W' = B (or A^T), zero-padded to 16.
     //     Every wave is past the last barrier of the main loop, so every LDS stage is free.
-    if (a.r > 0 && split == 0) {                            // the first workgroup of a split contraction adds it
+    constexpr int ESTR = TN + 8;                            // row pitch of a wave's epilogue area
+    constexpr int SIDE_R = 32;                              // adapter columns of the masked epilogue's side tiles
+    uint16_t *const side_u = smem + MW * TM * ESTR;         // [BM][SIDE_R] rows of u, behind the epilogue areas
+    uint16_t *const side_a = side_u + BM * SIDE_R;          // [SIDE_R][BN] columns of A
+    if constexpr (MASKED) {
+        if (stager) {                                       // the prefetched pieces, as they are (zero past the rank)
+#pragma unroll
+            for (int st = 0; st < EXT_STEPS; ++st) {
+#pragma unroll
+                for (int i = 0; i < EXT_A; ++i) {
+                    const int c = stid + STAGERS * i;
+                    *(u16x8_t *)(side_u + (c >> 1) * SIDE_R + 16 * st + (c & 1) * 8) = ext_a[st][i];
+                }
+#pragma unroll
+                for (int i = 0; i < EXT_W; ++i) {
+                    const int c = stid + STAGERS * i;
+                    *(u16x8_t *)(side_a + (16 * st + c / (BN / 8)) * BN + (c % (BN / 8)) * 8) = ext_w[st][i];
+                }
+            }
+        }
+    }
+    if (!MASKED && a.r > 0 && split == 0) {                 // the first workgroup of a split contraction adds it
         const int nsteps = (a.r + 15) / 16, width = nsteps * 16;
         if (stager && nsteps <= EXT_STEPS) {                // operands already in registers
 #pragma unroll
@@ -492,7 +520,6 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
         }
         return;
     }
-    constexpr int ESTR = TN + 8;
     if (!stager) {
         uint16_t *E = smem + cw * (TM * ESTR);
 #pragma unroll
@@ -512,7 +539,31 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
             const int w = c / PER_AREA, cc = c % PER_AREA;
             const int r = cc / CPR, ch = (cc % CPR) * 8;
             const int grow = row0 + (w / WN) * TM + r, gcol = col0 + (w % WN) * TN + ch;
-            const u32x4_t v = *(const u32x4_t *)(smem + w * (TM * ESTR) + r * ESTR + ch);
+            u32x4_t v = *(const u32x4_t *)(smem + w * (TM * ESTR) + r * ESTR + ch);
+            if constexpr (MASKED) {
+                if (grow < a.M && gcol < NO) {
+                    const uint32_t bits = a.keep[(size_t)grow * (NO / 8) + gcol / 8];
+                    const uint16_t *ur = side_u + ((w / WN) * TM + r) * SIDE_R, *ap = side_a + (w % WN) * TN + ch;
+                    float l[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                    const int rp = (a.r + 7) / 8;               // 8-column pieces of the adapter
+                    for (int jp = 0; jp < rp; ++jp) {
+                        const u16x8_t u8 = *(const u16x8_t *)(ur + 8 * jp);
+#pragma unroll
+                        for (int jj = 0; jj < 8; ++jj) {
+                            const float uj = cvt16<BF16>(u8[jj]);
+                            const u16x8_t a8 = *(const u16x8_t *)(ap + (8 * jp + jj) * BN);
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) l[e] = fmaf(uj, cvt16<BF16>(a8[e]), l[e]);
+                        }
+                    }
+                    const u16x8_t b8 = __builtin_bit_cast(u16x8_t, v);
+                    u16x8_t o8;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        o8[e] = ((bits >> e) & 1u) ? to16<BF16>(cvt16<BF16>(b8[e]) + a.keep_sc * l[e]) : b8[e];
+                    v = __builtin_bit_cast(u32x4_t, o8);
+                }
+            }
             // written once and not read by this kernel: the non-temporal hint keeps the output from displacing the
             // activation rows and weight columns that other tiles still want from L2 (-1 us per GEMM)
             if (grow < a.M && gcol < NO) __builtin_nontemporal_store(v, (u32x4_t *)(a.out + ((long)grow * NO + gcol)));
@@ -520,14 +571,15 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
     }
 }
 
-template <int BITS, bool BF16, bool TRANS, int BM, int BN, int WM, int WN>
+template <int BITS, bool BF16, bool TRANS, int BM, int BN, int WM, int WN, bool MASKED = false>
 void launch_variant(const GemmArgs &a, hipStream_t s)
 {
     constexpr size_t wstage = TRANS ? (size_t)BK * BN : (size_t)BN * LDS_STRIDE;
     constexpr size_t lds_pipe = (QLORA_NXS * (size_t)BM * BK + 2 * wstage) * sizeof(uint16_t);
-    constexpr size_t lds_epi = (size_t)WM * WN * (BM / WM) * (BN / WN + 8) * sizeof(uint16_t);
+    constexpr size_t lds_side = MASKED ? (size_t)32 * (BM + BN) * sizeof(uint16_t) : 0;    // side tiles of the masked epilogue
+    constexpr size_t lds_epi = (size_t)WM * WN * (BM / WM) * (BN / WN + 8) * sizeof(uint16_t) + lds_side;
     constexpr size_t lds = lds_pipe > lds_epi ? lds_pipe : lds_epi;
-    auto kern = qgemm_kernel<BITS, BF16, TRANS, BM, BN, WM, WN>;
+    auto kern = qgemm_kernel<BITS, BF16, TRANS, BM, BN, WM, WN, MASKED>;
     ensure_dynamic_lds((const void *)kern, (int)(lds));
     hipLaunchKernelGGL(kern, dim3(a.tiles_m * a.tiles_n * a.splits), dim3(WM * WN * 64 + STAGERS), lds, s, a);
 }
@@ -582,6 +634,12 @@ void launch_tiles(GemmArgs &a, hipStream_t s)
     if constexpr (BM == 256) {
         if (((a.M + 255) / 256) * a.tiles_n < 256) {
             a.tiles_m = (a.M + 127) / 128;
+            if constexpr (TRANS) {
+                if (a.keep) {           // the masked epilogue needs the whole contraction in one workgroup
+                    launch_variant<BITS, BF16, TRANS, 128, BN, QLORA_WM, QLORA_WN, true>(a, s);
+                    return;
+                }
+            }
             const int splits = a.part ? gemm_splits(a.M, NO, KC) : 1;
             if (splits > 1) {
                 a.splits = splits;
@@ -597,6 +655,12 @@ void launch_tiles(GemmArgs &a, hipStream_t s)
         }
     }
     a.tiles_m = (a.M + BM - 1) / BM;
+    if constexpr (TRANS) {
+        if (a.keep) {
+            launch_variant<BITS, BF16, TRANS, BM, BN, QLORA_WM, QLORA_WN, true>(a, s);
+            return;
+        }
+    }
     launch_variant<BITS, BF16, TRANS, BM, BN, QLORA_WM, QLORA_WN>(a, s);
 }
 
@@ -634,15 +698,17 @@ void launch_fwd_mfma(const Problem &p, const void *x, const uint32_t *packed, co
                      const void *t, const void *B, void *y, float *part, hipStream_t s)
 {
     GemmArgs a{(const uint16_t *)x, packed, (const uint16_t *)scales, zeros, (const uint16_t *)t, (const uint16_t *)B,
-               (uint16_t *)y, p.M, p.N, p.K, p.G, p.r, p.sc, 0, 0, group_magic(p.G), part, 1, 0};
+               (uint16_t *)y, p.M, p.N, p.K, p.G, p.r, p.sc, 0, 0, group_magic(p.G), part, 1, 0, nullptr, 0.f};
     launch_bits_dtype<false>(p, a, s);
 }
 
 void launch_bwd_dx_mfma(const Problem &p, const void *dy, const uint32_t *packed, const void *scales,
-                        const uint8_t *zeros, const void *u, const void *A, void *dx, float *part, hipStream_t s)
+                        const uint8_t *zeros, const void *u, const void *A, void *dx, float *part,
+                        const uint32_t *keep, float keep_scale, hipStream_t s)
 {
     GemmArgs a{(const uint16_t *)dy, packed, (const uint16_t *)scales, zeros, (const uint16_t *)u, (const uint16_t *)A,
-               (uint16_t *)dx, p.M, p.N, p.K, p.G, p.r, p.sc, 0, 0, group_magic(p.G), part, 1, 0};
+               (uint16_t *)dx, p.M, p.N, p.K, p.G, p.r, p.sc, 0, 0, group_magic(p.G), part, 1, 0,
+               p.r > 0 ? (const uint8_t *)keep : nullptr, p.sc * keep_scale};
     launch_bits_dtype<true>(p, a, s);
 }
 

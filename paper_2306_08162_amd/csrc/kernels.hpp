@@ -68,8 +68,12 @@ inline int gemm_splits(int M, int NO, int KC)
 // backward); NULL switches splitting off
 void launch_fwd_mfma(const Problem &p, const void *x, const uint32_t *packed, const void *scales,
                      const uint8_t *zeros, const void *t, const void *B, void *y, float *part, hipStream_t s);
+// keep != NULL (LoRA dropout, ranks up to GEMM_MASKED_MAX_RANK): dX = dY Wd + sc keep_scale keep (.) (u A), the
+// masked product added in the epilogue (the contraction is then never split)
+constexpr int GEMM_MASKED_MAX_RANK = 32;
 void launch_bwd_dx_mfma(const Problem &p, const void *dy, const uint32_t *packed, const void *scales,
-                        const uint8_t *zeros, const void *u, const void *A, void *dx, float *part, hipStream_t s);
+                        const uint8_t *zeros, const void *u, const void *A, void *dx, float *part,
+                        const uint32_t *keep, float keep_scale, hipStream_t s);
 
 // gemv.hip -- small token counts: weight-streaming kernels, one pass over the packed weight
 constexpr int SMALL_M_FWD_MAX = 64;   // forward kernel handles up to four 16-row token blocks

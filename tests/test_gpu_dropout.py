@@ -61,6 +61,8 @@ CASES = [
     (200, 384, 264, 4, 128, 24, "f16", 0.3),             # rank 24 in the 32-wide one-pass gradient kernel, masked
     (90, 512, 136, 2, 128, 56, "bf16", 0.05),            # rank 56 in the 64-wide one
     (65, 256, 1000, 4, 64, 0, "f16", 0.05),              # no adapter: the mask has nothing to act on
+    (2048, 4096, 264, 4, 128, 16, "f16", 0.05),          # 256-row tiles: masked product added in the GEMM's epilogue
+    (2050, 4128, 136, 2, 96, 32, "bf16", 0.3),           # the same with ragged last tiles and two 16-column groups
 ]
 
 
