@@ -15,14 +15,14 @@ def _snapshot(layer, sib=None):
     return out
 
 
-@pytest.mark.parametrize("M", [16, 300], ids=["weight_streaming", "tiled"])
-def test_graph_replays_match_eager(M):
+@pytest.mark.parametrize("M,K", [(16, 512), (300, 512), (300, 2048)], ids=["weight_streaming", "tiled", "tiled_split"])
+def test_graph_replays_match_eager(M, K):
     import torch
     from paper_2306_08162_amd.device import DeviceLayer, DeviceSiblings
-    announce(f"graph replay M={M}")
-    inp = small_inputs(123 + M, M, 512, 264, 4, 128, 8, "f16")
+    announce(f"graph replay M={M} K={K}")   # K = 2048: the forward GEMM's contraction is split over 4 workgroups per tile
+    inp = small_inputs(123 + M, M, K, 264, 4, 128, 8, "f16")
     layer = DeviceLayer(inp)
-    other = DeviceLayer(small_inputs(124 + M, M, 512, 136, 4, 128, 8, "f16"))
+    other = DeviceLayer(small_inputs(124 + M, M, K, 136, 4, 128, 8, "f16"))
     other.x = layer.x
     sib = DeviceSiblings([layer, other]) if M <= 16 else None
 
