@@ -286,6 +286,16 @@ int qlora_lrec_loss(const void *student_logits, const void *teacher_logits, cons
  */
 int qlora_profile_gemm(void *ev_before, void *ev_after);
 
+/*
+ * Which stretch of a tiled pass (more than 64 token rows forward, more than 16 backward) the two events of
+ * qlora_profile_gemm enclose.  0 (default): the GEMM kernel alone.  1: the adapter kernel launched before it
+ * (t = x A^T forward, u = dY B backward) and the GEMM.  2: that adapter kernel alone.  An event pair around one
+ * kernel also measures the latency of dispatching it behind an event; the difference of spans 1 and 2 does not
+ * (the GEMM then follows a kernel, as it does in an untimed pass), which is how bench.py prices the kernel.
+ * Other values count as 0.  Always returns QLORA_OK.
+ */
+int qlora_profile_gemm_span(int span);
+
 #ifdef __cplusplus
 }
 #endif

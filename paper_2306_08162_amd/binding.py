@@ -22,7 +22,8 @@ EXPORTS = ["qlora_status_string", "qlora_packed_words", "qlora_workspace_bytes",
            "qlora_packed_zero_words", "qlora_pack_zeros", "qlora_unpack_zeros",
            "qlora_linear_fwd", "qlora_linear_bwd", "qlora_linear_bwd_accumulate", "qlora_linear_fwd_dropout",
            "qlora_linear_bwd_dropout", "qlora_linear_bwd_stacked", "qlora_siblings_workspace_bytes", "qlora_linear_fwd_siblings",
-           "qlora_linear_bwd_siblings", "qlora_lrec_workspace_bytes", "qlora_lrec_loss", "qlora_profile_gemm"]
+           "qlora_linear_bwd_siblings", "qlora_lrec_workspace_bytes", "qlora_lrec_loss", "qlora_profile_gemm",
+           "qlora_profile_gemm_span"]
 MAX_SIBLINGS, SIBLINGS_MAX_M = 4, 16
 
 _lib = None
@@ -75,6 +76,8 @@ def load() -> ctypes.CDLL:
     lib.qlora_linear_bwd.argtypes = [vp] * 11 + [c_int] * 6 + [f32, c_int, vp, c_sz, vp]
     lib.qlora_profile_gemm.restype = c_int
     lib.qlora_profile_gemm.argtypes = [vp, vp]
+    lib.qlora_profile_gemm_span.restype = c_int
+    lib.qlora_profile_gemm_span.argtypes = [c_int]
     lib.qlora_linear_bwd_accumulate.restype = c_int
     lib.qlora_linear_bwd_accumulate.argtypes = [vp] * 11 + [f32] + [c_int] * 6 + [f32, c_int, vp, c_sz, vp]
     lib.qlora_linear_fwd_dropout.restype = c_int
@@ -136,6 +139,11 @@ def qlora_workspace_bytes(M: int, N: int, K: int, bits: int, group_size: int, ra
 def qlora_profile_gemm(ev_before: Optional[int], ev_after: Optional[int]) -> int:
     """Set (or clear with None, None) the raw hipEvent_t handles recorded around the GEMM kernel."""
     return int(load().qlora_profile_gemm(ev_before, ev_after))
+
+
+def qlora_profile_gemm_span(span: int) -> int:
+    """0: the events enclose the GEMM alone; 1: the adapter kernel before it and the GEMM; 2: that kernel alone."""
+    return int(load().qlora_profile_gemm_span(span))
 
 
 def qlora_pack(codes, packed, N: int, K: int, bits: int, stream=None, check: bool = True) -> int:

@@ -77,16 +77,28 @@ Workspace carve(int M, int N, int K, int r, int bits)
 }
 
 hipEvent_t g_ev_before = nullptr, g_ev_after = nullptr;   // benchmark instrumentation, see qlora_profile_gemm
+int g_ev_span = 0;      // 0: events around the GEMM; 1: around the adapter kernel before it and the GEMM; 2: that kernel alone
+
+// Tiled passes: called before the adapter kernel that precedes the GEMM (t in the forward pass, u in the backward
+// pass) and between the two; the end of the GEMM is marked by GemmTimer.
+inline void mark_pre_begin(hipStream_t s)
+{
+    if (g_ev_before && g_ev_span != 0) (void)hipEventRecord(g_ev_before, s);
+}
+inline void mark_pre_end(hipStream_t s)
+{
+    if (g_ev_after && g_ev_span == 2) (void)hipEventRecord(g_ev_after, s);
+}
 
 struct GemmTimer {   // records the two events around the scope when instrumentation is on
     hipStream_t s;
     explicit GemmTimer(hipStream_t st) : s(st)
     {
-        if (g_ev_before) (void)hipEventRecord(g_ev_before, s);
+        if (g_ev_before && g_ev_span == 0) (void)hipEventRecord(g_ev_before, s);
     }
     ~GemmTimer()
     {
-        if (g_ev_after) (void)hipEventRecord(g_ev_after, s);
+        if (g_ev_after && g_ev_span != 2) (void)hipEventRecord(g_ev_after, s);
     }
 };
 
@@ -121,6 +133,12 @@ int qlora_profile_gemm(void *ev_before, void *ev_after)
 {
     g_ev_before = (hipEvent_t)ev_before;
     g_ev_after = (hipEvent_t)ev_after;
+    return QLORA_OK;
+}
+
+int qlora_profile_gemm_span(int span)
+{
+    g_ev_span = span == 1 || span == 2 ? span : 0;
     return QLORA_OK;
 }
 
@@ -260,10 +278,12 @@ int qlora_linear_fwd_dropout(const void *x, const uint32_t *packed, const void *
         launch_fwd_small(p, 1, x, &packed, &scales, &zeros, &A, &B, &tc, &t, &y, &N, t_first, s);
     } else {
         void *t = nullptr;
+        mark_pre_begin(s);
         if (rank > 0) {
             t = t_save ? t_save : (void *)(ws + w.t_off);
             launch_lora_down(x, A, t, M, K, rank, p.bf16, keep_mask, keep_scale, s);
         }
+        mark_pre_end(s);
         GemmTimer timer(s);
         launch_fwd_mfma(p, x, packed, scales, zeros, t, B, y, (float *)(ws + w.split_off), s);
     }
@@ -325,10 +345,12 @@ static int backward(const void *dy, const void *x, const uint32_t *packed, const
         return hip_status();
     }
     void *u = nullptr;
+    mark_pre_begin(s);
     if (rank > 0) {
         u = ws + w.u_off;
         launch_lora_u(dy, B, ws + w.bt_off, u, M, N, rank, p.bf16, s);
     }
+    mark_pre_end(s);
     {
         GemmTimer timer(s);
         if (keep_mask && rank > GEMM_MASKED_MAX_RANK) {
