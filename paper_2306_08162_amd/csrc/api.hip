@@ -92,13 +92,14 @@ inline void mark_pre_end(hipStream_t s)
 
 struct GemmTimer {   // records the two events around the scope when instrumentation is on
     hipStream_t s;
-    explicit GemmTimer(hipStream_t st) : s(st)
+    int span;           // the spans other than 0 exist in the tiled passes only
+    explicit GemmTimer(hipStream_t st, bool tiled = false) : s(st), span(tiled ? g_ev_span : 0)
     {
-        if (g_ev_before && g_ev_span == 0) (void)hipEventRecord(g_ev_before, s);
+        if (g_ev_before && span == 0) (void)hipEventRecord(g_ev_before, s);
     }
     ~GemmTimer()
     {
-        if (g_ev_after && g_ev_span != 2) (void)hipEventRecord(g_ev_after, s);
+        if (g_ev_after && span != 2) (void)hipEventRecord(g_ev_after, s);
     }
 };
 
@@ -284,7 +285,7 @@ int qlora_linear_fwd_dropout(const void *x, const uint32_t *packed, const void *
             launch_lora_down(x, A, t, M, K, rank, p.bf16, keep_mask, keep_scale, s);
         }
         mark_pre_end(s);
-        GemmTimer timer(s);
+        GemmTimer timer(s, true);
         launch_fwd_mfma(p, x, packed, scales, zeros, t, B, y, (float *)(ws + w.split_off), s);
     }
     return hip_status();
@@ -352,7 +353,7 @@ static int backward(const void *dy, const void *x, const uint32_t *packed, const
     }
     mark_pre_end(s);
     {
-        GemmTimer timer(s);
+        GemmTimer timer(s, true);
         if (keep_mask && rank > GEMM_MASKED_MAX_RANK) {
             // the GEMM leaves the base product; the adapter's masked share is added afterwards
             Problem base = p;
