@@ -244,3 +244,37 @@ def test_backward_accumulates_into_adapter_gradients(M):
     layer.backward_accumulate(0.0)
     torch.cuda.synchronize()
     assert np.array_equal(layer.host_dA(), dA1) and np.array_equal(layer.host_dB(), dB1)
+
+
+def test_benchmark_event_spans_leave_results_alone():
+    """The instrumentation events can enclose the GEMM, the adapter kernel before it plus the GEMM, or that kernel
+    alone; every choice records both events and none changes what the passes compute."""
+    import torch
+    from paper_2306_08162_amd import binding as ql
+    from paper_2306_08162_amd.device import DeviceLayer
+    from paper_2306_08162_amd.hiprt import Event
+    layer = DeviceLayer(small_inputs(77, 300, 512, 264, 4, 128, 8, "f16"))
+    layer.forward()
+    layer.backward()
+    torch.cuda.synchronize()
+    want = [layer.host_y().copy(), layer.host_dx().copy(), layer.host_dA().copy(), layer.host_dB().copy()]
+    ms = {}
+    try:
+        for span in (0, 1, 2):
+            ev = [Event() for _ in range(4)]
+            ql.qlora_profile_gemm_span(span)
+            ql.qlora_profile_gemm(ev[0].handle, ev[1].handle)
+            layer.forward()
+            ql.qlora_profile_gemm(ev[2].handle, ev[3].handle)
+            layer.backward()
+            torch.cuda.synchronize()
+            ms[span] = (ev[0].elapsed_ms(ev[1]), ev[2].elapsed_ms(ev[3]))
+            for a, b in zip(want, [layer.host_y(), layer.host_dx(), layer.host_dA(), layer.host_dB()]):
+                assert np.array_equal(a, b)
+    finally:
+        ql.qlora_profile_gemm(None, None)
+        ql.qlora_profile_gemm_span(0)
+    announce(f"event spans (fwd, bwd) ms: {ms}")
+    for span in (0, 1, 2):
+        assert ms[span][0] > 0 and ms[span][1] > 0
+    assert ms[1][0] > ms[2][0] and ms[1][1] > ms[2][1]      # adapter kernel + GEMM takes longer than the adapter kernel
