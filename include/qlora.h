@@ -28,16 +28,19 @@
  *
  * Every pointer is a DEVICE pointer (HIP, current device) unless stated
  * otherwise; the caller owns all buffers; the library allocates nothing and
- * keeps no state between calls (apart from the benchmark hook at the end).  Base pointers must be 16-byte aligned.
+ * keeps no state between calls: the entry points are re-entrant and may be
+ * called from several host threads.  Base pointers must be 16-byte aligned.
  * `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls
  * enqueue work on `stream` and return without synchronising.
  *
  * Errors: every function returning int returns a qlora_status_t.  Arguments
  * are validated on the host before anything is launched, so a status other
- * than QLORA_OK / QLORA_E_HIP means no device memory was written.
+ * than QLORA_OK / QLORA_E_HIP means no device memory was written.  QLORA_E_HIP
+ * reports the first failure among this call's own launches (an error some
+ * earlier, unrelated HIP call left behind in the runtime is discarded first).
  *
  * Accepted domain: bits in {2,3,4,8}; K % 32 == 0, K <= 2^20; N <= 2^24;
- * M*K and M*N below 2^31 elements; group_size % 32 == 0 and
+ * N*K below 2^32 codes; M*K and M*N below 2^31 elements; group_size % 32 == 0 and
  * K % group_size == 0 (group_size == K is per-row quantisation); N % 8 == 0;
  * rank in {0, 8, 16, ..., 64}; M >= 1; dtype f16 or bf16.  rank == 0 means the
  * projection carries no adapter: A, B, t, dA, dB are ignored (may be NULL).
@@ -278,23 +281,16 @@ int qlora_lrec_loss(const void *student_logits, const void *teacher_logits, cons
                     int M, int V, int dtype, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
- * Instrumentation for benchmarks (not part of the layer, not thread-safe): while a pair of hipEvent_t
- * handles is set, every qlora_linear_fwd / qlora_linear_bwd call records ev_before on its stream right
- * before its GEMM kernel (the fused dequantise + MFMA kernel that dominates the pass) and ev_after right
- * after it, so a caller can time that kernel alone inside a whole-pass timed region.  Pass NULL, NULL to
- * clear.  Host pointers (event handles).  Always returns QLORA_OK.
+ * The same with loss scaling: dlogits = grad_scale * d loss_mean / d student_logits (kl, ce and loss_mean are not
+ * scaled).  The mean over M tokens puts a factor 1/M on every gradient entry: at the LREC setting of Appendix C
+ * (2048-token sequences, 32000 logits) most entries of an fp16 gradient would be subnormal or flush to zero;
+ * a power-of-two grad_scale (undone by the caller after the backward pass, in fp32) keeps them representable.
+ * grad_scale == 1 is qlora_lrec_loss.
  */
-int qlora_profile_gemm(void *ev_before, void *ev_after);
-
-/*
- * Which stretch of a tiled pass (more than 64 token rows forward, more than 16 backward) the two events of
- * qlora_profile_gemm enclose.  0 (default): the GEMM kernel alone.  1: the adapter kernel launched before it
- * (t = x A^T forward, u = dY B backward) and the GEMM.  2: that adapter kernel alone.  An event pair around one
- * kernel also measures the latency of dispatching it behind an event; the difference of spans 1 and 2 does not
- * (the GEMM then follows a kernel, as it does in an untimed pass), which is how bench.py prices the kernel.
- * Other values count as 0.  Always returns QLORA_OK.
- */
-int qlora_profile_gemm_span(int span);
+int qlora_lrec_loss_scaled(const void *student_logits, const void *teacher_logits, const int32_t *labels,
+                           float lambda_kl, float lambda_ce, float grad_scale, float *kl, float *ce,
+                           float *loss_mean, void *dlogits, int M, int V, int dtype,
+                           void *workspace, size_t workspace_bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -1,0 +1,36 @@
+/*
+ * qlora_bench.h -- timing instrumentation for benchmarks of libqlora.so.  Not part of the layer's interface
+ * (qlora.h): nothing here changes what a layer call computes, and a program that never calls these functions
+ * pays one thread-local read per layer call.
+ *
+ * The state is per host thread: events set by a thread are recorded by the qlora_linear_fwd / qlora_linear_bwd
+ * calls that the same thread makes, and by no other thread's calls, so the layer entry points stay re-entrant.
+ */
+#ifndef QLORA_BENCH_H
+#define QLORA_BENCH_H
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/*
+ * While a pair of hipEvent_t handles is set, every qlora_linear_fwd / qlora_linear_bwd call of this thread records
+ * ev_before on its stream right before its GEMM kernel (the fused dequantise + MFMA kernel that dominates the pass)
+ * and ev_after right after it, so a caller can time that kernel alone inside a whole-pass timed region.  Pass NULL,
+ * NULL to clear.  Host pointers (event handles).  Always returns 0 (QLORA_OK).
+ */
+int qlora_profile_gemm(void *ev_before, void *ev_after);
+
+/*
+ * Which stretch of a tiled pass (more than 64 token rows forward, more than 16 backward) the two events of
+ * qlora_profile_gemm enclose.  0 (default): the GEMM kernel alone.  1: the adapter kernel launched before it
+ * (t = x A^T forward, u = dY B backward) and the GEMM.  2: that adapter kernel alone.  An event pair around one
+ * kernel also measures the latency of dispatching it behind an event; the difference of spans 1 and 2 does not
+ * (the GEMM then follows a kernel, as it does in an untimed pass).  Other values count as 0.  Always returns 0.
+ */
+int qlora_profile_gemm_span(int span);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QLORA_BENCH_H */

@@ -12,7 +12,7 @@ import os
 from typing import Optional
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.environ.get("QLORA_LIB", os.path.join(HERE, "libqlora.so"))   # QLORA_LIB: a variant built for tuning
+LIB_PATH = os.path.join(HERE, "libqlora.so")
 
 QLORA_F16, QLORA_BF16 = 0, 1
 STATUS_NAMES = ["QLORA_OK", "QLORA_E_NULL", "QLORA_E_BITS", "QLORA_E_SHAPE", "QLORA_E_GROUP", "QLORA_E_RANK",
@@ -22,8 +22,8 @@ EXPORTS = ["qlora_status_string", "qlora_packed_words", "qlora_workspace_bytes",
            "qlora_packed_zero_words", "qlora_pack_zeros", "qlora_unpack_zeros",
            "qlora_linear_fwd", "qlora_linear_bwd", "qlora_linear_bwd_accumulate", "qlora_linear_fwd_dropout",
            "qlora_linear_bwd_dropout", "qlora_linear_bwd_stacked", "qlora_siblings_workspace_bytes", "qlora_linear_fwd_siblings",
-           "qlora_linear_bwd_siblings", "qlora_lrec_workspace_bytes", "qlora_lrec_loss", "qlora_profile_gemm",
-           "qlora_profile_gemm_span"]
+           "qlora_linear_bwd_siblings", "qlora_lrec_workspace_bytes", "qlora_lrec_loss", "qlora_lrec_loss_scaled"]
+BENCH_EXPORTS = ["qlora_profile_gemm", "qlora_profile_gemm_span"]        # include/qlora_bench.h
 MAX_SIBLINGS, SIBLINGS_MAX_M = 4, 16
 
 _lib = None
@@ -96,6 +96,8 @@ def load() -> ctypes.CDLL:
     lib.qlora_lrec_workspace_bytes.argtypes = [c_int]
     lib.qlora_lrec_loss.restype = c_int
     lib.qlora_lrec_loss.argtypes = [vp] * 3 + [f32, f32] + [vp] * 4 + [c_int] * 3 + [vp, c_sz, vp]
+    lib.qlora_lrec_loss_scaled.restype = c_int
+    lib.qlora_lrec_loss_scaled.argtypes = [vp] * 3 + [f32, f32, f32] + [vp] * 4 + [c_int] * 3 + [vp, c_sz, vp]
     _lib = lib
     return lib
 
@@ -306,6 +308,19 @@ def qlora_lrec_loss(student_logits, teacher_logits, labels, lambda_kl: float, la
                                 _ptr(workspace), workspace_bytes, _stream(stream))
     if check and st != 0:
         raise QLoraError(st, "qlora_lrec_loss")
+    return st
+
+
+def qlora_lrec_loss_scaled(student_logits, teacher_logits, labels, lambda_kl: float, lambda_ce: float,
+                           grad_scale: float, kl, ce, loss_mean, dlogits, M: int, V: int, dtype: int, workspace,
+                           workspace_bytes: Optional[int] = None, stream=None, check: bool = True) -> int:
+    if workspace_bytes is None:
+        workspace_bytes = _nbytes(workspace)
+    st = load().qlora_lrec_loss_scaled(_ptr(student_logits), _ptr(teacher_logits), _ptr(labels), float(lambda_kl),
+                                       float(lambda_ce), float(grad_scale), _ptr(kl), _ptr(ce), _ptr(loss_mean),
+                                       _ptr(dlogits), M, V, dtype, _ptr(workspace), workspace_bytes, _stream(stream))
+    if check and st != 0:
+        raise QLoraError(st, "qlora_lrec_loss_scaled")
     return st
 
 

@@ -36,85 +36,14 @@ __device__ __forceinline__ u16x8_t keep_halves(u16x8_t v, uint32_t keep_byte)
 // ------------------------------------------------------------------------------------------------------------
 // out[M,r] = act[M,C] * small[r,C]^T        (t = x A^T with small = A;  u = dY B with small = B^T)
 //
-// First form, kept for byte offsets beyond 32 bits: a workgroup of 8 waves owns
-// 8 or 16 token rows; the waves split the contraction into 32-wide chunks (wave w takes chunks w, w+8, ...) and
-// feed them straight from global memory into the MFMA: both operands are contiguous along the contraction, so a
-// lane's fragment is one 16-byte load.  Partial 16 x r tiles meet in LDS.  Every other call takes
-// skinny_rows_staged_kernel below.
+// A workgroup of 8 waves owns 8 or 16 token rows (SK_ROWS: the MFMA block has 16; with 8 the upper half of the block
+// stays zero and there are twice as many workgroups, which pays while 16-row workgroups would not fill the chip:
+// 1.2 us per launch at 2048 x 4096).  Byte offsets of the loads are 32-bit: the entry points accept at most 2^31
+// elements per activation matrix.
 // ------------------------------------------------------------------------------------------------------------
 constexpr int SK_WAVES = 8;
-constexpr int SK_UNROLL = 16;
 
-// MASKED: act is x under LoRA dropout: out = keep_scale * (x * keep) small^T, keep one byte per fragment [M, C/8]
-// SK_ROWS token rows per workgroup: the MFMA block has 16; with 8 the upper half of the block stays zero and there are
-// twice as many workgroups, which pays while 16-row workgroups would not fill the chip (measured: 1.2 us per launch
-// at 2048 x 4096)
-template <bool BF16, int RG, bool MASKED, int SK_ROWS>   // RG = ceil(r / 16)
-__global__ __launch_bounds__(SK_WAVES * 64) void skinny_rows_kernel(const uint16_t *__restrict__ act,
-                                                                   const uint16_t *__restrict__ small,
-                                                                   uint16_t *__restrict__ out, int M, int C, int r,
-                                                                   const uint8_t *__restrict__ keep, float keep_scale)
-{
-    __shared__ float red[SK_WAVES][RG][16][17];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int m0 = blockIdx.x * SK_ROWS;
-    const int li = lane & 15, q = lane >> 4;
-    const bool rowin = li < SK_ROWS;
-    const uint16_t *arow = act + (long)min(m0 + li, M - 1) * C + q * 8;
-    const uint8_t *krow = MASKED ? keep + (long)min(m0 + li, M - 1) * (C / 8) + q : nullptr;
-    const uint16_t *srow[RG];
-    bool sval[RG];
-#pragma unroll
-    for (int g = 0; g < RG; ++g) {
-        sval[g] = g * 16 + li < r;
-        srow[g] = small + (long)min(g * 16 + li, r - 1) * C + q * 8;
-    }
-    float4_t acc[RG];
-#pragma unroll
-    for (int g = 0; g < RG; ++g) acc[g] = float4_t{0.f, 0.f, 0.f, 0.f};
-
-    const int chunks = (C + 31) / 32;   // C % 8 == 0: a chunk may be ragged in whole 8-element pieces
-    constexpr int UNROLL = RG == 1 ? SK_UNROLL : SK_UNROLL / 2;   // registers: two workgroups per CU at every rank
-    for (int c0 = wave; c0 < chunks; c0 += SK_WAVES * UNROLL) {
-        u16x8_t xa[UNROLL], sb[UNROLL][RG];
-#pragma unroll
-        for (int uu = 0; uu < UNROLL; ++uu) {
-            const int k = (c0 + uu * SK_WAVES) * 32;
-            const bool in = k + q * 8 < C;
-            const int kk = in ? k : 0;
-            xa[uu] = u16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
-            if (in && rowin) {
-                xa[uu] = *(const u16x8_t *)(arow + kk);
-                if constexpr (MASKED) xa[uu] = keep_halves(xa[uu], krow[(kk >> 3)]);
-            }
-#pragma unroll
-            for (int g = 0; g < RG; ++g) {
-                sb[uu][g] = *(const u16x8_t *)(srow[g] + kk);
-                if (!sval[g]) sb[uu][g] = u16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
-            }
-        }
-#pragma unroll
-        for (int uu = 0; uu < UNROLL; ++uu)
-#pragma unroll
-            for (int g = 0; g < RG; ++g) acc[g] = mfma16<BF16>(xa[uu], sb[uu][g], acc[g]);
-    }
-    // D[row = 4*q + v][col = li]
-#pragma unroll
-    for (int g = 0; g < RG; ++g)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) red[wave][g][4 * q + v][li] = acc[g][v];
-    __syncthreads();
-    for (int e = threadIdx.x; e < RG * 256; e += SK_WAVES * 64) {
-        const int g = e >> 8, row = (e >> 4) & 15, col = e & 15;
-        float s = 0.f;
-#pragma unroll
-        for (int w = 0; w < SK_WAVES; ++w) s += red[w][g][row][col];
-        if constexpr (MASKED) s *= keep_scale;
-        if (row < SK_ROWS && m0 + row < M && g * 16 + col < r) out[(long)(m0 + row) * r + g * 16 + col] = to16<BF16>(s);
-    }
-}
-
-// The same product with both operands staged through LDS, the form every unmasked call takes: every wave walks
+// Both operands are staged through LDS: every wave walks
 // 64-column stretches of the contraction (wave w the stretches w, w + 8, ...) and pulls the stretch of its token rows
 // and of `small` into one of two private LDS buffers with direct-to-LDS loads, the next stretch in flight while this
 // one is multiplied; no workgroup barrier in the loop.  (Fragment loads straight from global memory are 16 bytes out
@@ -272,106 +201,18 @@ __global__ __launch_bounds__(SK_WAVES * 64) void skinny_rows_staged_kernel(const
     }
 }
 
-// ------------------------------------------------------------------------------------------------------------
-// partial[s][c][j] = sum over the token rows m of slice s of act[m,c] * side[m,j]
-//      (dB: act = dY, side = t;  dA: act = x, side = u)
-// Both gradients go out in one launch: column blocks [0, nb0) belong to the first problem, the rest to the second.
-//
-// The contraction runs over m, the strided index of both operands, so 32-row chunks of act (64 columns wide)
-// and of side are laid into LDS as they come and the MFMA fragments are gathered from there column-wise.
-// A workgroup owns 64 columns x one slice; every global load of the slice is issued before the first MFMA.
-// ------------------------------------------------------------------------------------------------------------
-constexpr int GR_COLS = 64;       // columns per workgroup (16 per wave)
-constexpr int grad_rows(int rg) { return rg <= 2 ? 256 : 128; }   // token rows per slice (LDS budget: 64 KB)
-constexpr int GR_PITCH = GR_COLS + 2;   // halfs; odd dword pitch keeps the column gathers off the same banks
-
+// Arguments of the adapter-gradient launch: dB (problem 0: act = dY, side = t) and dA (problem 1: act = x, side = u).
 struct GradArgs {
     const uint16_t *act[2], *side[2];
-    float *partial[2];      // [slices][C][r] each
     float *out[2];          // dB [C0, r] and dA [r, C1]
     int C[2];
     int nb0;                // column blocks of the first problem
-    int M, r, slices;       // r: adapter columns the gradients are formed for
+    int M, r;               // r: adapter columns the gradients are formed for
     int side_pitch, side_c0;   // side is [M, side_pitch]; its columns side_c0 .. side_c0 + r are used (stacked adapters:
                                // the leading side_c0 columns belong to a frozen pair)
     float sc[2], beta;      // out = beta * out + sc * sum (beta == 0: out is not read)
     const uint8_t *keep;    // LoRA dropout: keep bits of x (the second problem's act), [M, C1/8] bytes, or NULL
 };
-
-template <bool BF16, int RG, bool MASKED>   // MASKED: a.keep != NULL (kept out of the load loop as a template argument)
-__global__ __launch_bounds__(256) void adapter_grad_partial_kernel(const GradArgs a)
-{
-    constexpr int GR_ROWS = grad_rows(RG), GR_CHUNKS = GR_ROWS / 32;
-    const int which = (int)blockIdx.x >= a.nb0 ? 1 : 0;
-    const uint16_t *__restrict__ act = a.act[which];
-    const uint16_t *__restrict__ side = a.side[which];
-    float *__restrict__ partial = a.partial[which];
-    const int M = a.M, C = a.C[which], r = a.r;
-    __shared__ uint16_t As[GR_ROWS * GR_PITCH];
-    constexpr int SP = RG * 16 + 2;         // side pitch in halfs, odd dword pitch as well
-    __shared__ uint16_t Ss[GR_ROWS * SP];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int c0 = ((int)blockIdx.x - (which ? a.nb0 : 0)) * GR_COLS, slice = blockIdx.y, m0 = slice * GR_ROWS;
-
-    // global -> LDS: act rows are 128 bytes wide here (8 lanes x 16 B); rows past M or columns past C become zero
-    {
-        const int rr = tid >> 3, cc = (tid & 7) * 8;
-        u16x8_t v[GR_CHUNKS];
-#pragma unroll
-        for (int ch = 0; ch < GR_CHUNKS; ++ch) {
-            const int m = m0 + ch * 32 + rr;
-            const bool in = m < M && c0 + cc < C;
-            v[ch] = *(const u16x8_t *)(act + (in ? (long)m * C + c0 + cc : 0));
-            if (MASKED && which) v[ch] = keep_halves(v[ch], a.keep[in ? (long)m * (C / 8) + ((c0 + cc) >> 3) : 0]);
-            if (!in) v[ch] = u16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
-        }
-#pragma unroll
-        for (int ch = 0; ch < GR_CHUNKS; ++ch) {
-            uint32_t *dst = (uint32_t *)(As + (ch * 32 + rr) * GR_PITCH + cc);   // 4-byte aligned: pitch and cc even
-            const u32x4_t w = __builtin_bit_cast(u32x4_t, v[ch]);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) dst[e] = w[e];
-        }
-        for (int e = tid; e < GR_ROWS * RG * 2; e += 256) {     // side rows, padded to RG*16 columns, 8 at a time
-            const int row = e / (RG * 2), j = (e % (RG * 2)) * 8;
-            const bool in = m0 + row < M && j < r;
-            u16x8_t sv = *(const u16x8_t *)(side + (in ? (long)(m0 + row) * a.side_pitch + a.side_c0 + j : 0));
-            if (!in) sv = u16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
-            uint32_t *sd = (uint32_t *)(Ss + row * SP + j);
-            const u32x4_t sw = __builtin_bit_cast(u32x4_t, sv);
-#pragma unroll
-            for (int k = 0; k < 4; ++k) sd[k] = sw[k];
-        }
-    }
-    __syncthreads();
-
-    const int li = lane & 15, q = lane >> 4;
-    float4_t acc[RG];
-#pragma unroll
-    for (int g = 0; g < RG; ++g) acc[g] = float4_t{0.f, 0.f, 0.f, 0.f};
-#pragma unroll 2
-    for (int ch = 0; ch < GR_CHUNKS; ++ch) {
-        const int mb = ch * 32 + q * 8;
-        u16x8_t fb;       // act^T fragment: column c = 16*wave + li, rows mb .. mb+7
-#pragma unroll
-        for (int e = 0; e < 8; ++e) fb[e] = As[(mb + e) * GR_PITCH + wave * 16 + li];
-#pragma unroll
-        for (int g = 0; g < RG; ++g) {
-            u16x8_t fa;   // side^T fragment: column j = 16*g + li
-#pragma unroll
-            for (int e = 0; e < 8; ++e) fa[e] = Ss[(mb + e) * SP + g * 16 + li];
-            acc[g] = mfma16<BF16>(fa, fb, acc[g]);      // D[j = 4*q + v][c = li]
-        }
-    }
-    const int c = c0 + wave * 16 + li;
-    if (c < C) {
-#pragma unroll
-        for (int g = 0; g < RG; ++g) {
-            const int j = g * 16 + 4 * q;
-            if (j < r) *(float4_t *)(partial + ((long)slice * C + c) * r + j) = acc[g];   // r % 8 == 0: j..j+3 < r
-        }
-    }
-}
 
 // ------------------------------------------------------------------------------------------------------------
 // dB and dA in one pass, without slice partial sums (ranks <= 16, no dropout mask): a workgroup owns 32 columns of
@@ -541,7 +382,7 @@ void launch_grad_onepass_masked(const GradArgs &a, int blocks, hipStream_t s)
     constexpr int lds = go_lds_bytes(R);
     auto kern = adapter_grad_onepass_kernel<BF16, R, MASKED>;
     ensure_dynamic_lds((const void *)kern, (int)(lds));
-    hipLaunchKernelGGL(kern, dim3(blocks), dim3(GO_WAVES * 64), lds, s, a);
+    QLORA_LAUNCH(kern, dim3(blocks), dim3(GO_WAVES * 64), lds, s, a);
 }
 
 template <bool BF16, int R>
@@ -549,31 +390,6 @@ void launch_grad_onepass(const GradArgs &a, int blocks, hipStream_t s)
 {
     if (a.keep) launch_grad_onepass_masked<BF16, R, true>(a, blocks, s);
     else launch_grad_onepass_masked<BF16, R, false>(a, blocks, s);
-}
-
-// out = sc * sum over slices (in slice order) of partial, both problems in one launch: the first C0*r threads
-// write dB as [C0, r], the next C1*r threads dA as [r, C1].
-__global__ __launch_bounds__(256) void adapter_grad_reduce_kernel(const GradArgs a)
-{
-    long idx = (long)blockIdx.x * 256 + threadIdx.x;
-    const long n0 = (long)a.C[0] * a.r;
-    const int which = idx >= n0 ? 1 : 0;
-    if (which) idx -= n0;
-    const int C = a.C[which], r = a.r;
-    const long stride = (long)C * r;
-    if (idx >= stride) return;
-    const float *__restrict__ partial = a.partial[which];
-    float acc = 0.f;
-    int s = 0;
-    for (; s + 4 <= a.slices; s += 4) {
-        const float a0 = partial[(s + 0) * stride + idx], a1 = partial[(s + 1) * stride + idx];
-        const float a2 = partial[(s + 2) * stride + idx], a3 = partial[(s + 3) * stride + idx];
-        acc = (((acc + a0) + a1) + a2) + a3;
-    }
-    for (; s < a.slices; ++s) acc += partial[s * stride + idx];
-    const int c = (int)(idx / r), j = (int)(idx % r);
-    float *dst = a.out[which] + (which ? (long)j * C + c : idx);
-    *dst = a.beta == 0.f ? a.sc[which] * acc : fmaf(a.beta, *dst, a.sc[which] * acc);
 }
 
 template <bool BF16, int RG, int SK_ROWS, bool NATURAL, bool MASKED>
@@ -585,7 +401,7 @@ void launch_skinny_staged(const uint16_t *act, const uint16_t *small, uint16_t *
     constexpr int lds = pipe > sum ? pipe : sum;
     auto kern = skinny_rows_staged_kernel<BF16, RG, SK_ROWS, NATURAL, MASKED>;
     ensure_dynamic_lds((const void *)kern, (int)(lds));
-    hipLaunchKernelGGL(kern, dim3((M + SK_ROWS - 1) / SK_ROWS), dim3(SK_WAVES * 64), lds, s, act, small, out, M, C, r, keep,
+    QLORA_LAUNCH(kern, dim3((M + SK_ROWS - 1) / SK_ROWS), dim3(SK_WAVES * 64), lds, s, act, small, out, M, C, r, keep,
                        keep_scale);
 }
 
@@ -597,28 +413,10 @@ void launch_skinny_staged_rank(const uint16_t *act, const uint16_t *small, uint1
     case 1: launch_skinny_staged<BF16, 1, SK_ROWS, NATURAL, MASKED>(act, small, out, M, C, r, keep, keep_scale, s); break;
     case 2: launch_skinny_staged<BF16, 2, SK_ROWS, NATURAL, MASKED>(act, small, out, M, C, r, keep, keep_scale, s); break;
     case 3: launch_skinny_staged<BF16, 3, SK_ROWS, NATURAL, MASKED>(act, small, out, M, C, r, keep, keep_scale, s); break;
-    default:    // (masked, 16 rows, four rank groups do not fit the LDS: the caller keeps that case away)
+    default:    // (masked, 16 rows, four rank groups do not fit the LDS: launch_skinny keeps that case away)
         if constexpr (!(MASKED && SK_ROWS == 16))
             launch_skinny_staged<BF16, 4, SK_ROWS, NATURAL, MASKED>(act, small, out, M, C, r, keep, keep_scale, s);
         break;
-    }
-}
-
-template <bool BF16, bool MASKED, int SK_ROWS>
-void launch_skinny_rows(const uint16_t *act, const uint16_t *small, uint16_t *out, int M, int C, int r,
-                        const uint8_t *keep, float keep_scale, hipStream_t s)
-{
-    // staged: byte offsets of the loads in 32 bits; masked, 16 rows and ranks above 48 together exceed the LDS
-    if ((long)M * C * 2 < (1L << 32) && (long)r * C * 2 < (1L << 32) && !(MASKED && SK_ROWS == 16 && r > 48)) {
-        launch_skinny_staged_rank<BF16, SK_ROWS, false, MASKED>(act, small, out, M, C, r, keep, keep_scale, s);
-        return;
-    }
-    const dim3 grid((M + SK_ROWS - 1) / SK_ROWS), block(SK_WAVES * 64);
-    switch ((r + 15) / 16) {
-    case 1: hipLaunchKernelGGL((skinny_rows_kernel<BF16, 1, MASKED, SK_ROWS>), grid, block, 0, s, act, small, out, M, C, r, keep, keep_scale); break;
-    case 2: hipLaunchKernelGGL((skinny_rows_kernel<BF16, 2, MASKED, SK_ROWS>), grid, block, 0, s, act, small, out, M, C, r, keep, keep_scale); break;
-    case 3: hipLaunchKernelGGL((skinny_rows_kernel<BF16, 3, MASKED, SK_ROWS>), grid, block, 0, s, act, small, out, M, C, r, keep, keep_scale); break;
-    default: hipLaunchKernelGGL((skinny_rows_kernel<BF16, 4, MASKED, SK_ROWS>), grid, block, 0, s, act, small, out, M, C, r, keep, keep_scale); break;
     }
 }
 
@@ -626,26 +424,12 @@ template <bool BF16, bool MASKED>
 void launch_skinny(const uint16_t *act, const uint16_t *small, uint16_t *out, int M, int C, int r, const uint8_t *keep,
                    float keep_scale, hipStream_t s)
 {
-    if (M >= 16 * 256) launch_skinny_rows<BF16, MASKED, 16>(act, small, out, M, C, r, keep, keep_scale, s);
-    else launch_skinny_rows<BF16, MASKED, 8>(act, small, out, M, C, r, keep, keep_scale, s);
-}
-
-template <bool BF16>
-void launch_grad_partial(const GradArgs &a, hipStream_t s)
-{
-    const int nb1 = (a.C[1] + GR_COLS - 1) / GR_COLS;
-    const dim3 grid(a.nb0 + nb1, a.slices), block(256);
-#define QLORA_GRAD_CASE(RG)                                                                                   \
-    if (a.keep) hipLaunchKernelGGL((adapter_grad_partial_kernel<BF16, RG, true>), grid, block, 0, s, a);        \
-    else hipLaunchKernelGGL((adapter_grad_partial_kernel<BF16, RG, false>), grid, block, 0, s, a);              \
-    break
-    switch ((a.r + 15) / 16) {
-    case 1: QLORA_GRAD_CASE(1);
-    case 2: QLORA_GRAD_CASE(2);
-    case 3: QLORA_GRAD_CASE(3);
-    default: QLORA_GRAD_CASE(4);
-    }
-#undef QLORA_GRAD_CASE
+    // 16 token rows per workgroup once that fills the chip; under a mask, 16 rows and ranks above 48 together exceed
+    // the LDS, so those keep 8-row workgroups
+    if (M >= 16 * 256 && !(MASKED && r > 48))
+        launch_skinny_staged_rank<BF16, 16, false, MASKED>(act, small, out, M, C, r, keep, keep_scale, s);
+    else
+        launch_skinny_staged_rank<BF16, 8, false, MASKED>(act, small, out, M, C, r, keep, keep_scale, s);
 }
 
 }  // namespace
@@ -665,34 +449,18 @@ void launch_lora_down(const void *x, const void *A, void *t, int M, int K, int r
     }
 }
 
-// bt[r,N] = b[N,r]^T, for the rare call whose byte offsets do not fit the staged kernel
-__global__ __launch_bounds__(256) void transpose_small_kernel(const uint16_t *__restrict__ b, uint16_t *__restrict__ bt,
-                                                              int N, int r)
-{
-    const long idx = (long)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= (long)N * r) return;
-    const int j = (int)(idx / N), n = (int)(idx % N);
-    bt[idx] = b[(long)n * r + j];
-}
-
-void launch_lora_u(const void *dy, const void *B, void *bt, void *u, int M, int N, int r, bool bf16, hipStream_t s)
+void launch_lora_u(const void *dy, const void *B, void *u, int M, int N, int r, bool bf16, hipStream_t s)
 {
     const uint16_t *a = (const uint16_t *)dy, *b = (const uint16_t *)B;
     uint16_t *o = (uint16_t *)u;
-    if ((long)M * N * 2 < (1L << 32) && (long)N * r * 2 < (1L << 32)) {     // B is read as it lies in memory
-        if (M >= 16 * 256) {
-            if (bf16) launch_skinny_staged_rank<true, 16, true, false>(a, b, o, M, N, r, nullptr, 1.f, s);
-            else launch_skinny_staged_rank<false, 16, true, false>(a, b, o, M, N, r, nullptr, 1.f, s);
-        } else {
-            if (bf16) launch_skinny_staged_rank<true, 8, true, false>(a, b, o, M, N, r, nullptr, 1.f, s);
-            else launch_skinny_staged_rank<false, 8, true, false>(a, b, o, M, N, r, nullptr, 1.f, s);
-        }
-        return;
+    // B is read as it lies in memory (the contraction index is its strided one: transposing LDS reads)
+    if (M >= 16 * 256) {
+        if (bf16) launch_skinny_staged_rank<true, 16, true, false>(a, b, o, M, N, r, nullptr, 1.f, s);
+        else launch_skinny_staged_rank<false, 16, true, false>(a, b, o, M, N, r, nullptr, 1.f, s);
+    } else {
+        if (bf16) launch_skinny_staged_rank<true, 8, true, false>(a, b, o, M, N, r, nullptr, 1.f, s);
+        else launch_skinny_staged_rank<false, 8, true, false>(a, b, o, M, N, r, nullptr, 1.f, s);
     }
-    const long n = (long)N * r;
-    hipLaunchKernelGGL(transpose_small_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, b, (uint16_t *)bt, N, r);
-    if (bf16) launch_skinny<true, false>(a, (const uint16_t *)bt, o, M, N, r, nullptr, 1.f, s);
-    else launch_skinny<false, false>(a, (const uint16_t *)bt, o, M, N, r, nullptr, 1.f, s);
 }
 
 // dX[m,k] += f[m,k] * sum_j u[m,j] A[j,k],  f = sc * keep_scale where the keep bit of (m,k) is set, else 0:
@@ -745,68 +513,49 @@ void launch_lora_dx_masked(void *dx, const void *u, const void *A, const uint32_
 {
     const dim3 grid((K + 255) / 256, (M + 63) / 64), block(256);
     if (bf16)
-        hipLaunchKernelGGL(lora_dx_masked_kernel<true>, grid, block, 0, s, (uint16_t *)dx, (const uint16_t *)u,
+        QLORA_LAUNCH(lora_dx_masked_kernel<true>, grid, block, 0, s, (uint16_t *)dx, (const uint16_t *)u,
                            (const uint16_t *)A, (const uint8_t *)keep, M, K, r, f);
     else
-        hipLaunchKernelGGL(lora_dx_masked_kernel<false>, grid, block, 0, s, (uint16_t *)dx, (const uint16_t *)u,
+        QLORA_LAUNCH(lora_dx_masked_kernel<false>, grid, block, 0, s, (uint16_t *)dx, (const uint16_t *)u,
                            (const uint16_t *)A, (const uint8_t *)keep, M, K, r, f);
 }
 
-int adapter_grad_slices(int M, int r)
-{
-    if (r <= 0) return 0;
-    const int rows = grad_rows((r + 15) / 16);
-    return (M + rows - 1) / rows;
-}
-
-void launch_adapter_grads(const void *dy, const void *t, const void *x, const void *u, float *dB, float *dA,
-                          float *partial, int M, int N, int K, int r_all, int frozen, float sc, float beta,
-                          const uint32_t *keep, float keep_scale, bool bf16, hipStream_t s)
+void launch_adapter_grads(const void *dy, const void *t, const void *x, const void *u, float *dB, float *dA, int M, int N,
+                          int K, int r_all, int frozen, float sc, float beta, const uint32_t *keep, float keep_scale,
+                          bool bf16, hipStream_t s)
 {
     const int r = r_all - frozen;
-    const int slices = adapter_grad_slices(M, r);
     GradArgs a;
     a.act[0] = (const uint16_t *)dy;
     a.side[0] = (const uint16_t *)t;
     a.act[1] = (const uint16_t *)x;
     a.side[1] = (const uint16_t *)u;
-    a.partial[0] = partial;
-    a.partial[1] = partial + (size_t)slices * N * r;
     a.out[0] = dB;
     a.out[1] = dA;
     a.C[0] = N;
     a.C[1] = K;
-    a.nb0 = (N + GR_COLS - 1) / GR_COLS;
+    a.nb0 = (N + GO_COLS - 1) / GO_COLS;
     a.M = M;
     a.r = r;
     a.side_pitch = r_all;
     a.side_c0 = frozen;
-    a.slices = slices;
     a.sc[0] = sc;
     a.sc[1] = keep ? sc * keep_scale : sc;
     a.beta = beta;
     a.keep = (const uint8_t *)keep;
-    // one pass, no partial sums: byte offsets of the staged loads in 32 bits (ranks 24, 40, 48 and 56 run in the next
-    // larger of the kernel's side widths 8, 16, 32, 64)
-    if ((long)M * N * 2 < (1L << 32) && (long)M * K * 2 < (1L << 32) && (long)M * r_all * 2 < (1L << 32)) {
-        a.nb0 = (N + GO_COLS - 1) / GO_COLS;
-        const int blocks = a.nb0 + (K + GO_COLS - 1) / GO_COLS;
+    // ranks 24, 40, 48 and 56 run in the next larger of the kernel's side widths 8, 16, 32, 64
+    const int blocks = a.nb0 + (K + GO_COLS - 1) / GO_COLS;
 #define QLORA_ONEPASS(R)                                       \
-    if (bf16) launch_grad_onepass<true, R>(a, blocks, s);      \
-    else launch_grad_onepass<false, R>(a, blocks, s);          \
-    return
-        if (r == 8) { QLORA_ONEPASS(8); }
-        if (r == 16) { QLORA_ONEPASS(16); }
-        if (r <= 32) { QLORA_ONEPASS(32); }
-        QLORA_ONEPASS(64);
+    do {                                                       \
+        if (bf16) launch_grad_onepass<true, R>(a, blocks, s);  \
+        else launch_grad_onepass<false, R>(a, blocks, s);      \
+        return;                                                \
+    } while (0)
+    if (r == 8) QLORA_ONEPASS(8);
+    if (r == 16) QLORA_ONEPASS(16);
+    if (r <= 32) QLORA_ONEPASS(32);
+    QLORA_ONEPASS(64);
 #undef QLORA_ONEPASS
-    }
-    if (bf16)
-        launch_grad_partial<true>(a, s);
-    else
-        launch_grad_partial<false>(a, s);
-    const long n = (long)(N + K) * r;
-    hipLaunchKernelGGL(adapter_grad_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, a);
 }
 
 }  // namespace qlora

@@ -1,6 +1,7 @@
 // C ABI of the library: argument validation, workspace carve-up, kernel selection.
 // Nothing here touches the device before every argument has been checked.
 #include "../../include/qlora.h"
+#include "../../include/qlora_bench.h"
 #include "kernels.hpp"
 
 #include <hip/hip_runtime.h>
@@ -22,6 +23,7 @@ int check_weight_shape(int N, int K, int bits)
     if (bits != 2 && bits != 3 && bits != 4 && bits != 8) return QLORA_E_BITS;
     if (N < 1 || K < 1 || K % 32 != 0 || N % 8 != 0) return QLORA_E_SHAPE;
     if (K > (1 << 20) || N > (1 << 24)) return QLORA_E_SHAPE;   // kernels index groups and rows in 32 bits
+    if ((long long)N * K >= (1ll << 32)) return QLORA_E_SHAPE;  // pack / unpack launch one thread per word / per code
     return QLORA_OK;
 }
 
@@ -46,7 +48,7 @@ int check_problem(int M, int N, int K, int bits, int G, int r, int dtype)
 }
 
 struct Workspace {
-    size_t t_off, u_off, bt_off, upartial_off, partial_off, split_off, total;
+    size_t t_off, u_off, upartial_off, partial_off, split_off, total;
 };
 
 Workspace carve(int M, int N, int K, int r, int bits)
@@ -57,17 +59,13 @@ Workspace carve(int M, int N, int K, int r, int bits)
     off += round_up((size_t)M * r * 2);
     w.u_off = off;
     off += round_up((size_t)M * r * 2);
-    w.bt_off = off;
-    off += round_up((size_t)N * r * 2);
     w.upartial_off = off;
-    off += round_up((size_t)gemv_bwd_slices(N, K, bits) * 1024 * sizeof(float));
     w.partial_off = off;
-    size_t pmax = (size_t)adapter_grad_slices(M, r) * ((size_t)N + K) * r * sizeof(float);   // dB and dA slices
-    if (M <= SMALL_M_BWD_MAX) {     // the small-M backward kernel sums row slices of dX through the same buffer
-        const size_t pg = (size_t)gemv_bwd_slices(N, K, bits) * M * K * sizeof(float);
-        pmax = pg > pmax ? pg : pmax;
+    if (M <= SMALL_M_BWD_MAX) {     // the weight-streaming backward kernel: per row slice, partial u and partial dX
+        off += round_up((size_t)gemv_bwd_slices(N, K, bits) * 1024 * sizeof(float));
+        w.partial_off = off;
+        off += round_up((size_t)gemv_bwd_slices(N, K, bits) * M * K * sizeof(float));
     }
-    off += round_up(pmax);
     w.split_off = off;              // fp32 planes of a GEMM whose contraction is split over workgroups
     const size_t sf = (size_t)gemm_splits(M, N, K), sb = (size_t)gemm_splits(M, K, N);
     const size_t pf = sf > 1 ? sf * M * N * sizeof(float) : 0, pb = sb > 1 ? sb * M * K * sizeof(float) : 0;
@@ -76,8 +74,9 @@ Workspace carve(int M, int N, int K, int r, int bits)
     return w;
 }
 
-hipEvent_t g_ev_before = nullptr, g_ev_after = nullptr;   // benchmark instrumentation, see qlora_profile_gemm
-int g_ev_span = 0;      // 0: events around the GEMM; 1: around the adapter kernel before it and the GEMM; 2: that kernel alone
+// benchmark instrumentation of the calling thread (include/qlora_bench.h); the layer's entry points only read it
+thread_local hipEvent_t g_ev_before = nullptr, g_ev_after = nullptr;
+thread_local int g_ev_span = 0;   // 0: events around the GEMM; 1: around the adapter kernel before it and the GEMM; 2: that kernel alone
 
 // Tiled passes: called before the adapter kernel that precedes the GEMM (t in the forward pass, u in the backward
 // pass) and between the two; the end of the GEMM is marked by GemmTimer.
@@ -103,10 +102,9 @@ struct GemmTimer {   // records the two events around the scope when instrumenta
     }
 };
 
-inline int hip_status()
-{
-    return hipGetLastError() == hipSuccess ? QLORA_OK : QLORA_E_HIP;
-}
+// Every entry point that launches: begin_call() after validation and before the first launch, end_call() to return.
+inline void begin_call() { launch_errors_clear(); }
+inline int end_call() { return launch_errors_seen() ? QLORA_E_HIP : QLORA_OK; }
 
 }  // namespace
 
@@ -161,8 +159,9 @@ int qlora_pack(const uint8_t *codes, uint32_t *packed, int N, int K, int bits, v
     if (st != QLORA_OK) return st;
     if (!codes || !packed) return QLORA_E_NULL;
     if (misaligned(codes) || misaligned(packed)) return QLORA_E_ALIGN;
+    begin_call();
     launch_pack(codes, packed, N, K, bits, (hipStream_t)stream);
-    return hip_status();
+    return end_call();
 }
 
 int qlora_unpack(const uint32_t *packed, uint8_t *codes, int N, int K, int bits, void *stream)
@@ -171,8 +170,9 @@ int qlora_unpack(const uint32_t *packed, uint8_t *codes, int N, int K, int bits,
     if (st != QLORA_OK) return st;
     if (!codes || !packed) return QLORA_E_NULL;
     if (misaligned(codes) || misaligned(packed)) return QLORA_E_ALIGN;
+    begin_call();
     launch_unpack(packed, codes, N, K, bits, (hipStream_t)stream);
-    return hip_status();
+    return end_call();
 }
 
 size_t qlora_packed_zero_words(int N, int groups, int bits)
@@ -186,8 +186,9 @@ int qlora_pack_zeros(const uint8_t *zeros, uint32_t *packed_zeros, int N, int gr
     const int st = check_zero_shape(N, groups, bits);
     if (st != QLORA_OK) return st;
     if (!zeros || !packed_zeros) return QLORA_E_NULL;
+    begin_call();
     launch_pack_zeros(zeros, packed_zeros, N, groups, bits, (hipStream_t)stream);
-    return hip_status();
+    return end_call();
 }
 
 int qlora_unpack_zeros(const uint32_t *packed_zeros, uint8_t *zeros, int N, int groups, int bits, void *stream)
@@ -195,8 +196,9 @@ int qlora_unpack_zeros(const uint32_t *packed_zeros, uint8_t *zeros, int N, int 
     const int st = check_zero_shape(N, groups, bits);
     if (st != QLORA_OK) return st;
     if (!zeros || !packed_zeros) return QLORA_E_NULL;
+    begin_call();
     launch_unpack_zeros(packed_zeros, zeros, N, groups, bits, (hipStream_t)stream);
-    return hip_status();
+    return end_call();
 }
 
 int qlora_actorder_perm(const int32_t *g_idx, int32_t *perm, int32_t *inv_perm, int K, int group_size)
@@ -229,8 +231,9 @@ int qlora_pack_permuted(const uint8_t *codes, const int32_t *perm, uint32_t *pac
     if (st != QLORA_OK) return st;
     if (!codes || !perm || !packed) return QLORA_E_NULL;
     if (misaligned(codes) || misaligned(packed)) return QLORA_E_ALIGN;
+    begin_call();
     launch_pack_permuted(codes, perm, packed, N, K, bits, (hipStream_t)stream);
-    return hip_status();
+    return end_call();
 }
 
 int qlora_gather_columns(const void *src, const int32_t *index, void *dst, int M, int K, void *stream)
@@ -238,8 +241,9 @@ int qlora_gather_columns(const void *src, const int32_t *index, void *dst, int M
     if (M < 1 || K < 32 || K % 32 != 0 || K > (1 << 20) || (long)M * K >= (1L << 31)) return QLORA_E_SHAPE;
     if (!src || !index || !dst) return QLORA_E_NULL;
     if (misaligned(src) || misaligned(dst)) return QLORA_E_ALIGN;
+    begin_call();
     launch_gather_columns(src, index, dst, M, K, (hipStream_t)stream);
-    return hip_status();
+    return end_call();
 }
 
 int qlora_linear_fwd(const void *x, const uint32_t *packed, const void *scales, const uint8_t *zeros, const void *A,
@@ -250,25 +254,24 @@ int qlora_linear_fwd(const void *x, const uint32_t *packed, const void *scales, 
                                     rank, alpha, dtype, workspace, workspace_bytes, stream);
 }
 
-int qlora_linear_fwd_dropout(const void *x, const uint32_t *packed, const void *scales, const uint8_t *zeros,
-                             const void *A, const void *B, const uint32_t *keep_mask, float keep_scale, void *y,
-                             void *t_save, int M, int N, int K, int bits, int group_size, int rank, float alpha,
-                             int dtype, void *workspace, size_t workspace_bytes, void *stream)
+// The forward pass behind every single-projection entry point.  `ws` + w.t_off holds t when it is not saved, `ws` +
+// w.split_off the planes of a split contraction; ws_bytes is what the caller's buffer holds beyond `ws`.
+static int forward(const void *x, const uint32_t *packed, const void *scales, const uint8_t *zeros, const void *A,
+                   const void *B, const uint32_t *keep_mask, float keep_scale, void *y, void *t_save, int M, int N,
+                   int K, int bits, int group_size, int rank, float alpha, int dtype, char *ws, const Workspace &w,
+                   size_t ws_bytes, void *stream)
 {
-    const int st = check_problem(M, N, K, bits, group_size, rank, dtype);
-    if (st != QLORA_OK) return st;
     if (!x || !packed || !scales || !zeros || !y) return QLORA_E_NULL;
     if (rank > 0 && (!A || !B)) return QLORA_E_NULL;
     if (misaligned(x) || misaligned(packed) || misaligned(scales) || misaligned(zeros) || misaligned(y) ||
-        misaligned(A) || misaligned(B) || misaligned(t_save) || misaligned(workspace) || misaligned(keep_mask))
+        misaligned(A) || misaligned(B) || misaligned(t_save) || misaligned(ws) || misaligned(keep_mask))
         return QLORA_E_ALIGN;
-    const Workspace w = carve(M, N, K, rank, bits);
-    if (!workspace || workspace_bytes < w.total) return QLORA_E_WORKSPACE;
+    if (!ws || ws_bytes < w.total) return QLORA_E_WORKSPACE;
     if (rank == 0) keep_mask = nullptr;         // no adapter branch: nothing is dropped
 
     const hipStream_t s = (hipStream_t)stream;
+    begin_call();
     const Problem p{M, N, K, bits, group_size, rank, rank > 0 ? alpha / (float)rank : 0.f, dtype == QLORA_BF16};
-    char *ws = (char *)workspace;
     if (M <= SMALL_M_FWD_MAX) {
         // one launch: the weight-streaming kernel also forms t (ranks up to 32, no dropout)
         void *t = rank > 0 ? (t_save ? t_save : (void *)(ws + w.t_off)) : nullptr;
@@ -288,7 +291,18 @@ int qlora_linear_fwd_dropout(const void *x, const uint32_t *packed, const void *
         GemmTimer timer(s, true);
         launch_fwd_mfma(p, x, packed, scales, zeros, t, B, y, (float *)(ws + w.split_off), s);
     }
-    return hip_status();
+    return end_call();
+}
+
+int qlora_linear_fwd_dropout(const void *x, const uint32_t *packed, const void *scales, const uint8_t *zeros,
+                             const void *A, const void *B, const uint32_t *keep_mask, float keep_scale, void *y,
+                             void *t_save, int M, int N, int K, int bits, int group_size, int rank, float alpha,
+                             int dtype, void *workspace, size_t workspace_bytes, void *stream)
+{
+    const int st = check_problem(M, N, K, bits, group_size, rank, dtype);
+    if (st != QLORA_OK) return st;
+    return forward(x, packed, scales, zeros, A, B, keep_mask, keep_scale, y, t_save, M, N, K, bits, group_size, rank,
+                   alpha, dtype, (char *)workspace, carve(M, N, K, rank, bits), workspace_bytes, stream);
 }
 
 int qlora_linear_bwd(const void *dy, const void *x, const uint32_t *packed, const void *scales, const uint8_t *zeros,
@@ -330,6 +344,7 @@ static int backward(const void *dy, const void *x, const uint32_t *packed, const
     if (rank == 0) keep_mask = nullptr;
 
     const hipStream_t s = (hipStream_t)stream;
+    begin_call();
     const Problem p{M, N, K, bits, group_size, rank, rank > 0 ? alpha / (float)rank : 0.f, dtype == QLORA_BF16};
     char *ws = (char *)workspace;
     if (M <= SMALL_M_BWD_MAX) {
@@ -343,13 +358,13 @@ static int backward(const void *dy, const void *x, const uint32_t *packed, const
         launch_bwd_small(p, 1, &dy, x, &packed, &scales, &zeros, &A, &B, &t, dx, &dA, &dB, &N,
                          (float *)(ws + w.partial_off), (float *)(ws + w.upartial_off), beta, keep_mask, keep_scale, frozen,
                          s);
-        return hip_status();
+        return end_call();
     }
     void *u = nullptr;
     mark_pre_begin(s);
     if (rank > 0) {
         u = ws + w.u_off;
-        launch_lora_u(dy, B, ws + w.bt_off, u, M, N, rank, p.bf16, s);
+        launch_lora_u(dy, B, u, M, N, rank, p.bf16, s);
     }
     mark_pre_end(s);
     {
@@ -374,11 +389,9 @@ static int backward(const void *dy, const void *x, const uint32_t *packed, const
             launch_lora_down(x, A, ws + w.t_off, M, K, rank, p.bf16, keep_mask, keep_scale, s);
             t = ws + w.t_off;
         }
-        float *partial = (float *)(ws + w.partial_off);
-        launch_adapter_grads(dy, t, x, u, dB, dA, partial, M, N, K, rank, frozen, p.sc, beta, keep_mask, keep_scale,
-                             p.bf16, s);
+        launch_adapter_grads(dy, t, x, u, dB, dA, M, N, K, rank, frozen, p.sc, beta, keep_mask, keep_scale, p.bf16, s);
     }
-    return hip_status();
+    return end_call();
 }
 
 int qlora_linear_bwd_dropout(const void *dy, const void *x, const uint32_t *packed, const void *scales,
@@ -468,6 +481,7 @@ int qlora_linear_fwd_siblings(int count, const void *x, const uint32_t *const *p
     if (!workspace || workspace_bytes < w.total) return QLORA_E_WORKSPACE;
 
     const hipStream_t s = (hipStream_t)stream;
+    begin_call();
     const Problem p{M, 0, K, bits, group_size, rank, rank > 0 ? alpha / (float)rank : 0.f, dtype == QLORA_BF16};
     char *ws = (char *)workspace;
     void *t[MAX_SIBLINGS] = {};
@@ -479,7 +493,7 @@ int qlora_linear_fwd_siblings(int count, const void *x, const uint32_t *const *p
     }
     GemmTimer timer(s);
     launch_fwd_small(p, count, x, packed, scales, zeros, A, B, tc, t, y, N, false, s);
-    return hip_status();
+    return end_call();
 }
 
 int qlora_linear_bwd_siblings(int count, const void *const *dy, const void *x, const uint32_t *const *packed,
@@ -505,6 +519,7 @@ int qlora_linear_bwd_siblings(int count, const void *const *dy, const void *x, c
     if (!workspace || workspace_bytes < w.total) return QLORA_E_WORKSPACE;
 
     const hipStream_t s = (hipStream_t)stream;
+    begin_call();
     const Problem p{M, 0, K, bits, group_size, rank, rank > 0 ? alpha / (float)rank : 0.f, dtype == QLORA_BF16};
     char *ws = (char *)workspace;
     const void *t[MAX_SIBLINGS] = {};
@@ -518,7 +533,7 @@ int qlora_linear_bwd_siblings(int count, const void *const *dy, const void *x, c
     GemmTimer timer(s);
     launch_bwd_small(p, count, dy, x, packed, scales, zeros, A, B, t, dx, dA, dB, N, (float *)(ws + w.partial_off),
                      (float *)(ws + w.upartial_off), 0.f, nullptr, 1.f, 0, s);
-    return hip_status();
+    return end_call();
 }
 
 size_t qlora_lrec_workspace_bytes(int M)
@@ -530,6 +545,14 @@ int qlora_lrec_loss(const void *student_logits, const void *teacher_logits, cons
                     float lambda_ce, float *kl, float *ce, float *loss_mean, void *dlogits, int M, int V, int dtype,
                     void *workspace, size_t workspace_bytes, void *stream)
 {
+    return qlora_lrec_loss_scaled(student_logits, teacher_logits, labels, lambda_kl, lambda_ce, 1.f, kl, ce, loss_mean,
+                                  dlogits, M, V, dtype, workspace, workspace_bytes, stream);
+}
+
+int qlora_lrec_loss_scaled(const void *student_logits, const void *teacher_logits, const int32_t *labels,
+                           float lambda_kl, float lambda_ce, float grad_scale, float *kl, float *ce, float *loss_mean,
+                           void *dlogits, int M, int V, int dtype, void *workspace, size_t workspace_bytes, void *stream)
+{
     if (M < 1 || V < 8 || V % 8 != 0 || (long long)M * V >= (1ll << 40)) return QLORA_E_SHAPE;
     if (dtype != QLORA_F16 && dtype != QLORA_BF16) return QLORA_E_DTYPE;
     if (!student_logits || !teacher_logits || !labels || !loss_mean) return QLORA_E_NULL;
@@ -538,9 +561,10 @@ int qlora_lrec_loss(const void *student_logits, const void *teacher_logits, cons
         (reinterpret_cast<uintptr_t>(ce) & 3u) || (reinterpret_cast<uintptr_t>(loss_mean) & 3u))
         return QLORA_E_ALIGN;
     if (!workspace || workspace_bytes < qlora_lrec_workspace_bytes(M)) return QLORA_E_WORKSPACE;
-    launch_lrec_loss(student_logits, teacher_logits, labels, lambda_kl, lambda_ce, kl, ce, (float *)workspace,
+    begin_call();
+    launch_lrec_loss(student_logits, teacher_logits, labels, lambda_kl, lambda_ce, grad_scale, kl, ce, (float *)workspace,
                      loss_mean, dlogits, M, V, dtype == QLORA_BF16, (hipStream_t)stream);
-    return hip_status();
+    return end_call();
 }
 
 }  // extern "C"

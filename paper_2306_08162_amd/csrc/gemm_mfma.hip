@@ -581,7 +581,7 @@ void launch_variant(const GemmArgs &a, hipStream_t s)
     constexpr size_t lds = lds_pipe > lds_epi ? lds_pipe : lds_epi;
     auto kern = qgemm_kernel<BITS, BF16, TRANS, BM, BN, WM, WN, MASKED>;
     ensure_dynamic_lds((const void *)kern, (int)(lds));
-    hipLaunchKernelGGL(kern, dim3(a.tiles_m * a.tiles_n * a.splits), dim3(WM * WN * 64 + STAGERS), lds, s, a);
+    QLORA_LAUNCH(kern, dim3(a.tiles_m * a.tiles_n * a.splits), dim3(WM * WN * 64 + STAGERS), lds, s, a);
 }
 
 // out = round16(sum over the split planes, in order): 8 elements per thread
@@ -648,7 +648,7 @@ void launch_tiles(GemmArgs &a, hipStream_t s)
             launch_variant<BITS, BF16, TRANS, 128, BN, QLORA_WM, QLORA_WN>(a, s);
             if (splits > 1) {
                 const size_t plane = (size_t)a.M * NO;
-                hipLaunchKernelGGL(splitk_sum_kernel<BF16>, dim3((unsigned)((plane / 8 + 255) / 256)), dim3(256), 0, s,
+                QLORA_LAUNCH(splitk_sum_kernel<BF16>, dim3((unsigned)((plane / 8 + 255) / 256)), dim3(256), 0, s,
                                    a.part, a.out, plane, splits);
             }
             return;

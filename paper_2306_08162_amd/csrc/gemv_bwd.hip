@@ -464,20 +464,20 @@ void launch_bwd_bits(const BwdMulti &m, hipStream_t s)
     if (m.count == 1) {
         if constexpr (BITS != 3) {
             if (eight) {
-                hipLaunchKernelGGL((gemv_bwd_kernel<BITS, BF16, 8, 2>), grid, dim3(512), 0, s, m.p[0]);
+                QLORA_LAUNCH((gemv_bwd_kernel<BITS, BF16, 8, 2>), grid, dim3(512), 0, s, m.p[0]);
                 return;
             }
         }
-        hipLaunchKernelGGL((gemv_bwd_kernel<BITS, BF16, 4, 2>), grid, dim3(256), 0, s, m.p[0]);
+        QLORA_LAUNCH((gemv_bwd_kernel<BITS, BF16, 4, 2>), grid, dim3(256), 0, s, m.p[0]);
         return;
     }
     if constexpr (BITS != 3) {
         if (eight) {
-            hipLaunchKernelGGL((gemv_bwd_siblings_kernel<BITS, BF16, 8, 2>), grid, dim3(512), 0, s, m);
+            QLORA_LAUNCH((gemv_bwd_siblings_kernel<BITS, BF16, 8, 2>), grid, dim3(512), 0, s, m);
             return;
         }
     }
-    hipLaunchKernelGGL((gemv_bwd_siblings_kernel<BITS, BF16, 4, 2>), grid, dim3(256), 0, s, m);
+    QLORA_LAUNCH((gemv_bwd_siblings_kernel<BITS, BF16, 4, 2>), grid, dim3(256), 0, s, m);
 }
 
 int bwd_cb(int bits) { return bits == 3 ? BwdShape<3>::CB : (bits == 2 ? BwdShape<2>::CB : (bits == 4 ? BwdShape<4>::CB : BwdShape<8>::CB)); }
@@ -554,11 +554,11 @@ void launch_bwd_small(const Problem &p, int count, const void *const *dy, const 
                            (const uint8_t *)keep, keep_scale, frozen};
         const dim3 grid(xb + ab + bb), block(256);
         if (keep) {
-            if (p.bf16) hipLaunchKernelGGL((gemv_bwd_finish_kernel<true, true>), grid, block, 0, s, f);
-            else hipLaunchKernelGGL((gemv_bwd_finish_kernel<false, true>), grid, block, 0, s, f);
+            if (p.bf16) QLORA_LAUNCH((gemv_bwd_finish_kernel<true, true>), grid, block, 0, s, f);
+            else QLORA_LAUNCH((gemv_bwd_finish_kernel<false, true>), grid, block, 0, s, f);
         } else {
-            if (p.bf16) hipLaunchKernelGGL((gemv_bwd_finish_kernel<true, false>), grid, block, 0, s, f);
-            else hipLaunchKernelGGL((gemv_bwd_finish_kernel<false, false>), grid, block, 0, s, f);
+            if (p.bf16) QLORA_LAUNCH((gemv_bwd_finish_kernel<true, false>), grid, block, 0, s, f);
+            else QLORA_LAUNCH((gemv_bwd_finish_kernel<false, false>), grid, block, 0, s, f);
         }
         return;
     }
@@ -586,9 +586,9 @@ void launch_bwd_small(const Problem &p, int count, const void *const *dy, const 
     }
     const int blocks = xb + count * ab + bb_end;
     if (p.bf16)
-        hipLaunchKernelGGL((gemv_bwd_finish_siblings_kernel<true>), dim3(blocks), dim3(256), 0, s, f);
+        QLORA_LAUNCH((gemv_bwd_finish_siblings_kernel<true>), dim3(blocks), dim3(256), 0, s, f);
     else
-        hipLaunchKernelGGL((gemv_bwd_finish_siblings_kernel<false>), dim3(blocks), dim3(256), 0, s, f);
+        QLORA_LAUNCH((gemv_bwd_finish_siblings_kernel<false>), dim3(blocks), dim3(256), 0, s, f);
 }
 
 }  // namespace qlora

@@ -414,9 +414,9 @@ void launch_fwd_rg(const FwdArgs &a, int rg, hipStream_t s)
     constexpr int NW = 4;
     const dim3 grid((a.N + 15) / 16), block(NW * 64);
     switch (rg) {
-    case 0: hipLaunchKernelGGL((gemv_fwd_kernel<BITS, BF16, MB, 0, NW, 1>), grid, block, 0, s, a); break;
-    case 1: hipLaunchKernelGGL((gemv_fwd_kernel<BITS, BF16, MB, 1, NW, 1>), grid, block, 0, s, a); break;
-    default: hipLaunchKernelGGL((gemv_fwd_kernel<BITS, BF16, MB, 2, NW, 1>), grid, block, 0, s, a); break;
+    case 0: QLORA_LAUNCH((gemv_fwd_kernel<BITS, BF16, MB, 0, NW, 1>), grid, block, 0, s, a); break;
+    case 1: QLORA_LAUNCH((gemv_fwd_kernel<BITS, BF16, MB, 1, NW, 1>), grid, block, 0, s, a); break;
+    default: QLORA_LAUNCH((gemv_fwd_kernel<BITS, BF16, MB, 2, NW, 1>), grid, block, 0, s, a); break;
     }
 }
 
@@ -434,13 +434,13 @@ void launch_fwd_staged_one(FwdMulti m, hipStream_t s)
     if (m.count == 1) {
         auto kern = gemv_fwd_staged_kernel<BITS, BF16, MB, RG, NW, NB>;
         ensure_dynamic_lds((const void *)kern, (int)(lds));
-        hipLaunchKernelGGL(kern, dim3(wgs), dim3(NW * 64), lds, s, m.p[0]);
+        QLORA_LAUNCH(kern, dim3(wgs), dim3(NW * 64), lds, s, m.p[0]);
         return;
     }
     if constexpr (MB == 1) {          // the callers hand siblings over together only up to 16 token rows
         auto kern = gemv_fwd_staged_siblings_kernel<BITS, BF16, MB, RG, NW, NB>;
         ensure_dynamic_lds((const void *)kern, (int)(lds));
-        hipLaunchKernelGGL(kern, dim3(wgs), dim3(NW * 64), lds, s, m);
+        QLORA_LAUNCH(kern, dim3(wgs), dim3(NW * 64), lds, s, m);
     }
 }
 

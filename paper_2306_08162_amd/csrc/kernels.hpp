@@ -18,6 +18,19 @@ struct Problem {
 // call from several host threads.
 void ensure_dynamic_lds(const void *kernel, int bytes);
 
+// Launch bookkeeping of the calling host thread: every kernel launch of the library goes through QLORA_LAUNCH, which
+// asks the runtime for the launch's status right away and keeps the first failure.  An entry point clears both the
+// runtime's sticky error and this record before its first launch (an error left behind by somebody else's earlier
+// call is not this call's) and reports the record when it returns.
+void launch_errors_clear();
+void launch_errors_note();          // after a launch (or a runtime call that may fail): keep the first error
+bool launch_errors_seen();
+#define QLORA_LAUNCH(...)                \
+    do {                                 \
+        hipLaunchKernelGGL(__VA_ARGS__); \
+        ::qlora::launch_errors_note();   \
+    } while (0)
+
 // pack.hip
 void launch_pack(const uint8_t *codes, uint32_t *packed, int N, int K, int bits, hipStream_t s);
 void launch_unpack(const uint32_t *packed, uint8_t *codes, int N, int K, int bits, hipStream_t s);
@@ -38,17 +51,15 @@ void launch_lora_down(const void *x, const void *A, void *t, int M, int K, int r
 // dx[m,k] += f * keep[m,k] * sum_j u[m,j] A[j,k]: the adapter's share of dX under dropout, on top of the base product
 void launch_lora_dx_masked(void *dx, const void *u, const void *A, const uint32_t *keep, int M, int K, int r, float f,
                            bool bf16, hipStream_t s);
-// u[M,r] = dy[M,N] B[N,r]; bt is scratch for B^T (N*r 16-bit values)
-void launch_lora_u(const void *dy, const void *B, void *bt, void *u, int M, int N, int r, bool bf16, hipStream_t s);
-// Number of token slices the adapter-gradient reductions are cut into (fixed by the shape alone).
-int adapter_grad_slices(int M, int r);
-// dB[N,r] = sc * dy[M,N]^T t[M,r] and dA[r,K] = sc * u[M,r]^T x[M,K], two launches for both (slice partial sums,
-// then their fixed-order reduction); partial holds slices*(N+K)*r floats.  beta != 0: dB = beta*dB + ..., dA likewise.
-// keep != NULL (LoRA dropout): x stands for keep_scale * x * keep in dA.  Stacked adapters: t and u are [M, r_all],
-// the first `frozen` adapter columns have no gradient, r = r_all - frozen, dB is [N, r], dA [r, K].
-void launch_adapter_grads(const void *dy, const void *t, const void *x, const void *u, float *dB, float *dA,
-                          float *partial, int M, int N, int K, int r_all, int frozen, float sc, float beta,
-                          const uint32_t *keep, float keep_scale, bool bf16, hipStream_t s);
+// u[M,r] = dy[M,N] B[N,r]
+void launch_lora_u(const void *dy, const void *B, void *u, int M, int N, int r, bool bf16, hipStream_t s);
+// dB[N,r] = sc * dy[M,N]^T t[M,r] and dA[r,K] = sc * u[M,r]^T x[M,K], one launch for both, sums in a fixed order.
+// beta != 0: dB = beta*dB + ..., dA likewise.  keep != NULL (LoRA dropout): x stands for keep_scale * x * keep in dA.
+// Stacked adapters: t and u are [M, r_all], the first `frozen` adapter columns have no gradient, r = r_all - frozen,
+// dB is [N, r], dA [r, K].
+void launch_adapter_grads(const void *dy, const void *t, const void *x, const void *u, float *dB, float *dA, int M, int N,
+                          int K, int r_all, int frozen, float sc, float beta, const uint32_t *keep, float keep_scale,
+                          bool bf16, hipStream_t s);
 
 // gemm_mfma.hip -- tiled MFMA GEMMs with fused dequantisation (any accepted shape)
 // Workgroups per output tile along the contraction.  An [M, NO] output with a contraction of length KC that makes
@@ -105,9 +116,10 @@ void launch_bwd_small(const Problem &p, int count, const void *const *dy, const 
                       float keep_scale, int frozen, hipStream_t s);
 
 // loss.hip -- the LREC objective (KL student || teacher + next-token CE, mean over tokens) and its gradient
-// kl, ce (per token) and grad may be NULL; tok receives lambda_kl*KL + lambda_ce*CE per token, loss_mean their mean
+// kl, ce (per token) and grad may be NULL; tok receives lambda_kl*KL + lambda_ce*CE per token, loss_mean their mean;
+// grad is written multiplied by grad_scale (loss scaling)
 void launch_lrec_loss(const void *student, const void *teacher, const int32_t *labels, float lambda_kl,
-                      float lambda_ce, float *kl, float *ce, float *tok, float *loss_mean, void *grad, int M, int V,
-                      bool bf16, hipStream_t s);
+                      float lambda_ce, float grad_scale, float *kl, float *ce, float *tok, float *loss_mean, void *grad,
+                      int M, int V, bool bf16, hipStream_t s);
 
 }  // namespace qlora

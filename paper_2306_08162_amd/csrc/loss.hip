@@ -37,6 +37,7 @@ struct LossArgs {
     uint16_t *grad;                  // [M,V], may be NULL
     int M, V;
     float lkl, lce;
+    float gscale;                    // loss scaling: the gradient is written multiplied by this factor
 };
 
 // Running softmax state: m an upper bound of the values seen, s = sum exp(v - m), q = sum exp(v - m) w for a weight
@@ -158,7 +159,9 @@ __global__ __launch_bounds__(LT) void lrec_loss_kernel(const LossArgs a)
             qs = fmaf(es, dz, qs);
             st += fast_exp2(fmaf(val(t8, e), LOG2E, ot));
             eh[e] = (half_t)es;
-            dh[e] = (half_t)dz;
+            // kept as fp16: a masked student logit (-65504) against an ordinary teacher logit would round to -inf
+            // and turn its zero gradient entry, 0 * inf, into a NaN
+            dh[e] = (half_t)__builtin_amdgcn_fmed3f(dz, -65504.f, 65504.f);
         }
         if constexpr (CH > 0) {       // e_i and zs_i - zt_i (2^-11 relative) take the place of the logits
             rs[i] = __builtin_bit_cast(u16x8_t, eh);
@@ -198,7 +201,7 @@ __global__ __launch_bounds__(LT) void lrec_loss_kernel(const LossArgs a)
     // sweep 2: the gradient row, g_i = y_hat_i (c1 (zs_i - zt_i) + c2) - [i = label] lce / M, with
     // y_hat_i = e_i phi, phi = exp(ls - m) / S the thread's share of the normalisation
     const float row_m = bc[0], row_s = bc[1], delta = bc[2], klv = bc[3];
-    const float inv_m = 1.f / (float)a.M, lce = has ? a.lce : 0.f;
+    const float inv_m = a.gscale / (float)a.M, lce = has ? a.lce : 0.f;   // 1/M of the mean, times the loss scale
     const float c1 = a.lkl * inv_m, c2 = (lce - a.lkl * (klv + delta)) * inv_m;
     const float phi = fast_exp2((ls - row_m) * LOG2E) / row_s;
     const float c1p = c1 * phi, c2p = c2 * phi;
@@ -229,7 +232,8 @@ __global__ __launch_bounds__(LT) void lrec_loss_kernel(const LossArgs a)
         const float z = cvt16<BF16>(zs[label]), t = cvt16<BF16>(zt[label]);
         float gl;
         if constexpr (CH > 0)         // from the values the sweep used: e and zs - zt as the fp16 they were kept in
-            gl = fmaf((float)(half_t)fast_exp2(fmaf(z, LOG2E, os)), fmaf((float)(half_t)(z - t), c1p, c2p), zero);
+            gl = fmaf((float)(half_t)fast_exp2(fmaf(z, LOG2E, os)),
+                      fmaf((float)(half_t)__builtin_amdgcn_fmed3f(z - t, -65504.f, 65504.f), c1p, c2p), zero);
         else
             gl = fast_exp2(fmaf(z, LOG2E, off_s)) * fmaf(z - t, c1, c2);
         grow[label] = to16<BF16>(gl - lce * inv_m);
@@ -256,27 +260,27 @@ void launch_loss(const LossArgs &a, hipStream_t s)
 {
     const int per_thread = (a.V / 8 + LT - 1) / LT;
     const dim3 grid(a.M), block(LT);
-    if (per_thread <= 1) hipLaunchKernelGGL((lrec_loss_kernel<BF16, 1>), grid, block, 0, s, a);
-    else if (per_thread <= 2) hipLaunchKernelGGL((lrec_loss_kernel<BF16, 2>), grid, block, 0, s, a);
-    else if (per_thread <= 4) hipLaunchKernelGGL((lrec_loss_kernel<BF16, 4>), grid, block, 0, s, a);
-    else if (per_thread <= 8) hipLaunchKernelGGL((lrec_loss_kernel<BF16, 8>), grid, block, 0, s, a);
-    else if (per_thread <= 16) hipLaunchKernelGGL((lrec_loss_kernel<BF16, 16>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((lrec_loss_kernel<BF16, 0>), grid, block, 0, s, a);
+    if (per_thread <= 1) QLORA_LAUNCH((lrec_loss_kernel<BF16, 1>), grid, block, 0, s, a);
+    else if (per_thread <= 2) QLORA_LAUNCH((lrec_loss_kernel<BF16, 2>), grid, block, 0, s, a);
+    else if (per_thread <= 4) QLORA_LAUNCH((lrec_loss_kernel<BF16, 4>), grid, block, 0, s, a);
+    else if (per_thread <= 8) QLORA_LAUNCH((lrec_loss_kernel<BF16, 8>), grid, block, 0, s, a);
+    else if (per_thread <= 16) QLORA_LAUNCH((lrec_loss_kernel<BF16, 16>), grid, block, 0, s, a);
+    else QLORA_LAUNCH((lrec_loss_kernel<BF16, 0>), grid, block, 0, s, a);
 }
 
 }  // namespace
 
 void launch_lrec_loss(const void *student, const void *teacher, const int32_t *labels, float lambda_kl,
-                      float lambda_ce, float *kl, float *ce, float *tok, float *loss_mean, void *grad, int M, int V,
-                      bool bf16, hipStream_t s)
+                      float lambda_ce, float grad_scale, float *kl, float *ce, float *tok, float *loss_mean, void *grad,
+                      int M, int V, bool bf16, hipStream_t s)
 {
     const LossArgs a{(const uint16_t *)student, (const uint16_t *)teacher, labels, kl, ce, tok, (uint16_t *)grad, M, V,
-                     lambda_kl, lambda_ce};
+                     lambda_kl, lambda_ce, grad_scale};
     if (bf16)
         launch_loss<true>(a, s);
     else
         launch_loss<false>(a, s);
-    hipLaunchKernelGGL(lrec_mean_kernel, dim3(1), dim3(256), 0, s, tok, loss_mean, M);
+    QLORA_LAUNCH(lrec_mean_kernel, dim3(1), dim3(256), 0, s, tok, loss_mean, M);
 }
 
 }  // namespace qlora

@@ -8,6 +8,10 @@
 
 namespace qlora {
 
+namespace {
+thread_local hipError_t first_launch_error = hipSuccess;
+}
+
 void ensure_dynamic_lds(const void *kernel, int bytes)
 {
     static std::mutex mu;
@@ -18,9 +22,25 @@ void ensure_dynamic_lds(const void *kernel, int bytes)
     std::lock_guard<std::mutex> guard(mu);
     uint64_t &mask = done[kernel];
     if (mask & bit) return;
-    (void)hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-    mask |= bit;
+    // remembered only when it took: a failure is reported by this call's launch and the next call tries again
+    const hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess) mask |= bit;
+    else if (first_launch_error == hipSuccess) first_launch_error = e;
 }
+
+void launch_errors_clear()
+{
+    (void)hipGetLastError();
+    first_launch_error = hipSuccess;
+}
+
+void launch_errors_note()
+{
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess && first_launch_error == hipSuccess) first_launch_error = e;
+}
+
+bool launch_errors_seen() { return first_launch_error != hipSuccess; }
 
 // One thread builds one 32-bit word of the row's little-endian bit stream.
 template <int BITS>
@@ -72,14 +92,8 @@ __global__ __launch_bounds__(256) void pack_permuted_kernel(const uint8_t *__res
 // builds eight neighbouring output columns per row from LDS and writes them with one 16-byte store.  The index is read
 // once per thread and row block.  A workgroup takes as many rows as fit GATHER_LDS_BYTES (at most GATHER_ROWS); rows
 // longer than that take the direct kernel below.
-#ifndef QLORA_GATHER_ROWS
-#define QLORA_GATHER_ROWS 2
-#endif
-#ifndef QLORA_GATHER_LDS_BYTES
-#define QLORA_GATHER_LDS_BYTES 16384
-#endif
-constexpr int GATHER_ROWS = QLORA_GATHER_ROWS;
-constexpr int GATHER_LDS_BYTES = QLORA_GATHER_LDS_BYTES;
+constexpr int GATHER_ROWS = 2;
+constexpr int GATHER_LDS_BYTES = 16384;
 constexpr int GATHER_LDS_K = 32768;      // one row of 64 KB: the most a launch gets without asking for more
 __global__ __launch_bounds__(256) void gather_columns_lds_kernel(const uint16_t *__restrict__ src,
                                                                  const int32_t *__restrict__ index,
@@ -196,10 +210,10 @@ void launch_pack(const uint8_t *codes, uint32_t *packed, int N, int K, int bits,
     const long words = (long)N * (K * bits / 32);
     const dim3 grid((unsigned)((words + 255) / 256)), block(256);
     switch (bits) {
-    case 2: hipLaunchKernelGGL(pack_kernel<2>, grid, block, 0, s, codes, packed, N, K); break;
-    case 3: hipLaunchKernelGGL(pack_kernel<3>, grid, block, 0, s, codes, packed, N, K); break;
-    case 4: hipLaunchKernelGGL(pack_kernel<4>, grid, block, 0, s, codes, packed, N, K); break;
-    default: hipLaunchKernelGGL(pack_kernel<8>, grid, block, 0, s, codes, packed, N, K); break;
+    case 2: QLORA_LAUNCH(pack_kernel<2>, grid, block, 0, s, codes, packed, N, K); break;
+    case 3: QLORA_LAUNCH(pack_kernel<3>, grid, block, 0, s, codes, packed, N, K); break;
+    case 4: QLORA_LAUNCH(pack_kernel<4>, grid, block, 0, s, codes, packed, N, K); break;
+    default: QLORA_LAUNCH(pack_kernel<8>, grid, block, 0, s, codes, packed, N, K); break;
     }
 }
 
@@ -209,10 +223,10 @@ void launch_pack_permuted(const uint8_t *codes, const int32_t *perm, uint32_t *p
     const long words = (long)N * (K * bits / 32);
     const dim3 grid((unsigned)((words + 255) / 256)), block(256);
     switch (bits) {
-    case 2: hipLaunchKernelGGL(pack_permuted_kernel<2>, grid, block, 0, s, codes, perm, packed, N, K); break;
-    case 3: hipLaunchKernelGGL(pack_permuted_kernel<3>, grid, block, 0, s, codes, perm, packed, N, K); break;
-    case 4: hipLaunchKernelGGL(pack_permuted_kernel<4>, grid, block, 0, s, codes, perm, packed, N, K); break;
-    default: hipLaunchKernelGGL(pack_permuted_kernel<8>, grid, block, 0, s, codes, perm, packed, N, K); break;
+    case 2: QLORA_LAUNCH(pack_permuted_kernel<2>, grid, block, 0, s, codes, perm, packed, N, K); break;
+    case 3: QLORA_LAUNCH(pack_permuted_kernel<3>, grid, block, 0, s, codes, perm, packed, N, K); break;
+    case 4: QLORA_LAUNCH(pack_permuted_kernel<4>, grid, block, 0, s, codes, perm, packed, N, K); break;
+    default: QLORA_LAUNCH(pack_permuted_kernel<8>, grid, block, 0, s, codes, perm, packed, N, K); break;
     }
 }
 
@@ -221,13 +235,13 @@ void launch_gather_columns(const void *src, const int32_t *index, void *dst, int
     if (K <= GATHER_LDS_K) {
         int R = GATHER_LDS_BYTES / (K * 2);
         R = R < 1 ? 1 : (R > GATHER_ROWS ? GATHER_ROWS : R);
-        hipLaunchKernelGGL(gather_columns_lds_kernel, dim3((unsigned)((M + R - 1) / R)), dim3(256), (size_t)R * K * 2, s,
+        QLORA_LAUNCH(gather_columns_lds_kernel, dim3((unsigned)((M + R - 1) / R)), dim3(256), (size_t)R * K * 2, s,
                            (const uint16_t *)src, index, (uint16_t *)dst, M, K, R);
         return;
     }
     const unsigned row_blocks = (unsigned)((M + GATHER_ROWS - 1) / GATHER_ROWS);
     const dim3 grid(row_blocks, (unsigned)((K / 8 + 255) / 256)), block(256);
-    hipLaunchKernelGGL(gather_columns_kernel, grid, block, 0, s, (const uint16_t *)src, index, (uint16_t *)dst, M, K);
+    QLORA_LAUNCH(gather_columns_kernel, grid, block, 0, s, (const uint16_t *)src, index, (uint16_t *)dst, M, K);
 }
 
 void launch_unpack(const uint32_t *packed, uint8_t *codes, int N, int K, int bits, hipStream_t s)
@@ -235,10 +249,10 @@ void launch_unpack(const uint32_t *packed, uint8_t *codes, int N, int K, int bit
     const long n = (long)N * K;
     const dim3 grid((unsigned)((n + 255) / 256)), block(256);
     switch (bits) {
-    case 2: hipLaunchKernelGGL(unpack_kernel<2>, grid, block, 0, s, packed, codes, N, K); break;
-    case 3: hipLaunchKernelGGL(unpack_kernel<3>, grid, block, 0, s, packed, codes, N, K); break;
-    case 4: hipLaunchKernelGGL(unpack_kernel<4>, grid, block, 0, s, packed, codes, N, K); break;
-    default: hipLaunchKernelGGL(unpack_kernel<8>, grid, block, 0, s, packed, codes, N, K); break;
+    case 2: QLORA_LAUNCH(unpack_kernel<2>, grid, block, 0, s, packed, codes, N, K); break;
+    case 3: QLORA_LAUNCH(unpack_kernel<3>, grid, block, 0, s, packed, codes, N, K); break;
+    case 4: QLORA_LAUNCH(unpack_kernel<4>, grid, block, 0, s, packed, codes, N, K); break;
+    default: QLORA_LAUNCH(unpack_kernel<8>, grid, block, 0, s, packed, codes, N, K); break;
     }
 }
 
@@ -247,10 +261,10 @@ void launch_pack_zeros(const uint8_t *zeros, uint32_t *packed, int N, int groups
     const int zw = (groups * bits + 31) / 32;
     const dim3 grid((unsigned)(((long)N * zw + 255) / 256)), block(256);
     switch (bits) {
-    case 2: hipLaunchKernelGGL(pack_zeros_kernel<2>, grid, block, 0, s, zeros, packed, N, groups, zw); break;
-    case 3: hipLaunchKernelGGL(pack_zeros_kernel<3>, grid, block, 0, s, zeros, packed, N, groups, zw); break;
-    case 4: hipLaunchKernelGGL(pack_zeros_kernel<4>, grid, block, 0, s, zeros, packed, N, groups, zw); break;
-    default: hipLaunchKernelGGL(pack_zeros_kernel<8>, grid, block, 0, s, zeros, packed, N, groups, zw); break;
+    case 2: QLORA_LAUNCH(pack_zeros_kernel<2>, grid, block, 0, s, zeros, packed, N, groups, zw); break;
+    case 3: QLORA_LAUNCH(pack_zeros_kernel<3>, grid, block, 0, s, zeros, packed, N, groups, zw); break;
+    case 4: QLORA_LAUNCH(pack_zeros_kernel<4>, grid, block, 0, s, zeros, packed, N, groups, zw); break;
+    default: QLORA_LAUNCH(pack_zeros_kernel<8>, grid, block, 0, s, zeros, packed, N, groups, zw); break;
     }
 }
 
@@ -259,10 +273,10 @@ void launch_unpack_zeros(const uint32_t *packed, uint8_t *zeros, int N, int grou
     const int zw = (groups * bits + 31) / 32;
     const dim3 grid((unsigned)(((long)N * groups + 255) / 256)), block(256);
     switch (bits) {
-    case 2: hipLaunchKernelGGL(unpack_zeros_kernel<2>, grid, block, 0, s, packed, zeros, N, groups, zw); break;
-    case 3: hipLaunchKernelGGL(unpack_zeros_kernel<3>, grid, block, 0, s, packed, zeros, N, groups, zw); break;
-    case 4: hipLaunchKernelGGL(unpack_zeros_kernel<4>, grid, block, 0, s, packed, zeros, N, groups, zw); break;
-    default: hipLaunchKernelGGL(unpack_zeros_kernel<8>, grid, block, 0, s, packed, zeros, N, groups, zw); break;
+    case 2: QLORA_LAUNCH(unpack_zeros_kernel<2>, grid, block, 0, s, packed, zeros, N, groups, zw); break;
+    case 3: QLORA_LAUNCH(unpack_zeros_kernel<3>, grid, block, 0, s, packed, zeros, N, groups, zw); break;
+    case 4: QLORA_LAUNCH(unpack_zeros_kernel<4>, grid, block, 0, s, packed, zeros, N, groups, zw); break;
+    default: QLORA_LAUNCH(unpack_zeros_kernel<8>, grid, block, 0, s, packed, zeros, N, groups, zw); break;
     }
 }
 

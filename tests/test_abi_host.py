@@ -16,12 +16,13 @@ ODD = 0x10008           # 8-byte aligned only
 
 def test_library_exports_every_declared_symbol():
     lib = ql.load()
-    header = open(os.path.join(ROOT, "include", "qlora.h")).read()
-    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = sorted(set(re.findall(r"\b(qlora_[a-z_]+)\s*\(", header)))
-    assert declared == sorted(ql.EXPORTS)
-    for name in declared:
-        assert hasattr(lib, name), name
+    for fname, exports in (("qlora.h", ql.EXPORTS), ("qlora_bench.h", ql.BENCH_EXPORTS)):
+        header = open(os.path.join(ROOT, "include", fname)).read()
+        header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+        declared = sorted(set(re.findall(r"\b(qlora_[a-z_]+)\s*\(", header)))
+        assert declared == sorted(exports), fname
+        for name in declared:
+            assert hasattr(lib, name), name
 
 
 def test_status_strings():

@@ -7,7 +7,7 @@ import pytest
 import oracle
 from paper_2306_08162_amd import binding as ql
 from paper_2306_08162_amd import workloads as wl
-from parity import TOL, announce, rel_fro, small_inputs
+from parity import Report, announce, layer_bounds, small_inputs
 
 pytestmark = pytest.mark.gpu
 
@@ -51,15 +51,18 @@ def test_actorder_layer(case):
     A_ckpt = A_sorted[:, inv_ref] if r else A_sorted
     y_ref, _ = oracle.forward(x, Wd, A_ckpt, B, c.alpha)
     dx_ref = oracle.backward_dx(dy, Wd, A_ckpt, B, c.alpha)
-    errs = {"y": rel_fro(oracle.widen(layer.host_y(), dtype), y_ref),
-            "dx": rel_fro(oracle.widen(layer.host_dx(), dtype), dx_ref)}
+    sc = c.alpha / r if r else 0.0
+    t_ref = oracle.lora_down(x, A_ckpt) if r else None
+    u_ref = oracle.lora_u(dy, B) if r else None
+    b = layer_bounds(Wd, A_ckpt, B, sc, x=x, dy=dy, t=t_ref, u=u_ref, x_adapter=x)
+    rep = Report(f"act-order {c.name}", dtype)
+    rep.add("y", oracle.widen(layer.host_y(), dtype), y_ref, lines="rows", bound=b["y"])
+    rep.add("dx", oracle.widen(layer.host_dx(), dtype), dx_ref, lines="rows", bound=b["dx"])
     if r:
         dA_ref, dB_ref = oracle.backward_adapters(dy, x, A_ckpt, B, c.alpha)
-        errs["dA"] = rel_fro(layer.host_dA(), dA_ref[:, perm_ref])
-        errs["dB"] = rel_fro(layer.host_dB(), dB_ref)
-    announce(" ".join(f"{k}={v:.2e}" for k, v in errs.items()))
-    for k, v in errs.items():
-        assert np.isfinite(v) and v <= TOL, f"{c.name}: rel. Frobenius error of {k} = {v:.3e} > {TOL}"
+        rep.add("dA", layer.host_dA(), dA_ref[:, perm_ref], lines="rows", bound=b["dA"][:, perm_ref])
+        rep.add("dB", layer.host_dB(), dB_ref, lines="cols", bound=b["dB"])
+    rep.finish()
 
 
 def test_gather_columns_out_of_range_index_gives_zero():

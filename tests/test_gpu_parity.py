@@ -10,7 +10,7 @@ import pytest
 
 import oracle
 from paper_2306_08162_amd import workloads as wl
-from parity import TOL, announce, check_layer, make_oracle, rel_fro, small_inputs
+from parity import TOL, announce, check_layer, integer_inputs, make_oracle, rel_fro, small_inputs
 
 pytestmark = pytest.mark.gpu
 
@@ -162,6 +162,46 @@ def test_integer_exact_case_matches_bit_for_bit():
     y_ref, _ = make_oracle(inp).forward(inp.x)
     assert np.abs(y_ref).max() < 2048 and np.all(y_ref == np.round(y_ref))
     assert np.array_equal(oracle.widen(layer.host_y(), "f16"), y_ref)
+
+
+EXACT_CASES = [
+    # (M, K, N, bits, G, r, dtype, density, adapter): integer inputs, every output compared bit for bit.
+    # weight-streaming kernels (M <= 16 both passes; 17..64 forward), every code width, both dtypes
+    (16, 512, 264, 4, 128, 8, "f16", 1.0, True),
+    (1, 1024, 136, 2, 128, 8, "f16", 1.0, True),
+    (9, 640, 200, 3, 32, 16, "f16", 1.0, True),
+    (13, 512, 72, 8, 64, 8, "f16", 1.0, True),
+    (16, 4096, 4096, 2, 128, 8, "f16", 1.0, True),         # a decoder-block projection at full size
+    (16, 1024, 520, 4, 128, 8, "bf16", 0.25, True),
+    (7, 512, 136, 2, 64, 16, "bf16", 0.25, True),
+    (5, 384, 72, 8, 128, 8, "bf16", 0.25, False),
+    (11, 768, 264, 3, 128, 0, "bf16", 0.25, False),
+    (40, 512, 264, 4, 64, 8, "f16", 1.0, True),            # forward streaming, backward tiled with a split contraction
+    (64, 384, 136, 2, 128, 16, "bf16", 0.25, True),
+    # tiled kernels: one tile, ragged tiles, split contraction, 256-row tiles, every width, both dtypes
+    (70, 256, 136, 2, 64, 8, "f16", 1.0, True),
+    (300, 640, 392, 4, 128, 24, "f16", 1.0, True),
+    (257, 1024, 520, 3, 128, 32, "f16", 1.0, True),
+    (130, 512, 264, 8, 128, 8, "f16", 1.0, True),
+    (100, 2048, 512, 4, 128, 8, "f16", 1.0, True),         # forward contraction split over 4 workgroups per tile
+    (300, 640, 392, 4, 128, 16, "bf16", 0.25, True),
+    (257, 1024, 264, 2, 128, 8, "bf16", 0.125, True),
+    (150, 768, 200, 3, 32, 8, "bf16", 0.25, True),
+    (200, 512, 136, 8, 64, 40, "bf16", 0.25, True),
+    (2048, 512, 4096, 4, 128, 8, "f16", 0.25, True),       # 256 tiles of 256 rows: the launch shape of the headline
+    (4096, 256, 2048, 2, 128, 8, "bf16", 0.0625, True),
+]
+
+
+@pytest.mark.parametrize("case", EXACT_CASES, ids=lambda c: "M{}_K{}_N{}_b{}_G{}_r{}_{}".format(*c[:7]))
+def test_integer_inputs_are_reproduced_bit_for_bit(case):
+    """Integer-valued inputs (scales 1, codes near their zero-point, x, dY, A, B in {-1,0,1}): every product and sum
+    is exact in fp16 / bf16 / fp32, so y, dX, t, dA and dB must equal the fp64 oracle bit for bit on every path."""
+    M, K, N, bits, G, r, dtype, density, adapter = case
+    inp = integer_inputs(3 * M + K + N + bits, M, K, N, bits, G, r, dtype, density=density, adapter=adapter)
+    check_layer(inp, exact=True)
+    if r:
+        check_layer(inp, exact=True, recompute_t=True)
 
 
 def test_B_zero_gives_zero_dA_and_pure_base_paths():

@@ -11,7 +11,7 @@ import pytest
 
 import oracle
 from paper_2306_08162_amd import workloads as wl
-from parity import TOL, announce, make_oracle, rel_fro, small_inputs
+from parity import TOL, Report, announce, layer_bounds, make_oracle, rel_fro, small_inputs
 
 pytestmark = pytest.mark.gpu
 
@@ -35,23 +35,26 @@ def _check(inps, recompute_t=False):
     sib.forward(save_t=not recompute_t)
     sib.backward(use_saved_t=not recompute_t)
     torch.cuda.synchronize()
-    errs = {}
-    dx_ref = 0.0
+    rep = Report(f"siblings N={[i.cfg.N for i in inps]} M={c.M}", c.dtype)
+    dx_ref, dx_bound = 0.0, 0.0
+    sc = c.alpha / c.rank if c.rank else 0.0
     for i, (inp, layer) in enumerate(zip(inps, layers)):
         lo = make_oracle(inp)
         y_ref, t_ref = lo.forward(inp.x)
         dx_ref = dx_ref + lo.backward_dx(inp.dy)
-        errs[f"y{i}"] = rel_fro(oracle.widen(layer.host_y(), c.dtype), y_ref)
+        x, dy = oracle.widen(inp.x, c.dtype), oracle.widen(inp.dy, c.dtype)
+        u_ref = oracle.lora_u(dy, lo.B) if c.rank else None
+        b = layer_bounds(lo.Wd, lo.A, lo.B, sc, x=x, dy=dy, t=t_ref if c.rank else None, u=u_ref, x_adapter=x)
+        dx_bound = dx_bound + b["dx"]
+        rep.add(f"y{i}", oracle.widen(layer.host_y(), c.dtype), y_ref, lines="rows", bound=b["y"])
         if c.rank:
             dA_ref, dB_ref = lo.backward_adapters(inp.dy, inp.x)
-            errs[f"dA{i}"] = rel_fro(layer.host_dA(), dA_ref)
-            errs[f"dB{i}"] = rel_fro(layer.host_dB(), dB_ref)
+            rep.add(f"dA{i}", layer.host_dA(), dA_ref, lines="rows", bound=b["dA"])
+            rep.add(f"dB{i}", layer.host_dB(), dB_ref, lines="cols", bound=b["dB"])
             if not recompute_t:
-                errs[f"t{i}"] = rel_fro(oracle.widen(layer.host_t(), c.dtype), t_ref)
-    errs["dx"] = rel_fro(oracle.widen(sib.host_dx(), c.dtype), dx_ref)
-    announce(" ".join(f"{k}={v:.2e}" for k, v in errs.items()))
-    for k, v in errs.items():
-        assert np.isfinite(v) and v <= TOL, f"rel. Frobenius error of {k} = {v:.3e} > {TOL}"
+                rep.add(f"t{i}", oracle.widen(layer.host_t(), c.dtype), t_ref, lines="cols")
+    rep.add("dx", oracle.widen(sib.host_dx(), c.dtype), dx_ref, lines="rows", bound=dx_bound)
+    rep.finish()
     return layers, sib
 
 
@@ -148,17 +151,20 @@ def test_siblings_above_16_rows_as_one_concatenated_layer(case):
     layer.backward()
     torch.cuda.synchronize()
     y, dA, dB = oracle.widen(layer.host_y(), dtype), layer.host_dA(), layer.host_dB()
-    errs, dx_ref, row = {}, 0.0, 0
+    rep = Report(f"concatenated siblings N={Ns} M={M}", dtype)
+    dx_ref, dx_bound, row = 0.0, 0.0, 0
+    sc = c0.alpha / r
     for i, inp in enumerate(inps):
         lo, n = make_oracle(inp), inp.cfg.N
-        y_ref, _ = lo.forward(inp.x)
+        y_ref, t_ref = lo.forward(inp.x)
         dx_ref = dx_ref + lo.backward_dx(inp.dy)
         dA_ref, dB_ref = lo.backward_adapters(inp.dy, inp.x)
-        errs[f"y{i}"] = rel_fro(y[:, row:row + n], y_ref)
-        errs[f"dA{i}"] = rel_fro(dA[i * r:(i + 1) * r], dA_ref)
-        errs[f"dB{i}"] = rel_fro(dB[row:row + n, i * r:(i + 1) * r], dB_ref)
+        xw, dyw = oracle.widen(inp.x, dtype), oracle.widen(inp.dy, dtype)
+        b = layer_bounds(lo.Wd, lo.A, lo.B, sc, x=xw, dy=dyw, t=t_ref, u=oracle.lora_u(dyw, lo.B), x_adapter=xw)
+        dx_bound = dx_bound + b["dx"]
+        rep.add(f"y{i}", y[:, row:row + n], y_ref, lines="rows", bound=b["y"])
+        rep.add(f"dA{i}", dA[i * r:(i + 1) * r], dA_ref, lines="rows", bound=b["dA"])
+        rep.add(f"dB{i}", dB[row:row + n, i * r:(i + 1) * r], dB_ref, lines="cols", bound=b["dB"])
         row += n
-    errs["dx"] = rel_fro(oracle.widen(layer.host_dx(), dtype), dx_ref)
-    announce(" ".join(f"{k}={v:.2e}" for k, v in errs.items()))
-    for k, v in errs.items():
-        assert np.isfinite(v) and v <= TOL, f"rel. Frobenius error of {k} = {v:.3e} > {TOL}"
+    rep.add("dx", oracle.widen(layer.host_dx(), dtype), dx_ref, lines="rows", bound=dx_bound)
+    rep.finish()

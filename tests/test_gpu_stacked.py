@@ -4,7 +4,7 @@ import pytest
 
 import oracle
 from paper_2306_08162_amd import binding as ql
-from parity import TOL, announce, make_oracle, rel_fro, small_inputs
+from parity import Report, announce, layer_bounds, make_oracle, small_inputs
 
 pytestmark = pytest.mark.gpu
 
@@ -42,12 +42,16 @@ def test_stacked_backward(case, beta):
     x, dy = oracle.widen(inp.x, dtype), oracle.widen(inp.dy, dtype)
     A, B = oracle.widen(inp.A, dtype), oracle.widen(inp.B, dtype)
     dA_ref, dB_ref = oracle.backward_adapters_stacked(dy, x, A, B, c.alpha, f)
-    errs = {"dx": rel_fro(oracle.widen(layer.host_dx(), dtype), dx_ref),
-            "dA": rel_fro(dA_t.cpu().numpy(), beta * 0.5 + dA_ref),
-            "dB": rel_fro(dB_t.cpu().numpy(), beta * -1.5 + dB_ref)}
-    announce(" ".join(f"{k}={v:.2e}" for k, v in errs.items()))
-    for k, v in errs.items():
-        assert np.isfinite(v) and v <= TOL, f"{c.name}: rel. Frobenius error of {k} = {v:.3e} > {TOL}"
+    sc = c.alpha / r
+    t_ref, u_ref = oracle.lora_down(x, A), oracle.lora_u(dy, B)
+    bounds = layer_bounds(lo.Wd, A, B, sc, dy=dy, t=t_ref, u=u_ref, x_adapter=x)
+    rep = Report(f"stacked {c.name} f={f} beta={beta}", dtype)
+    rep.add("dx", oracle.widen(layer.host_dx(), dtype), dx_ref, lines="rows", bound=bounds["dx"])
+    rep.add("dA", dA_t.cpu().numpy(), beta * 0.5 + dA_ref, bound=bounds["dA"][f:, :] + 1e-3 * beta)
+    rep.add("dB", dB_t.cpu().numpy(), beta * -1.5 + dB_ref, bound=bounds["dB"][:, f:] + 1e-3 * beta)
+    rep.add("dA_new", dA_t.cpu().numpy() - beta * 0.5, dA_ref, lines="rows")
+    rep.add("dB_new", dB_t.cpu().numpy() - beta * -1.5, dB_ref, lines="cols")
+    rep.finish()
 
 
 def test_stacked_with_nothing_frozen_is_the_plain_backward():
