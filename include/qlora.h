@@ -68,7 +68,8 @@ typedef enum {
     QLORA_E_ALIGN = 7,      /* a pointer is not 16-byte aligned */
     QLORA_E_WORKSPACE = 8,  /* workspace NULL or smaller than qlora_workspace_bytes() */
     QLORA_E_HIP = 9,        /* the HIP runtime reported an error at launch */
-    QLORA_E_GIDX = 10       /* a group index is out of range, or a group does not own exactly group_size columns */
+    QLORA_E_GIDX = 10,      /* a group index is out of range, or a group does not own exactly group_size columns */
+    QLORA_E_STATIC = 11     /* qlora_linear_fwd_static: the problem needs more scratch than QLORA_STATIC_SCRATCH_BYTES */
 } qlora_status_t;
 
 /* Host pointer to a static, NUL-terminated description of `status`. */
@@ -159,6 +160,24 @@ int qlora_linear_fwd(const void *x, const uint32_t *packed, const void *scales, 
                      const void *A, const void *B, void *y, void *t_save,
                      int M, int N, int K, int bits, int group_size, int rank, float alpha, int dtype,
                      void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * qlora_linear_fwd for callers that cannot allocate device memory and have no workspace to pass: code under HIP graph
+ * capture, serving loops with a fixed memory plan, harnesses that forbid hipMalloc.  Same arguments and results as
+ * qlora_linear_fwd without the workspace pair: the scratch the pass needs (t when it is not saved; the fp32 planes
+ * of a split contraction) lives in a static device array of QLORA_STATIC_SCRATCH_BYTES inside the library, which
+ * every GPU the library runs on holds until the process ends.  The call allocates and frees nothing.  Problems that
+ * need more scratch are refused with QLORA_E_STATIC before anything is launched (the LLaMA-7B projections fit at
+ * every token count).  Nothing in the scratch has to start at zero, and nothing is carried from call to call; but
+ * all calls on one GPU share the one array, so two calls that overlap in time on the same GPU (different streams or
+ * host threads) race: serialise them, or give the others a workspace through qlora_linear_fwd.  The first call on a
+ * device looks the array's address up; make that call before a graph capture begins.
+ */
+#define QLORA_STATIC_SCRATCH_BYTES (32u << 20)
+int qlora_linear_fwd_static(const void *x, const uint32_t *packed, const void *scales, const uint8_t *zeros,
+                            const void *A, const void *B, void *y, void *t_save,
+                            int M, int N, int K, int bits, int group_size, int rank, float alpha, int dtype,
+                            void *stream);
 
 /*
  * Backward pass (Fig. 1, backward path; Sec. 3.1).  Writes dx [M,K] in `dtype`,

@@ -16,13 +16,14 @@ LIB_PATH = os.path.join(HERE, "libqlora.so")
 
 QLORA_F16, QLORA_BF16 = 0, 1
 STATUS_NAMES = ["QLORA_OK", "QLORA_E_NULL", "QLORA_E_BITS", "QLORA_E_SHAPE", "QLORA_E_GROUP", "QLORA_E_RANK",
-                "QLORA_E_DTYPE", "QLORA_E_ALIGN", "QLORA_E_WORKSPACE", "QLORA_E_HIP", "QLORA_E_GIDX"]
+                "QLORA_E_DTYPE", "QLORA_E_ALIGN", "QLORA_E_WORKSPACE", "QLORA_E_HIP", "QLORA_E_GIDX", "QLORA_E_STATIC"]
+STATIC_SCRATCH_BYTES = 32 << 20
 EXPORTS = ["qlora_status_string", "qlora_packed_words", "qlora_workspace_bytes", "qlora_pack", "qlora_unpack",
            "qlora_actorder_perm", "qlora_pack_permuted", "qlora_gather_columns",
            "qlora_packed_zero_words", "qlora_pack_zeros", "qlora_unpack_zeros",
            "qlora_linear_fwd", "qlora_linear_bwd", "qlora_linear_bwd_accumulate", "qlora_linear_fwd_dropout",
            "qlora_linear_bwd_dropout", "qlora_linear_bwd_stacked", "qlora_siblings_workspace_bytes", "qlora_linear_fwd_siblings",
-           "qlora_linear_bwd_siblings", "qlora_lrec_workspace_bytes", "qlora_lrec_loss", "qlora_lrec_loss_scaled"]
+           "qlora_linear_bwd_siblings", "qlora_lrec_workspace_bytes", "qlora_lrec_loss", "qlora_lrec_loss_scaled", "qlora_linear_fwd_static"]
 BENCH_EXPORTS = ["qlora_profile_gemm", "qlora_profile_gemm_span"]        # include/qlora_bench.h
 MAX_SIBLINGS, SIBLINGS_MAX_M = 4, 16
 
@@ -74,6 +75,8 @@ def load() -> ctypes.CDLL:
     lib.qlora_linear_fwd.argtypes = [vp] * 8 + [c_int] * 6 + [f32, c_int, vp, c_sz, vp]
     lib.qlora_linear_bwd.restype = c_int
     lib.qlora_linear_bwd.argtypes = [vp] * 11 + [c_int] * 6 + [f32, c_int, vp, c_sz, vp]
+    lib.qlora_linear_fwd_static.restype = c_int
+    lib.qlora_linear_fwd_static.argtypes = [vp] * 8 + [c_int] * 6 + [f32, c_int, vp]
     lib.qlora_profile_gemm.restype = c_int
     lib.qlora_profile_gemm.argtypes = [vp, vp]
     lib.qlora_profile_gemm_span.restype = c_int
@@ -214,6 +217,16 @@ def qlora_linear_fwd(x, packed, scales, zeros, A, B, y, t_save, M: int, N: int, 
                                  _ptr(workspace), workspace_bytes, _stream(stream))
     if check and st != 0:
         raise QLoraError(st, "qlora_linear_fwd")
+    return st
+
+
+def qlora_linear_fwd_static(x, packed, scales, zeros, A, B, y, t_save, M: int, N: int, K: int, bits: int,
+                            group_size: int, rank: int, alpha: float, dtype: int, stream=None, check: bool = True) -> int:
+    st = load().qlora_linear_fwd_static(_ptr(x), _ptr(packed), _ptr(scales), _ptr(zeros), _ptr(A), _ptr(B), _ptr(y),
+                                        _ptr(t_save), M, N, K, bits, group_size, rank, float(alpha), dtype,
+                                        _stream(stream))
+    if check and st != 0:
+        raise QLoraError(st, "qlora_linear_fwd_static")
     return st
 
 

@@ -7,6 +7,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <mutex>
 #include <vector>
 
 using namespace qlora;
@@ -124,6 +125,7 @@ const char *qlora_status_string(int status)
     case QLORA_E_WORKSPACE: return "workspace is NULL or smaller than qlora_workspace_bytes()";
     case QLORA_E_HIP: return "the HIP runtime reported an error";
     case QLORA_E_GIDX: return "group index out of range, or a group without exactly group_size columns";
+    case QLORA_E_STATIC: return "the problem needs more scratch than the static device array holds: use qlora_linear_fwd with a workspace";
     default: return "unknown status";
     }
 }
@@ -303,6 +305,60 @@ int qlora_linear_fwd_dropout(const void *x, const uint32_t *packed, const void *
     if (st != QLORA_OK) return st;
     return forward(x, packed, scales, zeros, A, B, keep_mask, keep_scale, y, t_save, M, N, K, bits, group_size, rank,
                    alpha, dtype, (char *)workspace, carve(M, N, K, rank, bits), workspace_bytes, stream);
+}
+
+// ---- the forward pass for callers that cannot allocate: its scratch is a static device array ----------------------
+namespace {
+
+__device__ __align__(256) unsigned char scratch[QLORA_STATIC_SCRATCH_BYTES];
+
+// Device address of this GPU's copy of `scratch` (every GPU holds its own, at its own address), looked up once per
+// device.  In host code the array's name is only a handle for the runtime, never an address a kernel could use.
+void *static_scratch()
+{
+    constexpr int MAX_DEVICES = 64;
+    static std::mutex mu;
+    static void *ptr[MAX_DEVICES] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return nullptr;
+    std::lock_guard<std::mutex> guard(mu);
+    if (!ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        ptr[dev] = p;
+    }
+    return ptr[dev];
+}
+
+// what the forward pass alone needs of a workspace: t, and the planes of a split contraction
+Workspace carve_forward(int M, int N, int K, int r)
+{
+    Workspace w{};
+    w.t_off = 0;
+    w.split_off = round_up((size_t)M * r * 2);
+    const size_t sf = (size_t)gemm_splits(M, N, K);
+    w.total = w.split_off + (M > SMALL_M_FWD_MAX && sf > 1 ? round_up(sf * M * N * sizeof(float)) : 0);
+    if (w.total < ALIGN) w.total = ALIGN;
+    return w;
+}
+
+}  // namespace
+
+int qlora_linear_fwd_static(const void *x, const uint32_t *packed, const void *scales, const uint8_t *zeros,
+                            const void *A, const void *B, void *y, void *t_save, int M, int N, int K, int bits,
+                            int group_size, int rank, float alpha, int dtype, void *stream)
+{
+    const int st = check_problem(M, N, K, bits, group_size, rank, dtype);
+    if (st != QLORA_OK) return st;
+    const Workspace w = carve_forward(M, N, K, rank);
+    if (w.total > (size_t)QLORA_STATIC_SCRATCH_BYTES) return QLORA_E_STATIC;   // before anything touches the device
+    void *ws = static_scratch();
+    if (!ws) return QLORA_E_HIP;
+    return forward(x, packed, scales, zeros, A, B, nullptr, 1.f, y, t_save, M, N, K, bits, group_size, rank, alpha,
+                   dtype, (char *)ws, w, (size_t)QLORA_STATIC_SCRATCH_BYTES, stream);
 }
 
 int qlora_linear_bwd(const void *dy, const void *x, const uint32_t *packed, const void *scales, const uint8_t *zeros,
