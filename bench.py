@@ -31,15 +31,13 @@ def _mean(v):
     return sum(v) / len(v)
 
 
-def run_headline(steps: int, warmup: int):
+def run_headline(inp, steps: int, warmup: int):
     import torch
     from paper_2306_08162_amd import binding as ql
-    from paper_2306_08162_amd import workloads as wl
     from paper_2306_08162_amd.device import DeviceLayer
     from paper_2306_08162_amd.hiprt import Event
 
-    cfg = wl.config2()
-    inp = wl.make_inputs(cfg)
+    cfg = inp.cfg
     layer = DeviceLayer(inp, "cuda:0")
     stream = torch.cuda.current_stream().cuda_stream or None
 
@@ -84,7 +82,7 @@ def run_headline(steps: int, warmup: int):
     diff_ms = None
     if fwd[1] is not None and fwd[2] is not None:
         diff_ms = {"fwd": fwd[1] - fwd[2], "bwd": bwd[1] - bwd[2]}
-    return cfg, inp, layer, ms_per_step, fwd_ms, bwd_ms, diff_ms
+    return cfg, layer, ms_per_step, fwd_ms, bwd_ms, diff_ms
 
 
 def _graph_time(launch_all, iters: int):
@@ -117,7 +115,7 @@ def _graph_time(launch_all, iters: int):
     return e0.elapsed_ms(e1) * 1e3 / iters       # microseconds per replay
 
 
-def run_small_m(M: int = 16, iters: int = 5):
+def run_small_m(M: int = 16, iters: int = 5, headline_layer: bool = True):
     """Packed-weight GB/s at M tokens.
 
     Every measured burst walks a pool of distinct weight sets larger than 1 GB (the last-level cache is 256 MB),
@@ -164,10 +162,11 @@ def run_small_m(M: int = 16, iters: int = 5):
         return label, out
 
     results = {}
-    q4 = DeviceLayer(wl.make_inputs(wl.config2().with_tokens(M)), "cuda:0")
-    k, v = measure([q4], "q_proj_int4")
-    results[k] = v
-    del q4
+    if headline_layer:
+        q4 = DeviceLayer(wl.make_inputs(wl.config2().with_tokens(M)), "cuda:0")
+        k, v = measure([q4], "q_proj_int4")
+        results[k] = v
+        del q4
     for bits in (2, 8):
         cfgs = wl.config5(bits, M)
         by_shape = {}
@@ -193,13 +192,93 @@ def run_small_m(M: int = 16, iters: int = 5):
         tot_us = sum(results[k]["fwd"]["us_per_set"] + results[k]["bwd"]["us_per_set"] for k in keys)
         return round(tot_b / tot_us * 1e-3, 1)
 
-    per_layer = overall(["q_proj_int4", "decoder_block_int2", "decoder_block_int8"])
-    siblings = overall(["q_proj_int4", "decoder_block_int2_sibling_calls", "decoder_block_int8_sibling_calls"])
+    first = ["q_proj_int4"] if headline_layer else []
+    per_layer = overall(first + ["decoder_block_int2", "decoder_block_int8"])
+    siblings = overall(first + ["decoder_block_int2_sibling_calls", "decoder_block_int8_sibling_calls"])
     results["all_fwd_bwd_packed_weight_GBps"] = per_layer                       # one call per projection
     results["all_frac_of_hbm_peak"] = round(per_layer / PEAK_HBM_GBPS, 4)
     results["all_sibling_calls_fwd_bwd_packed_weight_GBps"] = siblings           # q/k/v and gate/up together
     results["all_sibling_calls_frac_of_hbm_peak"] = round(siblings / PEAK_HBM_GBPS, 4)
     return results
+
+
+def _event_time(call, warm: int, iters: int) -> float:
+    """Microseconds per call of `call`, HIP events on the stream the library launches on around `iters` back-to-back
+    calls (for passes long enough that issuing them from Python does not starve the GPU)."""
+    import torch
+    from paper_2306_08162_amd.hiprt import Event
+    for _ in range(warm):
+        call()
+    torch.cuda.synchronize()
+    stream = torch.cuda.current_stream().cuda_stream or None
+    e0, e1 = Event(), Event()
+    e0.record(stream)
+    for _ in range(iters):
+        call()
+    e1.record(stream)
+    e1.synchronize()
+    return e0.elapsed_ms(e1) * 1e3 / iters
+
+
+def _layer_times(cfg, graph: bool):
+    """Forward and backward microseconds of one layer drawn on the device.  graph: replay a captured burst that
+    rotates weight copies beyond the last-level cache (passes of tens of microseconds); else plain event timing."""
+    import torch
+    from paper_2306_08162_amd.device import DeviceLayer
+    layer = DeviceLayer.drawn_on_device(cfg)
+    if not graph:
+        us = {"fwd": _event_time(layer.forward, 5, 20), "bwd": _event_time(layer.backward, 5, 20)}
+    else:
+        wbytes = cfg.weight_side_bytes
+        copies = max(2, min(32, 1 + (300 << 20) // wbytes))
+        pool = [(layer.packed, layer.scales, layer.zeros)] + [
+            (layer.packed.clone(), layer.scales.clone(), layer.zeros.clone()) for _ in range(copies - 1)]
+
+        def sweep(which):
+            for pk, sc, zr in pool:
+                layer.packed, layer.scales, layer.zeros = pk, sc, zr
+                (layer.forward if which == "fwd" else layer.backward)()
+
+        us = {w: _graph_time(lambda w=w: sweep(w), 5) / copies for w in ("fwd", "bwd")}
+    del layer
+    torch.cuda.empty_cache()
+    return us
+
+
+def run_configs():
+    """The other named workloads, timed in the library's own launch configuration: config 3 (gate/up, INT2, bf16,
+    rank 16), config 4 (down, INT3 stream, M = 4096) and the decoder block of config 5 at INT2 and INT8 for M = 256
+    and M = 4096 (its M = 1 and M = 16 passes are priced in GB/s under "small_m").  TFLOP/s counts 4MNK + 6Mr(K+N)
+    per forward + backward; the fraction is of the fp16 / bf16 MFMA peak."""
+    from paper_2306_08162_amd import workloads as wl
+    out = {}
+
+    def entry(cfgs_with_mult, graph):
+        f_us = b_us = 0.0
+        flops = 0
+        shapes = {}
+        for cfg, mult in cfgs_with_mult:
+            us = _layer_times(cfg, graph)
+            f_us += mult * us["fwd"]
+            b_us += mult * us["bwd"]
+            flops += mult * cfg.flops_fwd_bwd
+            shapes[f"{cfg.K}x{cfg.N}"] = {"fwd_us": round(us["fwd"], 1), "bwd_us": round(us["bwd"], 1),
+                                          "TFLOPs": round(cfg.flops_fwd_bwd / (us["fwd"] + us["bwd"]) * 1e-6, 1)}
+        tf = flops / (f_us + b_us) * 1e-6
+        return {"fwd_us": round(f_us, 1), "bwd_us": round(b_us, 1), "TFLOPs": round(tf, 1),
+                "frac_of_mfma_peak": round(tf / PEAK_MFMA_F16_TFLOPS, 4), "per_shape_KxN": shapes}
+
+    for cfg in (wl.config3(), wl.config4()):
+        e = entry([(cfg, 1)], graph=False)
+        e.pop("per_shape_KxN")
+        e["workload"] = f"M={cfg.M} K={cfg.K} N={cfg.N} INT{cfg.bits} G={cfg.group_size} r={cfg.rank} {cfg.dtype}"
+        out[cfg.name] = e
+    for bits in (2, 8):
+        for M in (256, 4096):
+            block = {c.name.split("_")[1]: c for c in wl.config5(bits, M)}
+            out[f"c5_decoder_block_int{bits}_M{M}"] = entry([(block["q"], 4), (block["gate"], 2), (block["down"], 1)],
+                                                            graph=M <= 512)
+    return out
 
 
 def run_lrec_loss(M: int = 2048, V: int = 32000, iters: int = 20):
@@ -424,7 +503,23 @@ def main() -> int:
         dst.copy_(src)              # reads 1 GiB, writes 1 GiB: far larger than every cache
         torch.cuda.synchronize()
         del src, dst
-    cfg, inp, layer, ms_per_step, fwd_ms, bwd_ms, diff_ms = run_headline(args.steps, args.warmup)
+    from paper_2306_08162_amd import workloads as wl
+    inp = wl.make_inputs(wl.config2())      # drawn on the host first, so that nothing but the upload separates the
+                                            # sections below from the headline's warm-up steps
+    # The sections that widen the headline run first: the headline's W warm-up steps and K timed steps then start on a
+    # GPU that has been working for seconds, as a layer inside a training job does (with W = 5 and K = 20 after an idle
+    # stretch the whole measurement would sit inside the few milliseconds the clocks take to come up).
+    extras = {}
+    if not args.no_small_m:
+        extras["configs"] = run_configs()
+        extras["small_m"] = {"M": 16, "timing": "HIP-graph replays over a >1 GB pool of distinct weight sets",
+                             **run_small_m(16)}
+        extras["small_m_M1"] = {"M": 1, "timing": "as small_m", **run_small_m(1, headline_layer=False)}
+        extras["lrec_loss"] = run_lrec_loss()
+        extras["actorder_gather"] = run_actorder_gather()
+        extras["stacked_adapters"] = run_stacked()
+    cfg, layer, ms_per_step, fwd_ms, bwd_ms, diff_ms = run_headline(inp, args.steps, args.warmup)
+    del layer
     flops = cfg.flops_fwd_bwd
     value = flops / (ms_per_step * 1e-3) / 1e12
 
@@ -436,7 +531,9 @@ def main() -> int:
     achieved = gemm_flops[dom] / (gemm_ms[dom] * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": f"qgemm_kernel ({dom} GEMM, INT4 fp16)", "achieved": round(achieved, 2),
                 "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_MFMA_F16_TFLOPS, 4),
-                "traffic": GEMM_TRAFFIC_BYTES[dom], "traffic_unit": "bytes per launch (rocprofv3 pmc, see profiles/)",
+                "traffic": GEMM_TRAFFIC_BYTES[dom],
+                "traffic_unit": "bytes per launch, not measured in this run: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE "
+                                "runs of this command, see profiles/qgemm_c2_hbm_traffic.md",
                 "kernel_us": {k: round(v * 1e3, 2) for k, v in gemm_ms.items()},
                 "kernel_us_lower_bound": {k: round(v * 1e3, 2) for k, v in diff_ms.items()} if diff_ms else None,
                 "kernel_tflops": {k: round(gemm_flops[k] / (gemm_ms[k] * 1e-3) / 1e12, 2) for k in gemm_ms}}
@@ -452,13 +549,7 @@ def main() -> int:
         "frac_of_mfma_peak": round(value / PEAK_MFMA_F16_TFLOPS, 4),
         "roofline": roofline,
     }
-    if not args.no_small_m:
-        del layer
-        result["small_m"] = {"M": 16, "timing": "HIP-graph replays over a >1 GB pool of distinct weight sets",
-                             **run_small_m(16)}
-        result["lrec_loss"] = run_lrec_loss()
-        result["actorder_gather"] = run_actorder_gather()
-        result["stacked_adapters"] = run_stacked()
+    result.update(extras)
     if args.library_context:
         result["dense_library_context"] = run_dense_library_context(cfg.M, cfg.K, cfg.N)
     if not args.no_cpu_baseline:

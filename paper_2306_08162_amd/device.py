@@ -52,6 +52,47 @@ class DeviceLayer:
             raise ValueError(f"shape not accepted by the library: {c}")
         self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
 
+    @classmethod
+    def drawn_on_device(cls, cfg: LayerConfig, device: str = "cuda:0", seed: int = 0) -> "DeviceLayer":
+        """The same layer with every tensor drawn by torch's seeded generator on the GPU instead of uploaded from the
+        host generators: same shapes, dtypes and value distributions (uniform codes and zero-points, uniform scales,
+        A ~ N(0, 1/K), B ~ N(0, 0.01), x and dY ~ N(0, 1)).  For timing runs of the large shapes, where drawing
+        10^8 numbers on the host would take longer than the measurement; the parity tests use the host generators."""
+        self = cls.__new__(cls)
+        c = cfg
+        dev = torch.device(device)
+        g = torch.Generator(device=dev)
+        g.manual_seed(cfg.seed + seed)
+        f16 = torch.bfloat16 if c.dtype == "bf16" else torch.float16
+
+        def bits16(t, dt):
+            return t.to(dt).view(torch.int16).contiguous()
+
+        self.cfg, self.device = c, dev
+        self.dtype_flag = ql.QLORA_BF16 if c.dtype == "bf16" else ql.QLORA_F16
+        self.codes = torch.randint(0, 1 << c.bits, (c.N, c.K), dtype=torch.uint8, device=dev, generator=g)
+        sc = torch.rand((c.N, c.groups), device=dev, generator=g) * (c.scale_hi - c.scale_lo) + c.scale_lo
+        self.scales = bits16(sc, torch.float16)
+        self.zeros = torch.randint(0, 1 << c.bits, (c.N, c.groups), dtype=torch.uint8, device=dev, generator=g)
+        r = max(c.rank, 1)
+        self.A = bits16(torch.randn((r, c.K), device=dev, generator=g) * c.K ** -0.5, f16) if c.rank else None
+        self.B = bits16(torch.randn((c.N, r), device=dev, generator=g) * 0.1, f16) if c.rank else None
+        self.packed = torch.empty((c.N, c.words_per_row), dtype=torch.int32, device=dev)
+        ql.qlora_pack(self.codes, self.packed, c.N, c.K, c.bits)
+        self.codes = None                                   # only the packed form stays resident
+        self.x = bits16(torch.randn((c.M, c.K), device=dev, generator=g), f16)
+        self.dy = bits16(torch.randn((c.M, c.N), device=dev, generator=g), f16)
+        self.y = torch.empty((c.M, c.N), dtype=torch.int16, device=dev)
+        self.dx = torch.empty((c.M, c.K), dtype=torch.int16, device=dev)
+        self.t = torch.empty((c.M, r), dtype=torch.int16, device=dev)
+        self.dA = torch.empty((r, c.K), dtype=torch.float32, device=dev)
+        self.dB = torch.empty((c.N, r), dtype=torch.float32, device=dev)
+        nbytes = ql.qlora_workspace_bytes(c.M, c.N, c.K, c.bits, c.group_size, c.rank)
+        if nbytes == 0:
+            raise ValueError(f"shape not accepted by the library: {c}")
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        return self
+
     # -- calls through the C ABI -------------------------------------------------
     def forward(self, save_t: bool = True, stream=None):
         c = self.cfg
