@@ -57,10 +57,13 @@ __device__ __forceinline__ uint32_t spread_byte(uint32_t x, int b)
 
 __device__ __forceinline__ uint32_t h2_bits(half2_t v) { return __builtin_bit_cast(uint32_t, v); }
 
+// SCALE false: the exact integers q - z are returned and the caller applies the group's scale to its sums
+template <bool SCALE = true>
 __device__ __forceinline__ uint32_t fp16_pair(uint32_t bits, half2_t mul, half2_t off, half2_t s2)
 {
     const half2_t h = __builtin_bit_cast(half2_t, bits);
-    return h2_bits((h * mul + off) * s2);
+    if constexpr (SCALE) return h2_bits((h * mul + off) * s2);
+    else return h2_bits(h * mul + off);
 }
 
 // 32-bit window of the unit starting at bit `bit` (compile-time after unrolling).
@@ -73,7 +76,7 @@ __device__ __forceinline__ uint32_t window(const uint32_t (&w)[BITS], int bit)
     return __builtin_amdgcn_alignbit(hi, w[wi], (uint32_t)sh);
 }
 
-template <int BITS, bool BF16>
+template <int BITS, bool BF16, bool SCALE = true>     // SCALE false: c was set with scale 1, the result is q - z
 __device__ __forceinline__ u16x8_t dequant8(const uint32_t (&w)[BITS], int part, const DequantConst<BITS, BF16> &c)
 {
     u32x4_t out;
@@ -84,15 +87,15 @@ __device__ __forceinline__ u16x8_t dequant8(const uint32_t (&w)[BITS], int part,
             const half2_t mul = {(half_t)1.f, (half_t)0.0625f};
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                out[i] = fp16_pair(spread_byte(x, i) & (0x00F0000Fu | MAGIC), mul, c.off[0], c.s2);
+                out[i] = fp16_pair<SCALE>(spread_byte(x, i) & (0x00F0000Fu | MAGIC), mul, c.off[0], c.s2);
         } else if constexpr (BITS == 2) {
             const uint32_t x = w[part >> 1];
             const half2_t mul0 = {(half_t)1.f, (half_t)0.25f}, mul1 = {(half_t)0.0625f, (half_t)0.015625f};
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
                 const uint32_t p = spread_byte(x, 2 * (part & 1) + i);
-                out[2 * i] = fp16_pair(p & (0x000C0003u | MAGIC), mul0, c.off[0], c.s2);
-                out[2 * i + 1] = fp16_pair(p & (0x00C00030u | MAGIC), mul1, c.off[1], c.s2);
+                out[2 * i] = fp16_pair<SCALE>(p & (0x000C0003u | MAGIC), mul0, c.off[0], c.s2);
+                out[2 * i + 1] = fp16_pair<SCALE>(p & (0x00C00030u | MAGIC), mul1, c.off[1], c.s2);
             }
         } else if constexpr (BITS == 8) {
             const half2_t one = {(half_t)1.f, (half_t)1.f};
@@ -100,14 +103,14 @@ __device__ __forceinline__ u16x8_t dequant8(const uint32_t (&w)[BITS], int part,
             for (int i = 0; i < 4; ++i) {
                 const uint32_t x = w[2 * part + (i >> 1)];
                 const uint32_t sel = (i & 1) ? 0x05030502u : 0x05010500u;   // [b0,0x64,b1,0x64] or [b2,0x64,b3,0x64]
-                out[i] = fp16_pair(__builtin_amdgcn_perm(MAGIC, x, sel), one, c.off[0], c.s2);
+                out[i] = fp16_pair<SCALE>(__builtin_amdgcn_perm(MAGIC, x, sel), one, c.off[0], c.s2);
             }
         } else {   // BITS == 3: eight codes = 24 bits starting at bit 24*part
             const uint32_t x = window<BITS>(w, 24 * part);
             const half2_t mul = {(half_t)1.f, (half_t)0.125f};
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                out[i] = fp16_pair(spread_byte(x >> (6 * i), 0) & (0x00380007u | MAGIC), mul, c.off[0], c.s2);
+                out[i] = fp16_pair<SCALE>(spread_byte(x >> (6 * i), 0) & (0x00380007u | MAGIC), mul, c.off[0], c.s2);
         }
     } else {
         constexpr uint32_t mask = (1u << BITS) - 1u;

@@ -489,11 +489,23 @@ void launch_fwd_staged(const FwdMulti &m, int rg, hipStream_t s)
     }
 }
 
+}  // namespace
+
+}  // namespace qlora
+
+#include "gemv_fwd_m16.hpp"
+
+namespace qlora {
+
+namespace {
+
 template <int BITS, bool BF16>
 void launch_fwd_mb(const FwdMulti &m, int rg, hipStream_t s)
 {
     switch ((m.p[0].M + 15) / 16) {
-    case 1: launch_fwd_staged<BITS, BF16, 1>(m, rg, s); break;
+    case 1:
+        if (!launch_fwd_m16<BITS, BF16>(m, rg, s)) launch_fwd_staged<BITS, BF16, 1>(m, rg, s);
+        break;
     case 2:
         for (int i = 0; i < m.count; ++i) {
             FwdMulti one{};

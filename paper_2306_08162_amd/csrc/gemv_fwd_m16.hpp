@@ -1,0 +1,369 @@
+// Forward pass for up to 16 token rows with the packed weight staged through LDS (included by gemv_fwd_impl.hpp).
+//
+// What bounds the pass at this size is the number of memory instructions and cache lines a compute unit has to work
+// through, not the bytes: a lane that fetches its own MFMA fragment of a 2-bit weight touches 8 bytes of a row, so a
+// wave instruction brings in sixteen 32-byte pieces, and the group constants cost two more such instructions per
+// fragment.  Here nothing is fetched fragment-wise.  A workgroup of eight waves owns 16 NB weight rows and walks K in
+// stages of 1024: per stage the packed words of all its rows (row segments of 128 BITS bytes, whole cache lines),
+// sixteen token rows of x and the adapter rows of A arrive by direct-to-LDS loads of 1 KB per instruction, two stages
+// deep, and every wave takes the fragments of its 128 contraction indices from LDS.  The group constants of all the
+// workgroup's rows are copied to LDS once, at the start.
+//
+// Layout of a stage in LDS: per wave a 16-row x 128-column slice of x and an AR-row slice of A, both as in the staged
+// kernel (piece c of row w in slot 16 w + (c ^ w)); then the weight chunk, row n at n * 128 BITS bytes, its 16-byte
+// pieces permuted by wswz() so that sixteen rows read at one piece index fall on different banks.
+#pragma once
+
+namespace qlora {
+
+namespace {
+
+constexpr int M16_NW = 8;                  // waves of a workgroup; wave w owns columns 128 w .. 128 w + 128 of a stage
+constexpr int M16_KC = 128 * M16_NW;       // contraction indices per stage
+constexpr int M16_LDS = 160 * 1024;
+
+// slot of the 16-byte piece `piece` of weight row n inside the row's stage segment (its own inverse)
+template <int BITS>
+__device__ __forceinline__ int wswz(int n, int piece)
+{
+    if constexpr (BITS == 3) return 3 * ((piece / 3) ^ (n & 7)) + piece % 3;       // whole units of 12 bytes stay together
+    else return piece ^ (n & 15);
+}
+
+constexpr int m16_xa(int ar) { return 4096 + ar * 256; }                                      // a wave's slices
+constexpr int m16_stage(int bits, int nb, int ar) { return M16_NW * m16_xa(ar) + nb * 16 * 128 * bits; }
+constexpr int m16_table(int nb, int ng)                                                       // scales (2 B), zero-points (1 B),
+{                                                                                             // each filled in whole KB
+    return ((nb * 16 * ng * 2 + 1023) & ~1023) + ((nb * 16 * ng + 1023) & ~1023);
+}
+constexpr int m16_tc(int ar) { return ar > 0 ? 16 : 64; }                                     // columns of t kept
+constexpr int m16_static(int ar) { return 16 * (m16_tc(ar) + 1) * 4; }
+
+template <int BITS, bool BF16, int NB, int AR>     // NB 16-row weight blocks; AR rows of A staged (0: t is given, or no adapter)
+__device__ __forceinline__ void gemv_fwd_m16_body(const FwdArgs &a, const int wg)
+{
+    constexpr int NW = M16_NW, NT = NW * 64, R = 16 * NB, PPR = 8 * BITS, UB = 4 * BITS;
+    constexpr int XA = m16_xa(AR), WOFF = NW * XA, STAGE = m16_stage(BITS, NB, AR);
+    constexpr int WI = R * PPR / 64;                         // weight instructions per stage, dealt out wave by wave
+    constexpr int WI_HI = (WI + NW - 1) / NW, WI_LO = WI / NW;
+    constexpr int XI = 4 + AR / 4;                           // instructions of a wave's own slices
+    constexpr int TC = m16_tc(AR);
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    __shared__ float tfull[16][TC + 1];
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int li = lane & 15, q = lane >> 4;
+    const int n0 = wg * R, K = a.K, Kw = K * BITS / 32, r = a.r, ng = a.ng;
+    const int rows_here = min(R, a.N - n0);                  // at least one
+    const int S = (K + M16_KC - 1) / M16_KC;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)lds;
+    const uint16_t *sct = (const uint16_t *)(lds + 2 * STAGE);                          // [R][ng], then, from the next
+    const uint8_t *zt = lds + 2 * STAGE + ((R * ng * 2 + 1023) & ~1023);                // full KB on, the zero-points
+
+    // ---- this lane's part of the copies.  Weight instruction i of a stage fills slots 64 i .. 64 i + 64 of the chunk.
+    const uint32_t *wbase = a.packed + (long)n0 * Kw;
+    const uint32_t row_bytes = (uint32_t)Kw * 4u;
+    uint32_t w_src[WI_HI], w_piece[WI_HI];                   // byte offset of the row; byte position of the piece in a stage
+#pragma unroll
+    for (int c = 0; c < WI_HI; ++c) {
+        const int e = 64 * (wave + NW * c) + lane, n = min(e / PPR, R - 1), slot = e % PPR;
+        w_src[c] = (uint32_t)min(n, rows_here - 1) * row_bytes;
+        w_piece[c] = (uint32_t)wswz<BITS>(n, slot) * 16u;
+    }
+    uint32_t x_src[4], a_src[AR > 0 ? AR / 4 : 1];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int w16 = 4 * j + (lane >> 4), piece = (lane & 15) ^ w16;
+        x_src[j] = (uint32_t)(((long)min(w16, a.M - 1) * K + 8 * piece) * 2);
+        if (AR > 0 && 4 * j < AR) a_src[j] = (uint32_t)(((long)min(w16, r - 1) * K + 8 * piece) * 2);
+    }
+    // the requests of one stage, one at a time (they are spread over the arithmetic of the stage before: a request
+    // waits for room in the memory pipeline, and meanwhile the wave could be multiplying)
+    constexpr int NS = WI_HI + XI;
+    auto issue_step = [&](int st, int buf, int j) {
+        const uint32_t base = lds0 + (uint32_t)buf * STAGE;
+        const int k0 = st * M16_KC + wave * 128;
+        const uint32_t kb = k0 < K ? (uint32_t)k0 * 2u : 0u;                 // a slice past K repeats the first one, unused
+        if (j < WI_HI) {
+            if (wave + NW * j < WI) {                                         // wave-uniform
+                const uint32_t at = (uint32_t)st * (128u * BITS) + w_piece[j];   // the stage's segment of a packed row
+                dma16(wbase, w_src[j] + (at < row_bytes ? at : 0u), base + WOFF + (uint32_t)(wave + NW * j) * 1024u);
+            }
+        } else if (j < WI_HI + 4) {
+            dma16(a.x, x_src[j - WI_HI] + kb, base + (uint32_t)wave * XA + (j - WI_HI) * 1024u);
+        } else {
+            dma16(a.A, a_src[j - WI_HI - 4] + kb, base + (uint32_t)wave * XA + 4096u + (j - WI_HI - 4) * 1024u);
+        }
+    };
+    auto issue = [&](int st, int buf) {
+#pragma unroll
+        for (int j = 0; j < NS; ++j) issue_step(st, buf, j);
+    };
+    const bool w_hi = wave < WI - NW * WI_LO;                                 // this wave issues WI_HI weight instructions
+
+    // ---- group constants of all rows of the workgroup: copied as they lie (the rows are neighbours), 1 KB per request;
+    //      a piece past the end of the array repeats the array's first one (it belongs to rows past N)
+    {
+        const uint32_t sbytes = (uint32_t)R * ng * 2u, zbytes = (uint32_t)R * ng;
+        const uint32_t s_all = (uint32_t)a.N * ng * 2u, z_all = (uint32_t)a.N * ng;
+        const uint32_t s0 = (uint32_t)n0 * ng * 2u, z0 = (uint32_t)n0 * ng;
+        const uint32_t tb = lds0 + 2 * STAGE, zb = tb + ((sbytes + 1023u) & ~1023u);
+        for (uint32_t o = (uint32_t)wave * 1024u; o < sbytes; o += NW * 1024u) {
+            const uint32_t at = s0 + o + lane * 16u;
+            dma16(a.scales, at + 16u <= s_all ? at : 0u, tb + o);
+        }
+        for (uint32_t o = (uint32_t)wave * 1024u; o < zbytes; o += NW * 1024u) {
+            const uint32_t at = z0 + o + lane * 16u;
+            dma16(a.zeros, at + 16u <= z_all ? at : 0u, zb + o);
+        }
+    }
+    issue(0, 0);
+    if (S > 1) issue(1, 1);
+    // the rows of B the outputs need at the very end
+    constexpr int EPT = (NB * 256 + NT - 1) / NT, BV = AR > 0 ? AR / 8 : 1;
+    u16x8_t bpre[EPT][BV];
+    if constexpr (AR > 0) {
+#pragma unroll
+        for (int x = 0; x < EPT; ++x) {
+            const int e = threadIdx.x + x * NT, nn = n0 + (e >> 8) * 16 + (e & 15);
+            const bool live = e < NB * 256 && nn < a.N;
+#pragma unroll
+            for (int h = 0; h < BV; ++h)
+                bpre[x][h] = (live && 8 * h < r) ? *(const u16x8_t *)(a.B + (long)nn * r + 8 * h) : ZERO8;
+        }
+    }
+
+    float4_t acc[NB], tacc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) acc[nb] = float4_t{0.f, 0.f, 0.f, 0.f};
+
+    for (int st = 0; st < S; ++st) {
+        // stage st has landed once at most the requests of stage st + 1 (issued after it) are outstanding
+        if (st + 1 < S) {
+            if (w_hi) wait_vm<WI_HI + XI>(); else wait_vm<WI_LO + XI>();
+        } else {
+            wait_vm<0>();
+        }
+        __syncthreads();                                     // ... for every wave; also publishes the group constants
+        const uint8_t *buf = lds + (size_t)(st & 1) * STAGE;
+        const uint8_t *xs = buf + (size_t)wave * XA, *wc = buf + WOFF;
+        const int k0 = st * M16_KC + wave * 128;
+        const bool live = k0 < K;                            // wave-uniform
+        u16x8_t xf[4], af[4];
+        uint32_t w[NB][BITS];
+        float sc[NB], zp[NB];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int slot = li * 16 + ((4 * q + s) ^ li);
+            xf[s] = *(const u16x8_t *)(xs + slot * 16);
+            if constexpr (AR > 0) af[s] = li < min(r, AR) ? *(const u16x8_t *)(xs + 4096 + slot * 16) : ZERO8;
+        }
+        const int grp = live ? group_of(k0, a.magic) : 0;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            const int n = nb * 16 + li;
+            const uint8_t *rowp = wc + n * (PPR * 16);
+            if constexpr (BITS == 3) {
+                const uint32_t *p = (const uint32_t *)(rowp + (wave ^ (n & 7)) * 48 + 12 * q);
+#pragma unroll
+                for (int i = 0; i < 3; ++i) w[nb][i] = p[i];
+            } else if constexpr (BITS == 2) {
+                const int u = 4 * wave + q;
+                const u32x2_t v = *(const u32x2_t *)(rowp + wswz<BITS>(n, u >> 1) * 16 + (u & 1) * 8);
+                w[nb][0] = v[0];
+                w[nb][1] = v[1];
+            } else {
+                constexpr int PU = UB / 16;                  // pieces of a unit
+#pragma unroll
+                for (int h = 0; h < PU; ++h) {
+                    const u32x4_t v = *(const u32x4_t *)(rowp + wswz<BITS>(n, (4 * wave + q) * PU + h) * 16);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) w[nb][4 * h + i] = v[i];
+                }
+            }
+            sc[nb] = live ? f16_bits_to_f32(sct[n * ng + grp]) : 0.f;
+            zp[nb] = (float)zt[n * ng + grp];
+        }
+        wait_lds();                                          // everything of this stage is in registers
+        const bool more = st + 2 < S;                        // workgroup-uniform
+        if (more) __syncthreads();                           // ... in every wave: the buffer may be overwritten
+        if (!live) {
+            if (more) issue(st + 2, st & 1);
+            continue;
+        }
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            // the wave's 128 columns lie in one group: the MFMAs sum x (q - z), exact integers times x, and the
+            // scale is applied to the four sums of the lane's weight row
+            DequantConst<BITS, BF16> dq;
+            dq.set(1.f, zp[nb]);
+            float4_t part = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                if (more && 4 * nb + s < NS) issue_step(st + 2, st & 1, 4 * nb + s);
+                part = mfma16<BF16>(xf[s], dequant8<BITS, BF16, false>(w[nb], s, dq), part);   // D[m = 4q+v][n = li]
+            }
+#pragma unroll
+            for (int v = 0; v < 4; ++v) acc[nb][v] = fmaf(sc[nb], part[v], acc[nb][v]);
+        }
+        if constexpr (AR > 0) {
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                if (more && 4 * NB + s < NS) issue_step(st + 2, st & 1, 4 * NB + s);
+                tacc = mfma16<BF16>(xf[s], af[s], tacc);                                      // D[m][j = li]
+            }
+        }
+        if (more) {
+#pragma unroll
+            for (int j = 4 * NB + (AR > 0 ? 4 : 0); j < NS; ++j) issue_step(st + 2, st & 1, j);
+        }
+    }
+
+    // ---- the waves' partial sums meet in LDS (where the stages were)
+    __syncthreads();
+    float *red = (float *)lds;                               // [NW][NB + 1][16][17]
+    auto red_at = [&](int w, int blk, int row, int col) -> float & { return red[((w * (NB + 1) + blk) * 16 + row) * 17 + col]; };
+    static_assert(NW * (NB + 1) * 16 * 17 * 4 <= 2 * m16_stage(BITS, NB, AR), "partial sums fit where the stages were");
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) red_at(wave, nb, 4 * q + v, li) = acc[nb][v];
+        if constexpr (AR > 0) red_at(wave, NB, 4 * q + v, li) = tacc[v];
+    }
+    __syncthreads();
+    if constexpr (AR > 0) {
+        for (int e = threadIdx.x; e < 16 * 16; e += NT) {
+            const int m = e >> 4, j = e & 15;
+            float tv = 0.f;
+            if (j < r && m < a.M) {
+#pragma unroll
+                for (int w = 0; w < NW; ++w) tv += red_at(w, NB, m, j);
+                tv = cvt16<BF16>(to16<BF16>(tv));            // the value every consumer of t sees
+                if (wg == 0 && a.t_out) a.t_out[(long)m * r + j] = to16<BF16>(tv);
+            }
+            tfull[m][j] = tv;
+        }
+    } else {
+        for (int e = threadIdx.x; e < a.M * r; e += NT) tfull[e / r][e % r] = cvt16<BF16>(a.t_in[e]);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int x = 0; x < EPT; ++x) {
+        const int e = threadIdx.x + x * NT;
+        const int nb = e >> 8, m = (e >> 4) & 15, nl = e & 15, nn = n0 + nb * 16 + nl;
+        if (e >= NB * 256 || m >= a.M || nn >= a.N) continue;
+        float v = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) v += red_at(w, nb, m, nl);
+        float lo = 0.f;
+        if constexpr (AR > 0) {
+#pragma unroll
+            for (int h = 0; h < BV; ++h)
+#pragma unroll
+                for (int c = 0; c < 8; ++c) lo += tfull[m][8 * h + c] * cvt16<BF16>(bpre[x][h][c]);   // zero past r
+        } else {
+            for (int j0 = 0; j0 < r; j0 += 8) {
+                const u16x8_t bv = *(const u16x8_t *)(a.B + (long)nn * r + j0);
+#pragma unroll
+                for (int h = 0; h < 8; ++h) lo += tfull[m][j0 + h] * cvt16<BF16>(bv[h]);
+            }
+        }
+        a.y[(long)m * a.N + nn] = to16<BF16>(v + a.sc * lo);
+    }
+}
+
+template <int BITS, bool BF16, int NB, int AR>
+__global__ __launch_bounds__(M16_NW * 64) void gemv_fwd_m16_kernel(const FwdMulti ma)
+{
+    int pi = 0;
+    while (pi + 1 < ma.count && (int)blockIdx.x >= ma.wg_end[pi]) ++pi;          // wave-uniform
+    const FwdArgs a = ma.p[pi];
+    gemv_fwd_m16_body<BITS, BF16, NB, AR>(a, (int)blockIdx.x - (pi ? ma.wg_end[pi - 1] : 0));
+}
+
+// largest NB whose two stages and tables fit in LDS (0: none)
+template <int BITS>
+inline int m16_nb_max(int ar, int ng)
+{
+    for (int nb = 4; nb >= 1; --nb)
+        if (2 * m16_stage(BITS, nb, ar) + m16_table(nb, ng) + m16_static(ar) <= M16_LDS) return nb;
+    return 0;
+}
+
+template <int BITS, bool BF16, int NB, int AR>
+void launch_fwd_m16_one(FwdMulti m, hipStream_t s)
+{
+    const int lds = 2 * m16_stage(BITS, NB, AR) + m16_table(NB, m.p[0].ng);
+    int wgs = 0;
+    for (int i = 0; i < m.count; ++i) {
+        wgs += (blocks16(m.p[i].N) + NB - 1) / NB;
+        m.wg_end[i] = wgs;
+    }
+    auto kern = gemv_fwd_m16_kernel<BITS, BF16, NB, AR>;
+    ensure_dynamic_lds((const void *)kern, M16_LDS - m16_static(AR));
+    QLORA_LAUNCH(kern, dim3(wgs), dim3(M16_NW * 64), lds, s, m);
+}
+
+template <int BITS, bool BF16, int AR>
+void launch_fwd_m16_nb(const FwdMulti &m, int nb, hipStream_t s)
+{
+    switch (nb) {
+    case 4:
+        if constexpr (2 * m16_stage(BITS, 4, AR) < M16_LDS) { launch_fwd_m16_one<BITS, BF16, 4, AR>(m, s); return; }
+        [[fallthrough]];
+    case 3:
+        if constexpr (2 * m16_stage(BITS, 3, AR) < M16_LDS) { launch_fwd_m16_one<BITS, BF16, 3, AR>(m, s); return; }
+        [[fallthrough]];
+    case 2:
+        if constexpr (2 * m16_stage(BITS, 2, AR) < M16_LDS) { launch_fwd_m16_one<BITS, BF16, 2, AR>(m, s); return; }
+        [[fallthrough]];
+    default:
+        if constexpr (2 * m16_stage(BITS, 1, AR) < M16_LDS) launch_fwd_m16_one<BITS, BF16, 1, AR>(m, s);
+    }
+}
+
+// Serves the call if its shape allows: up to 16 token rows, K and the group size multiples of 128 (a wave's 128
+// columns of a stage then share their group constants), t either computed here from at most
+// 16 adapter rows or handed in, and room in LDS for two stages of at least two 16-row blocks (8-bit codes leave room
+// for one, which would pull x through every compute unit once per 16 weight rows: they stay with the other kernels).
+template <int BITS, bool BF16>
+bool launch_fwd_m16(const FwdMulti &m, int rg, hipStream_t s)
+{
+    const FwdArgs &a = m.p[0];
+    if (a.M > 16 || a.K % 128 != 0 || (a.K / a.ng) % 128 != 0 || rg > 1 || (rg == 0 && a.r > 64)) return false;
+    for (int i = 0; i < m.count; ++i) {
+        const FwdArgs &b = m.p[i];            // 16-byte requests: aligned arrays, constants in whole pieces
+        const uintptr_t bits_or = (uintptr_t)b.x | (uintptr_t)b.packed | (uintptr_t)b.scales | (uintptr_t)b.zeros |
+                                  (rg ? (uintptr_t)b.A : 0);
+        if ((bits_or & 15) != 0 || ((long)b.N * b.ng) % 16 != 0) return false;
+    }
+    const int ar = rg == 0 ? 0 : (a.r <= 8 ? 8 : 16);
+    const int nb_max = m16_nb_max<BITS>(ar, a.ng);
+    if (nb_max < 2) return false;
+    // one round of the 256 compute units if the rows allow it; siblings that do not fit one round together go one by one
+    int nb = 0;
+    for (int cand = 1; cand <= nb_max && nb == 0; ++cand) {
+        int wgs = 0;
+        for (int i = 0; i < m.count; ++i) wgs += (blocks16(m.p[i].N) + cand - 1) / cand;
+        if (wgs <= 256) nb = cand;
+    }
+    if (nb == 0 && m.count > 1) {
+        for (int i = 0; i < m.count; ++i) {
+            FwdMulti one{};
+            one.count = 1;
+            one.p[0] = m.p[i];
+            launch_fwd_m16<BITS, BF16>(one, rg, s);
+        }
+        return true;
+    }
+    if (nb == 0) nb = nb_max;
+    switch (ar) {
+    case 0: launch_fwd_m16_nb<BITS, BF16, 0>(m, nb, s); break;
+    case 8: launch_fwd_m16_nb<BITS, BF16, 8>(m, nb, s); break;
+    default: launch_fwd_m16_nb<BITS, BF16, 16>(m, nb, s); break;
+    }
+    return true;
+}
+
+}  // namespace
+
+}  // namespace qlora

@@ -79,6 +79,16 @@ SMALL_CASES = [
     (16, 96, 12312, 2, 32, 8, "bf16"),         # four blocks per workgroup, ragged; backward with many row slices
     (11, 2048, 1544, 4, 128, 16, "f16"),       # backward: 8-wave workgroups, slices that do not divide the rows
     (7, 512, 136, 4, 512, 8, "f16"),           # per-row grouping on the weight-streaming path
+    # up to 16 token rows, K and G multiples of 128: the forward kernel that stages the packed words through LDS
+    (16, 1152, 200, 2, 128, 8, "f16"),         # two stages, the second with one live wave; ragged last workgroup
+    (13, 2304, 328, 3, 256, 8, "bf16"),        # three stages; 3-bit units; groups of 256
+    (16, 1024, 264, 3, 128, 16, "f16"),        # sixteen adapter rows staged
+    (5, 384, 72, 8, 128, 0, "bf16"),           # 8-bit codes fit only without adapter rows in LDS
+    (16, 512, 136, 8, 128, 40, "f16"),         # ... or with t from its own launch (rank above 32)
+    (9, 640, 520, 4, 128, 40, "bf16"),
+    (16, 256, 12312, 2, 128, 8, "f16"),        # four 16-row blocks per workgroup, the last workgroup ragged
+    (16, 256, 12312, 4, 128, 8, "bf16"),       # three blocks, 257 workgroups
+    (1, 4096, 1024, 2, 4096, 8, "f16"),        # one group per row, four full stages
     (150, 1024, 264, 2, 1024, 8, "f16"),       # and on the tiled path, both passes
     (130, 256, 264, 4, 64, 48, "f16"),         # ranks 40, 48, 56: gradients by the 64-wide one-pass kernel
     (90, 512, 136, 2, 128, 56, "bf16"),
@@ -176,6 +186,10 @@ EXACT_CASES = [
     (7, 512, 136, 2, 64, 16, "bf16", 0.25, True),
     (5, 384, 72, 8, 128, 8, "bf16", 0.25, False),
     (11, 768, 264, 3, 128, 0, "bf16", 0.25, False),
+    (16, 1152, 200, 2, 128, 8, "bf16", 0.25, True),        # staged-weight forward kernel: two stages, ragged rows
+    (13, 2304, 328, 3, 256, 16, "f16", 1.0, True),
+    (16, 512, 136, 8, 128, 40, "f16", 1.0, True),
+    (16, 256, 12312, 4, 128, 8, "f16", 1.0, True),
     (40, 512, 264, 4, 64, 8, "f16", 1.0, True),            # forward streaming, backward tiled with a split contraction
     (64, 384, 136, 2, 128, 16, "bf16", 0.25, True),
     # tiled kernels: one tile, ragged tiles, split contraction, 256-row tiles, every width, both dtypes
