@@ -106,4 +106,12 @@ __device__ __forceinline__ void dma4(const void *base, uint32_t byte_offset, uin
                  : "memory");
 }
 
+// The 16-byte form with a full address per lane (the lanes of one request may read different arrays).
+__device__ __forceinline__ void dma16_at(const void *lane_address, uint32_t lds)
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 ::"v"(lane_address), "s"(lds)
+                 : "memory");
+}
+
 }  // namespace qlora

@@ -264,6 +264,271 @@ struct BwdMulti {
     int count;
 };
 
+// ------------------------------------------------------------------------------- backward, staged through LDS
+// The same products as gemv_bwd_body, with every operand brought in by direct-to-LDS loads instead of fragment-wise
+// loads: a 32-row chunk costs the kernel above eight 4-byte loads of packed words plus up to sixteen 1- and 2-byte
+// loads of group constants per lane, and what bounds it is the number of such instructions, not the bytes.  Here a
+// workgroup of eight waves walks its row slice in stages of 256 rows, NST stages in flight; a stage is the rows'
+// packed words inside the column block (RB bytes per row), the 16 x 256 piece of dY and, per row, the 16-byte piece of
+// the scale table and the one of the zero-point table that hold the block's one or two groups (such a pair never
+// straddles two pieces: with two groups per block the number of groups per row is even).  Wave w multiplies chunk w
+// of every stage.  One step ahead of their use the windows are turned into per-group arrays of fp16 scales and -z
+// over the rows, so that a lane picks up the constants of its eight rows with two 16-byte reads.
+//
+// LDS rows of a stage are permuted (bits 0-2 and 3-4 of the row index change places): the four rows 8 q + e that a
+// wave reads together then lie in four different bank ranges.  The dY pieces are permuted by the token row.
+constexpr int BS_RS = 256, BS_NW = 8;
+
+template <int BITS>
+struct BwdStaged {
+    using S = BwdShape<BITS>;
+    static constexpr int RB = S::CB * BITS / 8;             // bytes of a weight row inside the column block
+    static constexpr int PPR = RB / 16;
+    static constexpr int WBYTES = BS_RS * RB, DYB = 16 * BS_RS * 2, SZB = BS_RS * 32;
+    static constexpr int STAGE = WBYTES + DYB + SZB;
+    static constexpr int NST = BITS == 8 ? 3 : 4;
+    static constexpr int WD = WBYTES / 1024 / BS_NW;        // weight requests per wave and stage
+    static constexpr int WIN = 1;                           // window requests per wave and stage
+    static constexpr int GRP = WD + WIN + 1;                // ... and all requests: windows, 1 of dY, WD
+    static constexpr int CONV = 2 * 2 * 2 * BS_RS * 2;      // [parity][scale | -z][group][row] fp16
+    static constexpr int RED = BS_NW * 16 * S::CB * 4;      // the waves' partial sums
+    static constexpr int LDS = NST * STAGE + CONV > RED ? NST * STAGE + CONV : RED;
+    static_assert(BITS != 3 && WBYTES % (1024 * BS_NW) == 0 && LDS <= 160 * 1024, "stage shape");
+};
+
+__device__ __forceinline__ int bs_perm(int row) { return (row & ~31) | ((row & 7) << 2) | ((row >> 3) & 3); }
+__device__ __forceinline__ int bs_unperm(int p) { return (p & ~31) | ((p & 3) << 3) | ((p >> 2) & 7); }
+
+template <int N>
+__device__ __forceinline__ void bs_wait_vm()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+template <int BITS, bool BF16>
+__device__ __forceinline__ void gemv_bwd_staged_body(const BwdArgs &a, const int cb, const int sp_local, const int sp)
+{
+    using S = BwdShape<BITS>;
+    using T = BwdStaged<BITS>;
+    constexpr int CL = S::CL, WORDS = S::WORDS, CB = S::CB, NW = BS_NW, NT = NW * 64;
+    constexpr int RB = T::RB, PPR = T::PPR, NST = T::NST, WD = T::WD, GRP = T::GRP, STAGE = T::STAGE;
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wc = lane & 15, q = lane >> 4;
+    const int N = a.N, K = a.K, ng = a.ng;
+    const int Kw = K * BITS / 32;
+    const int nbeg = sp_local * a.rows_per_slice, nend = min(N, nbeg + a.rows_per_slice);
+    const int rows = nend - nbeg, stages = (rows + BS_RS - 1) / BS_RS;
+    if (rows <= 0) {                                                        // a slice past the last row (uniform): zeros
+        for (int e = threadIdx.x; e < a.M * CB; e += NT) a.partial[((long)sp * a.M + e / CB) * K + cb * CB + e % CB] = 0.f;
+        return;
+    }
+    const int g0 = group_of(cb * CB, a.magic);                              // first group of the column block
+    const int gl = group_of(cb * CB + CL * wc, a.magic) - g0;              // this lane's columns: 0 or 1
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)lds;
+    uint16_t *conv = (uint16_t *)(lds + NST * STAGE);                       // [parity][scale | -z][group][BS_RS]
+
+    // ---- this lane's part of the requests of a stage
+    const uint32_t *wbase = a.packed + (long)nbeg * Kw + cb * (RB / 4);
+    const uint32_t row_bytes = (uint32_t)Kw * 4u;
+    const int row_max = N - 1 - nbeg;                                       // rows past the matrix repeat its last row
+    int w_row[WD];
+    uint32_t w_pc[WD];
+#pragma unroll
+    for (int c = 0; c < WD; ++c) {
+        const int e = 64 * (wave + NW * c) + lane;
+        w_row[c] = bs_unperm(e / PPR);
+        w_pc[c] = (uint32_t)(e % PPR) * 16u;
+    }
+    // dY: request `wave` moves token rows 2 wave, 2 wave + 1; slot s of a row holds piece s ^ row
+    const int dy_m = 2 * wave + (lane >> 5), dy_piece = (lane & 31) ^ dy_m;
+    const uint32_t dy_row = (uint32_t)min(dy_m, a.M - 1) * (uint32_t)N * 2u;
+    // windows: request `wave` moves rows 32 wave .. 32 wave + 32, lane l the scale piece (l even) or the zero-point
+    // piece (l odd) of row 32 wave + l / 2
+    const uint32_t s_all = (uint32_t)N * ng * 2u, z_all = (uint32_t)N * ng;
+    auto issue = [&](int st) {
+        const uint32_t base = lds0 + (uint32_t)(st % NST) * STAGE;
+        {
+            const int row = 32 * wave + (lane >> 1);
+            const uint32_t n = (uint32_t)min(st * BS_RS + row, row_max) + nbeg;
+            const uint32_t e = n * ng + g0;
+            const uint32_t sat = (e * 2u) & ~15u, zat = e & ~15u;
+            const uint8_t *src = (lane & 1) == 0 ? (const uint8_t *)a.scales + (sat + 16u <= s_all ? sat : 0u)
+                                                 : a.zeros + (zat + 16u <= z_all ? zat : 0u);
+            dma16_at(src, base + T::WBYTES + T::DYB + (uint32_t)wave * 1024u);
+        }
+        {
+            const int n = nbeg + st * BS_RS + 8 * dy_piece;                 // N % 8 == 0: a piece is inside or outside
+            dma16(a.dy, dy_row + (n < N ? (uint32_t)n * 2u : 0u), base + T::WBYTES + (uint32_t)wave * 1024u);
+        }
+#pragma unroll
+        for (int c = 0; c < WD; ++c)
+            dma16(wbase, (uint32_t)min(st * BS_RS + w_row[c], row_max) * row_bytes + w_pc[c],
+                  base + (uint32_t)(wave + NW * c) * 1024u);
+    };
+    // the windows of stage st become scales and -z per group and row (thread = row); rows past the slice get scale 0
+    auto convert = [&](int st) {
+        if (threadIdx.x < BS_RS) {
+            const int row = threadIdx.x, rs = st * BS_RS + row;
+            const uint8_t *win = lds + (size_t)(st % NST) * STAGE + T::WBYTES + T::DYB + row * 32;
+            const uint32_t e = ((uint32_t)min(rs, row_max) + nbeg) * ng + g0;
+            const uint32_t sw = *(const uint32_t *)(win + ((e * 2u) & 12u)) >> (8 * ((e * 2u) & 3u));     // two scales
+            const uint32_t zw = *(const uint32_t *)(win + 16 + (e & 12u)) >> (8 * (e & 3u));             // two zero-points
+            uint16_t *dst = conv + (st & 1) * (4 * BS_RS) + row;
+#pragma unroll
+            for (int g = 0; g < 2; ++g) {
+                dst[g * BS_RS] = rs < rows ? (uint16_t)(sw >> (16 * g)) : (uint16_t)0;
+                dst[(2 + g) * BS_RS] = f32_to_f16_bits(-(float)((zw >> (8 * g)) & 0xffu));
+            }
+        }
+    };
+
+    float4_t acc[CL];
+#pragma unroll
+    for (int c = 0; c < CL; ++c) acc[c] = float4_t{0.f, 0.f, 0.f, 0.f};
+
+    // Requests complete in the order they were made, so "stage st has landed" is a bound on the number of requests
+    // still outstanding: those of the stages requested after it.  wait_later(n, keep): at most n later stages and, of
+    // the stage next in line, everything but its first `keep` requests (the windows) may be outstanding.
+    auto wait_later = [&](int later, int keep) {      // workgroup-uniform arguments
+        if (later >= 3) bs_wait_vm<3 * GRP>();        // (only without keep: the start-up)
+        else if (later == 2) { if (keep) bs_wait_vm<2 * GRP - T::WIN>(); else bs_wait_vm<2 * GRP>(); }
+        else if (later == 1) { if (keep) bs_wait_vm<GRP - T::WIN>(); else bs_wait_vm<GRP>(); }
+        else bs_wait_vm<0>();
+    };
+    static_assert(NST <= 4, "wait_later covers three stages in flight");
+    const int ahead = min(NST - 1, stages);            // stages requested before the first is used
+    for (int st = 0; st < ahead; ++st) issue(st);
+    // the windows of stage 0 (its first request) have landed
+    if (ahead == 3) bs_wait_vm<3 * GRP - T::WIN>();
+    else if (ahead == 2) bs_wait_vm<2 * GRP - T::WIN>();
+    else bs_wait_vm<GRP - T::WIN>();
+    __syncthreads();
+    convert(0);
+    for (int st = 0; st < stages; ++st) {
+        // stage st and the windows of stage st + 1
+        const int later = min(NST - 2, stages - 1 - st);
+        wait_later(later, later > 0);
+        __syncthreads();                              // ... for every wave; the arrays written by convert are visible
+        if (st + NST - 1 < stages) issue(st + NST - 1);   // into the buffer every wave has left with the step before
+        if (st + 1 < stages) convert(st + 1);
+        const uint8_t *buf = lds + (size_t)(st % NST) * STAGE;
+        const int rs0 = st * BS_RS + 32 * wave + 8 * q;                    // first of this lane's eight rows
+        if (st * BS_RS + 32 * wave >= rows) continue;                      // wave-uniform: the chunk is past the slice
+        const bool in = rs0 < rows;                                        // slices end on multiples of 8
+        uint32_t w[8][WORDS];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const uint8_t *src = buf + (32 * wave + 4 * e + q) * RB + wc * (WORDS * 4);
+            if constexpr (WORDS == 2) {
+                const u32x2_t v = *(const u32x2_t *)src;
+                w[e][0] = v[0];
+                w[e][1] = v[1];
+            } else {
+                w[e][0] = *(const uint32_t *)src;
+            }
+        }
+        u16x8_t df = *(const u16x8_t *)(buf + T::WBYTES + wc * 512 + (((4 * wave + q) ^ wc) * 16));
+        if (!in) df = ZERO8;
+        const uint16_t *cs = conv + (st & 1) * (4 * BS_RS) + gl * BS_RS + 32 * wave + 8 * q;
+        const u32x4_t sv = *(const u32x4_t *)cs, zv = *(const u32x4_t *)(cs + 2 * BS_RS);
+        if constexpr (BF16) {
+            float s[8], z[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                s[e] = f16_bits_to_f32((uint16_t)(sv[e >> 1] >> (16 * (e & 1))));
+                z[e] = -f16_bits_to_f32((uint16_t)(zv[e >> 1] >> (16 * (e & 1))));
+            }
+#pragma unroll
+            for (int c = 0; c < CL; ++c) {
+                u16x8_t wf;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) wf[e] = to16<BF16>(((float)code_of<BITS, WORDS>(w[e], c) - z[e]) * s[e]);
+                acc[c] = mfma16<BF16>(df, wf, acc[c]);                     // D[m = 4q+v][column CL wc + c]
+            }
+        } else {
+            half2_t s2[4], nz2[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t sw = sv[i], zw = zv[i];       // (a bit cast straight from a vector element reads element 0)
+                s2[i] = __builtin_bit_cast(half2_t, sw);
+                nz2[i] = __builtin_bit_cast(half2_t, zw);
+            }
+#pragma unroll
+            for (int c = 0; c < CL; ++c) acc[c] = mfma16<BF16>(df, dequant_rows8_f16<BITS, WORDS>(w, c, s2, nz2), acc[c]);
+        }
+    }
+    __syncthreads();                                  // every request has landed (the last wait was for all)
+    // ---- the waves' sums meet in LDS: [wave][m][CB] floats, then every thread adds up four columns of one row.  A
+    //      lane's CL columns are P = CL / 4 pieces of 16 bytes; piece j sits in slot j ^ f(lane) of the lane's P, with f
+    //      chosen so that the sixteen lanes of one store fall on sixteen different bank groups.
+    constexpr int P = CL / 4;
+    float *red = (float *)lds;
+    const int f = (wc / (16 / P)) & (P - 1);
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        float *dst = red + ((size_t)wave * 16 + 4 * q + v) * CB + CL * wc;
+#pragma unroll
+        for (int j = 0; j < P; ++j)
+            *(float4_t *)(dst + 4 * (j ^ f)) = float4_t{acc[4 * j][v], acc[4 * j + 1][v], acc[4 * j + 2][v], acc[4 * j + 3][v]};
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < 16 * CB / 4; e += NT) {
+        const int m = e / (CB / 4), k4 = e % (CB / 4);
+        if (m >= a.M) continue;
+        const int lw = k4 / P, slot = P * lw + ((k4 % P) ^ ((lw / (16 / P)) & (P - 1)));
+        float4_t v = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int w = 0; w < NW; ++w) v += *(const float4_t *)(red + ((size_t)w * 16 + m) * CB + 4 * slot);
+        *(float4_t *)(a.partial + ((long)sp * a.M + m) * K + cb * CB + 4 * k4) = v;
+    }
+}
+
+// u = dY B of one row slice (the workgroup past the last column block of every slice): B^T fragments gathered
+// column-wise, four 32-row chunks in flight per wave
+template <bool BF16>
+__device__ __forceinline__ void gemv_bwd_u_body(const BwdArgs &a, const int sp_local, const int sp)
+{
+    constexpr int NW = BS_NW, NT = NW * 64;
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    float (*ured)[16][64 + 1] = (float (*)[16][64 + 1])lds;                 // [NW][16][65], 33 KB of the dynamic LDS
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wc = lane & 15, q = lane >> 4;
+    const int N = a.N, r = a.r;
+    const int nbeg = sp_local * a.rows_per_slice, nend = min(N, nbeg + a.rows_per_slice);
+    const int mrow = min(wc, a.M - 1);
+    float4_t uacc[4];
+#pragma unroll
+    for (int gg = 0; gg < 4; ++gg) uacc[gg] = float4_t{0.f, 0.f, 0.f, 0.f};
+    for (int nb = nbeg + wave * 32; nb < nend; nb += 32 * NW) {
+        const int nn = nb + 8 * q;
+        const bool in = nn < nend;                                          // slices end on multiples of 8
+        const u16x8_t df = in ? *(const u16x8_t *)(a.dy + (long)mrow * N + nn) : ZERO8;
+#pragma unroll
+        for (int gg = 0; gg < 4; ++gg) {
+            const int j = gg * 16 + wc;
+            if (gg * 16 >= r) continue;                                     // uniform
+            u16x8_t bf = ZERO8;
+            if (in && j < r) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) bf[e] = a.B[(long)(nn + e) * r + j];
+            }
+            uacc[gg] = mfma16<BF16>(df, bf, uacc[gg]);                     // D[m = 4q+v][j = 16 gg + wc]
+        }
+    }
+#pragma unroll
+    for (int gg = 0; gg < 4; ++gg)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) ured[wave][4 * q + v][16 * gg + wc] = uacc[gg][v];
+    __syncthreads();
+    for (int e = threadIdx.x; e < 16 * 64; e += NT) {
+        const int m = e >> 6, j = e & 63;
+        float v = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) v += ured[w][m][j];
+        a.upartial[(long)sp * 1024 + e] = v;
+    }
+}
+
 template <int BITS, bool BF16, int NW, int BW_U>
 __global__ __launch_bounds__(NW * 64) void gemv_bwd_kernel(const BwdArgs a)
 {
@@ -279,6 +544,22 @@ __global__ __launch_bounds__(NW * 64) void gemv_bwd_siblings_kernel(const BwdMul
     while (pi + 1 < ma.count && sp >= ma.slice_end[pi]) ++pi;      // wave-uniform
     const BwdArgs a = ma.p[pi];
     gemv_bwd_body<BITS, BF16, NW, BW_U>(a, sp - (pi ? ma.slice_end[pi - 1] : 0), sp);
+}
+
+// grid (column blocks + 1, slices): the last workgroup of a slice computes u
+template <int BITS, bool BF16>
+__global__ __launch_bounds__(BS_NW * 64) void gemv_bwd_staged_kernel(const BwdMulti ma)
+{
+    const int sp = (int)blockIdx.y;
+    int pi = 0;
+    while (pi + 1 < ma.count && sp >= ma.slice_end[pi]) ++pi;      // wave-uniform
+    const BwdArgs a = ma.p[pi];
+    const int sp_local = sp - (pi ? ma.slice_end[pi - 1] : 0);
+    if ((int)blockIdx.x + 1 == (int)gridDim.x) {
+        if (a.r > 0) gemv_bwd_u_body<BF16>(a, sp_local, sp);
+    } else {
+        gemv_bwd_staged_body<BITS, BF16>(a, (int)blockIdx.x, sp_local, sp);
+    }
 }
 
 // Second backward kernel (M <= 16), one thread per output element:
@@ -450,9 +731,40 @@ __global__ __launch_bounds__(256) void gemv_bwd_finish_siblings_kernel(const Fin
     }
 }
 
+// whether the staged kernel takes the launch: column blocks that divide K and hold at most two groups, 16-byte
+// aligned operands and tables of whole 16-byte pieces (they are fetched by direct-to-LDS loads), packed rows
+// addressed with 32 bits
+template <int BITS>
+bool bwd_staged_applies(const BwdMulti &m)
+{
+    if constexpr (BITS == 3) {
+        return false;
+    } else {
+        constexpr int CB = BwdShape<BITS>::CB;
+        for (int i = 0; i < m.count; ++i) {
+            const BwdArgs &a = m.p[i];
+            const int G = a.K / a.ng;
+            if (a.K % CB != 0 || !(G % CB == 0 || (CB % G == 0 && CB / G <= 2))) return false;
+            if ((long)a.N * a.K * BITS / 8 >= (1ll << 32) || ((long)a.N * a.ng) % 16 != 0) return false;   // whole 16-byte pieces of constants
+            const uintptr_t bits_or = (uintptr_t)a.dy | (uintptr_t)a.packed | (uintptr_t)a.scales | (uintptr_t)a.zeros;
+            if ((bits_or & 15) != 0) return false;
+        }
+        return true;
+    }
+}
+
 template <int BITS, bool BF16>
 void launch_bwd_bits(const BwdMulti &m, hipStream_t s)
 {
+    if constexpr (BITS != 3) {
+        if (bwd_staged_applies<BITS>(m)) {
+            auto kern = gemv_bwd_staged_kernel<BITS, BF16>;
+            ensure_dynamic_lds((const void *)kern, BwdStaged<BITS>::LDS);
+            const dim3 grid(m.p[0].K / BwdShape<BITS>::CB + 1, m.slice_end[m.count - 1]);
+            QLORA_LAUNCH(kern, grid, dim3(BS_NW * 64), BwdStaged<BITS>::LDS, s, m);
+            return;
+        }
+    }
     const int slices = m.slice_end[m.count - 1];
     int max_rows = 0;
     for (int i = 0; i < m.count; ++i) max_rows = m.p[i].rows_per_slice > max_rows ? m.p[i].rows_per_slice : max_rows;
@@ -486,9 +798,9 @@ int bwd_cb(int bits) { return bits == 3 ? BwdShape<3>::CB : (bits == 2 ? BwdShap
 
 int gemv_bwd_slices(int N, int K, int bits)
 {
-    const int colblocks = (K + bwd_cb(bits) - 1) / bwd_cb(bits);
-    int slices = (256 + colblocks - 1) / colblocks;      // aim at one workgroup per compute unit: every extra slice
-                                                         // costs another M x K block of partial sums
+    const int colblocks = (K + bwd_cb(bits) - 1) / bwd_cb(bits) + 1;     // + 1: the workgroup that computes u
+    int slices = 256 / colblocks;                        // one workgroup per compute unit, in one round: every extra
+    if (slices < 1) slices = 1;                          // slice costs another M x K block of partial sums
     const int max_slices = (N + 127) / 128;              // at least four 32-row chunks per workgroup
     if (slices > max_slices) slices = max_slices;
     return slices < 1 ? 1 : slices;
@@ -500,8 +812,8 @@ int gemv_bwd_slices_siblings(int count, const int *N, int K, int bits, int *slic
         slices[0] = gemv_bwd_slices(N[0], K, bits);
         return slices[0];
     }
-    const int colblocks = (K + bwd_cb(bits) - 1) / bwd_cb(bits);
-    const int target = (256 + colblocks - 1) / colblocks;
+    const int colblocks = (K + bwd_cb(bits) - 1) / bwd_cb(bits) + 1;
+    const int target = 256 / colblocks < 1 ? 1 : 256 / colblocks;
     long rows = 0;
     for (int i = 0; i < count; ++i) rows += N[i];
     int total = 0;
