@@ -19,6 +19,7 @@ namespace qlora {
 namespace {
 
 constexpr int BK = 64;               // contraction elements per LDS stage
+constexpr int GEMM_NXS = 3;     // activation stages in LDS
 constexpr int LDS_STRIDE = BK + 8;   // 144-byte rows: the 16-byte reads of 8 consecutive rows fall in distinct bank groups
 constexpr int STAGERS = 256;        // staging threads (4 waves); the MFMA waves come on top
 
@@ -115,10 +116,7 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
     static_assert(XDMA >= 4 && XDMA % 4 == 0, "loads are spread over the four k-steps");
     constexpr int WU = BN / 128;                    // 32-code weight units per staging thread per stage
     constexpr int XS = BM * BK;                     // halfs per activation stage (128-byte rows, swizzled)
-#ifndef QLORA_NXS
-#define QLORA_NXS 3
-#endif
-    constexpr int NXS = QLORA_NXS;                  // activation stages (3, or 2 when two workgroups share a CU's LDS)
+    constexpr int NXS = GEMM_NXS;                   // (2 would let two workgroups share a CU's LDS: measured slower)
     static_assert(NXS == 2 || NXS == 3, "activation stages");
     // Weight stage.  Forward: [BN rows n][64 k + 8] (144-byte rows), fragments are 16-byte reads.  Backward: the
     // staging threads own rows n of the contraction, so the stage is kept as they produce it, [64 rows n][BN k],
@@ -162,10 +160,7 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
         const int bid = a.splits > 1 ? (int)blockIdx.x % nt : (int)blockIdx.x;
         const int xcd = bid & 7, loc = bid >> 3, per = nt >> 3, rem = nt & 7;
         const int t = xcd * per + min(xcd, rem) + loc;
-#ifndef QLORA_GM
-#define QLORA_GM 4
-#endif
-        constexpr int GM = QLORA_GM;
+        constexpr int GM = 4;
         const int in_group = GM * a.tiles_n, group = t / in_group, first_m = group * GM;
         const int gsz = min(a.tiles_m - first_m, GM), o = t % in_group;
         pm = first_m + o % gsz;
@@ -575,7 +570,7 @@ template <int BITS, bool BF16, bool TRANS, int BM, int BN, int WM, int WN, bool 
 void launch_variant(const GemmArgs &a, hipStream_t s)
 {
     constexpr size_t wstage = TRANS ? (size_t)BK * BN : (size_t)BN * LDS_STRIDE;
-    constexpr size_t lds_pipe = (QLORA_NXS * (size_t)BM * BK + 2 * wstage) * sizeof(uint16_t);
+    constexpr size_t lds_pipe = (GEMM_NXS * (size_t)BM * BK + 2 * wstage) * sizeof(uint16_t);
     constexpr size_t lds_side = MASKED ? (size_t)32 * (BM + BN) * sizeof(uint16_t) : 0;    // side tiles of the masked epilogue
     constexpr size_t lds_epi = (size_t)WM * WN * (BM / WM) * (BN / WN + 8) * sizeof(uint16_t) + lds_side;
     constexpr size_t lds = lds_pipe > lds_epi ? lds_pipe : lds_epi;
@@ -611,19 +606,7 @@ __global__ __launch_bounds__(256) void splitk_sum_kernel(const float *__restrict
 template <int BITS, bool BF16, bool TRANS>
 void launch_tiles(GemmArgs &a, hipStream_t s)
 {
-#ifndef QLORA_BM          // tile shape and MFMA-wave grid can be overridden at build time for tuning runs
-#define QLORA_BM 256
-#endif
-#ifndef QLORA_BN
-#define QLORA_BN 128
-#endif
-#ifndef QLORA_WM
-#define QLORA_WM 2
-#endif
-#ifndef QLORA_WN
-#define QLORA_WN 2
-#endif
-    constexpr int BM = QLORA_BM, BN = QLORA_BN;
+    constexpr int BM = 256, BN = 128, WM = 2, WN = 2;       // tile shape and grid of MFMA waves
     static_assert(BN == GEMM_SPLIT_BN, "gemm_splits() counts tiles of this width");
     const int NO = TRANS ? a.K : a.N, KC = TRANS ? a.N : a.K;
     a.tiles_n = (NO + BN - 1) / BN;
@@ -636,7 +619,7 @@ void launch_tiles(GemmArgs &a, hipStream_t s)
             a.tiles_m = (a.M + 127) / 128;
             if constexpr (TRANS) {
                 if (a.keep) {           // the masked epilogue needs the whole contraction in one workgroup
-                    launch_variant<BITS, BF16, TRANS, 128, BN, QLORA_WM, QLORA_WN, true>(a, s);
+                    launch_variant<BITS, BF16, TRANS, 128, BN, WM, WN, true>(a, s);
                     return;
                 }
             }
@@ -645,7 +628,7 @@ void launch_tiles(GemmArgs &a, hipStream_t s)
                 a.splits = splits;
                 a.kt_split = (a.kt_split + splits - 1) / splits;
             }
-            launch_variant<BITS, BF16, TRANS, 128, BN, QLORA_WM, QLORA_WN>(a, s);
+            launch_variant<BITS, BF16, TRANS, 128, BN, WM, WN>(a, s);
             if (splits > 1) {
                 const size_t plane = (size_t)a.M * NO;
                 QLORA_LAUNCH(splitk_sum_kernel<BF16>, dim3((unsigned)((plane / 8 + 255) / 256)), dim3(256), 0, s,
@@ -657,11 +640,11 @@ void launch_tiles(GemmArgs &a, hipStream_t s)
     a.tiles_m = (a.M + BM - 1) / BM;
     if constexpr (TRANS) {
         if (a.keep) {
-            launch_variant<BITS, BF16, TRANS, BM, BN, QLORA_WM, QLORA_WN, true>(a, s);
+            launch_variant<BITS, BF16, TRANS, BM, BN, WM, WN, true>(a, s);
             return;
         }
     }
-    launch_variant<BITS, BF16, TRANS, BM, BN, QLORA_WM, QLORA_WN>(a, s);
+    launch_variant<BITS, BF16, TRANS, BM, BN, WM, WN>(a, s);
 }
 
 // Multiplier m with umulhi(q, m) == q / (G/32) for every q < 2^16 (q = k/32, K < 2^21): m = floor(2^32 / d) + 1

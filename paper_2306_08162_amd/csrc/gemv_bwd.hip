@@ -14,13 +14,7 @@ namespace {
 // CL wc + c of those rows: D_c[m][k = CB cb + CL wc + c].
 template <int BITS>
 struct BwdShape {
-#ifndef QLORA_BW_CL2
-#define QLORA_BW_CL2 16
-#endif
-#ifndef QLORA_BW_CL4
-#define QLORA_BW_CL4 8
-#endif
-    static constexpr int CL = BITS == 3 ? 32 : (BITS == 2 ? QLORA_BW_CL2 : (BITS == 4 ? QLORA_BW_CL4 : 8));   // columns per lane
+    static constexpr int CL = BITS == 3 ? 32 : (BITS == 2 ? 16 : 8);   // columns per lane: one packed word (3-bit: three)
     static constexpr int WORDS = CL * BITS / 32;
     static constexpr int CB = 16 * CL;
 };
@@ -587,17 +581,25 @@ __global__ __launch_bounds__(256) void gemv_bwd_finish_kernel(const FinishArgs a
     __shared__ float side[16][64 + 1];       // u (dX and dA blocks) or t (dB blocks), as the 16-bit values they round to
     const int M = a.M, r = a.r, K = a.K, N = a.N;
     const int b = blockIdx.x;
+    // The kernel is a few dependent memory round trips long, so every load that can be is requested before the first
+    // result is needed: a dX thread asks for its slice sums (sixteen at a time) before the block turns to u.
+    const long idx_x = (long)b * 256 + threadIdx.x;
+    const bool x_thread = b < a.xb && idx_x < (long)M * K;
+    const long stride = (long)M * K;
+    float pv[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) pv[i] = x_thread && i < a.slices ? a.partial[i * stride + idx_x] : 0.f;
     if (b < a.xb + a.ab) {
         for (int e = threadIdx.x; e < M * r; e += 256) {
             const int m = e / r, j = e % r;
             const float *up = a.upartial + m * 64 + j;
             float v = 0.f;
-            for (int s0 = 0; s0 < a.slices; s0 += 8) {       // eight slices requested together, summed in slice order
-                float pv[8];
+            for (int s0 = 0; s0 < a.slices; s0 += 16) {      // sixteen slices requested together, summed in slice order
+                float uv[16];
 #pragma unroll
-                for (int i = 0; i < 8; ++i) pv[i] = s0 + i < a.slices ? up[(long)(s0 + i) * 1024] : 0.f;
+                for (int i = 0; i < 16; ++i) uv[i] = s0 + i < a.slices ? up[(long)(s0 + i) * 1024] : 0.f;
 #pragma unroll
-                for (int i = 0; i < 8; ++i) v += pv[i];
+                for (int i = 0; i < 16; ++i) v += uv[i];
             }
             side[m][j] = cvt16<BF16>(to16<BF16>(v));
         }
@@ -606,18 +608,19 @@ __global__ __launch_bounds__(256) void gemv_bwd_finish_kernel(const FinishArgs a
     }
     __syncthreads();
     if (b < a.xb) {
-        const long idx = (long)b * 256 + threadIdx.x;
-        if (idx >= (long)M * K) return;
+        if (!x_thread) return;
+        const long idx = idx_x;
         const int m = (int)(idx / K), k = (int)(idx % K);
-        const long stride = (long)M * K;
         float v = 0.f;
-        int s = 0;
-        for (; s + 4 <= a.slices; s += 4) {
-            const float p0 = a.partial[(s + 0) * stride + idx], p1 = a.partial[(s + 1) * stride + idx];
-            const float p2 = a.partial[(s + 2) * stride + idx], p3 = a.partial[(s + 3) * stride + idx];
-            v = (((v + p0) + p1) + p2) + p3;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) v += pv[i];                 // slice order; the entries past the last slice are zero
+        for (int s0 = 16; s0 < a.slices; s0 += 16) {
+            float more[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) more[i] = s0 + i < a.slices ? a.partial[(s0 + i) * stride + idx] : 0.f;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) v += more[i];
         }
-        for (; s < a.slices; ++s) v += a.partial[s * stride + idx];
         float lo = 0.f;
         for (int j = 0; j < r; ++j) lo += side[m][j] * cvt16<BF16>(a.A[(long)j * K + k]);
         if constexpr (MASKED) lo = ((a.keep[(long)m * (K / 8) + (k >> 3)] >> (k & 7)) & 1) ? lo * a.keep_scale : 0.f;
@@ -675,31 +678,37 @@ __global__ __launch_bounds__(256) void gemv_bwd_finish_siblings_kernel(const Fin
             const int m = e / r, j = e % r;
             const float *up = a.upartial + m * 64 + j;
             float v = 0.f;
-            for (int s0 = sb; s0 < se; s0 += 8) {
-                float pv[8];
+            for (int s0 = sb; s0 < se; s0 += 16) {
+                float uv[16];
 #pragma unroll
-                for (int i8 = 0; i8 < 8; ++i8) pv[i8] = s0 + i8 < se ? up[(long)(s0 + i8) * 1024] : 0.f;
+                for (int i16 = 0; i16 < 16; ++i16) uv[i16] = s0 + i16 < se ? up[(long)(s0 + i16) * 1024] : 0.f;
 #pragma unroll
-                for (int i8 = 0; i8 < 8; ++i8) v += pv[i8];
+                for (int i16 = 0; i16 < 16; ++i16) v += uv[i16];
             }
             side[slot][m][j] = cvt16<BF16>(to16<BF16>(v));
         }
     };
     if (b < a.xb) {
+        // the thread's slice sums are requested (sixteen at a time) before the block turns to u
+        const long idx = (long)b * 256 + threadIdx.x, stride = (long)M * K;
+        const bool live = idx < stride;
+        float pv[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) pv[i] = live && i < a.slices ? a.partial[i * stride + idx] : 0.f;
         for (int i = 0; i < a.count; ++i) sum_u(i, i);
         __syncthreads();
-        const long idx = (long)b * 256 + threadIdx.x;
-        if (idx >= (long)M * K) return;
+        if (!live) return;
         const int m = (int)(idx / K), k = (int)(idx % K);
-        const long stride = (long)M * K;
         float v = 0.f;
-        int s = 0;
-        for (; s + 4 <= a.slices; s += 4) {
-            const float p0 = a.partial[(s + 0) * stride + idx], p1 = a.partial[(s + 1) * stride + idx];
-            const float p2 = a.partial[(s + 2) * stride + idx], p3 = a.partial[(s + 3) * stride + idx];
-            v = (((v + p0) + p1) + p2) + p3;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) v += pv[i];                 // slice order; the entries past the last slice are zero
+        for (int s0 = 16; s0 < a.slices; s0 += 16) {
+            float more[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) more[i] = s0 + i < a.slices ? a.partial[(s0 + i) * stride + idx] : 0.f;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) v += more[i];
         }
-        for (; s < a.slices; ++s) v += a.partial[s * stride + idx];
         float lo = 0.f;
         for (int i = 0; i < a.count; ++i)
             for (int j = 0; j < r; ++j) lo += side[i][m][j] * cvt16<BF16>(a.p[i].A[(long)j * K + k]);

@@ -9,13 +9,7 @@ namespace qlora {
 namespace {
 
 // ------------------------------------------------------------------------------------------------- forward
-#ifndef QLORA_FW_U
-#define QLORA_FW_U 4
-#endif
-constexpr int FW_U = QLORA_FW_U;   // iterations (128 codes per row each) whose loads are in flight together
-
-
-
+constexpr int FW_U = 4;            // iterations (128 codes per row each) whose loads are in flight together
 
 
 template <int BITS, bool BF16, int MB, int RG, int NW, int NB>   // RG: 16-column groups of t formed here (0: none);
@@ -174,10 +168,8 @@ __global__ __launch_bounds__(NW * 64) void gemv_fwd_kernel(const FwdArgs a)
 // LDS slice of one 16-row block: 16 rows x 16 pieces of 16 bytes; piece c of row w sits in slot 16 w + (c ^ w), so
 // the fragment reads of 16 rows at one piece index fall on 16 different bank groups.
 constexpr int ST_BLOCK = 4096;      // bytes of one 16-row x 128-column block
-#ifndef QLORA_ST_U
-#define QLORA_ST_U 4
-#endif
-constexpr int ST_U = QLORA_ST_U;    // iterations whose packed words are requested together
+constexpr int ST_U = 4;             // iterations whose packed words are requested together
+static_assert(ST_U % 2 == 0, "a batch starts on slice buffer 0: the buffer of iteration i0 + u is u & 1");
 
 template <int N>
 __device__ __forceinline__ void wait_vm()

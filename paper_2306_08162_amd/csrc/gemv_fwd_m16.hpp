@@ -4,13 +4,13 @@
 // through, not the bytes: a lane that fetches its own MFMA fragment of a 2-bit weight touches 8 bytes of a row, so a
 // wave instruction brings in sixteen 32-byte pieces, and the group constants cost two more such instructions per
 // fragment.  Here nothing is fetched fragment-wise.  A workgroup of eight waves owns 16 NB weight rows and walks K in
-// stages of 1024: per stage the packed words of all its rows (row segments of 128 BITS bytes, whole cache lines),
-// sixteen token rows of x and the adapter rows of A arrive by direct-to-LDS loads of 1 KB per instruction, two stages
-// deep, and every wave takes the fragments of its 128 contraction indices from LDS.  The group constants of all the
-// workgroup's rows are copied to LDS once, at the start.
+// stages of 8 KS columns (KS = 128; 64 for 8-bit codes): per stage the packed words of all its rows (row segments of
+// KS BITS bytes, whole cache lines), sixteen token rows of x and the adapter rows of A arrive by direct-to-LDS loads
+// of 1 KB per instruction, two stages in flight, and every wave takes the fragments of its KS contraction indices from
+// LDS.  The group constants of all the workgroup's rows are copied to LDS once, at the start.
 //
-// Layout of a stage in LDS: per wave a 16-row x 128-column slice of x and an AR-row slice of A, both as in the staged
-// kernel (piece c of row w in slot 16 w + (c ^ w)); then the weight chunk, row n at n * 128 BITS bytes, its 16-byte
+// Layout of a stage in LDS: per wave a 16-row x KS-column slice of x and an AR-row slice of A (piece c of row w in
+// slot (KS / 8) w + (c ^ w), as in the staged kernel); then the weight chunk, row n at n * KS BITS bytes, its 16-byte
 // pieces permuted by wswz() so that sixteen rows read at one piece index fall on different banks.
 #pragma once
 
@@ -18,9 +18,13 @@ namespace qlora {
 
 namespace {
 
-constexpr int M16_NW = 8;                  // waves of a workgroup; wave w owns columns 128 w .. 128 w + 128 of a stage
-constexpr int M16_KC = 128 * M16_NW;       // contraction indices per stage
+constexpr int M16_NW = 8;                  // waves of a workgroup; wave w owns columns KS w .. KS w + KS of a stage
 constexpr int M16_LDS = 160 * 1024;
+// Columns of a wave per stage and stages in LDS.  8-bit codes: half the columns, so that three blocks of weight rows
+// fit beside the activations, and three stages (one barrier per stage instead of two).  The narrower widths are
+// faster with the wide slices (INT2 gate/up at M = 16: 12.0 against 13.3 us).
+constexpr int m16_ks(int bits) { return bits == 8 ? 64 : 128; }
+constexpr int m16_nst(int bits) { return bits == 8 ? 3 : 2; }
 
 // slot of the 16-byte piece `piece` of weight row n inside the row's stage segment (its own inverse)
 template <int BITS>
@@ -30,8 +34,8 @@ __device__ __forceinline__ int wswz(int n, int piece)
     else return piece ^ (n & 15);
 }
 
-constexpr int m16_xa(int ar) { return 4096 + ar * 256; }                                      // a wave's slices
-constexpr int m16_stage(int bits, int nb, int ar) { return M16_NW * m16_xa(ar) + nb * 16 * 128 * bits; }
+constexpr int m16_xa(int bits, int ar) { return (16 + ar) * 2 * m16_ks(bits); }               // a wave's slices of x and A
+constexpr int m16_stage(int bits, int nb, int ar) { return M16_NW * m16_xa(bits, ar) + nb * 16 * m16_ks(bits) * bits; }
 constexpr int m16_table(int nb, int ng)                                                       // scales (2 B), zero-points (1 B),
 {                                                                                             // each filled in whole KB
     return ((nb * 16 * ng * 2 + 1023) & ~1023) + ((nb * 16 * ng + 1023) & ~1023);
@@ -42,11 +46,15 @@ constexpr int m16_static(int ar) { return 16 * (m16_tc(ar) + 1) * 4; }
 template <int BITS, bool BF16, int NB, int AR>     // NB 16-row weight blocks; AR rows of A staged (0: t is given, or no adapter)
 __device__ __forceinline__ void gemv_fwd_m16_body(const FwdArgs &a, const int wg)
 {
-    constexpr int NW = M16_NW, NT = NW * 64, R = 16 * NB, PPR = 8 * BITS, UB = 4 * BITS;
-    constexpr int XA = m16_xa(AR), WOFF = NW * XA, STAGE = m16_stage(BITS, NB, AR);
-    constexpr int WI = R * PPR / 64;                         // weight instructions per stage, dealt out wave by wave
+    constexpr int NW = M16_NW, NT = NW * 64, R = 16 * NB;
+    constexpr int KS = m16_ks(BITS), KC = NW * KS, NST = m16_nst(BITS), SS = KS / 32;   // SS: MFMA steps of a wave per stage
+    constexpr int PPR = KS * BITS / 16, UB = KS * BITS / 32; // pieces of a weight row per stage; bytes of a lane's codes
+    constexpr int PR = KS / 8, RPI = 64 / PR;                // pieces of an activation row per stage; rows per request
+    constexpr int XBYTES = 32 * KS;                          // a wave's slice of x
+    constexpr int XA = m16_xa(BITS, AR), WOFF = NW * XA, STAGE = m16_stage(BITS, NB, AR);
+    constexpr int WI = R * PPR / 64;                         // weight requests per stage, dealt out wave by wave
     constexpr int WI_HI = (WI + NW - 1) / NW, WI_LO = WI / NW;
-    constexpr int XI = 4 + AR / 4;                           // instructions of a wave's own slices
+    constexpr int XIX = 16 / RPI, XIA = AR / RPI, XI = XIX + XIA;   // requests of a wave's own slices
     constexpr int TC = m16_tc(AR);
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     __shared__ float tfull[16][TC + 1];
@@ -54,10 +62,10 @@ __device__ __forceinline__ void gemv_fwd_m16_body(const FwdArgs &a, const int wg
     const int li = lane & 15, q = lane >> 4;
     const int n0 = wg * R, K = a.K, Kw = K * BITS / 32, r = a.r, ng = a.ng;
     const int rows_here = min(R, a.N - n0);                  // at least one
-    const int S = (K + M16_KC - 1) / M16_KC;
+    const int S = (K + KC - 1) / KC;
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)lds;
-    const uint16_t *sct = (const uint16_t *)(lds + 2 * STAGE);                          // [R][ng], then, from the next
-    const uint8_t *zt = lds + 2 * STAGE + ((R * ng * 2 + 1023) & ~1023);                // full KB on, the zero-points
+    const uint16_t *sct = (const uint16_t *)(lds + NST * STAGE);                          // [R][ng], then, from the next
+    const uint8_t *zt = lds + NST * STAGE + ((R * ng * 2 + 1023) & ~1023);                // full KB on, the zero-points
 
     // ---- this lane's part of the copies.  Weight instruction i of a stage fills slots 64 i .. 64 i + 64 of the chunk.
     const uint32_t *wbase = a.packed + (long)n0 * Kw;
@@ -69,29 +77,29 @@ __device__ __forceinline__ void gemv_fwd_m16_body(const FwdArgs &a, const int wg
         w_src[c] = (uint32_t)min(n, rows_here - 1) * row_bytes;
         w_piece[c] = (uint32_t)wswz<BITS>(n, slot) * 16u;
     }
-    uint32_t x_src[4], a_src[AR > 0 ? AR / 4 : 1];
+    uint32_t x_src[XIX], a_src[XIA > 0 ? XIA : 1];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int w16 = 4 * j + (lane >> 4), piece = (lane & 15) ^ w16;
-        x_src[j] = (uint32_t)(((long)min(w16, a.M - 1) * K + 8 * piece) * 2);
-        if (AR > 0 && 4 * j < AR) a_src[j] = (uint32_t)(((long)min(w16, r - 1) * K + 8 * piece) * 2);
+    for (int j = 0; j < XIX; ++j) {
+        const int row = RPI * j + lane / PR, piece = (lane % PR) ^ (row & (PR - 1));
+        x_src[j] = (uint32_t)(((long)min(row, a.M - 1) * K + 8 * piece) * 2);
+        if (j < XIA) a_src[j] = (uint32_t)(((long)min(row, r - 1) * K + 8 * piece) * 2);
     }
     // the requests of one stage, one at a time (they are spread over the arithmetic of the stage before: a request
     // waits for room in the memory pipeline, and meanwhile the wave could be multiplying)
     constexpr int NS = WI_HI + XI;
     auto issue_step = [&](int st, int buf, int j) {
         const uint32_t base = lds0 + (uint32_t)buf * STAGE;
-        const int k0 = st * M16_KC + wave * 128;
+        const int k0 = st * KC + wave * KS;
         const uint32_t kb = k0 < K ? (uint32_t)k0 * 2u : 0u;                 // a slice past K repeats the first one, unused
         if (j < WI_HI) {
             if (wave + NW * j < WI) {                                         // wave-uniform
-                const uint32_t at = (uint32_t)st * (128u * BITS) + w_piece[j];   // the stage's segment of a packed row
+                const uint32_t at = (uint32_t)st * (uint32_t)(KS * BITS) + w_piece[j];   // the stage's segment of a packed row
                 dma16(wbase, w_src[j] + (at < row_bytes ? at : 0u), base + WOFF + (uint32_t)(wave + NW * j) * 1024u);
             }
-        } else if (j < WI_HI + 4) {
+        } else if (j < WI_HI + XIX) {
             dma16(a.x, x_src[j - WI_HI] + kb, base + (uint32_t)wave * XA + (j - WI_HI) * 1024u);
         } else {
-            dma16(a.A, a_src[j - WI_HI - 4] + kb, base + (uint32_t)wave * XA + 4096u + (j - WI_HI - 4) * 1024u);
+            dma16(a.A, a_src[j - WI_HI - XIX] + kb, base + (uint32_t)wave * XA + XBYTES + (j - WI_HI - XIX) * 1024u);
         }
     };
     auto issue = [&](int st, int buf) {
@@ -106,7 +114,7 @@ __device__ __forceinline__ void gemv_fwd_m16_body(const FwdArgs &a, const int wg
         const uint32_t sbytes = (uint32_t)R * ng * 2u, zbytes = (uint32_t)R * ng;
         const uint32_t s_all = (uint32_t)a.N * ng * 2u, z_all = (uint32_t)a.N * ng;
         const uint32_t s0 = (uint32_t)n0 * ng * 2u, z0 = (uint32_t)n0 * ng;
-        const uint32_t tb = lds0 + 2 * STAGE, zb = tb + ((sbytes + 1023u) & ~1023u);
+        const uint32_t tb = lds0 + NST * STAGE, zb = tb + ((sbytes + 1023u) & ~1023u);
         for (uint32_t o = (uint32_t)wave * 1024u; o < sbytes; o += NW * 1024u) {
             const uint32_t at = s0 + o + lane * 16u;
             dma16(a.scales, at + 16u <= s_all ? at : 0u, tb + o);
@@ -144,18 +152,19 @@ __device__ __forceinline__ void gemv_fwd_m16_body(const FwdArgs &a, const int wg
             wait_vm<0>();
         }
         __syncthreads();                                     // ... for every wave; also publishes the group constants
-        const uint8_t *buf = lds + (size_t)(st & 1) * STAGE;
+        const int bi = st % NST;
+        const uint8_t *buf = lds + (size_t)bi * STAGE;
         const uint8_t *xs = buf + (size_t)wave * XA, *wc = buf + WOFF;
-        const int k0 = st * M16_KC + wave * 128;
+        const int k0 = st * KC + wave * KS;
         const bool live = k0 < K;                            // wave-uniform
-        u16x8_t xf[4], af[4];
-        uint32_t w[NB][BITS];
+        u16x8_t xf[SS], af[SS];
+        uint32_t w[NB][BITS];                                // the first UB bytes are used
         float sc[NB], zp[NB];
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const int slot = li * 16 + ((4 * q + s) ^ li);
+        for (int s = 0; s < SS; ++s) {
+            const int slot = li * PR + ((SS * q + s) ^ (li & (PR - 1)));
             xf[s] = *(const u16x8_t *)(xs + slot * 16);
-            if constexpr (AR > 0) af[s] = li < min(r, AR) ? *(const u16x8_t *)(xs + 4096 + slot * 16) : ZERO8;
+            if constexpr (AR > 0) af[s] = li < min(r, AR) ? *(const u16x8_t *)(xs + XBYTES + slot * 16) : ZERO8;
         }
         const int grp = live ? group_of(k0, a.magic) : 0;
 #pragma unroll
@@ -166,40 +175,46 @@ __device__ __forceinline__ void gemv_fwd_m16_body(const FwdArgs &a, const int wg
                 const uint32_t *p = (const uint32_t *)(rowp + (wave ^ (n & 7)) * 48 + 12 * q);
 #pragma unroll
                 for (int i = 0; i < 3; ++i) w[nb][i] = p[i];
-            } else if constexpr (BITS == 2) {
-                const int u = 4 * wave + q;
-                const u32x2_t v = *(const u32x2_t *)(rowp + wswz<BITS>(n, u >> 1) * 16 + (u & 1) * 8);
-                w[nb][0] = v[0];
-                w[nb][1] = v[1];
             } else {
-                constexpr int PU = UB / 16;                  // pieces of a unit
+                const int ob = (4 * wave + q) * UB;           // the lane's codes inside the row's segment
+                if constexpr (UB >= 16) {
 #pragma unroll
-                for (int h = 0; h < PU; ++h) {
-                    const u32x4_t v = *(const u32x4_t *)(rowp + wswz<BITS>(n, (4 * wave + q) * PU + h) * 16);
+                    for (int h = 0; h < UB / 16; ++h) {
+                        const u32x4_t v = *(const u32x4_t *)(rowp + wswz<BITS>(n, (ob >> 4) + h) * 16);
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) w[nb][4 * h + i] = v[i];
+                        for (int i = 0; i < 4; ++i) w[nb][4 * h + i] = v[i];
+                    }
+                } else if constexpr (UB == 8) {
+                    const u32x2_t v = *(const u32x2_t *)(rowp + wswz<BITS>(n, ob >> 4) * 16 + (ob & 15));
+                    w[nb][0] = v[0];
+                    w[nb][1] = v[1];
+                } else {
+                    w[nb][0] = *(const uint32_t *)(rowp + wswz<BITS>(n, ob >> 4) * 16 + (ob & 15));
                 }
+#pragma unroll
+                for (int i = UB / 4; i < BITS; ++i) w[nb][i] = 0u;
             }
             sc[nb] = live ? f16_bits_to_f32(sct[n * ng + grp]) : 0.f;
             zp[nb] = (float)zt[n * ng + grp];
         }
         wait_lds();                                          // everything of this stage is in registers
         const bool more = st + 2 < S;                        // workgroup-uniform
-        if (more) __syncthreads();                           // ... in every wave: the buffer may be overwritten
+        const int fill = (st + 2) % NST;                     // two stages: the buffer just read, once every wave is done
+        if (NST == 2 && more) __syncthreads();               // with it; three: the one every wave left a step ago
         if (!live) {
-            if (more) issue(st + 2, st & 1);
+            if (more) issue(st + 2, fill);
             continue;
         }
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
-            // the wave's 128 columns lie in one group: the MFMAs sum x (q - z), exact integers times x, and the
+            // the wave's columns lie in one group: the MFMAs sum x (q - z), exact integers times x, and the
             // scale is applied to the four sums of the lane's weight row
             DequantConst<BITS, BF16> dq;
             dq.set(1.f, zp[nb]);
             float4_t part = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                if (more && 4 * nb + s < NS) issue_step(st + 2, st & 1, 4 * nb + s);
+            for (int s = 0; s < SS; ++s) {
+                if (more && SS * nb + s < NS) issue_step(st + 2, fill, SS * nb + s);
                 part = mfma16<BF16>(xf[s], dequant8<BITS, BF16, false>(w[nb], s, dq), part);   // D[m = 4q+v][n = li]
             }
 #pragma unroll
@@ -207,14 +222,14 @@ __device__ __forceinline__ void gemv_fwd_m16_body(const FwdArgs &a, const int wg
         }
         if constexpr (AR > 0) {
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                if (more && 4 * NB + s < NS) issue_step(st + 2, st & 1, 4 * NB + s);
+            for (int s = 0; s < SS; ++s) {
+                if (more && SS * NB + s < NS) issue_step(st + 2, fill, SS * NB + s);
                 tacc = mfma16<BF16>(xf[s], af[s], tacc);                                      // D[m][j = li]
             }
         }
         if (more) {
 #pragma unroll
-            for (int j = 4 * NB + (AR > 0 ? 4 : 0); j < NS; ++j) issue_step(st + 2, st & 1, j);
+            for (int j = SS * NB + (AR > 0 ? SS : 0); j < NS; ++j) issue_step(st + 2, fill, j);
         }
     }
 
@@ -222,7 +237,7 @@ __device__ __forceinline__ void gemv_fwd_m16_body(const FwdArgs &a, const int wg
     __syncthreads();
     float *red = (float *)lds;                               // [NW][NB + 1][16][17]
     auto red_at = [&](int w, int blk, int row, int col) -> float & { return red[((w * (NB + 1) + blk) * 16 + row) * 17 + col]; };
-    static_assert(NW * (NB + 1) * 16 * 17 * 4 <= 2 * m16_stage(BITS, NB, AR), "partial sums fit where the stages were");
+    static_assert(NW * (NB + 1) * 16 * 17 * 4 <= NST * m16_stage(BITS, NB, AR), "partial sums fit where the stages were");
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
 #pragma unroll
@@ -285,14 +300,14 @@ template <int BITS>
 inline int m16_nb_max(int ar, int ng)
 {
     for (int nb = 4; nb >= 1; --nb)
-        if (2 * m16_stage(BITS, nb, ar) + m16_table(nb, ng) + m16_static(ar) <= M16_LDS) return nb;
+        if (m16_nst(BITS) * m16_stage(BITS, nb, ar) + m16_table(nb, ng) + m16_static(ar) <= M16_LDS) return nb;
     return 0;
 }
 
 template <int BITS, bool BF16, int NB, int AR>
 void launch_fwd_m16_one(FwdMulti m, hipStream_t s)
 {
-    const int lds = 2 * m16_stage(BITS, NB, AR) + m16_table(NB, m.p[0].ng);
+    const int lds = m16_nst(BITS) * m16_stage(BITS, NB, AR) + m16_table(NB, m.p[0].ng);
     int wgs = 0;
     for (int i = 0; i < m.count; ++i) {
         wgs += (blocks16(m.p[i].N) + NB - 1) / NB;
@@ -308,23 +323,23 @@ void launch_fwd_m16_nb(const FwdMulti &m, int nb, hipStream_t s)
 {
     switch (nb) {
     case 4:
-        if constexpr (2 * m16_stage(BITS, 4, AR) < M16_LDS) { launch_fwd_m16_one<BITS, BF16, 4, AR>(m, s); return; }
+        if constexpr (m16_nst(BITS) * m16_stage(BITS, 4, AR) < M16_LDS) { launch_fwd_m16_one<BITS, BF16, 4, AR>(m, s); return; }
         [[fallthrough]];
     case 3:
-        if constexpr (2 * m16_stage(BITS, 3, AR) < M16_LDS) { launch_fwd_m16_one<BITS, BF16, 3, AR>(m, s); return; }
+        if constexpr (m16_nst(BITS) * m16_stage(BITS, 3, AR) < M16_LDS) { launch_fwd_m16_one<BITS, BF16, 3, AR>(m, s); return; }
         [[fallthrough]];
     case 2:
-        if constexpr (2 * m16_stage(BITS, 2, AR) < M16_LDS) { launch_fwd_m16_one<BITS, BF16, 2, AR>(m, s); return; }
+        if constexpr (m16_nst(BITS) * m16_stage(BITS, 2, AR) < M16_LDS) { launch_fwd_m16_one<BITS, BF16, 2, AR>(m, s); return; }
         [[fallthrough]];
     default:
-        if constexpr (2 * m16_stage(BITS, 1, AR) < M16_LDS) launch_fwd_m16_one<BITS, BF16, 1, AR>(m, s);
+        if constexpr (m16_nst(BITS) * m16_stage(BITS, 1, AR) < M16_LDS) launch_fwd_m16_one<BITS, BF16, 1, AR>(m, s);
     }
 }
 
 // Serves the call if its shape allows: up to 16 token rows, K and the group size multiples of 128 (a wave's 128
 // columns of a stage then share their group constants), t either computed here from at most
-// 16 adapter rows or handed in, and room in LDS for two stages of at least two 16-row blocks (8-bit codes leave room
-// for one, which would pull x through every compute unit once per 16 weight rows: they stay with the other kernels).
+// 16 adapter rows or handed in, and room in LDS for the stages of at least two 16-row blocks (one block would pull x
+// through every compute unit once per 16 weight rows).
 template <int BITS, bool BF16>
 bool launch_fwd_m16(const FwdMulti &m, int rg, hipStream_t s)
 {

@@ -123,3 +123,20 @@ def test_packed_zero_points_bit_exact(bits, groups):
     ql.qlora_unpack_zeros(pd2, back.fill_(255), N, groups, bits)
     torch.cuda.synchronize()
     assert np.array_equal(back.cpu().numpy(), oracle.unpack_zeros(ref, groups, bits))
+
+
+def test_gather_rows_wider_than_the_lds_staging():
+    """Rows of more than 32768 columns do not fit the kernel that stages a row in LDS: the direct kernel takes them.
+    Seeded permutation with two indices out of range; every element compared."""
+    import torch
+    M, K = 5, 40000
+    x = wl.to_f16_bits(wl.normal(77, M * K)).reshape(M, K)
+    order = np.argsort(wl.uniform01(78, 0, K), kind="stable").astype(np.int32)
+    order[11], order[39999] = -5, K + 3
+    xd = torch.from_numpy(x.view(np.int16)).to("cuda:0")
+    out = torch.full((M, K), 77, dtype=torch.int16, device="cuda:0")
+    ql.qlora_gather_columns(xd, torch.from_numpy(order).to("cuda:0"), out, M, K)
+    torch.cuda.synchronize()
+    ref = x[:, np.clip(order, 0, K - 1)].copy()
+    ref[:, [11, 39999]] = 0
+    assert np.array_equal(out.cpu().numpy().view(np.uint16), ref)
