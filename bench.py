@@ -124,6 +124,7 @@ def run_small_m(M: int = 16, iters: int = 5, headline_layer: bool = True):
     INT2 and INT8.  GB/s counts weight-side bytes only (packed codes + scales + zero-points).
     """
     import torch
+    from paper_2306_08162_amd import binding as ql
     from paper_2306_08162_amd import workloads as wl
     from paper_2306_08162_amd.device import DeviceLayer, DeviceSiblings
 
@@ -159,6 +160,20 @@ def run_small_m(M: int = 16, iters: int = 5, headline_layer: bool = True):
             out[which] = {"us_per_set": round(us, 2), "packed_weight_GBps": round(per_set / us * 1e-3, 1)}
         out["fwd_bwd_packed_weight_GBps"] = round(2 * per_set / total * 1e-3, 1)
         out["frac_of_hbm_peak"] = round(out["fwd_bwd_packed_weight_GBps"] / PEAK_HBM_GBPS, 4)
+        if groups is None:
+            # The floor of this regime: one launch per projection of a kernel that only reads the projection's packed
+            # words (16-byte loads over the whole chip, an exclusive-or, nothing else), over the same pool.
+            words = torch.empty(ql.STREAM_PROBE_WORDS, dtype=torch.int32, device="cuda:0")
+
+            def probe():
+                for st in sets:
+                    for l, pk, sc, zr in st:
+                        ql.qlora_stream_probe(pk, pk.numel() * pk.element_size(), words, check=False)
+
+            packed_bytes = sum(pk.numel() * pk.element_size() for _, pk, _, _ in sets[0])
+            us = _graph_time(probe, iters) / len(sets)
+            out["stream_only_floor"] = {"us_per_set": round(us, 2), "packed_GBps": round(packed_bytes / us * 1e-3, 1),
+                                        "what": "one read-only launch per projection over its packed words"}
         return label, out
 
     results = {}

@@ -30,6 +30,17 @@ int qlora_profile_gemm(void *ev_before, void *ev_after);
  */
 int qlora_profile_gemm_span(int span);
 
+/*
+ * Reads `bytes` bytes at src (device pointer, 16-byte aligned, bytes a multiple of 16) once, with 16-byte loads
+ * spread over the whole chip, and writes QLORA_STREAM_PROBE_WORDS partial sums to out (device pointer, 16-byte
+ * aligned): their exclusive-or is the exclusive-or of all 32-bit words read.  It does nothing else: one launch whose
+ * duration is the least a kernel that streams that many bytes can take on this machine, the floor a
+ * weight-streaming pass is measured against.  Returns 0, or the QLORA_E_* codes of qlora.h for NULL pointers (1),
+ * misaligned pointers or sizes (7) and HIP errors (9).
+ */
+#define QLORA_STREAM_PROBE_WORDS 1024
+int qlora_stream_probe(const void *src, unsigned long long bytes, unsigned int *out, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

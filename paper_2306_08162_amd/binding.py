@@ -24,7 +24,8 @@ EXPORTS = ["qlora_status_string", "qlora_packed_words", "qlora_workspace_bytes",
            "qlora_linear_fwd", "qlora_linear_bwd", "qlora_linear_bwd_accumulate", "qlora_linear_fwd_dropout",
            "qlora_linear_bwd_dropout", "qlora_linear_bwd_stacked", "qlora_siblings_workspace_bytes", "qlora_linear_fwd_siblings",
            "qlora_linear_bwd_siblings", "qlora_lrec_workspace_bytes", "qlora_lrec_loss", "qlora_lrec_loss_scaled", "qlora_linear_fwd_static"]
-BENCH_EXPORTS = ["qlora_profile_gemm", "qlora_profile_gemm_span"]        # include/qlora_bench.h
+BENCH_EXPORTS = ["qlora_profile_gemm", "qlora_profile_gemm_span", "qlora_stream_probe"]        # include/qlora_bench.h
+STREAM_PROBE_WORDS = 1024
 MAX_SIBLINGS, SIBLINGS_MAX_M = 4, 16
 
 _lib = None
@@ -81,6 +82,8 @@ def load() -> ctypes.CDLL:
     lib.qlora_profile_gemm.argtypes = [vp, vp]
     lib.qlora_profile_gemm_span.restype = c_int
     lib.qlora_profile_gemm_span.argtypes = [c_int]
+    lib.qlora_stream_probe.restype = c_int
+    lib.qlora_stream_probe.argtypes = [vp, ctypes.c_ulonglong, vp, vp]
     lib.qlora_linear_bwd_accumulate.restype = c_int
     lib.qlora_linear_bwd_accumulate.argtypes = [vp] * 11 + [f32] + [c_int] * 6 + [f32, c_int, vp, c_sz, vp]
     lib.qlora_linear_fwd_dropout.restype = c_int
@@ -149,6 +152,15 @@ def qlora_profile_gemm(ev_before: Optional[int], ev_after: Optional[int]) -> int
 def qlora_profile_gemm_span(span: int) -> int:
     """0: the events enclose the GEMM alone; 1: the adapter kernel before it and the GEMM; 2: that kernel alone."""
     return int(load().qlora_profile_gemm_span(span))
+
+
+def qlora_stream_probe(src, nbytes: int, out, stream=None, check: bool = True) -> int:
+    """STREAM_PROBE_WORDS partial exclusive-ors of the 32-bit words of `nbytes` bytes at src: a kernel that only
+    streams the buffer."""
+    st = load().qlora_stream_probe(_ptr(src), nbytes, _ptr(out), _stream(stream))
+    if check and st != 0:
+        raise QLoraError(st, "qlora_stream_probe")
+    return st
 
 
 def qlora_pack(codes, packed, N: int, K: int, bits: int, stream=None, check: bool = True) -> int:

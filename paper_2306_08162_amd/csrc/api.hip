@@ -143,6 +143,15 @@ int qlora_profile_gemm_span(int span)
     return QLORA_OK;
 }
 
+int qlora_stream_probe(const void *src, unsigned long long bytes, uint32_t *out, void *stream)
+{
+    if (!src || !out) return QLORA_E_NULL;
+    if (misaligned(src) || misaligned(out) || bytes % 16 != 0) return QLORA_E_ALIGN;
+    begin_call();
+    launch_stream_probe(src, (size_t)bytes, out, (hipStream_t)stream);
+    return end_call();
+}
+
 size_t qlora_packed_words(int N, int K, int bits)
 {
     if (check_weight_shape(N, K, bits) != QLORA_OK) return 0;

@@ -42,6 +42,8 @@ void launch_pack_permuted(const uint8_t *codes, const int32_t *perm, uint32_t *p
                           hipStream_t s);
 // dst[m, j] = src[m, index[j]], 16-bit elements, K % 8 == 0 (0 where index[j] is outside [0, K))
 void launch_gather_columns(const void *src, const int32_t *index, void *dst, int M, int K, hipStream_t s);
+// benchmark instrumentation: 1024 partial exclusive-ors of the 32-bit words of a buffer, read once with 16-byte loads
+void launch_stream_probe(const void *src, size_t bytes, uint32_t *out, hipStream_t s);
 
 // adapters.hip -- the rank-r side products and the adapter gradients
 // t[M,r] = x[M,K] A[r,K]^T; with a keep mask (LoRA dropout, one bit per element of x, bit k % 32 of word k / 32 of

@@ -280,4 +280,34 @@ void launch_unpack_zeros(const uint32_t *packed, uint8_t *zeros, int N, int grou
     }
 }
 
+// ---- stream probe (benchmark instrumentation): reads a buffer once and does nothing else
+constexpr int PROBE_WGS = 1024, PROBE_THREADS = 256;
+
+__global__ __launch_bounds__(PROBE_THREADS) void stream_probe_kernel(const u32x4_t *__restrict__ src, long pieces,
+                                                                     uint32_t *__restrict__ part)
+{
+    __shared__ uint32_t red[PROBE_THREADS / WAVE];
+    const long step = (long)PROBE_WGS * PROBE_THREADS;
+    u32x4_t acc = {0u, 0u, 0u, 0u};
+    long i = (long)blockIdx.x * PROBE_THREADS + threadIdx.x;
+    for (; i + 3 * step < pieces; i += 4 * step) {          // four loads in flight per thread
+        const u32x4_t a = src[i], b = src[i + step], c = src[i + 2 * step], d = src[i + 3 * step];
+        acc ^= a ^ b ^ c ^ d;
+    }
+    for (; i < pieces; i += step) acc ^= src[i];
+    uint32_t v = acc[0] ^ acc[1] ^ acc[2] ^ acc[3];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v ^= (uint32_t)__shfl_xor((int)v, off, WAVE);
+    if ((threadIdx.x & (WAVE - 1)) == 0) red[threadIdx.x / WAVE] = v;
+    __syncthreads();
+    if (threadIdx.x == 0) part[blockIdx.x] = red[0] ^ red[1] ^ red[2] ^ red[3];
+}
+
+void launch_stream_probe(const void *src, size_t bytes, uint32_t *out, hipStream_t s)
+{
+    static_assert(PROBE_WGS == 1024, "the header promises 1024 partial words");
+    QLORA_LAUNCH(stream_probe_kernel, dim3(PROBE_WGS), dim3(PROBE_THREADS), 0, s, (const u32x4_t *)src,
+                 (long)(bytes / 16), out);
+}
+
 }  // namespace qlora

@@ -332,3 +332,18 @@ def test_benchmark_event_spans_leave_results_alone():
     for span in (0, 1, 2):
         assert ms[span][0] > 0 and ms[span][1] > 0
     assert ms[1][0] > ms[2][0] and ms[1][1] > ms[2][1]      # adapter kernel + GEMM takes longer than the adapter kernel
+
+
+def test_stream_probe_reads_every_word_once():
+    """The benchmark's read-only kernel: its exclusive-or over a seeded buffer equals numpy's, for sizes on both sides
+    of its unrolled loop."""
+    import torch
+    from paper_2306_08162_amd import binding as ql
+    for words in (4, 4 * 1024 * 256 * 4 + 12, 3_000_004):
+        announce(f"stream probe, {words} words")
+        host = (wl.splitmix64(99 + words, 0, words) >> np.uint64(32)).astype(np.uint32)
+        buf = torch.from_numpy(host.view(np.int32)).cuda()
+        out = torch.zeros(ql.STREAM_PROBE_WORDS, dtype=torch.int32, device="cuda")
+        ql.qlora_stream_probe(buf, words * 4, out)
+        torch.cuda.synchronize()
+        assert int(np.bitwise_xor.reduce(out.cpu().numpy().view(np.uint32))) == int(np.bitwise_xor.reduce(host))
