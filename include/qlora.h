@@ -244,6 +244,22 @@ int qlora_linear_bwd_stacked(const void *dy, const void *x, const uint32_t *pack
                              void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Stacked adapters trained with LoRA dropout (App. B: the fine-tuning runs use a
+ * dropout rate of 0.05; App. D: the task adapter is trained on top of the frozen
+ * recovery adapter): qlora_linear_bwd_stacked with the keep mask of
+ * qlora_linear_bwd_dropout.  The mask acts on the input of the whole stack (both
+ * pairs see keep_scale * (x . keep)), as in the forward pass
+ * qlora_linear_fwd_dropout with the full rank.  keep_mask NULL: the same as
+ * qlora_linear_bwd_stacked.  Arguments, layouts and errors as for the two.
+ */
+int qlora_linear_bwd_dropout_stacked(const void *dy, const void *x, const uint32_t *packed, const void *scales,
+                                     const uint8_t *zeros, const void *A, const void *B, const uint32_t *keep_mask,
+                                     float keep_scale, const void *t_saved, void *dx, float *dA_train, float *dB_train,
+                                     float beta, int frozen_rank, int M, int N, int K, int bits, int group_size,
+                                     int rank, float alpha, int dtype, void *workspace, size_t workspace_bytes,
+                                     void *stream);
+
+/*
  * Sibling projections at small token counts.  Projections that read the same
  * input (q/k/v of an attention block, gate/up of an MLP; the paper adapts "every
  * linear projection", Appendix C) can be handed over together: one launch

@@ -22,7 +22,7 @@ EXPORTS = ["qlora_status_string", "qlora_packed_words", "qlora_workspace_bytes",
            "qlora_actorder_perm", "qlora_pack_permuted", "qlora_gather_columns",
            "qlora_packed_zero_words", "qlora_pack_zeros", "qlora_unpack_zeros",
            "qlora_linear_fwd", "qlora_linear_bwd", "qlora_linear_bwd_accumulate", "qlora_linear_fwd_dropout",
-           "qlora_linear_bwd_dropout", "qlora_linear_bwd_stacked", "qlora_siblings_workspace_bytes", "qlora_linear_fwd_siblings",
+           "qlora_linear_bwd_dropout", "qlora_linear_bwd_stacked", "qlora_linear_bwd_dropout_stacked", "qlora_siblings_workspace_bytes", "qlora_linear_fwd_siblings",
            "qlora_linear_bwd_siblings", "qlora_lrec_workspace_bytes", "qlora_lrec_loss", "qlora_lrec_loss_scaled", "qlora_linear_fwd_static"]
 BENCH_EXPORTS = ["qlora_profile_gemm", "qlora_profile_gemm_span", "qlora_stream_probe"]        # include/qlora_bench.h
 STREAM_PROBE_WORDS = 1024
@@ -92,6 +92,9 @@ def load() -> ctypes.CDLL:
     lib.qlora_linear_bwd_dropout.argtypes = [vp] * 8 + [f32] + [vp] * 4 + [f32] + [c_int] * 6 + [f32, c_int, vp, c_sz, vp]
     lib.qlora_linear_bwd_stacked.restype = c_int
     lib.qlora_linear_bwd_stacked.argtypes = [vp] * 11 + [f32, c_int] + [c_int] * 6 + [f32, c_int, vp, c_sz, vp]
+    lib.qlora_linear_bwd_dropout_stacked.restype = c_int
+    lib.qlora_linear_bwd_dropout_stacked.argtypes = ([vp] * 8 + [f32] + [vp] * 4 + [f32, c_int] + [c_int] * 6 +
+                                                     [f32, c_int, vp, c_sz, vp])
     lib.qlora_siblings_workspace_bytes.restype = c_sz
     lib.qlora_siblings_workspace_bytes.argtypes = [c_int, vp] + [c_int] * 5
     lib.qlora_linear_fwd_siblings.restype = c_int
@@ -280,6 +283,22 @@ def qlora_linear_bwd_stacked(dy, x, packed, scales, zeros, A, B, t_saved, dx, dA
                                          _ptr(workspace), workspace_bytes, _stream(stream))
     if check and st != 0:
         raise QLoraError(st, "qlora_linear_bwd_stacked")
+    return st
+
+
+def qlora_linear_bwd_dropout_stacked(dy, x, packed, scales, zeros, A, B, keep_mask, keep_scale: float, t_saved, dx,
+                                     dA_train, dB_train, beta: float, frozen_rank: int, M: int, N: int, K: int,
+                                     bits: int, group_size: int, rank: int, alpha: float, dtype: int, workspace,
+                                     workspace_bytes: Optional[int] = None, stream=None, check: bool = True) -> int:
+    if workspace_bytes is None:
+        workspace_bytes = _nbytes(workspace)
+    st = load().qlora_linear_bwd_dropout_stacked(_ptr(dy), _ptr(x), _ptr(packed), _ptr(scales), _ptr(zeros), _ptr(A),
+                                                 _ptr(B), _ptr(keep_mask), float(keep_scale), _ptr(t_saved), _ptr(dx),
+                                                 _ptr(dA_train), _ptr(dB_train), float(beta), frozen_rank, M, N, K,
+                                                 bits, group_size, rank, float(alpha), dtype, _ptr(workspace),
+                                                 workspace_bytes, _stream(stream))
+    if check and st != 0:
+        raise QLoraError(st, "qlora_linear_bwd_dropout_stacked")
     return st
 
 

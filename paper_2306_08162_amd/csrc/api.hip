@@ -479,6 +479,17 @@ int qlora_linear_bwd_stacked(const void *dy, const void *x, const uint32_t *pack
                     frozen_rank, M, N, K, bits, group_size, rank, alpha, dtype, workspace, workspace_bytes, stream);
 }
 
+int qlora_linear_bwd_dropout_stacked(const void *dy, const void *x, const uint32_t *packed, const void *scales,
+                                     const uint8_t *zeros, const void *A, const void *B, const uint32_t *keep_mask,
+                                     float keep_scale, const void *t_saved, void *dx, float *dA_train, float *dB_train,
+                                     float beta, int frozen_rank, int M, int N, int K, int bits, int group_size,
+                                     int rank, float alpha, int dtype, void *workspace, size_t workspace_bytes,
+                                     void *stream)
+{
+    return backward(dy, x, packed, scales, zeros, A, B, keep_mask, keep_scale, t_saved, dx, dA_train, dB_train, beta,
+                    frozen_rank, M, N, K, bits, group_size, rank, alpha, dtype, workspace, workspace_bytes, stream);
+}
+
 namespace {
 
 struct SiblingWorkspace {

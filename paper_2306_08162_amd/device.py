@@ -129,6 +129,21 @@ class DeviceLayer:
                                     self.workspace, stream=stream)
         return self.dA_train, self.dB_train
 
+    def backward_dropout_stacked(self, keep_mask, keep_scale: float, frozen_rank: int, beta: float = 0.0,
+                                 use_saved_t: bool = True, stream=None):
+        """backward_stacked with the keep mask of the dropout pass: returns (dA_train, dB_train) device tensors."""
+        c = self.cfg
+        rt = c.rank - frozen_rank
+        if not hasattr(self, "dA_train") or self.dA_train.shape[0] != rt:
+            self.dA_train = torch.zeros((rt, c.K), dtype=torch.float32, device=self.device)
+            self.dB_train = torch.zeros((c.N, rt), dtype=torch.float32, device=self.device)
+        ql.qlora_linear_bwd_dropout_stacked(self.dy, self.x, self.packed, self.scales, self.zeros, self.A, self.B,
+                                            keep_mask, keep_scale, self.t if use_saved_t else None, self.dx,
+                                            self.dA_train, self.dB_train, beta, frozen_rank, c.M, c.N, c.K, c.bits,
+                                            c.group_size, c.rank, c.alpha, self.dtype_flag, self.workspace,
+                                            stream=stream)
+        return self.dA_train, self.dB_train
+
     def forward_dropout(self, keep_mask, keep_scale: float, save_t: bool = True, stream=None):
         """keep_mask: int32 tensor [M, K/32] of keep bits (bit k % 32 of word k / 32)."""
         c = self.cfg
