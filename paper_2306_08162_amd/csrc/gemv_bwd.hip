@@ -540,19 +540,25 @@ __global__ __launch_bounds__(NW * 64) void gemv_bwd_siblings_kernel(const BwdMul
     gemv_bwd_body<BITS, BF16, NW, BW_U>(a, sp - (pi ? ma.slice_end[pi - 1] : 0), sp);
 }
 
-// grid (column blocks + 1, slices): the last workgroup of a slice computes u
+// grid (column blocks + 1, slices): the last workgroup of a slice computes u.  Workgroups are dealt to the eight XCDs
+// round-robin by their linear index, and two neighbouring column blocks share the 128-byte lines of the packed rows
+// (a block covers 64 bytes of a row at 2 and 4 bits): the work items are renumbered so that each XCD gets a
+// contiguous run of (slice, column block) pairs, column block fastest, and a line is fetched into one L2 only.
 template <int BITS, bool BF16>
 __global__ __launch_bounds__(BS_NW * 64) void gemv_bwd_staged_kernel(const BwdMulti ma)
 {
-    const int sp = (int)blockIdx.y;
+    const int gx = (int)gridDim.x, total = gx * (int)gridDim.y;
+    const int linear = (int)blockIdx.y * gx + (int)blockIdx.x, die = linear & 7;
+    const int item = die * (total >> 3) + min(die, total & 7) + (linear >> 3);
+    const int sp = item / gx, cbx = item % gx;
     int pi = 0;
     while (pi + 1 < ma.count && sp >= ma.slice_end[pi]) ++pi;      // wave-uniform
     const BwdArgs a = ma.p[pi];
     const int sp_local = sp - (pi ? ma.slice_end[pi - 1] : 0);
-    if ((int)blockIdx.x + 1 == (int)gridDim.x) {
+    if (cbx + 1 == gx) {
         if (a.r > 0) gemv_bwd_u_body<BF16>(a, sp_local, sp);
     } else {
-        gemv_bwd_staged_body<BITS, BF16>(a, (int)blockIdx.x, sp_local, sp);
+        gemv_bwd_staged_body<BITS, BF16>(a, cbx, sp_local, sp);
     }
 }
 
