@@ -425,7 +425,9 @@ __device__ __forceinline__ void gemv_bwd_staged_body(const BwdArgs &a, const int
         u16x8_t df = *(const u16x8_t *)(buf + T::WBYTES + wc * 512 + (((4 * wave + q) ^ wc) * 16));
         if (!in) df = ZERO8;
         const uint16_t *cs = conv + (st & 1) * (4 * BS_RS) + gl * BS_RS + 32 * wave + 8 * q;
-        const u32x4_t sv = *(const u32x4_t *)cs, zv = *(const u32x4_t *)(cs + 2 * BS_RS);
+        // read with the element type they were written with, then regrouped into pairs
+        const u32x4_t sv = __builtin_bit_cast(u32x4_t, *(const u16x8_t *)cs);
+        const u32x4_t zv = __builtin_bit_cast(u32x4_t, *(const u16x8_t *)(cs + 2 * BS_RS));
         if constexpr (BF16) {
             float s[8], z[8];
 #pragma unroll
