@@ -138,6 +138,38 @@ def test_random_shapes(case):
     check_layer(inp, recompute_t=bool(r) and (M + N) % 2 == 0)
 
 
+def _random_small_token_cases(count, seed):
+    """Seeded random shapes inside the domain of the kernels that stage everything through LDS (up to 16 token rows, K and
+    G multiples of 128): stage counts with and without a tail, one to four weight blocks per workgroup, row slices that
+    do and do not divide the rows, every width, both dtypes, adapters computed in the kernel, handed in, or absent."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    while len(cases) < count:
+        bits = int(rng.choice([2, 3, 4, 8]))
+        K = 128 * int(rng.integers(1, 25))                        # 128 .. 3072
+        divisors = [g for g in range(128, K + 1, 128) if K % g == 0]
+        G = int(rng.choice(divisors))
+        M = int(rng.integers(1, 17))
+        N = 8 * int(rng.integers(1, 120))
+        if rng.random() < 0.3:
+            N = 8 * int(rng.integers(400, 1700))
+        if (N * (K // G)) % 16:
+            N = (N + 15) // 16 * 16
+        r = int(rng.choice([0, 8, 8, 16, 16, 24, 40]))
+        dtype = "f16" if rng.random() < 0.5 else "bf16"
+        cases.append((M, K, N, bits, G, r, dtype))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_small_token_cases(int(os.environ.get("QLORA_FUZZ_CASES", "40")),
+                                                           int(os.environ.get("QLORA_FUZZ_SEED", "20230608")) + 1),
+                         ids=lambda c: "M{}_K{}_N{}_b{}_G{}_r{}_{}".format(*c))
+def test_random_shapes_small_token_counts(case):
+    M, K, N, bits, G, r, dtype = case
+    inp = small_inputs(17 * M + 5 * K + N + bits, M, K, N, bits, G, r, dtype)
+    check_layer(inp, recompute_t=bool(r) and (M + N) % 2 == 0)
+
+
 def test_results_are_bitwise_reproducible():
     import torch
     from paper_2306_08162_amd.device import DeviceLayer
