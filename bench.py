@@ -450,6 +450,32 @@ def run_stacked(iters: int = 20):
     return out
 
 
+def run_mfma_probe(iters: int = 40000, reps: int = 4):
+    """What the matrix cores of this machine sustain: register-resident MFMAs and nothing else (no memory, no LDS, no
+    other arithmetic), two waves per SIMD, about 10 ms per launch, the last of `reps` launches reported.  With constant
+    operands the published peak is reached; with random operands that change from MFMA to MFMA the chip's power
+    management lowers the clock.  Context for the roofline fraction, which is priced at the published peak."""
+    import torch
+    from paper_2306_08162_amd import binding as ql
+    from paper_2306_08162_amd.hiprt import Event
+
+    out = torch.empty(ql.MFMA_PROBE_FLOATS, dtype=torch.float32, device="cuda:0")
+    stream = torch.cuda.current_stream().cuda_stream or None
+    res = {}
+    for name, rnd in (("constant_operands", False), ("random_operands", True)):
+        tf = 0.0
+        for _ in range(reps):
+            e0, e1 = Event(), Event()
+            e0.record(stream)
+            ql.qlora_mfma_probe(out, iters, rnd, stream=stream)
+            e1.record(stream)
+            e1.synchronize()
+            tf = iters * ql.MFMA_PROBE_FLOP_PER_ITER / (e0.elapsed_ms(e1) * 1e-3) / 1e12
+        res[name + "_TFLOPs"] = round(tf, 1)
+    res["what"] = "register-resident v_mfma_f32_32x32x16_f16 only, 2 waves per SIMD, ~10 ms launches"
+    return res
+
+
 def run_dense_library_context(M: int, K: int, N: int, iters: int = 200):
     """CONTEXT ONLY, never part of `value`: the vendor library's dense fp16 GEMM (torch.matmul) on already
     dequantised weights of the headline shape, in the two operand orders of the layer's passes.  It reads four
@@ -565,6 +591,9 @@ def main() -> int:
         "roofline": roofline,
     }
     result.update(extras)
+    if not args.no_small_m:
+        result["mfma_probe"] = run_mfma_probe()
+        result["frac_of_sustained_mfma_rate"] = round(value / result["mfma_probe"]["random_operands_TFLOPs"], 4)
     if args.library_context:
         result["dense_library_context"] = run_dense_library_context(cfg.M, cfg.K, cfg.N)
     if not args.no_cpu_baseline:

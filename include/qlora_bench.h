@@ -41,6 +41,18 @@ int qlora_profile_gemm_span(int span);
 #define QLORA_STREAM_PROBE_WORDS 1024
 int qlora_stream_probe(const void *src, unsigned long long bytes, unsigned int *out, void *stream);
 
+/*
+ * Runs `iters` rounds of eight register-resident v_mfma_f32_32x32x16_f16 per wave on 256 workgroups of eight waves
+ * (two per SIMD: the matrix pipe is never idle) and nothing else: no memory, no LDS, no other arithmetic.  Its rate,
+ * 256 x 8 x iters x 8 x 32768 flop over its duration, is what the matrix cores of this machine sustain.  random != 0:
+ * the operands are pseudo-random fp16 values in (-1, 1) and change from one MFMA to the next (four register sets);
+ * random == 0: small constants, the same for every MFMA.  The two differ because the chip's clock follows its power
+ * draw, and that follows the data.  out: device pointer to 256 * 512 floats (one per thread, so that nothing is
+ * optimised away), 16-byte aligned.  iters >= 1.  Returns 0, or the QLORA_E_* codes of qlora.h for a NULL pointer
+ * (1), iters < 1 (3), a misaligned pointer (7) and HIP errors (9).
+ */
+int qlora_mfma_probe(float *out, int iters, int random, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

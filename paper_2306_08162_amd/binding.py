@@ -24,8 +24,10 @@ EXPORTS = ["qlora_status_string", "qlora_packed_words", "qlora_workspace_bytes",
            "qlora_linear_fwd", "qlora_linear_bwd", "qlora_linear_bwd_accumulate", "qlora_linear_fwd_dropout",
            "qlora_linear_bwd_dropout", "qlora_linear_bwd_stacked", "qlora_linear_bwd_dropout_stacked", "qlora_siblings_workspace_bytes", "qlora_linear_fwd_siblings",
            "qlora_linear_bwd_siblings", "qlora_lrec_workspace_bytes", "qlora_lrec_loss", "qlora_lrec_loss_scaled", "qlora_linear_fwd_static"]
-BENCH_EXPORTS = ["qlora_profile_gemm", "qlora_profile_gemm_span", "qlora_stream_probe"]        # include/qlora_bench.h
+BENCH_EXPORTS = ["qlora_profile_gemm", "qlora_profile_gemm_span", "qlora_stream_probe", "qlora_mfma_probe"]        # include/qlora_bench.h
 STREAM_PROBE_WORDS = 1024
+MFMA_PROBE_FLOATS = 256 * 512              # floats of the probe's output
+MFMA_PROBE_FLOP_PER_ITER = 256 * 8 * 8 * 32768   # per round: workgroups x waves x MFMAs x flop of a 32x32x16 MFMA
 MAX_SIBLINGS, SIBLINGS_MAX_M = 4, 16
 
 _lib = None
@@ -84,6 +86,8 @@ def load() -> ctypes.CDLL:
     lib.qlora_profile_gemm_span.argtypes = [c_int]
     lib.qlora_stream_probe.restype = c_int
     lib.qlora_stream_probe.argtypes = [vp, ctypes.c_ulonglong, vp, vp]
+    lib.qlora_mfma_probe.restype = c_int
+    lib.qlora_mfma_probe.argtypes = [vp, c_int, c_int, vp]
     lib.qlora_linear_bwd_accumulate.restype = c_int
     lib.qlora_linear_bwd_accumulate.argtypes = [vp] * 11 + [f32] + [c_int] * 6 + [f32, c_int, vp, c_sz, vp]
     lib.qlora_linear_fwd_dropout.restype = c_int
@@ -163,6 +167,14 @@ def qlora_stream_probe(src, nbytes: int, out, stream=None, check: bool = True) -
     st = load().qlora_stream_probe(_ptr(src), nbytes, _ptr(out), _stream(stream))
     if check and st != 0:
         raise QLoraError(st, "qlora_stream_probe")
+    return st
+
+
+def qlora_mfma_probe(out, iters: int, random: bool, stream=None, check: bool = True) -> int:
+    """Register-resident MFMAs and nothing else (MFMA_PROBE_FLOP_PER_ITER flop per round); out: MFMA_PROBE_FLOATS floats."""
+    st = load().qlora_mfma_probe(_ptr(out), iters, 1 if random else 0, _stream(stream))
+    if check and st != 0:
+        raise QLoraError(st, "qlora_mfma_probe")
     return st
 
 

@@ -152,6 +152,16 @@ int qlora_stream_probe(const void *src, unsigned long long bytes, uint32_t *out,
     return end_call();
 }
 
+int qlora_mfma_probe(float *out, int iters, int random, void *stream)
+{
+    if (!out) return QLORA_E_NULL;
+    if (iters < 1) return QLORA_E_SHAPE;
+    if (misaligned(out)) return QLORA_E_ALIGN;
+    begin_call();
+    launch_mfma_probe(out, iters, random != 0, (hipStream_t)stream);
+    return end_call();
+}
+
 size_t qlora_packed_words(int N, int K, int bits)
 {
     if (check_weight_shape(N, K, bits) != QLORA_OK) return 0;

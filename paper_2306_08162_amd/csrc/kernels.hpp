@@ -44,6 +44,8 @@ void launch_pack_permuted(const uint8_t *codes, const int32_t *perm, uint32_t *p
 void launch_gather_columns(const void *src, const int32_t *index, void *dst, int M, int K, hipStream_t s);
 // benchmark instrumentation: 1024 partial exclusive-ors of the 32-bit words of a buffer, read once with 16-byte loads
 void launch_stream_probe(const void *src, size_t bytes, uint32_t *out, hipStream_t s);
+// benchmark instrumentation: iters x 8 register-resident 32x32x16 fp16 MFMAs per wave, 256 workgroups of 8 waves
+void launch_mfma_probe(float *out, int iters, bool random, hipStream_t s);
 
 // adapters.hip -- the rank-r side products and the adapter gradients
 // t[M,r] = x[M,K] A[r,K]^T; with a keep mask (LoRA dropout, one bit per element of x, bit k % 32 of word k / 32 of

@@ -310,4 +310,58 @@ void launch_stream_probe(const void *src, size_t bytes, uint32_t *out, hipStream
                  (long)(bytes / 16), out);
 }
 
+// ---- matrix-core probe (benchmark instrumentation): register-resident MFMAs and nothing else
+constexpr int MFMA_PROBE_WGS = 256, MFMA_PROBE_THREADS = 512;
+
+__device__ __forceinline__ uint32_t probe_mix(uint32_t x)
+{
+    x ^= x >> 16;
+    x *= 0x7feb352dU;
+    x ^= x >> 15;
+    x *= 0x846ca68bU;
+    x ^= x >> 16;
+    return x;
+}
+
+template <bool RANDOM>
+__global__ __launch_bounds__(MFMA_PROBE_THREADS) void mfma_probe_kernel(float *__restrict__ out, int iters)
+{
+    float16_t acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+    half8_t a[4], b[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            if constexpr (RANDOM) {
+                const uint32_t r = probe_mix(threadIdx.x * 64 + s * 8 + i + blockIdx.x * 7919);
+                a[s][i] = (half_t)((float)((int)(r & 0xffffu) - 32768) * (1.f / 32768.f));
+                b[s][i] = (half_t)((float)((int)(r >> 16) - 32768) * (1.f / 32768.f));
+            } else {
+                a[s][i] = (half_t)(float)(threadIdx.x & 3);
+                b[s][i] = (half_t)1.f;
+            }
+        }
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i & 3], b[(i + (i >> 2)) & 3], acc[i], 0, 0, 0);
+    }
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) sum += acc[i][v];
+    out[blockIdx.x * MFMA_PROBE_THREADS + threadIdx.x] = sum;
+}
+
+void launch_mfma_probe(float *out, int iters, bool random, hipStream_t s)
+{
+    if (random) QLORA_LAUNCH(mfma_probe_kernel<true>, dim3(MFMA_PROBE_WGS), dim3(MFMA_PROBE_THREADS), 0, s, out, iters);
+    else QLORA_LAUNCH(mfma_probe_kernel<false>, dim3(MFMA_PROBE_WGS), dim3(MFMA_PROBE_THREADS), 0, s, out, iters);
+}
+
 }  // namespace qlora

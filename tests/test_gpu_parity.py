@@ -379,3 +379,29 @@ def test_stream_probe_reads_every_word_once():
         ql.qlora_stream_probe(buf, words * 4, out)
         torch.cuda.synchronize()
         assert int(np.bitwise_xor.reduce(out.cpu().numpy().view(np.uint32))) == int(np.bitwise_xor.reduce(host))
+
+
+def test_mfma_probe_runs_and_its_sums_are_what_the_operands_give():
+    """The benchmark's matrix-core probe.  Constant operands: every wave multiplies rows of (lane & 3) by ones, so after
+    `iters` rounds a thread's 8 x 16 accumulators sum to iters * 8 * 16 * 16 * (its row constant) -- exact in fp32 for
+    small iters.  Random operands: finite, reproducible."""
+    import torch
+    from paper_2306_08162_amd import binding as ql
+    announce("mfma probe")
+    out = torch.zeros(ql.MFMA_PROBE_FLOATS, dtype=torch.float32, device="cuda")
+    iters = 3
+    ql.qlora_mfma_probe(out, iters, False)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().reshape(256, 512)
+    # A[i][k] = (thread & 3) for the lane's row i = lane % 32, B = 1: D[i][j] += 16 * a_i per MFMA; a thread holds 16
+    # entries of D whose rows are 8 * (lane / 32) + (v % 4) + 8 * (v / 4) ... all carry that row's lane constant
+    lane = np.arange(512) % 64
+    rows = (8 * (np.arange(16)[None, :] // 4) + (np.arange(16)[None, :] % 4) + 4 * (lane[:, None] // 32))   # [thread, v]
+    want = (iters * 8 * 16.0 * (rows % 4)).sum(axis=1)
+    assert np.array_equal(got, np.broadcast_to(want, got.shape))
+    ql.qlora_mfma_probe(out, iters, True)
+    torch.cuda.synchronize()
+    first = out.cpu().numpy().copy()
+    ql.qlora_mfma_probe(out, iters, True)
+    torch.cuda.synchronize()
+    assert np.all(np.isfinite(first)) and np.array_equal(first, out.cpu().numpy()) and np.any(first != 0)
