@@ -104,9 +104,9 @@ int qlora_unpack(const uint32_t *packed, uint8_t *codes, int N, int K, int bits,
  * GPTQ-format files keep them bit-packed like the codes): packed_zeros
  * [N, Zw] uint32 with Zw = ceil(groups*bits/32), row n holding the zero-points
  * of its groups in order as one little-endian stream of `bits`-wide fields,
- * the last word zero-padded.  The layer entry points take unpacked uint8
- * zero-points; these two convert at load time (packing them in the kernels
- * would save under 2 % of the weight-side bytes).  groups >= 1, N >= 1,
+ * the last word zero-padded.  Most layer entry points take unpacked uint8
+ * zero-points and these two convert at load time; qlora_linear_fwd_zp and
+ * qlora_linear_bwd_zp take the packed form as it is.  groups >= 1, N >= 1,
  * N * groups < 2^31.  qlora_packed_zero_words returns N * Zw, 0 on bad arguments.
  */
 size_t qlora_packed_zero_words(int N, int groups, int bits);
@@ -258,6 +258,33 @@ int qlora_linear_bwd_dropout_stacked(const void *dy, const void *x, const uint32
                                      float beta, int frozen_rank, int M, int N, int K, int bits, int group_size,
                                      int rank, float alpha, int dtype, void *workspace, size_t workspace_bytes,
                                      void *stream);
+
+/*
+ * The layer with its zero-points left in their storage form (Sec. 3.2 counts
+ * `bits` bits of zero-point per group: INT2 with G = 128 is 2 + (16 + 2) / 128
+ * = 2.14 bits per weight, where a uint8 zero-point makes it 2.19).
+ * packed_zeros is device memory [N, Zw] uint32 as qlora_pack_zeros writes it,
+ * 16-byte aligned; everything else as for qlora_linear_fwd and
+ * qlora_linear_bwd_accumulate, results bit-identical to those calls on the
+ * unpacked zero-points.  The weight-streaming kernels for M <= 16 read the
+ * packed rows themselves (forward: K and group_size multiples of 128, rank
+ * <= 16; backward: bits != 3, the column blocks of 128 or 256 dividing K and
+ * holding at most two groups; both: N * groups a multiple of 16 and N * Zw of
+ * 4: the shapes of the paper's models at bits 2, 4 and 8 all qualify).  For
+ * every other shape the zero-points are first unpacked into the workspace by
+ * one more launch, which is why the workspace is larger:
+ * qlora_workspace_bytes_zp = qlora_workspace_bytes plus N * groups rounded up
+ * to 256 (0 on bad arguments); QLORA_E_WORKSPACE if the buffer is smaller.
+ */
+size_t qlora_workspace_bytes_zp(int M, int N, int K, int bits, int group_size, int rank);
+int qlora_linear_fwd_zp(const void *x, const uint32_t *packed, const void *scales, const uint32_t *packed_zeros,
+                        const void *A, const void *B, void *y, void *t_save, int M, int N, int K, int bits,
+                        int group_size, int rank, float alpha, int dtype, void *workspace, size_t workspace_bytes,
+                        void *stream);
+int qlora_linear_bwd_zp(const void *dy, const void *x, const uint32_t *packed, const void *scales,
+                        const uint32_t *packed_zeros, const void *A, const void *B, const void *t_saved, void *dx,
+                        float *dA, float *dB, float beta, int M, int N, int K, int bits, int group_size, int rank,
+                        float alpha, int dtype, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Sibling projections at small token counts.  Projections that read the same

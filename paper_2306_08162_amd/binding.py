@@ -23,7 +23,8 @@ EXPORTS = ["qlora_status_string", "qlora_packed_words", "qlora_workspace_bytes",
            "qlora_packed_zero_words", "qlora_pack_zeros", "qlora_unpack_zeros",
            "qlora_linear_fwd", "qlora_linear_bwd", "qlora_linear_bwd_accumulate", "qlora_linear_fwd_dropout",
            "qlora_linear_bwd_dropout", "qlora_linear_bwd_stacked", "qlora_linear_bwd_dropout_stacked", "qlora_siblings_workspace_bytes", "qlora_linear_fwd_siblings",
-           "qlora_linear_bwd_siblings", "qlora_lrec_workspace_bytes", "qlora_lrec_loss", "qlora_lrec_loss_scaled", "qlora_linear_fwd_static"]
+           "qlora_linear_bwd_siblings", "qlora_lrec_workspace_bytes", "qlora_lrec_loss", "qlora_lrec_loss_scaled", "qlora_linear_fwd_static",
+           "qlora_workspace_bytes_zp", "qlora_linear_fwd_zp", "qlora_linear_bwd_zp"]
 BENCH_EXPORTS = ["qlora_profile_gemm", "qlora_profile_gemm_span", "qlora_stream_probe", "qlora_mfma_probe"]        # include/qlora_bench.h
 STREAM_PROBE_WORDS = 1024
 MFMA_PROBE_FLOATS = 256 * 512              # floats of the probe's output
@@ -88,6 +89,12 @@ def load() -> ctypes.CDLL:
     lib.qlora_stream_probe.argtypes = [vp, ctypes.c_ulonglong, vp, vp]
     lib.qlora_mfma_probe.restype = c_int
     lib.qlora_mfma_probe.argtypes = [vp, c_int, c_int, vp]
+    lib.qlora_workspace_bytes_zp.restype = c_sz
+    lib.qlora_workspace_bytes_zp.argtypes = [c_int] * 6
+    lib.qlora_linear_fwd_zp.restype = c_int
+    lib.qlora_linear_fwd_zp.argtypes = lib.qlora_linear_fwd.argtypes
+    lib.qlora_linear_bwd_zp.restype = c_int
+    lib.qlora_linear_bwd_zp.argtypes = [vp] * 11 + [f32] + [c_int] * 6 + [f32, c_int, vp, c_sz, vp]
     lib.qlora_linear_bwd_accumulate.restype = c_int
     lib.qlora_linear_bwd_accumulate.argtypes = [vp] * 11 + [f32] + [c_int] * 6 + [f32, c_int, vp, c_sz, vp]
     lib.qlora_linear_fwd_dropout.restype = c_int
@@ -391,6 +398,37 @@ def qlora_linear_bwd_accumulate(dy, x, packed, scales, zeros, A, B, t_saved, dx,
                                             workspace_bytes, _stream(stream))
     if check and st != 0:
         raise QLoraError(st, "qlora_linear_bwd_accumulate")
+    return st
+
+
+def qlora_workspace_bytes_zp(M: int, N: int, K: int, bits: int, group_size: int, rank: int) -> int:
+    return int(load().qlora_workspace_bytes_zp(M, N, K, bits, group_size, rank))
+
+
+def qlora_linear_fwd_zp(x, packed, scales, packed_zeros, A, B, y, t_save, M: int, N: int, K: int, bits: int,
+                        group_size: int, rank: int, alpha: float, dtype: int, workspace,
+                        workspace_bytes: Optional[int] = None, stream=None, check: bool = True) -> int:
+    if workspace_bytes is None:
+        workspace_bytes = _nbytes(workspace)
+    st = load().qlora_linear_fwd_zp(_ptr(x), _ptr(packed), _ptr(scales), _ptr(packed_zeros), _ptr(A), _ptr(B),
+                                    _ptr(y), _ptr(t_save), M, N, K, bits, group_size, rank, float(alpha), dtype,
+                                    _ptr(workspace), workspace_bytes, _stream(stream))
+    if check and st != 0:
+        raise QLoraError(st, "qlora_linear_fwd_zp")
+    return st
+
+
+def qlora_linear_bwd_zp(dy, x, packed, scales, packed_zeros, A, B, t_saved, dx, dA, dB, beta: float, M: int, N: int,
+                        K: int, bits: int, group_size: int, rank: int, alpha: float, dtype: int, workspace,
+                        workspace_bytes: Optional[int] = None, stream=None, check: bool = True) -> int:
+    if workspace_bytes is None:
+        workspace_bytes = _nbytes(workspace)
+    st = load().qlora_linear_bwd_zp(_ptr(dy), _ptr(x), _ptr(packed), _ptr(scales), _ptr(packed_zeros), _ptr(A),
+                                    _ptr(B), _ptr(t_saved), _ptr(dx), _ptr(dA), _ptr(dB), float(beta), M, N, K, bits,
+                                    group_size, rank, float(alpha), dtype, _ptr(workspace), workspace_bytes,
+                                    _stream(stream))
+    if check and st != 0:
+        raise QLoraError(st, "qlora_linear_bwd_zp")
     return st
 
 

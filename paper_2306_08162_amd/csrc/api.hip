@@ -277,11 +277,15 @@ int qlora_linear_fwd(const void *x, const uint32_t *packed, const void *scales, 
 
 // The forward pass behind every single-projection entry point.  `ws` + w.t_off holds t when it is not saved, `ws` +
 // w.split_off the planes of a split contraction; ws_bytes is what the caller's buffer holds beyond `ws`.
+// zpacked: the zero-points in their bit-packed storage form instead of `zeros`; a kernel that reads that form takes
+// them as they are, for any other they are unpacked into zscratch (N * groups bytes) first.
 static int forward(const void *x, const uint32_t *packed, const void *scales, const uint8_t *zeros, const void *A,
                    const void *B, const uint32_t *keep_mask, float keep_scale, void *y, void *t_save, int M, int N,
                    int K, int bits, int group_size, int rank, float alpha, int dtype, char *ws, const Workspace &w,
-                   size_t ws_bytes, void *stream)
+                   size_t ws_bytes, void *stream, const uint32_t *zpacked = nullptr, uint8_t *zscratch = nullptr)
 {
+    if (zpacked) zeros = zscratch;
+    if (misaligned(zpacked)) return QLORA_E_ALIGN;
     if (!x || !packed || !scales || !zeros || !y) return QLORA_E_NULL;
     if (rank > 0 && (!A || !B)) return QLORA_E_NULL;
     if (misaligned(x) || misaligned(packed) || misaligned(scales) || misaligned(zeros) || misaligned(y) ||
@@ -300,10 +304,14 @@ static int forward(const void *x, const uint32_t *packed, const void *scales, co
         if (t_first) launch_lora_down(x, A, t, M, K, rank, p.bf16, keep_mask, keep_scale, s);
         GemmTimer timer(s);
         const void *tc = t;
-        launch_fwd_small(p, 1, x, &packed, &scales, &zeros, &A, &B, &tc, &t, &y, &N, t_first, s);
+        if (!zpacked || !launch_fwd_small(p, 1, x, &packed, &scales, &zeros, &A, &B, &tc, &t, &y, &N, t_first, s, &zpacked)) {
+            if (zpacked) launch_unpack_zeros(zpacked, zscratch, N, K / group_size, bits, s);
+            launch_fwd_small(p, 1, x, &packed, &scales, &zeros, &A, &B, &tc, &t, &y, &N, t_first, s);
+        }
     } else {
         void *t = nullptr;
         mark_pre_begin(s);
+        if (zpacked) launch_unpack_zeros(zpacked, zscratch, N, K / group_size, bits, s);
         if (rank > 0) {
             t = t_save ? t_save : (void *)(ws + w.t_off);
             launch_lora_down(x, A, t, M, K, rank, p.bf16, keep_mask, keep_scale, s);
@@ -403,10 +411,12 @@ static int backward(const void *dy, const void *x, const uint32_t *packed, const
                     const void *A, const void *B, const uint32_t *keep_mask, float keep_scale, const void *t_saved,
                     void *dx, float *dA, float *dB, float beta, int frozen, int M, int N, int K, int bits,
                     int group_size, int rank, float alpha, int dtype, void *workspace, size_t workspace_bytes,
-                    void *stream)
+                    void *stream, const uint32_t *zpacked = nullptr, uint8_t *zscratch = nullptr)
 {
     const int st = check_problem(M, N, K, bits, group_size, rank, dtype);
     if (st != QLORA_OK) return st;
+    if (zpacked) zeros = zscratch;               // as in forward()
+    if (misaligned(zpacked)) return QLORA_E_ALIGN;
     if (frozen < 0 || frozen % 8 != 0 || (frozen > 0 && frozen >= rank)) return QLORA_E_RANK;
     if (!dy || !packed || !scales || !zeros || !dx) return QLORA_E_NULL;
     if (rank > 0 && (!x || !A || !B || !dA || !dB)) return QLORA_E_NULL;
@@ -430,13 +440,18 @@ static int backward(const void *dy, const void *x, const uint32_t *packed, const
             t = ws + w.t_off;
         }
         GemmTimer timer(s);
-        launch_bwd_small(p, 1, &dy, x, &packed, &scales, &zeros, &A, &B, &t, dx, &dA, &dB, &N,
-                         (float *)(ws + w.partial_off), (float *)(ws + w.upartial_off), beta, keep_mask, keep_scale, frozen,
-                         s);
+        float *const partial = (float *)(ws + w.partial_off), *const upartial = (float *)(ws + w.upartial_off);
+        if (!zpacked || !launch_bwd_small(p, 1, &dy, x, &packed, &scales, &zeros, &A, &B, &t, dx, &dA, &dB, &N, partial,
+                                          upartial, beta, keep_mask, keep_scale, frozen, s, &zpacked)) {
+            if (zpacked) launch_unpack_zeros(zpacked, zscratch, N, K / group_size, bits, s);
+            launch_bwd_small(p, 1, &dy, x, &packed, &scales, &zeros, &A, &B, &t, dx, &dA, &dB, &N, partial, upartial, beta,
+                             keep_mask, keep_scale, frozen, s);
+        }
         return end_call();
     }
     void *u = nullptr;
     mark_pre_begin(s);
+    if (zpacked) launch_unpack_zeros(zpacked, zscratch, N, K / group_size, bits, s);
     if (rank > 0) {
         u = ws + w.u_off;
         launch_lora_u(dy, B, u, M, N, rank, p.bf16, s);
@@ -498,6 +513,42 @@ int qlora_linear_bwd_dropout_stacked(const void *dy, const void *x, const uint32
 {
     return backward(dy, x, packed, scales, zeros, A, B, keep_mask, keep_scale, t_saved, dx, dA_train, dB_train, beta,
                     frozen_rank, M, N, K, bits, group_size, rank, alpha, dtype, workspace, workspace_bytes, stream);
+}
+
+// ---- zero-points in their bit-packed storage form: the workspace is followed by room for their unpacked form
+size_t qlora_workspace_bytes_zp(int M, int N, int K, int bits, int group_size, int rank)
+{
+    if (check_problem(M, N, K, bits, group_size, rank, QLORA_F16) != QLORA_OK) return 0;
+    return carve(M, N, K, rank, bits).total + round_up((size_t)N * (K / group_size));
+}
+
+int qlora_linear_fwd_zp(const void *x, const uint32_t *packed, const void *scales, const uint32_t *packed_zeros,
+                        const void *A, const void *B, void *y, void *t_save, int M, int N, int K, int bits,
+                        int group_size, int rank, float alpha, int dtype, void *workspace, size_t workspace_bytes,
+                        void *stream)
+{
+    const int st = check_problem(M, N, K, bits, group_size, rank, dtype);
+    if (st != QLORA_OK) return st;
+    if (!packed_zeros) return QLORA_E_NULL;
+    const Workspace w = carve(M, N, K, rank, bits);
+    if (!workspace || workspace_bytes < w.total + round_up((size_t)N * (K / group_size))) return QLORA_E_WORKSPACE;
+    return forward(x, packed, scales, nullptr, A, B, nullptr, 1.f, y, t_save, M, N, K, bits, group_size, rank, alpha,
+                   dtype, (char *)workspace, w, w.total, stream, packed_zeros, (uint8_t *)workspace + w.total);
+}
+
+int qlora_linear_bwd_zp(const void *dy, const void *x, const uint32_t *packed, const void *scales,
+                        const uint32_t *packed_zeros, const void *A, const void *B, const void *t_saved, void *dx,
+                        float *dA, float *dB, float beta, int M, int N, int K, int bits, int group_size, int rank,
+                        float alpha, int dtype, void *workspace, size_t workspace_bytes, void *stream)
+{
+    const int st = check_problem(M, N, K, bits, group_size, rank, dtype);
+    if (st != QLORA_OK) return st;
+    if (!packed_zeros) return QLORA_E_NULL;
+    const Workspace w = carve(M, N, K, rank, bits);
+    if (!workspace || workspace_bytes < w.total + round_up((size_t)N * (K / group_size))) return QLORA_E_WORKSPACE;
+    return backward(dy, x, packed, scales, nullptr, A, B, nullptr, 1.f, t_saved, dx, dA, dB, beta, 0, M, N, K, bits,
+                    group_size, rank, alpha, dtype, workspace, w.total, stream, packed_zeros,
+                    (uint8_t *)workspace + w.total);
 }
 
 namespace {

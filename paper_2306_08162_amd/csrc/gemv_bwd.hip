@@ -30,6 +30,8 @@ struct BwdArgs {
     float *upartial;      // [slices][16][64]
     int M, N, K, r, ng, rows_per_slice;
     uint32_t magic;
+    const uint32_t *zpacked;   // zero-points in their bit-packed storage form [N, zw] (then `zeros` is not read), or NULL
+    int zw;                    // words per row of zpacked
 };
 
 // code c (compile-time) of a lane's CL codes held in WORDS words
@@ -339,16 +341,21 @@ __device__ __forceinline__ void gemv_bwd_staged_body(const BwdArgs &a, const int
     const uint32_t dy_row = (uint32_t)min(dy_m, a.M - 1) * (uint32_t)N * 2u;
     // windows: request `wave` moves rows 32 wave .. 32 wave + 32, lane l the scale piece (l even) or the zero-point
     // piece (l odd) of row 32 wave + l / 2
-    const uint32_t s_all = (uint32_t)N * ng * 2u, z_all = (uint32_t)N * ng;
+    // (bit-packed zero-points: the piece of the row's words that holds the block's groups; two groups of a block
+    // share a word, the code widths here being powers of two)
+    const bool zpk = a.zpacked != nullptr;                                  // workgroup-uniform
+    const uint32_t zrow = zpk ? (uint32_t)a.zw * 4u : (uint32_t)ng, zg0 = zpk ? ((uint32_t)(g0 * BITS) >> 5) * 4u : (uint32_t)g0;
+    const uint8_t *zsrc = zpk ? (const uint8_t *)a.zpacked : a.zeros;
+    const uint32_t s_all = (uint32_t)N * ng * 2u, z_all = (uint32_t)N * zrow;
     auto issue = [&](int st) {
         const uint32_t base = lds0 + (uint32_t)(st % NST) * STAGE;
         {
             const int row = 32 * wave + (lane >> 1);
             const uint32_t n = (uint32_t)min(st * BS_RS + row, row_max) + nbeg;
             const uint32_t e = n * ng + g0;
-            const uint32_t sat = (e * 2u) & ~15u, zat = e & ~15u;
+            const uint32_t sat = (e * 2u) & ~15u, zat = (n * zrow + zg0) & ~15u;
             const uint8_t *src = (lane & 1) == 0 ? (const uint8_t *)a.scales + (sat + 16u <= s_all ? sat : 0u)
-                                                 : a.zeros + (zat + 16u <= z_all ? zat : 0u);
+                                                 : zsrc + (zat + 16u <= z_all ? zat : 0u);
             dma16_at(src, base + T::WBYTES + T::DYB + (uint32_t)wave * 1024u);
         }
         {
@@ -365,14 +372,17 @@ __device__ __forceinline__ void gemv_bwd_staged_body(const BwdArgs &a, const int
         if (threadIdx.x < BS_RS) {
             const int row = threadIdx.x, rs = st * BS_RS + row;
             const uint8_t *win = lds + (size_t)(st % NST) * STAGE + T::WBYTES + T::DYB + row * 32;
-            const uint32_t e = ((uint32_t)min(rs, row_max) + nbeg) * ng + g0;
+            const uint32_t n = (uint32_t)min(rs, row_max) + nbeg, e = n * ng + g0;
             const uint32_t sw = *(const uint32_t *)(win + ((e * 2u) & 12u)) >> (8 * ((e * 2u) & 3u));     // two scales
-            const uint32_t zw = *(const uint32_t *)(win + 16 + (e & 12u)) >> (8 * (e & 3u));             // two zero-points
+            const uint32_t za = n * zrow + zg0;                                                          // as in issue()
+            uint32_t zw = *(const uint32_t *)(win + 16 + (za & 12u));                                    // two zero-points
+            zw >>= zpk ? (uint32_t)(g0 * BITS) & 31u : 8u * (za & 3u);
+            const uint32_t zbits = zpk ? (uint32_t)BITS : 8u, zmask = (1u << zbits) - 1u;
             uint16_t *dst = conv + (st & 1) * (4 * BS_RS) + row;
 #pragma unroll
             for (int g = 0; g < 2; ++g) {
                 dst[g * BS_RS] = rs < rows ? (uint16_t)(sw >> (16 * g)) : (uint16_t)0;
-                dst[(2 + g) * BS_RS] = f32_to_f16_bits(-(float)((zw >> (8 * g)) & 0xffu));
+                dst[(2 + g) * BS_RS] = f32_to_f16_bits(-(float)((zw >> (zbits * g)) & zmask));
             }
         }
     };
@@ -763,16 +773,20 @@ bool bwd_staged_applies(const BwdMulti &m)
             const int G = a.K / a.ng;
             if (a.K % CB != 0 || !(G % CB == 0 || (CB % G == 0 && CB / G <= 2))) return false;
             if ((long)a.N * a.K * BITS / 8 >= (1ll << 32) || ((long)a.N * a.ng) % 16 != 0) return false;   // whole 16-byte pieces of constants
-            const uintptr_t bits_or = (uintptr_t)a.dy | (uintptr_t)a.packed | (uintptr_t)a.scales | (uintptr_t)a.zeros;
-            if ((bits_or & 15) != 0) return false;
+            const uintptr_t bits_or = (uintptr_t)a.dy | (uintptr_t)a.packed | (uintptr_t)a.scales | (uintptr_t)a.zeros |
+                                      (uintptr_t)a.zpacked;
+            if ((bits_or & 15) != 0 || (a.zpacked && ((long)a.N * a.zw) % 4 != 0)) return false;
         }
         return true;
     }
 }
 
+// *taken = false and nothing launched: bit-packed zero-points were handed in and the staged kernel, the one that
+// reads them, does not take the shape
 template <int BITS, bool BF16>
-void launch_bwd_bits(const BwdMulti &m, hipStream_t s)
+void launch_bwd_bits(const BwdMulti &m, hipStream_t s, bool *taken)
 {
+    *taken = true;
     if constexpr (BITS != 3) {
         if (bwd_staged_applies<BITS>(m)) {
             auto kern = gemv_bwd_staged_kernel<BITS, BF16>;
@@ -781,6 +795,10 @@ void launch_bwd_bits(const BwdMulti &m, hipStream_t s)
             QLORA_LAUNCH(kern, grid, dim3(BS_NW * 64), BwdStaged<BITS>::LDS, s, m);
             return;
         }
+    }
+    if (m.p[0].zpacked) {
+        *taken = false;
+        return;
     }
     const int slices = m.slice_end[m.count - 1];
     int max_rows = 0;
@@ -853,11 +871,11 @@ int gemv_bwd_slices_siblings(int count, const int *N, int K, int bits, int *slic
     return total;
 }
 
-void launch_bwd_small(const Problem &p, int count, const void *const *dy, const void *x,
+bool launch_bwd_small(const Problem &p, int count, const void *const *dy, const void *x,
                       const uint32_t *const *packed, const void *const *scales, const uint8_t *const *zeros,
                       const void *const *A, const void *const *B, const void *const *t, void *dx, float *const *dA,
                       float *const *dB, const int *N, float *partial, float *upartial, float beta, const uint32_t *keep,
-                      float keep_scale, int frozen, hipStream_t s)
+                      float keep_scale, int frozen, hipStream_t s, const uint32_t *const *zpacked)
 {
     int slices[MAX_SIBLINGS];
     const int total = gemv_bwd_slices_siblings(count, N, p.K, p.bits, slices);
@@ -868,11 +886,14 @@ void launch_bwd_small(const Problem &p, int count, const void *const *dy, const 
         const int rows_per_slice = ((N[i] + slices[i] - 1) / slices[i] + 31) / 32 * 32;
         m.p[i] = BwdArgs{(const uint16_t *)dy[i], packed[i], (const uint16_t *)scales[i], zeros[i],
                          (const uint16_t *)(B ? B[i] : nullptr), partial, upartial, p.M, N[i], p.K, p.r, p.K / p.G,
-                         rows_per_slice, group_magic(p.G)};
+                         rows_per_slice, group_magic(p.G), zpacked ? zpacked[i] : nullptr,
+                         zpacked ? zero_words(p.K / p.G, p.bits) : 0};
         end += slices[i];
         m.slice_end[i] = end;
     }
-    QLORA_BITS_DTYPE(launch_bwd_bits, m, s);
+    bool taken = true;
+    QLORA_BITS_DTYPE(launch_bwd_bits, m, s, &taken);
+    if (!taken) return false;
     const int rt = count == 1 ? p.r - frozen : p.r;     // adapter columns with gradients (siblings: no frozen part)
     const int xb = (int)(((long)p.M * p.K + 255) / 256), ab = (int)(((long)rt * p.K + 255) / 256);
     if (count == 1) {
@@ -889,7 +910,7 @@ void launch_bwd_small(const Problem &p, int count, const void *const *dy, const 
             if (p.bf16) QLORA_LAUNCH((gemv_bwd_finish_kernel<true, false>), grid, block, 0, s, f);
             else QLORA_LAUNCH((gemv_bwd_finish_kernel<false, false>), grid, block, 0, s, f);
         }
-        return;
+        return true;
     }
     FinishMulti f{};
     f.partial = partial;
@@ -918,6 +939,7 @@ void launch_bwd_small(const Problem &p, int count, const void *const *dy, const 
         QLORA_LAUNCH((gemv_bwd_finish_siblings_kernel<true>), dim3(blocks), dim3(256), 0, s, f);
     else
         QLORA_LAUNCH((gemv_bwd_finish_siblings_kernel<false>), dim3(blocks), dim3(256), 0, s, f);
+    return true;
 }
 
 }  // namespace qlora

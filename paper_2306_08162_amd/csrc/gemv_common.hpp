@@ -6,6 +6,9 @@
 
 namespace qlora {
 
+// words per row of the bit-packed zero-points of `groups` groups (Sec. 3.2's storage count: bits per group)
+inline int zero_words(int groups, int bits) { return (groups * bits + 31) / 32; }
+
 // ---- forward: arguments of one projection, and of up to four sibling projections in one launch
 struct FwdArgs {
     const uint16_t *x;
@@ -18,6 +21,8 @@ struct FwdArgs {
     int M, N, K, r, ng;
     float sc;
     uint32_t magic;
+    const uint32_t *zpacked;  // zero-points in their bit-packed storage form [N, zw] (then `zeros` is not read), or NULL
+    int zw;                   // words per row of zpacked
 };
 
 // Sibling projections (q/k/v, gate/up) read the same x: one launch serves up to four of them.  They share M, K, the
@@ -28,9 +33,20 @@ struct FwdMulti {
     int count;
 };
 
-// the forward kernels of one code width (each width is its own translation unit)
+// the forward kernels of one code width (each width is its own translation unit).  false: nothing was launched
+// (bit-packed zero-points were handed in and no kernel that reads them takes the shape)
 template <int BITS>
-void launch_fwd_small_bits(const FwdMulti &m, int rg, bool bf16, hipStream_t s);
+bool launch_fwd_small_bits(const FwdMulti &m, int rg, bool bf16, hipStream_t s);
+
+// zero-point of group g from a row of bit-packed zero-points (little-endian stream of BITS-wide fields)
+template <int BITS>
+__device__ __forceinline__ uint32_t packed_zero(const uint32_t *row_words, int g)
+{
+    const int o = g * BITS, w = o >> 5, sh = o & 31;
+    uint32_t v = row_words[w] >> sh;
+    if (BITS == 3 && sh > 29) v |= row_words[w + 1] << (32 - sh);
+    return v & ((1u << BITS) - 1u);
+}
 
 namespace {
 

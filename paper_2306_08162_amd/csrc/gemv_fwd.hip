@@ -16,10 +16,10 @@ namespace qlora {
 
 bool fwd_small_computes_t(int rank) { return rank > 0 && rank <= 32; }
 
-void launch_fwd_small(const Problem &p, int count, const void *x, const uint32_t *const *packed,
+bool launch_fwd_small(const Problem &p, int count, const void *x, const uint32_t *const *packed,
                       const void *const *scales, const uint8_t *const *zeros, const void *const *A,
                       const void *const *B, const void *const *t_in, void *const *t_out, void *const *y, const int *N,
-                      bool t_given, hipStream_t s)
+                      bool t_given, hipStream_t s, const uint32_t *const *zpacked)
 {
     const bool fused = fwd_small_computes_t(p.r) && !t_given;
     FwdMulti m{};
@@ -40,13 +40,15 @@ void launch_fwd_small(const Problem &p, int count, const void *x, const uint32_t
                          p.r,
                          p.K / p.G,
                          p.sc,
-                         group_magic(p.G)};
+                         group_magic(p.G),
+                         zpacked ? zpacked[i] : nullptr,
+                         zpacked ? zero_words(p.K / p.G, p.bits) : 0};
     const int rg = fused ? (p.r + 15) / 16 : 0;
     switch (p.bits) {
-    case 2: launch_fwd_small_bits<2>(m, rg, p.bf16, s); break;
-    case 3: launch_fwd_small_bits<3>(m, rg, p.bf16, s); break;
-    case 4: launch_fwd_small_bits<4>(m, rg, p.bf16, s); break;
-    default: launch_fwd_small_bits<8>(m, rg, p.bf16, s); break;
+    case 2: return launch_fwd_small_bits<2>(m, rg, p.bf16, s);
+    case 3: return launch_fwd_small_bits<3>(m, rg, p.bf16, s);
+    case 4: return launch_fwd_small_bits<4>(m, rg, p.bf16, s);
+    default: return launch_fwd_small_bits<8>(m, rg, p.bf16, s);
     }
 }
 

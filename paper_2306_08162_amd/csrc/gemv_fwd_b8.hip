@@ -3,6 +3,6 @@
 
 namespace qlora {
 
-template void launch_fwd_small_bits<8>(const FwdMulti &, int, bool, hipStream_t);
+template bool launch_fwd_small_bits<8>(const FwdMulti &, int, bool, hipStream_t);
 
 }  // namespace qlora

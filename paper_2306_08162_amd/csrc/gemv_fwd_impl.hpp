@@ -492,11 +492,15 @@ namespace qlora {
 namespace {
 
 template <int BITS, bool BF16>
-void launch_fwd_mb(const FwdMulti &m, int rg, hipStream_t s)
+bool launch_fwd_mb(const FwdMulti &m, int rg, hipStream_t s)
 {
+    const bool zpacked = m.p[0].zpacked != nullptr;       // only the kernel with staged group constants reads those
+    if (zpacked && m.p[0].M > 16) return false;
     switch ((m.p[0].M + 15) / 16) {
     case 1:
-        if (!launch_fwd_m16<BITS, BF16>(m, rg, s)) launch_fwd_staged<BITS, BF16, 1>(m, rg, s);
+        if (launch_fwd_m16<BITS, BF16>(m, rg, s)) return true;
+        if (zpacked) return false;
+        launch_fwd_staged<BITS, BF16, 1>(m, rg, s);
         break;
     case 2:
         for (int i = 0; i < m.count; ++i) {
@@ -513,17 +517,15 @@ void launch_fwd_mb(const FwdMulti &m, int rg, hipStream_t s)
         for (int i = 0; i < m.count; ++i) launch_fwd_rg<BITS, BF16, 4>(m.p[i], rg, s);
         break;
     }
+    return true;
 }
 
 }  // namespace
 
 template <int BITS>
-void launch_fwd_small_bits(const FwdMulti &m, int rg, bool bf16, hipStream_t s)
+bool launch_fwd_small_bits(const FwdMulti &m, int rg, bool bf16, hipStream_t s)
 {
-    if (bf16)
-        launch_fwd_mb<BITS, true>(m, rg, s);
-    else
-        launch_fwd_mb<BITS, false>(m, rg, s);
+    return bf16 ? launch_fwd_mb<BITS, true>(m, rg, s) : launch_fwd_mb<BITS, false>(m, rg, s);
 }
 
 }  // namespace qlora

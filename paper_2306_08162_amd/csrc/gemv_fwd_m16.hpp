@@ -36,9 +36,9 @@ __device__ __forceinline__ int wswz(int n, int piece)
 
 constexpr int m16_xa(int bits, int ar) { return (16 + ar) * 2 * m16_ks(bits); }               // a wave's slices of x and A
 constexpr int m16_stage(int bits, int nb, int ar) { return M16_NW * m16_xa(bits, ar) + nb * 16 * m16_ks(bits) * bits; }
-constexpr int m16_table(int nb, int ng)                                                       // scales (2 B), zero-points (1 B),
-{                                                                                             // each filled in whole KB
-    return ((nb * 16 * ng * 2 + 1023) & ~1023) + ((nb * 16 * ng + 1023) & ~1023);
+constexpr int m16_table(int nb, int ng, int zrow)     // scales (2 B per group), zero-points (zrow bytes per row: one per
+{                                                     // group, or the row's packed words), each filled in whole KB
+    return ((nb * 16 * ng * 2 + 1023) & ~1023) + ((nb * 16 * zrow + 1023) & ~1023);
 }
 constexpr int m16_tc(int ar) { return ar > 0 ? 16 : 64; }                                     // columns of t kept
 constexpr int m16_static(int ar) { return 16 * (m16_tc(ar) + 1) * 4; }
@@ -66,6 +66,7 @@ __device__ __forceinline__ void gemv_fwd_m16_body(const FwdArgs &a, const int wg
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)lds;
     const uint16_t *sct = (const uint16_t *)(lds + NST * STAGE);                          // [R][ng], then, from the next
     const uint8_t *zt = lds + NST * STAGE + ((R * ng * 2 + 1023) & ~1023);                // full KB on, the zero-points
+    const int zrow = a.zpacked ? a.zw * 4 : ng;                                         // bytes of a row of zero-points
 
     // ---- this lane's part of the copies.  Weight instruction i of a stage fills slots 64 i .. 64 i + 64 of the chunk.
     const uint32_t *wbase = a.packed + (long)n0 * Kw;
@@ -111,9 +112,10 @@ __device__ __forceinline__ void gemv_fwd_m16_body(const FwdArgs &a, const int wg
     // ---- group constants of all rows of the workgroup: copied as they lie (the rows are neighbours), 1 KB per request;
     //      a piece past the end of the array repeats the array's first one (it belongs to rows past N)
     {
-        const uint32_t sbytes = (uint32_t)R * ng * 2u, zbytes = (uint32_t)R * ng;
-        const uint32_t s_all = (uint32_t)a.N * ng * 2u, z_all = (uint32_t)a.N * ng;
-        const uint32_t s0 = (uint32_t)n0 * ng * 2u, z0 = (uint32_t)n0 * ng;
+        const uint32_t sbytes = (uint32_t)R * ng * 2u, zbytes = (uint32_t)R * zrow;
+        const uint32_t s_all = (uint32_t)a.N * ng * 2u, z_all = (uint32_t)a.N * zrow;
+        const uint32_t s0 = (uint32_t)n0 * ng * 2u, z0 = (uint32_t)n0 * zrow;
+        const void *zsrc = a.zpacked ? (const void *)a.zpacked : (const void *)a.zeros;
         const uint32_t tb = lds0 + NST * STAGE, zb = tb + ((sbytes + 1023u) & ~1023u);
         for (uint32_t o = (uint32_t)wave * 1024u; o < sbytes; o += NW * 1024u) {
             const uint32_t at = s0 + o + lane * 16u;
@@ -121,7 +123,7 @@ __device__ __forceinline__ void gemv_fwd_m16_body(const FwdArgs &a, const int wg
         }
         for (uint32_t o = (uint32_t)wave * 1024u; o < zbytes; o += NW * 1024u) {
             const uint32_t at = z0 + o + lane * 16u;
-            dma16(a.zeros, at + 16u <= z_all ? at : 0u, zb + o);
+            dma16(zsrc, at + 16u <= z_all ? at : 0u, zb + o);
         }
     }
     issue(0, 0);
@@ -195,7 +197,7 @@ __device__ __forceinline__ void gemv_fwd_m16_body(const FwdArgs &a, const int wg
                 for (int i = UB / 4; i < BITS; ++i) w[nb][i] = 0u;
             }
             sc[nb] = live ? f16_bits_to_f32(sct[n * ng + grp]) : 0.f;
-            zp[nb] = (float)zt[n * ng + grp];
+            zp[nb] = a.zpacked ? (float)packed_zero<BITS>((const uint32_t *)(zt + n * zrow), grp) : (float)zt[n * ng + grp];
         }
         wait_lds();                                          // everything of this stage is in registers
         const bool more = st + 2 < S;                        // workgroup-uniform
@@ -295,19 +297,21 @@ __global__ __launch_bounds__(M16_NW * 64) void gemv_fwd_m16_kernel(const FwdMult
     gemv_fwd_m16_body<BITS, BF16, NB, AR>(a, (int)blockIdx.x - (pi ? ma.wg_end[pi - 1] : 0));
 }
 
-// largest NB whose two stages and tables fit in LDS (0: none)
+inline int m16_zrow(const FwdArgs &a) { return a.zpacked ? a.zw * 4 : a.ng; }
+
+// largest NB whose stages and tables fit in LDS (0: none)
 template <int BITS>
-inline int m16_nb_max(int ar, int ng)
+inline int m16_nb_max(int ar, int ng, int zrow)
 {
     for (int nb = 4; nb >= 1; --nb)
-        if (m16_nst(BITS) * m16_stage(BITS, nb, ar) + m16_table(nb, ng) + m16_static(ar) <= M16_LDS) return nb;
+        if (m16_nst(BITS) * m16_stage(BITS, nb, ar) + m16_table(nb, ng, zrow) + m16_static(ar) <= M16_LDS) return nb;
     return 0;
 }
 
 template <int BITS, bool BF16, int NB, int AR>
 void launch_fwd_m16_one(FwdMulti m, hipStream_t s)
 {
-    const int lds = m16_nst(BITS) * m16_stage(BITS, NB, AR) + m16_table(NB, m.p[0].ng);
+    const int lds = m16_nst(BITS) * m16_stage(BITS, NB, AR) + m16_table(NB, m.p[0].ng, m16_zrow(m.p[0]));
     int wgs = 0;
     for (int i = 0; i < m.count; ++i) {
         wgs += (blocks16(m.p[i].N) + NB - 1) / NB;
@@ -348,11 +352,11 @@ bool launch_fwd_m16(const FwdMulti &m, int rg, hipStream_t s)
     for (int i = 0; i < m.count; ++i) {
         const FwdArgs &b = m.p[i];            // 16-byte requests: aligned arrays, constants in whole pieces
         const uintptr_t bits_or = (uintptr_t)b.x | (uintptr_t)b.packed | (uintptr_t)b.scales | (uintptr_t)b.zeros |
-                                  (rg ? (uintptr_t)b.A : 0);
-        if ((bits_or & 15) != 0 || ((long)b.N * b.ng) % 16 != 0) return false;
+                                  (uintptr_t)b.zpacked | (rg ? (uintptr_t)b.A : 0);
+        if ((bits_or & 15) != 0 || ((long)b.N * b.ng) % 16 != 0 || ((long)b.N * m16_zrow(b)) % 16 != 0) return false;
     }
     const int ar = rg == 0 ? 0 : (a.r <= 8 ? 8 : 16);
-    const int nb_max = m16_nb_max<BITS>(ar, a.ng);
+    const int nb_max = m16_nb_max<BITS>(ar, a.ng, m16_zrow(a));
     if (nb_max < 2) return false;
     // one round of the 256 compute units if the rows allow it; siblings that do not fit one round together go one by one
     int nb = 0;

@@ -99,11 +99,13 @@ constexpr int MAX_SIBLINGS = 4;                // projections that read the same
 // `count` sibling projections (same x, M, K, code width, grouping, rank; own weights, adapters, N and outputs):
 // y[i] (and t_out[i], if not NULL and the kernel forms t) from one launch up to 16 token rows, one launch each above;
 // t_in[i] is used when the kernel does not form t (ranks above 32, or t_given: t was computed beforehand, e.g. under
-// dropout).  The arrays are host arrays of `count` device pointers.
-void launch_fwd_small(const Problem &p, int count, const void *x, const uint32_t *const *packed,
+// dropout).  The arrays are host arrays of `count` device pointers.  With `zpacked` (the zero-points of each
+// projection in their bit-packed storage form, [N, zero_words]) `zeros` is not read; only the staged kernel for up
+// to 16 rows reads that form, and where it does not take the shape nothing is launched and false comes back.
+bool launch_fwd_small(const Problem &p, int count, const void *x, const uint32_t *const *packed,
                       const void *const *scales, const uint8_t *const *zeros, const void *const *A,
                       const void *const *B, const void *const *t_in, void *const *t_out, void *const *y, const int *N,
-                      bool t_given, hipStream_t s);
+                      bool t_given, hipStream_t s, const uint32_t *const *zpacked = nullptr);
 // Row slices of the backward kernel for `count` sibling projections launched together: slices[i] for each, the
 // total returned (count == 1: gemv_bwd_slices).
 int gemv_bwd_slices_siblings(int count, const int *N, int K, int bits, int *slices);
@@ -112,12 +114,13 @@ int gemv_bwd_slices_siblings(int count, const int *N, int K, int bits, int *slic
 // arrays are host arrays of `count` device pointers.  keep != NULL (LoRA dropout, single projection only): the
 // adapter's share of dX is multiplied by keep_scale * keep and x stands for keep_scale * x * keep in dA.
 // frozen (single projection only): the first `frozen` adapter columns have no gradient; dA is [r - frozen, K], dB
-// [N, r - frozen].
-void launch_bwd_small(const Problem &p, int count, const void *const *dy, const void *x,
+// [N, r - frozen].  zpacked: as for launch_fwd_small (here the staged kernel reads that form; false, and nothing
+// launched, where it does not take the shape).
+bool launch_bwd_small(const Problem &p, int count, const void *const *dy, const void *x,
                       const uint32_t *const *packed, const void *const *scales, const uint8_t *const *zeros,
                       const void *const *A, const void *const *B, const void *const *t, void *dx, float *const *dA,
                       float *const *dB, const int *N, float *partial, float *upartial, float beta, const uint32_t *keep,
-                      float keep_scale, int frozen, hipStream_t s);
+                      float keep_scale, int frozen, hipStream_t s, const uint32_t *const *zpacked = nullptr);
 
 // loss.hip -- the LREC objective (KL student || teacher + next-token CE, mean over tokens) and its gradient
 // kl, ce (per token) and grad may be NULL; tok receives lambda_kl*KL + lambda_ce*CE per token, loss_mean their mean;

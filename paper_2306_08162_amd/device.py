@@ -5,6 +5,8 @@ C ABI the same way.  Nothing here computes anything.
 """
 from __future__ import annotations
 
+from typing import Optional
+
 import numpy as np
 import torch
 
@@ -93,15 +95,40 @@ class DeviceLayer:
         self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=dev)
         return self
 
+    def use_packed_zeros(self, packed_zeros: Optional[np.ndarray] = None) -> None:
+        """Hand the zero-points over in their bit-packed storage form ([N, ceil(groups * bits / 32)] uint32, packed
+        by the caller; None: packed here from the resident ones by qlora_pack_zeros): forward() and backward() then
+        go through qlora_linear_fwd_zp / qlora_linear_bwd_zp and the unpacked zero-points are dropped."""
+        c = self.cfg
+        want = (c.N, ql.qlora_packed_zero_words(c.N, c.groups, c.bits) // c.N)
+        if packed_zeros is None:
+            self.packed_zeros = torch.empty(want, dtype=torch.int32, device=self.device)
+            ql.qlora_pack_zeros(self.zeros, self.packed_zeros, c.N, c.groups, c.bits)
+            torch.cuda.synchronize(self.device)
+        else:
+            if packed_zeros.shape != want:
+                raise ValueError(f"packed zero-points of shape {packed_zeros.shape}, expected {want}")
+            self.packed_zeros = _dev(np.ascontiguousarray(packed_zeros).view(np.int32), self.device)
+        self.zeros = None
+        nbytes = ql.qlora_workspace_bytes_zp(c.M, c.N, c.K, c.bits, c.group_size, c.rank)
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+
     # -- calls through the C ABI -------------------------------------------------
     def forward(self, save_t: bool = True, stream=None):
         c = self.cfg
+        if getattr(self, "packed_zeros", None) is not None:
+            ql.qlora_linear_fwd_zp(self.x, self.packed, self.scales, self.packed_zeros, self.A, self.B, self.y,
+                                   self.t if (save_t and c.rank) else None, c.M, c.N, c.K, c.bits, c.group_size,
+                                   c.rank, c.alpha, self.dtype_flag, self.workspace, stream=stream)
+            return
         ql.qlora_linear_fwd(self.x, self.packed, self.scales, self.zeros, self.A, self.B, self.y,
                             self.t if (save_t and c.rank) else None, c.M, c.N, c.K, c.bits, c.group_size, c.rank,
                             c.alpha, self.dtype_flag, self.workspace, stream=stream)
 
     def backward(self, use_saved_t: bool = True, stream=None):
         c = self.cfg
+        if getattr(self, "packed_zeros", None) is not None:
+            return self.backward_accumulate(0.0, use_saved_t, stream)
         ql.qlora_linear_bwd(self.dy, self.x, self.packed, self.scales, self.zeros, self.A, self.B,
                             self.t if (use_saved_t and c.rank) else None, self.dx,
                             self.dA if c.rank else None, self.dB if c.rank else None,
@@ -110,6 +137,13 @@ class DeviceLayer:
 
     def backward_accumulate(self, beta: float, use_saved_t: bool = True, stream=None):
         c = self.cfg
+        if getattr(self, "packed_zeros", None) is not None:
+            ql.qlora_linear_bwd_zp(self.dy, self.x, self.packed, self.scales, self.packed_zeros, self.A, self.B,
+                                   self.t if (use_saved_t and c.rank) else None, self.dx,
+                                   self.dA if c.rank else None, self.dB if c.rank else None, beta,
+                                   c.M, c.N, c.K, c.bits, c.group_size, c.rank, c.alpha, self.dtype_flag,
+                                   self.workspace, stream=stream)
+            return
         ql.qlora_linear_bwd_accumulate(self.dy, self.x, self.packed, self.scales, self.zeros, self.A, self.B,
                                        self.t if (use_saved_t and c.rank) else None, self.dx,
                                        self.dA if c.rank else None, self.dB if c.rank else None, beta,
@@ -216,6 +250,8 @@ class ActOrderLayer(DeviceLayer):
 
     def backward(self, use_saved_t: bool = True, stream=None):
         c = self.cfg
+        if getattr(self, "packed_zeros", None) is not None:
+            return self.backward_accumulate(0.0, use_saved_t, stream)
         super().backward(use_saved_t=use_saved_t, stream=stream)
         ql.qlora_gather_columns(self.dx, self.inv_perm, self.dx_checkpoint_order, c.M, c.K, stream=stream)
 
@@ -260,6 +296,8 @@ class DeviceSiblings:
 
     def backward(self, use_saved_t: bool = True, stream=None):
         c = self.cfg
+        if getattr(self, "packed_zeros", None) is not None:
+            return self.backward_accumulate(0.0, use_saved_t, stream)
         ql.qlora_linear_bwd_siblings(self._each("dy"), self.x, self._each("packed"), self._each("scales"),
                                      self._each("zeros"), self._each("A") if c.rank else None,
                                      self._each("B") if c.rank else None,

@@ -169,12 +169,13 @@ def integer_inputs(seed: int, M: int, K: int, N: int, bits: int, G: int, r: int,
 
 
 def check_layer(inp: wl.LayerInputs, rows: np.ndarray | None = None, recompute_t: bool = False,
-                device: str = "cuda:0", exact: bool = False) -> dict:
+                device: str = "cuda:0", exact: bool = False, packed_zeros: bool = False) -> dict:
     """Forward + backward on the GPU, compared with the oracle.
 
     `rows`: token rows on which y / dX are compared (None = all).  dA, dB and
     the packed words are always compared in full.  `exact`: the inputs make every
     result an exactly representable integer (integer_inputs): demand equality.
+    `packed_zeros`: the zero-points reach the library in their bit-packed storage form, packed by the oracle.
     Returns the Frobenius figures.
     """
     import torch
@@ -182,8 +183,10 @@ def check_layer(inp: wl.LayerInputs, rows: np.ndarray | None = None, recompute_t
 
     c = inp.cfg
     announce(f"{c.name}: M={c.M} K={c.K} N={c.N} bits={c.bits} G={c.group_size} r={c.rank} {c.dtype} "
-             f"recompute_t={recompute_t}" + (" exact" if exact else ""))
+             f"recompute_t={recompute_t}" + (" exact" if exact else "") + (" packed zero-points" if packed_zeros else ""))
     layer = DeviceLayer(inp, device)
+    if packed_zeros:
+        layer.use_packed_zeros(oracle.pack_zeros(inp.zeros, c.bits))
     layer.forward(save_t=not recompute_t)
     layer.backward(use_saved_t=not recompute_t)
     torch.cuda.synchronize()
