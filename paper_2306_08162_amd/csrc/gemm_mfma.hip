@@ -10,6 +10,8 @@
 // 16 bit) -> LDS (two stages); four MFMA waves pull the activation tile global -> LDS directly (three stages, no
 // registers) and read 16-byte fragments of both operands into v_mfma_f32_32x32x16.  One barrier per stage.
 // The dequantised weight never reaches HBM.  The rank-r LoRA term is folded in as extra contraction steps.
+// Launches that give every compute unit at least one 256 x 256 tile use a second arrangement of the same parts
+// (SYM below): eight waves that each stage, load and multiply an eighth.
 #include "common.hpp"
 #include "dequant.hpp"
 #include "kernels.hpp"
@@ -102,19 +104,26 @@ __device__ __forceinline__ constexpr int wswz(int row) { return ((row & 3) << 2)
 // dX = dY Wd + keep_sc * keep (.) (u A), so it cannot ride in the accumulators.  The LoRA steps are left out; the
 // staging waves lay the tile's rows of u and columns of A (both fetched at kernel start) beside the epilogue area, and
 // the copy-out adds the masked product to every 8-element piece before it is stored.
-template <int BITS, bool BF16, bool TRANS, int BM, int BN, int WM, int WN, bool MASKED = false>
-__global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const GemmArgs a)
+//
+// SYM (256 x 256 tiles, for launches of at least one such tile per compute unit): four waves, one per SIMD, each with
+// a 128 x 128 block of accumulators (256 registers, which leaves no room for a second wave on the SIMD) and each
+// doing a quarter of everything: activation loads, weight staging and the MFMAs.  Twice the flops per byte moved
+// through LDS and through the direct-to-LDS path of the 256 x 128 tile.
+template <int BITS, bool BF16, bool TRANS, int BM, int BN, int WM, int WN, bool MASKED = false, bool SYM = false>
+__global__ __launch_bounds__(WM * WN * 64 + (SYM ? 0 : STAGERS)) void qgemm_kernel(const GemmArgs a)
 {
     static_assert(!MASKED || TRANS, "the dropout mask acts on dX only");
     constexpr int MW = WM * WN;                     // MFMA waves
-    constexpr int THREADS = MW * 64 + STAGERS;
+    constexpr int THREADS = MW * 64 + (SYM ? 0 : STAGERS);
     static_assert(MW == 4 || MW == 8, "one or two MFMA waves per SIMD");
+    static_assert(!SYM || !MASKED, "symmetric waves: no masked epilogue");
+    constexpr int NSTG = SYM ? MW * 64 : STAGERS;   // staging threads: all of them, or the four staging waves
     static_assert(BN % 128 == 0 && BM % 128 == 0, "tile shape");
     constexpr int TM = BM / WM, TN = BN / WN;       // per-wave output tile
     constexpr int MI = TM / 32, NI = TN / 32;       // 32x32 MFMA blocks per wave
     constexpr int XDMA = BM / 8 / MW;               // direct-to-LDS loads per MFMA wave per stage (8 rows each)
     static_assert(XDMA >= 4 && XDMA % 4 == 0, "loads are spread over the four k-steps");
-    constexpr int WU = BN / 128;                    // 32-code weight units per staging thread per stage
+    constexpr int WU = 2 * BN / NSTG;               // 32-code weight units per staging thread per stage
     constexpr int XS = BM * BK;                     // halfs per activation stage (128-byte rows, swizzled)
     constexpr int NXS = GEMM_NXS;                   // (2 would let two workgroups share a CU's LDS: measured slower)
     static_assert(NXS == 2 || NXS == 3, "activation stages");
@@ -125,8 +134,9 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
     // sixteen different bank quads (the stagers' 16-byte writes, one row per lane), and four consecutive rows put
     // four consecutive pieces into disjoint runs of 16 banks (the transposing reads: 4 rows x 64 bytes per half
     // wave).  Unpadded 320-byte rows served the reads equally well but made the writes collide four ways.
-    constexpr int WPITCH = TRANS ? BN : LDS_STRIDE;
-    constexpr int WS = TRANS ? BK * WPITCH : BN * LDS_STRIDE;   // halfs per weight stage
+    // SYM, forward: 128-byte rows with the activation tile's slot swizzle instead of the padding (LDS is full).
+    constexpr int WPITCH = TRANS ? BN : (SYM ? BK : LDS_STRIDE);
+    constexpr int WS = TRANS ? BK * WPITCH : BN * WPITCH;       // halfs per weight stage
     using Regs = StageRegs<BITS, WU>;
 
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
@@ -140,8 +150,8 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
     // wave cannot hide its own instruction issue behind its MFMAs.
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform, kept in a scalar register
-    const bool stager = wave >= MW;
-    const int stid = tid - MW * 64;                 // index among the staging threads
+    const bool stager = SYM || wave >= MW, feeder = SYM || wave < MW;
+    const int stid = SYM ? tid : tid - MW * 64;     // index among the staging threads
     const int cw = wave, wm = cw / WN, wn = cw % WN;
     const int NO = TRANS ? a.K : a.N;    // output columns
     const int KC = TRANS ? a.N : a.K;    // contraction length
@@ -194,7 +204,7 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
     // 8 (b/2) + e, columns 16 (b%2) + 4g .. +4 of the 16 x 32 k-step slab, and lane l ends up with contraction
     // elements 8 (l/32) .. +4 of column l % 32: half an MFMA operand; the second read starts four rows further down.
     // The row's swizzle key is 4 e + 2 (l/32) + (second read), so each of the 2 NI reads has its own offset.
-    const int boff = TRANS ? 0 : (wn * TN + fr) * LDS_STRIDE + fh * 8;
+    const int boff = TRANS ? 0 : (wn * TN + fr) * WPITCH + (SYM ? 0 : fh * 8);
     int toff[TRANS ? NI : 1][2];
     if constexpr (TRANS) {
         const int e = (lane & 15) >> 2, row = 8 * (lane >> 5) + e;
@@ -222,9 +232,10 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
                                  (uint16_t)hi[0], (uint16_t)hi[1], (uint16_t)hi[2], (uint16_t)hi[3]};
             }
         } else {
-            const uint16_t *Bs = wsm + wstage * WS + boff + ks * 16;
+            // (SYM: the slot key (row >> 1) & 7 is the same 32 rows further down)
+            const uint16_t *Bs = wsm + wstage * WS + boff + (SYM ? ((2 * ks + fh) ^ ((fr >> 1) & 7)) * 8 : ks * 16);
 #pragma unroll
-            for (int j = 0; j < NI; ++j) f.b[j] = *(const u16x8_t *)(Bs + j * 32 * LDS_STRIDE);
+            for (int j = 0; j < NI; ++j) f.b[j] = *(const u16x8_t *)(Bs + j * 32 * WPITCH);
         }
     };
     auto mfma_frags = [&](const Frags &f) {
@@ -235,9 +246,152 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
     };
 
     constexpr int EXT_STEPS = 2;                                        // LoRA steps whose operands are prefetched
-    constexpr int EXT_A = BM * 2 / STAGERS, EXT_W = BN * 2 / STAGERS;   // pieces per staging thread and LoRA step
+    constexpr int EXT_A = BM * 2 / NSTG, EXT_W = BN * 2 / NSTG;   // pieces per staging thread and LoRA step
     u16x8_t ext_a[EXT_STEPS][EXT_A], ext_w[EXT_STEPS][EXT_W];
 
+    // global -> registers for stage kt.  Branch-free: every address is clamped into the valid range and
+    // whatever lies beyond the contraction length (or beyond the weight's rows / columns) is neutralised by a
+    // zero scale, so stages past the end may be fetched and staged harmlessly.
+    auto load_global = [&](int kt, Regs &rg) {
+        const int kbase = (kt_first + kt) * BK;
+#pragma unroll
+        for (int i = 0; i < WU; ++i) {
+            const int u = stid + NSTG * i;
+            int n, k0;
+            bool ok;
+            if constexpr (TRANS) {          // 64 contraction rows n, BN/32 units across the output columns k
+                n = kbase + (u & 63);
+                k0 = col0 + (u >> 6) * 32;
+                ok = n < a.N && k0 < a.K;
+            } else {                        // BN output rows n, 2 units along the contraction k
+                n = col0 + (u >> 1);
+                k0 = kbase + (u & 1) * 32;
+                ok = k0 < a.K;
+            }
+            n = min(n, a.N - 1);
+            k0 = min(k0, a.K - 32);
+            load_unit<BITS>(a.packed + (long)n * Kw + (k0 >> 5) * BITS, rg.w[i]);
+            const long gi = (long)n * ng + (a.g32_magic ? (int)__umulhi((uint32_t)(k0 >> 5), a.g32_magic) : (k0 >> 5));
+            rg.s[i] = a.scales[gi];
+            rg.z[i] = a.zeros[gi];
+            rg.ok[i] = ok;
+        }
+    };
+
+    // registers -> LDS: every unit dequantised 8 codes at a time; parts p0 .. p1 of unit i
+    auto stage_parts = [&](const Regs &rg, int buf, int i, int p0, int p1) {
+        uint16_t *Bs = wsm + buf * WS;
+        const int u = stid + NSTG * i;
+        DequantConst<BITS, BF16> dq;
+        dq.set(rg.ok[i] ? f16_bits_to_f32(rg.s[i]) : 0.f, (float)rg.z[i]);
+#pragma unroll
+        for (int part = p0; part < p1; ++part) {
+            const u16x8_t v = dequant8<BITS, BF16>(rg.w[i], part, dq);
+            if constexpr (TRANS) {
+                *(u16x8_t *)(Bs + (u & 63) * WPITCH + ((((u >> 6) * 4 + part) ^ wswz(u & 63)) * 8)) = v;
+            } else if constexpr (SYM) {        // row u / 2, pieces 4 (u % 2) + part, slot key (row / 2) % 8
+                *(u16x8_t *)(Bs + (u >> 1) * WPITCH + ((((u & 1) * 4 + part) ^ ((u >> 2) & 7)) * 8)) = v;
+            } else {
+                *(u16x8_t *)(Bs + (u >> 1) * LDS_STRIDE + (u & 1) * 32 + part * 8) = v;
+            }
+        }
+    };
+    auto stage = [&](const Regs &rg, int buf) {
+#pragma unroll
+        for (int i = 0; i < WU; ++i) stage_parts(rg, buf, i, 0, 4);
+    };
+
+    if constexpr (SYM) {
+        // ---- symmetric waves: every wave requests an MW-th of the activation tile, stages an MW-th of the weight
+        //      stage and multiplies its own block.  Per 64-deep stage and wave: 16 MI NI / 4 MFMAs in four k-steps,
+        //      XDMA direct-to-LDS requests (a quarter per k-step), WU units dequantised into the other weight
+        //      buffer (half a unit per k-step) and WU units requested from memory NSETS stages ahead.
+        static_assert((WU == 1 || WU == 2) && NXS == 3, "a quarter of the staging per k-step; three activation stages");
+        const int drow = lane >> 3;
+        const int dchunk = ((lane & 7) ^ ((4 * cw + (drow >> 1)) & 7)) * 8;
+        const uint32_t xs_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint16_t *)xs;
+        uint32_t xoff[XDMA];
+#pragma unroll
+        for (int i = 0; i < XDMA; ++i)
+            xoff[i] = (uint32_t)min(row0 + (MW * i + cw) * 8 + drow, a.M - 1) * (uint32_t)KC * 2u;
+        auto issue_x = [&](int kt, int stage, int i) {
+            const uint32_t k2 = (uint32_t)min((kt_first + kt) * BK + dchunk, KC - 8) * 2u;
+            const uint32_t dst = xs_lds + (uint32_t)(stage * XS + (MW * i + cw) * 512) * 2u;
+            dma16(a.act, xoff[i] + k2, (uint32_t)__builtin_amdgcn_readfirstlane((int)dst));
+        };
+        // a k-step's MFMAs with the next fragments' LDS reads, a piece of dequantisation and its LDS writes spread
+        // between them
+        auto spread = [&]() {
+#pragma unroll
+            for (int i = 0; i < MI * NI; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                        // one MFMA
+                if (i < MI + (TRANS ? 2 * NI : NI)) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
+            }
+        };
+        // Requests complete in the order they were made.  Per stage a wave first requests its weight units (at least
+        // WL instructions), then the XDMA activation pieces for the stage after next; "the activation pieces of the
+        // next stage have landed" is therefore "at most XDMA + WL requests are outstanding".
+        constexpr int WL = WU * (BITS == 3 ? 3 : (BITS == 8 ? 2 : 1));
+        constexpr int NSETS = 3;
+        Regs rs[NSETS];
+#pragma unroll
+        for (int i = 0; i < NSETS; ++i) load_global(i, rs[i]);
+#pragma unroll
+        for (int i = 0; i < XDMA; ++i) issue_x(0, 0, i);
+#pragma unroll
+        for (int i = 0; i < XDMA; ++i) issue_x(1, 1, i);
+        stage(rs[0], 0);
+        load_global(NSETS, rs[0]);
+        wait_vm_and_barrier<XDMA + WL>();       // activation stage 0 and every wave's share of weight stage 0 are in LDS
+        Frags f[2];
+        load_frags(0, 0, 0, f[0]);
+        int xstage = 0;
+        // stage kt: rg holds the units of stage kt + 1, and is refilled with those of stage kt + 1 + NSETS
+        auto step = [&](int kt, Regs &rg) {
+            const int wstage = kt & 1, wfill = wstage ^ 1;
+            const int xnext = xstage + 1 == NXS ? 0 : xstage + 1;
+            const int xfill = xnext + 1 == NXS ? 0 : xnext + 1;
+            auto issue_quarter = [&](int qtr) {
+#pragma unroll
+                for (int i = qtr * (XDMA / 4); i < (qtr + 1) * (XDMA / 4); ++i) issue_x(kt + 2, xfill, i);
+            };
+            auto stage_quarter = [&](int qtr) {      // WU parts: quarter 4 i / WU + .. of unit i
+                stage_parts(rg, wfill, qtr * WU / 4, (qtr * WU) % 4, (qtr * WU) % 4 + WU);
+            };
+            load_frags(xstage, wstage, 1, f[1]);
+            stage_quarter(0);
+            mfma_frags(f[0]);
+            spread();
+            issue_quarter(0);
+            load_frags(xstage, wstage, 2, f[0]);
+            stage_quarter(1);
+            mfma_frags(f[1]);
+            spread();
+            issue_quarter(1);
+            load_frags(xstage, wstage, 3, f[1]);
+            stage_quarter(2);
+            mfma_frags(f[0]);
+            spread();
+            issue_quarter(2);
+            stage_quarter(3);
+            issue_quarter(3);
+            wait_vm_and_barrier<XDMA + WL>();   // activation stage kt + 1 has landed; weight stage kt + 1 is written
+            load_global(kt + 1 + NSETS, rg);
+            load_frags(xnext, wfill, 0, f[0]);
+            mfma_frags(f[1]);
+            spread();
+            xstage = xnext;
+        };
+        int kt0 = 0;
+        for (; kt0 + NSETS <= KT; kt0 += NSETS) {
+#pragma unroll
+            for (int i = 0; i < NSETS; ++i) step(kt0 + i, rs[(i + 1) % NSETS]);
+        }
+#pragma unroll
+        for (int i = 0; i < NSETS - 1; ++i)
+            if (kt0 + i < KT) step(kt0 + i, rs[(i + 1) % NSETS]);
+        wait_vm_and_barrier<0>();               // nothing in flight any more: LDS is quiet
+    } else
     if (!stager) {
         // ---- MFMA waves ----
         __builtin_amdgcn_s_setprio(1);          // when both kinds of wave are ready, the matrix pipe's feeder goes first
@@ -311,13 +465,13 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
             for (int st = 0; st < EXT_STEPS; ++st) {
 #pragma unroll
                 for (int i = 0; i < EXT_A; ++i) {
-                    const int c = stid + STAGERS * i, r = c >> 1, j = 16 * st + (c & 1) * 8;
+                    const int c = stid + NSTG * i, r = c >> 1, j = 16 * st + (c & 1) * 8;
                     ext_a[st][i] = u16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
                     if (j < a.r) ext_a[st][i] = *(const u16x8_t *)(a.ext_act + (long)min(row0 + r, a.M - 1) * a.r + j);
                 }
 #pragma unroll
                 for (int i = 0; i < EXT_W; ++i) {
-                    const int c = stid + STAGERS * i;
+                    const int c = stid + NSTG * i;
                     ext_w[st][i] = u16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
                     if constexpr (TRANS) {
                         const int j = 16 * st + c / (BN / 8), col = col0 + (c % (BN / 8)) * 8;
@@ -329,55 +483,6 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
                 }
             }
         }
-        // global -> registers for stage kt.  Branch-free: every address is clamped into the valid range and
-        // whatever lies beyond the contraction length (or beyond the weight's rows / columns) is neutralised by a
-        // zero scale, so stages past the end may be fetched and staged harmlessly.
-        auto load_global = [&](int kt, Regs &rg) {
-            const int kbase = (kt_first + kt) * BK;
-#pragma unroll
-            for (int i = 0; i < WU; ++i) {
-                const int u = stid + STAGERS * i;
-                int n, k0;
-                bool ok;
-                if constexpr (TRANS) {          // 64 contraction rows n, BN/32 units across the output columns k
-                    n = kbase + (u & 63);
-                    k0 = col0 + (u >> 6) * 32;
-                    ok = n < a.N && k0 < a.K;
-                } else {                        // BN output rows n, 2 units along the contraction k
-                    n = col0 + (u >> 1);
-                    k0 = kbase + (u & 1) * 32;
-                    ok = k0 < a.K;
-                }
-                n = min(n, a.N - 1);
-                k0 = min(k0, a.K - 32);
-                load_unit<BITS>(a.packed + (long)n * Kw + (k0 >> 5) * BITS, rg.w[i]);
-                const long gi = (long)n * ng + (a.g32_magic ? (int)__umulhi((uint32_t)(k0 >> 5), a.g32_magic) : (k0 >> 5));
-                rg.s[i] = a.scales[gi];
-                rg.z[i] = a.zeros[gi];
-                rg.ok[i] = ok;
-            }
-        };
-
-        // registers -> LDS: every unit dequantised 8 codes at a time
-        auto stage = [&](const Regs &rg, int buf) {
-            uint16_t *Bs = wsm + buf * WS;
-#pragma unroll
-            for (int i = 0; i < WU; ++i) {
-                const int u = stid + STAGERS * i;
-                DequantConst<BITS, BF16> dq;
-                dq.set(rg.ok[i] ? f16_bits_to_f32(rg.s[i]) : 0.f, (float)rg.z[i]);
-#pragma unroll
-                for (int part = 0; part < 4; ++part) {
-                    const u16x8_t v = dequant8<BITS, BF16>(rg.w[i], part, dq);
-                    if constexpr (TRANS) {
-                        *(u16x8_t *)(Bs + (u & 63) * WPITCH + ((((u >> 6) * 4 + part) ^ wswz(u & 63)) * 8)) = v;
-                    } else {
-                        *(u16x8_t *)(Bs + (u >> 1) * LDS_STRIDE + (u & 1) * 32 + part * 8) = v;
-                    }
-                }
-            }
-        };
-
         // stage kt+1 is written while the MFMA waves work on stage kt; NSETS later stages are in flight from
         // memory (one register set each)
         constexpr int NSETS = 3;
@@ -417,12 +522,12 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
             for (int st = 0; st < EXT_STEPS; ++st) {
 #pragma unroll
                 for (int i = 0; i < EXT_A; ++i) {
-                    const int c = stid + STAGERS * i;
+                    const int c = stid + NSTG * i;
                     *(u16x8_t *)(side_u + (c >> 1) * SIDE_R + 16 * st + (c & 1) * 8) = ext_a[st][i];
                 }
 #pragma unroll
                 for (int i = 0; i < EXT_W; ++i) {
-                    const int c = stid + STAGERS * i;
+                    const int c = stid + NSTG * i;
                     *(u16x8_t *)(side_a + (16 * st + c / (BN / 8)) * BN + (c % (BN / 8)) * 8) = ext_w[st][i];
                 }
             }
@@ -430,13 +535,13 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
     }
     if (!MASKED && a.r > 0 && split == 0) {                 // the first workgroup of a split contraction adds it
         const int nsteps = (a.r + 15) / 16, width = nsteps * 16;
-        if (stager && nsteps <= EXT_STEPS) {                // operands already in registers
+        if (!SYM && stager && nsteps <= EXT_STEPS) {        // operands already in registers
 #pragma unroll
             for (int st = 0; st < EXT_STEPS; ++st) {
                 if (st >= nsteps) break;
 #pragma unroll
                 for (int i = 0; i < EXT_A; ++i) {
-                    const int c = stid + STAGERS * i, r = c >> 1, jc = 2 * st + (c & 1);
+                    const int c = stid + NSTG * i, r = c >> 1, jc = 2 * st + (c & 1);
                     u16x8_t p;
 #pragma unroll
                     for (int h = 0; h < 8; ++h) p[h] = to16<BF16>(a.sc * cvt16<BF16>(ext_a[st][i][h]));
@@ -444,17 +549,17 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
                 }
 #pragma unroll
                 for (int i = 0; i < EXT_W; ++i) {
-                    const int c = stid + STAGERS * i;
+                    const int c = stid + NSTG * i;
                     if constexpr (TRANS)
                         *(u16x8_t *)(wsm + (16 * st + c / (BN / 8)) * WPITCH
                                      + (((c % (BN / 8)) ^ wswz(c / (BN / 8))) * 8)) = ext_w[st][i];
-                    else
+                    else if constexpr (!SYM)
                         *(u16x8_t *)(wsm + (c >> 1) * LDS_STRIDE + 16 * st + (c & 1) * 8) = ext_w[st][i];
                 }
             }
         } else if (stager) {
             const int cpr = width / 8;                      // 8-element chunks per row
-            for (int c = stid; c < BM * cpr; c += STAGERS) {
+            for (int c = stid; c < BM * cpr; c += NSTG) {
                 const int r = c / cpr, jc = c % cpr, j = jc * 8;
                 u16x8_t p = {0, 0, 0, 0, 0, 0, 0, 0};
                 if (j < a.r) {
@@ -466,24 +571,25 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
                 *(u16x8_t *)(xs + r * BK + ((jc ^ ((r >> 1) & 7)) * 8)) = p;  // same swizzle as the main loop
             }
             if constexpr (TRANS) {          // rows j of A, the tile's columns contiguous: the stage's own layout
-                for (int c = stid; c < width * (BN / 8); c += STAGERS) {
+                for (int c = stid; c < width * (BN / 8); c += NSTG) {
                     const int j = c / (BN / 8), col = col0 + (c % (BN / 8)) * 8;
                     u16x8_t p = {0, 0, 0, 0, 0, 0, 0, 0};
                     if (j < a.r && col < NO) p = *(const u16x8_t *)(a.ext_w + (long)j * a.K + col);
                     *(u16x8_t *)(wsm + j * WPITCH + (((c % (BN / 8)) ^ wswz(j)) * 8)) = p;
                 }
             } else {
-                for (int c = stid; c < BN * cpr; c += STAGERS) {
+                for (int c = stid; c < BN * cpr; c += NSTG) {
                     const int r = c / cpr, j = (c % cpr) * 8;
                     const int col = col0 + r;
                     u16x8_t p = {0, 0, 0, 0, 0, 0, 0, 0};
                     if (j < a.r && col < NO) p = *(const u16x8_t *)(a.ext_w + (long)col * a.r + j);
-                    *(u16x8_t *)(wsm + r * LDS_STRIDE + j) = p;
+                    if constexpr (SYM) *(u16x8_t *)(wsm + r * WPITCH + (((c % cpr) ^ ((r >> 1) & 7)) * 8)) = p;
+                    else *(u16x8_t *)(wsm + r * LDS_STRIDE + j) = p;
                 }
             }
         }
         __syncthreads();
-        if (!stager) {
+        if (feeder) {
             for (int ks = 0; ks < nsteps; ++ks) {
                 Frags fx;
                 load_frags(0, 0, ks, fx);
@@ -499,7 +605,7 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
     if (a.splits > 1) {
         // split contraction: the fp32 accumulators go to this split's plane as they are (a lane's 32 neighbours
         // write 128 consecutive bytes of a row); a second kernel sums the planes in order and rounds once
-        if (!stager) {
+        if (feeder) {
             float *P = a.part + (size_t)split * a.M * NO;
 #pragma unroll
             for (int i = 0; i < MI; ++i)
@@ -515,7 +621,7 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
         }
         return;
     }
-    if (!stager) {
+    if (feeder) {
         uint16_t *E = smem + cw * (TM * ESTR);
 #pragma unroll
         for (int i = 0; i < MI; ++i)
@@ -566,17 +672,18 @@ __global__ __launch_bounds__(WM * WN * 64 + STAGERS) void qgemm_kernel(const Gem
     }
 }
 
-template <int BITS, bool BF16, bool TRANS, int BM, int BN, int WM, int WN, bool MASKED = false>
+template <int BITS, bool BF16, bool TRANS, int BM, int BN, int WM, int WN, bool MASKED = false, bool SYM = false>
 void launch_variant(const GemmArgs &a, hipStream_t s)
 {
-    constexpr size_t wstage = TRANS ? (size_t)BK * BN : (size_t)BN * LDS_STRIDE;
+    constexpr size_t wstage = TRANS ? (size_t)BK * BN : (size_t)BN * (SYM ? BK : LDS_STRIDE);
     constexpr size_t lds_pipe = (GEMM_NXS * (size_t)BM * BK + 2 * wstage) * sizeof(uint16_t);
     constexpr size_t lds_side = MASKED ? (size_t)32 * (BM + BN) * sizeof(uint16_t) : 0;    // side tiles of the masked epilogue
     constexpr size_t lds_epi = (size_t)WM * WN * (BM / WM) * (BN / WN + 8) * sizeof(uint16_t) + lds_side;
     constexpr size_t lds = lds_pipe > lds_epi ? lds_pipe : lds_epi;
-    auto kern = qgemm_kernel<BITS, BF16, TRANS, BM, BN, WM, WN, MASKED>;
+    static_assert(lds <= 160 * 1024, "LDS of a compute unit");
+    auto kern = qgemm_kernel<BITS, BF16, TRANS, BM, BN, WM, WN, MASKED, SYM>;
     ensure_dynamic_lds((const void *)kern, (int)(lds));
-    QLORA_LAUNCH(kern, dim3(a.tiles_m * a.tiles_n * a.splits), dim3(WM * WN * 64 + STAGERS), lds, s, a);
+    QLORA_LAUNCH(kern, dim3(a.tiles_m * a.tiles_n * a.splits), dim3(WM * WN * 64 + (SYM ? 0 : STAGERS)), lds, s, a);
 }
 
 // out = round16(sum over the split planes, in order): 8 elements per thread
@@ -641,6 +748,17 @@ void launch_tiles(GemmArgs &a, hipStream_t s)
     if constexpr (TRANS) {
         if (a.keep) {
             launch_variant<BITS, BF16, TRANS, BM, BN, WM, WN, true>(a, s);
+            return;
+        }
+    }
+    // At least one 256 x 256 tile per compute unit, and rounds of 256 tiles that are at least 80 % full: the
+    // symmetric-wave kernel (5-11 % less time than the 256 x 128 tiles at M = 4096 and 8192; a launch of 344 tiles,
+    // two rounds of which the second is a third full, is 10 % slower than the 688 smaller tiles).
+    {
+        const int tn = (NO + 255) / 256, tiles = a.tiles_m * tn, rounds = (tiles + 255) / 256;
+        if (tiles >= 256 && tiles * 10 >= rounds * 256 * 8) {
+            a.tiles_n = tn;
+            launch_variant<BITS, BF16, TRANS, 256, 256, 2, 4, false, true>(a, s);
             return;
         }
     }

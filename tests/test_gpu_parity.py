@@ -405,3 +405,34 @@ def test_mfma_probe_runs_and_its_sums_are_what_the_operands_give():
     ql.qlora_mfma_probe(out, iters, True)
     torch.cuda.synchronize()
     assert np.all(np.isfinite(first)) and np.array_equal(first, out.cpu().numpy()) and np.any(first != 0)
+
+
+# Launches of at least 256 tiles of 256 x 256 go to the symmetric-wave GEMM kernel: the forward pass when
+# ceil(M / 256) * ceil(N / 256) >= 256 (and the rounds of 256 tiles are at least 80 % full), the backward pass when
+# ceil(M / 256) * ceil(K / 256) is.  Short contractions keep the oracle fast; every row and column is compared.
+LARGE_TILE_CASES = [
+    # (M, K, N, bits, G, rank, dtype)
+    (4096, 256, 4096, 4, 128, 8, "f16"),        # forward: 256 tiles, four stages
+    (4104, 320, 6200, 2, 64, 16, "bf16"),       # forward: 17 x 25 tiles, ragged rows and columns, five stages
+    (4096, 448, 4096, 3, 64, 40, "f16"),        # forward: seven stages (not a multiple of the register rotation), rank 40
+    (4096, 4096, 256, 8, 128, 8, "f16"),        # backward: 256 tiles
+    (4104, 6208, 320, 3, 64, 16, "f16"),        # backward: 17 x 25 tiles, ragged
+    (4096, 4096, 192, 2, 128, 64, "bf16"),      # backward: three stages, rank 64
+    (8192, 2048, 2048, 4, 128, 8, "f16"),       # both passes
+]
+
+
+@pytest.mark.parametrize("case", LARGE_TILE_CASES, ids=lambda c: "M{}_K{}_N{}_b{}_G{}_r{}_{}".format(*c))
+def test_large_tile_kernel(case):
+    M, K, N, bits, G, r, dtype = case
+    inp = small_inputs(M + 3 * K + 7 * N + bits, M, K, N, bits, G, r, dtype)
+    check_layer(inp)
+
+
+@pytest.mark.parametrize("case", [(4096, 256, 4096, 4, 128, 8, "f16"), (4096, 4096, 256, 2, 128, 8, "bf16"),
+                                  (4104, 4096, 320, 8, 64, 8, "f16")],
+                         ids=lambda c: "M{}_K{}_N{}_b{}_G{}_r{}_{}".format(*c))
+def test_large_tile_kernel_exact(case):
+    M, K, N, bits, G, r, dtype = case
+    inp = integer_inputs(M + K + N + bits, M, K, N, bits, G, r, dtype, density=0.03)
+    check_layer(inp, exact=True)
