@@ -9,162 +9,6 @@ namespace qlora {
 namespace {
 
 // ------------------------------------------------------------------------------------------------- forward
-constexpr int FW_U = 4;            // iterations (128 codes per row each) whose loads are in flight together
-
-
-template <int BITS, bool BF16, int MB, int RG, int NW, int NB>   // RG: 16-column groups of t formed here (0: none);
-                                                                  // NW waves; NB 16-row weight blocks per workgroup
-__global__ __launch_bounds__(NW * 64) void gemv_fwd_kernel(const FwdArgs a)
-{
-    constexpr int RGS = RG > 0 ? RG : 1, NT = NW * 64;
-    __shared__ float red[NW][MB][NB][16][17];
-    __shared__ float tred[NW][MB][RGS][16][17];
-    constexpr int TC = RG > 0 ? RG * 16 : 64;      // columns of t kept in LDS
-    __shared__ float tfull[MB * 16][TC + 1];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, li = lane & 15, q = lane >> 4;
-    const int n0 = blockIdx.x * 16 * NB;
-    const int K = a.K, Kw = K * BITS / 32, r = a.r;
-    // the activation (and A) fragments of a k-step are fetched once and used for all NB weight blocks: they, not the
-    // packed weight, are most of what a workgroup pulls through its L1
-    int nrow[NB];
-    const uint32_t *wrow[NB];
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-        nrow[nb] = min(n0 + nb * 16 + li, a.N - 1);
-        wrow[nb] = a.packed + (long)nrow[nb] * Kw;
-    }
-    const uint16_t *xrow[MB], *arow[RGS];
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb) xrow[mb] = a.x + (long)min(mb * 16 + li, a.M - 1) * K;
-    bool aval[RGS];
-#pragma unroll
-    for (int g = 0; g < RGS; ++g) {
-        aval[g] = RG > 0 && g * 16 + li < r;
-        arow[g] = a.A + (long)(RG > 0 ? min(g * 16 + li, r - 1) : 0) * K;
-    }
-
-    float4_t acc[MB][NB], tacc[MB][RGS];
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb) {
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = float4_t{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int g = 0; g < RGS; ++g) tacc[mb][g] = float4_t{0.f, 0.f, 0.f, 0.f};
-    }
-
-    const int iters = (K + 127) / 128;          // wave w takes iterations w, w+NW, ...: neighbours read neighbouring bytes
-    for (int it0 = wave; it0 < iters; it0 += NW * FW_U) {
-        uint32_t w[FW_U][NB][BITS];
-        uint16_t sraw[FW_U][NB];
-        uint8_t zraw[FW_U][NB];
-        bool ok[FW_U];
-        u16x8_t xf[FW_U][MB][4], af[FW_U][RGS][4];
-#pragma unroll
-        for (int u = 0; u < FW_U; ++u) {
-            const int kb = (it0 + NW * u) * 128 + 32 * q;
-            ok[u] = kb < K;
-            const int kc = ok[u] ? kb : 0;
-            const int grp = group_of(kc, a.magic);
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-                load_words<BITS>(wrow[nb] + (kc >> 5) * BITS, w[u][nb]);
-                const long gi = (long)nrow[nb] * a.ng + grp;
-                sraw[u][nb] = a.scales[gi];
-                zraw[u][nb] = a.zeros[gi];
-            }
-#pragma unroll
-            for (int s = 0; s < 4; ++s) {
-#pragma unroll
-                for (int mb = 0; mb < MB; ++mb) xf[u][mb][s] = *(const u16x8_t *)(xrow[mb] + kc + 8 * s);
-                if constexpr (RG > 0) {
-#pragma unroll
-                    for (int g = 0; g < RG; ++g)
-                        af[u][g][s] = aval[g] ? *(const u16x8_t *)(arow[g] + kc + 8 * s) : ZERO8;
-                }
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < FW_U; ++u) {
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-                DequantConst<BITS, BF16> dq;
-                dq.set(ok[u] ? f16_bits_to_f32(sraw[u][nb]) : 0.f, (float)zraw[u][nb]);
-#pragma unroll
-                for (int s = 0; s < 4; ++s) {
-                    const u16x8_t wf = dequant8<BITS, BF16>(w[u][nb], s, dq);
-#pragma unroll
-                    for (int mb = 0; mb < MB; ++mb)
-                        acc[mb][nb] = mfma16<BF16>(xf[u][mb][s], wf, acc[mb][nb]);    // D[m = 4q+v][n = li]
-                }
-            }
-            if constexpr (RG > 0) {
-#pragma unroll
-                for (int s = 0; s < 4; ++s)
-#pragma unroll
-                    for (int g = 0; g < RG; ++g) {
-                        const u16x8_t afz = ok[u] ? af[u][g][s] : ZERO8;
-#pragma unroll
-                        for (int mb = 0; mb < MB; ++mb) tacc[mb][g] = mfma16<BF16>(xf[u][mb][s], afz, tacc[mb][g]);   // D[m][j = li]
-                    }
-            }
-        }
-    }
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) red[wave][mb][nb][4 * q + v][li] = acc[mb][nb][v];
-            if constexpr (RG > 0) {
-#pragma unroll
-                for (int g = 0; g < RG; ++g) tred[wave][mb][g][4 * q + v][li] = tacc[mb][g][v];
-            }
-        }
-    __syncthreads();
-    // t for all token rows of the call (every workgroup computes the same t; workgroup 0 hands it out)
-    if constexpr (RG > 0) {
-        for (int e = threadIdx.x; e < MB * 16 * RG * 16; e += NT) {
-            const int m = e / (RG * 16), j = e % (RG * 16);
-            float tv = 0.f;
-            if (j < r && m < a.M) {
-                const int mb = m >> 4, ml = m & 15, g = j >> 4, jl = j & 15;
-#pragma unroll
-                for (int w = 0; w < NW; ++w) tv += tred[w][mb][g][ml][jl];
-                tv = cvt16<BF16>(to16<BF16>(tv));          // the value every consumer of t sees
-                if (blockIdx.x == 0 && a.t_out) a.t_out[(long)m * r + j] = to16<BF16>(tv);
-            }
-            tfull[m][j] = tv;
-        }
-    } else {
-        for (int e = threadIdx.x; e < a.M * r; e += NT) tfull[e / r][e % r] = cvt16<BF16>(a.t_in[e]);
-    }
-    __syncthreads();
-    for (int e = threadIdx.x; e < MB * NB * 256; e += NT) {
-        const int mb = e / (NB * 256), nb = (e >> 8) % NB, ml = (e >> 4) & 15, nl = e & 15;
-        const int m = mb * 16 + ml, nn = n0 + nb * 16 + nl;
-        if (m >= a.M || nn >= a.N) continue;
-        float v = 0.f;
-#pragma unroll
-        for (int w = 0; w < NW; ++w) v += red[w][mb][nb][ml][nl];
-        float lo = 0.f;
-        for (int j0 = 0; j0 < r; j0 += 8) {
-            const u16x8_t bv = *(const u16x8_t *)(a.B + (long)nn * r + j0);
-#pragma unroll
-            for (int h = 0; h < 8; ++h) lo += tfull[m][j0 + h] * cvt16<BF16>(bv[h]);
-        }
-        a.y[(long)m * a.N + nn] = to16<BF16>(v + a.sc * lo);
-    }
-}
-
-// ------------------------------------------------------------------------------- forward, staged activations
-// Same products as gemv_fwd_kernel for up to two 16-row token blocks, with a different route for x and A.  A lane's
-// MFMA fragment of x is 16 bytes out of each of 16 different rows: fetched as such, a wave touches 64 separate
-// 64-byte pieces per instruction and the pass is bound by that, not by the packed weight.  Here every wave copies
-// its 128-column slice of x and A straight into LDS with row-contiguous requests (global_load_lds, 16 lanes per
-// 256-byte row segment, no registers in between) and takes the fragments from there.  The slices are private to
-// the wave, two deep, so the loop has no workgroup barrier; the packed words still go from global memory to
-// registers, a batch of iterations ahead.
-//
 // LDS slice of one 16-row block: 16 rows x 16 pieces of 16 bytes; piece c of row w sits in slot 16 w + (c ^ w), so
 // the fragment reads of 16 rows at one piece index fall on 16 different bank groups.
 constexpr int ST_BLOCK = 4096;      // bytes of one 16-row x 128-column block
@@ -400,18 +244,6 @@ __global__ __launch_bounds__(NW * 64) void gemv_fwd_staged_siblings_kernel(const
     gemv_fwd_staged_body<BITS, BF16, MB, RG, NW, NB>(a, (int)blockIdx.x - (pi ? ma.wg_end[pi - 1] : 0));
 }
 
-template <int BITS, bool BF16, int MB>
-void launch_fwd_rg(const FwdArgs &a, int rg, hipStream_t s)
-{
-    constexpr int NW = 4;
-    const dim3 grid((a.N + 15) / 16), block(NW * 64);
-    switch (rg) {
-    case 0: QLORA_LAUNCH((gemv_fwd_kernel<BITS, BF16, MB, 0, NW, 1>), grid, block, 0, s, a); break;
-    case 1: QLORA_LAUNCH((gemv_fwd_kernel<BITS, BF16, MB, 1, NW, 1>), grid, block, 0, s, a); break;
-    default: QLORA_LAUNCH((gemv_fwd_kernel<BITS, BF16, MB, 2, NW, 1>), grid, block, 0, s, a); break;
-    }
-}
-
 inline int blocks16(int N) { return (N + 15) / 16; }
 
 template <int BITS, bool BF16, int MB, int RG, int NW, int NB>
@@ -495,27 +327,17 @@ template <int BITS, bool BF16>
 bool launch_fwd_mb(const FwdMulti &m, int rg, hipStream_t s)
 {
     const bool zpacked = m.p[0].zpacked != nullptr;       // only the kernel with staged group constants reads those
-    if (zpacked && m.p[0].M > 16) return false;
-    switch ((m.p[0].M + 15) / 16) {
-    case 1:
-        if (launch_fwd_m16<BITS, BF16>(m, rg, s)) return true;
-        if (zpacked) return false;
+    if (launch_fwd_m16<BITS, BF16>(m, rg, s)) return true;
+    if (zpacked) return false;
+    if (m.p[0].M <= 16) {
         launch_fwd_staged<BITS, BF16, 1>(m, rg, s);
-        break;
-    case 2:
+    } else {                                              // up to SMALL_M_FWD_MAX = 32 rows
         for (int i = 0; i < m.count; ++i) {
             FwdMulti one{};
             one.count = 1;
             one.p[0] = m.p[i];
             launch_fwd_staged<BITS, BF16, 2>(one, rg, s);
         }
-        break;
-    case 3:
-        for (int i = 0; i < m.count; ++i) launch_fwd_rg<BITS, BF16, 3>(m.p[i], rg, s);
-        break;
-    default:
-        for (int i = 0; i < m.count; ++i) launch_fwd_rg<BITS, BF16, 4>(m.p[i], rg, s);
-        break;
     }
     return true;
 }

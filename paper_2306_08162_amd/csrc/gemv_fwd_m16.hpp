@@ -23,41 +23,48 @@ constexpr int M16_LDS = 160 * 1024;
 // Columns of a wave per stage and stages in LDS.  8-bit codes: half the columns, so that three blocks of weight rows
 // fit beside the activations, and three stages (one barrier per stage instead of two).  The narrower widths are
 // faster with the wide slices (INT2 gate/up at M = 16: 12.0 against 13.3 us).
-constexpr int m16_ks(int bits) { return bits == 8 ? 64 : 128; }
-constexpr int m16_nst(int bits) { return bits == 8 ? 3 : 2; }
+// With two 16-row token blocks (mb = 2: 17 to 32 token rows) the slices are 64 columns wide for every code width, so
+// that 32 rows of x per wave fit, and there are two stages.
+constexpr int m16_ks(int bits, int mb) { return bits == 8 || mb == 2 ? 64 : 128; }
+constexpr int m16_nst(int bits, int mb) { return bits == 8 && mb == 1 ? 3 : 2; }
 
-// slot of the 16-byte piece `piece` of weight row n inside the row's stage segment (its own inverse)
-template <int BITS>
+// slot of the 16-byte piece `piece` of weight row n inside the row's stage segment of PPR pieces (its own inverse)
+template <int BITS, int PPR>
 __device__ __forceinline__ int wswz(int n, int piece)
 {
     if constexpr (BITS == 3) return 3 * ((piece / 3) ^ (n & 7)) + piece % 3;       // whole units of 12 bytes stay together
-    else return piece ^ (n & 15);
+    else return piece ^ (n & (PPR < 16 ? PPR - 1 : 15));
 }
 
-constexpr int m16_xa(int bits, int ar) { return (16 + ar) * 2 * m16_ks(bits); }               // a wave's slices of x and A
-constexpr int m16_stage(int bits, int nb, int ar) { return M16_NW * m16_xa(bits, ar) + nb * 16 * m16_ks(bits) * bits; }
+constexpr int m16_xa(int bits, int ar, int mb) { return (16 * mb + ar) * 2 * m16_ks(bits, mb); }   // a wave's slices of x and A
+constexpr int m16_stage(int bits, int nb, int ar, int mb)
+{
+    return M16_NW * m16_xa(bits, ar, mb) + nb * 16 * m16_ks(bits, mb) * bits;
+}
 constexpr int m16_table(int nb, int ng, int zrow)     // scales (2 B per group), zero-points (zrow bytes per row: one per
 {                                                     // group, or the row's packed words), each filled in whole KB
     return ((nb * 16 * ng * 2 + 1023) & ~1023) + ((nb * 16 * zrow + 1023) & ~1023);
 }
+constexpr int m16_red(int nb, int mb) { return M16_NW * (nb + 1) * 16 * mb * 17 * 4; }      // the waves' partial sums
 constexpr int m16_tc(int ar) { return ar > 0 ? 16 : 64; }                                     // columns of t kept
-constexpr int m16_static(int ar) { return 16 * (m16_tc(ar) + 1) * 4; }
+constexpr int m16_static(int ar, int mb) { return 16 * mb * (m16_tc(ar) + 1) * 4; }
 
-template <int BITS, bool BF16, int NB, int AR>     // NB 16-row weight blocks; AR rows of A staged (0: t is given, or no adapter)
+// NB 16-row weight blocks; AR rows of A staged (0: t is given, or no adapter); MB 16-row token blocks (1 or 2)
+template <int BITS, bool BF16, int NB, int AR, int MB>
 __device__ __forceinline__ void gemv_fwd_m16_body(const FwdArgs &a, const int wg)
 {
-    constexpr int NW = M16_NW, NT = NW * 64, R = 16 * NB;
-    constexpr int KS = m16_ks(BITS), KC = NW * KS, NST = m16_nst(BITS), SS = KS / 32;   // SS: MFMA steps of a wave per stage
+    constexpr int NW = M16_NW, NT = NW * 64, R = 16 * NB, XROWS = 16 * MB;
+    constexpr int KS = m16_ks(BITS, MB), KC = NW * KS, NST = m16_nst(BITS, MB), SS = KS / 32;   // SS: MFMA steps of a wave per stage
     constexpr int PPR = KS * BITS / 16, UB = KS * BITS / 32; // pieces of a weight row per stage; bytes of a lane's codes
     constexpr int PR = KS / 8, RPI = 64 / PR;                // pieces of an activation row per stage; rows per request
-    constexpr int XBYTES = 32 * KS;                          // a wave's slice of x
-    constexpr int XA = m16_xa(BITS, AR), WOFF = NW * XA, STAGE = m16_stage(BITS, NB, AR);
+    constexpr int XBYTES = 2 * XROWS * KS;                   // a wave's slice of x
+    constexpr int XA = m16_xa(BITS, AR, MB), WOFF = NW * XA, STAGE = m16_stage(BITS, NB, AR, MB);
     constexpr int WI = R * PPR / 64;                         // weight requests per stage, dealt out wave by wave
     constexpr int WI_HI = (WI + NW - 1) / NW, WI_LO = WI / NW;
-    constexpr int XIX = 16 / RPI, XIA = AR / RPI, XI = XIX + XIA;   // requests of a wave's own slices
+    constexpr int XIX = XROWS / RPI, XIA = AR / RPI, XI = XIX + XIA;   // requests of a wave's own slices
     constexpr int TC = m16_tc(AR);
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-    __shared__ float tfull[16][TC + 1];
+    __shared__ float tfull[XROWS][TC + 1];
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int li = lane & 15, q = lane >> 4;
     const int n0 = wg * R, K = a.K, Kw = K * BITS / 32, r = a.r, ng = a.ng;
@@ -76,7 +83,7 @@ __device__ __forceinline__ void gemv_fwd_m16_body(const FwdArgs &a, const int wg
     for (int c = 0; c < WI_HI; ++c) {
         const int e = 64 * (wave + NW * c) + lane, n = min(e / PPR, R - 1), slot = e % PPR;
         w_src[c] = (uint32_t)min(n, rows_here - 1) * row_bytes;
-        w_piece[c] = (uint32_t)wswz<BITS>(n, slot) * 16u;
+        w_piece[c] = (uint32_t)wswz<BITS, PPR>(n, slot) * 16u;
     }
     uint32_t x_src[XIX], a_src[XIA > 0 ? XIA : 1];
 #pragma unroll
@@ -129,22 +136,27 @@ __device__ __forceinline__ void gemv_fwd_m16_body(const FwdArgs &a, const int wg
     issue(0, 0);
     if (S > 1) issue(1, 1);
     // the rows of B the outputs need at the very end
-    constexpr int EPT = (NB * 256 + NT - 1) / NT, BV = AR > 0 ? AR / 8 : 1;
+    constexpr int OPB = 16 * XROWS;                          // outputs per block of weight rows
+    constexpr int EPT = (NB * OPB + NT - 1) / NT, BV = AR > 0 ? AR / 8 : 1;
     u16x8_t bpre[EPT][BV];
     if constexpr (AR > 0) {
 #pragma unroll
         for (int x = 0; x < EPT; ++x) {
-            const int e = threadIdx.x + x * NT, nn = n0 + (e >> 8) * 16 + (e & 15);
-            const bool live = e < NB * 256 && nn < a.N;
+            const int e = threadIdx.x + x * NT, nn = n0 + (e / OPB) * 16 + (e & 15);
+            const bool live = e < NB * OPB && nn < a.N;
 #pragma unroll
             for (int h = 0; h < BV; ++h)
                 bpre[x][h] = (live && 8 * h < r) ? *(const u16x8_t *)(a.B + (long)nn * r + 8 * h) : ZERO8;
         }
     }
 
-    float4_t acc[NB], tacc = {0.f, 0.f, 0.f, 0.f};
+    float4_t acc[MB][NB], tacc[MB];
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) acc[nb] = float4_t{0.f, 0.f, 0.f, 0.f};
+    for (int mb = 0; mb < MB; ++mb) {
+        tacc[mb] = float4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = float4_t{0.f, 0.f, 0.f, 0.f};
+    }
 
     for (int st = 0; st < S; ++st) {
         // stage st has landed once at most the requests of stage st + 1 (issued after it) are outstanding
@@ -159,13 +171,14 @@ __device__ __forceinline__ void gemv_fwd_m16_body(const FwdArgs &a, const int wg
         const uint8_t *xs = buf + (size_t)wave * XA, *wc = buf + WOFF;
         const int k0 = st * KC + wave * KS;
         const bool live = k0 < K;                            // wave-uniform
-        u16x8_t xf[SS], af[SS];
+        u16x8_t xf[MB][SS], af[SS];
         uint32_t w[NB][BITS];                                // the first UB bytes are used
         float sc[NB], zp[NB];
 #pragma unroll
         for (int s = 0; s < SS; ++s) {
-            const int slot = li * PR + ((SS * q + s) ^ (li & (PR - 1)));
-            xf[s] = *(const u16x8_t *)(xs + slot * 16);
+            const int slot = li * PR + ((SS * q + s) ^ (li & (PR - 1)));        // 16 rows on: the same slot key
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) xf[mb][s] = *(const u16x8_t *)(xs + (16 * mb * PR + slot) * 16);
             if constexpr (AR > 0) af[s] = li < min(r, AR) ? *(const u16x8_t *)(xs + XBYTES + slot * 16) : ZERO8;
         }
         const int grp = live ? group_of(k0, a.magic) : 0;
@@ -182,16 +195,16 @@ __device__ __forceinline__ void gemv_fwd_m16_body(const FwdArgs &a, const int wg
                 if constexpr (UB >= 16) {
 #pragma unroll
                     for (int h = 0; h < UB / 16; ++h) {
-                        const u32x4_t v = *(const u32x4_t *)(rowp + wswz<BITS>(n, (ob >> 4) + h) * 16);
+                        const u32x4_t v = *(const u32x4_t *)(rowp + wswz<BITS, PPR>(n, (ob >> 4) + h) * 16);
 #pragma unroll
                         for (int i = 0; i < 4; ++i) w[nb][4 * h + i] = v[i];
                     }
                 } else if constexpr (UB == 8) {
-                    const u32x2_t v = *(const u32x2_t *)(rowp + wswz<BITS>(n, ob >> 4) * 16 + (ob & 15));
+                    const u32x2_t v = *(const u32x2_t *)(rowp + wswz<BITS, PPR>(n, ob >> 4) * 16 + (ob & 15));
                     w[nb][0] = v[0];
                     w[nb][1] = v[1];
                 } else {
-                    w[nb][0] = *(const uint32_t *)(rowp + wswz<BITS>(n, ob >> 4) * 16 + (ob & 15));
+                    w[nb][0] = *(const uint32_t *)(rowp + wswz<BITS, PPR>(n, ob >> 4) * 16 + (ob & 15));
                 }
 #pragma unroll
                 for (int i = UB / 4; i < BITS; ++i) w[nb][i] = 0u;
@@ -213,20 +226,27 @@ __device__ __forceinline__ void gemv_fwd_m16_body(const FwdArgs &a, const int wg
             // scale is applied to the four sums of the lane's weight row
             DequantConst<BITS, BF16> dq;
             dq.set(1.f, zp[nb]);
-            float4_t part = {0.f, 0.f, 0.f, 0.f};
+            float4_t part[MB];
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) part[mb] = float4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int s = 0; s < SS; ++s) {
                 if (more && SS * nb + s < NS) issue_step(st + 2, fill, SS * nb + s);
-                part = mfma16<BF16>(xf[s], dequant8<BITS, BF16, false>(w[nb], s, dq), part);   // D[m = 4q+v][n = li]
+                const u16x8_t wf = dequant8<BITS, BF16, false>(w[nb], s, dq);
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) part[mb] = mfma16<BF16>(xf[mb][s], wf, part[mb]);   // D[m = 4q+v][n = li]
             }
 #pragma unroll
-            for (int v = 0; v < 4; ++v) acc[nb][v] = fmaf(sc[nb], part[v], acc[nb][v]);
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) acc[mb][nb][v] = fmaf(sc[nb], part[mb][v], acc[mb][nb][v]);
         }
         if constexpr (AR > 0) {
 #pragma unroll
             for (int s = 0; s < SS; ++s) {
                 if (more && SS * NB + s < NS) issue_step(st + 2, fill, SS * NB + s);
-                tacc = mfma16<BF16>(xf[s], af[s], tacc);                                      // D[m][j = li]
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) tacc[mb] = mfma16<BF16>(xf[mb][s], af[s], tacc[mb]);   // D[m][j = li]
             }
         }
         if (more) {
@@ -237,18 +257,22 @@ __device__ __forceinline__ void gemv_fwd_m16_body(const FwdArgs &a, const int wg
 
     // ---- the waves' partial sums meet in LDS (where the stages were)
     __syncthreads();
-    float *red = (float *)lds;                               // [NW][NB + 1][16][17]
-    auto red_at = [&](int w, int blk, int row, int col) -> float & { return red[((w * (NB + 1) + blk) * 16 + row) * 17 + col]; };
-    static_assert(NW * (NB + 1) * 16 * 17 * 4 <= NST * m16_stage(BITS, NB, AR), "partial sums fit where the stages were");
+    float *red = (float *)lds;                               // [NW][NB + 1][XROWS][17], over the stages and tables
+    auto red_at = [&](int w, int blk, int row, int col) -> float & {
+        return red[((w * (NB + 1) + blk) * XROWS + row) * 17 + col];
+    };
+    static_assert(m16_red(NB, MB) <= M16_LDS - m16_static(AR, MB), "partial sums fit (the launch sizes LDS for them)");
 #pragma unroll
-    for (int v = 0; v < 4; ++v) {
+    for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) red_at(wave, nb, 4 * q + v, li) = acc[nb][v];
-        if constexpr (AR > 0) red_at(wave, NB, 4 * q + v, li) = tacc[v];
-    }
+        for (int v = 0; v < 4; ++v) {
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) red_at(wave, nb, 16 * mb + 4 * q + v, li) = acc[mb][nb][v];
+            if constexpr (AR > 0) red_at(wave, NB, 16 * mb + 4 * q + v, li) = tacc[mb][v];
+        }
     __syncthreads();
     if constexpr (AR > 0) {
-        for (int e = threadIdx.x; e < 16 * 16; e += NT) {
+        for (int e = threadIdx.x; e < XROWS * 16; e += NT) {
             const int m = e >> 4, j = e & 15;
             float tv = 0.f;
             if (j < r && m < a.M) {
@@ -266,8 +290,8 @@ __device__ __forceinline__ void gemv_fwd_m16_body(const FwdArgs &a, const int wg
 #pragma unroll
     for (int x = 0; x < EPT; ++x) {
         const int e = threadIdx.x + x * NT;
-        const int nb = e >> 8, m = (e >> 4) & 15, nl = e & 15, nn = n0 + nb * 16 + nl;
-        if (e >= NB * 256 || m >= a.M || nn >= a.N) continue;
+        const int nb = e / OPB, m = (e >> 4) % XROWS, nl = e & 15, nn = n0 + nb * 16 + nl;
+        if (e >= NB * OPB || m >= a.M || nn >= a.N) continue;
         float v = 0.f;
 #pragma unroll
         for (int w = 0; w < NW; ++w) v += red_at(w, nb, m, nl);
@@ -288,67 +312,72 @@ __device__ __forceinline__ void gemv_fwd_m16_body(const FwdArgs &a, const int wg
     }
 }
 
-template <int BITS, bool BF16, int NB, int AR>
+template <int BITS, bool BF16, int NB, int AR, int MB>
 __global__ __launch_bounds__(M16_NW * 64) void gemv_fwd_m16_kernel(const FwdMulti ma)
 {
     int pi = 0;
     while (pi + 1 < ma.count && (int)blockIdx.x >= ma.wg_end[pi]) ++pi;          // wave-uniform
     const FwdArgs a = ma.p[pi];
-    gemv_fwd_m16_body<BITS, BF16, NB, AR>(a, (int)blockIdx.x - (pi ? ma.wg_end[pi - 1] : 0));
+    gemv_fwd_m16_body<BITS, BF16, NB, AR, MB>(a, (int)blockIdx.x - (pi ? ma.wg_end[pi - 1] : 0));
 }
 
 inline int m16_zrow(const FwdArgs &a) { return a.zpacked ? a.zw * 4 : a.ng; }
 
 // largest NB whose stages and tables fit in LDS (0: none)
 template <int BITS>
-inline int m16_nb_max(int ar, int ng, int zrow)
+inline int m16_nb_max(int ar, int ng, int zrow, int mb)
 {
     for (int nb = 4; nb >= 1; --nb)
-        if (m16_nst(BITS) * m16_stage(BITS, nb, ar) + m16_table(nb, ng, zrow) + m16_static(ar) <= M16_LDS) return nb;
+        if (m16_nst(BITS, mb) * m16_stage(BITS, nb, ar, mb) + m16_table(nb, ng, zrow) + m16_static(ar, mb) <= M16_LDS)
+            return nb;
     return 0;
 }
 
-template <int BITS, bool BF16, int NB, int AR>
+template <int BITS, bool BF16, int NB, int AR, int MB>
 void launch_fwd_m16_one(FwdMulti m, hipStream_t s)
 {
-    const int lds = m16_nst(BITS) * m16_stage(BITS, NB, AR) + m16_table(NB, m.p[0].ng, m16_zrow(m.p[0]));
+    const int pipe = m16_nst(BITS, MB) * m16_stage(BITS, NB, AR, MB) + m16_table(NB, m.p[0].ng, m16_zrow(m.p[0]));
+    const int lds = pipe > m16_red(NB, MB) ? pipe : m16_red(NB, MB);
     int wgs = 0;
     for (int i = 0; i < m.count; ++i) {
         wgs += (blocks16(m.p[i].N) + NB - 1) / NB;
         m.wg_end[i] = wgs;
     }
-    auto kern = gemv_fwd_m16_kernel<BITS, BF16, NB, AR>;
-    ensure_dynamic_lds((const void *)kern, M16_LDS - m16_static(AR));
+    auto kern = gemv_fwd_m16_kernel<BITS, BF16, NB, AR, MB>;
+    ensure_dynamic_lds((const void *)kern, M16_LDS - m16_static(AR, MB));
     QLORA_LAUNCH(kern, dim3(wgs), dim3(M16_NW * 64), lds, s, m);
 }
 
-template <int BITS, bool BF16, int AR>
+template <int BITS, bool BF16, int AR, int MB>
 void launch_fwd_m16_nb(const FwdMulti &m, int nb, hipStream_t s)
 {
+    constexpr int NST = m16_nst(BITS, MB);
     switch (nb) {
     case 4:
-        if constexpr (m16_nst(BITS) * m16_stage(BITS, 4, AR) < M16_LDS) { launch_fwd_m16_one<BITS, BF16, 4, AR>(m, s); return; }
+        if constexpr (NST * m16_stage(BITS, 4, AR, MB) < M16_LDS) { launch_fwd_m16_one<BITS, BF16, 4, AR, MB>(m, s); return; }
         [[fallthrough]];
     case 3:
-        if constexpr (m16_nst(BITS) * m16_stage(BITS, 3, AR) < M16_LDS) { launch_fwd_m16_one<BITS, BF16, 3, AR>(m, s); return; }
+        if constexpr (NST * m16_stage(BITS, 3, AR, MB) < M16_LDS) { launch_fwd_m16_one<BITS, BF16, 3, AR, MB>(m, s); return; }
         [[fallthrough]];
     case 2:
-        if constexpr (m16_nst(BITS) * m16_stage(BITS, 2, AR) < M16_LDS) { launch_fwd_m16_one<BITS, BF16, 2, AR>(m, s); return; }
+        if constexpr (NST * m16_stage(BITS, 2, AR, MB) < M16_LDS) { launch_fwd_m16_one<BITS, BF16, 2, AR, MB>(m, s); return; }
         [[fallthrough]];
     default:
-        if constexpr (m16_nst(BITS) * m16_stage(BITS, 1, AR) < M16_LDS) launch_fwd_m16_one<BITS, BF16, 1, AR>(m, s);
+        if constexpr (NST * m16_stage(BITS, 1, AR, MB) < M16_LDS) launch_fwd_m16_one<BITS, BF16, 1, AR, MB>(m, s);
     }
 }
 
-// Serves the call if its shape allows: up to 16 token rows, K and the group size multiples of 128 (a wave's 128
-// columns of a stage then share their group constants), t either computed here from at most
+// Serves the call if its shape allows: up to 32 token rows (above 16: not for 3-bit codes), K and the group size
+// multiples of 128 (a wave's columns of a stage then share their group constants), t either computed here from at most
 // 16 adapter rows or handed in, and room in LDS for the stages of at least two 16-row blocks (one block would pull x
 // through every compute unit once per 16 weight rows).
 template <int BITS, bool BF16>
 bool launch_fwd_m16(const FwdMulti &m, int rg, hipStream_t s)
 {
     const FwdArgs &a = m.p[0];
-    if (a.M > 16 || a.K % 128 != 0 || (a.K / a.ng) % 128 != 0 || rg > 1 || (rg == 0 && a.r > 64)) return false;
+    if (a.M > 32 || a.K % 128 != 0 || (a.K / a.ng) % 128 != 0 || rg > 1 || (rg == 0 && a.r > 64)) return false;
+    const int mb = a.M > 16 ? 2 : 1;
+    if (BITS == 3 && mb == 2) return false;      // 64-column slices would cut the 12-byte units of 3-bit codes
     for (int i = 0; i < m.count; ++i) {
         const FwdArgs &b = m.p[i];            // 16-byte requests: aligned arrays, constants in whole pieces
         const uintptr_t bits_or = (uintptr_t)b.x | (uintptr_t)b.packed | (uintptr_t)b.scales | (uintptr_t)b.zeros |
@@ -356,7 +385,7 @@ bool launch_fwd_m16(const FwdMulti &m, int rg, hipStream_t s)
         if ((bits_or & 15) != 0 || ((long)b.N * b.ng) % 16 != 0 || ((long)b.N * m16_zrow(b)) % 16 != 0) return false;
     }
     const int ar = rg == 0 ? 0 : (a.r <= 8 ? 8 : 16);
-    const int nb_max = m16_nb_max<BITS>(ar, a.ng, m16_zrow(a));
+    const int nb_max = m16_nb_max<BITS>(ar, a.ng, m16_zrow(a), mb);
     if (nb_max < 2) return false;
     // one round of the 256 compute units if the rows allow it; siblings that do not fit one round together go one by one
     int nb = 0;
@@ -375,10 +404,18 @@ bool launch_fwd_m16(const FwdMulti &m, int rg, hipStream_t s)
         return true;
     }
     if (nb == 0) nb = nb_max;
-    switch (ar) {
-    case 0: launch_fwd_m16_nb<BITS, BF16, 0>(m, nb, s); break;
-    case 8: launch_fwd_m16_nb<BITS, BF16, 8>(m, nb, s); break;
-    default: launch_fwd_m16_nb<BITS, BF16, 16>(m, nb, s); break;
+    if (mb == 1) {
+        switch (ar) {
+        case 0: launch_fwd_m16_nb<BITS, BF16, 0, 1>(m, nb, s); break;
+        case 8: launch_fwd_m16_nb<BITS, BF16, 8, 1>(m, nb, s); break;
+        default: launch_fwd_m16_nb<BITS, BF16, 16, 1>(m, nb, s); break;
+        }
+    } else if constexpr (BITS != 3) {
+        switch (ar) {
+        case 0: launch_fwd_m16_nb<BITS, BF16, 0, 2>(m, nb, s); break;
+        case 8: launch_fwd_m16_nb<BITS, BF16, 8, 2>(m, nb, s); break;
+        default: launch_fwd_m16_nb<BITS, BF16, 16, 2>(m, nb, s); break;
+        }
     }
     return true;
 }

@@ -91,7 +91,7 @@ void launch_bwd_dx_mfma(const Problem &p, const void *dy, const uint32_t *packed
                         const uint32_t *keep, float keep_scale, hipStream_t s);
 
 // gemv.hip -- small token counts: weight-streaming kernels, one pass over the packed weight
-constexpr int SMALL_M_FWD_MAX = 64;   // forward kernel handles up to four 16-row token blocks
+constexpr int SMALL_M_FWD_MAX = 32;   // above: the tiled GEMM with its contraction split over workgroups is faster
 constexpr int SMALL_M_BWD_MAX = 16;   // backward kernel keeps one 16-row token block
 int gemv_bwd_slices(int N, int K, int bits);   // row slices of the backward kernel
 bool fwd_small_computes_t(int rank);           // true: the forward kernel forms t = x A^T itself (unless t is handed in)

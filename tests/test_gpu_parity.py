@@ -436,3 +436,35 @@ def test_large_tile_kernel_exact(case):
     M, K, N, bits, G, r, dtype = case
     inp = integer_inputs(M + K + N + bits, M, K, N, bits, G, r, dtype, density=0.03)
     check_layer(inp, exact=True)
+
+
+# 17 to 32 token rows: the staged forward kernel with two 16-row token blocks (64-column slices); 3-bit codes and
+# groups narrower than 128 columns go to the older kernel, everything above 32 rows to the tiled GEMM.
+TWO_BLOCK_CASES = [
+    (17, 512, 136, 2, 128, 8, "f16"),
+    (32, 1024, 264, 4, 128, 16, "bf16"),
+    (24, 2048, 200, 8, 128, 8, "f16"),
+    (31, 640, 72, 2, 128, 0, "f16"),            # K not a multiple of a stage's 512 columns; no adapter
+    (20, 4096, 520, 4, 128, 40, "f16"),         # rank 40: t is formed beforehand
+    (29, 1536, 1096, 2, 256, 8, "bf16"),        # more than 256 blocks of 16 weight rows / 4: several rounds
+    (32, 1024, 136, 3, 128, 8, "f16"),          # 3 bits: the older kernel
+    (18, 512, 136, 4, 64, 8, "f16"),            # G = 64: the older kernel
+    (33, 1024, 264, 4, 128, 8, "f16"),          # the tiled GEMM
+    (64, 512, 136, 2, 128, 16, "bf16"),
+]
+
+
+@pytest.mark.parametrize("case", TWO_BLOCK_CASES, ids=lambda c: "M{}_K{}_N{}_b{}_G{}_r{}_{}".format(*c))
+def test_seventeen_to_sixty_four_token_rows(case):
+    M, K, N, bits, G, r, dtype = case
+    inp = small_inputs(2 * M + K + N + bits, M, K, N, bits, G, r, dtype)
+    check_layer(inp, recompute_t=(M % 2 == 0))
+
+
+@pytest.mark.parametrize("case", [(32, 1024, 136, 2, 128, 8, "f16"), (25, 2048, 72, 8, 128, 8, "bf16"),
+                                  (17, 4096, 264, 4, 128, 16, "f16")],
+                         ids=lambda c: "M{}_K{}_N{}_b{}_G{}_r{}_{}".format(*c))
+def test_two_token_blocks_exact(case):
+    M, K, N, bits, G, r, dtype = case
+    inp = integer_inputs(M + K + N + bits, M, K, N, bits, G, r, dtype, density=0.05 if K > 1024 else 0.2)
+    check_layer(inp, exact=True)
