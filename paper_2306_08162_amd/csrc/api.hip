@@ -63,7 +63,7 @@ Workspace carve(int M, int N, int K, int r, int bits)
     w.upartial_off = off;
     w.partial_off = off;
     if (M <= SMALL_M_BWD_MAX) {     // the weight-streaming backward kernel: per row slice, partial u and partial dX
-        off += round_up((size_t)gemv_bwd_slices(N, K, bits) * 1024 * sizeof(float));
+        off += round_up((size_t)gemv_bwd_slices(N, K, bits) * (M > 16 ? 2048 : 1024) * sizeof(float));
         w.partial_off = off;
         off += round_up((size_t)gemv_bwd_slices(N, K, bits) * M * K * sizeof(float));
     }
@@ -432,26 +432,37 @@ static int backward(const void *dy, const void *x, const uint32_t *packed, const
     begin_call();
     const Problem p{M, N, K, bits, group_size, rank, rank > 0 ? alpha / (float)rank : 0.f, dtype == QLORA_BF16};
     char *ws = (char *)workspace;
+    bool t_ready = false, unpacked = false;
     if (M <= SMALL_M_BWD_MAX) {
-        // two launches: partial dX and u over row slices of the weight, then the sums, dA and dB
+        // two launches: partial dX and u over row slices of the weight, then the sums, dA and dB.  Above 16 token
+        // rows only the staged kernel serves, and not every shape: then the tiled kernels below take over.
         const void *t = t_saved;
         if (rank > 0 && !t) {
             launch_lora_down(x, A, ws + w.t_off, M, K, rank, p.bf16, keep_mask, keep_scale, s);
             t = ws + w.t_off;
+            t_ready = true;
         }
-        GemmTimer timer(s);
-        float *const partial = (float *)(ws + w.partial_off), *const upartial = (float *)(ws + w.upartial_off);
-        if (!zpacked || !launch_bwd_small(p, 1, &dy, x, &packed, &scales, &zeros, &A, &B, &t, dx, &dA, &dB, &N, partial,
-                                          upartial, beta, keep_mask, keep_scale, frozen, s, &zpacked)) {
-            if (zpacked) launch_unpack_zeros(zpacked, zscratch, N, K / group_size, bits, s);
-            launch_bwd_small(p, 1, &dy, x, &packed, &scales, &zeros, &A, &B, &t, dx, &dA, &dB, &N, partial, upartial, beta,
-                             keep_mask, keep_scale, frozen, s);
+        bool done = false;
+        {
+            GemmTimer timer(s);
+            float *const partial = (float *)(ws + w.partial_off), *const upartial = (float *)(ws + w.upartial_off);
+            if (zpacked)
+                done = launch_bwd_small(p, 1, &dy, x, &packed, &scales, &zeros, &A, &B, &t, dx, &dA, &dB, &N, partial,
+                                        upartial, beta, keep_mask, keep_scale, frozen, s, &zpacked);
+            if (!done) {
+                if (zpacked) {
+                    launch_unpack_zeros(zpacked, zscratch, N, K / group_size, bits, s);
+                    unpacked = true;
+                }
+                done = launch_bwd_small(p, 1, &dy, x, &packed, &scales, &zeros, &A, &B, &t, dx, &dA, &dB, &N, partial,
+                                        upartial, beta, keep_mask, keep_scale, frozen, s);
+            }
         }
-        return end_call();
+        if (done) return end_call();
     }
     void *u = nullptr;
     mark_pre_begin(s);
-    if (zpacked) launch_unpack_zeros(zpacked, zscratch, N, K / group_size, bits, s);
+    if (zpacked && !unpacked) launch_unpack_zeros(zpacked, zscratch, N, K / group_size, bits, s);
     if (rank > 0) {
         u = ws + w.u_off;
         launch_lora_u(dy, B, u, M, N, rank, p.bf16, s);
@@ -476,7 +487,7 @@ static int backward(const void *dy, const void *x, const uint32_t *packed, const
     if (rank > 0) {
         const void *t = t_saved;
         if (!t) {
-            launch_lora_down(x, A, ws + w.t_off, M, K, rank, p.bf16, keep_mask, keep_scale, s);
+            if (!t_ready) launch_lora_down(x, A, ws + w.t_off, M, K, rank, p.bf16, keep_mask, keep_scale, s);
             t = ws + w.t_off;
         }
         launch_adapter_grads(dy, t, x, u, dB, dA, M, N, K, rank, frozen, p.sc, beta, keep_mask, keep_scale, p.bf16, s);
@@ -588,7 +599,7 @@ int check_siblings(int count, const int *N, int M, int K, int bits, int G, int r
 
 }  // namespace
 
-static_assert(QLORA_MAX_SIBLINGS == MAX_SIBLINGS && QLORA_SIBLINGS_MAX_M == SMALL_M_BWD_MAX, "header and kernels agree");
+static_assert(QLORA_MAX_SIBLINGS == MAX_SIBLINGS && QLORA_SIBLINGS_MAX_M == SIBLINGS_MAX_M, "header and kernels agree");
 
 size_t qlora_siblings_workspace_bytes(int count, const int *N, int M, int K, int bits, int group_size, int rank)
 {

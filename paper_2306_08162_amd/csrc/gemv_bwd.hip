@@ -27,7 +27,7 @@ struct BwdArgs {
     const uint8_t *zeros;
     const uint16_t *B;
     float *partial;       // [slices][M][K]
-    float *upartial;      // [slices][16][64]
+    float *upartial;      // [slices][16][64] ([slices][32][64] above 16 token rows)
     int M, N, K, r, ng, rows_per_slice;
     uint32_t magic;
     const uint32_t *zpacked;   // zero-points in their bit-packed storage form [N, zw] (then `zeros` is not read), or NULL
@@ -275,21 +275,24 @@ struct BwdMulti {
 // wave reads together then lie in four different bank ranges.  The dY pieces are permuted by the token row.
 constexpr int BS_RS = 256, BS_NW = 8;
 
-template <int BITS>
+// MB: 16-row token blocks (1, or 2 for 17 to 32 token rows: a stage then holds 32 rows of dY, three stages fit, and
+// 8-bit codes, whose rows are twice as wide, do not)
+template <int BITS, int MB = 1>
 struct BwdStaged {
     using S = BwdShape<BITS>;
     static constexpr int RB = S::CB * BITS / 8;             // bytes of a weight row inside the column block
     static constexpr int PPR = RB / 16;
-    static constexpr int WBYTES = BS_RS * RB, DYB = 16 * BS_RS * 2, SZB = BS_RS * 32;
+    static constexpr int WBYTES = BS_RS * RB, DYB = 16 * MB * BS_RS * 2, SZB = BS_RS * 32;
     static constexpr int STAGE = WBYTES + DYB + SZB;
-    static constexpr int NST = BITS == 8 ? 3 : 4;
+    static constexpr int NST = BITS == 8 || MB == 2 ? 3 : 4;
     static constexpr int WD = WBYTES / 1024 / BS_NW;        // weight requests per wave and stage
     static constexpr int WIN = 1;                           // window requests per wave and stage
-    static constexpr int GRP = WD + WIN + 1;                // ... and all requests: windows, 1 of dY, WD
+    static constexpr int GRP = WD + WIN + MB;               // ... and all requests: windows, MB of dY, WD
     static constexpr int CONV = 2 * 2 * 2 * BS_RS * 2;      // [parity][scale | -z][group][row] fp16
-    static constexpr int RED = BS_NW * 16 * S::CB * 4;      // the waves' partial sums
+    static constexpr int RED = BS_NW * 16 * S::CB * 4;      // the waves' partial sums of one token block
     static constexpr int LDS = NST * STAGE + CONV > RED ? NST * STAGE + CONV : RED;
-    static_assert(BITS != 3 && WBYTES % (1024 * BS_NW) == 0 && LDS <= 160 * 1024, "stage shape");
+    static constexpr bool FITS = LDS <= 160 * 1024;
+    static_assert(BITS != 3 && WBYTES % (1024 * BS_NW) == 0 && (FITS || MB == 2), "stage shape");
 };
 
 __device__ __forceinline__ int bs_perm(int row) { return (row & ~31) | ((row & 7) << 2) | ((row >> 3) & 3); }
@@ -301,11 +304,11 @@ __device__ __forceinline__ void bs_wait_vm()
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-template <int BITS, bool BF16>
+template <int BITS, bool BF16, int MB>
 __device__ __forceinline__ void gemv_bwd_staged_body(const BwdArgs &a, const int cb, const int sp_local, const int sp)
 {
     using S = BwdShape<BITS>;
-    using T = BwdStaged<BITS>;
+    using T = BwdStaged<BITS, MB>;
     constexpr int CL = S::CL, WORDS = S::WORDS, CB = S::CB, NW = BS_NW, NT = NW * 64;
     constexpr int RB = T::RB, PPR = T::PPR, NST = T::NST, WD = T::WD, GRP = T::GRP, STAGE = T::STAGE;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
@@ -336,9 +339,11 @@ __device__ __forceinline__ void gemv_bwd_staged_body(const BwdArgs &a, const int
         w_row[c] = bs_unperm(e / PPR);
         w_pc[c] = (uint32_t)(e % PPR) * 16u;
     }
-    // dY: request `wave` moves token rows 2 wave, 2 wave + 1; slot s of a row holds piece s ^ row
+    // dY: request `wave` of token block b moves token rows 16 b + 2 wave, + 1; slot s of a row holds piece s ^ (row % 16)
     const int dy_m = 2 * wave + (lane >> 5), dy_piece = (lane & 31) ^ dy_m;
-    const uint32_t dy_row = (uint32_t)min(dy_m, a.M - 1) * (uint32_t)N * 2u;
+    uint32_t dy_row[MB];
+#pragma unroll
+    for (int b = 0; b < MB; ++b) dy_row[b] = (uint32_t)min(16 * b + dy_m, a.M - 1) * (uint32_t)N * 2u;
     // windows: request `wave` moves rows 32 wave .. 32 wave + 32, lane l the scale piece (l even) or the zero-point
     // piece (l odd) of row 32 wave + l / 2
     // (bit-packed zero-points: the piece of the row's words that holds the block's groups; two groups of a block
@@ -358,9 +363,11 @@ __device__ __forceinline__ void gemv_bwd_staged_body(const BwdArgs &a, const int
                                                  : zsrc + (zat + 16u <= z_all ? zat : 0u);
             dma16_at(src, base + T::WBYTES + T::DYB + (uint32_t)wave * 1024u);
         }
-        {
+#pragma unroll
+        for (int b = 0; b < MB; ++b) {
             const int n = nbeg + st * BS_RS + 8 * dy_piece;                 // N % 8 == 0: a piece is inside or outside
-            dma16(a.dy, dy_row + (n < N ? (uint32_t)n * 2u : 0u), base + T::WBYTES + (uint32_t)wave * 1024u);
+            dma16(a.dy, dy_row[b] + (n < N ? (uint32_t)n * 2u : 0u),
+                  base + T::WBYTES + (uint32_t)(8 * b + wave) * 1024u);
         }
 #pragma unroll
         for (int c = 0; c < WD; ++c)
@@ -387,9 +394,11 @@ __device__ __forceinline__ void gemv_bwd_staged_body(const BwdArgs &a, const int
         }
     };
 
-    float4_t acc[CL];
+    float4_t acc[MB][CL];
 #pragma unroll
-    for (int c = 0; c < CL; ++c) acc[c] = float4_t{0.f, 0.f, 0.f, 0.f};
+    for (int b = 0; b < MB; ++b)
+#pragma unroll
+        for (int c = 0; c < CL; ++c) acc[b][c] = float4_t{0.f, 0.f, 0.f, 0.f};
 
     // Requests complete in the order they were made, so "stage st has landed" is a bound on the number of requests
     // still outstanding: those of the stages requested after it.  wait_later(n, keep): at most n later stages and, of
@@ -432,8 +441,12 @@ __device__ __forceinline__ void gemv_bwd_staged_body(const BwdArgs &a, const int
                 w[e][0] = *(const uint32_t *)src;
             }
         }
-        u16x8_t df = *(const u16x8_t *)(buf + T::WBYTES + wc * 512 + (((4 * wave + q) ^ wc) * 16));
-        if (!in) df = ZERO8;
+        u16x8_t df[MB];
+#pragma unroll
+        for (int b = 0; b < MB; ++b) {
+            df[b] = *(const u16x8_t *)(buf + T::WBYTES + (16 * b + wc) * 512 + (((4 * wave + q) ^ wc) * 16));
+            if (!in) df[b] = ZERO8;
+        }
         const uint16_t *cs = conv + (st & 1) * (4 * BS_RS) + gl * BS_RS + 32 * wave + 8 * q;
         // read with the element type they were written with, then regrouped into pairs
         const u32x4_t sv = __builtin_bit_cast(u32x4_t, *(const u16x8_t *)cs);
@@ -450,7 +463,8 @@ __device__ __forceinline__ void gemv_bwd_staged_body(const BwdArgs &a, const int
                 u16x8_t wf;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) wf[e] = to16<BF16>(((float)code_of<BITS, WORDS>(w[e], c) - z[e]) * s[e]);
-                acc[c] = mfma16<BF16>(df, wf, acc[c]);                     // D[m = 4q+v][column CL wc + c]
+#pragma unroll
+                for (int b = 0; b < MB; ++b) acc[b][c] = mfma16<BF16>(df[b], wf, acc[b][c]);   // D[m = 4q+v][column CL wc + c]
             }
         } else {
             half2_t s2[4], nz2[4];
@@ -461,54 +475,68 @@ __device__ __forceinline__ void gemv_bwd_staged_body(const BwdArgs &a, const int
                 nz2[i] = __builtin_bit_cast(half2_t, zw);
             }
 #pragma unroll
-            for (int c = 0; c < CL; ++c) acc[c] = mfma16<BF16>(df, dequant_rows8_f16<BITS, WORDS>(w, c, s2, nz2), acc[c]);
+            for (int c = 0; c < CL; ++c) {
+                const u16x8_t wf = dequant_rows8_f16<BITS, WORDS>(w, c, s2, nz2);
+#pragma unroll
+                for (int b = 0; b < MB; ++b) acc[b][c] = mfma16<BF16>(df[b], wf, acc[b][c]);
+            }
         }
     }
     __syncthreads();                                  // every request has landed (the last wait was for all)
     // ---- the waves' sums meet in LDS: [wave][m][CB] floats, then every thread adds up four columns of one row.  A
     //      lane's CL columns are P = CL / 4 pieces of 16 bytes; piece j sits in slot j ^ f(lane) of the lane's P, with f
     //      chosen so that the sixteen lanes of one store fall on sixteen different bank groups.
+    //      (one token block at a time: the area holds the sums of sixteen token rows)
     constexpr int P = CL / 4;
     float *red = (float *)lds;
     const int f = (wc / (16 / P)) & (P - 1);
 #pragma unroll
-    for (int v = 0; v < 4; ++v) {
-        float *dst = red + ((size_t)wave * 16 + 4 * q + v) * CB + CL * wc;
+    for (int b = 0; b < MB; ++b) {
+        if (b > 0) __syncthreads();                   // the sums of the block before have been read
 #pragma unroll
-        for (int j = 0; j < P; ++j)
-            *(float4_t *)(dst + 4 * (j ^ f)) = float4_t{acc[4 * j][v], acc[4 * j + 1][v], acc[4 * j + 2][v], acc[4 * j + 3][v]};
-    }
-    __syncthreads();
-    for (int e = threadIdx.x; e < 16 * CB / 4; e += NT) {
-        const int m = e / (CB / 4), k4 = e % (CB / 4);
-        if (m >= a.M) continue;
-        const int lw = k4 / P, slot = P * lw + ((k4 % P) ^ ((lw / (16 / P)) & (P - 1)));
-        float4_t v = {0.f, 0.f, 0.f, 0.f};
+        for (int v = 0; v < 4; ++v) {
+            float *dst = red + ((size_t)wave * 16 + 4 * q + v) * CB + CL * wc;
 #pragma unroll
-        for (int w = 0; w < NW; ++w) v += *(const float4_t *)(red + ((size_t)w * 16 + m) * CB + 4 * slot);
-        *(float4_t *)(a.partial + ((long)sp * a.M + m) * K + cb * CB + 4 * k4) = v;
+            for (int j = 0; j < P; ++j)
+                *(float4_t *)(dst + 4 * (j ^ f)) =
+                    float4_t{acc[b][4 * j][v], acc[b][4 * j + 1][v], acc[b][4 * j + 2][v], acc[b][4 * j + 3][v]};
+        }
+        __syncthreads();
+        for (int e = threadIdx.x; e < 16 * CB / 4; e += NT) {
+            const int m = 16 * b + e / (CB / 4), k4 = e % (CB / 4);
+            if (m >= a.M) continue;
+            const int lw = k4 / P, slot = P * lw + ((k4 % P) ^ ((lw / (16 / P)) & (P - 1)));
+            float4_t v = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int w = 0; w < NW; ++w) v += *(const float4_t *)(red + ((size_t)w * 16 + (m & 15)) * CB + 4 * slot);
+            *(float4_t *)(a.partial + ((long)sp * a.M + m) * K + cb * CB + 4 * k4) = v;
+        }
     }
 }
 
 // u = dY B of one row slice (the workgroup past the last column block of every slice): B^T fragments gathered
 // column-wise, four 32-row chunks in flight per wave
-template <bool BF16>
+template <bool BF16, int MB>
 __device__ __forceinline__ void gemv_bwd_u_body(const BwdArgs &a, const int sp_local, const int sp)
 {
-    constexpr int NW = BS_NW, NT = NW * 64;
+    constexpr int NW = BS_NW, NT = NW * 64, XR = 16 * MB;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-    float (*ured)[16][64 + 1] = (float (*)[16][64 + 1])lds;                 // [NW][16][65], 33 KB of the dynamic LDS
+    float (*ured)[XR][64 + 1] = (float (*)[XR][64 + 1])lds;                 // [NW][XR][65], 33 KB per token block
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wc = lane & 15, q = lane >> 4;
     const int N = a.N, r = a.r;
     const int nbeg = sp_local * a.rows_per_slice, nend = min(N, nbeg + a.rows_per_slice);
-    const int mrow = min(wc, a.M - 1);
-    float4_t uacc[4];
+    float4_t uacc[MB][4];
 #pragma unroll
-    for (int gg = 0; gg < 4; ++gg) uacc[gg] = float4_t{0.f, 0.f, 0.f, 0.f};
+    for (int b = 0; b < MB; ++b)
+#pragma unroll
+        for (int gg = 0; gg < 4; ++gg) uacc[b][gg] = float4_t{0.f, 0.f, 0.f, 0.f};
     for (int nb = nbeg + wave * 32; nb < nend; nb += 32 * NW) {
         const int nn = nb + 8 * q;
         const bool in = nn < nend;                                          // slices end on multiples of 8
-        const u16x8_t df = in ? *(const u16x8_t *)(a.dy + (long)mrow * N + nn) : ZERO8;
+        u16x8_t df[MB];
+#pragma unroll
+        for (int b = 0; b < MB; ++b)
+            df[b] = in ? *(const u16x8_t *)(a.dy + (long)min(16 * b + wc, a.M - 1) * N + nn) : ZERO8;
 #pragma unroll
         for (int gg = 0; gg < 4; ++gg) {
             const int j = gg * 16 + wc;
@@ -518,20 +546,23 @@ __device__ __forceinline__ void gemv_bwd_u_body(const BwdArgs &a, const int sp_l
 #pragma unroll
                 for (int e = 0; e < 8; ++e) bf[e] = a.B[(long)(nn + e) * r + j];
             }
-            uacc[gg] = mfma16<BF16>(df, bf, uacc[gg]);                     // D[m = 4q+v][j = 16 gg + wc]
+#pragma unroll
+            for (int b = 0; b < MB; ++b) uacc[b][gg] = mfma16<BF16>(df[b], bf, uacc[b][gg]);   // D[m = 4q+v][j = 16 gg + wc]
         }
     }
 #pragma unroll
-    for (int gg = 0; gg < 4; ++gg)
+    for (int b = 0; b < MB; ++b)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) ured[wave][4 * q + v][16 * gg + wc] = uacc[gg][v];
+        for (int gg = 0; gg < 4; ++gg)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) ured[wave][16 * b + 4 * q + v][16 * gg + wc] = uacc[b][gg][v];
     __syncthreads();
-    for (int e = threadIdx.x; e < 16 * 64; e += NT) {
+    for (int e = threadIdx.x; e < XR * 64; e += NT) {         // a slice's u: XR rows of 64 columns
         const int m = e >> 6, j = e & 63;
         float v = 0.f;
 #pragma unroll
         for (int w = 0; w < NW; ++w) v += ured[w][m][j];
-        a.upartial[(long)sp * 1024 + e] = v;
+        a.upartial[(long)sp * (XR * 64) + e] = v;
     }
 }
 
@@ -556,7 +587,7 @@ __global__ __launch_bounds__(NW * 64) void gemv_bwd_siblings_kernel(const BwdMul
 // round-robin by their linear index, and two neighbouring column blocks share the 128-byte lines of the packed rows
 // (a block covers 64 bytes of a row at 2 and 4 bits): the work items are renumbered so that each XCD gets a
 // contiguous run of (slice, column block) pairs, column block fastest, and a line is fetched into one L2 only.
-template <int BITS, bool BF16>
+template <int BITS, bool BF16, int MB>
 __global__ __launch_bounds__(BS_NW * 64) void gemv_bwd_staged_kernel(const BwdMulti ma)
 {
     const int gx = (int)gridDim.x, total = gx * (int)gridDim.y;
@@ -568,13 +599,13 @@ __global__ __launch_bounds__(BS_NW * 64) void gemv_bwd_staged_kernel(const BwdMu
     const BwdArgs a = ma.p[pi];
     const int sp_local = sp - (pi ? ma.slice_end[pi - 1] : 0);
     if (cbx + 1 == gx) {
-        if (a.r > 0) gemv_bwd_u_body<BF16>(a, sp_local, sp);
+        if (a.r > 0) gemv_bwd_u_body<BF16, MB>(a, sp_local, sp);
     } else {
-        gemv_bwd_staged_body<BITS, BF16>(a, cbx, sp_local, sp);
+        gemv_bwd_staged_body<BITS, BF16, MB>(a, cbx, sp_local, sp);
     }
 }
 
-// Second backward kernel (M <= 16), one thread per output element:
+// Second backward kernel (M <= 32), one thread per output element:
 //   blocks [0, xb)        dX[m,k] = sum over slices of partial + sc * sum_j u[m,j] A[j,k]
 //   blocks [xb, xb+ab)    dA[j,k] = sc * sum_m u[m,j] x[m,k]
 //   blocks [xb+ab, ...)   dB[n,j] = sc * sum_m dY[m,n] t[m,j]
@@ -589,6 +620,7 @@ struct FinishArgs {
     const uint8_t *keep; // LoRA dropout: keep bits of x as bytes [M, K/8], or NULL
     float keep_scale;
     int r0;              // stacked adapters: adapter columns below r0 are frozen; dA is [r - r0, K], dB [N, r - r0]
+    int ustride;         // floats of a slice's partial u: 64 columns x 16 or 32 token rows
 };
 
 // MASKED (a.keep != NULL) is a template argument: a test of the pointer inside the token loop kept the compiler from
@@ -596,7 +628,7 @@ struct FinishArgs {
 template <bool BF16, bool MASKED>
 __global__ __launch_bounds__(256) void gemv_bwd_finish_kernel(const FinishArgs a)
 {
-    __shared__ float side[16][64 + 1];       // u (dX and dA blocks) or t (dB blocks), as the 16-bit values they round to
+    __shared__ float side[32][64 + 1];       // u (dX and dA blocks) or t (dB blocks), as the 16-bit values they round to
     const int M = a.M, r = a.r, K = a.K, N = a.N;
     const int b = blockIdx.x;
     // The kernel is a few dependent memory round trips long, so every load that can be is requested before the first
@@ -615,7 +647,7 @@ __global__ __launch_bounds__(256) void gemv_bwd_finish_kernel(const FinishArgs a
             for (int s0 = 0; s0 < a.slices; s0 += 16) {      // sixteen slices requested together, summed in slice order
                 float uv[16];
 #pragma unroll
-                for (int i = 0; i < 16; ++i) uv[i] = s0 + i < a.slices ? up[(long)(s0 + i) * 1024] : 0.f;
+                for (int i = 0; i < 16; ++i) uv[i] = s0 + i < a.slices ? up[(long)(s0 + i) * a.ustride] : 0.f;
 #pragma unroll
                 for (int i = 0; i < 16; ++i) v += uv[i];
             }
@@ -767,6 +799,7 @@ bool bwd_staged_applies(const BwdMulti &m)
     if constexpr (BITS == 3) {
         return false;
     } else {
+        if (m.p[0].M > 16 && (m.count > 1 || !BwdStaged<BITS, 2>::FITS)) return false;
         constexpr int CB = BwdShape<BITS>::CB;
         for (int i = 0; i < m.count; ++i) {
             const BwdArgs &a = m.p[i];
@@ -781,22 +814,29 @@ bool bwd_staged_applies(const BwdMulti &m)
     }
 }
 
-// *taken = false and nothing launched: bit-packed zero-points were handed in and the staged kernel, the one that
-// reads them, does not take the shape
+// *taken = false and nothing launched: bit-packed zero-points or more than 16 token rows were handed in and the staged
+// kernel, the one that takes them, does not take the shape
 template <int BITS, bool BF16>
 void launch_bwd_bits(const BwdMulti &m, hipStream_t s, bool *taken)
 {
     *taken = true;
     if constexpr (BITS != 3) {
         if (bwd_staged_applies<BITS>(m)) {
-            auto kern = gemv_bwd_staged_kernel<BITS, BF16>;
-            ensure_dynamic_lds((const void *)kern, BwdStaged<BITS>::LDS);
             const dim3 grid(m.p[0].K / BwdShape<BITS>::CB + 1, m.slice_end[m.count - 1]);
-            QLORA_LAUNCH(kern, grid, dim3(BS_NW * 64), BwdStaged<BITS>::LDS, s, m);
+            if (m.p[0].M <= 16) {
+                auto kern = gemv_bwd_staged_kernel<BITS, BF16, 1>;
+                ensure_dynamic_lds((const void *)kern, BwdStaged<BITS>::LDS);
+                QLORA_LAUNCH(kern, grid, dim3(BS_NW * 64), BwdStaged<BITS>::LDS, s, m);
+            } else if constexpr (BwdStaged<BITS, 2>::FITS) {
+                auto kern = gemv_bwd_staged_kernel<BITS, BF16, 2>;
+                constexpr int lds2 = BwdStaged<BITS, 2>::LDS;
+                ensure_dynamic_lds((const void *)kern, lds2);
+                QLORA_LAUNCH(kern, grid, dim3(BS_NW * 64), lds2, s, m);
+            }
             return;
         }
     }
-    if (m.p[0].zpacked) {
+    if (m.p[0].zpacked || m.p[0].M > 16) {      // the kernels below read unpacked zero-points and hold 16 token rows
         *taken = false;
         return;
     }
@@ -901,7 +941,7 @@ bool launch_bwd_small(const Problem &p, int count, const void *const *dy, const 
         const FinishArgs f{partial, upartial, (const uint16_t *)(A ? A[0] : nullptr), (const uint16_t *)x,
                            (const uint16_t *)dy[0], (const uint16_t *)(t ? t[0] : nullptr), (uint16_t *)dx,
                            dA ? dA[0] : nullptr, dB ? dB[0] : nullptr, p.M, N[0], p.K, p.r, total, xb, ab, p.sc, beta,
-                           (const uint8_t *)keep, keep_scale, frozen};
+                           (const uint8_t *)keep, keep_scale, frozen, p.M > 16 ? 2048 : 1024};
         const dim3 grid(xb + ab + bb), block(256);
         if (keep) {
             if (p.bf16) QLORA_LAUNCH((gemv_bwd_finish_kernel<true, true>), grid, block, 0, s, f);

@@ -92,7 +92,8 @@ void launch_bwd_dx_mfma(const Problem &p, const void *dy, const uint32_t *packed
 
 // gemv.hip -- small token counts: weight-streaming kernels, one pass over the packed weight
 constexpr int SMALL_M_FWD_MAX = 32;   // above: the tiled GEMM with its contraction split over workgroups is faster
-constexpr int SMALL_M_BWD_MAX = 16;   // backward kernel keeps one 16-row token block
+constexpr int SMALL_M_BWD_MAX = 32;   // backward kernel: one 16-row token block, or two where its staged form applies
+constexpr int SIBLINGS_MAX_M = 16;    // sibling launches keep one token block
 int gemv_bwd_slices(int N, int K, int bits);   // row slices of the backward kernel
 bool fwd_small_computes_t(int rank);           // true: the forward kernel forms t = x A^T itself (unless t is handed in)
 constexpr int MAX_SIBLINGS = 4;                // projections that read the same x, served by one launch

@@ -63,6 +63,8 @@ CASES = [
     (7, 256, 72, 4, 64, 8, "f16", 0.05),
     (16, 1376, 520, 2, 32, 24, "bf16", 0.5),
     (3, 512, 136, 8, 128, 64, "f16", 0.05),
+    (27, 1024, 264, 4, 128, 16, "f16", 0.3),             # 17 to 32 token rows: the staged kernels with two token blocks
+    (32, 512, 136, 2, 128, 8, "bf16", 0.05),
     (40, 384, 264, 3, 128, 16, "f16", 0.3),
     (300, 640, 392, 4, 128, 8, "f16", 0.05),
     (257, 1024, 520, 2, 128, 32, "bf16", 0.5),

@@ -12,6 +12,7 @@ CASES = [
     # (M, K, N, bits, G, rank, frozen, dtype): weight-streaming backward, tiled backward at small and large M
     (6, 256, 72, 4, 64, 16, 8, "f16"),
     (16, 1376, 520, 2, 32, 40, 32, "bf16"),
+    (20, 512, 136, 2, 128, 40, 32, "bf16"),      # two token blocks in the staged backward kernel
     (40, 384, 264, 3, 128, 40, 32, "f16"),
     (300, 640, 392, 4, 128, 40, 32, "f16"),
     (257, 1024, 520, 8, 128, 64, 32, "bf16"),
@@ -76,6 +77,7 @@ DROPOUT_CASES = [
     # the GEMM's epilogue (ranks up to 32) and added afterwards (above), 256-row tiles
     (6, 256, 72, 4, 64, 16, 8, "f16", 0.05),
     (16, 1024, 520, 2, 128, 40, 32, "bf16", 0.3),
+    (29, 1024, 264, 4, 128, 24, 16, "f16", 0.3),          # 17 to 32 token rows: the staged backward kernel, two token blocks
     (40, 384, 264, 3, 128, 24, 16, "f16", 0.05),
     (300, 640, 392, 4, 128, 40, 32, "f16", 0.3),
     (257, 1024, 264, 8, 128, 32, 24, "bf16", 0.05),
