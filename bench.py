@@ -115,7 +115,7 @@ def _graph_time(launch_all, iters: int):
     return e0.elapsed_ms(e1) * 1e3 / iters       # microseconds per replay
 
 
-def run_small_m(M: int = 16, iters: int = 5, headline_layer: bool = True):
+def run_small_m(M: int = 16, iters: int = 5, headline_layer: bool = True, bit_widths=(2, 8), sibling_calls: bool = True):
     """Packed-weight GB/s at M tokens.
 
     Every measured burst walks a pool of distinct weight sets larger than 1 GB (the last-level cache is 256 MB),
@@ -182,7 +182,7 @@ def run_small_m(M: int = 16, iters: int = 5, headline_layer: bool = True):
         k, v = measure([q4], "q_proj_int4")
         results[k] = v
         del q4
-    for bits in (2, 8):
+    for bits in bit_widths:
         cfgs = wl.config5(bits, M)
         by_shape = {}
         layers = []
@@ -195,11 +195,12 @@ def run_small_m(M: int = 16, iters: int = 5, headline_layer: bool = True):
                                       "cuda:0"))
         k, v = measure(layers, f"decoder_block_int{bits}")
         results[k] = v
-        # the same block with q/k/v and gate/up handed over together (they read the same activations)
-        names = [c.name.split("_")[1] for c in cfgs]
-        groups = [[names.index(n) for n in g] for g in (("q", "k", "v"), ("o",), ("gate", "up"), ("down",))]
-        k, v = measure(layers, f"decoder_block_int{bits}_sibling_calls", groups)
-        results[k] = v
+        if sibling_calls:
+            # the same block with q/k/v and gate/up handed over together (they read the same activations)
+            names = [c.name.split("_")[1] for c in cfgs]
+            groups = [[names.index(n) for n in g] for g in (("q", "k", "v"), ("o",), ("gate", "up"), ("down",))]
+            k, v = measure(layers, f"decoder_block_int{bits}_sibling_calls", groups)
+            results[k] = v
         del layers, by_shape
         torch.cuda.empty_cache()
     def overall(keys):
@@ -208,12 +209,13 @@ def run_small_m(M: int = 16, iters: int = 5, headline_layer: bool = True):
         return round(tot_b / tot_us * 1e-3, 1)
 
     first = ["q_proj_int4"] if headline_layer else []
-    per_layer = overall(first + ["decoder_block_int2", "decoder_block_int8"])
-    siblings = overall(first + ["decoder_block_int2_sibling_calls", "decoder_block_int8_sibling_calls"])
+    per_layer = overall(first + [f"decoder_block_int{b}" for b in bit_widths])
     results["all_fwd_bwd_packed_weight_GBps"] = per_layer                       # one call per projection
     results["all_frac_of_hbm_peak"] = round(per_layer / PEAK_HBM_GBPS, 4)
-    results["all_sibling_calls_fwd_bwd_packed_weight_GBps"] = siblings           # q/k/v and gate/up together
-    results["all_sibling_calls_frac_of_hbm_peak"] = round(siblings / PEAK_HBM_GBPS, 4)
+    if sibling_calls:
+        siblings = overall(first + [f"decoder_block_int{b}_sibling_calls" for b in bit_widths])
+        results["all_sibling_calls_fwd_bwd_packed_weight_GBps"] = siblings       # q/k/v and gate/up together
+        results["all_sibling_calls_frac_of_hbm_peak"] = round(siblings / PEAK_HBM_GBPS, 4)
     return results
 
 
@@ -556,6 +558,8 @@ def main() -> int:
         extras["small_m"] = {"M": 16, "timing": "HIP-graph replays over a >1 GB pool of distinct weight sets",
                              **run_small_m(16)}
         extras["small_m_M1"] = {"M": 1, "timing": "as small_m", **run_small_m(1, headline_layer=False)}
+        extras["small_m_M32"] = {"M": 32, "timing": "as small_m; two 16-row token blocks per weight fragment",
+                                 **run_small_m(32, bit_widths=(2,), sibling_calls=False)}
         extras["lrec_loss"] = run_lrec_loss()
         extras["actorder_gather"] = run_actorder_gather()
         extras["stacked_adapters"] = run_stacked()

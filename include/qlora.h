@@ -266,11 +266,12 @@ int qlora_linear_bwd_dropout_stacked(const void *dy, const void *x, const uint32
  * packed_zeros is device memory [N, Zw] uint32 as qlora_pack_zeros writes it,
  * 16-byte aligned; everything else as for qlora_linear_fwd and
  * qlora_linear_bwd_accumulate, results bit-identical to those calls on the
- * unpacked zero-points.  The weight-streaming kernels for M <= 16 read the
+ * unpacked zero-points.  The weight-streaming kernels for M <= 32 read the
  * packed rows themselves (forward: K and group_size multiples of 128, rank
- * <= 16; backward: bits != 3, the column blocks of 128 or 256 dividing K and
- * holding at most two groups; both: N * groups a multiple of 16 and N * Zw of
- * 4: the shapes of the paper's models at bits 2, 4 and 8 all qualify).  For
+ * <= 16, above 16 rows bits != 3; backward: bits != 3, above 16 rows bits
+ * != 8, the column blocks of 128 or 256 dividing K and holding at most two
+ * groups; both: N * groups a multiple of 16 and N * Zw of 4: the shapes of the
+ * paper's models at bits 2, 4 and 8 all qualify up to 16 rows).  For
  * every other shape the zero-points are first unpacked into the workspace by
  * one more launch, which is why the workspace is larger:
  * qlora_workspace_bytes_zp = qlora_workspace_bytes plus N * groups rounded up

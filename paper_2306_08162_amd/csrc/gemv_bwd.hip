@@ -1,4 +1,4 @@
-// Small token counts, backward pass (M <= 16): see gemv_fwd.hip for the regime.  Two launches: row-sliced partial
+// Small token counts, backward pass (M <= 16; M <= 32 where the staged kernel applies): see gemv_fwd.hip for the regime.  Two launches: row-sliced partial
 // dX = dY Wd with the 8-row in-register transposition of the packed codes (Sec. 3.1: transpose + unpack + matmul in
 // one kernel) and partial u = dY B; then the slice sums, sc u A, dA = sc u^T x and dB = sc dY^T t.
 #include "gemv_common.hpp"

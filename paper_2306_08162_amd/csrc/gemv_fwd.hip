@@ -1,12 +1,12 @@
 // Small token counts: the pass is bound by streaming the packed weight once from HBM (Limitations of the paper:
-// the compressed weight cuts the memory traffic of both passes; this is the regime where that shows).  Every lane
-// fetches its own MFMA fragment of packed words straight from global memory, dequantises it in registers and feeds
-// v_mfma_f32_16x16x32; partial sums go through LDS (and, up to 32 token rows, so do x and A: see the staged
-// forward kernel in gemv_fwd_impl.hpp).  Launches are what the pass is made of at this size, so the rank-r products
-// ride along: one launch forward, two backward (gemv_bwd.hip).
+// the compressed weight cuts the memory traffic of both passes; this is the regime where that shows).  Launches are
+// what the pass is made of at this size, so the rank-r products ride along: one launch forward, two backward
+// (gemv_bwd.hip).
 //
-//   forward  (M <= 64)  y = x Wd^T + sc * t B^T with t = x A^T computed by the same MFMAs (one extra fragment of
-//            A per k-step); one workgroup per 16 weight rows (up to four such blocks), its waves split K.
+//   forward  (M <= 32)  y = x Wd^T + sc * t B^T with t = x A^T computed by the same v_mfma_f32_16x16x32 (one extra
+//            fragment of A per k-step); a workgroup owns up to four blocks of 16 weight rows, its waves split K.
+//            The packed words, x and A are staged through LDS by direct-to-LDS loads (gemv_fwd_m16.hpp); shapes
+//            that kernel does not take stage x and A only and fetch packed words fragment-wise (gemv_fwd_impl.hpp).
 //
 // This file holds the host side of the forward pass; the kernels are instantiated per code width in
 // gemv_fwd_b{2,3,4,8}.hip.

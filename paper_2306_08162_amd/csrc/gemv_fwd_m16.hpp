@@ -1,4 +1,5 @@
-// Forward pass for up to 16 token rows with the packed weight staged through LDS (included by gemv_fwd_impl.hpp).
+// Forward pass for up to 32 token rows (one or two 16-row token blocks) with the packed weight staged through LDS
+// (included by gemv_fwd_impl.hpp).
 //
 // What bounds the pass at this size is the number of memory instructions and cache lines a compute unit has to work
 // through, not the bytes: a lane that fetches its own MFMA fragment of a 2-bit weight touches 8 bytes of a row, so a
