@@ -50,6 +50,18 @@ constexpr int m16_red(int nb, int mb) { return M16_NW * (nb + 1) * 16 * mb * 17 
 constexpr int m16_tc(int ar) { return ar > 0 ? 16 : 64; }                                     // columns of t kept
 constexpr int m16_static(int ar, int mb) { return 16 * mb * (m16_tc(ar) + 1) * 4; }
 
+// s_waitcnt vmcnt(n) for a wave-uniform n in [0, MAX] (the count is an immediate of the instruction)
+template <int MAX>
+__device__ __forceinline__ void wait_vm_upto(int n)
+{
+    if constexpr (MAX == 0) {
+        wait_vm<0>();
+    } else {
+        if (n >= MAX) wait_vm<MAX>();
+        else wait_vm_upto<MAX - 1>(n);
+    }
+}
+
 // NB 16-row weight blocks; AR rows of A staged (0: t is given, or no adapter); MB 16-row token blocks (1 or 2)
 template <int BITS, bool BF16, int NB, int AR, int MB>
 __device__ __forceinline__ void gemv_fwd_m16_body(const FwdArgs &a, const int wg)
@@ -86,6 +98,9 @@ __device__ __forceinline__ void gemv_fwd_m16_body(const FwdArgs &a, const int wg
         w_src[c] = (uint32_t)min(n, rows_here - 1) * row_bytes;
         w_piece[c] = (uint32_t)wswz<BITS, PPR>(n, slot) * 16u;
     }
+    // requests that bring in token rows below M (a request moves RPI rows); the rows of x past them are never fetched:
+    // what the MFMAs make of the stale LDS there lands in output rows that are not stored
+    const int xreq = min(XIX, (a.M + RPI - 1) / RPI);                       // workgroup-uniform
     uint32_t x_src[XIX], a_src[XIA > 0 ? XIA : 1];
 #pragma unroll
     for (int j = 0; j < XIX; ++j) {
@@ -106,7 +121,7 @@ __device__ __forceinline__ void gemv_fwd_m16_body(const FwdArgs &a, const int wg
                 dma16(wbase, w_src[j] + (at < row_bytes ? at : 0u), base + WOFF + (uint32_t)(wave + NW * j) * 1024u);
             }
         } else if (j < WI_HI + XIX) {
-            dma16(a.x, x_src[j - WI_HI] + kb, base + (uint32_t)wave * XA + (j - WI_HI) * 1024u);
+            if (j - WI_HI < xreq) dma16(a.x, x_src[j - WI_HI] + kb, base + (uint32_t)wave * XA + (j - WI_HI) * 1024u);
         } else {
             dma16(a.A, a_src[j - WI_HI - XIX] + kb, base + (uint32_t)wave * XA + XBYTES + (j - WI_HI - XIX) * 1024u);
         }
@@ -162,7 +177,7 @@ __device__ __forceinline__ void gemv_fwd_m16_body(const FwdArgs &a, const int wg
     for (int st = 0; st < S; ++st) {
         // stage st has landed once at most the requests of stage st + 1 (issued after it) are outstanding
         if (st + 1 < S) {
-            if (w_hi) wait_vm<WI_HI + XI>(); else wait_vm<WI_LO + XI>();
+            wait_vm_upto<WI_HI + XI>((w_hi ? WI_HI : WI_LO) + xreq + XIA);
         } else {
             wait_vm<0>();
         }
