@@ -59,9 +59,10 @@ def _block_inputs(bits: int, M: int):
 
 
 @pytest.mark.parametrize("bits", [2, 8])
-@pytest.mark.parametrize("M", [1, 16])
+@pytest.mark.parametrize("M", [1, 16, 32])
 def test_config5_block_small_token_counts(bits, M):
-    """All seven projections, forward + backward, every row (the weight-streaming kernels)."""
+    """All seven projections, forward + backward, every row (the weight-streaming kernels; at 32 rows with two token
+    blocks, and the tiled backward kernels for the 8-bit block)."""
     for inp in _block_inputs(bits, M):
         check_layer(inp)
 

@@ -31,7 +31,9 @@ MIXED = [
     (11, 1024, 200, 8, 64, 8, "f16"),
     (6, 256, 72, 4, 32, 16, "f16"),            # four groups per column block: both unpack
     (14, 384, 56, 2, 128, 8, "f16"),           # N * groups not in whole 16-byte pieces
-    (27, 1024, 136, 4, 128, 8, "f16"),         # 17 to 32 token rows: forward reads the packed rows, backward unpacks
+    (27, 1024, 136, 4, 128, 8, "f16"),         # 17 to 32 token rows, two token blocks: both passes read the packed rows
+    (20, 1024, 72, 3, 128, 8, "f16"),          # ... 3 bits: both unpack
+    (32, 2048, 200, 8, 128, 8, "bf16"),        # ... 8 bits: forward reads them, the tiled backward kernel unpacks
     (16, 512, 136, 4, 128, 40, "f16"),         # rank above what the forward kernel computes t for
     (40, 512, 136, 4, 128, 8, "f16"),          # more than 16 token rows
     (200, 640, 264, 2, 128, 16, "bf16"),       # the tiled kernels
