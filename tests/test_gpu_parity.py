@@ -446,6 +446,9 @@ TWO_BLOCK_CASES = [
     (31, 640, 72, 2, 128, 0, "f16"),            # K not a multiple of a stage's 512 columns; no adapter
     (20, 4096, 520, 4, 128, 40, "f16"),         # rank 40: t is formed beforehand
     (29, 1536, 1096, 2, 256, 8, "bf16"),        # more than 256 blocks of 16 weight rows / 4: several rounds
+    (19, 128, 136, 4, 128, 8, "f16"),           # one stage, seven of the eight waves without columns
+    (32, 256, 72, 2, 128, 16, "bf16"),
+    (17, 11008, 264, 2, 128, 8, "f16"),         # 22 stages, the last one ragged
     (32, 1024, 136, 3, 128, 8, "f16"),          # 3 bits: the older kernel
     (18, 512, 136, 4, 64, 8, "f16"),            # G = 64: the older kernel
     (33, 1024, 264, 4, 128, 8, "f16"),          # the tiled GEMM
