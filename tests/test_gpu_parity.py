@@ -138,8 +138,8 @@ def test_random_shapes(case):
     check_layer(inp, recompute_t=bool(r) and (M + N) % 2 == 0)
 
 
-def _random_small_token_cases(count, seed):
-    """Seeded random shapes inside the domain of the kernels that stage everything through LDS (up to 16 token rows, K and
+def _random_small_token_cases(count, seed, m_lo=1, m_hi=16):
+    """Seeded random shapes inside the domain of the kernels that stage everything through LDS (m_lo to m_hi token rows, K and
     G multiples of 128): stage counts with and without a tail, one to four weight blocks per workgroup, row slices that
     do and do not divide the rows, every width, both dtypes, adapters computed in the kernel, handed in, or absent."""
     rng = np.random.default_rng(seed)
@@ -149,7 +149,7 @@ def _random_small_token_cases(count, seed):
         K = 128 * int(rng.integers(1, 25))                        # 128 .. 3072
         divisors = [g for g in range(128, K + 1, 128) if K % g == 0]
         G = int(rng.choice(divisors))
-        M = int(rng.integers(1, 17))
+        M = int(rng.integers(m_lo, m_hi + 1))
         N = 8 * int(rng.integers(1, 120))
         if rng.random() < 0.3:
             N = 8 * int(rng.integers(400, 1700))
@@ -167,6 +167,15 @@ def _random_small_token_cases(count, seed):
 def test_random_shapes_small_token_counts(case):
     M, K, N, bits, G, r, dtype = case
     inp = small_inputs(17 * M + 5 * K + N + bits, M, K, N, bits, G, r, dtype)
+    check_layer(inp, recompute_t=bool(r) and (M + N) % 2 == 0)
+
+
+@pytest.mark.parametrize("case", _random_small_token_cases(int(os.environ.get("QLORA_FUZZ_CASES", "40")) // 2,
+                                                           int(os.environ.get("QLORA_FUZZ_SEED", "20230608")) + 2, 17, 32),
+                         ids=lambda c: "M{}_K{}_N{}_b{}_G{}_r{}_{}".format(*c))
+def test_random_shapes_two_token_blocks(case):
+    M, K, N, bits, G, r, dtype = case
+    inp = small_inputs(13 * M + 3 * K + N + bits, M, K, N, bits, G, r, dtype)
     check_layer(inp, recompute_t=bool(r) and (M + N) % 2 == 0)
 
 
