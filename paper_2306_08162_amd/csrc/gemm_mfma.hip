@@ -96,9 +96,16 @@ __device__ __forceinline__ void wait_vm_and_barrier()
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 
-// Swizzle key of a row of the backward weight stage: a permutation of 0..15 over any 16 consecutive rows whose
-// upper two bits run through 0..3 over any 4 consecutive rows starting at a multiple of 4.
-__device__ __forceinline__ constexpr int wswz(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
+// Swizzle key of a row of the backward weight stage.  Its upper two bits run through 0..3 over any 4 consecutive
+// rows starting at a multiple of 4 (the transposing reads), its lower three bits through 0..7 over any 8 consecutive
+// rows starting at a multiple of 8 (the 16-byte writes, one row per lane: eight lanes per clock into a bank space of
+// 128 bytes.  Counters: with a key whose lower three bits took four values, a write took 16 LDS cycles instead of 8).
+__device__ __forceinline__ constexpr int wswz(int row) { return ((row & 3) << 2) | (row & 2) | ((row >> 2) & 1); }
+// Slot key of a row of the forward weight stage of the symmetric arrangement (128-byte rows): eight different values
+// over the even and over the odd rows of any 16 consecutive rows (16-byte reads: sixteen lanes per clock, two rows
+// fill the 256-byte bank space), four different values mod 4 over any 4 consecutive rows (16-byte writes: two
+// lanes per row, pieces p and p + 4, eight lanes per clock into 128 bytes).
+__device__ __forceinline__ constexpr int fswz(int row) { return ((row & 3) ^ ((row >> 2) & 1)) | (((row >> 3) & 1) << 2); }
 
 // MASKED (backward under LoRA dropout, ranks up to 32, no split): the adapter's share of dX is masked per element,
 // dX = dY Wd + keep_sc * keep (.) (u A), so it cannot ride in the accumulators.  The LoRA steps are left out; the
@@ -130,11 +137,12 @@ __global__ __launch_bounds__(WM * WN * 64 + (SYM ? 0 : STAGERS)) void qgemm_kern
     // Weight stage.  Forward: [BN rows n][64 k + 8] (144-byte rows), fragments are 16-byte reads.  Backward: the
     // staging threads own rows n of the contraction, so the stage is kept as they produce it, [64 rows n][BN k],
     // and the fragments are gathered with the transposing LDS read (ds_read_b64_tr_b16), two per fragment.  The
-    // 16-byte pieces of a row are XOR-swizzled with wswz(row): sixteen consecutive rows put the same piece into
-    // sixteen different bank quads (the stagers' 16-byte writes, one row per lane), and four consecutive rows put
-    // four consecutive pieces into disjoint runs of 16 banks (the transposing reads: 4 rows x 64 bytes per half
-    // wave).  Unpadded 320-byte rows served the reads equally well but made the writes collide four ways.
-    // SYM, forward: 128-byte rows with the activation tile's slot swizzle instead of the padding (LDS is full).
+    // 16-byte pieces of a row are XOR-swizzled with wswz(row): eight consecutive rows put the same piece into
+    // eight different bank quads of the 128 bytes a write cycle covers (the stagers' 16-byte writes, one row per
+    // lane), and four consecutive rows put four consecutive pieces into disjoint runs of 16 banks (the transposing
+    // reads: 4 rows x 64 bytes per half wave).  Unpadded 320-byte rows served the reads equally well but made the
+    // writes collide four ways.
+    // SYM, forward: 128-byte rows with a slot swizzle (fswz) instead of the padding (LDS is full).
     constexpr int WPITCH = TRANS ? BN : (SYM ? BK : LDS_STRIDE);
     constexpr int WS = TRANS ? BK * WPITCH : BN * WPITCH;       // halfs per weight stage
     using Regs = StageRegs<BITS, WU>;
@@ -232,8 +240,8 @@ __global__ __launch_bounds__(WM * WN * 64 + (SYM ? 0 : STAGERS)) void qgemm_kern
                                  (uint16_t)hi[0], (uint16_t)hi[1], (uint16_t)hi[2], (uint16_t)hi[3]};
             }
         } else {
-            // (SYM: the slot key (row >> 1) & 7 is the same 32 rows further down)
-            const uint16_t *Bs = wsm + wstage * WS + boff + (SYM ? ((2 * ks + fh) ^ ((fr >> 1) & 7)) * 8 : ks * 16);
+            // (SYM: the slot key depends on the row's lower four bits: the same 32 rows further down)
+            const uint16_t *Bs = wsm + wstage * WS + boff + (SYM ? ((2 * ks + fh) ^ fswz(fr)) * 8 : ks * 16);
 #pragma unroll
             for (int j = 0; j < NI; ++j) f.b[j] = *(const u16x8_t *)(Bs + j * 32 * WPITCH);
         }
@@ -289,8 +297,8 @@ __global__ __launch_bounds__(WM * WN * 64 + (SYM ? 0 : STAGERS)) void qgemm_kern
             const u16x8_t v = dequant8<BITS, BF16>(rg.w[i], part, dq);
             if constexpr (TRANS) {
                 *(u16x8_t *)(Bs + (u & 63) * WPITCH + ((((u >> 6) * 4 + part) ^ wswz(u & 63)) * 8)) = v;
-            } else if constexpr (SYM) {        // row u / 2, pieces 4 (u % 2) + part, slot key (row / 2) % 8
-                *(u16x8_t *)(Bs + (u >> 1) * WPITCH + ((((u & 1) * 4 + part) ^ ((u >> 2) & 7)) * 8)) = v;
+            } else if constexpr (SYM) {        // row u / 2, pieces 4 (u % 2) + part
+                *(u16x8_t *)(Bs + (u >> 1) * WPITCH + ((((u & 1) * 4 + part) ^ fswz(u >> 1)) * 8)) = v;
             } else {
                 *(u16x8_t *)(Bs + (u >> 1) * LDS_STRIDE + (u & 1) * 32 + part * 8) = v;
             }
@@ -583,7 +591,7 @@ __global__ __launch_bounds__(WM * WN * 64 + (SYM ? 0 : STAGERS)) void qgemm_kern
                     const int col = col0 + r;
                     u16x8_t p = {0, 0, 0, 0, 0, 0, 0, 0};
                     if (j < a.r && col < NO) p = *(const u16x8_t *)(a.ext_w + (long)col * a.r + j);
-                    if constexpr (SYM) *(u16x8_t *)(wsm + r * WPITCH + (((c % cpr) ^ ((r >> 1) & 7)) * 8)) = p;
+                    if constexpr (SYM) *(u16x8_t *)(wsm + r * WPITCH + (((c % cpr) ^ fswz(r)) * 8)) = p;
                     else *(u16x8_t *)(wsm + r * LDS_STRIDE + j) = p;
                 }
             }
