@@ -15,7 +15,8 @@ def _snapshot(layer, sib=None):
     return out
 
 
-@pytest.mark.parametrize("M,K", [(16, 512), (300, 512), (300, 2048)], ids=["weight_streaming", "tiled", "tiled_split"])
+@pytest.mark.parametrize("M,K", [(16, 512), (28, 1024), (300, 512), (300, 2048)],
+                         ids=["weight_streaming", "two_token_blocks", "tiled", "tiled_split"])
 def test_graph_replays_match_eager(M, K):
     import torch
     from paper_2306_08162_amd.device import DeviceLayer, DeviceSiblings
@@ -25,6 +26,8 @@ def test_graph_replays_match_eager(M, K):
     other = DeviceLayer(small_inputs(124 + M, M, K, 136, 4, 128, 8, "f16"))
     other.x = layer.x
     sib = DeviceSiblings([layer, other]) if M <= 16 else None
+    if M == 28:     # ... and the zero-points handed over bit-packed (packed on the device, before anything is captured)
+        layer.use_packed_zeros()
 
     def run():
         layer.forward()
