@@ -455,6 +455,8 @@ TWO_BLOCK_CASES = [
     (31, 640, 72, 2, 128, 0, "f16"),            # K not a multiple of a stage's 512 columns; no adapter
     (20, 4096, 520, 4, 128, 40, "f16"),         # rank 40: t is formed beforehand
     (29, 1536, 1096, 2, 256, 8, "bf16"),        # more than 256 blocks of 16 weight rows / 4: several rounds
+    (24, 512, 136, 4, 128, 0, "f16"),           # no adapter in the two-block kernels of both passes
+    (30, 1024, 72, 2, 128, 64, "bf16"),         # rank 64
     (19, 128, 136, 4, 128, 8, "f16"),           # one stage, seven of the eight waves without columns
     (32, 256, 72, 2, 128, 16, "bf16"),
     (17, 11008, 264, 2, 128, 8, "f16"),         # 22 stages, the last one ragged
