@@ -26,8 +26,9 @@ constexpr int M16_LDS = 160 * 1024;
 // faster with the wide slices (INT2 gate/up at M = 16: 12.0 against 13.3 us).
 // With two 16-row token blocks (mb = 2: 17 to 32 token rows) the slices are 64 columns wide for every code width, so
 // that 32 rows of x per wave fit, and there are two stages.
-constexpr int m16_ks(int bits, int mb) { return bits == 8 || mb == 2 ? 64 : 128; }
-constexpr int m16_nst(int bits, int mb) { return bits == 8 && mb == 1 ? 3 : 2; }
+// The same narrow slices when 32 rows of A ride along (ranks 17 to 32).
+constexpr int m16_ks(int bits, int mb, int ar) { return bits == 8 || mb == 2 || ar == 32 ? 64 : 128; }
+constexpr int m16_nst(int bits, int mb, int ar) { return bits == 8 && mb == 1 && ar <= 16 ? 3 : 2; }
 
 // slot of the 16-byte piece `piece` of weight row n inside the row's stage segment of PPR pieces (its own inverse)
 template <int BITS, int PPR>
@@ -37,17 +38,18 @@ __device__ __forceinline__ int wswz(int n, int piece)
     else return piece ^ (n & (PPR < 16 ? PPR - 1 : 15));
 }
 
-constexpr int m16_xa(int bits, int ar, int mb) { return (16 * mb + ar) * 2 * m16_ks(bits, mb); }   // a wave's slices of x and A
+constexpr int m16_xa(int bits, int ar, int mb) { return (16 * mb + ar) * 2 * m16_ks(bits, mb, ar); }   // a wave's slices of x and A
 constexpr int m16_stage(int bits, int nb, int ar, int mb)
 {
-    return M16_NW * m16_xa(bits, ar, mb) + nb * 16 * m16_ks(bits, mb) * bits;
+    return M16_NW * m16_xa(bits, ar, mb) + nb * 16 * m16_ks(bits, mb, ar) * bits;
 }
 constexpr int m16_table(int nb, int ng, int zrow)     // scales (2 B per group), zero-points (zrow bytes per row: one per
 {                                                     // group, or the row's packed words), each filled in whole KB
     return ((nb * 16 * ng * 2 + 1023) & ~1023) + ((nb * 16 * zrow + 1023) & ~1023);
 }
-constexpr int m16_red(int nb, int mb) { return M16_NW * (nb + 1) * 16 * mb * 17 * 4; }      // the waves' partial sums
-constexpr int m16_tc(int ar) { return ar > 0 ? 16 : 64; }                                     // columns of t kept
+constexpr int m16_rga(int ar) { return ar > 16 ? 2 : 1; }                                     // 16-column blocks of t formed here
+constexpr int m16_red(int nb, int mb, int ar) { return M16_NW * (nb + m16_rga(ar)) * 16 * mb * 17 * 4; }   // the waves' partial sums
+constexpr int m16_tc(int ar) { return ar > 16 ? 32 : (ar > 0 ? 16 : 64); }                    // columns of t kept
 constexpr int m16_static(int ar, int mb) { return 16 * mb * (m16_tc(ar) + 1) * 4; }
 
 // s_waitcnt vmcnt(n) for a wave-uniform n in [0, MAX] (the count is an immediate of the instruction)
@@ -67,7 +69,7 @@ template <int BITS, bool BF16, int NB, int AR, int MB>
 __device__ __forceinline__ void gemv_fwd_m16_body(const FwdArgs &a, const int wg)
 {
     constexpr int NW = M16_NW, NT = NW * 64, R = 16 * NB, XROWS = 16 * MB;
-    constexpr int KS = m16_ks(BITS, MB), KC = NW * KS, NST = m16_nst(BITS, MB), SS = KS / 32;   // SS: MFMA steps of a wave per stage
+    constexpr int KS = m16_ks(BITS, MB, AR), KC = NW * KS, NST = m16_nst(BITS, MB, AR), SS = KS / 32;   // SS: MFMA steps of a wave per stage
     constexpr int PPR = KS * BITS / 16, UB = KS * BITS / 32; // pieces of a weight row per stage; bytes of a lane's codes
     constexpr int PR = KS / 8, RPI = 64 / PR;                // pieces of an activation row per stage; rows per request
     constexpr int XBYTES = 2 * XROWS * KS;                   // a wave's slice of x
@@ -75,7 +77,7 @@ __device__ __forceinline__ void gemv_fwd_m16_body(const FwdArgs &a, const int wg
     constexpr int WI = R * PPR / 64;                         // weight requests per stage, dealt out wave by wave
     constexpr int WI_HI = (WI + NW - 1) / NW, WI_LO = WI / NW;
     constexpr int XIX = XROWS / RPI, XIA = AR / RPI, XI = XIX + XIA;   // requests of a wave's own slices
-    constexpr int TC = m16_tc(AR);
+    constexpr int TC = m16_tc(AR), RGA = m16_rga(AR);
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     __shared__ float tfull[XROWS][TC + 1];
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -106,7 +108,11 @@ __device__ __forceinline__ void gemv_fwd_m16_body(const FwdArgs &a, const int wg
     for (int j = 0; j < XIX; ++j) {
         const int row = RPI * j + lane / PR, piece = (lane % PR) ^ (row & (PR - 1));
         x_src[j] = (uint32_t)(((long)min(row, a.M - 1) * K + 8 * piece) * 2);
-        if (j < XIA) a_src[j] = (uint32_t)(((long)min(row, r - 1) * K + 8 * piece) * 2);
+    }
+#pragma unroll
+    for (int j = 0; j < XIA; ++j) {
+        const int row = RPI * j + lane / PR, piece = (lane % PR) ^ (row & (PR - 1));
+        a_src[j] = (uint32_t)(((long)min(row, r - 1) * K + 8 * piece) * 2);
     }
     // the requests of one stage, one at a time (they are spread over the arithmetic of the stage before: a request
     // waits for room in the memory pipeline, and meanwhile the wave could be multiplying)
@@ -166,10 +172,11 @@ __device__ __forceinline__ void gemv_fwd_m16_body(const FwdArgs &a, const int wg
         }
     }
 
-    float4_t acc[MB][NB], tacc[MB];
+    float4_t acc[MB][NB], tacc[MB][RGA];
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
-        tacc[mb] = float4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int g = 0; g < RGA; ++g) tacc[mb][g] = float4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = float4_t{0.f, 0.f, 0.f, 0.f};
     }
@@ -187,7 +194,7 @@ __device__ __forceinline__ void gemv_fwd_m16_body(const FwdArgs &a, const int wg
         const uint8_t *xs = buf + (size_t)wave * XA, *wc = buf + WOFF;
         const int k0 = st * KC + wave * KS;
         const bool live = k0 < K;                            // wave-uniform
-        u16x8_t xf[MB][SS], af[SS];
+        u16x8_t xf[MB][SS], af[RGA][SS];
         uint32_t w[NB][BITS];                                // the first UB bytes are used
         float sc[NB], zp[NB];
 #pragma unroll
@@ -195,7 +202,11 @@ __device__ __forceinline__ void gemv_fwd_m16_body(const FwdArgs &a, const int wg
             const int slot = li * PR + ((SS * q + s) ^ (li & (PR - 1)));        // 16 rows on: the same slot key
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) xf[mb][s] = *(const u16x8_t *)(xs + (16 * mb * PR + slot) * 16);
-            if constexpr (AR > 0) af[s] = li < min(r, AR) ? *(const u16x8_t *)(xs + XBYTES + slot * 16) : ZERO8;
+            if constexpr (AR > 0) {
+#pragma unroll
+                for (int g = 0; g < RGA; ++g)       // adapter rows 16 g + li: 16 rows on, the same slot key
+                    af[g][s] = 16 * g + li < min(r, AR) ? *(const u16x8_t *)(xs + XBYTES + (16 * g * PR + slot) * 16) : ZERO8;
+            }
         }
         const int grp = live ? group_of(k0, a.magic) : 0;
 #pragma unroll
@@ -262,7 +273,9 @@ __device__ __forceinline__ void gemv_fwd_m16_body(const FwdArgs &a, const int wg
             for (int s = 0; s < SS; ++s) {
                 if (more && SS * NB + s < NS) issue_step(st + 2, fill, SS * NB + s);
 #pragma unroll
-                for (int mb = 0; mb < MB; ++mb) tacc[mb] = mfma16<BF16>(xf[mb][s], af[s], tacc[mb]);   // D[m][j = li]
+                for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                    for (int g = 0; g < RGA; ++g) tacc[mb][g] = mfma16<BF16>(xf[mb][s], af[g][s], tacc[mb][g]);   // D[m][j = 16 g + li]
             }
         }
         if (more) {
@@ -273,27 +286,30 @@ __device__ __forceinline__ void gemv_fwd_m16_body(const FwdArgs &a, const int wg
 
     // ---- the waves' partial sums meet in LDS (where the stages were)
     __syncthreads();
-    float *red = (float *)lds;                               // [NW][NB + 1][XROWS][17], over the stages and tables
+    float *red = (float *)lds;                               // [NW][NB + RGA][XROWS][17], over the stages and tables
     auto red_at = [&](int w, int blk, int row, int col) -> float & {
-        return red[((w * (NB + 1) + blk) * XROWS + row) * 17 + col];
+        return red[((w * (NB + RGA) + blk) * XROWS + row) * 17 + col];
     };
-    static_assert(m16_red(NB, MB) <= M16_LDS - m16_static(AR, MB), "partial sums fit (the launch sizes LDS for them)");
+    static_assert(m16_red(NB, MB, AR) <= M16_LDS - m16_static(AR, MB), "partial sums fit (the launch sizes LDS for them)");
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) red_at(wave, nb, 16 * mb + 4 * q + v, li) = acc[mb][nb][v];
-            if constexpr (AR > 0) red_at(wave, NB, 16 * mb + 4 * q + v, li) = tacc[mb][v];
+            if constexpr (AR > 0) {
+#pragma unroll
+                for (int g = 0; g < RGA; ++g) red_at(wave, NB + g, 16 * mb + 4 * q + v, li) = tacc[mb][g][v];
+            }
         }
     __syncthreads();
     if constexpr (AR > 0) {
-        for (int e = threadIdx.x; e < XROWS * 16; e += NT) {
-            const int m = e >> 4, j = e & 15;
+        for (int e = threadIdx.x; e < XROWS * (16 * RGA); e += NT) {
+            const int m = e / (16 * RGA), j = e % (16 * RGA);
             float tv = 0.f;
             if (j < r && m < a.M) {
 #pragma unroll
-                for (int w = 0; w < NW; ++w) tv += red_at(w, NB, m, j);
+                for (int w = 0; w < NW; ++w) tv += red_at(w, NB + (j >> 4), m, j & 15);
                 tv = cvt16<BF16>(to16<BF16>(tv));            // the value every consumer of t sees
                 if (wg == 0 && a.t_out) a.t_out[(long)m * r + j] = to16<BF16>(tv);
             }
@@ -344,7 +360,7 @@ template <int BITS>
 inline int m16_nb_max(int ar, int ng, int zrow, int mb)
 {
     for (int nb = 4; nb >= 1; --nb)
-        if (m16_nst(BITS, mb) * m16_stage(BITS, nb, ar, mb) + m16_table(nb, ng, zrow) + m16_static(ar, mb) <= M16_LDS)
+        if (m16_nst(BITS, mb, ar) * m16_stage(BITS, nb, ar, mb) + m16_table(nb, ng, zrow) + m16_static(ar, mb) <= M16_LDS)
             return nb;
     return 0;
 }
@@ -352,8 +368,8 @@ inline int m16_nb_max(int ar, int ng, int zrow, int mb)
 template <int BITS, bool BF16, int NB, int AR, int MB>
 void launch_fwd_m16_one(FwdMulti m, hipStream_t s)
 {
-    const int pipe = m16_nst(BITS, MB) * m16_stage(BITS, NB, AR, MB) + m16_table(NB, m.p[0].ng, m16_zrow(m.p[0]));
-    const int lds = pipe > m16_red(NB, MB) ? pipe : m16_red(NB, MB);
+    const int pipe = m16_nst(BITS, MB, AR) * m16_stage(BITS, NB, AR, MB) + m16_table(NB, m.p[0].ng, m16_zrow(m.p[0]));
+    const int lds = pipe > m16_red(NB, MB, AR) ? pipe : m16_red(NB, MB, AR);
     int wgs = 0;
     for (int i = 0; i < m.count; ++i) {
         wgs += (blocks16(m.p[i].N) + NB - 1) / NB;
@@ -367,7 +383,7 @@ void launch_fwd_m16_one(FwdMulti m, hipStream_t s)
 template <int BITS, bool BF16, int AR, int MB>
 void launch_fwd_m16_nb(const FwdMulti &m, int nb, hipStream_t s)
 {
-    constexpr int NST = m16_nst(BITS, MB);
+    constexpr int NST = m16_nst(BITS, MB, AR);
     switch (nb) {
     case 4:
         if constexpr (NST * m16_stage(BITS, 4, AR, MB) < M16_LDS) { launch_fwd_m16_one<BITS, BF16, 4, AR, MB>(m, s); return; }
@@ -383,24 +399,25 @@ void launch_fwd_m16_nb(const FwdMulti &m, int nb, hipStream_t s)
     }
 }
 
-// Serves the call if its shape allows: up to 32 token rows (above 16: not for 3-bit codes), K and the group size
+// Serves the call if its shape allows: up to 32 token rows (above 16, or with more than 16 adapter rows: not for 3-bit
+// codes), K and the group size
 // multiples of 128 (a wave's columns of a stage then share their group constants), t either computed here from at most
-// 16 adapter rows or handed in, and room in LDS for the stages of at least two 16-row blocks (one block would pull x
+// 32 adapter rows or handed in, and room in LDS for the stages of at least two 16-row blocks (one block would pull x
 // through every compute unit once per 16 weight rows).
 template <int BITS, bool BF16>
 bool launch_fwd_m16(const FwdMulti &m, int rg, hipStream_t s)
 {
     const FwdArgs &a = m.p[0];
-    if (a.M > 32 || a.K % 128 != 0 || (a.K / a.ng) % 128 != 0 || rg > 1 || (rg == 0 && a.r > 64)) return false;
+    if (a.M > 32 || a.K % 128 != 0 || (a.K / a.ng) % 128 != 0 || rg > 2 || (rg == 0 && a.r > 64)) return false;
     const int mb = a.M > 16 ? 2 : 1;
-    if (BITS == 3 && mb == 2) return false;      // 64-column slices would cut the 12-byte units of 3-bit codes
+    if (BITS == 3 && (mb == 2 || rg == 2)) return false;   // 64-column slices would cut the 12-byte units of 3-bit codes
     for (int i = 0; i < m.count; ++i) {
         const FwdArgs &b = m.p[i];            // 16-byte requests: aligned arrays, constants in whole pieces
         const uintptr_t bits_or = (uintptr_t)b.x | (uintptr_t)b.packed | (uintptr_t)b.scales | (uintptr_t)b.zeros |
                                   (uintptr_t)b.zpacked | (rg ? (uintptr_t)b.A : 0);
         if ((bits_or & 15) != 0 || ((long)b.N * b.ng) % 16 != 0 || ((long)b.N * m16_zrow(b)) % 16 != 0) return false;
     }
-    const int ar = rg == 0 ? 0 : (a.r <= 8 ? 8 : 16);
+    const int ar = rg == 0 ? 0 : (a.r <= 8 ? 8 : (a.r <= 16 ? 16 : 32));
     const int nb_max = m16_nb_max<BITS>(ar, a.ng, m16_zrow(a), mb);
     if (nb_max < 2) return false;
     // one round of the 256 compute units if the rows allow it; siblings that do not fit one round together go one by one
@@ -424,13 +441,16 @@ bool launch_fwd_m16(const FwdMulti &m, int rg, hipStream_t s)
         switch (ar) {
         case 0: launch_fwd_m16_nb<BITS, BF16, 0, 1>(m, nb, s); break;
         case 8: launch_fwd_m16_nb<BITS, BF16, 8, 1>(m, nb, s); break;
-        default: launch_fwd_m16_nb<BITS, BF16, 16, 1>(m, nb, s); break;
+        case 16: launch_fwd_m16_nb<BITS, BF16, 16, 1>(m, nb, s); break;
+        default:
+            if constexpr (BITS != 3) launch_fwd_m16_nb<BITS, BF16, 32, 1>(m, nb, s);
         }
     } else if constexpr (BITS != 3) {
         switch (ar) {
         case 0: launch_fwd_m16_nb<BITS, BF16, 0, 2>(m, nb, s); break;
         case 8: launch_fwd_m16_nb<BITS, BF16, 8, 2>(m, nb, s); break;
-        default: launch_fwd_m16_nb<BITS, BF16, 16, 2>(m, nb, s); break;
+        case 16: launch_fwd_m16_nb<BITS, BF16, 16, 2>(m, nb, s); break;
+        default: launch_fwd_m16_nb<BITS, BF16, 32, 2>(m, nb, s); break;
         }
     }
     return true;

@@ -457,6 +457,8 @@ TWO_BLOCK_CASES = [
     (29, 1536, 1096, 2, 256, 8, "bf16"),        # more than 256 blocks of 16 weight rows / 4: several rounds
     (24, 512, 136, 4, 128, 0, "f16"),           # no adapter in the two-block kernels of both passes
     (30, 1024, 72, 2, 128, 64, "bf16"),         # rank 64
+    (27, 2048, 264, 4, 128, 32, "f16"),         # rank 32 formed in the kernel (32 adapter rows staged), two token blocks
+    (20, 1024, 136, 8, 128, 24, "bf16"),        # rank 24
     (19, 128, 136, 4, 128, 8, "f16"),           # one stage, seven of the eight waves without columns
     (32, 256, 72, 2, 128, 16, "bf16"),
     (17, 11008, 264, 2, 128, 8, "f16"),         # 22 stages, the last one ragged
@@ -480,4 +482,31 @@ def test_seventeen_to_sixty_four_token_rows(case):
 def test_two_token_blocks_exact(case):
     M, K, N, bits, G, r, dtype = case
     inp = integer_inputs(M + K + N + bits, M, K, N, bits, G, r, dtype, density=0.05 if K > 1024 else 0.2)
+    check_layer(inp, exact=True)
+
+
+# Ranks 17 to 32 (LREC trains rank 32, Appendix C; the ablations of Appendix D use 24): the staged forward kernel
+# stages 32 rows of A and forms t in two 16-column blocks.
+RANK32_CASES = [
+    (16, 4096, 264, 4, 128, 32, "f16"),
+    (7, 1024, 136, 2, 128, 32, "bf16"),
+    (16, 2048, 1096, 2, 128, 24, "f16"),
+    (1, 512, 72, 8, 128, 32, "f16"),
+    (12, 640, 200, 4, 128, 24, "bf16"),
+    (16, 1024, 136, 3, 128, 32, "f16"),         # 3 bits: the older kernel
+]
+
+
+@pytest.mark.parametrize("case", RANK32_CASES, ids=lambda c: "M{}_K{}_N{}_b{}_G{}_r{}_{}".format(*c))
+def test_ranks_17_to_32_small_token_counts(case):
+    M, K, N, bits, G, r, dtype = case
+    inp = small_inputs(M + 2 * K + 3 * N + r, M, K, N, bits, G, r, dtype)
+    check_layer(inp)
+
+
+@pytest.mark.parametrize("case", [(16, 1024, 136, 4, 128, 32, "f16"), (24, 2048, 72, 2, 128, 32, "bf16")],
+                         ids=lambda c: "M{}_K{}_N{}_b{}_G{}_r{}_{}".format(*c))
+def test_rank_32_exact(case):
+    M, K, N, bits, G, r, dtype = case
+    inp = integer_inputs(M + K + N + r, M, K, N, bits, G, r, dtype, density=0.1)
     check_layer(inp, exact=True)
