@@ -432,14 +432,102 @@ void launch_skinny(const uint16_t *act, const uint16_t *small, uint16_t *out, in
         launch_skinny_staged_rank<BF16, 8, false, MASKED>(act, small, out, M, C, r, keep, keep_scale, s);
 }
 
+// ---- t = x A^T for up to 32 token rows.  The kernel above gives a workgroup eight token rows and the whole
+//      contraction: at 16 rows that is two workgroups, each pulling all of A through one compute unit (8 us at K = 4096,
+//      rank 40).  Here the contraction is split instead: workgroup p multiplies columns [p chunk, (p + 1) chunk), its
+//      four waves taking 32-column steps in turn, and leaves an fp32 plane [M][r]; a second, tiny launch sums the planes
+//      in order and rounds once.
+template <bool BF16>
+__global__ __launch_bounds__(256) void lora_down_small_partial_kernel(const uint16_t *__restrict__ x,
+                                                                      const uint16_t *__restrict__ A,
+                                                                      float *__restrict__ part, int M, int K, int r,
+                                                                      int chunk)
+{
+    __shared__ float red[4][2][4][16][17];             // [wave][token block][rank block][m][j]
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, li = lane & 15, q = lane >> 4;
+    const int k_begin = (int)blockIdx.x * chunk, k_end = min(K, k_begin + chunk);
+    const int mbs = (M + 15) / 16, rgs = (r + 15) / 16;                       // at most 2 and 4
+    const u16x8_t ZERO8 = {0, 0, 0, 0, 0, 0, 0, 0};
+    float4_t acc[2][4];
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) acc[b][g] = float4_t{0.f, 0.f, 0.f, 0.f};
+    for (int k0 = k_begin + 32 * wave; k0 < k_end; k0 += 128) {             // K is a multiple of 32: whole steps
+        u16x8_t xf[2], af[4];
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+            xf[b] = b < mbs ? *(const u16x8_t *)(x + (long)min(16 * b + li, M - 1) * K + k0 + 8 * q) : ZERO8;
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+            af[g] = (g < rgs && 16 * g + li < r) ? *(const u16x8_t *)(A + (long)(16 * g + li) * K + k0 + 8 * q) : ZERO8;
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+                if (b < mbs && g < rgs) acc[b][g] = mfma16<BF16>(xf[b], af[g], acc[b][g]);   // D[m = 4q+v][j = li]
+    }
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) red[wave][b][g][4 * q + v][li] = acc[b][g][v];
+    __syncthreads();
+    float *plane = part + (size_t)blockIdx.x * M * r;
+    for (int e = threadIdx.x; e < M * r; e += 256) {
+        const int m = e / r, j = e % r;
+        float v = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) v += red[w][m >> 4][j >> 4][m & 15][j & 15];
+        plane[e] = v;
+    }
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void lora_down_small_sum_kernel(const float *__restrict__ part,
+                                                                  uint16_t *__restrict__ t, int planes, int count)
+{
+    const int e = (int)blockIdx.x * 256 + threadIdx.x;
+    if (e >= count) return;
+    float v = 0.f;
+    for (int p0 = 0; p0 < planes; p0 += 16) {           // sixteen planes requested together, summed in plane order
+        float pv[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) pv[i] = p0 + i < planes ? part[(size_t)(p0 + i) * count + e] : 0.f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) v += pv[i];
+    }
+    t[e] = to16<BF16>(v);
+}
+
 }  // namespace
 
+int lora_down_small_chunk(int K)
+{
+    const int c = (K / 64 + 127) / 128 * 128;          // about 64 planes at most, whole steps of the four waves
+    return c < 128 ? 128 : c;
+}
+int lora_down_small_planes(int K) { return (K + lora_down_small_chunk(K) - 1) / lora_down_small_chunk(K); }
+
 void launch_lora_down(const void *x, const void *A, void *t, int M, int K, int r, bool bf16, const uint32_t *keep,
-                      float keep_scale, hipStream_t s)
+                      float keep_scale, hipStream_t s, float *planes)
 {
     const uint16_t *xp = (const uint16_t *)x, *Ap = (const uint16_t *)A;
     uint16_t *tp = (uint16_t *)t;
     const uint8_t *kb = (const uint8_t *)keep;
+    if (planes && !keep && M <= LORA_DOWN_SMALL_MAX_M) {
+        const int chunk = lora_down_small_chunk(K), np = lora_down_small_planes(K);
+        const dim3 sum_grid((unsigned)((M * r + 255) / 256));
+        if (bf16) {
+            QLORA_LAUNCH(lora_down_small_partial_kernel<true>, dim3(np), dim3(256), 0, s, xp, Ap, planes, M, K, r, chunk);
+            QLORA_LAUNCH(lora_down_small_sum_kernel<true>, sum_grid, dim3(256), 0, s, planes, tp, np, M * r);
+        } else {
+            QLORA_LAUNCH(lora_down_small_partial_kernel<false>, dim3(np), dim3(256), 0, s, xp, Ap, planes, M, K, r, chunk);
+            QLORA_LAUNCH(lora_down_small_sum_kernel<false>, sum_grid, dim3(256), 0, s, planes, tp, np, M * r);
+        }
+        return;
+    }
     if (keep) {
         if (bf16) launch_skinny<true, true>(xp, Ap, tp, M, K, r, kb, keep_scale, s);
         else launch_skinny<false, true>(xp, Ap, tp, M, K, r, kb, keep_scale, s);

@@ -50,6 +50,9 @@ int check_problem(int M, int N, int K, int bits, int G, int r, int dtype)
 
 struct Workspace {
     size_t t_off, u_off, upartial_off, partial_off, split_off, total;
+    bool t_planes;      // the partial-dX region may serve as the fp32 planes of t = x A^T at small token counts: it holds
+                        // at least M * K floats, the planes at most ceil(K / 128) * M * 64 of them (K >= 128: no more
+                        // than that), and t is formed before anything else uses the region
 };
 
 Workspace carve(int M, int N, int K, int r, int bits)
@@ -72,6 +75,7 @@ Workspace carve(int M, int N, int K, int r, int bits)
     const size_t pf = sf > 1 ? sf * M * N * sizeof(float) : 0, pb = sb > 1 ? sb * M * K * sizeof(float) : 0;
     off += round_up(pf > pb ? pf : pb);
     w.total = off < ALIGN ? ALIGN : off;
+    w.t_planes = M <= SMALL_M_BWD_MAX && M <= LORA_DOWN_SMALL_MAX_M && K >= 128;    // (K >= 128: see Workspace)
     return w;
 }
 
@@ -301,7 +305,9 @@ static int forward(const void *x, const uint32_t *packed, const void *scales, co
         // one launch: the weight-streaming kernel also forms t (ranks up to 32, no dropout)
         void *t = rank > 0 ? (t_save ? t_save : (void *)(ws + w.t_off)) : nullptr;
         const bool t_first = rank > 0 && (keep_mask || !fwd_small_computes_t(rank));
-        if (t_first) launch_lora_down(x, A, t, M, K, rank, p.bf16, keep_mask, keep_scale, s);
+        if (t_first)
+            launch_lora_down(x, A, t, M, K, rank, p.bf16, keep_mask, keep_scale, s,
+                             w.t_planes ? (float *)(ws + w.partial_off) : nullptr);
         GemmTimer timer(s);
         const void *tc = t;
         if (!zpacked || !launch_fwd_small(p, 1, x, &packed, &scales, &zeros, &A, &B, &tc, &t, &y, &N, t_first, s, &zpacked)) {
@@ -438,7 +444,8 @@ static int backward(const void *dy, const void *x, const uint32_t *packed, const
         // rows only the staged kernel serves, and not every shape: then the tiled kernels below take over.
         const void *t = t_saved;
         if (rank > 0 && !t) {
-            launch_lora_down(x, A, ws + w.t_off, M, K, rank, p.bf16, keep_mask, keep_scale, s);
+            launch_lora_down(x, A, ws + w.t_off, M, K, rank, p.bf16, keep_mask, keep_scale, s,
+                             w.t_planes ? (float *)(ws + w.partial_off) : nullptr);
             t = ws + w.t_off;
             t_ready = true;
         }

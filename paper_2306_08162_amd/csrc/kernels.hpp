@@ -50,8 +50,12 @@ void launch_mfma_probe(float *out, int iters, bool random, hipStream_t s);
 // adapters.hip -- the rank-r side products and the adapter gradients
 // t[M,r] = x[M,K] A[r,K]^T; with a keep mask (LoRA dropout, one bit per element of x, bit k % 32 of word k / 32 of
 // the row) t = keep_scale * (x * keep) A^T
+// planes != NULL, no mask and at most LORA_DOWN_SMALL_MAX_M token rows: the contraction is split over workgroups
+// (planes holds lora_down_small_planes(K) * M * r floats), two launches.
+constexpr int LORA_DOWN_SMALL_MAX_M = 32;
+int lora_down_small_planes(int K);
 void launch_lora_down(const void *x, const void *A, void *t, int M, int K, int r, bool bf16, const uint32_t *keep,
-                      float keep_scale, hipStream_t s);
+                      float keep_scale, hipStream_t s, float *planes = nullptr);
 // dx[m,k] += f * keep[m,k] * sum_j u[m,j] A[j,k]: the adapter's share of dX under dropout, on top of the base product
 void launch_lora_dx_masked(void *dx, const void *u, const void *A, const uint32_t *keep, int M, int K, int r, float f,
                            bool bf16, hipStream_t s);
