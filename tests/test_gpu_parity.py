@@ -510,3 +510,22 @@ def test_rank_32_exact(case):
     M, K, N, bits, G, r, dtype = case
     inp = integer_inputs(M + K + N + r, M, K, N, bits, G, r, dtype, density=0.1)
     check_layer(inp, exact=True)
+
+
+# Ranks above 32 at up to 32 token rows: t = x A^T is formed beforehand by the launches that split the contraction over
+# workgroups (one plane, many planes, a contraction too short for them), then handed to the streaming kernels; the
+# odd token counts recompute t in the backward pass the same way.
+SPLIT_T_CASES = [
+    (1, 128, 72, 4, 64, 40, "f16"),
+    (32, 96, 72, 2, 32, 64, "bf16"),
+    (16, 11008, 136, 2, 128, 48, "f16"),
+    (9, 640, 72, 8, 128, 56, "bf16"),
+    (25, 4096, 264, 4, 128, 64, "f16"),
+]
+
+
+@pytest.mark.parametrize("case", SPLIT_T_CASES, ids=lambda c: "M{}_K{}_N{}_b{}_G{}_r{}_{}".format(*c))
+def test_ranks_above_32_small_token_counts(case):
+    M, K, N, bits, G, r, dtype = case
+    inp = small_inputs(M + K + N + r, M, K, N, bits, G, r, dtype)
+    check_layer(inp, recompute_t=(M % 2 == 1))
