@@ -644,7 +644,10 @@ int qlora_linear_fwd_siblings(int count, const void *x, const uint32_t *const *p
     for (int i = 0; i < count && rank > 0; ++i) {
         t[i] = (t_save && t_save[i]) ? t_save[i] : (void *)(ws + w.t_off[i]);
         tc[i] = t[i];
-        if (!fwd_small_computes_t(rank)) launch_lora_down(x, A[i], t[i], M, K, rank, p.bf16, nullptr, 1.f, s);
+        // (the partial-dX region serves as the fp32 planes of t, one projection after the other: see Workspace)
+        if (!fwd_small_computes_t(rank))
+            launch_lora_down(x, A[i], t[i], M, K, rank, p.bf16, nullptr, 1.f, s,
+                             K >= 128 ? (float *)(ws + w.partial_off) : nullptr);
     }
     GemmTimer timer(s);
     launch_fwd_small(p, count, x, packed, scales, zeros, A, B, tc, t, y, N, false, s);
@@ -681,7 +684,8 @@ int qlora_linear_bwd_siblings(int count, const void *const *dy, const void *x, c
     for (int i = 0; i < count && rank > 0; ++i) {
         t[i] = t_saved ? t_saved[i] : nullptr;
         if (!t[i]) {
-            launch_lora_down(x, A[i], ws + w.t_off[i], M, K, rank, p.bf16, nullptr, 1.f, s);
+            launch_lora_down(x, A[i], ws + w.t_off[i], M, K, rank, p.bf16, nullptr, 1.f, s,
+                             K >= 128 ? (float *)(ws + w.partial_off) : nullptr);
             t[i] = ws + w.t_off[i];
         }
     }

@@ -64,6 +64,7 @@ CASES = [
     (16, 512, (1000, 520), 2, 128, 16, "bf16"),
     (1, 128, (64, 64, 64, 64), 8, 32, 0, "f16"),           # four projections, no adapters
     (9, 320, (264, 48), 3, 32, 64, "bf16"),                # rank 64: t from its own launches
+    (16, 4096, (136, 264, 72), 4, 128, 40, "f16"),         # rank 40: ... which split the contraction over workgroups
     (13, 1376, (520, 2056, 8), 2, 32, 24, "f16"),          # very different sizes, K not a multiple of 128
     (16, 160, (4200, 4104), 8, 32, 8, "f16"),              # many row slices, ragged column block
     (7, 96, (12312,), 4, 96, 8, "f16"),                    # a single projection through the sibling entry points
