@@ -81,11 +81,12 @@ size_t qlora_packed_words(int N, int K, int bits);
 /*
  * Bytes of device scratch qlora_linear_fwd / qlora_linear_bwd need for this
  * problem (the larger of the two); 0 if the arguments are invalid.  The
- * workspace holds t = x A^T and u = dY B when they are not passed in, the
- * per-slice partial sums of dA and dB, and, for token counts whose output
- * makes too few tiles to occupy the chip, the fp32 partial products of a GEMM
- * whose contraction is split over several workgroups (all summed in a fixed
- * order, so results are bitwise reproducible run to run).
+ * workspace holds t = x A^T and u = dY B when they are not passed in, at up
+ * to 32 token rows the per-slice partial sums of u and dX of the
+ * weight-streaming backward kernels, and, for token counts whose output makes
+ * too few tiles to occupy the chip, the fp32 partial products of a GEMM whose
+ * contraction is split over several workgroups (all summed in a fixed order,
+ * so results are bitwise reproducible run to run).
  */
 size_t qlora_workspace_bytes(int M, int N, int K, int bits, int group_size, int rank);
 
