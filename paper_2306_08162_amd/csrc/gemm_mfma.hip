@@ -311,9 +311,9 @@ __global__ __launch_bounds__(WM * WN * 64 + (SYM ? 0 : STAGERS)) void qgemm_kern
 
     if constexpr (SYM) {
         // ---- symmetric waves: every wave requests an MW-th of the activation tile, stages an MW-th of the weight
-        //      stage and multiplies its own block.  Per 64-deep stage and wave: 16 MI NI / 4 MFMAs in four k-steps,
-        //      XDMA direct-to-LDS requests (a quarter per k-step), WU units dequantised into the other weight
-        //      buffer (half a unit per k-step) and WU units requested from memory NSETS stages ahead.
+        //      stage and multiplies its own block.  Per 64-deep stage and wave: four k-steps of MI NI MFMAs, XDMA
+        //      direct-to-LDS requests (a quarter per k-step), WU units dequantised into the other weight buffer (a
+        //      quarter of them per k-step) and WU units requested from memory NSETS stages ahead.
         static_assert((WU == 1 || WU == 2) && NXS == 3, "a quarter of the staging per k-step; three activation stages");
         const int drow = lane >> 3;
         const int dchunk = ((lane & 7) ^ ((4 * cw + (drow >> 1)) & 7)) * 8;
@@ -327,8 +327,8 @@ __global__ __launch_bounds__(WM * WN * 64 + (SYM ? 0 : STAGERS)) void qgemm_kern
             const uint32_t dst = xs_lds + (uint32_t)(stage * XS + (MW * i + cw) * 512) * 2u;
             dma16(a.act, xoff[i] + k2, (uint32_t)__builtin_amdgcn_readfirstlane((int)dst));
         };
-        // a k-step's MFMAs with the next fragments' LDS reads, a piece of dequantisation and its LDS writes spread
-        // between them
+        // a k-step's MFMAs with the next fragments' LDS reads slotted between them (the dequantisation and its LDS
+        // writes are left to the compiler's own schedule: a hint that placed them too took minutes to compile)
         auto spread = [&]() {
 #pragma unroll
             for (int i = 0; i < MI * NI; ++i) {
