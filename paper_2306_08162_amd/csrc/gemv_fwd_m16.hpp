@@ -5,14 +5,15 @@
 // through, not the bytes: a lane that fetches its own MFMA fragment of a 2-bit weight touches 8 bytes of a row, so a
 // wave instruction brings in sixteen 32-byte pieces, and the group constants cost two more such instructions per
 // fragment.  Here nothing is fetched fragment-wise.  A workgroup of eight waves owns 16 NB weight rows and walks K in
-// stages of 8 KS columns (KS = 128; 64 for 8-bit codes): per stage the packed words of all its rows (row segments of
-// KS BITS bytes, whole cache lines), sixteen token rows of x and the adapter rows of A arrive by direct-to-LDS loads
-// of 1 KB per instruction, two stages in flight, and every wave takes the fragments of its KS contraction indices from
-// LDS.  The group constants of all the workgroup's rows are copied to LDS once, at the start.
+// stages of 8 KS columns (KS = 128; 64 for 8-bit codes, for two token blocks and for 32 adapter rows): per stage the
+// packed words of all its rows (row segments of KS BITS bytes, whole cache lines), the token rows of x (16 or 32; only
+// the requests that hold rows below M are made) and the adapter rows of A arrive by direct-to-LDS loads of 1 KB per
+// instruction, two stages in flight, and every wave takes the fragments of its KS contraction indices from LDS.  The
+// group constants of all the workgroup's rows are copied to LDS once, at the start.
 //
-// Layout of a stage in LDS: per wave a 16-row x KS-column slice of x and an AR-row slice of A (piece c of row w in
-// slot (KS / 8) w + (c ^ w), as in the staged kernel); then the weight chunk, row n at n * KS BITS bytes, its 16-byte
-// pieces permuted by wswz() so that sixteen rows read at one piece index fall on different banks.
+// Layout of a stage in LDS: per wave a slice of x (16 MB rows x KS columns) and an AR-row slice of A (piece c of row
+// w in slot (KS / 8) w + (c ^ w mod KS / 8), as in the staged kernel); then the weight chunk, row n at n * KS BITS
+// bytes, its 16-byte pieces permuted by wswz() so that sixteen rows read at one piece index fall on different banks.
 #pragma once
 
 namespace qlora {
