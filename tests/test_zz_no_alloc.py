@@ -57,6 +57,7 @@ def test_two_calls_in_a_row_the_second_smaller():
     _check(small_inputs(903, 300, 640, 392, 2, 128, 24, "bf16"))
     _check(small_inputs(904, 16, 512, 264, 8, 128, 64, "f16"))      # rank 64: t from its own launch, into the scratch
     _check(small_inputs(905, 9, 256, 72, 3, 32, 16, "bf16"))
+    _check(small_inputs(907, 28, 1024, 136, 4, 128, 32, "f16"))     # two token blocks, rank 32 formed in the kernel
 
 
 def test_llama_block_shapes_fit_and_oversized_problems_are_refused():
