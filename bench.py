@@ -24,7 +24,7 @@ PEAK_HBM_GBPS = 8000.0
 # HBM bytes per launch of the two GEMM kernels on the headline workload, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE runs of this script, scaled by a 1 GiB copy in the same runs (profiles/qgemm_c2_hbm_traffic.md).
 EVENT_EVERY = 5
-GEMM_TRAFFIC_BYTES = {"fwd": 102.3e6, "bwd": 105.1e6}
+GEMM_TRAFFIC_BYTES = {"fwd": 86.5e6, "bwd": 88.6e6}
 
 
 def _mean(v):

@@ -178,7 +178,11 @@ __global__ __launch_bounds__(WM * WN * 64 + (SYM ? 0 : STAGERS)) void qgemm_kern
         const int bid = a.splits > 1 ? (int)blockIdx.x % nt : (int)blockIdx.x;
         const int xcd = bid & 7, loc = bid >> 3, per = nt >> 3, rem = nt & 7;
         const int t = xcd * per + min(xcd, rem) + loc;
-        constexpr int GM = 4;
+        // Tile ids run down GM tile rows before they move to the next tile column.  An activation tile row is 32 / bits
+        // times the bytes of a packed weight tile column, so a run should be wide rather than tall: with 32 tiles per
+        // XCD (the headline launch) GM = 2 makes it 2 x 16 and the launch fetches 69 MB where GM = 4 (4 x 8) fetched
+        // 85 MB; the time is the same (the fetches are not what the kernel waits for).
+        constexpr int GM = 2;
         const int in_group = GM * a.tiles_n, group = t / in_group, first_m = group * GM;
         const int gsz = min(a.tiles_m - first_m, GM), o = t % in_group;
         pm = first_m + o % gsz;
