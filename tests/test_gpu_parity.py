@@ -427,6 +427,8 @@ LARGE_TILE_CASES = [
     (4104, 6208, 320, 3, 64, 16, "f16"),        # backward: 17 x 25 tiles, ragged
     (4096, 4096, 192, 2, 128, 64, "bf16"),      # backward: three stages, rank 64
     (8192, 2048, 2048, 4, 128, 8, "f16"),       # both passes
+    (4096, 96, 4096, 4, 32, 8, "f16"),          # forward: the contraction ends inside the second stage
+    (4096, 4096, 72, 2, 128, 16, "bf16"),       # backward: likewise
 ]
 
 
